@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the int8 brute-force top-k search on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--nq NQ] [--k 10]
+
+Workload: the 1M x 128 skewed-integer corpus (stand-in for the 128-d descriptor benchmark
+of the paper's Table 2), 10 000 queries, squared L2, k = 10, int8 codes, seeded synthetic
+data generated on the GPU.  One step = one lpq_search call over the whole query batch
+(query encode, contraction + top-k over the whole corpus, merge), with the corpus codes
+already resident in HBM.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_INT8_OPS = 5.0e15      # MI355X dense int8 matrix peak, op/s
+PEAK_HBM = 8.0e12           # MI355X HBM3E, B/s
+
+
+def cpu_baseline(oracle, x_host, q_host, params, k, metric, gpu_ids, gpu_dists, sample):
+    """The oracle as it stands, timed on the host cores on `sample` queries; also checks the
+    GPU result of those queries bit for bit."""
+    import numpy as np
+    kq, sb, se, _ = params
+    oq = oracle.Quantizer(x_host.shape[1], 8).set_params(kq, sb, se)
+    codes = oq.encode(x_host)
+    qcodes = oq.encode(q_host[:sample])
+    threads = max(1, min(16, oracle.max_threads(), os.cpu_count() or 1))
+    t0 = time.perf_counter()
+    oids, odists = oracle.search_i8(codes, qcodes, k, metric, threads=threads)
+    dt = time.perf_counter() - t0
+    ok = bool(np.array_equal(oids, gpu_ids[:sample]) and np.array_equal(odists, gpu_dists[:sample]))
+    return {"value": sample / dt, "unit": "queries/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {sample} queries against the full corpus, {dt:.1f} s wall",
+            "gpu_matches_oracle_on_sample": ok}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--nq", type=int, default=0, help="query batch (default: the workload's 10 000)")
+    ap.add_argument("--k", type=int, default=10)
+    ap.add_argument("--n", type=int, default=0, help="corpus rows (default: the workload's 1 000 000)")
+    ap.add_argument("--cpu-sample", type=int, default=48)
+    ap.add_argument("--recall-queries", type=int, default=1000)
+    ap.add_argument("--path", type=int, default=0, help="0 auto, 1 generic kernel, 2 matrix-core kernel")
+    ap.add_argument("--splits", type=int, default=0)
+    ap.add_argument("--seed-rows", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; multi-GPU sharding is a design note only "
+              "(--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2110_08919_amd import lpq, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    lpq.lib()
+    w = synth.SKEWED_1M.scaled(n=args.n or None, nq=args.nq or None)
+    k, metric = args.k, w.metric
+
+    # ---- inputs and index build (not part of the timed search step) -------------------
+    x = w.corpus("cuda")
+    q = w.queries("cuda")
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    quant = lpq.Quantizer(w.d, 8).calibrate(x, w.calib, w.scope)
+    torch.cuda.synchronize()
+    t_cal = time.perf_counter() - t0
+    index = lpq.Index(quant, w.n)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    index.add_f32(x)
+    torch.cuda.synchronize()
+    t_enc = time.perf_counter() - t0
+
+    lpq.set_tuning(lpq.TUNE_PATH, args.path)
+    lpq.set_tuning(lpq.TUNE_SPLITS, args.splits)
+    lpq.set_tuning(lpq.TUNE_SEED_ROWS, args.seed_rows)
+    ids = torch.empty((w.nq, k), dtype=torch.int32, device="cuda")
+    dists = torch.empty((w.nq, k), dtype=torch.int32, device="cuda")
+    ws = torch.empty(index.workspace_bytes(w.nq, k, metric) + 256, dtype=torch.uint8, device="cuda")
+
+    for _ in range(args.warmup):
+        index.search(q, k, metric, out=(ids, dists), workspace=ws)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly `steps` searches ------------------------------------------
+    lpq.profile_enable(True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        index.search(q, k, metric, out=(ids, dists), workspace=ws)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    launches, kern_ms = lpq.profile_read()
+    lpq.profile_enable(False)
+
+    ops_per_step = 2.0 * w.nq * w.n * w.d                    # true d, not the padded one
+    kern_ms_per_step = kern_ms / args.steps
+    bytes_per_step = float(w.n) * (w.d + 4)                  # corpus codes + norms, streamed once
+    mfma_frac = ops_per_step / (kern_ms_per_step * 1e-3) / PEAK_INT8_OPS
+    hbm_frac = bytes_per_step / (kern_ms_per_step * 1e-3) / PEAK_HBM
+    if mfma_frac >= hbm_frac:
+        roofline = {"bound": "mfma", "achieved": ops_per_step / (kern_ms_per_step * 1e-3) / 1e12,
+                    "peak": PEAK_INT8_OPS / 1e12, "unit": "TOP/s", "frac": mfma_frac, "traffic": None}
+    else:
+        roofline = {"bound": "hbm", "achieved": bytes_per_step / (kern_ms_per_step * 1e-3) / 1e9,
+                    "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": hbm_frac, "traffic": None}
+    roofline["kernel"] = "contraction + top-k scan (all launches of one search)"
+    roofline["kernel_ms_per_step"] = kern_ms_per_step
+    roofline["launches_per_step"] = launches / args.steps
+
+    # ---- recall@k of the int8 search against fp32 exact search (GPU), on a query subset ----
+    rq = min(args.recall_queries, w.nq)
+    recall = None
+    if rq > 0:
+        eids, _ = lpq.search_f32(x, q[:rq], k, metric)
+        a, e = ids[:rq].cpu().numpy(), eids.cpu().numpy()
+        recall = float(np.mean([len(set(a[i]) & set(e[i])) / k for i in range(rq)]))
+
+    # ---- CPU baseline: the oracle, on a bounded sample -----------------------------------
+    cpu = None
+    if args.cpu_sample > 0:
+        from oracle import lpq_oracle as oracle
+        sample = min(args.cpu_sample, w.nq)
+        cpu = cpu_baseline(oracle, x.cpu().numpy(), q[:sample].cpu().numpy(), quant.get_params(), k, metric,
+                           ids.cpu().numpy(), dists.cpu().numpy(), sample)
+
+    out = {
+        "metric": "queries/sec, int8 brute-force top-10, 1M x 128",
+        "value": w.nq / (ms_per_step * 1e-3),
+        "unit": "queries/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": w.name, "n": w.n, "d": w.d, "nq": w.nq, "k": k, "metric": metric,
+                   "calibration": f"{w.calib}/{w.scope}", "seed": w.seed,
+                   "path": {0: "auto", 1: "generic", 2: "matrix-core"}[args.path]},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "recall_at_k_vs_fp32": recall,
+        "recall_queries": rq,
+        "index_build": {"calibrate_ms": t_cal * 1e3, "encode_ms": t_enc * 1e3,
+                        "encode_GBps": w.n * w.d * 5 / t_enc / 1e9},
+        "wall_s_timed_region": wall,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,171 @@
+/*
+ * lpq.h - low-precision (int8) brute-force k-nearest-neighbour search on one
+ * AMD Instinct MI355X (gfx950).  C ABI of liblpq.so.
+ *
+ * The library implements the exhaustive-search hot path of "Low-Precision
+ * Quantization for Efficient Nearest Neighbor Search": a feature-wise clamped linear
+ * quantizer learned from the corpus (Section 3.2, Equation 1; Sections 4.1, 4.2)
+ * maps items and queries into a low-precision integer domain, the distance function
+ * is evaluated on the integers (phi : Z^d x Z^d -> Z, Section 3.1), and the k nearest
+ * items of every query are returned (problem statement, Section 1).
+ *
+ * General conventions
+ *   - "dev" pointers are DEVICE pointers of the current HIP device, owned by the
+ *     caller (e.g. storage of a torch tensor); "host" pointers are host memory.
+ *     Matrices are row-major; `ld` is the row stride in ELEMENTS (ld >= d).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     only enqueue work on it and do not synchronise unless stated otherwise.
+ *   - Every function returning int returns LPQ_OK (0) or an error code below; on
+ *     error no output buffer has been written by the failing call and
+ *     lpq_last_error() describes the failure.  No C++ exception crosses the ABI.
+ *   - The library owns only its two opaque handle types.  A handle may be used from
+ *     one thread at a time.
+ *   - Item ids are 0-based row numbers in the order the items were added.
+ */
+#ifndef LPQ_H
+#define LPQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lpq_quantizer lpq_quantizer;
+typedef struct lpq_index lpq_index;
+
+enum {
+    LPQ_OK = 0,
+    LPQ_EINVAL = 1,     /* null pointer, d < 1, bits outside 1..8, ld < d, k < 1, unknown enum */
+    LPQ_ERANGE = 2,     /* k > n, n >= 2^31, d beyond the int32 bound, capacity or workspace too small */
+    LPQ_ENOMEM = 3,     /* device or host allocation failed */
+    LPQ_EDEVICE = 4,    /* a HIP call failed */
+    LPQ_ENONFINITE = 5, /* calibration data held a NaN or an infinity */
+    LPQ_ESTATE = 6      /* encode before calibrate/set_params, search on an empty index */
+};
+
+/* How the range [S_b, S_e] and the offset k of Equation 1 are learned.
+ *   MINMAX  S_b = min, S_e = max, k = (min + max) / 2: the observed range (Section 1,
+ *           "the range of values that appear in practice").
+ *   ABSMAX  S_b = -A, S_e = +A, k = 0 with A the absolute maximum observed in the
+ *           dimension (Section 4.2).
+ *   GAUSS   S_b = mu - c sigma, S_e = mu + c sigma, k = mu, with the maximum-likelihood
+ *           (1/n) estimates of a normal law per dimension; the paper uses c = 1
+ *           (Section 3.2). */
+enum { LPQ_CALIB_MINMAX = 0, LPQ_CALIB_ABSMAX = 1, LPQ_CALIB_GAUSS = 2 };
+
+/* PER_FEATURE: constants per dimension (the superscripts i of Equation 1).
+ * GLOBAL: one set of constants from all n*d values, for all dimensions (Section 4.1). */
+enum { LPQ_SCOPE_PER_FEATURE = 0, LPQ_SCOPE_GLOBAL = 1 };
+
+/* L2SQ: sum_i (a_i - b_i)^2 on codes, smaller = nearer.
+ * IP:   sum_i a_i b_i on codes, LARGER = nearer (maximum inner product search, Section
+ *       3.1).  Angular search = IP on vectors the caller normalised to unit length. */
+enum { LPQ_METRIC_L2SQ = 0, LPQ_METRIC_IP = 1 };
+
+/* ------------------------------------------------------------------ quantizer ---- */
+
+/* New quantizer for d-dimensional vectors and bit-width B = bits (1..8); codes lie in
+ * [-2^(B-1), 2^(B-1)] and are stored one per int8 (at B = 8 the value +128 of the upper
+ * clamp is stored as 127).  *out is written on success only. */
+int lpq_quantizer_create(lpq_quantizer **out, int d, int bits);
+void lpq_quantizer_destroy(lpq_quantizer *q);
+
+/* Learn the constants from n >= 1 vectors x_dev[n][ld] (fp32, device).  sigma_mult is c
+ * above (GAUSS only; must be > 0).  Statistics are exact for MINMAX/ABSMAX; GAUSS sums in
+ * fp64 (two passes: mean, then centred second moment).  This call SYNCHRONISES `stream`
+ * before returning, because its status depends on the data: LPQ_ENONFINITE if a NaN or
+ * an infinity was seen (the quantizer then keeps its previous state). */
+int lpq_quantizer_calibrate(lpq_quantizer *q, const float *x_dev, int64_t n, int64_t ld,
+                            int mode, int scope, float sigma_mult, void *stream);
+
+/* Set / read the constants directly (host arrays of d floats each; `m` may be NULL).
+ * m_i = fl32(2^B / (S_e_i - S_b_i)) is derived in fp64; a feature with S_e <= S_b gets
+ * m = 0 and encodes to 0 everywhere.  Both calls synchronise the device. */
+int lpq_quantizer_set_params(lpq_quantizer *q, const float *k, const float *s_b, const float *s_e);
+int lpq_quantizer_get_params(const lpq_quantizer *q, float *k, float *s_b, float *s_e, float *m);
+
+/* Equation 1 on n vectors: codes_dev[j][i] for i < d (row stride ld_codes >= d bytes;
+ * bytes i >= d of a row are not touched), and, if norms_dev is not NULL, norms_dev[j] =
+ * sum_i code^2 (int32).  Per value, in IEEE binary32 without fused multiply-add:
+ * NaN -> 0; x < S_b -> -2^(B-1); x > S_e -> +2^(B-1); otherwise floor((x - k) * m). */
+int lpq_encode(const lpq_quantizer *q, const float *x_dev, int64_t n, int64_t ld,
+               int8_t *codes_dev, int64_t ld_codes, int32_t *norms_dev, void *stream);
+
+/* ---------------------------------------------------------------------- index ---- */
+
+/* Flat index for up to `capacity` items (1 <= capacity < 2^31).  The index takes a copy
+ * of the quantizer's constants (later changes to q do not affect it) and allocates, with
+ * hipMalloc, the int8 codes (rows padded to a multiple of 32 bytes) and the integer norms.
+ * d <= 32 768 keeps every integer distance inside int32. */
+int lpq_index_create(lpq_index **out, const lpq_quantizer *q, int64_t capacity);
+void lpq_index_destroy(lpq_index *idx);
+
+/* Append n items: fp32 vectors (encoded with the index's quantizer, Equation 1) or codes
+ * produced earlier by lpq_encode with the same constants (row stride ld bytes). */
+int lpq_index_add_f32(lpq_index *idx, const float *x_dev, int64_t n, int64_t ld, void *stream);
+int lpq_index_add_i8(lpq_index *idx, const int8_t *codes_dev, int64_t n, int64_t ld, void *stream);
+int64_t lpq_index_size(const lpq_index *idx);  /* items added so far; -1 for NULL */
+
+/* Read-only view of the index storage (device pointers owned by the index, valid until it
+ * is destroyed): codes [size][*ld_codes] int8 and norms [size] int32.  Any may be NULL. */
+int lpq_index_data(const lpq_index *idx, const int8_t **codes_dev, int64_t *ld_codes,
+                   const int32_t **norms_dev);
+
+/* --------------------------------------------------------------------- search ---- */
+
+/* Bytes of device workspace lpq_search / lpq_search_i8 need for nq queries and k results
+ * (0 on invalid arguments).  The workspace needs 256-byte alignment. */
+size_t lpq_search_workspace_bytes(const lpq_index *idx, int64_t nq, int k, int metric);
+
+/* k nearest items of each of nq queries q_dev[nq][ld] (fp32; encoded with the index's
+ * quantizer exactly like the items).  Outputs, row i = query i, best first:
+ *   ids_dev [nq][k] int32 item ids;
+ *   dist_dev[nq][k] int32: L2SQ the full integer distance sum (cq - cx)^2, ascending;
+ *                          IP the integer inner product, descending.
+ * Equal distances are ordered by ascending id, so the result is unique.
+ * 1 <= k <= min(size, 1024).  nq = 0 is a no-op.  Asynchronous on `stream`. */
+int lpq_search(const lpq_index *idx, const float *q_dev, int64_t nq, int64_t ld, int k,
+               int metric, int32_t *ids_dev, int32_t *dist_dev, void *workspace_dev,
+               size_t workspace_bytes, void *stream);
+
+/* Same, for queries that are already codes (int8, row stride ld bytes). */
+int lpq_search_i8(const lpq_index *idx, const int8_t *qcodes_dev, int64_t nq, int64_t ld, int k,
+                  int metric, int32_t *ids_dev, int32_t *dist_dev, void *workspace_dev,
+                  size_t workspace_bytes, void *stream);
+
+/* Exact search on the original fp32 vectors (the reference set S_E of the recall
+ * definition, Section 5.3): x_dev[n][ldx], q_dev[nq][ldq], fp32 arithmetic (the squared
+ * distance is summed directly as (q - x)^2, never through norms).  dist_dev [nq][k] fp32,
+ * L2SQ ascending / IP descending, ties to the lower id.  1 <= k <= min(n, 1024). */
+size_t lpq_search_f32_workspace_bytes(int64_t n, int64_t nq, int d, int k);
+int lpq_search_f32(const float *x_dev, int64_t n, int64_t ldx, const float *q_dev, int64_t nq,
+                   int64_t ldq, int d, int k, int metric, int32_t *ids_dev, float *dist_dev,
+                   void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------- diagnostics ---- */
+
+/* Process-wide tuning knobs for measurements; 0 restores the built-in choice.
+ *   LPQ_TUNE_PATH        1 = generic dot-product kernel, 2 = matrix-core kernel
+ *   LPQ_TUNE_SPLITS      number of corpus splits per query tile in the main pass
+ *   LPQ_TUNE_SEED_ROWS   rows of the threshold-seeding pass (0 = built-in choice,
+ *                        -1 = no seeding pass)
+ * Results never depend on these. */
+enum { LPQ_TUNE_PATH = 0, LPQ_TUNE_SPLITS = 1, LPQ_TUNE_SEED_ROWS = 2, LPQ_TUNE_COUNT_ = 3 };
+int lpq_set_tuning(int key, int64_t value);
+
+/* Kernel timing for benchmarks.  While enabled, every launch of the contraction/top-k
+ * kernel of lpq_search* is bracketed by a pair of HIP events on the launch stream.
+ * lpq_profile_read synchronises those events and returns the number of bracketed
+ * launches and their summed duration in milliseconds since the last enable. */
+int lpq_profile_enable(int on);
+int lpq_profile_read(int64_t *launches, double *total_ms);
+
+/* Message of the last error on the calling thread ("" if none). */
+const char *lpq_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LPQ_H */

@@ -1,0 +1,504 @@
+// C ABI of liblpq.so: argument checks, handle lifetimes, workspace planning and the order
+// in which the kernels of a search are enqueued.  No kernel lives here.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "lpq_internal.h"
+
+using namespace lpq;
+
+// ------------------------------------------------------------------------ errors ----
+static thread_local char g_err[512] = "";
+
+static int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                        \
+    do {                                                                                     \
+        hipError_t e_ = (expr);                                                              \
+        if (e_ != hipSuccess)                                                                \
+            return fail(e_ == hipErrorOutOfMemory ? LPQ_ENOMEM : LPQ_EDEVICE, "%s: %s", #expr, \
+                        hipGetErrorString(e_));                                              \
+    } while (0)
+
+extern "C" const char *lpq_last_error(void) { return g_err; }
+
+// ------------------------------------------------------------------------ tuning ----
+static int64_t g_tune[LPQ_TUNE_COUNT_] = {0, 0, 0};
+
+extern "C" int lpq_set_tuning(int key, int64_t value)
+{
+    if (key < 0 || key >= LPQ_TUNE_COUNT_) return fail(LPQ_EINVAL, "unknown tuning key %d", key);
+    g_tune[key] = value;
+    return LPQ_OK;
+}
+
+// --------------------------------------------------------------------- profiling ----
+namespace {
+struct Profile {
+    std::mutex mu;
+    bool on = false;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> spans;
+    void clear()
+    {
+        for (auto &s : spans) { (void)hipEventDestroy(s.first); (void)hipEventDestroy(s.second); }
+        spans.clear();
+    }
+};
+Profile g_prof;
+
+struct KernelSpan {  // brackets the main search kernel with two events while profiling is on
+    hipEvent_t a = nullptr, b = nullptr;
+    hipStream_t st;
+    explicit KernelSpan(hipStream_t s) : st(s)
+    {
+        std::lock_guard<std::mutex> l(g_prof.mu);
+        if (!g_prof.on) return;
+        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { a = b = nullptr; return; }
+        (void)hipEventRecord(a, st);
+    }
+    ~KernelSpan()
+    {
+        if (!a) return;
+        (void)hipEventRecord(b, st);
+        std::lock_guard<std::mutex> l(g_prof.mu);
+        g_prof.spans.emplace_back(a, b);
+    }
+};
+}  // namespace
+
+extern "C" int lpq_profile_enable(int on)
+{
+    std::lock_guard<std::mutex> l(g_prof.mu);
+    g_prof.clear();
+    g_prof.on = on != 0;
+    return LPQ_OK;
+}
+
+extern "C" int lpq_profile_read(int64_t *launches, double *total_ms)
+{
+    if (!launches || !total_ms) return fail(LPQ_EINVAL, "null output");
+    std::lock_guard<std::mutex> l(g_prof.mu);
+    double tot = 0.0;
+    for (auto &s : g_prof.spans) {
+        HIP_TRY(hipEventSynchronize(s.second));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, s.first, s.second));
+        tot += ms;
+    }
+    *launches = (int64_t)g_prof.spans.size();
+    *total_ms = tot;
+    return LPQ_OK;
+}
+
+// --------------------------------------------------------------------- quantizer ----
+struct lpq_quantizer {
+    int d = 0, bits = 0;
+    bool ready = false;
+    float *params = nullptr;   // device [4][d]: k, S_b, S_e, m
+    float *staging = nullptr;  // device [4][d]: calibration result before it is committed
+    void *scratch = nullptr;   // calibration partials
+    int *flag = nullptr;       // device: non-finite value seen
+};
+
+static QuantParams view(const float *params, int d, int bits)
+{
+    QuantParams qp;
+    qp.k = params; qp.sb = params + d; qp.se = params + 2 * d; qp.m = params + 3 * d;
+    qp.d = d; qp.bits = bits;
+    return qp;
+}
+
+extern "C" void lpq_quantizer_destroy(lpq_quantizer *q)
+{
+    if (!q) return;
+    (void)hipFree(q->params);
+    (void)hipFree(q->staging);
+    (void)hipFree(q->scratch);
+    (void)hipFree(q->flag);
+    delete q;
+}
+
+extern "C" int lpq_quantizer_create(lpq_quantizer **out, int d, int bits)
+{
+    if (!out) return fail(LPQ_EINVAL, "out is null");
+    if (d < 1) return fail(LPQ_EINVAL, "d = %d < 1", d);
+    if (bits < 1 || bits > 8) return fail(LPQ_EINVAL, "bits = %d outside 1..8", bits);
+    if (d > MAX_D) return fail(LPQ_ERANGE, "d = %d > %d", d, (int)MAX_D);
+    lpq_quantizer *q = new (std::nothrow) lpq_quantizer;
+    if (!q) return fail(LPQ_ENOMEM, "host allocation failed");
+    q->d = d; q->bits = bits;
+    hipError_t e = hipMalloc(&q->params, sizeof(float) * 4 * d);
+    if (e == hipSuccess) e = hipMalloc(&q->staging, sizeof(float) * 4 * d);
+    if (e == hipSuccess) e = hipMalloc(&q->scratch, calib_scratch_bytes(d));
+    if (e == hipSuccess) e = hipMalloc(&q->flag, 256);
+    if (e != hipSuccess) {
+        lpq_quantizer_destroy(q);
+        return fail(e == hipErrorOutOfMemory ? LPQ_ENOMEM : LPQ_EDEVICE, "hipMalloc: %s", hipGetErrorString(e));
+    }
+    *out = q;
+    return LPQ_OK;
+}
+
+extern "C" int lpq_quantizer_calibrate(lpq_quantizer *q, const float *x_dev, int64_t n, int64_t ld, int mode,
+                                       int scope, float sigma_mult, void *stream)
+{
+    if (!q || !x_dev) return fail(LPQ_EINVAL, "null argument");
+    if (n < 1) return fail(LPQ_EINVAL, "n = %lld < 1", (long long)n);
+    if (ld < q->d) return fail(LPQ_EINVAL, "ld = %lld < d = %d", (long long)ld, q->d);
+    if (mode < LPQ_CALIB_MINMAX || mode > LPQ_CALIB_GAUSS) return fail(LPQ_EINVAL, "unknown calibration mode %d", mode);
+    if (scope != LPQ_SCOPE_PER_FEATURE && scope != LPQ_SCOPE_GLOBAL) return fail(LPQ_EINVAL, "unknown scope %d", scope);
+    if (mode == LPQ_CALIB_GAUSS && !(sigma_mult > 0.0f)) return fail(LPQ_EINVAL, "sigma_mult must be > 0");
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(launch_calibrate(x_dev, n, ld, q->d, q->bits, mode, scope, (double)sigma_mult, q->scratch,
+                             q->staging, q->flag, st));
+    int bad = 0;
+    HIP_TRY(hipMemcpyAsync(&bad, q->flag, sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (bad) return fail(LPQ_ENONFINITE, "calibration data holds a NaN or an infinity");
+    HIP_TRY(hipMemcpyAsync(q->params, q->staging, sizeof(float) * 4 * q->d, hipMemcpyDeviceToDevice, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    q->ready = true;
+    return LPQ_OK;
+}
+
+extern "C" int lpq_quantizer_set_params(lpq_quantizer *q, const float *k, const float *s_b, const float *s_e)
+{
+    if (!q || !k || !s_b || !s_e) return fail(LPQ_EINVAL, "null argument");
+    const size_t bytes = sizeof(float) * q->d;
+    HIP_TRY(hipMemcpy(q->params, k, bytes, hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(q->params + q->d, s_b, bytes, hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(q->params + 2 * q->d, s_e, bytes, hipMemcpyHostToDevice));
+    HIP_TRY(launch_derive_m(q->params, q->d, q->bits, nullptr));
+    HIP_TRY(hipDeviceSynchronize());
+    q->ready = true;
+    return LPQ_OK;
+}
+
+extern "C" int lpq_quantizer_get_params(const lpq_quantizer *q, float *k, float *s_b, float *s_e, float *m)
+{
+    if (!q || !k || !s_b || !s_e) return fail(LPQ_EINVAL, "null argument");
+    if (!q->ready) return fail(LPQ_ESTATE, "quantizer has no constants yet");
+    const size_t bytes = sizeof(float) * q->d;
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipMemcpy(k, q->params, bytes, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(s_b, q->params + q->d, bytes, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(s_e, q->params + 2 * q->d, bytes, hipMemcpyDeviceToHost));
+    if (m) HIP_TRY(hipMemcpy(m, q->params + 3 * q->d, bytes, hipMemcpyDeviceToHost));
+    return LPQ_OK;
+}
+
+extern "C" int lpq_encode(const lpq_quantizer *q, const float *x_dev, int64_t n, int64_t ld, int8_t *codes_dev,
+                          int64_t ld_codes, int32_t *norms_dev, void *stream)
+{
+    if (!q || !x_dev || !codes_dev) return fail(LPQ_EINVAL, "null argument");
+    if (n < 0) return fail(LPQ_EINVAL, "n < 0");
+    if (ld < q->d || ld_codes < q->d) return fail(LPQ_EINVAL, "row stride smaller than d = %d", q->d);
+    if (!q->ready) return fail(LPQ_ESTATE, "encode before calibrate/set_params");
+    HIP_TRY(launch_encode(view(q->params, q->d, q->bits), x_dev, n, ld, codes_dev, ld_codes, 0, norms_dev,
+                          (hipStream_t)stream));
+    return LPQ_OK;
+}
+
+// ------------------------------------------------------------------------- index ----
+struct lpq_index {
+    int d = 0, d_pad = 0, bits = 0;
+    int64_t capacity = 0, cap_rows = 0, size = 0;
+    float *params = nullptr;     // device copy of the quantizer constants
+    int8_t *codes = nullptr;     // [cap_rows][d_pad], zero padded
+    int32_t *norms = nullptr;    // [cap_rows]
+    int32_t *cinit = nullptr;    // [cap_rows]   accumulator seeds of the matrix-core kernel
+    uint32_t *parity = nullptr;  // [cap_rows/32]
+};
+
+extern "C" void lpq_index_destroy(lpq_index *idx)
+{
+    if (!idx) return;
+    (void)hipFree(idx->params);
+    (void)hipFree(idx->codes);
+    (void)hipFree(idx->norms);
+    (void)hipFree(idx->cinit);
+    (void)hipFree(idx->parity);
+    delete idx;
+}
+
+extern "C" int lpq_index_create(lpq_index **out, const lpq_quantizer *q, int64_t capacity)
+{
+    if (!out || !q) return fail(LPQ_EINVAL, "null argument");
+    if (!q->ready) return fail(LPQ_ESTATE, "quantizer has no constants yet");
+    if (capacity < 1) return fail(LPQ_EINVAL, "capacity < 1");
+    if (capacity >= (int64_t(1) << 31) - 1024) return fail(LPQ_ERANGE, "capacity must stay below 2^31 - 1024");
+    lpq_index *idx = new (std::nothrow) lpq_index;
+    if (!idx) return fail(LPQ_ENOMEM, "host allocation failed");
+    idx->d = q->d; idx->bits = q->bits;
+    idx->d_pad = (int)round_up(q->d, 32);
+    idx->capacity = capacity;
+    idx->cap_rows = round_up(capacity, 256) + 256;  // whole tiles may be read past the last item
+    const size_t code_bytes = (size_t)idx->cap_rows * idx->d_pad;
+    hipError_t e = hipMalloc(&idx->params, sizeof(float) * 4 * idx->d);
+    if (e == hipSuccess) e = hipMalloc(&idx->codes, code_bytes);
+    if (e == hipSuccess) e = hipMalloc(&idx->norms, sizeof(int32_t) * idx->cap_rows);
+    if (e == hipSuccess) e = hipMalloc(&idx->cinit, sizeof(int32_t) * idx->cap_rows);
+    if (e == hipSuccess) e = hipMalloc(&idx->parity, sizeof(uint32_t) * (idx->cap_rows / 32));
+    if (e == hipSuccess) e = hipMemcpy(idx->params, q->params, sizeof(float) * 4 * idx->d, hipMemcpyDeviceToDevice);
+    if (e == hipSuccess) e = hipMemset(idx->codes, 0, code_bytes);
+    if (e == hipSuccess) e = hipMemset(idx->norms, 0, sizeof(int32_t) * idx->cap_rows);
+    if (e == hipSuccess) e = hipMemset(idx->parity, 0, sizeof(uint32_t) * (idx->cap_rows / 32));
+    if (e == hipSuccess) e = hipMemsetD32((hipDeviceptr_t)idx->cinit, CINIT_PAD, (size_t)idx->cap_rows);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        lpq_index_destroy(idx);
+        return fail(e == hipErrorOutOfMemory ? LPQ_ENOMEM : LPQ_EDEVICE, "index allocation: %s", hipGetErrorString(e));
+    }
+    *out = idx;
+    return LPQ_OK;
+}
+
+static int index_after_add(lpq_index *idx, int64_t n, hipStream_t st)
+{
+    const int64_t row0 = idx->size;
+    idx->size += n;
+    // Seeds for every row of every tile that can be touched: rows beyond size get the padding seed.
+    HIP_TRY(launch_item_aux(idx->norms, row0, idx->size, idx->cinit, idx->parity, st));
+    return LPQ_OK;
+}
+
+extern "C" int lpq_index_add_f32(lpq_index *idx, const float *x_dev, int64_t n, int64_t ld, void *stream)
+{
+    if (!idx || !x_dev) return fail(LPQ_EINVAL, "null argument");
+    if (n < 0) return fail(LPQ_EINVAL, "n < 0");
+    if (ld < idx->d) return fail(LPQ_EINVAL, "ld < d");
+    if (idx->size + n > idx->capacity) return fail(LPQ_ERANGE, "index capacity %lld exceeded", (long long)idx->capacity);
+    if (n == 0) return LPQ_OK;
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(launch_encode(view(idx->params, idx->d, idx->bits), x_dev, n, ld,
+                          idx->codes + (size_t)idx->size * idx->d_pad, idx->d_pad, idx->d_pad,
+                          idx->norms + idx->size, st));
+    return index_after_add(idx, n, st);
+}
+
+extern "C" int lpq_index_add_i8(lpq_index *idx, const int8_t *codes_dev, int64_t n, int64_t ld, void *stream)
+{
+    if (!idx || !codes_dev) return fail(LPQ_EINVAL, "null argument");
+    if (n < 0) return fail(LPQ_EINVAL, "n < 0");
+    if (ld < idx->d) return fail(LPQ_EINVAL, "ld < d");
+    if (idx->size + n > idx->capacity) return fail(LPQ_ERANGE, "index capacity %lld exceeded", (long long)idx->capacity);
+    if (n == 0) return LPQ_OK;
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(launch_repack_i8(codes_dev, n, ld, idx->d, idx->codes + (size_t)idx->size * idx->d_pad, idx->d_pad,
+                             idx->d_pad, idx->norms + idx->size, st));
+    return index_after_add(idx, n, st);
+}
+
+extern "C" int64_t lpq_index_size(const lpq_index *idx) { return idx ? idx->size : -1; }
+
+extern "C" int lpq_index_data(const lpq_index *idx, const int8_t **codes_dev, int64_t *ld_codes,
+                              const int32_t **norms_dev)
+{
+    if (!idx) return fail(LPQ_EINVAL, "null index");
+    if (codes_dev) *codes_dev = idx->codes;
+    if (ld_codes) *ld_codes = idx->d_pad;
+    if (norms_dev) *norms_dev = idx->norms;
+    return LPQ_OK;
+}
+
+// ------------------------------------------------------------------------ search ----
+namespace {
+
+// How a search over n items is cut up, and where its intermediates live in the workspace.
+struct Plan {
+    bool mfma = false;
+    int64_t nq_pad = 0;
+    int64_t seed_rows = 0;  // rows of the threshold-seeding pass (0 = none)
+    int S1 = 0, S2 = 0;     // corpus splits of the seeding pass and of the main pass
+    size_t off_qcodes = 0, off_qnorms = 0, off_lists1 = 0, off_seedlist = 0, off_seeds = 0, off_lists2 = 0,
+           off_scratch = 0, total = 0;
+};
+
+size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
+
+Plan make_plan(const lpq_index *idx, int64_t nq, int k)
+{
+    Plan p;
+    const int64_t n = idx->size;
+    p.mfma = mfma_supported(idx->d_pad, k) && g_tune[LPQ_TUNE_PATH] != 1;
+    if (g_tune[LPQ_TUNE_PATH] == 2 && !mfma_supported(idx->d_pad, k)) p.mfma = false;
+    p.nq_pad = round_up(nq, 256);
+    const int max_lists = merge_max_lists(k);
+
+    // Seeding pass: a first slice of the corpus is searched alone; its k-th best candidate
+    // per query is an upper bound on the final k-th best and lets the main pass reject
+    // almost everything from its first tile on.
+    int64_t seed = 0;
+    if (g_tune[LPQ_TUNE_SEED_ROWS] > 0) seed = g_tune[LPQ_TUNE_SEED_ROWS];
+    else if (g_tune[LPQ_TUNE_SEED_ROWS] == 0 && p.mfma) seed = n / 64 < 4096 ? 4096 : (n / 64 > 32768 ? 32768 : n / 64);
+    seed = round_up(seed, 256);
+    if (seed < k || seed * 4 > n) seed = 0;
+    p.seed_rows = seed;
+
+    auto splits_for = [&](int64_t rows, int64_t tiles_q) {
+        int64_t s;
+        if (p.mfma) {
+            s = g_tune[LPQ_TUNE_SPLITS] > 0 ? g_tune[LPQ_TUNE_SPLITS] : ceil_div(512, tiles_q > 0 ? tiles_q : 1);
+            const int64_t max_by_rows = rows / 1024 > 0 ? rows / 1024 : 1;
+            if (s > max_by_rows) s = max_by_rows;
+        } else {
+            s = g_tune[LPQ_TUNE_SPLITS] > 0 ? g_tune[LPQ_TUNE_SPLITS] : ceil_div(2048, nq > 0 ? nq : 1);
+            const int64_t max_by_rows = rows / 2048 > 0 ? rows / 2048 : 1;
+            if (s > max_by_rows) s = max_by_rows;
+        }
+        if (s > max_lists) s = max_lists;
+        if (s < 1) s = 1;
+        return (int)s;
+    };
+    const int64_t tiles_q = p.nq_pad / 256;
+    if (seed) p.S1 = splits_for(seed, tiles_q);
+    p.S2 = splits_for(n - seed, tiles_q);
+
+    size_t o = 0;
+    p.off_qcodes = o;   o = align256(o + (size_t)p.nq_pad * idx->d_pad);
+    p.off_qnorms = o;   o = align256(o + (size_t)p.nq_pad * sizeof(int32_t));
+    p.off_lists1 = o;   o = align256(o + (size_t)nq * p.S1 * k * sizeof(cand_t));
+    p.off_seedlist = o; o = align256(o + (size_t)nq * k * sizeof(cand_t));
+    p.off_seeds = o;    o = align256(o + (size_t)p.nq_pad * sizeof(cand_t));
+    p.off_lists2 = o;   o = align256(o + (size_t)nq * p.S2 * k * sizeof(cand_t));
+    p.off_scratch = o;
+    if (p.mfma) o = align256(o + mfma_list_scratch_bytes(p.nq_pad, p.S1 > p.S2 ? p.S1 : p.S2, k));
+    p.total = o;
+    return p;
+}
+
+int check_search_args(const lpq_index *idx, const void *q, int64_t nq, int64_t ld, int k, int metric,
+                      const void *ids, const void *dist)
+{
+    if (!idx) return fail(LPQ_EINVAL, "null index");
+    if (nq < 0) return fail(LPQ_EINVAL, "nq < 0");
+    if (k < 1) return fail(LPQ_EINVAL, "k = %d < 1", k);
+    if (metric != LPQ_METRIC_L2SQ && metric != LPQ_METRIC_IP) return fail(LPQ_EINVAL, "unknown metric %d", metric);
+    if (idx->size < 1) return fail(LPQ_ESTATE, "search on an empty index");
+    if (k > idx->size) return fail(LPQ_ERANGE, "k = %d > number of items %lld", k, (long long)idx->size);
+    if (k > MAX_K) return fail(LPQ_ERANGE, "k = %d > %d", k, (int)MAX_K);
+    if (nq > 0 && (!q || !ids || !dist)) return fail(LPQ_EINVAL, "null argument");
+    if (nq > 0 && ld < idx->d) return fail(LPQ_EINVAL, "ld < d");
+    if (nq * (int64_t)k >= (int64_t(1) << 40)) return fail(LPQ_ERANGE, "nq too large");
+    return LPQ_OK;
+}
+
+// Everything after the queries are codes in the workspace.
+int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k, int metric, int32_t *ids,
+                int32_t *dist, hipStream_t st)
+{
+    SearchArgs a;
+    a.codes = idx->codes; a.norms = idx->norms; a.cinit = idx->cinit; a.parity = idx->parity;
+    a.n = idx->size; a.d_pad = idx->d_pad;
+    a.qcodes = reinterpret_cast<const int8_t *>(ws + p.off_qcodes);
+    a.nq = nq; a.k = k; a.metric = metric;
+    const int32_t *qnorms = reinterpret_cast<const int32_t *>(ws + p.off_qnorms);
+    cand_t *lists1 = reinterpret_cast<cand_t *>(ws + p.off_lists1);
+    cand_t *seedlist = reinterpret_cast<cand_t *>(ws + p.off_seedlist);
+    cand_t *seeds = reinterpret_cast<cand_t *>(ws + p.off_seeds);
+    cand_t *lists2 = reinterpret_cast<cand_t *>(ws + p.off_lists2);
+    void *scratch = ws + p.off_scratch;
+
+    auto scan = [&](int64_t r0, int64_t r1, int S, const cand_t *sd, cand_t *out) -> hipError_t {
+        KernelSpan span(st);
+        return p.mfma ? launch_search_mfma(a, r0, r1, S, sd, out, scratch, st)
+                      : launch_search_generic(a, r0, r1, S, sd, out, st);
+    };
+    if (p.seed_rows) {
+        HIP_TRY(scan(0, p.seed_rows, p.S1, nullptr, lists1));
+        HIP_TRY(launch_merge(lists1, nq, p.S1, k, nullptr, seedlist, seeds, nullptr, nullptr, nullptr, metric, st));
+        HIP_TRY(scan(p.seed_rows, a.n, p.S2, seeds, lists2));
+        HIP_TRY(launch_merge(lists2, nq, p.S2, k, seedlist, nullptr, nullptr, ids, dist, qnorms, metric, st));
+    } else {
+        HIP_TRY(scan(0, a.n, p.S2, nullptr, lists2));
+        HIP_TRY(launch_merge(lists2, nq, p.S2, k, nullptr, nullptr, nullptr, ids, dist, qnorms, metric, st));
+    }
+    return LPQ_OK;
+}
+
+}  // namespace
+
+extern "C" size_t lpq_search_workspace_bytes(const lpq_index *idx, int64_t nq, int k, int metric)
+{
+    if (!idx || nq < 0 || k < 1 || k > MAX_K || idx->size < 1 || k > idx->size) return 0;
+    (void)metric;
+    return make_plan(idx, nq, k).total + 256;
+}
+
+extern "C" int lpq_search(const lpq_index *idx, const float *q_dev, int64_t nq, int64_t ld, int k, int metric,
+                          int32_t *ids_dev, int32_t *dist_dev, void *workspace_dev, size_t workspace_bytes,
+                          void *stream)
+{
+    int rc = check_search_args(idx, q_dev, nq, ld, k, metric, ids_dev, dist_dev);
+    if (rc) return rc;
+    if (nq == 0) return LPQ_OK;
+    const Plan p = make_plan(idx, nq, k);
+    if (!workspace_dev || workspace_bytes < p.total) return fail(LPQ_ERANGE, "workspace of %zu bytes needed", p.total);
+    if ((uintptr_t)workspace_dev % 256) return fail(LPQ_EINVAL, "workspace must be 256-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)workspace_dev;
+    // Padding query rows [nq, nq_pad) are zero codes; their results are never written out.
+    HIP_TRY(launch_zero_bytes(ws + p.off_qcodes + (size_t)nq * idx->d_pad, (size_t)(p.nq_pad - nq) * idx->d_pad, st));
+    HIP_TRY(launch_encode(view(idx->params, idx->d, idx->bits), q_dev, nq, ld,
+                          reinterpret_cast<int8_t *>(ws + p.off_qcodes), idx->d_pad, idx->d_pad,
+                          reinterpret_cast<int32_t *>(ws + p.off_qnorms), st));
+    return search_core(idx, p, ws, nq, k, metric, ids_dev, dist_dev, st);
+}
+
+extern "C" int lpq_search_i8(const lpq_index *idx, const int8_t *qcodes_dev, int64_t nq, int64_t ld, int k,
+                             int metric, int32_t *ids_dev, int32_t *dist_dev, void *workspace_dev,
+                             size_t workspace_bytes, void *stream)
+{
+    int rc = check_search_args(idx, qcodes_dev, nq, ld, k, metric, ids_dev, dist_dev);
+    if (rc) return rc;
+    if (nq == 0) return LPQ_OK;
+    const Plan p = make_plan(idx, nq, k);
+    if (!workspace_dev || workspace_bytes < p.total) return fail(LPQ_ERANGE, "workspace of %zu bytes needed", p.total);
+    if ((uintptr_t)workspace_dev % 256) return fail(LPQ_EINVAL, "workspace must be 256-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)workspace_dev;
+    HIP_TRY(launch_zero_bytes(ws + p.off_qcodes + (size_t)nq * idx->d_pad, (size_t)(p.nq_pad - nq) * idx->d_pad, st));
+    HIP_TRY(launch_repack_i8(qcodes_dev, nq, ld, idx->d, reinterpret_cast<int8_t *>(ws + p.off_qcodes), idx->d_pad,
+                             idx->d_pad, reinterpret_cast<int32_t *>(ws + p.off_qnorms), st));
+    return search_core(idx, p, ws, nq, k, metric, ids_dev, dist_dev, st);
+}
+
+// -------------------------------------------------------------------- fp32 exact ----
+extern "C" size_t lpq_search_f32_workspace_bytes(int64_t n, int64_t nq, int d, int k)
+{
+    if (n < 1 || nq < 0 || d < 1 || k < 1 || k > MAX_K || k > n) return 0;
+    return f32_workspace_bytes(n, nq, d, k) + 256;
+}
+
+extern "C" int lpq_search_f32(const float *x_dev, int64_t n, int64_t ldx, const float *q_dev, int64_t nq,
+                              int64_t ldq, int d, int k, int metric, int32_t *ids_dev, float *dist_dev,
+                              void *workspace_dev, size_t workspace_bytes, void *stream)
+{
+    if (d < 1) return fail(LPQ_EINVAL, "d < 1");
+    if (n < 1) return fail(LPQ_ESTATE, "no items");
+    if (nq < 0) return fail(LPQ_EINVAL, "nq < 0");
+    if (k < 1) return fail(LPQ_EINVAL, "k < 1");
+    if (metric != LPQ_METRIC_L2SQ && metric != LPQ_METRIC_IP) return fail(LPQ_EINVAL, "unknown metric %d", metric);
+    if (k > n || k > MAX_K) return fail(LPQ_ERANGE, "k = %d out of range", k);
+    if (n >= (int64_t(1) << 31) - 1024) return fail(LPQ_ERANGE, "n must stay below 2^31 - 1024");
+    if (nq == 0) return LPQ_OK;
+    if (!x_dev || !q_dev || !ids_dev || !dist_dev) return fail(LPQ_EINVAL, "null argument");
+    if (ldx < d || ldq < d) return fail(LPQ_EINVAL, "row stride smaller than d");
+    const size_t need = f32_workspace_bytes(n, nq, d, k);
+    if (!workspace_dev || workspace_bytes < need) return fail(LPQ_ERANGE, "workspace of %zu bytes needed", need);
+    if ((uintptr_t)workspace_dev % 256) return fail(LPQ_EINVAL, "workspace must be 256-byte aligned");
+    HIP_TRY(launch_search_f32(x_dev, n, ldx, q_dev, nq, ldq, d, k, metric, ids_dev, dist_dev, workspace_dev,
+                              (hipStream_t)stream));
+    return LPQ_OK;
+}

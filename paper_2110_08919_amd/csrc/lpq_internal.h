@@ -1,0 +1,132 @@
+// Internal declarations shared by the translation units of liblpq.so (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "lpq.h"
+
+namespace lpq {
+
+// ---------------------------------------------------------------------------------
+// Candidate keys.  Inside the search every (item, query) pair is ranked by the pair
+//   key = nx_j - 2 * dot(cq_i, cx_j)      (nx_j = sum of squared codes of item j; 0 for IP)
+// which differs from the squared distance only by the per-query constant |cq_i|^2 and
+// from the inner product by the factor -2, so "smaller key = nearer" for both metrics.
+// A candidate is the 64-bit word  (key biased to unsigned) << 32 | id : one unsigned
+// compare orders by (key ascending, id ascending), the tie rule of the interface.
+// ---------------------------------------------------------------------------------
+typedef unsigned long long cand_t;
+static const cand_t CAND_NONE = ~0ull;  // sorts after every real candidate
+
+__host__ __device__ inline cand_t make_cand(int32_t key, uint32_t id)
+{
+    return ((cand_t)((uint32_t)key ^ 0x80000000u) << 32) | (cand_t)id;
+}
+__host__ __device__ inline int32_t cand_key(cand_t c) { return (int32_t)((uint32_t)(c >> 32) ^ 0x80000000u); }
+__host__ __device__ inline uint32_t cand_id(cand_t c) { return (uint32_t)c; }
+
+// Ranking modes of the merge kernel: the two integer metrics (same values as the public
+// LPQ_METRIC_* constants) and the two fp32 ones, whose keys are order-preserving integer
+// images of the float distance (L2) or of minus the inner product (IP).
+enum { MODE_I8_L2 = 0, MODE_I8_IP = 1, MODE_F32_L2 = 2, MODE_F32_IP = 3 };
+
+// Order-preserving map between finite floats and int32 (its own inverse); -0 is folded into +0.
+__host__ __device__ inline int32_t float_to_sortable(float f)
+{
+    f += 0.0f;
+    int32_t b;
+    __builtin_memcpy(&b, &f, 4);
+    return b >= 0 ? b : (b ^ 0x7fffffff);
+}
+__host__ __device__ inline float sortable_to_float(int32_t s)
+{
+    const int32_t b = s >= 0 ? s : (s ^ 0x7fffffff);
+    float f;
+    __builtin_memcpy(&f, &b, 4);
+    return f;
+}
+
+static inline int next_pow2(int v)
+{
+    int p = 1;
+    while (p < v) p <<= 1;
+    return p;
+}
+static inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+enum { MAX_K = 1024, MAX_D = 32768 };
+
+// Per-feature constants on the device: four arrays of d floats, [k | S_b | S_e | m].
+struct QuantParams {
+    const float *k, *sb, *se, *m;
+    int d, bits;
+};
+
+// ---- quantizer kernels (quant_kernels.hip) ---------------------------------------
+// Calibration scratch layout is private to quant_kernels.hip; the API allocates
+// calib_scratch_bytes(d) bytes once per quantizer.
+size_t calib_scratch_bytes(int d);
+hipError_t launch_calibrate(const float *x, int64_t n, int64_t ld, int d, int bits, int mode,
+                            int scope, double sigma_mult, void *scratch, float *params_out,
+                            int *nonfinite_flag, hipStream_t st);
+hipError_t launch_derive_m(float *params, int d, int bits, hipStream_t st);
+// Equation 1 on n rows.  zero_pad_to > d additionally writes zero bytes for columns
+// d .. zero_pad_to-1 of each row.
+hipError_t launch_encode(const QuantParams &qp, const float *x, int64_t n, int64_t ld, int8_t *codes,
+                         int64_t ldc, int zero_pad_to, int32_t *norms, hipStream_t st);
+// Copy codes into padded rows (zero padding), computing norms.
+hipError_t launch_repack_i8(const int8_t *src, int64_t n, int64_t ld, int d, int8_t *dst, int64_t ldd,
+                            int d_pad, int32_t *norms, hipStream_t st);
+// Derived per-item arrays used by the matrix-core kernel: cinit_j = -ceil(nx_j / 2) and one
+// word of 32 parity bits (bit r = nx_{32w+r} & 1) per 32 items; rows >= n of the last word's
+// block get cinit = CINIT_PAD.  use_norms = false (IP) gives cinit = 0 and parity = 0.
+hipError_t launch_zero_bytes(void *p, size_t bytes, hipStream_t st);  // bytes % 4 == 0, p 4-byte aligned
+hipError_t launch_item_aux(const int32_t *norms, int64_t row0, int64_t n_total, int32_t *cinit,
+                           uint32_t *parity, hipStream_t st);
+
+// ---- search kernels ---------------------------------------------------------------
+struct SearchArgs {
+    const int8_t *codes;    // [n][d_pad]
+    const int32_t *norms;   // [n] (ignored for IP)
+    const int32_t *cinit;   // [round_up(n,32)]
+    const uint32_t *parity; // [ceil(n/32)]
+    int64_t n;
+    int d_pad;
+    const int8_t *qcodes;   // [nq_pad][d_pad], zero padded
+    int64_t nq;
+    int k;
+    int metric;
+};
+
+// Generic kernel: one workgroup per (query, corpus split); any d_pad (multiple of 32), any k.
+// Writes lists[(q * S + s) * k + r], sorted ascending, CAND_NONE-filled.
+hipError_t launch_search_generic(const SearchArgs &a, int64_t row0, int64_t row1, int S,
+                                 const cand_t *seeds, cand_t *lists, hipStream_t st);
+
+// Matrix-core kernel (search_mfma.hip).  Supported shapes are reported by mfma_supported().
+bool mfma_supported(int d_pad, int k);
+size_t mfma_list_scratch_bytes(int64_t nq, int S, int k);
+hipError_t launch_search_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S,
+                              const cand_t *seeds, cand_t *lists, void *list_scratch, hipStream_t st);
+
+// Merge P lists of k candidates per query into one (merge.hip).  If ids/dists are given the
+// result is final: ids, and dist = key + qnorm (L2SQ) or -key/2 (IP).  Otherwise the merged
+// candidates go to out_lists[q][k] (sorted) and, if seeds_out, seeds_out[q] = the k-th best
+// candidate (CAND_NONE when fewer than k exist).
+hipError_t launch_merge(const cand_t *lists, int64_t nq, int P, int k, const cand_t *extra_lists,
+                        cand_t *out_lists, cand_t *seeds_out, int32_t *ids, int32_t *dists,
+                        const int32_t *qnorms, int metric, hipStream_t st);
+int merge_max_lists(int k);
+
+// ---- fp32 exact search (search_f32.hip) ---------------------------------------------
+size_t f32_workspace_bytes(int64_t n, int64_t nq, int d, int k);
+hipError_t launch_search_f32(const float *x, int64_t n, int64_t ldx, const float *q, int64_t nq,
+                             int64_t ldq, int d, int k, int metric, int32_t *ids, float *dists,
+                             void *ws, hipStream_t st);
+
+static const int32_t CINIT_PAD = -(1 << 30);
+
+}  // namespace lpq

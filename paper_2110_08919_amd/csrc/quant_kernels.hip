@@ -1,0 +1,482 @@
+// Quantizer kernels: per-feature range statistics (calibration) and the clamped linear
+// encode of Equation 1, with the integer norms of the codes.  All of them stream the fp32
+// matrix once with coalesced reads and are bound by HBM bandwidth.
+#include "lpq_internal.h"
+
+namespace lpq {
+
+namespace {
+
+constexpr int CAL_THREADS = 256;
+constexpr int CAL_WAVES = CAL_THREADS / 64;
+
+int calib_blocks(int d)
+{
+    int64_t g = (int64_t(1) << 20) / d;
+    if (g > 1024) g = 1024;
+    if (g < 16) g = 16;
+    return (int)g;
+}
+
+// Scratch: per-block partial results and the reduced per-column statistics.
+struct CalibScratch {
+    float *pmn, *pmx;   // [G][d]
+    double *psum;       // [G][d]  (pass 1: sum x; pass 2: sum (x - mu)^2)
+    double *mu;         // [d]
+    float *mn, *mx;     // [d]
+};
+
+CalibScratch carve(void *scratch, int d)
+{
+    const int64_t G = calib_blocks(d);
+    char *p = (char *)scratch;
+    CalibScratch s;
+    s.psum = (double *)p; p += sizeof(double) * G * d;
+    s.mu = (double *)p;   p += sizeof(double) * d;
+    s.pmn = (float *)p;   p += sizeof(float) * G * d;
+    s.pmx = (float *)p;   p += sizeof(float) * G * d;
+    s.mn = (float *)p;    p += sizeof(float) * d;
+    s.mx = (float *)p;
+    return s;
+}
+
+// One block reduces rows [b*R, (b+1)*R); a wave reads 64 consecutive columns of one row
+// per load (256 contiguous bytes), four rows in flight.
+template <int PASS>
+__global__ __launch_bounds__(CAL_THREADS) void calib_reduce_kernel(
+    const float *__restrict__ x, int64_t n, int64_t ld, int d, int64_t rows_per_block,
+    const double *__restrict__ mu, float *__restrict__ pmn, float *__restrict__ pmx,
+    double *__restrict__ psum, int *__restrict__ nonfinite)
+{
+    __shared__ float s_mn[CAL_WAVES][64], s_mx[CAL_WAVES][64];
+    __shared__ double s_sum[CAL_WAVES][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t r1 = (r0 + rows_per_block < n) ? r0 + rows_per_block : n;
+    for (int c0 = 0; c0 < d; c0 += 64) {
+        const int c = c0 + lane;
+        const bool live = c < d;
+        float mn = INFINITY, mx = -INFINITY;
+        double sum = 0.0;
+        bool bad = false;
+        const double m = (PASS == 2 && live) ? mu[c] : 0.0;
+        for (int64_t r = r0 + wave; r < r1; r += 4 * CAL_WAVES) {
+            float v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t rr = r + (int64_t)u * CAL_WAVES;
+                v[u] = (live && rr < r1) ? x[rr * ld + c] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t rr = r + (int64_t)u * CAL_WAVES;
+                if (live && rr < r1) {
+                    if (PASS == 1) {
+                        if (!isfinite(v[u])) {
+                            bad = true;
+                        } else {
+                            mn = fminf(mn, v[u]);
+                            mx = fmaxf(mx, v[u]);
+                            sum += (double)v[u];
+                        }
+                    } else {
+                        const double t = (double)v[u] - m;
+                        sum += t * t;
+                    }
+                }
+            }
+        }
+        if (PASS == 1 && bad) atomicOr(nonfinite, 1);
+        s_mn[wave][lane] = mn;
+        s_mx[wave][lane] = mx;
+        s_sum[wave][lane] = sum;
+        __syncthreads();
+        if (wave == 0 && live) {
+            for (int w = 1; w < CAL_WAVES; ++w) {
+                mn = fminf(mn, s_mn[w][lane]);
+                mx = fmaxf(mx, s_mx[w][lane]);
+                sum += s_sum[w][lane];
+            }
+            const int64_t o = (int64_t)blockIdx.x * d + c;
+            if (PASS == 1) { pmn[o] = mn; pmx[o] = mx; }
+            psum[o] = sum;
+        }
+        __syncthreads();
+    }
+}
+
+__device__ inline double block_sum(double v, double *sh)
+{
+    sh[threadIdx.x] = v;
+    __syncthreads();
+    for (int s = CAL_THREADS / 2; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) sh[threadIdx.x] += sh[threadIdx.x + s];
+        __syncthreads();
+    }
+    const double r = sh[0];
+    __syncthreads();
+    return r;
+}
+__device__ inline float block_min(float v, float *sh)
+{
+    sh[threadIdx.x] = v;
+    __syncthreads();
+    for (int s = CAL_THREADS / 2; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) sh[threadIdx.x] = fminf(sh[threadIdx.x], sh[threadIdx.x + s]);
+        __syncthreads();
+    }
+    const float r = sh[0];
+    __syncthreads();
+    return r;
+}
+
+// Pass-1 finalisation: reduce the block partials per column; GLOBAL scope pools all columns.
+__global__ __launch_bounds__(CAL_THREADS) void calib_stats_kernel(
+    int G, int d, int64_t n, int scope, const float *__restrict__ pmn, const float *__restrict__ pmx,
+    const double *__restrict__ psum, float *__restrict__ mn_out, float *__restrict__ mx_out,
+    double *__restrict__ mu_out)
+{
+    __shared__ double shd[CAL_THREADS];
+    __shared__ float shf[CAL_THREADS];
+    float gmn = INFINITY, gmx = -INFINITY;
+    double gsum = 0.0;
+    for (int c = threadIdx.x; c < d; c += CAL_THREADS) {
+        float mn = INFINITY, mx = -INFINITY;
+        double sum = 0.0;
+        for (int g = 0; g < G; ++g) {
+            const int64_t o = (int64_t)g * d + c;
+            mn = fminf(mn, pmn[o]);
+            mx = fmaxf(mx, pmx[o]);
+            sum += psum[o];
+        }
+        if (scope == LPQ_SCOPE_PER_FEATURE) {
+            mn_out[c] = mn;
+            mx_out[c] = mx;
+            mu_out[c] = sum / (double)n;
+        }
+        gmn = fminf(gmn, mn);
+        gmx = fmaxf(gmx, mx);
+        gsum += sum;
+    }
+    if (scope == LPQ_SCOPE_GLOBAL) {
+        gmn = block_min(gmn, shf);
+        gmx = -block_min(-gmx, shf);
+        gsum = block_sum(gsum, shd);
+        const double mu = gsum / ((double)n * (double)d);
+        for (int c = threadIdx.x; c < d; c += CAL_THREADS) {
+            mn_out[c] = gmn;
+            mx_out[c] = gmx;
+            mu_out[c] = mu;
+        }
+    }
+}
+
+__device__ inline float derive_m(float sb, float se, int bits)
+{
+    const double width = (double)se - (double)sb;
+    return (width > 0.0) ? (float)(ldexp(1.0, bits) / width) : 0.0f;
+}
+
+// Constants of Equation 1 from the statistics (Sections 3.2, 4.1, 4.2).
+__global__ __launch_bounds__(CAL_THREADS) void calib_params_kernel(
+    int G, int d, int64_t n, int bits, int mode, int scope, double sigma_mult,
+    const float *__restrict__ mn, const float *__restrict__ mx, const double *__restrict__ mu,
+    const double *__restrict__ pss, float *__restrict__ params)
+{
+    __shared__ double shd[CAL_THREADS];
+    double gss = 0.0;
+    if (mode == LPQ_CALIB_GAUSS && scope == LPQ_SCOPE_GLOBAL) {
+        for (int c = threadIdx.x; c < d; c += CAL_THREADS)
+            for (int g = 0; g < G; ++g) gss += pss[(int64_t)g * d + c];
+        gss = block_sum(gss, shd);
+    }
+    for (int c = threadIdx.x; c < d; c += CAL_THREADS) {
+        float k, sb, se;
+        if (mode == LPQ_CALIB_GAUSS) {
+            double ss = gss, cnt = (double)n * (double)d;
+            if (scope == LPQ_SCOPE_PER_FEATURE) {
+                ss = 0.0;
+                for (int g = 0; g < G; ++g) ss += pss[(int64_t)g * d + c];
+                cnt = (double)n;
+            }
+            const double sigma = sqrt(ss / cnt);
+            sb = (float)(mu[c] - sigma_mult * sigma);
+            se = (float)(mu[c] + sigma_mult * sigma);
+            k = (float)mu[c];
+        } else if (mode == LPQ_CALIB_ABSMAX) {
+            const double amax = fmax(fabs((double)mn[c]), fabs((double)mx[c]));
+            sb = (float)(-amax);
+            se = (float)amax;
+            k = 0.0f;
+        } else {
+            sb = mn[c];
+            se = mx[c];
+            k = (float)(((double)mn[c] + (double)mx[c]) / 2.0);
+        }
+        params[c] = k;
+        params[d + c] = sb;
+        params[2 * d + c] = se;
+        params[3 * d + c] = derive_m(sb, se, bits);
+    }
+}
+
+__global__ void derive_m_kernel(float *params, int d, int bits)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c < d) params[3 * d + c] = derive_m(params[d + c], params[2 * d + c], bits);
+}
+
+// ------------------------------------------------------------------------- encode --
+// Equation 1 for one value, in binary32 with separately rounded subtract and multiply.
+__device__ inline int quantize_one(float x, float k, float sb, float se, float m, int half)
+{
+    const float t = __fmul_rn(__fsub_rn(x, k), m);
+    const float f = floorf(t);
+    int r = (f >= (float)half) ? half : (f <= (float)(-half)) ? -half : (f == f) ? (int)f : 0;
+    r = (x > se) ? half : r;
+    r = (x < sb) ? -half : r;
+    r = (x != x) ? 0 : r;
+    r = (se > sb) ? r : 0;
+    return r < 127 ? r : 127;
+}
+
+constexpr int ENC_THREADS = 256;
+constexpr int ENC_UNROLL = 4;
+
+// TPR lanes share one row (4 columns each per step); a wave covers 64/TPR rows at once and
+// ENC_UNROLL such row groups are in flight.  VEC: rows are 16-byte aligned in x and 4-byte
+// aligned in codes, so float4 loads and packed 32-bit stores are used.
+template <int TPR, bool VEC>
+__global__ __launch_bounds__(ENC_THREADS) void encode_kernel(
+    QuantParams qp, const float *__restrict__ x, int64_t n, int64_t ld, int8_t *__restrict__ codes,
+    int64_t ldc, int zero_pad_to, int32_t *__restrict__ norms)
+{
+    constexpr int RPW = 64 / TPR;
+    const int lane = threadIdx.x & 63;
+    const int sub = lane % TPR, rsel = lane / TPR;
+    const int d = qp.d, half = 1 << (qp.bits - 1);
+    const int ngroups = (d + 3) >> 2;              // 4-column groups holding data
+    const int pgroups = (zero_pad_to > d) ? ((zero_pad_to + 3) >> 2) : ngroups;
+    const int64_t wave_id = ((int64_t)blockIdx.x * ENC_THREADS + threadIdx.x) >> 6;
+    const int64_t nwaves = ((int64_t)gridDim.x * ENC_THREADS) >> 6;
+    const bool single = pgroups <= TPR;            // each lane owns one column group: hoist constants
+
+    float ck[4] = {0, 0, 0, 0}, cb[4] = {0, 0, 0, 0}, ce[4] = {0, 0, 0, 0}, cm[4] = {0, 0, 0, 0};
+    if (single) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = 4 * sub + j;
+            if (c < d) { ck[j] = qp.k[c]; cb[j] = qp.sb[c]; ce[j] = qp.se[c]; cm[j] = qp.m[c]; }
+        }
+    }
+    for (int64_t base = wave_id * RPW * ENC_UNROLL; base < n; base += nwaves * RPW * ENC_UNROLL) {
+        int acc[ENC_UNROLL];
+#pragma unroll
+        for (int u = 0; u < ENC_UNROLL; ++u) acc[u] = 0;
+        for (int g0 = 0; g0 < pgroups; g0 += TPR) {
+            const int g = g0 + sub;
+            const int c0 = 4 * g;
+            if (!single) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int c = c0 + j;
+                    const bool in = c < d;
+                    ck[j] = in ? qp.k[c] : 0.f; cb[j] = in ? qp.sb[c] : 0.f;
+                    ce[j] = in ? qp.se[c] : 0.f; cm[j] = in ? qp.m[c] : 0.f;
+                }
+            }
+            float v[ENC_UNROLL][4];
+#pragma unroll
+            for (int u = 0; u < ENC_UNROLL; ++u) {
+                const int64_t r = base + u * RPW + rsel;
+                const bool rowok = r < n && g < ngroups;
+                if (VEC && rowok && c0 + 3 < d) {
+                    const float4 t = *reinterpret_cast<const float4 *>(x + r * ld + c0);
+                    v[u][0] = t.x; v[u][1] = t.y; v[u][2] = t.z; v[u][3] = t.w;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) v[u][j] = (rowok && c0 + j < d) ? x[r * ld + c0 + j] : 0.0f;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < ENC_UNROLL; ++u) {
+                const int64_t r = base + u * RPW + rsel;
+                if (r < n && g < pgroups) {
+                    int q[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        q[j] = (c0 + j < d) ? quantize_one(v[u][j], ck[j], cb[j], ce[j], cm[j], half) : 0;
+                        acc[u] += q[j] * q[j];
+                    }
+                    const int lim = (zero_pad_to > d) ? zero_pad_to : d;
+                    if (VEC && c0 + 3 < lim) {
+                        const uint32_t w = (uint32_t)(q[0] & 255) | ((uint32_t)(q[1] & 255) << 8) |
+                                           ((uint32_t)(q[2] & 255) << 16) | ((uint32_t)(q[3] & 255) << 24);
+                        *reinterpret_cast<uint32_t *>(codes + r * ldc + c0) = w;
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (c0 + j < lim) codes[r * ldc + c0 + j] = (int8_t)q[j];
+                    }
+                }
+            }
+        }
+        if (norms) {
+#pragma unroll
+            for (int u = 0; u < ENC_UNROLL; ++u) {
+                int s = acc[u];
+#pragma unroll
+                for (int o = TPR / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+                const int64_t r = base + u * RPW + rsel;
+                if (sub == 0 && r < n) norms[r] = s;
+            }
+        }
+    }
+}
+
+// Copy int8 rows into zero-padded rows and compute their norms; 16 lanes per row.
+__global__ __launch_bounds__(256) void repack_i8_kernel(
+    const int8_t *__restrict__ src, int64_t n, int64_t ld, int d, int8_t *__restrict__ dst,
+    int64_t ldd, int d_pad, int32_t *__restrict__ norms)
+{
+    const int sub = threadIdx.x & 15;
+    const int64_t r = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 4;
+    int s = 0;
+    if (r < n) {
+        for (int c = sub; c < d_pad; c += 16) {
+            const int v = (c < d) ? (int)src[r * ld + c] : 0;
+            dst[r * ldd + c] = (int8_t)v;
+            s += v * v;
+        }
+    }
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (r < n && sub == 0 && norms) norms[r] = s;
+}
+
+__global__ __launch_bounds__(256) void zero_words_kernel(uint32_t *p, size_t words)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words; i += (size_t)gridDim.x * 256) p[i] = 0u;
+}
+
+// One thread per 32-item word: accumulator seeds and norm parities for items
+// [32w, 32w + 32); items at or beyond n_total get the padding seed.
+__global__ __launch_bounds__(256) void item_aux_kernel(
+    const int32_t *__restrict__ norms, int64_t w0, int64_t w1, int64_t n_total,
+    int32_t *__restrict__ cinit, uint32_t *__restrict__ parity)
+{
+    const int64_t w = w0 + (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (w >= w1) return;
+    uint32_t bits = 0;
+    for (int r = 0; r < 32; ++r) {
+        const int64_t j = w * 32 + r;
+        int32_t ci = CINIT_PAD;
+        if (j < n_total) {
+            const int32_t nx = norms ? norms[j] : 0;
+            ci = -((nx + 1) >> 1);
+            bits |= (uint32_t)(nx & 1) << r;
+        }
+        cinit[j] = ci;
+    }
+    parity[w] = bits;
+}
+
+}  // namespace
+
+size_t calib_scratch_bytes(int d)
+{
+    const size_t G = calib_blocks(d);
+    return G * d * (sizeof(double) + 2 * sizeof(float)) + (size_t)d * (sizeof(double) + 2 * sizeof(float)) + 256;
+}
+
+hipError_t launch_calibrate(const float *x, int64_t n, int64_t ld, int d, int bits, int mode, int scope,
+                            double sigma_mult, void *scratch, float *params_out, int *nonfinite_flag,
+                            hipStream_t st)
+{
+    const int G = calib_blocks(d);
+    CalibScratch s = carve(scratch, d);
+    const int64_t rpb = ceil_div(n, G);
+    hipError_t e = hipMemsetAsync(nonfinite_flag, 0, sizeof(int), st);
+    if (e != hipSuccess) return e;
+    calib_reduce_kernel<1><<<G, CAL_THREADS, 0, st>>>(x, n, ld, d, rpb, nullptr, s.pmn, s.pmx, s.psum,
+                                                      nonfinite_flag);
+    calib_stats_kernel<<<1, CAL_THREADS, 0, st>>>(G, d, n, scope, s.pmn, s.pmx, s.psum, s.mn, s.mx, s.mu);
+    if (mode == LPQ_CALIB_GAUSS)
+        calib_reduce_kernel<2><<<G, CAL_THREADS, 0, st>>>(x, n, ld, d, rpb, s.mu, nullptr, nullptr, s.psum,
+                                                          nonfinite_flag);
+    calib_params_kernel<<<1, CAL_THREADS, 0, st>>>(G, d, n, bits, mode, scope, sigma_mult, s.mn, s.mx, s.mu,
+                                                   s.psum, params_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_derive_m(float *params, int d, int bits, hipStream_t st)
+{
+    derive_m_kernel<<<(d + 255) / 256, 256, 0, st>>>(params, d, bits);
+    return hipGetLastError();
+}
+
+template <int TPR>
+static void encode_dispatch(bool vec, int blocks, hipStream_t st, const QuantParams &qp, const float *x,
+                            int64_t n, int64_t ld, int8_t *codes, int64_t ldc, int zero_pad_to, int32_t *norms)
+{
+    if (vec)
+        encode_kernel<TPR, true><<<blocks, ENC_THREADS, 0, st>>>(qp, x, n, ld, codes, ldc, zero_pad_to, norms);
+    else
+        encode_kernel<TPR, false><<<blocks, ENC_THREADS, 0, st>>>(qp, x, n, ld, codes, ldc, zero_pad_to, norms);
+}
+
+hipError_t launch_encode(const QuantParams &qp, const float *x, int64_t n, int64_t ld, int8_t *codes,
+                         int64_t ldc, int zero_pad_to, int32_t *norms, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    const int lim = zero_pad_to > qp.d ? zero_pad_to : qp.d;
+    const int groups = (lim + 3) / 4;
+    int tpr = 1;
+    while (tpr < groups && tpr < 64) tpr <<= 1;
+    const bool vec = ((uintptr_t)x % 16 == 0) && (ld % 4 == 0) && ((uintptr_t)codes % 4 == 0) && (ldc % 4 == 0);
+    const int rpw = 64 / tpr;
+    int64_t waves = ceil_div(n, (int64_t)rpw * ENC_UNROLL);
+    int64_t blocks = ceil_div(waves, ENC_THREADS / 64);
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    switch (tpr) {
+    case 1: encode_dispatch<1>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms); break;
+    case 2: encode_dispatch<2>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms); break;
+    case 4: encode_dispatch<4>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms); break;
+    case 8: encode_dispatch<8>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms); break;
+    case 16: encode_dispatch<16>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms); break;
+    case 32: encode_dispatch<32>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms); break;
+    default: encode_dispatch<64>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_repack_i8(const int8_t *src, int64_t n, int64_t ld, int d, int8_t *dst, int64_t ldd,
+                            int d_pad, int32_t *norms, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    const int64_t blocks = ceil_div(n * 16, 256);
+    repack_i8_kernel<<<(unsigned)blocks, 256, 0, st>>>(src, n, ld, d, dst, ldd, d_pad, norms);
+    return hipGetLastError();
+}
+
+hipError_t launch_zero_bytes(void *p, size_t bytes, hipStream_t st)
+{
+    const size_t words = bytes / 4;
+    if (!words) return hipSuccess;
+    size_t blocks = (words + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    zero_words_kernel<<<(unsigned)blocks, 256, 0, st>>>((uint32_t *)p, words);
+    return hipGetLastError();
+}
+
+hipError_t launch_item_aux(const int32_t *norms, int64_t row0, int64_t n_total, int32_t *cinit,
+                           uint32_t *parity, hipStream_t st)
+{
+    const int64_t w0 = row0 / 32, w1 = ceil_div(n_total, 32);
+    if (w1 <= w0) return hipSuccess;
+    const int64_t blocks = ceil_div(w1 - w0, 256);
+    item_aux_kernel<<<(unsigned)blocks, 256, 0, st>>>(norms, w0, w1, n_total, cinit, parity);
+    return hipGetLastError();
+}
+
+}  // namespace lpq

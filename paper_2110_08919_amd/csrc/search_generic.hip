@@ -1,0 +1,141 @@
+// Generic integer search kernel: any padded dimension, any k <= MAX_K.  One workgroup scans
+// one corpus split for one query with 4-way int8 dot products, keeps the candidates that
+// beat the running k-th best in an LDS buffer and compacts the buffer by a bitonic sort
+// whenever it could overflow.  It is the fallback for shapes the matrix-core kernel does
+// not take and an independent second implementation of the same result.
+#include "block_select.h"
+#include "lpq_internal.h"
+
+namespace lpq {
+
+namespace {
+
+constexpr int GEN_THREADS = 256;
+constexpr int GEN_ROWS = GEN_THREADS / 8;  // rows per step: 8 lanes share a row
+
+__global__ __launch_bounds__(GEN_THREADS) void search_generic_kernel(
+    SearchArgs a, int64_t row0, int64_t row1, int S, int64_t split_rows, const cand_t *__restrict__ seeds,
+    cand_t *__restrict__ lists, int cap)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    cand_t *buf = reinterpret_cast<cand_t *>(smem);
+    uint4 *qs = reinterpret_cast<uint4 *>(buf + cap);
+    __shared__ int s_count;
+    __shared__ cand_t s_thr;
+
+    const int64_t q = blockIdx.x / S;
+    const int s = blockIdx.x % S;
+    const int chunks = a.d_pad >> 4;  // 16-byte chunks per row
+    const int64_t rs = row0 + (int64_t)s * split_rows;
+    const int64_t re = (rs + split_rows < row1) ? rs + split_rows : row1;
+    const bool l2 = a.metric == LPQ_METRIC_L2SQ;
+
+    for (int c = threadIdx.x; c < chunks; c += GEN_THREADS)
+        qs[c] = reinterpret_cast<const uint4 *>(a.qcodes + q * a.d_pad)[c];
+    for (int i = threadIdx.x; i < cap; i += GEN_THREADS) buf[i] = CAND_NONE;
+    if (threadIdx.x == 0) {
+        s_count = 0;
+        s_thr = seeds ? seeds[q] : CAND_NONE;
+    }
+    __syncthreads();
+
+    const int sub = threadIdx.x & 7, grp = threadIdx.x >> 3;
+    for (int64_t base = rs; base < re; base += GEN_ROWS) {
+        const int64_t row = base + grp;
+        int dot = 0;
+        if (row < re) {
+            const uint4 *xr = reinterpret_cast<const uint4 *>(a.codes + row * a.d_pad);
+            for (int c = sub; c < chunks; c += 8) {
+                const uint4 xv = xr[c], qv = qs[c];
+                dot = __builtin_amdgcn_sdot4((int)xv.x, (int)qv.x, dot, false);
+                dot = __builtin_amdgcn_sdot4((int)xv.y, (int)qv.y, dot, false);
+                dot = __builtin_amdgcn_sdot4((int)xv.z, (int)qv.z, dot, false);
+                dot = __builtin_amdgcn_sdot4((int)xv.w, (int)qv.w, dot, false);
+            }
+        }
+        dot += __shfl_xor(dot, 4, 64);
+        dot += __shfl_xor(dot, 2, 64);
+        dot += __shfl_xor(dot, 1, 64);
+        if (sub == 0 && row < re) {
+            const int32_t key = (l2 ? a.norms[row] : 0) - 2 * dot;  // see cand_t
+            const cand_t c = make_cand(key, (uint32_t)row);
+            if (c < s_thr) {
+                const int pos = atomicAdd(&s_count, 1);
+                buf[pos] = c;
+            }
+        }
+        __syncthreads();
+        block_compact_if_full(buf, cap, a.k, GEN_ROWS, &s_count, &s_thr);
+    }
+    block_bitonic_sort(buf, cap);
+    cand_t *out = lists + ((int64_t)q * S + s) * a.k;
+    for (int i = threadIdx.x; i < a.k; i += GEN_THREADS) out[i] = buf[i];
+}
+
+// One workgroup per query: sort all candidates of its P lists (plus an optional extra list).
+__global__ __launch_bounds__(256) void merge_kernel(
+    const cand_t *__restrict__ lists, int P, int k, const cand_t *__restrict__ extra, int cap,
+    cand_t *__restrict__ out_lists, cand_t *__restrict__ seeds_out, int32_t *__restrict__ ids,
+    int32_t *__restrict__ dists, const int32_t *__restrict__ qnorms, int metric)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    cand_t *buf = reinterpret_cast<cand_t *>(smem);
+    const int64_t q = blockIdx.x;
+    const int m = P * k;
+    for (int i = threadIdx.x; i < cap; i += 256) {
+        cand_t c = CAND_NONE;
+        if (i < m) c = lists[q * m + i];
+        else if (extra && i < m + k) c = extra[q * k + (i - m)];
+        buf[i] = c;
+    }
+    __syncthreads();
+    block_bitonic_sort(buf, cap);
+    for (int i = threadIdx.x; i < k; i += 256) {
+        const cand_t c = buf[i];
+        if (out_lists) out_lists[q * k + i] = c;
+        if (ids) {
+            const int32_t key = cand_key(c);
+            ids[q * k + i] = (c == CAND_NONE) ? -1 : (int32_t)cand_id(c);
+            int32_t v;
+            if (metric == MODE_I8_L2) v = key + qnorms[q];
+            else if (metric == MODE_I8_IP) v = -(key / 2);
+            else {
+                const float f = sortable_to_float(key);
+                v = __float_as_int(metric == MODE_F32_L2 ? f : -f);
+            }
+            dists[q * k + i] = v;
+        }
+    }
+    if (seeds_out && threadIdx.x == 0) seeds_out[q] = buf[k - 1];
+}
+
+}  // namespace
+
+int merge_max_lists(int k) { return 4096 / k - 1; }
+
+hipError_t launch_search_generic(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds,
+                                 cand_t *lists, hipStream_t st)
+{
+    if (a.nq <= 0 || row1 <= row0) return hipSuccess;
+    const int cap = next_pow2((2 * a.k > a.k + 2 * GEN_ROWS) ? 2 * a.k : a.k + 2 * GEN_ROWS);
+    const int64_t split_rows = round_up(ceil_div(row1 - row0, S), GEN_ROWS);
+    const size_t shmem = (size_t)cap * sizeof(cand_t) + (size_t)a.d_pad;
+    search_generic_kernel<<<(unsigned)(a.nq * S), GEN_THREADS, shmem, st>>>(a, row0, row1, S, split_rows,
+                                                                              seeds, lists, cap);
+    return hipGetLastError();
+}
+
+hipError_t launch_merge(const cand_t *lists, int64_t nq, int P, int k, const cand_t *extra_lists,
+                        cand_t *out_lists, cand_t *seeds_out, int32_t *ids, int32_t *dists,
+                        const int32_t *qnorms, int metric, hipStream_t st)
+{
+    if (nq <= 0) return hipSuccess;
+    const int total = P * k + (extra_lists ? k : 0);
+    const int cap = next_pow2(total < 2 ? 2 : total);
+    if (cap > 4096) return hipErrorInvalidValue;
+    merge_kernel<<<(unsigned)nq, 256, (size_t)cap * sizeof(cand_t), st>>>(
+        lists, P, k, extra_lists, cap, out_lists, seeds_out, ids, dists, qnorms, metric);
+    return hipGetLastError();
+}
+
+}  // namespace lpq

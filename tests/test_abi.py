@@ -1,0 +1,72 @@
+"""The C-ABI library loads without a GPU and exports every function lpq.h declares;
+argument checks that precede any device work return the documented codes."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2110_08919_amd import build, lpq
+    if not os.path.exists(lpq.LIB_PATH):
+        build.build()
+    return lpq.lib()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "lpq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lpq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = _declared_functions()
+    assert len(names) >= 20
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_binding_covers_every_declared_symbol(L):
+    from paper_2110_08919_amd import lpq
+    for n in _declared_functions():
+        assert getattr(L, n).argtypes is not None, f"{n} has no signature in the binding"
+
+
+def test_argument_checks_without_device(L):
+    from paper_2110_08919_amd import lpq
+    h = C.c_void_p()
+    assert L.lpq_quantizer_create(None, 8, 8) == lpq.EINVAL
+    assert L.lpq_quantizer_create(C.byref(h), 0, 8) == lpq.EINVAL
+    assert L.lpq_quantizer_create(C.byref(h), 8, 0) == lpq.EINVAL
+    assert L.lpq_quantizer_create(C.byref(h), 8, 9) == lpq.EINVAL
+    assert b"bits" in L.lpq_last_error()
+    assert L.lpq_quantizer_create(C.byref(h), 1 << 20, 8) == lpq.ERANGE
+    assert h.value is None                                    # never written on failure
+    assert L.lpq_index_size(None) == -1
+    assert L.lpq_index_create(None, None, 10) == lpq.EINVAL
+    assert L.lpq_search_workspace_bytes(None, 10, 10, 0) == 0
+    assert L.lpq_search(None, None, 1, 1, 1, 0, None, None, None, 0, None) == lpq.EINVAL
+    assert L.lpq_search_f32(None, 10, 4, None, 1, 4, 4, 11, 0, None, None, None, 0, None) == lpq.ERANGE
+    assert L.lpq_search_f32(None, 10, 4, None, 1, 4, 4, 5, 7, None, None, None, 0, None) == lpq.EINVAL
+    assert L.lpq_search_f32(None, 10, 4, None, 0, 4, 4, 5, 0, None, None, None, 0, None) == lpq.OK  # nq = 0
+    assert L.lpq_search_f32_workspace_bytes(0, 1, 4, 1) == 0
+    assert L.lpq_set_tuning(99, 0) == lpq.EINVAL
+    assert L.lpq_set_tuning(lpq.TUNE_SPLITS, 0) == lpq.OK
+    assert L.lpq_profile_read(None, None) == lpq.EINVAL
+    L.lpq_quantizer_destroy(None)
+    L.lpq_index_destroy(None)
+
+
+def test_product_path_does_not_import_the_oracle():
+    """The package (binding, generators, build) never touches oracle/."""
+    pkg = os.path.join(ROOT, "paper_2110_08919_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle\b", src, flags=re.M), f
+                assert "lpq_oracle" not in src and "lpqo_" not in src, f

@@ -1,0 +1,307 @@
+"""Parity of the HIP library against the CPU oracle, through the C ABI, on the same
+seeded inputs: bit-exact codes, norms, ids and int32 distances; fp32 exact search within
+1e-5 relative on distances.  Needs a real MI355X."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2110_08919_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL_F32 = 1e-5     # stated tolerance of the fp32 exact-search path, on distances
+CALIB_REL_TOL = 1e-6   # Gaussian statistics: the reduction order differs from the oracle's
+
+
+@pytest.fixture(scope="module")
+def lpq():
+    from paper_2110_08919_amd import lpq as m
+    assert torch.cuda.is_available(), "no GPU visible"
+    m.lib()                                    # fails loudly if liblpq.so is missing
+    return m
+
+
+def dev(a):
+    return torch.as_tensor(a).cuda()
+
+
+def _oracle_quant(oracle, gq):
+    """An oracle quantizer holding exactly the constants of the GPU one."""
+    k, sb, se, m = gq.get_params()
+    oq = oracle.Quantizer(gq.d, gq.bits).set_params(k, sb, se)
+    assert np.array_equal(oq.m, m), "derived multiplier differs"
+    return oq
+
+
+# ------------------------------------------------------------------ calibrate + encode
+@pytest.mark.parametrize("mode,scope", [("minmax", "per_feature"), ("minmax", "global"),
+                                        ("absmax", "per_feature"), ("absmax", "global")])
+@pytest.mark.parametrize("wl", ["tiny", "skewed", "aniso"])
+def test_calibrate_range_modes_bit_exact(lpq, oracle, wl, mode, scope):
+    w = {"tiny": synth.TINY.scaled(n=5000), "skewed": synth.SKEWED_1M.scaled(n=7001),
+         "aniso": synth.ANISO_1M2.scaled(n=3333)}[wl]
+    x = w.corpus()
+    gq = lpq.Quantizer(w.d, 8).calibrate(x.cuda(), mode, scope)
+    oq = oracle.Quantizer(w.d, 8).calibrate(x.numpy(), mode, scope)
+    k, sb, se, m = gq.get_params()
+    assert np.array_equal(k, oq.k) and np.array_equal(sb, oq.sb)
+    assert np.array_equal(se, oq.se) and np.array_equal(m, oq.m)
+
+
+@pytest.mark.parametrize("scope", ["per_feature", "global"])
+def test_calibrate_gauss_within_tolerance_then_codes_exact(lpq, oracle, scope):
+    w = synth.SCALED_10M.scaled(n=20011)
+    x = w.corpus()
+    gq = lpq.Quantizer(w.d, 8).calibrate(x.cuda(), "gauss", scope, 2.0)
+    oq = oracle.Quantizer(w.d, 8).calibrate(x.numpy(), "gauss", scope, 2.0)
+    k, sb, se, m = gq.get_params()
+    np.testing.assert_allclose(sb, oq.sb, rtol=CALIB_REL_TOL, atol=1e-9)
+    np.testing.assert_allclose(se, oq.se, rtol=CALIB_REL_TOL, atol=1e-9)
+    np.testing.assert_allclose(k, oq.k, rtol=CALIB_REL_TOL, atol=1e-9)
+    np.testing.assert_allclose(m, oq.m, rtol=CALIB_REL_TOL)
+    oq2 = _oracle_quant(oracle, gq)               # identical constants on both sides
+    codes, norms = gq.encode(x.cuda(), with_norms=True)
+    ocodes, onorms = oq2.encode(x.numpy(), with_norms=True)
+    assert np.array_equal(codes.cpu().numpy(), ocodes)
+    assert np.array_equal(norms.cpu().numpy(), onorms)
+
+
+def test_calibrate_rejects_non_finite(lpq):
+    x = synth.TINY.scaled(n=1000).corpus()
+    gq = lpq.Quantizer(128, 8).calibrate(x.cuda(), "minmax", "per_feature")
+    before = gq.get_params()
+    x[777, 5] = float("nan")
+    with pytest.raises(lpq.LpqError) as e:
+        gq.calibrate(x.cuda(), "minmax", "per_feature")
+    assert e.value.code == lpq.ENONFINITE
+    x[777, 5] = float("inf")
+    with pytest.raises(lpq.LpqError):
+        gq.calibrate(x.cuda(), "gauss", "global")
+    after = gq.get_params()
+    assert all(np.array_equal(a, b) for a, b in zip(before, after))   # previous state kept
+
+
+@pytest.mark.parametrize("d,bits", [(128, 8), (100, 8), (96, 5), (256, 8), (1, 3), (7, 8), (33, 2), (300, 8), (1030, 4)])
+def test_encode_bit_exact_many_shapes(lpq, oracle, d, bits):
+    rng = np.random.default_rng(d * 10 + bits)
+    n = 1237
+    x = (rng.normal(size=(n, d)) * rng.uniform(0.01, 5, size=d) + rng.normal(size=d)).astype(np.float32)
+    x[3, 0] = np.nan
+    x[4, d - 1] = np.inf
+    x[5, d // 2] = -np.inf
+    k = rng.normal(size=d).astype(np.float32)
+    sb = (k - rng.uniform(0.5, 4, size=d)).astype(np.float32)
+    se = (k + rng.uniform(0.5, 4, size=d)).astype(np.float32)
+    if d > 2:
+        se[2] = sb[2]                                   # an empty range: codes 0
+    x[10:20] = sb[None, :]                              # exactly on the lower edge
+    x[20:30] = se[None, :]                              # exactly on the upper edge
+    gq = lpq.Quantizer(d, bits).set_params(k, sb, se)
+    oq = _oracle_quant(oracle, gq)
+    ocodes, onorms = oq.encode(x, with_norms=True)
+    codes, norms = gq.encode(dev(x), with_norms=True)
+    assert np.array_equal(codes.cpu().numpy(), ocodes)
+    assert np.array_equal(norms.cpu().numpy(), onorms)
+    # strided input and output (ld > d), unaligned for the vector path
+    wide = np.full((n, d + 3), 7.0, np.float32)
+    wide[:, :d] = x
+    codes2 = gq.encode(dev(wide)[:, :d], ld_codes=d + 5)
+    assert np.array_equal(codes2.cpu().numpy(), ocodes)
+
+
+def test_worked_example_on_gpu(lpq):
+    gq = lpq.Quantizer(1, 3).set_params([0.0], [-4.0], [4.0])
+    codes = gq.encode(dev(np.array([[1.23], [2.34], [3.09], [1.4e7]], np.float32)))
+    assert codes.cpu().numpy()[:, 0].tolist() == [1, 2, 3, 4]
+
+
+# ------------------------------------------------------------------ int8 search
+def _run_search_case(lpq, oracle, w, k, metric, mode, scope, path, nq=None, threads=16, bits=8):
+    x, q = w.corpus(), w.queries()
+    if nq is not None:
+        q = q[:nq]
+    xd, qd = x.cuda(), q.cuda()
+    gq = lpq.Quantizer(w.d, bits).calibrate(xd, mode, scope)
+    idx = lpq.Index(gq, w.n).add_f32(xd)
+    assert idx.size == w.n
+    lpq.set_tuning(lpq.TUNE_PATH, path)
+    try:
+        ids, dists = idx.search(qd, k, metric)
+        torch.cuda.synchronize()
+    finally:
+        lpq.set_tuning(lpq.TUNE_PATH, 0)
+    oq = _oracle_quant(oracle, gq)
+    ocodes, oqcodes = oq.encode(x.numpy()), oq.encode(q.numpy())
+    oids, odists = oracle.search_i8(ocodes, oqcodes, k, metric, threads=threads)
+    assert np.array_equal(dists.cpu().numpy(), odists)
+    assert np.array_equal(ids.cpu().numpy(), oids)
+    return idx, gq, ids, dists
+
+
+PATHS = [1, 2]   # generic kernel, matrix-core kernel (falls back when a shape is unsupported)
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_search_tiny_config_full(lpq, oracle, path):
+    """Config 1 in full: 10 000 x 128 bimodal, 100 queries, L2, k = 10, per-feature min/max."""
+    _run_search_case(lpq, oracle, synth.TINY, 10, "l2sq", "minmax", "per_feature", path)
+
+
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("name,n,nq,k,metric,mode,scope", [
+    ("skewed", 20011, 300, 10, "l2sq", "minmax", "global"),       # ragged tail, several tiles
+    ("skewed", 9000, 70, 100, "l2sq", "minmax", "per_feature"),
+    ("aniso", 12345, 130, 10, "ip", "absmax", "global"),          # d = 100 -> padded to 128
+    ("scaled", 8200, 257, 10, "l2sq", "absmax", "global"),        # d = 96
+    ("product", 5000, 33, 100, "ip", "absmax", "per_feature"),    # d = 256
+    ("tiny", 300, 5, 300, "l2sq", "minmax", "per_feature"),       # k = n
+    ("tiny", 40, 3, 1, "ip", "absmax", "global"),                 # fewer items than one tile
+])
+def test_search_parity_shapes(lpq, oracle, path, name, n, nq, k, metric, mode, scope):
+    base = {"skewed": synth.SKEWED_1M, "aniso": synth.ANISO_1M2, "scaled": synth.SCALED_10M,
+            "product": synth.PRODUCT_100M, "tiny": synth.TINY}[name]
+    _run_search_case(lpq, oracle, base.scaled(n=n, nq=nq), k, metric, mode, scope, path)
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_search_many_ties_low_bits(lpq, oracle, path):
+    """3-bit codes in 8 dimensions: almost every distance is tied; order must follow ids."""
+    w = synth.TINY.scaled(n=6000, nq=64)
+    x, q = w.corpus()[:, :8].contiguous(), w.queries()[:, :8].contiguous()
+    gq = lpq.Quantizer(8, 3).calibrate(x.cuda(), "absmax", "global")
+    idx = lpq.Index(gq, 6000).add_f32(x.cuda())
+    oq = _oracle_quant(oracle, gq)
+    oc, oqc = oq.encode(x.numpy()), oq.encode(q.numpy())
+    for metric in ("l2sq", "ip"):
+        lpq.set_tuning(lpq.TUNE_PATH, path)
+        try:
+            ids, dists = idx.search(q.cuda(), 50, metric)
+        finally:
+            lpq.set_tuning(lpq.TUNE_PATH, 0)
+        oids, odists = oracle.search_i8(oc, oqc, 50, metric, threads=8)
+        assert np.array_equal(ids.cpu().numpy(), oids) and np.array_equal(dists.cpu().numpy(), odists)
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_search_adversarial_order_and_duplicates(lpq, oracle, path):
+    """Items sorted from far to near (every item beats the running threshold), plus blocks
+    of identical items: the worst case for threshold filtering and for tie handling."""
+    rng = np.random.default_rng(11)
+    d, n = 64, 5000
+    q = rng.integers(-20, 20, size=(40, d)).astype(np.int8)
+    steps = np.linspace(100, 0, n).astype(np.int32)
+    c = np.clip(q[0][None, :].astype(np.int32) + steps[:, None] * ((np.arange(d) % 2) * 2 - 1)[None, :], -128, 127).astype(np.int8)
+    c[1000:1300] = c[999]
+    gq = lpq.Quantizer(d, 8).set_params(np.zeros(d), np.full(d, -128.0), np.full(d, 128.0))
+    idx = lpq.Index(gq, n).add_i8(dev(c))
+    lpq.set_tuning(lpq.TUNE_PATH, path)
+    try:
+        for metric, k in (("l2sq", 10), ("ip", 37)):
+            ids, dists = idx.search(dev(q), k, metric)        # int8 queries -> lpq_search_i8
+            oids, odists = oracle.search_i8(c, q, k, metric, threads=8)
+            assert np.array_equal(ids.cpu().numpy(), oids) and np.array_equal(dists.cpu().numpy(), odists)
+    finally:
+        lpq.set_tuning(lpq.TUNE_PATH, 0)
+
+
+def test_search_extreme_codes_no_overflow(lpq, oracle):
+    d, n = 512, 600
+    rng = np.random.default_rng(12)
+    c = rng.choice(np.array([-128, 127], np.int8), size=(n, d))
+    q = rng.choice(np.array([-128, 127], np.int8), size=(9, d))
+    gq = lpq.Quantizer(d, 8).set_params(np.zeros(d), np.full(d, -128.0), np.full(d, 128.0))
+    idx = lpq.Index(gq, n).add_i8(dev(c))
+    for metric in ("l2sq", "ip"):
+        ids, dists = idx.search(dev(q), 20, metric)
+        oids, odists = oracle.search_i8(c, q, 20, metric, threads=4)
+        assert np.array_equal(ids.cpu().numpy(), oids) and np.array_equal(dists.cpu().numpy(), odists)
+
+
+def test_incremental_add_and_determinism(lpq, oracle):
+    w = synth.SKEWED_1M.scaled(n=5003, nq=50)
+    x, q = w.corpus().cuda(), w.queries().cuda()
+    gq = lpq.Quantizer(w.d, 8).calibrate(x, "minmax", "global")
+    one = lpq.Index(gq, w.n).add_f32(x)
+    parts = lpq.Index(gq, w.n + 10)
+    for a, b in ((0, 17), (17, 1000), (1000, 1001), (1001, 5003)):
+        parts.add_f32(x[a:b])
+    r1, r2 = one.search(q, 10, "l2sq"), parts.search(q, 10, "l2sq")
+    r3 = one.search(q, 10, "l2sq")
+    for a, b in zip(r1, r2):
+        assert torch.equal(a, b)
+    for a, b in zip(r1, r3):
+        assert torch.equal(a, b)
+    with pytest.raises(lpq.LpqError) as e:
+        parts.add_f32(x[:100])
+    assert e.value.code == lpq.ERANGE
+
+
+def test_search_error_codes(lpq):
+    w = synth.TINY.scaled(n=500, nq=4)
+    x, q = w.corpus().cuda(), w.queries().cuda()
+    gq = lpq.Quantizer(w.d, 8)
+    with pytest.raises(lpq.LpqError) as e:
+        gq.encode(x)
+    assert e.value.code == lpq.ESTATE
+    gq.calibrate(x, "minmax", "per_feature")
+    idx = lpq.Index(gq, 500)
+    ids = torch.full((4, 10), -7, dtype=torch.int32, device="cuda")
+    dists = torch.full((4, 10), -7, dtype=torch.int32, device="cuda")
+    L = lpq.lib()
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    args = lambda k, wsb: (idx._h, q.data_ptr(), 4, 128, k, 0, ids.data_ptr(), dists.data_ptr(), ws.data_ptr(), wsb, None)
+    assert L.lpq_search(*args(10, ws.numel())) == lpq.ESTATE          # empty index
+    idx.add_f32(x)
+    assert L.lpq_search(*args(501, ws.numel())) == lpq.ERANGE         # k > n
+    assert L.lpq_search(*args(0, ws.numel())) == lpq.EINVAL
+    assert L.lpq_search(*args(10, 16)) == lpq.ERANGE                  # workspace too small
+    torch.cuda.synchronize()
+    assert int(ids.min()) == -7 and int(dists.max()) == -7            # outputs untouched on error
+    e_ids, e_d = idx.search(q[:0], 10, "l2sq")                        # nq = 0: no-op
+    assert e_ids.shape == (0, 10)
+
+
+# ------------------------------------------------------------------ fp32 exact search
+@pytest.mark.parametrize("name,n,nq,k,metric", [
+    ("tiny", 10000, 100, 10, "l2sq"), ("aniso", 7001, 64, 10, "ip"), ("scaled", 5000, 33, 100, "l2sq"),
+    ("skewed", 3000, 20, 10, "l2sq"),
+])
+def test_fp32_exact_search_within_tolerance(lpq, oracle, name, n, nq, k, metric):
+    base = {"skewed": synth.SKEWED_1M, "aniso": synth.ANISO_1M2, "scaled": synth.SCALED_10M, "tiny": synth.TINY}[name]
+    w = base.scaled(n=n, nq=nq)
+    x, q = w.corpus(), w.queries()
+    ids, dists = lpq.search_f32(x.cuda(), q.cuda(), k, metric)
+    oids, odists = oracle.search_f32(x.numpy(), q.numpy(), k, metric, threads=16)
+    ids, dists = ids.cpu().numpy(), dists.cpu().numpy()
+    # distances, rank by rank, within the stated relative tolerance; for the inner product
+    # "relative" is to |q||x| (= 1 for the unit-length vectors used here), since the sum cancels
+    scale = np.abs(odists) if metric == "l2sq" else np.maximum(np.abs(odists), 1.0)
+    assert np.all(np.abs(dists - odists) <= REL_TOL_F32 * scale)
+    # ids must agree wherever the neighbouring distances are separated by more than the tolerance
+    xs, qs = x.numpy().astype(np.float64), q.numpy().astype(np.float64)
+    for i in range(nq):
+        if metric == "l2sq":
+            mine = ((xs[ids[i]] - qs[i]) ** 2).sum(1)
+        else:
+            mine = xs[ids[i]] @ qs[i]
+        np.testing.assert_allclose(mine, odists[i], rtol=4 * REL_TOL_F32, atol=4 * REL_TOL_F32 * (metric == "ip"))
+        assert len(set(ids[i].tolist())) == k
+    agree = (ids == oids).mean()
+    assert agree > 0.98
+
+
+def test_recall_of_int8_against_fp32_on_gpu(lpq, oracle):
+    """Recall@10 of the int8 search against the fp32 exact search, both on the GPU,
+    equals the oracle's own recall figure for the same data (same definition)."""
+    w = synth.TINY.scaled(n=10000, nq=100)
+    x, q = w.corpus(), w.queries()
+    gq = lpq.Quantizer(w.d, 8).calibrate(x.cuda(), "minmax", "per_feature")
+    idx = lpq.Index(gq, w.n).add_f32(x.cuda())
+    ids, _ = idx.search(q.cuda(), 10, "l2sq")
+    eids, _ = lpq.search_f32(x.cuda(), q.cuda(), 10, "l2sq")
+    r_gpu = oracle.recall(ids.cpu().numpy(), eids.cpu().numpy())
+    oq = _oracle_quant(oracle, gq)
+    oids, _ = oracle.search_i8(oq.encode(x.numpy()), oq.encode(q.numpy()), 10, "l2sq", threads=16)
+    oeids, _ = oracle.search_f32(x.numpy(), q.numpy(), 10, "l2sq", threads=16)
+    assert abs(r_gpu - oracle.recall(oids, oeids)) < 0.005
+    assert r_gpu > 0.9
