@@ -151,8 +151,10 @@ int lpq_search_f32(const float *x_dev, int64_t n, int64_t ldx, const float *q_de
  *   LPQ_TUNE_SPLITS      number of corpus splits per query tile in the main pass
  *   LPQ_TUNE_SEED_ROWS   rows of the threshold-seeding pass (0 = built-in choice,
  *                        -1 = no seeding pass)
- * Results never depend on these. */
-enum { LPQ_TUNE_PATH = 0, LPQ_TUNE_SPLITS = 1, LPQ_TUNE_SEED_ROWS = 2, LPQ_TUNE_COUNT_ = 3 };
+ *   LPQ_TUNE_DRY_RUN     1 = the matrix-core kernel never collects a candidate (timing of
+ *                        the bare contraction only; the results are then meaningless)
+ * Results never depend on the first three. */
+enum { LPQ_TUNE_PATH = 0, LPQ_TUNE_SPLITS = 1, LPQ_TUNE_SEED_ROWS = 2, LPQ_TUNE_DRY_RUN = 3, LPQ_TUNE_COUNT_ = 4 };
 int lpq_set_tuning(int key, int64_t value);
 
 /* Kernel timing for benchmarks.  While enabled, every launch of the contraction/top-k

@@ -34,7 +34,7 @@ static int fail(int code, const char *fmt, ...)
 extern "C" const char *lpq_last_error(void) { return g_err; }
 
 // ------------------------------------------------------------------------ tuning ----
-static int64_t g_tune[LPQ_TUNE_COUNT_] = {0, 0, 0};
+static int64_t g_tune[LPQ_TUNE_COUNT_] = {0, 0, 0, 0};
 
 extern "C" int lpq_set_tuning(int key, int64_t value)
 {
@@ -403,6 +403,7 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k
     a.n = idx->size; a.d_pad = idx->d_pad;
     a.qcodes = reinterpret_cast<const int8_t *>(ws + p.off_qcodes);
     a.nq = nq; a.k = k; a.metric = metric;
+    a.dry_run = g_tune[LPQ_TUNE_DRY_RUN] != 0;
     const int32_t *qnorms = reinterpret_cast<const int32_t *>(ws + p.off_qnorms);
     cand_t *lists1 = reinterpret_cast<cand_t *>(ws + p.off_lists1);
     cand_t *seedlist = reinterpret_cast<cand_t *>(ws + p.off_seedlist);

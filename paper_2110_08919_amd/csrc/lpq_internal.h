@@ -99,6 +99,7 @@ struct SearchArgs {
     int64_t nq;
     int k;
     int metric;
+    bool dry_run;           // timing experiments: never collect a candidate
 };
 
 // Generic kernel: one workgroup per (query, corpus split); any d_pad (multiple of 32), any k.

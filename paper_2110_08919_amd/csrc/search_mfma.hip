@@ -3,11 +3,17 @@
 //
 // Work split.  A workgroup of 4 waves owns one query tile (4 x 32*NB queries) and one
 // corpus split.  Each wave keeps the codes of its 32*NB queries in registers for the whole
-// kernel (B operands); corpus rows stream through LDS in stages of 64 rows shared by the
-// four waves (A operands), double buffered.  The corpus is the M side on purpose: the 16
-// accumulators of a lane then belong to ONE query (column = lane % 32) and 16 different
-// items, so the common-case epilogue is a max tree over the 16 values (v_max3) and one
-// compare against that query's threshold: about 0.6 VALU operations per distance.
+// kernel (B operands); corpus rows stream through an LDS ring of NSTG stages shared by the
+// four waves (A operands).  The ring is filled by asynchronous global->LDS loads
+// (global_load_lds_dwordx4) issued NSTG-1 stages ahead, so three stages of corpus are in
+// flight per workgroup while one is being consumed; rows sit in LDS row-major with an XOR
+// swizzle of their 16-byte chunks, which keeps the global side fully coalesced and the
+// ds_read_b128 of the A operands free of bank conflicts.
+//
+// The corpus is the M side on purpose: the 16 accumulators of a lane then belong to ONE
+// query (column = lane % 32) and 16 different items, so the common-case epilogue is a max
+// tree over the 16 values (v_max3) and one compare against that query's threshold: about
+// 0.6 VALU operations per distance.
 //
 // Keys.  The accumulators start from cinit_j = -ceil(nx_j / 2) (0 for inner product), so
 // the matrix core itself delivers E = dot - ceil(nx_j/2).  The exact ranking key is
@@ -16,8 +22,8 @@
 //
 // Rare path.  A lane whose maximum passes dumps its 16 accumulators into a per-wave LDS
 // queue (no atomics: the queue, the thresholds and the per-query lists are private to the
-// wave).  When the queue is full the wave drains it densely - one (dump, accumulator) pair
-// per lane - rebuilds exact candidates, inserts them into per-query lists of the k best
+// wave).  When the queue is full the wave drains it - one dump per lane, accumulator by
+// accumulator - rebuilds exact candidates, inserts them into per-query lists of the k best
 // (claim loop: one winner per query per round) and tightens the thresholds.
 #include "lpq_internal.h"
 
@@ -30,18 +36,56 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int WAVES = 4;
 constexpr int THREADS = WAVES * 64;
-constexpr int RS = 64;     // corpus rows per LDS stage
+constexpr int NSTG = 4;    // LDS ring depth
 constexpr int QCAP = 64;   // dumps a wave can queue; one epilogue makes at most 64
 
-__device__ inline void wave_sync()
+__device__ __forceinline__ void wave_sync()
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Largest E that cannot beat the candidate threshold c is one below the returned value:
-// a candidate can only pass if E >= thr_e(c).
+// Asynchronous 16-byte-per-lane copy global -> LDS: lane l of the wave writes LDS bytes
+// [base + 16 l, base + 16 l + 16).  `base` must be wave-uniform.  The copy is tracked by the
+// vector-memory counter only; the caller orders it with wait_vmcnt() and a barrier.
+__device__ __forceinline__ void async_copy16(const void *gptr, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+}
+__device__ __forceinline__ void async_copy4(const void *gptr, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+}
+__device__ __forceinline__ unsigned lds_offset(const void *p)
+{
+    return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
+}
+
+// s_waitcnt vmcnt(n) with n a run-time value in 0..15 (other counters untouched).
+__device__ __forceinline__ void wait_vmcnt(int n)
+{
+    switch (n) {
+    case 0: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+    case 1: __builtin_amdgcn_s_waitcnt(0x0F71); break;
+    case 2: __builtin_amdgcn_s_waitcnt(0x0F72); break;
+    case 3: __builtin_amdgcn_s_waitcnt(0x0F73); break;
+    case 4: __builtin_amdgcn_s_waitcnt(0x0F74); break;
+    case 5: __builtin_amdgcn_s_waitcnt(0x0F75); break;
+    case 6: __builtin_amdgcn_s_waitcnt(0x0F76); break;
+    case 7: __builtin_amdgcn_s_waitcnt(0x0F77); break;
+    case 8: __builtin_amdgcn_s_waitcnt(0x0F78); break;
+    case 9: __builtin_amdgcn_s_waitcnt(0x0F79); break;
+    case 10: __builtin_amdgcn_s_waitcnt(0x0F7A); break;
+    case 11: __builtin_amdgcn_s_waitcnt(0x0F7B); break;
+    case 12: __builtin_amdgcn_s_waitcnt(0x0F7C); break;
+    case 13: __builtin_amdgcn_s_waitcnt(0x0F7D); break;
+    case 14: __builtin_amdgcn_s_waitcnt(0x0F7E); break;
+    default: __builtin_amdgcn_s_waitcnt(0x0F7F); break;
+    }
+}
+
+// A candidate can only beat the threshold candidate c if its E is >= thr_e(c).
 __device__ inline int thr_e(cand_t c)
 {
     if (c == CAND_NONE) return INT32_MIN;
@@ -51,7 +95,7 @@ __device__ inline int thr_e(cand_t c)
 }
 
 struct WaveState {   // pointers into the wave's private LDS region
-    int *qvals;      // [QCAP][16]
+    int *qvals;      // [16][QCAP]  accumulator r of dump s at qvals[r * QCAP + s]
     int *qrow;       // [QCAP] first row of the 32-row block the dump came from
     unsigned *qpar;  // [QCAP] parity word of that block
     int *qmeta;      // [QCAP] query slot | lane half << 8
@@ -76,7 +120,6 @@ __device__ inline WaveState carve_wave(unsigned char *p, int nqw)
     WaveState w;
     w.qvals = (int *)p;       p += QCAP * 16 * 4;
     w.thrC = (cand_t *)p;     p += nqw * 8;
-    w.lists = nullptr;
     w.qrow = (int *)p;        p += QCAP * 4;
     w.qpar = (unsigned *)p;   p += QCAP * 4;
     w.qmeta = (int *)p;       p += QCAP * 4;
@@ -84,8 +127,7 @@ __device__ inline WaveState carve_wave(unsigned char *p, int nqw)
     w.cnt = (int *)p;         p += nqw * 4;
     w.worst = (int *)p;       p += nqw * 4;
     w.claim = (int *)p;       p += nqw * 4;
-    p = (unsigned char *)(((uintptr_t)p + 7) & ~uintptr_t(7));
-    w.lists = (cand_t *)p;
+    w.lists = (cand_t *)p;    // 8-byte aligned: every size above is a multiple of 8
     return w;
 }
 
@@ -114,38 +156,52 @@ __device__ inline void list_insert(const WaveState &w, int k, int ql, cand_t c)
 
 // Empty the wave's dump queue into its per-query lists.  Wave-uniform control flow.
 template <bool L2>
-__device__ inline void drain_queue(const WaveState &w, int qcnt, int k, int64_t row_end, int lane)
+__device__ __noinline__ void drain_queue(unsigned char *wave_region, int nqw, int qcnt, int k, int64_t row_end, int lane)
 {
+    const WaveState w = carve_wave(wave_region, nqw);
     wave_sync();
-    const int total = qcnt * 16;
-    for (int base = 0; base < total; base += 64) {
-        const int idx = base + lane;
-        bool pend = false;
-        int ql = 0;
-        cand_t c = 0;
-        if (idx < total) {
-            const int dump = idx >> 4, r = idx & 15;
-            const int e = w.qvals[idx];
-            const int meta = w.qmeta[dump];
-            ql = meta & 255;
-            if (e >= w.thrE[ql]) {
-                const int off = 8 * (r >> 2) + 4 * (meta >> 8) + (r & 3);
-                const int64_t row = (int64_t)w.qrow[dump] + off;
-                const int b = L2 ? (int)((w.qpar[dump] >> off) & 1u) : 0;
-                c = make_cand(-(2 * e + b), (uint32_t)row);
-                pend = row < row_end && c < w.thrC[ql];
+    for (int dbase = 0; dbase < qcnt; dbase += 64) {
+        const int d = dbase + lane;
+        const bool live = d < qcnt;
+        const int meta = live ? w.qmeta[d] : 0;
+        const int ql = meta & 255, hf = meta >> 8;
+        const int rbase = live ? w.qrow[d] : 0;
+        const unsigned pw = (L2 && live) ? w.qpar[d] : 0u;
+        for (int r = 0; r < 16; ++r) {
+            bool pend = false;
+            cand_t c = 0;
+            if (live) {
+                const int e = w.qvals[r * QCAP + d];
+                if (e >= w.thrE[ql]) {
+                    const int off = 8 * (r >> 2) + 4 * hf + (r & 3);
+                    const int64_t row = (int64_t)rbase + off;
+                    const int b = (int)((pw >> off) & 1u);
+                    c = make_cand(-(2 * e + b), (uint32_t)row);
+                    pend = row < row_end && c < w.thrC[ql];
+                }
             }
-        }
-        while (__ballot(pend)) {  // one winner per query and round
-            if (pend) w.claim[ql] = lane;
-            wave_sync();
-            if (pend && w.claim[ql] == lane) {
-                if (c < w.thrC[ql]) list_insert(w, k, ql, c);
-                pend = false;
+            while (__ballot(pend)) {  // one winner per query and round
+                if (pend) w.claim[ql] = lane;
+                wave_sync();
+                if (pend && w.claim[ql] == lane) {
+                    if (c < w.thrC[ql]) list_insert(w, k, ql, c);
+                    pend = false;
+                }
+                wave_sync();
             }
-            wave_sync();
         }
     }
+}
+
+// Swizzle of the 16-byte chunk slots of LDS row i (SLOTS slots per row, a power of two):
+// chunk c of row i lives in slot c ^ swz(i).  Conflict-free for ds_read_b128 of one chunk
+// column by 32 consecutive rows, with 32 or 64 LDS banks.
+template <int SLOTS>
+__device__ __forceinline__ int swz(int i)
+{
+    if (SLOTS == 16) return i & 15;
+    constexpr int A = SLOTS == 8 ? 0 : (SLOTS == 4 ? 1 : 2);
+    return ((i >> A) ^ (i >> 3)) & (SLOTS - 1);
 }
 
 template <int KS, int NB, bool L2>
@@ -156,12 +212,16 @@ __global__ __launch_bounds__(THREADS, 2) void search_mfma_kernel(
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int NQW = 32 * NB;           // queries per wave
     constexpr int QT = WAVES * NQW;        // queries per workgroup
-    constexpr int STRIDE = 32 * KS + 16;   // LDS row stride: odd multiple of 16 bytes -> conflict-free b128 reads
-    constexpr int CPR = 2 * KS;            // 16-byte chunks per row
-    constexpr int CHUNKS = RS * CPR;
-    constexpr int CH = (CHUNKS + THREADS - 1) / THREADS;
+    constexpr int CPR = 2 * KS;            // 16-byte chunks per corpus row
+    constexpr int SLOTS = CPR <= 2 ? 2 : (CPR <= 4 ? 4 : (CPR <= 8 ? 8 : 16));  // LDS slots per row
+    constexpr int RS = KS <= 4 ? 64 : 32;  // corpus rows per stage
+    constexpr int STAGE_BYTES = RS * SLOTS * 16;
+    constexpr int IPW = RS * SLOTS / 64 / WAVES;   // async copy instructions per wave and stage
+    constexpr int AUX_INTS = RS + 4;       // cinit[RS] then parity words
+    static_assert(RS * SLOTS % (64 * WAVES) == 0 && IPW >= 1, "stage must split evenly over the waves");
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction
     const int col = lane & 31, half = lane >> 5;
     const int k = a.k;
 
@@ -176,16 +236,16 @@ __global__ __launch_bounds__(THREADS, 2) void search_mfma_kernel(
     const int64_t rs = row0 + (int64_t)s * split_rows;
     const int64_t re = (rs + split_rows < row1) ? rs + split_rows : row1;
 
-    unsigned char *stage = smem;
-    int *cin = (int *)(smem + 2 * RS * STRIDE);
-    unsigned *par = (unsigned *)(cin + 2 * RS);
-    unsigned char *wbase = (unsigned char *)(par + 8);
-    const WaveState w = carve_wave(wbase + (size_t)wave * wave_region_bytes(NQW, k), NQW);
+    unsigned char *ring = smem;
+    int *aux = (int *)(smem + NSTG * STAGE_BYTES);
+    unsigned char *wbase = (unsigned char *)(aux + NSTG * AUX_INTS);
+    unsigned char *wregion = wbase + (size_t)wave * wave_region_bytes(NQW, k);
+    const WaveState w = carve_wave(wregion, NQW);
 
     const int64_t q_first = (int64_t)qt * QT + wave * NQW;
     if (lane < NQW) {
         const int64_t gq = q_first + lane;
-        const cand_t sd = (gq < a.nq) ? (seeds ? seeds[gq] : CAND_NONE) : 0;
+        const cand_t sd = (gq < a.nq && !a.dry_run) ? (seeds ? seeds[gq] : CAND_NONE) : 0;
         w.thrC[lane] = sd;
         w.thrE[lane] = thr_e(sd);
         w.cnt[lane] = 0;
@@ -203,48 +263,56 @@ __global__ __launch_bounds__(THREADS, 2) void search_mfma_kernel(
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) thr[nb] = w.thrE[nb * 32 + col];
     int qcnt = 0;
+    int a_off[KS];   // byte offset of this lane's A chunk of k-step ks inside a 32-row block of a stage
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) a_off[ks] = col * (SLOTS * 16) + ((2 * ks + half) ^ swz<SLOTS>(col)) * 16;
 
-    // Stage prefetch registers (named scalars, so they are never demoted to scratch memory).
-    static_assert(CH >= 1 && CH <= 4, "stage loader handles up to 4 chunks per thread");
-    uint4 pre0 = {0, 0, 0, 0}, pre1 = {0, 0, 0, 0}, pre2 = {0, 0, 0, 0}, pre3 = {0, 0, 0, 0};
-    int pre_cin = 0;
-    unsigned pre_par = 0;
-#define LPQ_CHUNK_SRC(J) \
-    reinterpret_cast<const uint4 *>(a.codes + (r0_ + ((tid + THREADS * (J)) % CHUNKS) / CPR) * a.d_pad + ((tid + THREADS * (J)) % CPR) * 16)
-#define LPQ_CHUNK_DST(J) \
-    reinterpret_cast<uint4 *>(stage + (size_t)buf_ * RS * STRIDE + ((tid + THREADS * (J)) / CPR) * STRIDE + ((tid + THREADS * (J)) % CPR) * 16)
-#define LPQ_GLOAD(R0)                                                                         \
-    do {                                                                                      \
-        const int64_t r0_ = (R0);                                                             \
-        if (CH > 0) pre0 = *LPQ_CHUNK_SRC(0);                                                 \
-        if (CH > 1) pre1 = *LPQ_CHUNK_SRC(1);                                                 \
-        if (CH > 2) pre2 = *LPQ_CHUNK_SRC(2);                                                 \
-        if (CH > 3) pre3 = *LPQ_CHUNK_SRC(3);                                                 \
-        if (L2 && tid < RS) pre_cin = a.cinit[r0_ + tid];                                     \
-        if (L2 && tid >= 64 && tid < 64 + RS / 32) pre_par = a.parity[r0_ / 32 + (tid - 64)]; \
-    } while (0)
-#define LPQ_SSTORE(BUF)                                                                       \
-    do {                                                                                      \
-        const int buf_ = (BUF);                                                               \
-        if (CH > 0 && tid + THREADS * 0 < CHUNKS) *LPQ_CHUNK_DST(0) = pre0;                   \
-        if (CH > 1 && tid + THREADS * 1 < CHUNKS) *LPQ_CHUNK_DST(1) = pre1;                   \
-        if (CH > 2 && tid + THREADS * 2 < CHUNKS) *LPQ_CHUNK_DST(2) = pre2;                   \
-        if (CH > 3 && tid + THREADS * 3 < CHUNKS) *LPQ_CHUNK_DST(3) = pre3;                   \
-        if (L2 && tid < RS) cin[buf_ * RS + tid] = pre_cin;                                   \
-        if (L2 && tid >= 64 && tid < 64 + RS / 32) par[buf_ * 4 + (tid - 64)] = pre_par;      \
+    // ---- stage loader -----------------------------------------------------------------
+    // Position p of a stage = LDS bytes [16p, 16p+16) = (row p / SLOTS, slot p % SLOTS).  Wave
+    // `wave` copies positions [(wave*IPW + j)*64, +64) with instruction j; the lane's source
+    // is the chunk that belongs in its slot, so every instruction reads whole rows.
+    const unsigned ring_lds = lds_offset(ring), aux_lds = lds_offset(aux);
+    const int lpt = IPW + ((L2 && wave < 2) ? 1 : 0);   // copies this wave issues per stage
+    int src_off[IPW];   // byte offset of the lane's source chunk inside a stage of corpus rows
+#pragma unroll
+    for (int j = 0; j < IPW; ++j) {
+        const int p = (wave * IPW + j) * 64 + lane;
+        const int r = p / SLOTS, sl = p % SLOTS;
+        int c = sl ^ swz<SLOTS>(r & 31);
+        c = c < CPR ? c : CPR - 1;          // padding slots of non-power-of-two rows: any valid chunk
+        src_off[j] = r * (32 * KS) + c * 16;
+    }
+#define LPQ_ISSUE(ST)                                                                                   \
+    do {                                                                                                \
+        const int st_ = (ST);                                                                           \
+        const int64_t r0_ = rs + (int64_t)st_ * RS;                                                     \
+        const int ring_slot_ = st_ % NSTG;                                                              \
+        const int8_t *src_ = a.codes + r0_ * (32 * KS);                                                 \
+        _Pragma("unroll") for (int j = 0; j < IPW; ++j)                                                 \
+            async_copy16(src_ + src_off[j], ring_lds + ring_slot_ * STAGE_BYTES + (wave * IPW + j) * 1024); \
+        if (L2 && wave == 0) {                                                                          \
+            if (lane < RS) async_copy4(a.cinit + r0_ + lane, aux_lds + ring_slot_ * AUX_INTS * 4);      \
+        } else if (L2 && wave == 1) {                                                                   \
+            if (lane < RS / 32)                                                                         \
+                async_copy4(a.parity + r0_ / 32 + lane, aux_lds + (ring_slot_ * AUX_INTS + RS) * 4);    \
+        }                                                                                               \
     } while (0)
 
     const int T = (re > rs) ? (int)((re - rs + RS - 1) / RS) : 0;
-    if (T > 0) { LPQ_GLOAD(rs); LPQ_SSTORE(0); }
-    // All loads so far (query fragments included) have landed: inside the loop only the stage
-    // prefetch is ever outstanding, so the matrix instructions never wait on the memory counter.
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-    __syncthreads();
+    // Query fragments have landed before any copy is issued, so inside the loop only async
+    // copies are ever outstanding on the vector-memory counter.
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    for (int st = 0; st < NSTG - 1 && st < T; ++st) LPQ_ISSUE(st);
 
     for (int t = 0; t < T; ++t) {
-        if (t + 1 < T) LPQ_GLOAD(rs + (int64_t)(t + 1) * RS);
-        const unsigned char *sb = stage + (size_t)(t & 1) * RS * STRIDE;
-        const int *cb = cin + (t & 1) * RS;
+        // stages issued so far: 0 .. min(T-1, t+NSTG-2); wait until stage t has landed
+        const int newer = (T - 1 < t + NSTG - 2 ? T - 1 : t + NSTG - 2) - t;
+        wait_vmcnt(newer * lpt);
+        __syncthreads();   // everybody's part of stage t is in LDS; stage t-1 is no longer read
+        if (t + NSTG - 1 < T) LPQ_ISSUE(t + NSTG - 1);   // refills the slot of stage t-1
+
+        const unsigned char *sb = ring + (size_t)(t % NSTG) * STAGE_BYTES;
+        const int *cb = aux + (t % NSTG) * AUX_INTS;
 #pragma unroll
         for (int blk = 0; blk < RS / 32; ++blk) {
             v16i c0;
@@ -261,7 +329,7 @@ __global__ __launch_bounds__(THREADS, 2) void search_mfma_kernel(
             v4i A[KS];
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
-                A[ks] = *reinterpret_cast<const v4i *>(sb + (blk * 32 + col) * STRIDE + ks * 32 + half * 16);
+                A[ks] = *reinterpret_cast<const v4i *>(sb + blk * 32 * (SLOTS * 16) + a_off[ks]);
             v16i acc[NB];
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
@@ -285,7 +353,8 @@ __global__ __launch_bounds__(THREADS, 2) void search_mfma_kernel(
                 unsigned long long mask = __ballot(trip);
                 if (mask) {
                     if (qcnt + __popcll(mask) > QCAP) {
-                        drain_queue<L2>(w, qcnt, k, re, lane);
+                        drain_queue<L2>(wregion, NQW, qcnt, k, re, lane);
+                        wave_sync();
                         qcnt = 0;
 #pragma unroll
                         for (int j = 0; j < NB; ++j) thr[j] = w.thrE[j * 32 + col];
@@ -297,13 +366,10 @@ __global__ __launch_bounds__(THREADS, 2) void search_mfma_kernel(
                                                                     __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
                         if (trip) {
                             const int slot = qcnt + below;
-                            v4i *dst = reinterpret_cast<v4i *>(w.qvals + slot * 16);
-                            dst[0] = v4i{v[0], v[1], v[2], v[3]};
-                            dst[1] = v4i{v[4], v[5], v[6], v[7]};
-                            dst[2] = v4i{v[8], v[9], v[10], v[11]};
-                            dst[3] = v4i{v[12], v[13], v[14], v[15]};
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) w.qvals[r * QCAP + slot] = v[r];
                             w.qrow[slot] = rowbase;
-                            w.qpar[slot] = L2 ? par[(t & 1) * 4 + blk] : 0u;
+                            w.qpar[slot] = L2 ? (unsigned)cb[RS + blk] : 0u;
                             w.qmeta[slot] = (nb * 32 + col) | (half << 8);
                         }
                         qcnt += __popcll(mask);
@@ -311,16 +377,10 @@ __global__ __launch_bounds__(THREADS, 2) void search_mfma_kernel(
                 }
             }
         }
-        if (t + 1 < T) LPQ_SSTORE((t + 1) & 1);
-        __syncthreads();
     }
+#undef LPQ_ISSUE
 
-#undef LPQ_GLOAD
-#undef LPQ_SSTORE
-#undef LPQ_CHUNK_SRC
-#undef LPQ_CHUNK_DST
-
-    drain_queue<L2>(w, qcnt, k, re, lane);
+    drain_queue<L2>(wregion, NQW, qcnt, k, re, lane);
     wave_sync();
     if (lane < NQW) {
         const int64_t gq = q_first + lane;
@@ -335,8 +395,10 @@ __global__ __launch_bounds__(THREADS, 2) void search_mfma_kernel(
 
 size_t lds_bytes(int ks, int nb, int k)
 {
-    const size_t stride = 32 * ks + 16;
-    return 2 * RS * stride + 2 * RS * 4 + 32 + WAVES * wave_region_bytes(32 * nb, k);
+    const int cpr = 2 * ks;
+    const int slots = cpr <= 2 ? 2 : (cpr <= 4 ? 4 : (cpr <= 8 ? 8 : 16));
+    const int rs = ks <= 4 ? 64 : 32;
+    return (size_t)NSTG * rs * slots * 16 + (size_t)NSTG * (rs + 4) * 4 + WAVES * wave_region_bytes(32 * nb, k);
 }
 
 int nb_for(int k) { return k <= 16 ? 2 : 1; }
@@ -347,7 +409,7 @@ hipError_t launch_one(const SearchArgs &a, int64_t row0, int64_t row1, int S, co
 {
     const int qt = 128 * NB;
     const int qtiles = (int)ceil_div(a.nq, qt);
-    const int64_t split_rows = round_up(ceil_div(row1 - row0, S), RS);
+    const int64_t split_rows = round_up(ceil_div(row1 - row0, S), 64);
     const size_t lds = lds_bytes(KS, NB, a.k);
     auto kern = search_mfma_kernel<KS, NB, L2>;
     static bool attr_set = false;  // per instantiation
@@ -378,7 +440,7 @@ hipError_t launch_ks(const SearchArgs &a, int64_t row0, int64_t row1, int S, con
 bool mfma_supported(int d_pad, int k)
 {
     const int ks = d_pad / 32;
-    if (d_pad % 32 || !(ks == 1 || ks == 2 || ks == 3 || ks == 4 || ks == 6 || ks == 8)) return false;
+    if (d_pad % 32 || !(ks == 2 || ks == 3 || ks == 4 || ks == 6 || ks == 8)) return false;
     return k >= 1 && lds_bytes(ks, nb_for(k), k) <= 160 * 1024;
 }
 
@@ -388,9 +450,8 @@ hipError_t launch_search_mfma(const SearchArgs &a, int64_t row0, int64_t row1, i
                               cand_t *lists, void *, hipStream_t st)
 {
     if (a.nq <= 0 || row1 <= row0) return hipSuccess;
-    if (row0 % 32) return hipErrorInvalidValue;  // parity words cover aligned 32-item blocks
+    if (row0 % 64) return hipErrorInvalidValue;  // stages and parity words cover aligned blocks
     switch (a.d_pad / 32) {
-    case 1: return launch_ks<1>(a, row0, row1, S, seeds, lists, st);
     case 2: return launch_ks<2>(a, row0, row1, S, seeds, lists, st);
     case 3: return launch_ks<3>(a, row0, row1, S, seeds, lists, st);
     case 4: return launch_ks<4>(a, row0, row1, S, seeds, lists, st);
