@@ -316,13 +316,15 @@ extern "C" int lpq_index_data(const lpq_index *idx, const int8_t **codes_dev, in
 namespace {
 
 // How a search over n items is cut up, and where its intermediates live in the workspace.
+enum PlanMode { PLAN_GENERIC = 0, PLAN_MFMA_LDS = 1, PLAN_MFMA_REG = 2 };
 struct Plan {
-    bool mfma = false;
+    int mode = PLAN_GENERIC;
     int64_t nq_pad = 0;
     int64_t seed_rows = 0;  // rows of the threshold-seeding pass (0 = none)
     int S1 = 0, S2 = 0;     // corpus splits of the seeding pass and of the main pass
+    int SEG = 0;            // PLAN_MFMA_REG: segments per split in the seeding pass
     size_t off_qcodes = 0, off_qnorms = 0, off_lists1 = 0, off_seedlist = 0, off_seeds = 0, off_lists2 = 0,
-           off_scratch = 0, total = 0;
+           off_gmax = 0, total = 0;
 };
 
 size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
@@ -331,49 +333,56 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
 {
     Plan p;
     const int64_t n = idx->size;
-    p.mfma = mfma_supported(idx->d_pad, k) && g_tune[LPQ_TUNE_PATH] != 1;
-    if (g_tune[LPQ_TUNE_PATH] == 2 && !mfma_supported(idx->d_pad, k)) p.mfma = false;
-    p.nq_pad = round_up(nq, 256);
+    const int64_t want = g_tune[LPQ_TUNE_PATH];
+    if (want != 1 && mfma_reg_supported(idx->d_pad, k)) p.mode = PLAN_MFMA_REG;
+    else if (want != 1 && mfma_lds_supported(idx->d_pad, k)) p.mode = PLAN_MFMA_LDS;
+    p.nq_pad = round_up(nq > 0 ? nq : 1, 256);
     const int max_lists = merge_max_lists(k);
+    const int64_t slots = 512;   // workgroups of the matrix-core kernels resident at once (2 per CU)
 
-    // Seeding pass: a first slice of the corpus is searched alone; its k-th best candidate
-    // per query is an upper bound on the final k-th best and lets the main pass reject
-    // almost everything from its first tile on.
+    // Seeding pass over a first slice of the corpus: it yields, per query, an upper bound on
+    // the final k-th best key, so the main pass rejects almost everything from its first
+    // tile on.  PLAN_MFMA_REG derives the bound from group maxima (no candidates collected)
+    // and then scans ALL rows; PLAN_MFMA_LDS searches the slice exactly and scans the rest.
     int64_t seed = 0;
     if (g_tune[LPQ_TUNE_SEED_ROWS] > 0) seed = g_tune[LPQ_TUNE_SEED_ROWS];
-    else if (g_tune[LPQ_TUNE_SEED_ROWS] == 0 && p.mfma) seed = n / 64 < 4096 ? 4096 : (n / 64 > 32768 ? 32768 : n / 64);
-    seed = round_up(seed, 256);
-    if (seed < k || seed * 4 > n) seed = 0;
+    else if (g_tune[LPQ_TUNE_SEED_ROWS] == 0 && p.mode != PLAN_GENERIC) {
+        seed = p.mode == PLAN_MFMA_REG ? n / 16 : n / 64;
+        const int64_t lo = p.mode == PLAN_MFMA_REG ? 8192 : 4096, hi = p.mode == PLAN_MFMA_REG ? 65536 : 32768;
+        seed = seed < lo ? lo : (seed > hi ? hi : seed);
+    }
+    seed = seed / 256 * 256;
+    if (seed < 64 * k || seed * 4 > n) seed = 0;
     p.seed_rows = seed;
 
-    auto splits_for = [&](int64_t rows, int64_t tiles_q) {
+    auto splits_for = [&](int64_t rows, int64_t tiles_q, int64_t min_rows) {
         int64_t s;
-        if (p.mfma) {
-            s = g_tune[LPQ_TUNE_SPLITS] > 0 ? g_tune[LPQ_TUNE_SPLITS] : ceil_div(512, tiles_q > 0 ? tiles_q : 1);
-            const int64_t max_by_rows = rows / 1024 > 0 ? rows / 1024 : 1;
-            if (s > max_by_rows) s = max_by_rows;
-        } else {
-            s = g_tune[LPQ_TUNE_SPLITS] > 0 ? g_tune[LPQ_TUNE_SPLITS] : ceil_div(2048, nq > 0 ? nq : 1);
-            const int64_t max_by_rows = rows / 2048 > 0 ? rows / 2048 : 1;
-            if (s > max_by_rows) s = max_by_rows;
-        }
+        if (p.mode != PLAN_GENERIC) s = g_tune[LPQ_TUNE_SPLITS] > 0 ? g_tune[LPQ_TUNE_SPLITS] : slots / (tiles_q > 0 ? tiles_q : 1);
+        else s = g_tune[LPQ_TUNE_SPLITS] > 0 ? g_tune[LPQ_TUNE_SPLITS] : ceil_div(2048, nq > 0 ? nq : 1);
+        const int64_t by_rows = rows / min_rows > 0 ? rows / min_rows : 1;
+        if (s > by_rows) s = by_rows;
         if (s > max_lists) s = max_lists;
         if (s < 1) s = 1;
         return (int)s;
     };
-    const int64_t tiles_q = p.nq_pad / 256;
-    if (seed) p.S1 = splits_for(seed, tiles_q);
-    p.S2 = splits_for(n - seed, tiles_q);
+    const int64_t qt = (p.mode == PLAN_MFMA_LDS && k > 16) ? 128 : 256;   // queries per workgroup
+    const int64_t tiles_q = ceil_div(nq > 0 ? nq : 1, qt);
+    const int64_t min_rows = p.mode == PLAN_GENERIC ? 2048 : 512;
+    if (seed) {
+        p.S1 = splits_for(seed, tiles_q, min_rows);
+        if (p.mode == PLAN_MFMA_REG) p.SEG = mfma_seed_segments(p.S1, k);
+    }
+    p.S2 = splits_for(p.mode == PLAN_MFMA_REG ? n : n - seed, tiles_q, min_rows);
 
     size_t o = 0;
     p.off_qcodes = o;   o = align256(o + (size_t)p.nq_pad * idx->d_pad);
     p.off_qnorms = o;   o = align256(o + (size_t)p.nq_pad * sizeof(int32_t));
-    p.off_lists1 = o;   o = align256(o + (size_t)nq * p.S1 * k * sizeof(cand_t));
+    p.off_lists1 = o;   o = align256(o + (p.mode == PLAN_MFMA_REG ? 0 : (size_t)nq * p.S1 * k * sizeof(cand_t)));
     p.off_seedlist = o; o = align256(o + (size_t)nq * k * sizeof(cand_t));
     p.off_seeds = o;    o = align256(o + (size_t)p.nq_pad * sizeof(cand_t));
     p.off_lists2 = o;   o = align256(o + (size_t)nq * p.S2 * k * sizeof(cand_t));
-    p.off_scratch = o;
-    if (p.mfma) o = align256(o + mfma_list_scratch_bytes(p.nq_pad, p.S1 > p.S2 ? p.S1 : p.S2, k));
+    p.off_gmax = o;
+    if (p.mode == PLAN_MFMA_REG && seed) o = align256(o + (size_t)p.nq_pad * 2 * p.S1 * p.SEG * sizeof(int32_t));
     p.total = o;
     return p;
 }
@@ -409,14 +418,26 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k
     cand_t *seedlist = reinterpret_cast<cand_t *>(ws + p.off_seedlist);
     cand_t *seeds = reinterpret_cast<cand_t *>(ws + p.off_seeds);
     cand_t *lists2 = reinterpret_cast<cand_t *>(ws + p.off_lists2);
-    void *scratch = ws + p.off_scratch;
+    int32_t *gmax = reinterpret_cast<int32_t *>(ws + p.off_gmax);
 
     auto scan = [&](int64_t r0, int64_t r1, int S, const cand_t *sd, cand_t *out) -> hipError_t {
         KernelSpan span(st);
-        return p.mfma ? launch_search_mfma(a, r0, r1, S, sd, out, scratch, st)
-                      : launch_search_generic(a, r0, r1, S, sd, out, st);
+        return p.mode == PLAN_GENERIC ? launch_search_generic(a, r0, r1, S, sd, out, st)
+                                      : launch_search_mfma(a, r0, r1, S, sd, out, st);
     };
-    if (p.seed_rows) {
+    if (p.mode == PLAN_MFMA_REG) {
+        const cand_t *sd = nullptr;
+        if (p.seed_rows) {
+            {
+                KernelSpan span(st);
+                HIP_TRY(launch_seed_mfma(a, 0, p.seed_rows, p.S1, p.SEG, gmax, st));
+            }
+            HIP_TRY(launch_seed_finalize(gmax, nq, 2 * p.S1 * p.SEG, k, seeds, st));
+            sd = seeds;
+        }
+        HIP_TRY(scan(0, a.n, p.S2, sd, lists2));
+        HIP_TRY(launch_merge(lists2, nq, p.S2, k, nullptr, nullptr, nullptr, ids, dist, qnorms, metric, st));
+    } else if (p.seed_rows) {
         HIP_TRY(scan(0, p.seed_rows, p.S1, nullptr, lists1));
         HIP_TRY(launch_merge(lists1, nq, p.S1, k, nullptr, seedlist, seeds, nullptr, nullptr, nullptr, metric, st));
         HIP_TRY(scan(p.seed_rows, a.n, p.S2, seeds, lists2));

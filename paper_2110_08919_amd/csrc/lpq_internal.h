@@ -107,11 +107,22 @@ struct SearchArgs {
 hipError_t launch_search_generic(const SearchArgs &a, int64_t row0, int64_t row1, int S,
                                  const cand_t *seeds, cand_t *lists, hipStream_t st);
 
-// Matrix-core kernel (search_mfma.hip).  Supported shapes are reported by mfma_supported().
+// Matrix-core kernels.  search_mfma.hip keeps the k best of a query in registers (k <= 16) and
+// has a seeding pass; search_mfma_lds.hip keeps them in LDS (larger k).  launch_search_mfma
+// picks the variant; row0 must be a multiple of 64.
 bool mfma_supported(int d_pad, int k);
-size_t mfma_list_scratch_bytes(int64_t nq, int S, int k);
-hipError_t launch_search_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S,
-                              const cand_t *seeds, cand_t *lists, void *list_scratch, hipStream_t st);
+bool mfma_reg_supported(int d_pad, int k);
+bool mfma_lds_supported(int d_pad, int k);
+hipError_t launch_search_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds,
+                              cand_t *lists, hipStream_t st);
+hipError_t launch_search_mfma_lds(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds,
+                                  cand_t *lists, hipStream_t st);
+// Seeding pass of the register variant: group maxima gmax[nq_pad][2*S*SEG] over rows
+// [row0, row1) (all of them real items), then seeds[q] = bound from the k-th largest.
+int mfma_seed_segments(int S, int k);
+hipError_t launch_seed_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S, int SEG, int32_t *gmax,
+                            hipStream_t st);
+hipError_t launch_seed_finalize(const int32_t *gmax, int64_t nq, int G, int k, cand_t *seeds, hipStream_t st);
 
 // Merge P lists of k candidates per query into one (merge.hip).  If ids/dists are given the
 // result is final: ids, and dist = key + qnorm (L2SQ) or -key/2 (IP).  Otherwise the merged

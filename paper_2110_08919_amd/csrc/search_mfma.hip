@@ -1,12 +1,11 @@
 // Matrix-core search kernel for gfx950: int8 query x corpus^T contraction on
 // v_mfma_i32_32x32x32_i8 with the distance epilogue and the per-query top-k fused in.
 //
-// Work split.  A workgroup of 4 waves owns one query tile (4 x 32*NB queries) and one
-// corpus split.  Each wave keeps the codes of its 32*NB queries in registers for the whole
+// Work split.  A workgroup of 4 waves owns one query tile (256 queries, 64 per wave) and one
+// corpus split.  Each wave keeps the codes of its 64 queries in registers for the whole
 // kernel (B operands); corpus rows stream through an LDS ring of NSTG stages shared by the
 // four waves (A operands).  The ring is filled by asynchronous global->LDS loads
-// (global_load_lds_dwordx4) issued NSTG-1 stages ahead, so three stages of corpus are in
-// flight per workgroup while one is being consumed; rows sit in LDS row-major with an XOR
+// (global_load_lds_dwordx4) issued NSTG-1 stages ahead; rows sit in LDS row-major with an XOR
 // swizzle of their 16-byte chunks, which keeps the global side fully coalesced and the
 // ds_read_b128 of the A operands free of bank conflicts.
 //
@@ -21,197 +20,164 @@
 // conservative threshold and the rare path restores b from one parity word per 32 items.
 //
 // Rare path.  A lane whose maximum passes dumps its 16 accumulators into a per-wave LDS
-// queue (no atomics: the queue, the thresholds and the per-query lists are private to the
-// wave).  When the queue is full the wave drains it - one dump per lane, accumulator by
-// accumulator - rebuilds exact candidates, inserts them into per-query lists of the k best
-// (claim loop: one winner per query per round) and tightens the thresholds.
-#include "lpq_internal.h"
+// queue (no atomics: the queue and the thresholds are private to the wave).  Queues are
+// drained by all four waves together at a stage boundary as soon as one of them is half
+// full (a wave that overflows in between drains alone).  A drain scans the dumps densely,
+// compacts the exact candidates that still beat their query's threshold, and hands them to
+// the lane that owns the query (lane q of the wave owns query q): the owner keeps the k best
+// in registers as a sorted list and inserts with one compare-exchange pass.
+//
+// Seeding pass (SEED = true).  The same pipeline with collection switched off: every lane
+// only tracks the maximum E it has seen per segment of its split.  Each (segment, lane half)
+// is a group of items disjoint from the others, so the k-th largest group maximum of a query
+// is a value that at least k items reach: an upper bound on the k-th best key that costs
+// nothing but the contraction itself.  The main pass starts from it.
+#include "mfma_common.h"
 
 namespace lpq {
 
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
+constexpr int NQW = 64;      // queries per wave = lanes per wave: lane q owns query q
+constexpr int QT = WAVES * NQW;
+constexpr int TRIG = 32;     // queue fill that asks for a joint drain at the next stage boundary
+constexpr int SVCAP = 128;   // compacted candidates buffered before they are handed to owners
 
-constexpr int WAVES = 4;
-constexpr int THREADS = WAVES * 64;
-constexpr int NSTG = 4;    // LDS ring depth
-constexpr int QCAP = 64;   // dumps a wave can queue; one epilogue makes at most 64
-
-__device__ __forceinline__ void wave_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// Asynchronous 16-byte-per-lane copy global -> LDS: lane l of the wave writes LDS bytes
-// [base + 16 l, base + 16 l + 16).  `base` must be wave-uniform.  The copy is tracked by the
-// vector-memory counter only; the caller orders it with wait_vmcnt() and a barrier.
-__device__ __forceinline__ void async_copy16(const void *gptr, unsigned lds_base)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
-}
-__device__ __forceinline__ void async_copy4(const void *gptr, unsigned lds_base)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
-}
-__device__ __forceinline__ unsigned lds_offset(const void *p)
-{
-    return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
-}
-
-// s_waitcnt vmcnt(n) with n a run-time value in 0..15 (other counters untouched).
-__device__ __forceinline__ void wait_vmcnt(int n)
-{
-    switch (n) {
-    case 0: __builtin_amdgcn_s_waitcnt(0x0F70); break;
-    case 1: __builtin_amdgcn_s_waitcnt(0x0F71); break;
-    case 2: __builtin_amdgcn_s_waitcnt(0x0F72); break;
-    case 3: __builtin_amdgcn_s_waitcnt(0x0F73); break;
-    case 4: __builtin_amdgcn_s_waitcnt(0x0F74); break;
-    case 5: __builtin_amdgcn_s_waitcnt(0x0F75); break;
-    case 6: __builtin_amdgcn_s_waitcnt(0x0F76); break;
-    case 7: __builtin_amdgcn_s_waitcnt(0x0F77); break;
-    case 8: __builtin_amdgcn_s_waitcnt(0x0F78); break;
-    case 9: __builtin_amdgcn_s_waitcnt(0x0F79); break;
-    case 10: __builtin_amdgcn_s_waitcnt(0x0F7A); break;
-    case 11: __builtin_amdgcn_s_waitcnt(0x0F7B); break;
-    case 12: __builtin_amdgcn_s_waitcnt(0x0F7C); break;
-    case 13: __builtin_amdgcn_s_waitcnt(0x0F7D); break;
-    case 14: __builtin_amdgcn_s_waitcnt(0x0F7E); break;
-    default: __builtin_amdgcn_s_waitcnt(0x0F7F); break;
-    }
-}
-
-// A candidate can only beat the threshold candidate c if its E is >= thr_e(c).
-__device__ inline int thr_e(cand_t c)
-{
-    if (c == CAND_NONE) return INT32_MIN;
-    if (c == 0) return INT32_MAX;  // a query slot that must never collect anything
-    const long long t = (-(long long)cand_key(c)) >> 1;
-    return t > INT32_MAX ? INT32_MAX : (t < INT32_MIN ? INT32_MIN : (int)t);
-}
-
-struct WaveState {   // pointers into the wave's private LDS region
-    int *qvals;      // [16][QCAP]  accumulator r of dump s at qvals[r * QCAP + s]
-    int *qrow;       // [QCAP] first row of the 32-row block the dump came from
-    unsigned *qpar;  // [QCAP] parity word of that block
-    int *qmeta;      // [QCAP] query slot | lane half << 8
-    int *thrE;       // [NQW]
-    cand_t *thrC;    // [NQW]
-    int *cnt;        // [NQW]
-    int *worst;      // [NQW]
-    int *claim;      // [NQW]
-    cand_t *lists;   // [NQW][k]
+struct WaveQ {      // pointers into the wave's private LDS region
+    cand_t *thrC;   // [NQW] exact threshold candidate per query
+    cand_t *svc;    // [SVCAP] compacted candidates
+    int *qvals;     // [16][QCAP] accumulator r of dump s at qvals[r * QCAP + s]
+    int *qrow;      // [QCAP] first row of the 32-row block the dump came from
+    unsigned *qpar; // [QCAP] parity word of that block
+    int *qmeta;     // [QCAP] query slot | lane half << 8
+    int *thrE;      // [NQW] conservative threshold on E
+    int *mbox;      // [NQW] lane whose candidate the owner takes this round, or -1
+    int *svq;       // [SVCAP] query slot of each compacted candidate
 };
 
-__host__ __device__ inline size_t wave_region_bytes(int nqw, int k)
-{
-    size_t b = (size_t)QCAP * 16 * 4 + (size_t)QCAP * 12;
-    b += (size_t)nqw * (4 + 8 + 4 + 4 + 4);
-    b += (size_t)nqw * k * 8;
-    return (b + 15) & ~size_t(15);
-}
+constexpr size_t WAVEQ_BYTES = NQW * 8 + SVCAP * 8 + QCAP * 16 * 4 + QCAP * 12 + NQW * 8 + SVCAP * 4;
 
-__device__ inline WaveState carve_wave(unsigned char *p, int nqw)
+__device__ __forceinline__ WaveQ carve_waveq(unsigned char *p)
 {
-    WaveState w;
-    w.qvals = (int *)p;       p += QCAP * 16 * 4;
-    w.thrC = (cand_t *)p;     p += nqw * 8;
-    w.qrow = (int *)p;        p += QCAP * 4;
-    w.qpar = (unsigned *)p;   p += QCAP * 4;
-    w.qmeta = (int *)p;       p += QCAP * 4;
-    w.thrE = (int *)p;        p += nqw * 4;
-    w.cnt = (int *)p;         p += nqw * 4;
-    w.worst = (int *)p;       p += nqw * 4;
-    w.claim = (int *)p;       p += nqw * 4;
-    w.lists = (cand_t *)p;    // 8-byte aligned: every size above is a multiple of 8
+    WaveQ w;
+    w.thrC = (cand_t *)p;    p += NQW * 8;
+    w.svc = (cand_t *)p;     p += SVCAP * 8;
+    w.qvals = (int *)p;      p += QCAP * 16 * 4;
+    w.qrow = (int *)p;       p += QCAP * 4;
+    w.qpar = (unsigned *)p;  p += QCAP * 4;
+    w.qmeta = (int *)p;      p += QCAP * 4;
+    w.thrE = (int *)p;       p += NQW * 4;
+    w.mbox = (int *)p;       p += NQW * 4;
+    w.svq = (int *)p;
     return w;
 }
 
-// Put candidate c into the k-best list of query slot ql (called by one lane per query).
-__device__ inline void list_insert(const WaveState &w, int k, int ql, cand_t c)
+__device__ __forceinline__ cand_t shfl_cand(cand_t c, int src_lane)
 {
-    cand_t *list = w.lists + (size_t)ql * k;
-    int n = w.cnt[ql];
-    if (n < k) {
-        list[n] = c;
-        w.cnt[ql] = ++n;
-        if (n < k) return;
-    } else {
-        list[w.worst[ql]] = c;
-    }
-    cand_t mx = 0;
-    int mp = 0;
-    for (int i = 0; i < k; ++i) {
-        const cand_t v = list[i];
-        if (v > mx) { mx = v; mp = i; }
-    }
-    w.worst[ql] = mp;
-    w.thrC[ql] = mx;
-    w.thrE[ql] = thr_e(mx);
+    const unsigned lo = (unsigned)__shfl((int)(unsigned)c, src_lane, 64);
+    const unsigned hi = (unsigned)__shfl((int)(unsigned)(c >> 32), src_lane, 64);
+    return ((cand_t)hi << 32) | lo;
 }
 
-// Empty the wave's dump queue into its per-query lists.  Wave-uniform control flow.
-template <bool L2>
-__device__ __noinline__ void drain_queue(unsigned char *wave_region, int nqw, int qcnt, int k, int64_t row_end, int lane)
+// Sorted (ascending) list of the KCAP best candidates of one query, in registers.
+template <int KCAP>
+__device__ __forceinline__ void reglist_insert(cand_t (&lst)[KCAP], cand_t c, bool doit)
 {
-    const WaveState w = carve_wave(wave_region, nqw);
-    wave_sync();
-    for (int dbase = 0; dbase < qcnt; dbase += 64) {
-        const int d = dbase + lane;
-        const bool live = d < qcnt;
-        const int meta = live ? w.qmeta[d] : 0;
-        const int ql = meta & 255, hf = meta >> 8;
-        const int rbase = live ? w.qrow[d] : 0;
-        const unsigned pw = (L2 && live) ? w.qpar[d] : 0u;
-        for (int r = 0; r < 16; ++r) {
-            bool pend = false;
-            cand_t c = 0;
-            if (live) {
-                const int e = w.qvals[r * QCAP + d];
-                if (e >= w.thrE[ql]) {
-                    const int off = 8 * (r >> 2) + 4 * hf + (r & 3);
-                    const int64_t row = (int64_t)rbase + off;
-                    const int b = (int)((pw >> off) & 1u);
-                    c = make_cand(-(2 * e + b), (uint32_t)row);
-                    pend = row < row_end && c < w.thrC[ql];
-                }
+#pragma unroll
+    for (int i = 0; i < KCAP; ++i) {
+        const cand_t t = lst[i];
+        const bool lt = doit && c < t;
+        lst[i] = lt ? c : t;
+        c = lt ? t : c;
+    }
+}
+
+// Hand the first `svcnt` compacted candidates to the owner lanes, then publish the owners'
+// new thresholds.  Wave-uniform control flow; lane q owns query q.
+template <int KCAP>
+__device__ __forceinline__ void give_to_owners(const WaveQ &w, int svcnt, int lane, cand_t (&lst)[KCAP], cand_t seedC)
+{
+    wave_lds_sync();
+    for (int base = 0; base < svcnt; base += 64) {
+        const int idx = base + lane;
+        bool pend = idx < svcnt;
+        const cand_t c = pend ? w.svc[idx] : 0;
+        const int ql = pend ? w.svq[idx] : 0;
+        while (__ballot(pend)) {   // every round each query with candidates left takes one
+            if (pend) w.mbox[ql] = lane;
+            wave_lds_sync();
+            const int wl = w.mbox[lane];             // owner: the lane whose candidate I take, or -1
+            if (wl >= 0) w.mbox[lane] = -1;
+            const cand_t cw = shfl_cand(c, wl & 63);
+            const int taken = __shfl(wl, ql, 64);    // sender: which lane my query's owner took
+            reglist_insert<KCAP>(lst, cw, wl >= 0);
+            if (pend && taken == lane) pend = false;
+            wave_lds_sync();
+        }
+    }
+    const cand_t kth = lst[KCAP - 1];
+    const cand_t tc = kth < seedC ? kth : seedC;
+    w.thrC[lane] = tc;
+    w.thrE[lane] = thr_e(tc);
+    wave_lds_sync();
+}
+
+// Empty the wave's dump queue.  Wave-uniform control flow.
+template <bool L2, int KCAP>
+__device__ __forceinline__ void drain_queue(const WaveQ &w, int qcnt, int64_t row_end, int lane,
+                                            cand_t (&lst)[KCAP], cand_t seedC)
+{
+    if (qcnt <= 0) return;
+    wave_lds_sync();
+    // Lanes cover (dump, accumulator) pairs: DW = pow2 >= qcnt dumps side by side, 64/DW
+    // accumulator indices per step.
+    int lg = 32 - __builtin_clz((unsigned)(qcnt > 1 ? qcnt - 1 : 1) | 1u);
+    if (qcnt <= 1) lg = 0;
+    if (lg > 6) lg = 6;
+    const int d = lane & ((1 << lg) - 1), rsub = lane >> lg, rstep = 64 >> lg;
+    const bool live = d < qcnt;
+    const int meta = live ? w.qmeta[d] : 0;
+    const int ql = meta & 255, hf = meta >> 8;
+    const int rbase = live ? w.qrow[d] : 0;
+    const unsigned pw = (L2 && live) ? w.qpar[d] : 0u;
+    int svcnt = 0;
+    for (int r0 = 0; r0 < 16; r0 += rstep) {
+        const int r = r0 + rsub;
+        bool pass = live && r < 16;
+        cand_t c = 0;
+        if (pass) {
+            const int e = w.qvals[r * QCAP + d];
+            pass = e >= w.thrE[ql];
+            if (pass) {
+                const int off = 8 * (r >> 2) + 4 * hf + (r & 3);
+                const int64_t row = (int64_t)rbase + off;
+                const int b = (int)((pw >> off) & 1u);
+                c = make_cand(-(2 * e + b), (uint32_t)row);
+                pass = row < row_end && c < w.thrC[ql];
             }
-            while (__ballot(pend)) {  // one winner per query and round
-                if (pend) w.claim[ql] = lane;
-                wave_sync();
-                if (pend && w.claim[ql] == lane) {
-                    if (c < w.thrC[ql]) list_insert(w, k, ql, c);
-                    pend = false;
-                }
-                wave_sync();
+        }
+        const unsigned long long mask = __ballot(pass);
+        if (mask) {
+            const int pos = svcnt + __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),
+                                                               __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
+            if (pass) { w.svc[pos] = c; w.svq[pos] = ql; }
+            svcnt += __popcll(mask);
+            if (svcnt > SVCAP - 64) {
+                give_to_owners<KCAP>(w, svcnt, lane, lst, seedC);
+                svcnt = 0;
             }
         }
     }
+    if (svcnt) give_to_owners<KCAP>(w, svcnt, lane, lst, seedC);
 }
 
-// Swizzle of the 16-byte chunk slots of LDS row i (SLOTS slots per row, a power of two):
-// chunk c of row i lives in slot c ^ swz(i).  Conflict-free for ds_read_b128 of one chunk
-// column by 32 consecutive rows, with 32 or 64 LDS banks.
-template <int SLOTS>
-__device__ __forceinline__ int swz(int i)
-{
-    if (SLOTS == 16) return i & 15;
-    constexpr int A = SLOTS == 8 ? 0 : (SLOTS == 4 ? 1 : 2);
-    return ((i >> A) ^ (i >> 3)) & (SLOTS - 1);
-}
-
-template <int KS, int NB, bool L2>
+template <int KS, bool L2, int KCAP, bool SEED>
 __global__ __launch_bounds__(THREADS, 2) void search_mfma_kernel(
     SearchArgs a, int64_t row0, int64_t row1, int S, int64_t split_rows, int qtiles,
-    const cand_t *__restrict__ seeds, cand_t *__restrict__ lists_out)
+    const cand_t *__restrict__ seeds, cand_t *__restrict__ lists_out, int32_t *__restrict__ gmax, int SEG)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    constexpr int NQW = 32 * NB;           // queries per wave
-    constexpr int QT = WAVES * NQW;        // queries per workgroup
+    constexpr int NB = 2;
     constexpr int CPR = 2 * KS;            // 16-byte chunks per corpus row
     constexpr int SLOTS = CPR <= 2 ? 2 : (CPR <= 4 ? 4 : (CPR <= 8 ? 8 : 16));  // LDS slots per row
     constexpr int RS = KS <= 4 ? 64 : 32;  // corpus rows per stage
@@ -238,20 +204,25 @@ __global__ __launch_bounds__(THREADS, 2) void search_mfma_kernel(
 
     unsigned char *ring = smem;
     int *aux = (int *)(smem + NSTG * STAGE_BYTES);
-    unsigned char *wbase = (unsigned char *)(aux + NSTG * AUX_INTS);
-    unsigned char *wregion = wbase + (size_t)wave * wave_region_bytes(NQW, k);
-    const WaveState w = carve_wave(wregion, NQW);
+    int *flags = aux + NSTG * AUX_INTS;          // [2][4] joint-drain requests, double buffered
+    const WaveQ w = carve_waveq((unsigned char *)(flags + 8) + (size_t)wave * WAVEQ_BYTES);
 
     const int64_t q_first = (int64_t)qt * QT + wave * NQW;
-    if (lane < NQW) {
+
+    // ---- owner state (lane q owns query q of this wave) ------------------------------
+    cand_t lst[KCAP];
+    cand_t seedC = 0;
+    if (!SEED) {
         const int64_t gq = q_first + lane;
-        const cand_t sd = (gq < a.nq && !a.dry_run) ? (seeds ? seeds[gq] : CAND_NONE) : 0;
-        w.thrC[lane] = sd;
-        w.thrE[lane] = thr_e(sd);
-        w.cnt[lane] = 0;
-        w.worst[lane] = 0;
+        seedC = (gq < a.nq && !a.dry_run) ? (seeds ? seeds[gq] : CAND_NONE) : 0;
+        // slots beyond k are pinned to the smallest candidate, so lst[KCAP-1] is the k-th best
+#pragma unroll
+        for (int i = 0; i < KCAP; ++i) lst[i] = (i < KCAP - k) ? 0 : CAND_NONE;
+        w.thrC[lane] = seedC;
+        w.thrE[lane] = thr_e(seedC);
+        w.mbox[lane] = -1;
     }
-    wave_sync();
+    wave_lds_sync();
 
     v4i B[NB][KS];
 #pragma unroll
@@ -259,9 +230,12 @@ __global__ __launch_bounds__(THREADS, 2) void search_mfma_kernel(
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
             B[nb][ks] = *reinterpret_cast<const v4i *>(a.qcodes + (q_first + nb * 32 + col) * a.d_pad + ks * 32 + half * 16);
-    int thr[NB];
+    int thr[NB], gm[NB];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) thr[nb] = w.thrE[nb * 32 + col];
+    for (int nb = 0; nb < NB; ++nb) {
+        thr[nb] = SEED ? INT32_MAX : w.thrE[nb * 32 + col];
+        gm[nb] = INT32_MIN;
+    }
     int qcnt = 0;
     int a_off[KS];   // byte offset of this lane's A chunk of k-step ks inside a 32-row block of a stage
 #pragma unroll
@@ -299,17 +273,42 @@ __global__ __launch_bounds__(THREADS, 2) void search_mfma_kernel(
     } while (0)
 
     const int T = (re > rs) ? (int)((re - rs + RS - 1) / RS) : 0;
+
+    // Seeding pass: group maxima of segment g of this split go to gmax[q][(s*SEG + g)*2 + half].
+    const int G = S * SEG * 2;
+#define LPQ_FLUSH_SEGMENT(SEGIDX)                                                                       \
+    do {                                                                                                \
+        _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) {                                             \
+            gmax[(size_t)(q_first + nb * 32 + col) * G + ((size_t)s * SEG + (SEGIDX)) * 2 + half] = gm[nb]; \
+            gm[nb] = INT32_MIN;                                                                         \
+        }                                                                                               \
+    } while (0)
+    if (SEED) {   // segments this split never reaches keep the neutral value
+        for (int g = 0; g < SEG; ++g) LPQ_FLUSH_SEGMENT(g);
+    }
+
     // Query fragments have landed before any copy is issued, so inside the loop only async
     // copies are ever outstanding on the vector-memory counter.
     __builtin_amdgcn_s_waitcnt(0x0F70);
     for (int st = 0; st < NSTG - 1 && st < T; ++st) LPQ_ISSUE(st);
 
     for (int t = 0; t < T; ++t) {
+        if (!SEED && lane == 0) flags[(t & 1) * 4 + wave] = qcnt >= TRIG;
         // stages issued so far: 0 .. min(T-1, t+NSTG-2); wait until stage t has landed
         const int newer = (T - 1 < t + NSTG - 2 ? T - 1 : t + NSTG - 2) - t;
         wait_vmcnt(newer * lpt);
         __syncthreads();   // everybody's part of stage t is in LDS; stage t-1 is no longer read
         if (t + NSTG - 1 < T) LPQ_ISSUE(t + NSTG - 1);   // refills the slot of stage t-1
+
+        if (!SEED) {
+            const v4i f = *reinterpret_cast<const v4i *>(flags + (t & 1) * 4);
+            if (f[0] | f[1] | f[2] | f[3]) {   // same answer in all four waves: drain together
+                drain_queue<L2, KCAP>(w, qcnt, re, lane, lst, seedC);
+                qcnt = 0;
+#pragma unroll
+                for (int j = 0; j < NB; ++j) thr[j] = w.thrE[j * 32 + col];
+            }
+        }
 
         const unsigned char *sb = ring + (size_t)(t % NSTG) * STAGE_BYTES;
         const int *cb = aux + (t % NSTG) * AUX_INTS;
@@ -349,12 +348,15 @@ __global__ __launch_bounds__(THREADS, 2) void search_mfma_kernel(
                 m = max(max(m, v[11]), v[12]);
                 m = max(max(m, v[13]), v[14]);
                 m = max(m, v[15]);
+                if (SEED) {
+                    gm[nb] = max(gm[nb], m);
+                    continue;
+                }
                 bool trip = m >= thr[nb];
                 unsigned long long mask = __ballot(trip);
                 if (mask) {
-                    if (qcnt + __popcll(mask) > QCAP) {
-                        drain_queue<L2>(wregion, NQW, qcnt, k, re, lane);
-                        wave_sync();
+                    if (qcnt + __popcll(mask) > QCAP) {   // no room: this wave drains alone
+                        drain_queue<L2, KCAP>(w, qcnt, re, lane, lst, seedC);
                         qcnt = 0;
 #pragma unroll
                         for (int j = 0; j < NB; ++j) thr[j] = w.thrE[j * 32 + col];
@@ -377,41 +379,71 @@ __global__ __launch_bounds__(THREADS, 2) void search_mfma_kernel(
                 }
             }
         }
+        if (SEED) {   // close a segment when the next stage belongs to the next one
+            const int seg = (int)((int64_t)t * SEG / T), seg_next = (int)((int64_t)(t + 1) * SEG / T);
+            if (t + 1 == T || seg_next != seg) {
+                LPQ_FLUSH_SEGMENT(seg);
+                __builtin_amdgcn_s_waitcnt(0x0F70);   // keep the counter to async copies only
+            }
+        }
     }
 #undef LPQ_ISSUE
+#undef LPQ_FLUSH_SEGMENT
 
-    drain_queue<L2>(wregion, NQW, qcnt, k, re, lane);
-    wave_sync();
-    if (lane < NQW) {
+    if (!SEED) {
+        drain_queue<L2, KCAP>(w, qcnt, re, lane, lst, seedC);
         const int64_t gq = q_first + lane;
         if (gq < a.nq) {
             cand_t *out = lists_out + ((size_t)gq * S + s) * k;
-            const int n = w.cnt[lane];
-            const cand_t *list = w.lists + (size_t)lane * k;
-            for (int i = 0; i < k; ++i) out[i] = (i < n) ? list[i] : CAND_NONE;
+#pragma unroll
+            for (int i = 0; i < KCAP; ++i)
+                if (i >= KCAP - k) out[i - (KCAP - k)] = lst[i];   // pinned slots are skipped; empty ones are CAND_NONE
         }
     }
 }
 
-size_t lds_bytes(int ks, int nb, int k)
+// One workgroup per query: the k-th largest of its G group maxima becomes the seed threshold.
+__global__ __launch_bounds__(128) void seed_finalize_kernel(const int32_t *__restrict__ gmax, int G, int cap, int k,
+                                                            cand_t *__restrict__ seeds)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    int *buf = reinterpret_cast<int *>(smem);
+    const int64_t q = blockIdx.x;
+    for (int i = threadIdx.x; i < cap; i += 128) buf[i] = (i < G) ? gmax[q * G + i] : INT32_MIN;
+    __syncthreads();
+    for (int size = 2; size <= cap; size <<= 1) {          // bitonic sort, descending
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int i = threadIdx.x; i < (cap >> 1); i += 128) {
+                const int lo = 2 * i - (i & (stride - 1)), hi = lo + stride;
+                const bool down = (lo & size) == 0;
+                const int x = buf[lo], y = buf[hi];
+                if ((x < y) == down) { buf[lo] = y; buf[hi] = x; }
+            }
+            __syncthreads();
+        }
+    }
+    if (threadIdx.x == 0) {
+        const int e = buf[k - 1];   // at least k items have E >= e, hence key <= -2e
+        seeds[q] = (G < k || e == INT32_MIN) ? CAND_NONE : make_cand(-2 * e, 0xFFFFFFFFu);
+    }
+}
+
+size_t lds_bytes(int ks, bool seed)
 {
     const int cpr = 2 * ks;
     const int slots = cpr <= 2 ? 2 : (cpr <= 4 ? 4 : (cpr <= 8 ? 8 : 16));
     const int rs = ks <= 4 ? 64 : 32;
-    return (size_t)NSTG * rs * slots * 16 + (size_t)NSTG * (rs + 4) * 4 + WAVES * wave_region_bytes(32 * nb, k);
+    return (size_t)NSTG * rs * slots * 16 + (size_t)NSTG * (rs + 4) * 4 + 32 + (seed ? 0 : WAVES * WAVEQ_BYTES);
 }
 
-int nb_for(int k) { return k <= 16 ? 2 : 1; }
-
-template <int KS, int NB, bool L2>
+template <int KS, bool L2, int KCAP, bool SEED>
 hipError_t launch_one(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds, cand_t *lists,
-                      hipStream_t st)
+                      int32_t *gmax, int SEG, hipStream_t st)
 {
-    const int qt = 128 * NB;
-    const int qtiles = (int)ceil_div(a.nq, qt);
+    const int qtiles = (int)ceil_div(a.nq, QT);
     const int64_t split_rows = round_up(ceil_div(row1 - row0, S), 64);
-    const size_t lds = lds_bytes(KS, NB, a.k);
-    auto kern = search_mfma_kernel<KS, NB, L2>;
+    const size_t lds = lds_bytes(KS, SEED);
+    auto kern = search_mfma_kernel<KS, L2, KCAP, SEED>;
     static bool attr_set = false;  // per instantiation
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -419,46 +451,81 @@ hipError_t launch_one(const SearchArgs &a, int64_t row0, int64_t row1, int S, co
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    kern<<<(unsigned)(qtiles * S), THREADS, lds, st>>>(a, row0, row1, S, split_rows, qtiles, seeds, lists);
+    kern<<<(unsigned)(qtiles * S), THREADS, lds, st>>>(a, row0, row1, S, split_rows, qtiles, seeds, lists, gmax, SEG);
     return hipGetLastError();
 }
 
 template <int KS>
 hipError_t launch_ks(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds, cand_t *lists,
-                     hipStream_t st)
+                     int32_t *gmax, int SEG, hipStream_t st)
 {
     const bool l2 = a.metric == LPQ_METRIC_L2SQ;
-    if (nb_for(a.k) == 2)
-        return l2 ? launch_one<KS, 2, true>(a, row0, row1, S, seeds, lists, st)
-                  : launch_one<KS, 2, false>(a, row0, row1, S, seeds, lists, st);
-    return l2 ? launch_one<KS, 1, true>(a, row0, row1, S, seeds, lists, st)
-              : launch_one<KS, 1, false>(a, row0, row1, S, seeds, lists, st);
+    if (gmax)
+        return l2 ? launch_one<KS, true, 1, true>(a, row0, row1, S, seeds, lists, gmax, SEG, st)
+                  : launch_one<KS, false, 1, true>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
+    if (a.k <= 10)
+        return l2 ? launch_one<KS, true, 10, false>(a, row0, row1, S, seeds, lists, gmax, SEG, st)
+                  : launch_one<KS, false, 10, false>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
+    return l2 ? launch_one<KS, true, 16, false>(a, row0, row1, S, seeds, lists, gmax, SEG, st)
+              : launch_one<KS, false, 16, false>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
 }
 
-}  // namespace
-
-bool mfma_supported(int d_pad, int k)
-{
-    const int ks = d_pad / 32;
-    if (d_pad % 32 || !(ks == 2 || ks == 3 || ks == 4 || ks == 6 || ks == 8)) return false;
-    return k >= 1 && lds_bytes(ks, nb_for(k), k) <= 160 * 1024;
-}
-
-size_t mfma_list_scratch_bytes(int64_t, int, int) { return 0; }
-
-hipError_t launch_search_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds,
-                              cand_t *lists, void *, hipStream_t st)
+hipError_t launch_any(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds, cand_t *lists,
+                      int32_t *gmax, int SEG, hipStream_t st)
 {
     if (a.nq <= 0 || row1 <= row0) return hipSuccess;
     if (row0 % 64) return hipErrorInvalidValue;  // stages and parity words cover aligned blocks
     switch (a.d_pad / 32) {
-    case 2: return launch_ks<2>(a, row0, row1, S, seeds, lists, st);
-    case 3: return launch_ks<3>(a, row0, row1, S, seeds, lists, st);
-    case 4: return launch_ks<4>(a, row0, row1, S, seeds, lists, st);
-    case 6: return launch_ks<6>(a, row0, row1, S, seeds, lists, st);
-    case 8: return launch_ks<8>(a, row0, row1, S, seeds, lists, st);
+    case 2: return launch_ks<2>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
+    case 3: return launch_ks<3>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
+    case 4: return launch_ks<4>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
+    case 6: return launch_ks<6>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
+    case 8: return launch_ks<8>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
     default: return hipErrorInvalidValue;
     }
+}
+
+bool shape_ok(int d_pad)
+{
+    const int ks = d_pad / 32;
+    return d_pad % 32 == 0 && (ks == 2 || ks == 3 || ks == 4 || ks == 6 || ks == 8);
+}
+
+}  // namespace
+
+bool mfma_reg_supported(int d_pad, int k) { return shape_ok(d_pad) && k >= 1 && k <= 16; }
+
+bool mfma_supported(int d_pad, int k) { return mfma_reg_supported(d_pad, k) || mfma_lds_supported(d_pad, k); }
+
+hipError_t launch_search_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds,
+                              cand_t *lists, hipStream_t st)
+{
+    if (mfma_reg_supported(a.d_pad, a.k)) return launch_any(a, row0, row1, S, seeds, lists, nullptr, 0, st);
+    return launch_search_mfma_lds(a, row0, row1, S, seeds, lists, st);
+}
+
+int mfma_seed_segments(int S, int k)
+{
+    int seg = (int)ceil_div(3 * k, S);   // 2 * S * SEG >= 6k groups: the k-th largest is then
+    if (seg < 1) seg = 1;                // close to the k-th best item of the seeded rows
+    while (2 * S * seg > 1024 && seg > 1) --seg;
+    return seg;
+}
+
+hipError_t launch_seed_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S, int SEG, int32_t *gmax,
+                            hipStream_t st)
+{
+    if (!mfma_reg_supported(a.d_pad, a.k) || !gmax) return hipErrorInvalidValue;
+    return launch_any(a, row0, row1, S, nullptr, nullptr, gmax, SEG, st);
+}
+
+hipError_t launch_seed_finalize(const int32_t *gmax, int64_t nq, int G, int k, cand_t *seeds, hipStream_t st)
+{
+    if (nq <= 0) return hipSuccess;
+    const int cap = next_pow2(G < 2 ? 2 : G);
+    if (cap > 2048) return hipErrorInvalidValue;
+    seed_finalize_kernel<<<(unsigned)nq, 128, (size_t)cap * sizeof(int), st>>>(gmax, G, cap, k, seeds);
+    return hipGetLastError();
 }
 
 }  // namespace lpq
