@@ -336,7 +336,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     const int64_t want = g_tune[LPQ_TUNE_PATH];
     if (want != 1 && mfma_reg_supported(idx->d_pad, k)) p.mode = PLAN_MFMA_REG;
     else if (want != 1 && mfma_lds_supported(idx->d_pad, k)) p.mode = PLAN_MFMA_LDS;
-    p.nq_pad = round_up(nq > 0 ? nq : 1, 256);
+    p.nq_pad = round_up(nq > 0 ? nq : 1, 512);
     const int max_lists = merge_max_lists(k);
     const int64_t slots = 512;   // workgroups of the matrix-core kernels resident at once (2 per CU)
 
@@ -355,7 +355,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     if (seed < 64 * k || seed * 4 > n) seed = 0;
     p.seed_rows = seed;
 
-    auto splits_for = [&](int64_t rows, int64_t tiles_q, int64_t min_rows) {
+    auto splits_for = [&](int64_t rows, int64_t tiles_q, int64_t min_rows, int64_t slots) {
         int64_t s;
         if (p.mode != PLAN_GENERIC) s = g_tune[LPQ_TUNE_SPLITS] > 0 ? g_tune[LPQ_TUNE_SPLITS] : slots / (tiles_q > 0 ? tiles_q : 1);
         else s = g_tune[LPQ_TUNE_SPLITS] > 0 ? g_tune[LPQ_TUNE_SPLITS] : ceil_div(2048, nq > 0 ? nq : 1);
@@ -365,14 +365,19 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
         if (s < 1) s = 1;
         return (int)s;
     };
-    const int64_t qt = (p.mode == PLAN_MFMA_LDS && k > 16) ? 128 : 256;   // queries per workgroup
+    int64_t qt = (p.mode == PLAN_MFMA_LDS && k > 16) ? 128 : 256;   // queries per workgroup
+    int64_t slots_now = slots;
+    if (p.mode == PLAN_MFMA_REG) {
+        qt = mfma_queries_per_workgroup(nq, idx->d_pad);
+        if (qt == 512) slots_now = 256;   // eight-wave workgroups: one per CU
+    }
     const int64_t tiles_q = ceil_div(nq > 0 ? nq : 1, qt);
     const int64_t min_rows = p.mode == PLAN_GENERIC ? 2048 : 512;
     if (seed) {
-        p.S1 = splits_for(seed, tiles_q, min_rows);
+        p.S1 = splits_for(seed, tiles_q, min_rows, slots_now);
         if (p.mode == PLAN_MFMA_REG) p.SEG = mfma_seed_segments(p.S1, k);
     }
-    p.S2 = splits_for(p.mode == PLAN_MFMA_REG ? n : n - seed, tiles_q, min_rows);
+    p.S2 = splits_for(p.mode == PLAN_MFMA_REG ? n : n - seed, tiles_q, min_rows, slots_now);
 
     size_t o = 0;
     p.off_qcodes = o;   o = align256(o + (size_t)p.nq_pad * idx->d_pad);
@@ -412,7 +417,7 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k
     a.n = idx->size; a.d_pad = idx->d_pad;
     a.qcodes = reinterpret_cast<const int8_t *>(ws + p.off_qcodes);
     a.nq = nq; a.k = k; a.metric = metric;
-    a.dry_run = g_tune[LPQ_TUNE_DRY_RUN] != 0;
+    a.dry_run = (int)g_tune[LPQ_TUNE_DRY_RUN];
     const int32_t *qnorms = reinterpret_cast<const int32_t *>(ws + p.off_qnorms);
     cand_t *lists1 = reinterpret_cast<cand_t *>(ws + p.off_lists1);
     cand_t *seedlist = reinterpret_cast<cand_t *>(ws + p.off_seedlist);

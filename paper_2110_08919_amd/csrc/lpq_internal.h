@@ -99,7 +99,7 @@ struct SearchArgs {
     int64_t nq;
     int k;
     int metric;
-    bool dry_run;           // timing experiments: never collect a candidate
+    int dry_run;            // timing experiments: != 0 never collects a candidate (2..4: ablations)
 };
 
 // Generic kernel: one workgroup per (query, corpus split); any d_pad (multiple of 32), any k.
@@ -120,6 +120,7 @@ hipError_t launch_search_mfma_lds(const SearchArgs &a, int64_t row0, int64_t row
 // Seeding pass of the register variant: group maxima gmax[nq_pad][2*S*SEG] over rows
 // [row0, row1) (all of them real items), then seeds[q] = bound from the k-th largest.
 int mfma_seed_segments(int S, int k);
+int mfma_queries_per_workgroup(int64_t nq, int d_pad);   // query tile of the register variant: 256 or 512
 hipError_t launch_seed_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S, int SEG, int32_t *gmax,
                             hipStream_t st);
 hipError_t launch_seed_finalize(const int32_t *gmax, int64_t nq, int G, int k, cand_t *seeds, hipStream_t st);

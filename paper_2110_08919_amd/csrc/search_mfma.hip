@@ -39,7 +39,6 @@ namespace lpq {
 namespace {
 
 constexpr int NQW = 64;      // queries per wave = lanes per wave: lane q owns query q
-constexpr int QT = WAVES * NQW;
 constexpr int TRIG = 32;     // queue fill that asks for a joint drain at the next stage boundary
 constexpr int SVCAP = 128;   // compacted candidates buffered before they are handed to owners
 
@@ -171,20 +170,23 @@ __device__ __forceinline__ void drain_queue(const WaveQ &w, int qcnt, int64_t ro
     if (svcnt) give_to_owners<KCAP>(w, svcnt, lane, lst, seedC);
 }
 
-template <int KS, bool L2, int KCAP, bool SEED>
-__global__ __launch_bounds__(THREADS, 2) void search_mfma_kernel(
+template <int KS, bool L2, int KCAP, bool SEED, int NW>
+__global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     SearchArgs a, int64_t row0, int64_t row1, int S, int64_t split_rows, int qtiles,
     const cand_t *__restrict__ seeds, cand_t *__restrict__ lists_out, int32_t *__restrict__ gmax, int SEG)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int NB = 2;
+    constexpr int QT = NW * NQW;           // queries per workgroup
     constexpr int CPR = 2 * KS;            // 16-byte chunks per corpus row
     constexpr int SLOTS = CPR <= 2 ? 2 : (CPR <= 4 ? 4 : (CPR <= 8 ? 8 : 16));  // LDS slots per row
-    constexpr int RS = KS <= 4 ? 64 : 32;  // corpus rows per stage
+    constexpr int RS = 64;                 // corpus rows per stage: two 32-row blocks
+    constexpr int NST = KS <= 4 ? 4 : 3;   // LDS ring depth
     constexpr int STAGE_BYTES = RS * SLOTS * 16;
-    constexpr int IPW = RS * SLOTS / 64 / WAVES;   // async copy instructions per wave and stage
+    constexpr int IPW = RS * SLOTS / 64 / NW;   // async copy instructions per wave and stage
     constexpr int AUX_INTS = RS + 4;       // cinit[RS] then parity words
-    static_assert(RS * SLOTS % (64 * WAVES) == 0 && IPW >= 1, "stage must split evenly over the waves");
+    static_assert(RS * SLOTS % (64 * NW) == 0 && IPW >= 1, "stage must split evenly over the waves");
+    static_assert((NST - 1) * (IPW + 1) <= 15, "wait_vmcnt covers 0..15");
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction
@@ -203,9 +205,9 @@ __global__ __launch_bounds__(THREADS, 2) void search_mfma_kernel(
     const int64_t re = (rs + split_rows < row1) ? rs + split_rows : row1;
 
     unsigned char *ring = smem;
-    int *aux = (int *)(smem + NSTG * STAGE_BYTES);
-    int *flags = aux + NSTG * AUX_INTS;          // [2][4] joint-drain requests, double buffered
-    const WaveQ w = carve_waveq((unsigned char *)(flags + 8) + (size_t)wave * WAVEQ_BYTES);
+    int *aux = (int *)(smem + NST * STAGE_BYTES);
+    int *flags = aux + NST * AUX_INTS;           // [2][8] joint-drain requests, double buffered
+    const WaveQ w = carve_waveq((unsigned char *)(flags + 16) + (size_t)wave * WAVEQ_BYTES);
 
     const int64_t q_first = (int64_t)qt * QT + wave * NQW;
 
@@ -214,7 +216,7 @@ __global__ __launch_bounds__(THREADS, 2) void search_mfma_kernel(
     cand_t seedC = 0;
     if (!SEED) {
         const int64_t gq = q_first + lane;
-        seedC = (gq < a.nq && !a.dry_run) ? (seeds ? seeds[gq] : CAND_NONE) : 0;
+        seedC = (gq < a.nq && a.dry_run == 0) ? (seeds ? seeds[gq] : CAND_NONE) : 0;
         // slots beyond k are pinned to the smallest candidate, so lst[KCAP-1] is the k-th best
 #pragma unroll
         for (int i = 0; i < KCAP; ++i) lst[i] = (i < KCAP - k) ? 0 : CAND_NONE;
@@ -260,15 +262,84 @@ __global__ __launch_bounds__(THREADS, 2) void search_mfma_kernel(
     do {                                                                                                \
         const int st_ = (ST);                                                                           \
         const int64_t r0_ = rs + (int64_t)st_ * RS;                                                     \
-        const int ring_slot_ = st_ % NSTG;                                                              \
+        const int ring_slot_ = st_ % NST;                                                               \
         const int8_t *src_ = a.codes + r0_ * (32 * KS);                                                 \
         _Pragma("unroll") for (int j = 0; j < IPW; ++j)                                                 \
             async_copy16(src_ + src_off[j], ring_lds + ring_slot_ * STAGE_BYTES + (wave * IPW + j) * 1024); \
         if (L2 && wave == 0) {                                                                          \
-            if (lane < RS) async_copy4(a.cinit + r0_ + lane, aux_lds + ring_slot_ * AUX_INTS * 4);      \
+            async_copy4(a.cinit + r0_ + lane, aux_lds + ring_slot_ * AUX_INTS * 4);                     \
         } else if (L2 && wave == 1) {                                                                   \
             if (lane < RS / 32)                                                                         \
                 async_copy4(a.parity + r0_ / 32 + lane, aux_lds + (ring_slot_ * AUX_INTS + RS) * 4);    \
+        }                                                                                               \
+    } while (0)
+
+    // Operands of one 32-row block, LDS -> registers: the A fragments, the accumulator seeds
+    // of this lane's 16 rows, and the block's parity word.
+#define LPQ_LOAD_BLOCK(TT, BLK, AREG, CREG, PREG)                                                       \
+    do {                                                                                                \
+        const unsigned char *sb_ = ring + (size_t)((TT) % NST) * STAGE_BYTES + (BLK) * 32 * (SLOTS * 16); \
+        const int *cb_ = aux + ((TT) % NST) * AUX_INTS;                                                 \
+        _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                               \
+            AREG[ks] = *reinterpret_cast<const v4i *>(sb_ + a_off[ks]);                                 \
+        if (L2) {                                                                                       \
+            _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                             \
+                const v4i v_ = *reinterpret_cast<const v4i *>(cb_ + (BLK) * 32 + 8 * g + 4 * half);     \
+                CREG[4 * g + 0] = v_[0]; CREG[4 * g + 1] = v_[1];                                       \
+                CREG[4 * g + 2] = v_[2]; CREG[4 * g + 3] = v_[3];                                       \
+            }                                                                                           \
+            PREG = (unsigned)cb_[RS + (BLK)];                                                           \
+        } else {                                                                                        \
+            _Pragma("unroll") for (int i = 0; i < 16; ++i) CREG[i] = 0;                                 \
+            PREG = 0u;                                                                                  \
+        }                                                                                               \
+    } while (0)
+
+    // Contraction of one block against the wave's 64 queries, then the filter epilogue.
+#define LPQ_BLOCK(TT, BLK, AREG, CREG, PREG)                                                            \
+    do {                                                                                                \
+        v16i acc[NB];                                                                                   \
+        _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                               \
+            _Pragma("unroll") for (int nb = 0; nb < NB; ++nb)                                           \
+                acc[nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(AREG[ks], B[nb][ks], ks == 0 ? CREG : acc[nb], 0, 0, 0); \
+        const int rowbase = (int)(rs + (int64_t)(TT) * RS + (BLK) * 32);                                \
+        _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) {                                             \
+            const v16i v = acc[nb];                                                                     \
+            int m = max(max(v[0], v[1]), v[2]);                                                         \
+            m = max(max(m, v[3]), v[4]);                                                                \
+            m = max(max(m, v[5]), v[6]);                                                                \
+            m = max(max(m, v[7]), v[8]);                                                                \
+            m = max(max(m, v[9]), v[10]);                                                               \
+            m = max(max(m, v[11]), v[12]);                                                              \
+            m = max(max(m, v[13]), v[14]);                                                              \
+            m = max(m, v[15]);                                                                          \
+            if (SEED) {                                                                                 \
+                gm[nb] = max(gm[nb], m);                                                                \
+                continue;                                                                               \
+            }                                                                                           \
+            bool trip = m >= thr[nb];                                                                   \
+            unsigned long long mask = __ballot(trip);                                                   \
+            if (mask) {                                                                                 \
+                if (qcnt + __popcll(mask) > QCAP) { /* no room: this wave drains alone */               \
+                    drain_queue<L2, KCAP>(w, qcnt, re, lane, lst, seedC);                               \
+                    qcnt = 0;                                                                           \
+                    _Pragma("unroll") for (int j = 0; j < NB; ++j) thr[j] = w.thrE[j * 32 + col];       \
+                    trip = m >= thr[nb];                                                                \
+                    mask = __ballot(trip);                                                              \
+                }                                                                                       \
+                if (mask) {                                                                             \
+                    const int below = __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),                 \
+                                                                __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u)); \
+                    if (trip) {                                                                         \
+                        const int slot = qcnt + below;                                                  \
+                        _Pragma("unroll") for (int r = 0; r < 16; ++r) w.qvals[r * QCAP + slot] = v[r]; \
+                        w.qrow[slot] = rowbase;                                                         \
+                        w.qpar[slot] = PREG;                                                            \
+                        w.qmeta[slot] = (nb * 32 + col) | (half << 8);                                  \
+                    }                                                                                   \
+                    qcnt += __popcll(mask);                                                             \
+                }                                                                                       \
+            }                                                                                           \
         }                                                                                               \
     } while (0)
 
@@ -287,98 +358,56 @@ __global__ __launch_bounds__(THREADS, 2) void search_mfma_kernel(
         for (int g = 0; g < SEG; ++g) LPQ_FLUSH_SEGMENT(g);
     }
 
-    // Query fragments have landed before any copy is issued, so inside the loop only async
-    // copies are ever outstanding on the vector-memory counter.
+    // Query fragments (and the stores above) have completed before any copy is issued, so from
+    // here on only async copies are outstanding on the vector-memory counter.
     __builtin_amdgcn_s_waitcnt(0x0F70);
-    for (int st = 0; st < NSTG - 1 && st < T; ++st) LPQ_ISSUE(st);
 
+    // Software pipeline.  While block (t, 0) is in the matrix core the operands of (t, 1) are read
+    // from LDS; while (t, 1) is in the matrix core the operands of (t+1, 0) are read.  The
+    // workgroup barrier sits in front of block (t, 1): by then every wave has finished READING
+    // stage t (its last LDS reads were waited for), so the ring slot of stage t can be refilled
+    // with stage t + NST, and stage t+1 is known to have landed.
+    v4i A0[KS], A1[KS];
+    v16i C0, C1;
+    unsigned P0 = 0, P1 = 0;
+    const bool abl_nodma = a.dry_run >= 3, abl_nobar = a.dry_run == 2 || a.dry_run == 4;   // timing ablations
+    const int primed = T < NST ? T : NST;
+    if (!abl_nodma) for (int st = 0; st < primed; ++st) LPQ_ISSUE(st);
+    if (T > 0) {
+        wait_vmcnt((primed - 1) * lpt);
+        __syncthreads();
+        LPQ_LOAD_BLOCK(0, 0, A0, C0, P0);
+    }
     for (int t = 0; t < T; ++t) {
-        if (!SEED && lane == 0) flags[(t & 1) * 4 + wave] = qcnt >= TRIG;
-        // stages issued so far: 0 .. min(T-1, t+NSTG-2); wait until stage t has landed
-        const int newer = (T - 1 < t + NSTG - 2 ? T - 1 : t + NSTG - 2) - t;
-        wait_vmcnt(newer * lpt);
-        __syncthreads();   // everybody's part of stage t is in LDS; stage t-1 is no longer read
-        if (t + NSTG - 1 < T) LPQ_ISSUE(t + NSTG - 1);   // refills the slot of stage t-1
+        LPQ_LOAD_BLOCK(t, 1, A1, C1, P1);
+        LPQ_BLOCK(t, 0, A0, C0, P0);
 
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // my reads of stage t are complete
+        if (!SEED && lane == 0) flags[(t & 1) * 8 + wave] = qcnt >= TRIG;
+        if (t + 1 < T && !abl_nodma) {
+            // stages issued so far: 0 .. min(T-1, t+NST-1); stage t+1 must have landed
+            const int last = T - 1 < t + NST - 1 ? T - 1 : t + NST - 1;
+            wait_vmcnt((last - (t + 1)) * lpt);
+        }
+        if (!abl_nobar) __syncthreads();
+        if (t + NST < T && !abl_nodma) LPQ_ISSUE(t + NST);   // refills the slot of stage t
         if (!SEED) {
-            const v4i f = *reinterpret_cast<const v4i *>(flags + (t & 1) * 4);
-            if (f[0] | f[1] | f[2] | f[3]) {   // same answer in all four waves: drain together
+            const v4i f = *reinterpret_cast<const v4i *>(flags + (t & 1) * 8);
+            int any = f[0] | f[1] | f[2] | f[3];
+            if (NW > 4) {
+                const v4i g = *reinterpret_cast<const v4i *>(flags + (t & 1) * 8 + 4);
+                any |= g[0] | g[1] | g[2] | g[3];
+            }
+            if (any) {   // same answer in every wave of the workgroup: drain together
                 drain_queue<L2, KCAP>(w, qcnt, re, lane, lst, seedC);
                 qcnt = 0;
 #pragma unroll
                 for (int j = 0; j < NB; ++j) thr[j] = w.thrE[j * 32 + col];
             }
         }
+        if (t + 1 < T) LPQ_LOAD_BLOCK(t + 1, 0, A0, C0, P0);
+        LPQ_BLOCK(t, 1, A1, C1, P1);
 
-        const unsigned char *sb = ring + (size_t)(t % NSTG) * STAGE_BYTES;
-        const int *cb = aux + (t % NSTG) * AUX_INTS;
-#pragma unroll
-        for (int blk = 0; blk < RS / 32; ++blk) {
-            v16i c0;
-            if (L2) {
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const v4i v = *reinterpret_cast<const v4i *>(cb + blk * 32 + 8 * g + 4 * half);
-                    c0[4 * g + 0] = v[0]; c0[4 * g + 1] = v[1]; c0[4 * g + 2] = v[2]; c0[4 * g + 3] = v[3];
-                }
-            } else {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) c0[i] = 0;
-            }
-            v4i A[KS];
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                A[ks] = *reinterpret_cast<const v4i *>(sb + blk * 32 * (SLOTS * 16) + a_off[ks]);
-            v16i acc[NB];
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    acc[nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[ks], B[nb][ks], ks == 0 ? c0 : acc[nb], 0, 0, 0);
-
-            const int rowbase = (int)(rs + (int64_t)t * RS + blk * 32);
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const v16i v = acc[nb];
-                int m = max(max(v[0], v[1]), v[2]);
-                m = max(max(m, v[3]), v[4]);
-                m = max(max(m, v[5]), v[6]);
-                m = max(max(m, v[7]), v[8]);
-                m = max(max(m, v[9]), v[10]);
-                m = max(max(m, v[11]), v[12]);
-                m = max(max(m, v[13]), v[14]);
-                m = max(m, v[15]);
-                if (SEED) {
-                    gm[nb] = max(gm[nb], m);
-                    continue;
-                }
-                bool trip = m >= thr[nb];
-                unsigned long long mask = __ballot(trip);
-                if (mask) {
-                    if (qcnt + __popcll(mask) > QCAP) {   // no room: this wave drains alone
-                        drain_queue<L2, KCAP>(w, qcnt, re, lane, lst, seedC);
-                        qcnt = 0;
-#pragma unroll
-                        for (int j = 0; j < NB; ++j) thr[j] = w.thrE[j * 32 + col];
-                        trip = m >= thr[nb];
-                        mask = __ballot(trip);
-                    }
-                    if (mask) {
-                        const int below = __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),
-                                                                    __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
-                        if (trip) {
-                            const int slot = qcnt + below;
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) w.qvals[r * QCAP + slot] = v[r];
-                            w.qrow[slot] = rowbase;
-                            w.qpar[slot] = L2 ? (unsigned)cb[RS + blk] : 0u;
-                            w.qmeta[slot] = (nb * 32 + col) | (half << 8);
-                        }
-                        qcnt += __popcll(mask);
-                    }
-                }
-            }
-        }
         if (SEED) {   // close a segment when the next stage belongs to the next one
             const int seg = (int)((int64_t)t * SEG / T), seg_next = (int)((int64_t)(t + 1) * SEG / T);
             if (t + 1 == T || seg_next != seg) {
@@ -388,6 +417,8 @@ __global__ __launch_bounds__(THREADS, 2) void search_mfma_kernel(
         }
     }
 #undef LPQ_ISSUE
+#undef LPQ_LOAD_BLOCK
+#undef LPQ_BLOCK
 #undef LPQ_FLUSH_SEGMENT
 
     if (!SEED) {
@@ -428,22 +459,22 @@ __global__ __launch_bounds__(128) void seed_finalize_kernel(const int32_t *__res
     }
 }
 
-size_t lds_bytes(int ks, bool seed)
+size_t lds_bytes(int ks, bool seed, int nw)
 {
     const int cpr = 2 * ks;
     const int slots = cpr <= 2 ? 2 : (cpr <= 4 ? 4 : (cpr <= 8 ? 8 : 16));
-    const int rs = ks <= 4 ? 64 : 32;
-    return (size_t)NSTG * rs * slots * 16 + (size_t)NSTG * (rs + 4) * 4 + 32 + (seed ? 0 : WAVES * WAVEQ_BYTES);
+    const int nst = ks <= 4 ? 4 : 3;
+    return (size_t)nst * 64 * slots * 16 + (size_t)nst * (64 + 4) * 4 + 64 + (seed ? 0 : nw * WAVEQ_BYTES);
 }
 
-template <int KS, bool L2, int KCAP, bool SEED>
-hipError_t launch_one(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds, cand_t *lists,
-                      int32_t *gmax, int SEG, hipStream_t st)
+template <int KS, bool L2, int KCAP, bool SEED, int NW>
+hipError_t launch_nw(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds, cand_t *lists,
+                     int32_t *gmax, int SEG, hipStream_t st)
 {
-    const int qtiles = (int)ceil_div(a.nq, QT);
+    const int qtiles = (int)ceil_div(a.nq, NW * NQW);
     const int64_t split_rows = round_up(ceil_div(row1 - row0, S), 64);
-    const size_t lds = lds_bytes(KS, SEED);
-    auto kern = search_mfma_kernel<KS, L2, KCAP, SEED>;
+    const size_t lds = lds_bytes(KS, SEED, NW);
+    auto kern = search_mfma_kernel<KS, L2, KCAP, SEED, NW>;
     static bool attr_set = false;  // per instantiation
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -451,8 +482,18 @@ hipError_t launch_one(const SearchArgs &a, int64_t row0, int64_t row1, int S, co
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    kern<<<(unsigned)(qtiles * S), THREADS, lds, st>>>(a, row0, row1, S, split_rows, qtiles, seeds, lists, gmax, SEG);
+    kern<<<(unsigned)(qtiles * S), NW * 64, lds, st>>>(a, row0, row1, S, split_rows, qtiles, seeds, lists, gmax, SEG);
     return hipGetLastError();
+}
+
+// Four waves (256 queries) per workgroup, two workgroups per CU.  Eight-wave workgroups (one per
+// CU, half the corpus bytes per contraction) measured slower: the wider barrier costs more than
+// the saved L1 traffic.
+template <int KS, bool L2, int KCAP, bool SEED>
+hipError_t launch_one(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds, cand_t *lists,
+                      int32_t *gmax, int SEG, hipStream_t st)
+{
+    return launch_nw<KS, L2, KCAP, SEED, 4>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
 }
 
 template <int KS>
@@ -492,6 +533,8 @@ bool shape_ok(int d_pad)
 }
 
 }  // namespace
+
+int mfma_queries_per_workgroup(int64_t, int) { return 256; }
 
 bool mfma_reg_supported(int d_pad, int k) { return shape_ok(d_pad) && k >= 1 && k <= 16; }
 
