@@ -20,6 +20,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_INT8_OPS = 5.0e15      # MI355X dense int8 matrix peak, op/s
 PEAK_HBM = 8.0e12           # MI355X HBM3E, B/s
+# HBM bytes of one search of the default workload (seeding pass + main scan), from the rocprofv3
+# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/search_mfma_kernel_skewed_int_1m_x128_pmc.txt
+# (FETCH_SIZE scaled by 2.000, WRITE_SIZE by 1.000 against a 512 MiB copy in the same run).
+TRAFFIC_BYTES_DEFAULT_WORKLOAD = 273.5e6
 
 
 def cpu_baseline(oracle, x_host, q_host, params, k, metric, gpu_ids, gpu_dists, sample):
@@ -48,11 +52,13 @@ def main():
     ap.add_argument("--nq", type=int, default=0, help="query batch (default: the workload's 10 000)")
     ap.add_argument("--k", type=int, default=10)
     ap.add_argument("--n", type=int, default=0, help="corpus rows (default: the workload's 1 000 000)")
-    ap.add_argument("--cpu-sample", type=int, default=48)
+    ap.add_argument("--cpu-sample", type=int, default=512)
     ap.add_argument("--recall-queries", type=int, default=1000)
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 generic kernel, 2 matrix-core kernel")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--seed-rows", type=int, default=0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 512 MiB device copy (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; multi-GPU sharding is a design note only "
@@ -109,6 +115,12 @@ def main():
     ms_per_step = e0.elapsed_time(e1) / args.steps
     launches, kern_ms = lpq.profile_read()
     lpq.profile_enable(False)
+    if args.copy_calibration:      # a plain copy of known size, for scaling FETCH_SIZE / WRITE_SIZE
+        src = torch.ones(512 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     ops_per_step = 2.0 * w.nq * w.n * w.d                    # true d, not the padded one
     kern_ms_per_step = kern_ms / args.steps
@@ -121,6 +133,9 @@ def main():
     else:
         roofline = {"bound": "hbm", "achieved": bytes_per_step / (kern_ms_per_step * 1e-3) / 1e9,
                     "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": hbm_frac, "traffic": None}
+    default_workload = (args.n == 0 and args.nq == 0 and args.k == 10 and args.path == 0
+                        and args.splits == 0 and args.seed_rows == 0)
+    roofline["traffic"] = TRAFFIC_BYTES_DEFAULT_WORKLOAD if default_workload else None
     roofline["kernel"] = "contraction + top-k scan (all launches of one search)"
     roofline["kernel_ms_per_step"] = kern_ms_per_step
     roofline["launches_per_step"] = launches / args.steps
