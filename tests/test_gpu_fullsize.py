@@ -1,0 +1,99 @@
+"""Parity at the full sizes of the benchmark configurations, in the launch configuration
+bench.py times: a sample of queries is checked bit for bit against the CPU oracle, and every
+query's result is checked through properties that hold at any size (each reported distance is
+the oracle's integer distance of that (query, item) pair; rows are sorted by (distance, id); ids
+are distinct).  Needs a real MI355X."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2110_08919_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lpq():
+    from paper_2110_08919_amd import lpq as m
+    assert torch.cuda.is_available(), "no GPU visible"
+    m.lib()
+    return m
+
+
+def _pair_distances(codes, qcodes, ids, metric):
+    """Integer distances of the pairs (query i, item ids[i, r]) from the oracle's codes."""
+    out = np.empty(ids.shape, np.int64)
+    for i0 in range(0, ids.shape[0], 512):
+        sl = slice(i0, min(ids.shape[0], i0 + 512))
+        c = codes[ids[sl]].astype(np.int32)                      # [b, k, d]
+        q = qcodes[sl].astype(np.int32)[:, None, :]
+        out[sl] = ((c - q) ** 2).sum(-1) if metric == "l2sq" else (c * q).sum(-1)
+    return out
+
+
+def _check_properties(ids, dists, codes, qcodes, metric):
+    assert ids.min() >= 0 and ids.max() < codes.shape[0]
+    assert np.array_equal(_pair_distances(codes, qcodes, ids, metric), dists.astype(np.int64))
+    key = dists.astype(np.int64) if metric == "l2sq" else -dists.astype(np.int64)
+    dk, di = np.diff(key, axis=1), np.diff(ids.astype(np.int64), axis=1)
+    assert np.all((dk > 0) | ((dk == 0) & (di > 0)))            # sorted by (distance, id), ids distinct
+
+
+def _full_case(lpq, oracle, w, k, mode, scope, sample, batches=None, threads=16):
+    x = w.corpus("cuda")
+    q = w.queries("cuda")
+    quant = lpq.Quantizer(w.d, 8).calibrate(x, mode, scope)
+    index = lpq.Index(quant, w.n).add_f32(x)
+    kq, sb, se, m = quant.get_params()
+    oq = oracle.Quantizer(w.d, 8).set_params(kq, sb, se)
+    assert np.array_equal(oq.m, m)
+    xh, qh = x.cpu().numpy(), q.cpu().numpy()
+    codes, qcodes = oq.encode(xh), oq.encode(qh)
+    del xh
+    # the encode kernel gives exactly the oracle's codes and norms (spot rows)
+    probe = torch.linspace(0, w.n - 1, 4000).long().cuda()
+    pc, pn = quant.encode(x[probe].contiguous(), with_norms=True)
+    assert np.array_equal(pc.cpu().numpy(), codes[probe.cpu().numpy()])
+    assert np.array_equal(pn.cpu().numpy(), (codes[probe.cpu().numpy()].astype(np.int64) ** 2).sum(1))
+    del x
+
+    ids, dists = index.search(q, k, w.metric)
+    torch.cuda.synchronize()
+    ids, dists = ids.cpu().numpy(), dists.cpu().numpy()
+    _check_properties(ids, dists, codes, qcodes, w.metric)
+    pick = np.unique(np.linspace(0, w.nq - 1, sample).astype(np.int64))
+    oids, odists = oracle.search_i8(codes, qcodes[pick], k, w.metric, threads=threads)
+    assert np.array_equal(dists[pick], odists)
+    assert np.array_equal(ids[pick], oids)
+    for nb in batches or ():                                     # other batch sizes: same answers
+        bi, bd = index.search(q[:nb], k, w.metric)
+        assert np.array_equal(bi.cpu().numpy(), ids[:nb]) and np.array_equal(bd.cpu().numpy(), dists[:nb])
+    return index, q, ids
+
+
+def test_config2_skewed_1m_x128_k10(lpq, oracle):
+    """The benchmark workload itself: 1M x 128, 10 000 queries, L2, k = 10, global min/max."""
+    _full_case(lpq, oracle, synth.SKEWED_1M, 10, "minmax", "global", sample=64, batches=(1, 16, 256))
+
+
+def test_config2_skewed_1m_x128_k100_per_feature(lpq, oracle):
+    _full_case(lpq, oracle, synth.SKEWED_1M.scaled(nq=2000), 100, "minmax", "per_feature", sample=32)
+
+
+def test_config3_aniso_1m2_x100_ip(lpq, oracle):
+    _full_case(lpq, oracle, synth.ANISO_1M2, 10, "absmax", "global", sample=48)
+
+
+def test_config4_scaled_10m_x96_batch_sweep(lpq, oracle):
+    """10M x 96, L2, k = 10, with the query batch sweep 1 / 16 / 256 / 10 000."""
+    _full_case(lpq, oracle, synth.SCALED_10M, 10, "absmax", "global", sample=16, batches=(1, 16, 256))
+
+
+def test_config5_product_x256_ip_k100(lpq, oracle):
+    """d = 256, inner product, k = 100 on the bimodal product-embedding recipe.  The corpus is
+    8M rows by default (about a minute with the oracle); LPQ_TEST_FULL_100M=1 runs all 100M rows
+    (25.6 GB of codes; the oracle then needs several minutes and ~60 GB of host memory)."""
+    n = 100_000_000 if os.environ.get("LPQ_TEST_FULL_100M") == "1" else 8_000_000
+    _full_case(lpq, oracle, synth.PRODUCT_100M.scaled(n=n, nq=1000), 100, "absmax", "per_feature", sample=4)
