@@ -323,8 +323,11 @@ struct Plan {
     int64_t seed_rows = 0;  // rows of the threshold-seeding pass (0 = none)
     int S1 = 0, S2 = 0;     // corpus splits of the seeding pass and of the main pass
     int SEG = 0;            // PLAN_MFMA_REG: segments per split in the seeding pass
+    int G = 0;              // PLAN_MFMA_REG: group maxima per query
+    bool rsplit = false;    // PLAN_MFMA_REG: row-split workgroups (few queries)
+    int merge_group = 0;    // lists merged per workgroup in the first merge pass (0 = single pass)
     size_t off_qcodes = 0, off_qnorms = 0, off_lists1 = 0, off_seedlist = 0, off_seeds = 0, off_lists2 = 0,
-           off_gmax = 0, total = 0;
+           off_gmax = 0, off_merge_tmp = 0, total = 0;
 };
 
 size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
@@ -337,7 +340,9 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     if (want != 1 && mfma_reg_supported(idx->d_pad, k)) p.mode = PLAN_MFMA_REG;
     else if (want != 1 && mfma_lds_supported(idx->d_pad, k)) p.mode = PLAN_MFMA_LDS;
     p.nq_pad = round_up(nq > 0 ? nq : 1, 512);
-    const int max_lists = merge_max_lists(k);
+    // A merge pass sorts up to 4096 candidates per workgroup; more lists than that are merged in
+    // two passes, so the number of splits is bounded by max_lists^2 only.
+    const int max_lists = merge_max_lists(k) * (merge_max_lists(k) > 1 ? merge_max_lists(k) : 1);
     const int64_t slots = 512;   // workgroups of the matrix-core kernels resident at once (2 per CU)
 
     // Seeding pass over a first slice of the corpus: it yields, per query, an upper bound on
@@ -355,13 +360,13 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     if (seed < 64 * k || seed * 4 > n) seed = 0;
     p.seed_rows = seed;
 
-    auto splits_for = [&](int64_t rows, int64_t tiles_q, int64_t min_rows, int64_t slots) {
+    auto splits_for = [&](int64_t rows, int64_t tiles_q, int64_t min_rows, int64_t slots, int64_t cap) {
         int64_t s;
         if (p.mode != PLAN_GENERIC) s = g_tune[LPQ_TUNE_SPLITS] > 0 ? g_tune[LPQ_TUNE_SPLITS] : slots / (tiles_q > 0 ? tiles_q : 1);
         else s = g_tune[LPQ_TUNE_SPLITS] > 0 ? g_tune[LPQ_TUNE_SPLITS] : ceil_div(2048, nq > 0 ? nq : 1);
         const int64_t by_rows = rows / min_rows > 0 ? rows / min_rows : 1;
         if (s > by_rows) s = by_rows;
-        if (s > max_lists) s = max_lists;
+        if (s > cap) s = cap;
         if (s < 1) s = 1;
         return (int)s;
     };
@@ -369,15 +374,18 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     int64_t slots_now = slots;
     if (p.mode == PLAN_MFMA_REG) {
         qt = mfma_queries_per_workgroup(nq, idx->d_pad);
-        if (qt == 512) slots_now = 256;   // eight-wave workgroups: one per CU
+        p.rsplit = mfma_row_split(nq, idx->d_pad);
     }
     const int64_t tiles_q = ceil_div(nq > 0 ? nq : 1, qt);
     const int64_t min_rows = p.mode == PLAN_GENERIC ? 2048 : 512;
     if (seed) {
-        p.S1 = splits_for(seed, tiles_q, min_rows, slots_now);
-        if (p.mode == PLAN_MFMA_REG) p.SEG = mfma_seed_segments(p.S1, k);
+        p.S1 = splits_for(seed, tiles_q, min_rows, slots_now, p.mode == PLAN_MFMA_REG ? 1024 : merge_max_lists(k));
+        if (p.mode == PLAN_MFMA_REG) {
+            p.SEG = mfma_seed_segments(p.S1, k, p.rsplit);
+            p.G = mfma_seed_groups(p.S1, p.SEG, p.rsplit);
+        }
     }
-    p.S2 = splits_for(p.mode == PLAN_MFMA_REG ? n : n - seed, tiles_q, min_rows, slots_now);
+    p.S2 = splits_for(p.mode == PLAN_MFMA_REG ? n : n - seed, tiles_q, min_rows, slots_now, max_lists);
 
     size_t o = 0;
     p.off_qcodes = o;   o = align256(o + (size_t)p.nq_pad * idx->d_pad);
@@ -387,7 +395,12 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     p.off_seeds = o;    o = align256(o + (size_t)p.nq_pad * sizeof(cand_t));
     p.off_lists2 = o;   o = align256(o + (size_t)nq * p.S2 * k * sizeof(cand_t));
     p.off_gmax = o;
-    if (p.mode == PLAN_MFMA_REG && seed) o = align256(o + (size_t)p.nq_pad * 2 * p.S1 * p.SEG * sizeof(int32_t));
+    if (p.mode == PLAN_MFMA_REG && seed) o = align256(o + (size_t)p.nq_pad * p.G * sizeof(int32_t));
+    p.off_merge_tmp = o;
+    if (p.S2 > merge_max_lists(k)) {
+        p.merge_group = merge_max_lists(k);
+        o = align256(o + (size_t)nq * ceil_div(p.S2, p.merge_group) * k * sizeof(cand_t));
+    }
     p.total = o;
     return p;
 }
@@ -418,6 +431,7 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k
     a.qcodes = reinterpret_cast<const int8_t *>(ws + p.off_qcodes);
     a.nq = nq; a.k = k; a.metric = metric;
     a.dry_run = (int)g_tune[LPQ_TUNE_DRY_RUN];
+    a.rsplit = p.rsplit;
     const int32_t *qnorms = reinterpret_cast<const int32_t *>(ws + p.off_qnorms);
     cand_t *lists1 = reinterpret_cast<cand_t *>(ws + p.off_lists1);
     cand_t *seedlist = reinterpret_cast<cand_t *>(ws + p.off_seedlist);
@@ -425,6 +439,16 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k
     cand_t *lists2 = reinterpret_cast<cand_t *>(ws + p.off_lists2);
     int32_t *gmax = reinterpret_cast<int32_t *>(ws + p.off_gmax);
 
+    cand_t *merge_tmp = reinterpret_cast<cand_t *>(ws + p.off_merge_tmp);
+    // Final merge of the main pass' S2 lists (plus an optional extra list), in one or two passes.
+    auto final_merge = [&](const cand_t *extra) -> hipError_t {
+        if (!p.merge_group)
+            return launch_merge(lists2, nq, p.S2, k, extra, nullptr, nullptr, ids, dist, qnorms, metric, st);
+        const int groups = (int)ceil_div(p.S2, p.merge_group);
+        hipError_t e = launch_merge_groups(lists2, nq, p.S2, p.merge_group, k, merge_tmp, st);
+        if (e != hipSuccess) return e;
+        return launch_merge(merge_tmp, nq, groups, k, extra, nullptr, nullptr, ids, dist, qnorms, metric, st);
+    };
     auto scan = [&](int64_t r0, int64_t r1, int S, const cand_t *sd, cand_t *out) -> hipError_t {
         KernelSpan span(st);
         return p.mode == PLAN_GENERIC ? launch_search_generic(a, r0, r1, S, sd, out, st)
@@ -437,19 +461,19 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k
                 KernelSpan span(st);
                 HIP_TRY(launch_seed_mfma(a, 0, p.seed_rows, p.S1, p.SEG, gmax, st));
             }
-            HIP_TRY(launch_seed_finalize(gmax, nq, 2 * p.S1 * p.SEG, k, seeds, st));
+            HIP_TRY(launch_seed_finalize(gmax, nq, p.G, k, seeds, st));
             sd = seeds;
         }
         HIP_TRY(scan(0, a.n, p.S2, sd, lists2));
-        HIP_TRY(launch_merge(lists2, nq, p.S2, k, nullptr, nullptr, nullptr, ids, dist, qnorms, metric, st));
+        HIP_TRY(final_merge(nullptr));
     } else if (p.seed_rows) {
         HIP_TRY(scan(0, p.seed_rows, p.S1, nullptr, lists1));
         HIP_TRY(launch_merge(lists1, nq, p.S1, k, nullptr, seedlist, seeds, nullptr, nullptr, nullptr, metric, st));
         HIP_TRY(scan(p.seed_rows, a.n, p.S2, seeds, lists2));
-        HIP_TRY(launch_merge(lists2, nq, p.S2, k, seedlist, nullptr, nullptr, ids, dist, qnorms, metric, st));
+        HIP_TRY(final_merge(seedlist));
     } else {
         HIP_TRY(scan(0, a.n, p.S2, nullptr, lists2));
-        HIP_TRY(launch_merge(lists2, nq, p.S2, k, nullptr, nullptr, nullptr, ids, dist, qnorms, metric, st));
+        HIP_TRY(final_merge(nullptr));
     }
     return LPQ_OK;
 }

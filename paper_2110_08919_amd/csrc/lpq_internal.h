@@ -99,6 +99,7 @@ struct SearchArgs {
     int64_t nq;
     int k;
     int metric;
+    bool rsplit;            // register variant: row-split workgroups (set from mfma_row_split)
     int dry_run;            // timing experiments: != 0 never collects a candidate (2..4: ablations)
 };
 
@@ -119,8 +120,10 @@ hipError_t launch_search_mfma_lds(const SearchArgs &a, int64_t row0, int64_t row
                                   cand_t *lists, hipStream_t st);
 // Seeding pass of the register variant: group maxima gmax[nq_pad][2*S*SEG] over rows
 // [row0, row1) (all of them real items), then seeds[q] = bound from the k-th largest.
-int mfma_seed_segments(int S, int k);
-int mfma_queries_per_workgroup(int64_t nq, int d_pad);   // query tile of the register variant: 256 or 512
+int mfma_seed_segments(int S, int k, bool rsplit);
+int mfma_seed_groups(int S, int SEG, bool rsplit);        // = G, entries per query in gmax
+int mfma_queries_per_workgroup(int64_t nq, int d_pad);   // query tile of the register variant
+bool mfma_row_split(int64_t nq, int d_pad);              // few queries: waves split rows, share queries
 hipError_t launch_seed_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S, int SEG, int32_t *gmax,
                             hipStream_t st);
 hipError_t launch_seed_finalize(const int32_t *gmax, int64_t nq, int G, int k, cand_t *seeds, hipStream_t st);
@@ -133,6 +136,10 @@ hipError_t launch_merge(const cand_t *lists, int64_t nq, int P, int k, const can
                         cand_t *out_lists, cand_t *seeds_out, int32_t *ids, int32_t *dists,
                         const int32_t *qnorms, int metric, hipStream_t st);
 int merge_max_lists(int k);
+// First pass of a two-pass merge: groups of `group` consecutive lists of each query are merged
+// into out_lists[q][ceil(P/group)][k].
+hipError_t launch_merge_groups(const cand_t *lists, int64_t nq, int P, int group, int k, cand_t *out_lists,
+                               hipStream_t st);
 
 // ---- fp32 exact search (search_f32.hip) ---------------------------------------------
 size_t f32_workspace_bytes(int64_t n, int64_t nq, int d, int k);

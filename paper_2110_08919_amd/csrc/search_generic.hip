@@ -109,6 +109,36 @@ __global__ __launch_bounds__(256) void merge_kernel(
     if (seeds_out && threadIdx.x == 0) seeds_out[q] = buf[k - 1];
 }
 
+// One workgroup per (query, group): sort the candidates of `group` consecutive lists.
+__global__ __launch_bounds__(256) void merge_groups_kernel(const cand_t *__restrict__ lists, int P, int group, int groups,
+                                                           int k, int cap, cand_t *__restrict__ out_lists)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    cand_t *buf = reinterpret_cast<cand_t *>(smem);
+    const int64_t q = blockIdx.x / groups;
+    const int g = blockIdx.x % groups;
+    const int first = g * group, count = (first + group <= P ? group : P - first) * k;
+    for (int i = threadIdx.x; i < cap; i += 256) buf[i] = (i < count) ? lists[(q * P + first) * k + i] : CAND_NONE;
+    __syncthreads();
+    block_bitonic_sort(buf, cap);
+    for (int i = threadIdx.x; i < k; i += 256) out_lists[(q * groups + g) * k + i] = buf[i];
+}
+
+}  // namespace
+
+hipError_t launch_merge_groups(const cand_t *lists, int64_t nq, int P, int group, int k, cand_t *out_lists,
+                               hipStream_t st)
+{
+    if (nq <= 0) return hipSuccess;
+    const int groups = (int)ceil_div(P, group);
+    const int cap = next_pow2(group * k < 2 ? 2 : group * k);
+    if (cap > 4096) return hipErrorInvalidValue;
+    merge_groups_kernel<<<(unsigned)(nq * groups), 256, (size_t)cap * sizeof(cand_t), st>>>(lists, P, group, groups, k,
+                                                                                          cap, out_lists);
+    return hipGetLastError();
+}
+
+namespace {
 }  // namespace
 
 int merge_max_lists(int k) { return 4096 / k - 1; }

@@ -170,18 +170,21 @@ __device__ __forceinline__ void drain_queue(const WaveQ &w, int qcnt, int64_t ro
     if (svcnt) give_to_owners<KCAP>(w, svcnt, lane, lst, seedC);
 }
 
-template <int KS, bool L2, int KCAP, bool SEED, int NW>
+template <int KS, bool L2, int KCAP, bool SEED, int NW, bool RSPLIT>
 __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     SearchArgs a, int64_t row0, int64_t row1, int S, int64_t split_rows, int qtiles,
     const cand_t *__restrict__ seeds, cand_t *__restrict__ lists_out, int32_t *__restrict__ gmax, int SEG)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int NB = 2;
-    constexpr int QT = NW * NQW;           // queries per workgroup
+    // RSPLIT (few queries): the waves of a workgroup share ONE 64-query tile and split the rows of
+    // a stage between them (one 32-row block each), so no matrix work is spent on padding queries.
+    constexpr int QT = RSPLIT ? NQW : NW * NQW;   // queries per workgroup
     constexpr int CPR = 2 * KS;            // 16-byte chunks per corpus row
     constexpr int SLOTS = CPR <= 2 ? 2 : (CPR <= 4 ? 4 : (CPR <= 8 ? 8 : 16));  // LDS slots per row
-    constexpr int RS = 64;                 // corpus rows per stage: two 32-row blocks
-    constexpr int NST = KS <= 4 ? 4 : 3;   // LDS ring depth
+    constexpr int RS = RSPLIT ? 32 * NW : 64;   // corpus rows per stage
+    constexpr int NST = (KS <= 4 && !RSPLIT) ? 4 : 3;   // LDS ring depth
+    static_assert(!RSPLIT || KS <= 4, "row-split staging is sized for rows of up to 128 bytes");
     constexpr int STAGE_BYTES = RS * SLOTS * 16;
     constexpr int IPW = RS * SLOTS / 64 / NW;   // async copy instructions per wave and stage
     constexpr int AUX_INTS = RS + 4;       // cinit[RS] then parity words
@@ -209,7 +212,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     int *flags = aux + NST * AUX_INTS;           // [2][8] joint-drain requests, double buffered
     const WaveQ w = carve_waveq((unsigned char *)(flags + 16) + (size_t)wave * WAVEQ_BYTES);
 
-    const int64_t q_first = (int64_t)qt * QT + wave * NQW;
+    const int64_t q_first = (int64_t)qt * QT + (RSPLIT ? 0 : wave * NQW);
 
     // ---- owner state (lane q owns query q of this wave) ------------------------------
     cand_t lst[KCAP];
@@ -248,7 +251,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     // `wave` copies positions [(wave*IPW + j)*64, +64) with instruction j; the lane's source
     // is the chunk that belongs in its slot, so every instruction reads whole rows.
     const unsigned ring_lds = lds_offset(ring), aux_lds = lds_offset(aux);
-    const int lpt = IPW + ((L2 && wave < 2) ? 1 : 0);   // copies this wave issues per stage
+    const int lpt = IPW + ((L2 && wave < RS / 64 + 1) ? 1 : 0);   // copies this wave issues per stage
     int src_off[IPW];   // byte offset of the lane's source chunk inside a stage of corpus rows
 #pragma unroll
     for (int j = 0; j < IPW; ++j) {
@@ -266,9 +269,9 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
         const int8_t *src_ = a.codes + r0_ * (32 * KS);                                                 \
         _Pragma("unroll") for (int j = 0; j < IPW; ++j)                                                 \
             async_copy16(src_ + src_off[j], ring_lds + ring_slot_ * STAGE_BYTES + (wave * IPW + j) * 1024); \
-        if (L2 && wave == 0) {                                                                          \
-            async_copy4(a.cinit + r0_ + lane, aux_lds + ring_slot_ * AUX_INTS * 4);                     \
-        } else if (L2 && wave == 1) {                                                                   \
+        if (L2 && wave < RS / 64) {                                                                     \
+            async_copy4(a.cinit + r0_ + wave * 64 + lane, aux_lds + (ring_slot_ * AUX_INTS + wave * 64) * 4); \
+        } else if (L2 && wave == RS / 64) {                                                             \
             if (lane < RS / 32)                                                                         \
                 async_copy4(a.parity + r0_ / 32 + lane, aux_lds + (ring_slot_ * AUX_INTS + RS) * 4);    \
         }                                                                                               \
@@ -346,11 +349,12 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     const int T = (re > rs) ? (int)((re - rs + RS - 1) / RS) : 0;
 
     // Seeding pass: group maxima of segment g of this split go to gmax[q][(s*SEG + g)*2 + half].
-    const int G = S * SEG * 2;
+    const int G = S * SEG * 2 * (RSPLIT ? NW : 1);
 #define LPQ_FLUSH_SEGMENT(SEGIDX)                                                                       \
     do {                                                                                                \
         _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) {                                             \
-            gmax[(size_t)(q_first + nb * 32 + col) * G + ((size_t)s * SEG + (SEGIDX)) * 2 + half] = gm[nb]; \
+            gmax[(size_t)(q_first + nb * 32 + col) * G +                                                \
+                 (((size_t)s * SEG + (SEGIDX)) * (RSPLIT ? NW : 1) + (RSPLIT ? wave : 0)) * 2 + half] = gm[nb]; \
             gm[nb] = INT32_MIN;                                                                         \
         }                                                                                               \
     } while (0)
@@ -367,52 +371,87 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     // workgroup barrier sits in front of block (t, 1): by then every wave has finished READING
     // stage t (its last LDS reads were waited for), so the ring slot of stage t can be refilled
     // with stage t + NST, and stage t+1 is known to have landed.
-    v4i A0[KS], A1[KS];
-    v16i C0, C1;
-    unsigned P0 = 0, P1 = 0;
-    const bool abl_nodma = a.dry_run >= 3, abl_nobar = a.dry_run == 2 || a.dry_run == 4;   // timing ablations
-    const int primed = T < NST ? T : NST;
-    if (!abl_nodma) for (int st = 0; st < primed; ++st) LPQ_ISSUE(st);
-    if (T > 0) {
-        wait_vmcnt((primed - 1) * lpt);
-        __syncthreads();
-        LPQ_LOAD_BLOCK(0, 0, A0, C0, P0);
-    }
-    for (int t = 0; t < T; ++t) {
-        LPQ_LOAD_BLOCK(t, 1, A1, C1, P1);
-        LPQ_BLOCK(t, 0, A0, C0, P0);
-
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // my reads of stage t are complete
-        if (!SEED && lane == 0) flags[(t & 1) * 8 + wave] = qcnt >= TRIG;
-        if (t + 1 < T && !abl_nodma) {
-            // stages issued so far: 0 .. min(T-1, t+NST-1); stage t+1 must have landed
-            const int last = T - 1 < t + NST - 1 ? T - 1 : t + NST - 1;
-            wait_vmcnt((last - (t + 1)) * lpt);
-        }
-        if (!abl_nobar) __syncthreads();
-        if (t + NST < T && !abl_nodma) LPQ_ISSUE(t + NST);   // refills the slot of stage t
-        if (!SEED) {
-            const v4i f = *reinterpret_cast<const v4i *>(flags + (t & 1) * 8);
-            int any = f[0] | f[1] | f[2] | f[3];
-            if (NW > 4) {
-                const v4i g = *reinterpret_cast<const v4i *>(flags + (t & 1) * 8 + 4);
-                any |= g[0] | g[1] | g[2] | g[3];
-            }
-            if (any) {   // same answer in every wave of the workgroup: drain together
-                drain_queue<L2, KCAP>(w, qcnt, re, lane, lst, seedC);
-                qcnt = 0;
+    if constexpr (RSPLIT) {
+        // One 32-row block per wave and stage; the barrier is at the top of a stage.
+        v4i A0[KS];
+        v16i C0;
+        unsigned P0 = 0;
+        for (int st = 0; st < NST - 1 && st < T; ++st) LPQ_ISSUE(st);
+        for (int t = 0; t < T; ++t) {
+            if (!SEED && lane == 0) flags[(t & 1) * 8 + wave] = qcnt >= TRIG;
+            // stages issued so far: 0 .. min(T-1, t+NST-2); wait until stage t has landed
+            const int newer = (T - 1 < t + NST - 2 ? T - 1 : t + NST - 2) - t;
+            wait_vmcnt(newer * lpt);
+            __syncthreads();   // stage t is in LDS for everybody; stage t-1 is no longer read
+            if (t + NST - 1 < T) LPQ_ISSUE(t + NST - 1);   // refills the slot of stage t-1
+            if (!SEED) {
+                const v4i f = *reinterpret_cast<const v4i *>(flags + (t & 1) * 8);
+                if (f[0] | f[1] | f[2] | f[3]) {
+                    drain_queue<L2, KCAP>(w, qcnt, re, lane, lst, seedC);
+                    qcnt = 0;
 #pragma unroll
-                for (int j = 0; j < NB; ++j) thr[j] = w.thrE[j * 32 + col];
+                    for (int j = 0; j < NB; ++j) thr[j] = w.thrE[j * 32 + col];
+                }
+            }
+            LPQ_LOAD_BLOCK(t, wave, A0, C0, P0);
+            LPQ_BLOCK(t, wave, A0, C0, P0);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // my reads of stage t are complete
+            if (SEED) {
+                const int seg = (int)((int64_t)t * SEG / T), seg_next = (int)((int64_t)(t + 1) * SEG / T);
+                if (t + 1 == T || seg_next != seg) {
+                    LPQ_FLUSH_SEGMENT(seg);
+                    __builtin_amdgcn_s_waitcnt(0x0F70);
+                }
             }
         }
-        if (t + 1 < T) LPQ_LOAD_BLOCK(t + 1, 0, A0, C0, P0);
-        LPQ_BLOCK(t, 1, A1, C1, P1);
+    } else {
+    v4i A0[KS], A1[KS];
+        v16i C0, C1;
+        unsigned P0 = 0, P1 = 0;
+        const bool abl_nodma = a.dry_run >= 3, abl_nobar = a.dry_run == 2 || a.dry_run == 4;   // timing ablations
+        const int primed = T < NST ? T : NST;
+        if (!abl_nodma) for (int st = 0; st < primed; ++st) LPQ_ISSUE(st);
+        if (T > 0) {
+            wait_vmcnt((primed - 1) * lpt);
+            __syncthreads();
+            LPQ_LOAD_BLOCK(0, 0, A0, C0, P0);
+        }
+        for (int t = 0; t < T; ++t) {
+            LPQ_LOAD_BLOCK(t, 1, A1, C1, P1);
+            LPQ_BLOCK(t, 0, A0, C0, P0);
 
-        if (SEED) {   // close a segment when the next stage belongs to the next one
-            const int seg = (int)((int64_t)t * SEG / T), seg_next = (int)((int64_t)(t + 1) * SEG / T);
-            if (t + 1 == T || seg_next != seg) {
-                LPQ_FLUSH_SEGMENT(seg);
-                __builtin_amdgcn_s_waitcnt(0x0F70);   // keep the counter to async copies only
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // my reads of stage t are complete
+            if (!SEED && lane == 0) flags[(t & 1) * 8 + wave] = qcnt >= TRIG;
+            if (t + 1 < T && !abl_nodma) {
+                // stages issued so far: 0 .. min(T-1, t+NST-1); stage t+1 must have landed
+                const int last = T - 1 < t + NST - 1 ? T - 1 : t + NST - 1;
+                wait_vmcnt((last - (t + 1)) * lpt);
+            }
+            if (!abl_nobar) __syncthreads();
+            if (t + NST < T && !abl_nodma) LPQ_ISSUE(t + NST);   // refills the slot of stage t
+            if (!SEED) {
+                const v4i f = *reinterpret_cast<const v4i *>(flags + (t & 1) * 8);
+                int any = f[0] | f[1] | f[2] | f[3];
+                if (NW > 4) {
+                    const v4i g = *reinterpret_cast<const v4i *>(flags + (t & 1) * 8 + 4);
+                    any |= g[0] | g[1] | g[2] | g[3];
+                }
+                if (any) {   // same answer in every wave of the workgroup: drain together
+                    drain_queue<L2, KCAP>(w, qcnt, re, lane, lst, seedC);
+                    qcnt = 0;
+#pragma unroll
+                    for (int j = 0; j < NB; ++j) thr[j] = w.thrE[j * 32 + col];
+                }
+            }
+            if (t + 1 < T) LPQ_LOAD_BLOCK(t + 1, 0, A0, C0, P0);
+            LPQ_BLOCK(t, 1, A1, C1, P1);
+
+            if (SEED) {   // close a segment when the next stage belongs to the next one
+                const int seg = (int)((int64_t)t * SEG / T), seg_next = (int)((int64_t)(t + 1) * SEG / T);
+                if (t + 1 == T || seg_next != seg) {
+                    LPQ_FLUSH_SEGMENT(seg);
+                    __builtin_amdgcn_s_waitcnt(0x0F70);   // keep the counter to async copies only
+                }
             }
         }
     }
@@ -423,8 +462,23 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
 
     if (!SEED) {
         drain_queue<L2, KCAP>(w, qcnt, re, lane, lst, seedC);
+        if constexpr (RSPLIT) {
+            // The waves hold lists of the SAME 64 queries over different rows: waves 1.. publish
+            // theirs in the (now idle) ring and wave 0 folds them into its own.
+            cand_t *xl = reinterpret_cast<cand_t *>(ring);
+            __syncthreads();
+            if (wave > 0) {
+#pragma unroll
+                for (int i = 0; i < KCAP; ++i) xl[((wave - 1) * KCAP + i) * 64 + lane] = lst[i];
+            }
+            __syncthreads();
+            if (wave == 0) {
+                for (int i = 0; i < (NW - 1) * KCAP; ++i)   // pinned slots (index % KCAP < KCAP - k) are not candidates
+                    reglist_insert<KCAP>(lst, xl[i * 64 + lane], i % KCAP >= KCAP - k);
+            }
+        }
         const int64_t gq = q_first + lane;
-        if (gq < a.nq) {
+        if (gq < a.nq && (!RSPLIT || wave == 0)) {
             cand_t *out = lists_out + ((size_t)gq * S + s) * k;
 #pragma unroll
             for (int i = 0; i < KCAP; ++i)
@@ -459,22 +513,23 @@ __global__ __launch_bounds__(128) void seed_finalize_kernel(const int32_t *__res
     }
 }
 
-size_t lds_bytes(int ks, bool seed, int nw)
+size_t lds_bytes(int ks, bool seed, int nw, bool rsplit)
 {
     const int cpr = 2 * ks;
     const int slots = cpr <= 2 ? 2 : (cpr <= 4 ? 4 : (cpr <= 8 ? 8 : 16));
-    const int nst = ks <= 4 ? 4 : 3;
-    return (size_t)nst * 64 * slots * 16 + (size_t)nst * (64 + 4) * 4 + 64 + (seed ? 0 : nw * WAVEQ_BYTES);
+    const int nst = (ks <= 4 && !rsplit) ? 4 : 3;
+    const int rs = rsplit ? 32 * nw : 64;
+    return (size_t)nst * rs * slots * 16 + (size_t)nst * (rs + 4) * 4 + 64 + (seed ? 0 : nw * WAVEQ_BYTES);
 }
 
-template <int KS, bool L2, int KCAP, bool SEED, int NW>
+template <int KS, bool L2, int KCAP, bool SEED, int NW, bool RSPLIT>
 hipError_t launch_nw(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds, cand_t *lists,
                      int32_t *gmax, int SEG, hipStream_t st)
 {
-    const int qtiles = (int)ceil_div(a.nq, NW * NQW);
-    const int64_t split_rows = round_up(ceil_div(row1 - row0, S), 64);
-    const size_t lds = lds_bytes(KS, SEED, NW);
-    auto kern = search_mfma_kernel<KS, L2, KCAP, SEED, NW>;
+    const int qtiles = (int)ceil_div(a.nq, RSPLIT ? NQW : NW * NQW);
+    const int64_t split_rows = round_up(ceil_div(row1 - row0, S), RSPLIT ? 32 * NW : 64);
+    const size_t lds = lds_bytes(KS, SEED, NW, RSPLIT);
+    auto kern = search_mfma_kernel<KS, L2, KCAP, SEED, NW, RSPLIT>;
     static bool attr_set = false;  // per instantiation
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -493,7 +548,10 @@ template <int KS, bool L2, int KCAP, bool SEED>
 hipError_t launch_one(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds, cand_t *lists,
                       int32_t *gmax, int SEG, hipStream_t st)
 {
-    return launch_nw<KS, L2, KCAP, SEED, 4>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
+    if constexpr (KS <= 4) {
+        if (a.rsplit) return launch_nw<KS, L2, KCAP, SEED, 4, true>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
+    }
+    return launch_nw<KS, L2, KCAP, SEED, 4, false>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
 }
 
 template <int KS>
@@ -515,7 +573,7 @@ hipError_t launch_any(const SearchArgs &a, int64_t row0, int64_t row1, int S, co
                       int32_t *gmax, int SEG, hipStream_t st)
 {
     if (a.nq <= 0 || row1 <= row0) return hipSuccess;
-    if (row0 % 64) return hipErrorInvalidValue;  // stages and parity words cover aligned blocks
+    if (row0 % 128) return hipErrorInvalidValue;  // stages and parity words cover aligned blocks
     switch (a.d_pad / 32) {
     case 2: return launch_ks<2>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
     case 3: return launch_ks<3>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
@@ -534,7 +592,10 @@ bool shape_ok(int d_pad)
 
 }  // namespace
 
-int mfma_queries_per_workgroup(int64_t, int) { return 256; }
+int mfma_queries_per_workgroup(int64_t nq, int d_pad) { return mfma_row_split(nq, d_pad) ? 64 : 256; }
+
+// Few queries: the waves of a workgroup share them and split the rows instead.
+bool mfma_row_split(int64_t nq, int d_pad) { return nq <= 64 && d_pad <= 128; }
 
 bool mfma_reg_supported(int d_pad, int k) { return shape_ok(d_pad) && k >= 1 && k <= 16; }
 
@@ -547,11 +608,14 @@ hipError_t launch_search_mfma(const SearchArgs &a, int64_t row0, int64_t row1, i
     return launch_search_mfma_lds(a, row0, row1, S, seeds, lists, st);
 }
 
-int mfma_seed_segments(int S, int k)
+int mfma_seed_groups(int S, int SEG, bool rsplit) { return 2 * S * SEG * (rsplit ? 4 : 1); }
+
+int mfma_seed_segments(int S, int k, bool rsplit)
 {
-    int seg = (int)ceil_div(3 * k, S);   // 2 * S * SEG >= 6k groups: the k-th largest is then
-    if (seg < 1) seg = 1;                // close to the k-th best item of the seeded rows
-    while (2 * S * seg > 1024 && seg > 1) --seg;
+    const int per = rsplit ? 8 : 2;            // groups a split contributes per segment
+    int seg = (int)ceil_div(6 * k, per * S);   // >= 6k groups: the k-th largest is then close to
+    if (seg < 1) seg = 1;                      // the k-th best item of the seeded rows
+    while (per * S * seg > 2048 && seg > 1) --seg;
     return seg;
 }
 

@@ -91,7 +91,8 @@ def _ptr(t):
 
 def _dev_matrix(t: torch.Tensor, dtype):
     assert t.is_cuda and t.dtype == dtype and t.dim() == 2 and t.stride(1) == 1, "need a row-major device matrix"
-    return t.data_ptr(), t.shape[0], t.stride(0)
+    ld = t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])   # a 1-row stride is arbitrary
+    return t.data_ptr(), t.shape[0], ld
 
 
 def set_tuning(key: int, value: int):

@@ -163,6 +163,20 @@ def test_search_parity_shapes(lpq, oracle, path, name, n, nq, k, metric, mode, s
     _run_search_case(lpq, oracle, base.scaled(n=n, nq=nq), k, metric, mode, scope, path)
 
 
+@pytest.mark.parametrize("nq", [1, 7, 64, 65])
+@pytest.mark.parametrize("name,n,k,metric,mode,scope", [
+    ("skewed", 70001, 10, "l2sq", "minmax", "global"),      # seeded, d = 128
+    ("scaled", 50000, 16, "l2sq", "absmax", "global"),      # seeded, d = 96
+    ("aniso", 40000, 3, "ip", "absmax", "global"),          # seeded, d = 100, inner product
+    ("tiny", 5000, 10, "l2sq", "minmax", "per_feature"),    # too small for a seeding pass
+])
+def test_search_small_batches(lpq, oracle, nq, name, n, k, metric, mode, scope):
+    """Few queries: the matrix-core kernel shares them between the waves of a workgroup and
+    splits rows instead; many splits are merged in two passes."""
+    base = {"skewed": synth.SKEWED_1M, "aniso": synth.ANISO_1M2, "scaled": synth.SCALED_10M, "tiny": synth.TINY}[name]
+    _run_search_case(lpq, oracle, base.scaled(n=n, nq=nq), k, metric, mode, scope, 2)
+
+
 @pytest.mark.parametrize("path", PATHS)
 def test_search_many_ties_low_bits(lpq, oracle, path):
     """3-bit codes in 8 dimensions: almost every distance is tied; order must follow ids."""
