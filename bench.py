@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 generic kernel, 2 matrix-core kernel")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--seed-rows", type=int, default=0)
+    ap.add_argument("--workload", default="skewed_1m", choices=["tiny", "skewed_1m", "aniso_1m2", "scaled_10m", "product_100m"],
+                    help="synthetic workload shape (default: the benchmark configuration)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 512 MiB device copy (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -72,7 +74,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     lpq.lib()
-    w = synth.SKEWED_1M.scaled(n=args.n or None, nq=args.nq or None)
+    base = {"tiny": synth.TINY, "skewed_1m": synth.SKEWED_1M, "aniso_1m2": synth.ANISO_1M2,
+            "scaled_10m": synth.SCALED_10M, "product_100m": synth.PRODUCT_100M}[args.workload]
+    w = base.scaled(n=args.n or None, nq=args.nq or None)
     k, metric = args.k, w.metric
 
     # ---- inputs and index build (not part of the timed search step) -------------------
@@ -133,7 +137,7 @@ def main():
     else:
         roofline = {"bound": "hbm", "achieved": bytes_per_step / (kern_ms_per_step * 1e-3) / 1e9,
                     "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": hbm_frac, "traffic": None}
-    default_workload = (args.n == 0 and args.nq == 0 and args.k == 10 and args.path == 0
+    default_workload = (args.workload == "skewed_1m" and args.n == 0 and args.nq == 0 and args.k == 10 and args.path == 0
                         and args.splits == 0 and args.seed_rows == 0)
     roofline["traffic"] = TRAFFIC_BYTES_DEFAULT_WORKLOAD if default_workload else None
     roofline["kernel"] = "contraction + top-k scan (all launches of one search)"
@@ -157,7 +161,7 @@ def main():
                            ids.cpu().numpy(), dists.cpu().numpy(), sample)
 
     out = {
-        "metric": "queries/sec, int8 brute-force top-10, 1M x 128",
+        "metric": "queries/sec, int8 brute-force top-%d, %s" % (k, "1M x 128" if args.workload == "skewed_1m" and not args.n else f"{w.n} x {w.d}"),
         "value": w.nq / (ms_per_step * 1e-3),
         "unit": "queries/s",
         "n_gpus": 1,

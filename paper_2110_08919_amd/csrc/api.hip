@@ -385,7 +385,8 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
             p.G = mfma_seed_groups(p.S1, p.SEG, p.rsplit);
         }
     }
-    p.S2 = splits_for(p.mode == PLAN_MFMA_REG ? n : n - seed, tiles_q, min_rows, slots_now, max_lists);
+    p.S2 = splits_for(p.mode == PLAN_MFMA_REG ? n : n - seed, tiles_q, min_rows, slots_now,
+                      p.rsplit ? merge_max_lists(k) : max_lists);   // few queries: one merge pass, fewer launches
 
     size_t o = 0;
     p.off_qcodes = o;   o = align256(o + (size_t)p.nq_pad * idx->d_pad);
@@ -441,13 +442,14 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k
 
     cand_t *merge_tmp = reinterpret_cast<cand_t *>(ws + p.off_merge_tmp);
     // Final merge of the main pass' S2 lists (plus an optional extra list), in one or two passes.
+    const bool sorted = p.mode != PLAN_MFMA_LDS;   // that scan's lists come out in arrival order
     auto final_merge = [&](const cand_t *extra) -> hipError_t {
         if (!p.merge_group)
-            return launch_merge(lists2, nq, p.S2, k, extra, nullptr, nullptr, ids, dist, qnorms, metric, st);
+            return launch_merge(lists2, nq, p.S2, k, extra, nullptr, nullptr, ids, dist, qnorms, metric, st, sorted);
         const int groups = (int)ceil_div(p.S2, p.merge_group);
         hipError_t e = launch_merge_groups(lists2, nq, p.S2, p.merge_group, k, merge_tmp, st);
         if (e != hipSuccess) return e;
-        return launch_merge(merge_tmp, nq, groups, k, extra, nullptr, nullptr, ids, dist, qnorms, metric, st);
+        return launch_merge(merge_tmp, nq, groups, k, extra, nullptr, nullptr, ids, dist, qnorms, metric, st, true);
     };
     auto scan = [&](int64_t r0, int64_t r1, int S, const cand_t *sd, cand_t *out) -> hipError_t {
         KernelSpan span(st);
@@ -468,7 +470,7 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k
         HIP_TRY(final_merge(nullptr));
     } else if (p.seed_rows) {
         HIP_TRY(scan(0, p.seed_rows, p.S1, nullptr, lists1));
-        HIP_TRY(launch_merge(lists1, nq, p.S1, k, nullptr, seedlist, seeds, nullptr, nullptr, nullptr, metric, st));
+        HIP_TRY(launch_merge(lists1, nq, p.S1, k, nullptr, seedlist, seeds, nullptr, nullptr, nullptr, metric, st, sorted));
         HIP_TRY(scan(p.seed_rows, a.n, p.S2, seeds, lists2));
         HIP_TRY(final_merge(seedlist));
     } else {
@@ -499,11 +501,10 @@ extern "C" int lpq_search(const lpq_index *idx, const float *q_dev, int64_t nq, 
     if ((uintptr_t)workspace_dev % 256) return fail(LPQ_EINVAL, "workspace must be 256-byte aligned");
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace_dev;
-    // Padding query rows [nq, nq_pad) are zero codes; their results are never written out.
-    HIP_TRY(launch_zero_bytes(ws + p.off_qcodes + (size_t)nq * idx->d_pad, (size_t)(p.nq_pad - nq) * idx->d_pad, st));
+    // Padding query rows [nq, nq_pad) are written as zero codes; their results are never written out.
     HIP_TRY(launch_encode(view(idx->params, idx->d, idx->bits), q_dev, nq, ld,
                           reinterpret_cast<int8_t *>(ws + p.off_qcodes), idx->d_pad, idx->d_pad,
-                          reinterpret_cast<int32_t *>(ws + p.off_qnorms), st));
+                          reinterpret_cast<int32_t *>(ws + p.off_qnorms), st, p.nq_pad));
     return search_core(idx, p, ws, nq, k, metric, ids_dev, dist_dev, st);
 }
 
@@ -519,9 +520,8 @@ extern "C" int lpq_search_i8(const lpq_index *idx, const int8_t *qcodes_dev, int
     if ((uintptr_t)workspace_dev % 256) return fail(LPQ_EINVAL, "workspace must be 256-byte aligned");
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace_dev;
-    HIP_TRY(launch_zero_bytes(ws + p.off_qcodes + (size_t)nq * idx->d_pad, (size_t)(p.nq_pad - nq) * idx->d_pad, st));
     HIP_TRY(launch_repack_i8(qcodes_dev, nq, ld, idx->d, reinterpret_cast<int8_t *>(ws + p.off_qcodes), idx->d_pad,
-                             idx->d_pad, reinterpret_cast<int32_t *>(ws + p.off_qnorms), st));
+                             idx->d_pad, reinterpret_cast<int32_t *>(ws + p.off_qnorms), st, p.nq_pad));
     return search_core(idx, p, ws, nq, k, metric, ids_dev, dist_dev, st);
 }
 

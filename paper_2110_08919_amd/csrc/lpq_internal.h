@@ -74,12 +74,13 @@ hipError_t launch_calibrate(const float *x, int64_t n, int64_t ld, int d, int bi
                             int *nonfinite_flag, hipStream_t st);
 hipError_t launch_derive_m(float *params, int d, int bits, hipStream_t st);
 // Equation 1 on n rows.  zero_pad_to > d additionally writes zero bytes for columns
-// d .. zero_pad_to-1 of each row.
+// d .. zero_pad_to-1 of each row; n_out > n additionally writes rows n .. n_out-1 as zero codes
+// (and zero norms).
 hipError_t launch_encode(const QuantParams &qp, const float *x, int64_t n, int64_t ld, int8_t *codes,
-                         int64_t ldc, int zero_pad_to, int32_t *norms, hipStream_t st);
+                         int64_t ldc, int zero_pad_to, int32_t *norms, hipStream_t st, int64_t n_out = 0);
 // Copy codes into padded rows (zero padding), computing norms.
 hipError_t launch_repack_i8(const int8_t *src, int64_t n, int64_t ld, int d, int8_t *dst, int64_t ldd,
-                            int d_pad, int32_t *norms, hipStream_t st);
+                            int d_pad, int32_t *norms, hipStream_t st, int64_t n_out = 0);
 // Derived per-item arrays used by the matrix-core kernel: cinit_j = -ceil(nx_j / 2) and one
 // word of 32 parity bits (bit r = nx_{32w+r} & 1) per 32 items; rows >= n of the last word's
 // block get cinit = CINIT_PAD.  use_norms = false (IP) gives cinit = 0 and parity = 0.
@@ -131,10 +132,11 @@ hipError_t launch_seed_finalize(const int32_t *gmax, int64_t nq, int G, int k, c
 // Merge P lists of k candidates per query into one (merge.hip).  If ids/dists are given the
 // result is final: ids, and dist = key + qnorm (L2SQ) or -key/2 (IP).  Otherwise the merged
 // candidates go to out_lists[q][k] (sorted) and, if seeds_out, seeds_out[q] = the k-th best
-// candidate (CAND_NONE when fewer than k exist).
+// candidate (CAND_NONE when fewer than k exist).  sorted_lists: every input list is in
+// ascending order (allows the selection kernel for small k and many lists).
 hipError_t launch_merge(const cand_t *lists, int64_t nq, int P, int k, const cand_t *extra_lists,
                         cand_t *out_lists, cand_t *seeds_out, int32_t *ids, int32_t *dists,
-                        const int32_t *qnorms, int metric, hipStream_t st);
+                        const int32_t *qnorms, int metric, hipStream_t st, bool sorted_lists = false);
 int merge_max_lists(int k);
 // First pass of a two-pass merge: groups of `group` consecutive lists of each query are merged
 // into out_lists[q][ceil(P/group)][k].

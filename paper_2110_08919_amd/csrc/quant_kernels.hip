@@ -249,8 +249,9 @@ constexpr int ENC_UNROLL = 4;
 template <int TPR, bool VEC>
 __global__ __launch_bounds__(ENC_THREADS) void encode_kernel(
     QuantParams qp, const float *__restrict__ x, int64_t n, int64_t ld, int8_t *__restrict__ codes,
-    int64_t ldc, int zero_pad_to, int32_t *__restrict__ norms)
+    int64_t ldc, int zero_pad_to, int32_t *__restrict__ norms, int64_t n_out)
 {
+    // rows n .. n_out-1 (padding rows of a query tile) are written as zero codes
     constexpr int RPW = 64 / TPR;
     const int lane = threadIdx.x & 63;
     const int sub = lane % TPR, rsel = lane / TPR;
@@ -269,7 +270,7 @@ __global__ __launch_bounds__(ENC_THREADS) void encode_kernel(
             if (c < d) { ck[j] = qp.k[c]; cb[j] = qp.sb[c]; ce[j] = qp.se[c]; cm[j] = qp.m[c]; }
         }
     }
-    for (int64_t base = wave_id * RPW * ENC_UNROLL; base < n; base += nwaves * RPW * ENC_UNROLL) {
+    for (int64_t base = wave_id * RPW * ENC_UNROLL; base < n_out; base += nwaves * RPW * ENC_UNROLL) {
         int acc[ENC_UNROLL];
 #pragma unroll
         for (int u = 0; u < ENC_UNROLL; ++u) acc[u] = 0;
@@ -301,11 +302,11 @@ __global__ __launch_bounds__(ENC_THREADS) void encode_kernel(
 #pragma unroll
             for (int u = 0; u < ENC_UNROLL; ++u) {
                 const int64_t r = base + u * RPW + rsel;
-                if (r < n && g < pgroups) {
+                if (r < n_out && g < pgroups) {
                     int q[4];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        q[j] = (c0 + j < d) ? quantize_one(v[u][j], ck[j], cb[j], ce[j], cm[j], half) : 0;
+                        q[j] = (c0 + j < d && r < n) ? quantize_one(v[u][j], ck[j], cb[j], ce[j], cm[j], half) : 0;
                         acc[u] += q[j] * q[j];
                     }
                     const int lim = (zero_pad_to > d) ? zero_pad_to : d;
@@ -328,7 +329,7 @@ __global__ __launch_bounds__(ENC_THREADS) void encode_kernel(
 #pragma unroll
                 for (int o = TPR / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
                 const int64_t r = base + u * RPW + rsel;
-                if (sub == 0 && r < n) norms[r] = s;
+                if (sub == 0 && r < n_out) norms[r] = s;
             }
         }
     }
@@ -337,21 +338,21 @@ __global__ __launch_bounds__(ENC_THREADS) void encode_kernel(
 // Copy int8 rows into zero-padded rows and compute their norms; 16 lanes per row.
 __global__ __launch_bounds__(256) void repack_i8_kernel(
     const int8_t *__restrict__ src, int64_t n, int64_t ld, int d, int8_t *__restrict__ dst,
-    int64_t ldd, int d_pad, int32_t *__restrict__ norms)
+    int64_t ldd, int d_pad, int32_t *__restrict__ norms, int64_t n_out)
 {
     const int sub = threadIdx.x & 15;
     const int64_t r = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 4;
     int s = 0;
-    if (r < n) {
+    if (r < n_out) {
         for (int c = sub; c < d_pad; c += 16) {
-            const int v = (c < d) ? (int)src[r * ld + c] : 0;
+            const int v = (c < d && r < n) ? (int)src[r * ld + c] : 0;
             dst[r * ldd + c] = (int8_t)v;
             s += v * v;
         }
     }
 #pragma unroll
     for (int o = 8; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-    if (r < n && sub == 0 && norms) norms[r] = s;
+    if (r < n_out && sub == 0 && norms) norms[r] = s;
 }
 
 __global__ __launch_bounds__(256) void zero_words_kernel(uint32_t *p, size_t words)
@@ -417,45 +418,48 @@ hipError_t launch_derive_m(float *params, int d, int bits, hipStream_t st)
 
 template <int TPR>
 static void encode_dispatch(bool vec, int blocks, hipStream_t st, const QuantParams &qp, const float *x,
-                            int64_t n, int64_t ld, int8_t *codes, int64_t ldc, int zero_pad_to, int32_t *norms)
+                            int64_t n, int64_t ld, int8_t *codes, int64_t ldc, int zero_pad_to, int32_t *norms,
+                            int64_t n_out)
 {
     if (vec)
-        encode_kernel<TPR, true><<<blocks, ENC_THREADS, 0, st>>>(qp, x, n, ld, codes, ldc, zero_pad_to, norms);
+        encode_kernel<TPR, true><<<blocks, ENC_THREADS, 0, st>>>(qp, x, n, ld, codes, ldc, zero_pad_to, norms, n_out);
     else
-        encode_kernel<TPR, false><<<blocks, ENC_THREADS, 0, st>>>(qp, x, n, ld, codes, ldc, zero_pad_to, norms);
+        encode_kernel<TPR, false><<<blocks, ENC_THREADS, 0, st>>>(qp, x, n, ld, codes, ldc, zero_pad_to, norms, n_out);
 }
 
 hipError_t launch_encode(const QuantParams &qp, const float *x, int64_t n, int64_t ld, int8_t *codes,
-                         int64_t ldc, int zero_pad_to, int32_t *norms, hipStream_t st)
+                         int64_t ldc, int zero_pad_to, int32_t *norms, hipStream_t st, int64_t n_out)
 {
-    if (n <= 0) return hipSuccess;
+    if (n_out < n) n_out = n;
+    if (n_out <= 0) return hipSuccess;
     const int lim = zero_pad_to > qp.d ? zero_pad_to : qp.d;
     const int groups = (lim + 3) / 4;
     int tpr = 1;
     while (tpr < groups && tpr < 64) tpr <<= 1;
     const bool vec = ((uintptr_t)x % 16 == 0) && (ld % 4 == 0) && ((uintptr_t)codes % 4 == 0) && (ldc % 4 == 0);
     const int rpw = 64 / tpr;
-    int64_t waves = ceil_div(n, (int64_t)rpw * ENC_UNROLL);
+    int64_t waves = ceil_div(n_out, (int64_t)rpw * ENC_UNROLL);
     int64_t blocks = ceil_div(waves, ENC_THREADS / 64);
     if (blocks > 256 * 16) blocks = 256 * 16;
     switch (tpr) {
-    case 1: encode_dispatch<1>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms); break;
-    case 2: encode_dispatch<2>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms); break;
-    case 4: encode_dispatch<4>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms); break;
-    case 8: encode_dispatch<8>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms); break;
-    case 16: encode_dispatch<16>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms); break;
-    case 32: encode_dispatch<32>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms); break;
-    default: encode_dispatch<64>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms); break;
+    case 1: encode_dispatch<1>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms, n_out); break;
+    case 2: encode_dispatch<2>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms, n_out); break;
+    case 4: encode_dispatch<4>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms, n_out); break;
+    case 8: encode_dispatch<8>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms, n_out); break;
+    case 16: encode_dispatch<16>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms, n_out); break;
+    case 32: encode_dispatch<32>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms, n_out); break;
+    default: encode_dispatch<64>(vec, (int)blocks, st, qp, x, n, ld, codes, ldc, zero_pad_to, norms, n_out); break;
     }
     return hipGetLastError();
 }
 
 hipError_t launch_repack_i8(const int8_t *src, int64_t n, int64_t ld, int d, int8_t *dst, int64_t ldd,
-                            int d_pad, int32_t *norms, hipStream_t st)
+                            int d_pad, int32_t *norms, hipStream_t st, int64_t n_out)
 {
-    if (n <= 0) return hipSuccess;
-    const int64_t blocks = ceil_div(n * 16, 256);
-    repack_i8_kernel<<<(unsigned)blocks, 256, 0, st>>>(src, n, ld, d, dst, ldd, d_pad, norms);
+    if (n_out < n) n_out = n;
+    if (n_out <= 0) return hipSuccess;
+    const int64_t blocks = ceil_div(n_out * 16, 256);
+    repack_i8_kernel<<<(unsigned)blocks, 256, 0, st>>>(src, n, ld, d, dst, ldd, d_pad, norms, n_out);
     return hipGetLastError();
 }
 

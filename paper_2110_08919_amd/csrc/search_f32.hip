@@ -115,7 +115,7 @@ hipError_t launch_search_f32(const float *x, int64_t n, int64_t ldx, const float
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_merge(lists, nq, S, k, nullptr, nullptr, nullptr, ids, reinterpret_cast<int32_t *>(dists),
-                        nullptr, mode, st);
+                        nullptr, mode, st, true);
 }
 
 }  // namespace lpq

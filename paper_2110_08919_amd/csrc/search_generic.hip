@@ -109,6 +109,94 @@ __global__ __launch_bounds__(256) void merge_kernel(
     if (seeds_out && threadIdx.x == 0) seeds_out[q] = buf[k - 1];
 }
 
+// 64-bit minimum over the wave; every lane gets the result.
+__device__ __forceinline__ cand_t wave_min_cand(cand_t c)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const cand_t t = __shfl_xor(c, o, 64);
+        c = t < c ? t : c;
+    }
+    return c;
+}
+
+// Merge of lists that are each sorted ascending, for small k and many lists: one workgroup per
+// query; every wave takes k times the smallest head among its share of the lists (each lane owns
+// the lists first + lane, first + lane + 64, ...), then wave 0 does the same over the four wave
+// results.  Duplicated values come out once per copy, as a sort would give them.
+__global__ __launch_bounds__(256) void merge_sorted_kernel(
+    const cand_t *__restrict__ lists, int P, int k, const cand_t *__restrict__ extra,
+    cand_t *__restrict__ out_lists, cand_t *__restrict__ seeds_out, int32_t *__restrict__ ids,
+    int32_t *__restrict__ dists, const int32_t *__restrict__ qnorms, int metric)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int Pt = P + (extra ? 1 : 0);
+    cand_t *buf = reinterpret_cast<cand_t *>(smem);     // [Pt][k]
+    cand_t *wres = buf + (size_t)Pt * k;                // [4][k]
+    int *pos = reinterpret_cast<int *>(wres + 4 * k);   // [Pt] entries already taken from each list
+    const int64_t q = blockIdx.x;
+    const int m = P * k, mt = Pt * k;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int i = threadIdx.x; i < mt; i += 256) buf[i] = (i < m) ? lists[q * m + i] : extra[q * k + (i - m)];
+    for (int i = threadIdx.x; i < Pt; i += 256) pos[i] = 0;
+    __syncthreads();
+
+    const int lpw = (Pt + 3) >> 2;
+    const int first = wave * lpw, last = (first + lpw < Pt) ? first + lpw : Pt;
+    cand_t best = CAND_NONE;
+    int bl = -1;
+    for (int l = first + lane; l < last; l += 64) {
+        const cand_t c = buf[(size_t)l * k];
+        if (bl < 0 || c < best) { best = c; bl = l; }
+    }
+    for (int r = 0; r < k; ++r) {
+        const cand_t mn = wave_min_cand(best);
+        const int win = __ffsll((unsigned long long)__ballot(best == mn)) - 1;
+        if (lane == win) {
+            wres[wave * k + r] = mn;
+            if (bl >= 0 && mn != CAND_NONE) {
+                pos[bl] += 1;
+                best = CAND_NONE;
+                int nb = bl;
+                for (int l = first + lane; l < last; l += 64) {
+                    const int pp = pos[l];
+                    const cand_t c = (pp < k) ? buf[(size_t)l * k + pp] : CAND_NONE;
+                    if (c < best) { best = c; nb = l; }
+                }
+                bl = nb;
+            }
+        }
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    int p2 = 0;
+    best = (lane < 4) ? wres[lane * k] : CAND_NONE;
+    for (int r = 0; r < k; ++r) {
+        const cand_t mn = wave_min_cand(best);
+        const int win = __ffsll((unsigned long long)__ballot(best == mn)) - 1;
+        if (lane == win) {
+            if (out_lists) out_lists[q * k + r] = mn;
+            if (seeds_out && r == k - 1) seeds_out[q] = mn;
+            if (ids) {
+                const int32_t key = cand_key(mn);
+                ids[q * k + r] = (mn == CAND_NONE) ? -1 : (int32_t)cand_id(mn);
+                int32_t v;
+                if (metric == MODE_I8_L2) v = key + qnorms[q];
+                else if (metric == MODE_I8_IP) v = -(key / 2);
+                else {
+                    const float f = sortable_to_float(key);
+                    v = __float_as_int(metric == MODE_F32_L2 ? f : -f);
+                }
+                dists[q * k + r] = v;
+            }
+            if (lane < 4 && mn != CAND_NONE) {
+                ++p2;
+                best = (p2 < k) ? wres[lane * k + p2] : CAND_NONE;
+            }
+        }
+    }
+}
+
 // One workgroup per (query, group): sort the candidates of `group` consecutive lists.
 __global__ __launch_bounds__(256) void merge_groups_kernel(const cand_t *__restrict__ lists, int P, int group, int groups,
                                                            int k, int cap, cand_t *__restrict__ out_lists)
@@ -157,10 +245,17 @@ hipError_t launch_search_generic(const SearchArgs &a, int64_t row0, int64_t row1
 
 hipError_t launch_merge(const cand_t *lists, int64_t nq, int P, int k, const cand_t *extra_lists,
                         cand_t *out_lists, cand_t *seeds_out, int32_t *ids, int32_t *dists,
-                        const int32_t *qnorms, int metric, hipStream_t st)
+                        const int32_t *qnorms, int metric, hipStream_t st, bool sorted_lists)
 {
     if (nq <= 0) return hipSuccess;
     const int total = P * k + (extra_lists ? k : 0);
+    if (sorted_lists && k <= 32 && total >= 1024 && total <= 4096) {   // many short sorted lists
+        const int Pt = P + (extra_lists ? 1 : 0);
+        const size_t lds = (size_t)(Pt + 4) * k * sizeof(cand_t) + (size_t)Pt * sizeof(int);
+        merge_sorted_kernel<<<(unsigned)nq, 256, lds, st>>>(lists, P, k, extra_lists, out_lists, seeds_out, ids,
+                                                           dists, qnorms, metric);
+        return hipGetLastError();
+    }
     const int cap = next_pow2(total < 2 ? 2 : total);
     if (cap > 4096) return hipErrorInvalidValue;
     merge_kernel<<<(unsigned)nq, 256, (size_t)cap * sizeof(cand_t), st>>>(

@@ -179,17 +179,20 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     constexpr int NB = 2;
     // RSPLIT (few queries): the waves of a workgroup share ONE 64-query tile and split the rows of
     // a stage between them (one 32-row block each), so no matrix work is spent on padding queries.
+    // Every wave then copies, waits for and reads only its own quarter of each stage: the waves run
+    // without any workgroup barrier and the path is bound by how fast the corpus streams in.
     constexpr int QT = RSPLIT ? NQW : NW * NQW;   // queries per workgroup
     constexpr int CPR = 2 * KS;            // 16-byte chunks per corpus row
     constexpr int SLOTS = CPR <= 2 ? 2 : (CPR <= 4 ? 4 : (CPR <= 8 ? 8 : 16));  // LDS slots per row
     constexpr int RS = RSPLIT ? 32 * NW : 64;   // corpus rows per stage
-    constexpr int NST = (KS <= 4 && !RSPLIT) ? 4 : 3;   // LDS ring depth
+    constexpr int NST = (KS <= 4 && !RSPLIT) ? 4 : 3;   // LDS ring depth (a deeper ring measured slower for RSPLIT)
     static_assert(!RSPLIT || KS <= 4, "row-split staging is sized for rows of up to 128 bytes");
     constexpr int STAGE_BYTES = RS * SLOTS * 16;
     constexpr int IPW = RS * SLOTS / 64 / NW;   // async copy instructions per wave and stage
     constexpr int AUX_INTS = RS + 4;       // cinit[RS] then parity words
     static_assert(RS * SLOTS % (64 * NW) == 0 && IPW >= 1, "stage must split evenly over the waves");
-    static_assert((NST - 1) * (IPW + 1) <= 15, "wait_vmcnt covers 0..15");
+    static_assert((NST - 1) * (IPW + (RSPLIT ? 2 : 1)) <= 15, "wait_vmcnt covers 0..15");
+    static_assert(!RSPLIT || IPW * 64 == 32 * SLOTS, "row-split: a wave copies exactly its own 32 rows");
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction
@@ -251,7 +254,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     // `wave` copies positions [(wave*IPW + j)*64, +64) with instruction j; the lane's source
     // is the chunk that belongs in its slot, so every instruction reads whole rows.
     const unsigned ring_lds = lds_offset(ring), aux_lds = lds_offset(aux);
-    const int lpt = IPW + ((L2 && wave < RS / 64 + 1) ? 1 : 0);   // copies this wave issues per stage
+    const int lpt = IPW + (!L2 ? 0 : (RSPLIT ? 2 : (wave < RS / 64 + 1 ? 1 : 0)));   // copies this wave issues per stage
     int src_off[IPW];   // byte offset of the lane's source chunk inside a stage of corpus rows
 #pragma unroll
     for (int j = 0; j < IPW; ++j) {
@@ -269,7 +272,12 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
         const int8_t *src_ = a.codes + r0_ * (32 * KS);                                                 \
         _Pragma("unroll") for (int j = 0; j < IPW; ++j)                                                 \
             async_copy16(src_ + src_off[j], ring_lds + ring_slot_ * STAGE_BYTES + (wave * IPW + j) * 1024); \
-        if (L2 && wave < RS / 64) {                                                                     \
+        if (L2 && RSPLIT) { /* each wave brings the seeds and the parity word of its own block */       \
+            if (lane < 32)                                                                              \
+                async_copy4(a.cinit + r0_ + wave * 32 + lane, aux_lds + (ring_slot_ * AUX_INTS + wave * 32) * 4); \
+            if (lane < 1)                                                                               \
+                async_copy4(a.parity + r0_ / 32 + wave, aux_lds + (ring_slot_ * AUX_INTS + RS + wave) * 4); \
+        } else if (L2 && wave < RS / 64) {                                                              \
             async_copy4(a.cinit + r0_ + wave * 64 + lane, aux_lds + (ring_slot_ * AUX_INTS + wave * 64) * 4); \
         } else if (L2 && wave == RS / 64) {                                                             \
             if (lane < RS / 32)                                                                         \
@@ -372,27 +380,17 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     // stage t (its last LDS reads were waited for), so the ring slot of stage t can be refilled
     // with stage t + NST, and stage t+1 is known to have landed.
     if constexpr (RSPLIT) {
-        // One 32-row block per wave and stage; the barrier is at the top of a stage.
+        // One 32-row block per wave and stage, no workgroup barrier: the wave waits for its own
+        // copies of stage t, refills the slot it finished reading one step ago, and computes.
         v4i A0[KS];
         v16i C0;
         unsigned P0 = 0;
         for (int st = 0; st < NST - 1 && st < T; ++st) LPQ_ISSUE(st);
         for (int t = 0; t < T; ++t) {
-            if (!SEED && lane == 0) flags[(t & 1) * 8 + wave] = qcnt >= TRIG;
             // stages issued so far: 0 .. min(T-1, t+NST-2); wait until stage t has landed
             const int newer = (T - 1 < t + NST - 2 ? T - 1 : t + NST - 2) - t;
             wait_vmcnt(newer * lpt);
-            __syncthreads();   // stage t is in LDS for everybody; stage t-1 is no longer read
-            if (t + NST - 1 < T) LPQ_ISSUE(t + NST - 1);   // refills the slot of stage t-1
-            if (!SEED) {
-                const v4i f = *reinterpret_cast<const v4i *>(flags + (t & 1) * 8);
-                if (f[0] | f[1] | f[2] | f[3]) {
-                    drain_queue<L2, KCAP>(w, qcnt, re, lane, lst, seedC);
-                    qcnt = 0;
-#pragma unroll
-                    for (int j = 0; j < NB; ++j) thr[j] = w.thrE[j * 32 + col];
-                }
-            }
+            if (t + NST - 1 < T) LPQ_ISSUE(t + NST - 1);   // into the slot of stage t-1
             LPQ_LOAD_BLOCK(t, wave, A0, C0, P0);
             LPQ_BLOCK(t, wave, A0, C0, P0);
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // my reads of stage t are complete
@@ -405,7 +403,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
             }
         }
     } else {
-    v4i A0[KS], A1[KS];
+        v4i A0[KS], A1[KS];
         v16i C0, C1;
         unsigned P0 = 0, P1 = 0;
         const bool abl_nodma = a.dry_run >= 3, abl_nobar = a.dry_run == 2 || a.dry_run == 4;   // timing ablations
@@ -487,30 +485,45 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     }
 }
 
-// One workgroup per query: the k-th largest of its G group maxima becomes the seed threshold.
-__global__ __launch_bounds__(128) void seed_finalize_kernel(const int32_t *__restrict__ gmax, int G, int cap, int k,
+// One wave per query: the k-th largest of its G group maxima (duplicates counted) becomes the
+// seed threshold.  Each lane keeps E of the values in registers; k times the wave takes the
+// largest value left and the first lane holding it drops one copy.
+template <int E>
+__global__ __launch_bounds__(256) void seed_finalize_kernel(const int32_t *__restrict__ gmax, int64_t nq, int G, int k,
                                                             cand_t *__restrict__ seeds)
 {
-    extern __shared__ __align__(16) unsigned char smem[];
-    int *buf = reinterpret_cast<int *>(smem);
-    const int64_t q = blockIdx.x;
-    for (int i = threadIdx.x; i < cap; i += 128) buf[i] = (i < G) ? gmax[q * G + i] : INT32_MIN;
-    __syncthreads();
-    for (int size = 2; size <= cap; size <<= 1) {          // bitonic sort, descending
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int i = threadIdx.x; i < (cap >> 1); i += 128) {
-                const int lo = 2 * i - (i & (stride - 1)), hi = lo + stride;
-                const bool down = (lo & size) == 0;
-                const int x = buf[lo], y = buf[hi];
-                if ((x < y) == down) { buf[lo] = y; buf[hi] = x; }
-            }
-            __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int64_t q = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (q >= nq) return;                                   // wave-uniform
+    int v[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const int i = e * 64 + lane;
+        v[e] = (i < G) ? gmax[q * G + i] : INT32_MIN;
+    }
+    int kth = INT32_MIN;
+    for (int r = 0; r < k; ++r) {
+        int mx = v[0];
+#pragma unroll
+        for (int e = 1; e < E; ++e) mx = v[e] > mx ? v[e] : mx;
+        int wmx = mx;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const int t = __shfl_xor(wmx, o, 64);
+            wmx = t > wmx ? t : wmx;
+        }
+        kth = wmx;
+        const int win = __ffsll((unsigned long long)__ballot(mx == wmx)) - 1;
+        bool done = lane != win;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const bool hit = !done && v[e] == wmx;
+            v[e] = hit ? INT32_MIN : v[e];
+            done = done || hit;
         }
     }
-    if (threadIdx.x == 0) {
-        const int e = buf[k - 1];   // at least k items have E >= e, hence key <= -2e
-        seeds[q] = (G < k || e == INT32_MIN) ? CAND_NONE : make_cand(-2 * e, 0xFFFFFFFFu);
-    }
+    // at least k items have E >= kth, hence key <= -2 kth
+    if (lane == 0) seeds[q] = (G < k || kth == INT32_MIN) ? CAND_NONE : make_cand(-2 * kth, 0xFFFFFFFFu);
 }
 
 size_t lds_bytes(int ks, bool seed, int nw, bool rsplit)
@@ -629,9 +642,12 @@ hipError_t launch_seed_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int
 hipError_t launch_seed_finalize(const int32_t *gmax, int64_t nq, int G, int k, cand_t *seeds, hipStream_t st)
 {
     if (nq <= 0) return hipSuccess;
-    const int cap = next_pow2(G < 2 ? 2 : G);
-    if (cap > 2048) return hipErrorInvalidValue;
-    seed_finalize_kernel<<<(unsigned)nq, 128, (size_t)cap * sizeof(int), st>>>(gmax, G, cap, k, seeds);
+    if (G > 2048) return hipErrorInvalidValue;
+    const unsigned blocks = (unsigned)ceil_div(nq, (int64_t)4);
+    if (G <= 256) seed_finalize_kernel<4><<<blocks, 256, 0, st>>>(gmax, nq, G, k, seeds);
+    else if (G <= 512) seed_finalize_kernel<8><<<blocks, 256, 0, st>>>(gmax, nq, G, k, seeds);
+    else if (G <= 1024) seed_finalize_kernel<16><<<blocks, 256, 0, st>>>(gmax, nq, G, k, seeds);
+    else seed_finalize_kernel<32><<<blocks, 256, 0, st>>>(gmax, nq, G, k, seeds);
     return hipGetLastError();
 }
 

@@ -177,6 +177,24 @@ def test_search_small_batches(lpq, oracle, nq, name, n, k, metric, mode, scope):
     _run_search_case(lpq, oracle, base.scaled(n=n, nq=nq), k, metric, mode, scope, 2)
 
 
+@pytest.mark.parametrize("nq,k", [(1, 1), (3, 10), (16, 16), (64, 7)])
+def test_search_few_queries_many_splits_with_ties(lpq, oracle, nq, k):
+    """A few queries over 300k rows of 4-bit codes in 32 dimensions: hundreds of row splits each
+    hand in a sorted list, distances repeat across splits, and the merge must order by
+    (distance, id)."""
+    w = synth.SKEWED_1M.scaled(n=300_000, nq=nq)
+    x, q = w.corpus("cuda")[:, :32].contiguous(), w.queries("cuda")[:, :32].contiguous()
+    gq = lpq.Quantizer(32, 4).calibrate(x, "minmax", "global")
+    idx = lpq.Index(gq, w.n).add_f32(x)
+    oq = _oracle_quant(oracle, gq)
+    oc, oqc = oq.encode(x.cpu().numpy()), oq.encode(q.cpu().numpy())
+    for metric in ("l2sq", "ip"):
+        ids, dists = idx.search(q, k, metric)
+        oids, odists = oracle.search_i8(oc, oqc, k, metric, threads=16)
+        assert np.array_equal(dists.cpu().numpy(), odists)
+        assert np.array_equal(ids.cpu().numpy(), oids)
+
+
 @pytest.mark.parametrize("path", PATHS)
 def test_search_many_ties_low_bits(lpq, oracle, path):
     """3-bit codes in 8 dimensions: almost every distance is tied; order must follow ids."""
