@@ -147,7 +147,10 @@ int lpq_search_f32(const float *x_dev, int64_t n, int64_t ldx, const float *q_de
 /* ---------------------------------------------------------------- diagnostics ---- */
 
 /* Process-wide tuning knobs for measurements; 0 restores the built-in choice.
- *   LPQ_TUNE_PATH        1 = generic dot-product kernel, 2 = matrix-core kernel
+ *   LPQ_TUNE_PATH        1 = generic dot-product kernel, 2 = matrix-core kernels (built-in
+ *                        choice of variant), 3 = the collecting matrix-core variant for every
+ *                        k it takes (k <= 128), 4 = matrix-core kernels without the
+ *                        collecting variant
  *   LPQ_TUNE_SPLITS      number of corpus splits per query tile in the main pass
  *   LPQ_TUNE_SEED_ROWS   rows of the threshold-seeding pass (0 = built-in choice,
  *                        -1 = no seeding pass)

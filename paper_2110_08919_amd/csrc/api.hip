@@ -316,7 +316,7 @@ extern "C" int lpq_index_data(const lpq_index *idx, const int8_t **codes_dev, in
 namespace {
 
 // How a search over n items is cut up, and where its intermediates live in the workspace.
-enum PlanMode { PLAN_GENERIC = 0, PLAN_MFMA_LDS = 1, PLAN_MFMA_REG = 2 };
+enum PlanMode { PLAN_GENERIC = 0, PLAN_MFMA_LDS = 1, PLAN_MFMA_REG = 2, PLAN_MFMA_COLLECT = 3 };
 struct Plan {
     int mode = PLAN_GENERIC;
     int64_t nq_pad = 0;
@@ -326,8 +326,11 @@ struct Plan {
     int G = 0;              // PLAN_MFMA_REG: group maxima per query
     bool rsplit = false;    // PLAN_MFMA_REG: row-split workgroups (few queries)
     int merge_group = 0;    // lists merged per workgroup in the first merge pass (0 = single pass)
+    int64_t seed_stride = 0, seed_chunk = 0;   // seeding pass over S1 chunks spread over the corpus
+    int SS = 0, Cs = 0;     // PLAN_MFMA_COLLECT: regions per query, capacity of a region
+    int Sg = 0;             // PLAN_MFMA_COLLECT: splits of the generic kernel for overflowed queries
     size_t off_qcodes = 0, off_qnorms = 0, off_lists1 = 0, off_seedlist = 0, off_seeds = 0, off_lists2 = 0,
-           off_gmax = 0, off_merge_tmp = 0, total = 0;
+           off_gmax = 0, off_merge_tmp = 0, off_cbuf = 0, off_ccnt = 0, off_over = 0, total = 0;
 };
 
 size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
@@ -337,7 +340,10 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     Plan p;
     const int64_t n = idx->size;
     const int64_t want = g_tune[LPQ_TUNE_PATH];
-    if (want != 1 && mfma_reg_supported(idx->d_pad, k)) p.mode = PLAN_MFMA_REG;
+    const bool regs = mfma_reg_supported(idx->d_pad, k), coll = mfma_collect_supported(idx->d_pad, k);
+    if (want == 3 && coll) p.mode = PLAN_MFMA_COLLECT;
+    else if (want != 1 && regs) p.mode = PLAN_MFMA_REG;
+    else if (want != 1 && want != 4 && coll) p.mode = PLAN_MFMA_COLLECT;
     else if (want != 1 && mfma_lds_supported(idx->d_pad, k)) p.mode = PLAN_MFMA_LDS;
     p.nq_pad = round_up(nq > 0 ? nq : 1, 512);
     // A merge pass sorts up to 4096 candidates per workgroup; more lists than that are merged in
@@ -345,20 +351,30 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     const int max_lists = merge_max_lists(k) * (merge_max_lists(k) > 1 ? merge_max_lists(k) : 1);
     const int64_t slots = 512;   // workgroups of the matrix-core kernels resident at once (2 per CU)
 
-    // Seeding pass over a first slice of the corpus: it yields, per query, an upper bound on
-    // the final k-th best key, so the main pass rejects almost everything from its first
-    // tile on.  PLAN_MFMA_REG derives the bound from group maxima (no candidates collected)
-    // and then scans ALL rows; PLAN_MFMA_LDS searches the slice exactly and scans the rest.
+    // Seeding pass over a sample of the corpus: it yields, per query, an upper bound on the final
+    // k-th best key, so the main pass rejects almost everything from its first tile on.
+    // PLAN_MFMA_REG and PLAN_MFMA_COLLECT derive the bound from group maxima over chunks spread
+    // evenly over the corpus (no candidates collected) and then scan ALL rows; PLAN_MFMA_LDS
+    // searches a first slice exactly and scans the rest.  The collecting scan never tightens the
+    // bound, so its sample is a fixed fraction of the corpus: about k n / seed_rows candidates
+    // per query survive.
+    const bool gm = p.mode == PLAN_MFMA_REG || p.mode == PLAN_MFMA_COLLECT;
     int64_t seed = 0;
     if (g_tune[LPQ_TUNE_SEED_ROWS] > 0) seed = g_tune[LPQ_TUNE_SEED_ROWS];
     else if (g_tune[LPQ_TUNE_SEED_ROWS] == 0 && p.mode != PLAN_GENERIC) {
-        seed = p.mode == PLAN_MFMA_REG ? n / 16 : n / 64;
-        const int64_t lo = p.mode == PLAN_MFMA_REG ? 8192 : 4096, hi = p.mode == PLAN_MFMA_REG ? 65536 : 32768;
+        seed = gm ? n / 16 : n / 64;
+        if (p.mode == PLAN_MFMA_COLLECT) {   // measured optimum: the sample grows with k, n/16 .. n/4
+            const int64_t by_k = n / 400 * k;
+            seed = by_k < n / 16 ? n / 16 : (by_k > n / 4 ? n / 4 : by_k);
+        }
+        const int64_t lo = gm ? 8192 : 4096, hi = p.mode == PLAN_MFMA_COLLECT ? n : (gm ? 65536 : 32768);
         seed = seed < lo ? lo : (seed > hi ? hi : seed);
     }
     seed = seed / 256 * 256;
     if (seed < 64 * k || seed * 4 > n) seed = 0;
-    p.seed_rows = seed;
+    if (p.mode == PLAN_MFMA_COLLECT && !seed) {   // too few items to sample: exact paths
+        p.mode = (regs && want != 1) ? PLAN_MFMA_REG : (mfma_lds_supported(idx->d_pad, k) ? PLAN_MFMA_LDS : PLAN_GENERIC);
+    }
 
     auto splits_for = [&](int64_t rows, int64_t tiles_q, int64_t min_rows, int64_t slots, int64_t cap) {
         int64_t s;
@@ -370,37 +386,61 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
         if (s < 1) s = 1;
         return (int)s;
     };
+    const bool gmode = p.mode == PLAN_MFMA_REG || p.mode == PLAN_MFMA_COLLECT;
     int64_t qt = (p.mode == PLAN_MFMA_LDS && k > 16) ? 128 : 256;   // queries per workgroup
     int64_t slots_now = slots;
-    if (p.mode == PLAN_MFMA_REG) {
+    if (gmode) {
         qt = mfma_queries_per_workgroup(nq, idx->d_pad);
         p.rsplit = mfma_row_split(nq, idx->d_pad);
     }
     const int64_t tiles_q = ceil_div(nq > 0 ? nq : 1, qt);
     const int64_t min_rows = p.mode == PLAN_GENERIC ? 2048 : 512;
     if (seed) {
-        p.S1 = splits_for(seed, tiles_q, min_rows, slots_now, p.mode == PLAN_MFMA_REG ? 1024 : merge_max_lists(k));
-        if (p.mode == PLAN_MFMA_REG) {
+        p.S1 = splits_for(seed, tiles_q, min_rows, slots_now, gmode ? 1024 : merge_max_lists(k));
+        if (gmode) {
             p.SEG = mfma_seed_segments(p.S1, k, p.rsplit);
             p.G = mfma_seed_groups(p.S1, p.SEG, p.rsplit);
+            // S1 chunks of seed / S1 rows, first rows n / S1 apart (both whole 128-row blocks)
+            p.seed_chunk = seed / p.S1 / 128 * 128;
+            p.seed_stride = n / p.S1 / 128 * 128;
+            if (p.seed_chunk < 128 || p.seed_stride < p.seed_chunk) { p.seed_chunk = 0; p.seed_stride = 0; }
+            else seed = p.seed_chunk * p.S1;
         }
     }
-    p.S2 = splits_for(p.mode == PLAN_MFMA_REG ? n : n - seed, tiles_q, min_rows, slots_now,
-                      p.rsplit ? merge_max_lists(k) : max_lists);   // few queries: one merge pass, fewer launches
+    p.seed_rows = seed;
+    p.S2 = splits_for(gmode ? n : n - seed, tiles_q, min_rows, slots_now,
+                      p.mode == PLAN_MFMA_COLLECT ? (p.rsplit ? 512 : 2048)
+                                                  : (p.rsplit ? merge_max_lists(k) : max_lists));   // few queries: one merge pass
+    if (p.mode == PLAN_MFMA_COLLECT) {
+        // expected candidates per query ~ k n / seed_rows, spread over SS regions; a region holds
+        // three times its share (at least 32).  Overflow is caught per query and redone exactly.
+        p.SS = mfma_collect_regions(p.S2, p.rsplit);
+        const double per_region = 1.15 * (double)k * (double)n / (double)seed / p.SS;
+        int64_t cs = 32;
+        while ((double)cs < 3.0 * per_region && cs < 4096) cs <<= 1;
+        p.Cs = (int)cs;
+        p.Sg = 4;
+    }
 
     size_t o = 0;
     p.off_qcodes = o;   o = align256(o + (size_t)p.nq_pad * idx->d_pad);
     p.off_qnorms = o;   o = align256(o + (size_t)p.nq_pad * sizeof(int32_t));
-    p.off_lists1 = o;   o = align256(o + (p.mode == PLAN_MFMA_REG ? 0 : (size_t)nq * p.S1 * k * sizeof(cand_t)));
+    p.off_lists1 = o;   o = align256(o + (gmode ? 0 : (size_t)nq * p.S1 * k * sizeof(cand_t)));
     p.off_seedlist = o; o = align256(o + (size_t)nq * k * sizeof(cand_t));
     p.off_seeds = o;    o = align256(o + (size_t)p.nq_pad * sizeof(cand_t));
-    p.off_lists2 = o;   o = align256(o + (size_t)nq * p.S2 * k * sizeof(cand_t));
+    p.off_lists2 = o;
+    o = align256(o + (size_t)nq * (p.mode == PLAN_MFMA_COLLECT ? p.Sg : p.S2) * k * sizeof(cand_t));
     p.off_gmax = o;
-    if (p.mode == PLAN_MFMA_REG && seed) o = align256(o + (size_t)p.nq_pad * p.G * sizeof(int32_t));
+    if (gmode && seed) o = align256(o + (size_t)p.nq_pad * p.G * sizeof(int32_t));
     p.off_merge_tmp = o;
-    if (p.S2 > merge_max_lists(k)) {
+    if (p.mode != PLAN_MFMA_COLLECT && p.S2 > merge_max_lists(k)) {
         p.merge_group = merge_max_lists(k);
         o = align256(o + (size_t)nq * ceil_div(p.S2, p.merge_group) * k * sizeof(cand_t));
+    }
+    if (p.mode == PLAN_MFMA_COLLECT) {
+        p.off_cbuf = o; o = align256(o + (size_t)nq * p.SS * p.Cs * sizeof(cand_t));
+        p.off_ccnt = o; o = align256(o + (size_t)nq * p.SS * sizeof(int32_t));
+        p.off_over = o; o = align256(o + (size_t)nq * sizeof(int32_t));
     }
     p.total = o;
     return p;
@@ -456,14 +496,32 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k
         return p.mode == PLAN_GENERIC ? launch_search_generic(a, r0, r1, S, sd, out, st)
                                       : launch_search_mfma(a, r0, r1, S, sd, out, st);
     };
-    if (p.mode == PLAN_MFMA_REG) {
+    auto seed_pass = [&]() -> hipError_t {
+        {
+            KernelSpan span(st);
+            hipError_t e = p.seed_stride ? launch_seed_mfma(a, 0, a.n, p.S1, p.SEG, gmax, st, p.seed_stride, p.seed_chunk)
+                                         : launch_seed_mfma(a, 0, p.seed_rows, p.S1, p.SEG, gmax, st);
+            if (e != hipSuccess) return e;
+        }
+        return launch_seed_finalize(gmax, nq, p.G, k, seeds, st);
+    };
+    if (p.mode == PLAN_MFMA_COLLECT) {
+        cand_t *cbuf = reinterpret_cast<cand_t *>(ws + p.off_cbuf);
+        int32_t *ccnt = reinterpret_cast<int32_t *>(ws + p.off_ccnt);
+        int32_t *over = reinterpret_cast<int32_t *>(ws + p.off_over);
+        HIP_TRY(seed_pass());
+        {
+            KernelSpan span(st);
+            HIP_TRY(launch_collect_mfma(a, 0, a.n, p.S2, seeds, cbuf, ccnt, p.Cs, st));
+        }
+        HIP_TRY(launch_collect_select(cbuf, ccnt, nq, p.SS, p.Cs, k, over, ids, dist, qnorms, metric, st));
+        // queries whose candidates did not fit are searched again by the generic kernel
+        HIP_TRY(launch_search_generic(a, 0, a.n, p.Sg, nullptr, lists2, st, over));
+        HIP_TRY(launch_merge(lists2, nq, p.Sg, k, nullptr, nullptr, nullptr, ids, dist, qnorms, metric, st, false, over));
+    } else if (p.mode == PLAN_MFMA_REG) {
         const cand_t *sd = nullptr;
         if (p.seed_rows) {
-            {
-                KernelSpan span(st);
-                HIP_TRY(launch_seed_mfma(a, 0, p.seed_rows, p.S1, p.SEG, gmax, st));
-            }
-            HIP_TRY(launch_seed_finalize(gmax, nq, p.G, k, seeds, st));
+            HIP_TRY(seed_pass());
             sd = seeds;
         }
         HIP_TRY(scan(0, a.n, p.S2, sd, lists2));

@@ -48,7 +48,7 @@ __host__ __device__ inline float sortable_to_float(int32_t s)
     return f;
 }
 
-static inline int next_pow2(int v)
+__host__ __device__ static inline int next_pow2(int v)
 {
     int p = 1;
     while (p < v) p <<= 1;
@@ -106,8 +106,9 @@ struct SearchArgs {
 
 // Generic kernel: one workgroup per (query, corpus split); any d_pad (multiple of 32), any k.
 // Writes lists[(q * S + s) * k + r], sorted ascending, CAND_NONE-filled.
+// only (optional): int[nq]; workgroups of queries with only[q] == 0 return at once.
 hipError_t launch_search_generic(const SearchArgs &a, int64_t row0, int64_t row1, int S,
-                                 const cand_t *seeds, cand_t *lists, hipStream_t st);
+                                 const cand_t *seeds, cand_t *lists, hipStream_t st, const int32_t *only = nullptr);
 
 // Matrix-core kernels.  search_mfma.hip keeps the k best of a query in registers (k <= 16) and
 // has a seeding pass; search_mfma_lds.hip keeps them in LDS (larger k).  launch_search_mfma
@@ -125,8 +126,22 @@ int mfma_seed_segments(int S, int k, bool rsplit);
 int mfma_seed_groups(int S, int SEG, bool rsplit);        // = G, entries per query in gmax
 int mfma_queries_per_workgroup(int64_t nq, int d_pad);   // query tile of the register variant
 bool mfma_row_split(int64_t nq, int d_pad);              // few queries: waves split rows, share queries
+// With stride > 0 the pass reads S chunks of chunk_rows rows (a multiple of 128, <= stride) whose
+// first rows are row0, row0 + stride, ...: a sample spread over the corpus.
 hipError_t launch_seed_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S, int SEG, int32_t *gmax,
-                            hipStream_t st);
+                            hipStream_t st, int64_t stride = 0, int64_t chunk_rows = 0);
+// Collecting scan (k <= 128): thresholds stay at seeds[q] (required); every candidate beating its
+// query's seed is appended to cbuf[(q * SS + region) * Cs + ...], SS = mfma_collect_regions(S, rsplit),
+// and ccnt[q * SS + region] = number offered (entries beyond Cs were dropped).
+bool mfma_collect_supported(int d_pad, int k);
+int mfma_collect_regions(int S, bool rsplit);
+hipError_t launch_collect_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds,
+                               cand_t *cbuf, int32_t *ccnt, int Cs, hipStream_t st);
+// Per query: if no region overflowed and at most 4096 candidates were collected, sort them, write
+// the k best as the final result and set over[q] = 0; otherwise set over[q] = 1 and write nothing.
+hipError_t launch_collect_select(const cand_t *cbuf, const int32_t *ccnt, int64_t nq, int SS, int Cs, int k,
+                                 int32_t *over, int32_t *ids, int32_t *dists, const int32_t *qnorms, int metric,
+                                 hipStream_t st);
 hipError_t launch_seed_finalize(const int32_t *gmax, int64_t nq, int G, int k, cand_t *seeds, hipStream_t st);
 
 // Merge P lists of k candidates per query into one (merge.hip).  If ids/dists are given the
@@ -136,7 +151,8 @@ hipError_t launch_seed_finalize(const int32_t *gmax, int64_t nq, int G, int k, c
 // ascending order (allows the selection kernel for small k and many lists).
 hipError_t launch_merge(const cand_t *lists, int64_t nq, int P, int k, const cand_t *extra_lists,
                         cand_t *out_lists, cand_t *seeds_out, int32_t *ids, int32_t *dists,
-                        const int32_t *qnorms, int metric, hipStream_t st, bool sorted_lists = false);
+                        const int32_t *qnorms, int metric, hipStream_t st, bool sorted_lists = false,
+                        const int32_t *only = nullptr);   // only: as in launch_search_generic
 int merge_max_lists(int k);
 // First pass of a two-pass merge: groups of `group` consecutive lists of each query are merged
 // into out_lists[q][ceil(P/group)][k].

@@ -15,7 +15,7 @@ constexpr int GEN_ROWS = GEN_THREADS / 8;  // rows per step: 8 lanes share a row
 
 __global__ __launch_bounds__(GEN_THREADS) void search_generic_kernel(
     SearchArgs a, int64_t row0, int64_t row1, int S, int64_t split_rows, const cand_t *__restrict__ seeds,
-    cand_t *__restrict__ lists, int cap)
+    cand_t *__restrict__ lists, int cap, const int32_t *__restrict__ only)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     cand_t *buf = reinterpret_cast<cand_t *>(smem);
@@ -24,6 +24,7 @@ __global__ __launch_bounds__(GEN_THREADS) void search_generic_kernel(
     __shared__ cand_t s_thr;
 
     const int64_t q = blockIdx.x / S;
+    if (only && !only[q]) return;   // same for the whole workgroup
     const int s = blockIdx.x % S;
     const int chunks = a.d_pad >> 4;  // 16-byte chunks per row
     const int64_t rs = row0 + (int64_t)s * split_rows;
@@ -72,15 +73,32 @@ __global__ __launch_bounds__(GEN_THREADS) void search_generic_kernel(
     for (int i = threadIdx.x; i < a.k; i += GEN_THREADS) out[i] = buf[i];
 }
 
+// Final id and distance of candidate c of query q, written at position `at`.
+__device__ __forceinline__ void emit_result(cand_t c, int64_t at, int64_t q, int32_t *__restrict__ ids,
+                                            int32_t *__restrict__ dists, const int32_t *__restrict__ qnorms, int metric)
+{
+    const int32_t key = cand_key(c);
+    ids[at] = (c == CAND_NONE) ? -1 : (int32_t)cand_id(c);
+    int32_t v;
+    if (metric == MODE_I8_L2) v = key + qnorms[q];
+    else if (metric == MODE_I8_IP) v = -(key / 2);
+    else {
+        const float f = sortable_to_float(key);
+        v = __float_as_int(metric == MODE_F32_L2 ? f : -f);
+    }
+    dists[at] = v;
+}
+
 // One workgroup per query: sort all candidates of its P lists (plus an optional extra list).
 __global__ __launch_bounds__(256) void merge_kernel(
     const cand_t *__restrict__ lists, int P, int k, const cand_t *__restrict__ extra, int cap,
     cand_t *__restrict__ out_lists, cand_t *__restrict__ seeds_out, int32_t *__restrict__ ids,
-    int32_t *__restrict__ dists, const int32_t *__restrict__ qnorms, int metric)
+    int32_t *__restrict__ dists, const int32_t *__restrict__ qnorms, int metric, const int32_t *__restrict__ only)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     cand_t *buf = reinterpret_cast<cand_t *>(smem);
     const int64_t q = blockIdx.x;
+    if (only && !only[q]) return;   // same for the whole workgroup
     const int m = P * k;
     for (int i = threadIdx.x; i < cap; i += 256) {
         cand_t c = CAND_NONE;
@@ -93,20 +111,76 @@ __global__ __launch_bounds__(256) void merge_kernel(
     for (int i = threadIdx.x; i < k; i += 256) {
         const cand_t c = buf[i];
         if (out_lists) out_lists[q * k + i] = c;
-        if (ids) {
-            const int32_t key = cand_key(c);
-            ids[q * k + i] = (c == CAND_NONE) ? -1 : (int32_t)cand_id(c);
-            int32_t v;
-            if (metric == MODE_I8_L2) v = key + qnorms[q];
-            else if (metric == MODE_I8_IP) v = -(key / 2);
-            else {
-                const float f = sortable_to_float(key);
-                v = __float_as_int(metric == MODE_F32_L2 ? f : -f);
-            }
-            dists[q * k + i] = v;
-        }
+        if (ids) emit_result(c, q * k + i, q, ids, dists, qnorms, metric);
     }
     if (seeds_out && threadIdx.x == 0) seeds_out[q] = buf[k - 1];
+}
+
+// Last step of the collecting scan, one workgroup per query: gather the query's regions into LDS,
+// sort, write the k best.  A query with an overflowed region, more than `maxc` candidates or fewer
+// than k is flagged in over[] instead and left to the generic kernel.
+__global__ __launch_bounds__(256) void collect_select_kernel(
+    const cand_t *__restrict__ cbuf, const int32_t *__restrict__ ccnt, int SS, int Cs, int k, int maxc,
+    int32_t *__restrict__ over, int32_t *__restrict__ ids, int32_t *__restrict__ dists,
+    const int32_t *__restrict__ qnorms, int metric)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    cand_t *buf = reinterpret_cast<cand_t *>(smem);            // [maxc]
+    int *off = reinterpret_cast<int *>(buf + maxc);            // [SS + 1] first slot of each region
+    __shared__ int tsum[256];
+    __shared__ int s_bad;
+    const int64_t q = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int per = (SS + 255) / 256;                          // consecutive regions per thread
+    const int r0 = tid * per, r1 = (r0 + per < SS) ? r0 + per : SS;
+    if (tid == 0) s_bad = 0;
+    __syncthreads();
+    int local = 0;
+    bool bad = false;
+    for (int r = r0; r < r1; ++r) {
+        const int c = ccnt[q * SS + r];
+        bad |= c > Cs || c < 0;
+        local += (c > Cs) ? Cs : (c < 0 ? 0 : c);
+    }
+    if (bad) s_bad = 1;
+    tsum[tid] = local;
+    __syncthreads();
+    for (int o = 1; o < 256; o <<= 1) {                        // inclusive scan of the thread sums
+        const int v = (tid >= o) ? tsum[tid - o] : 0;
+        __syncthreads();
+        tsum[tid] += v;
+        __syncthreads();
+    }
+    const int M = tsum[255];
+    if (s_bad || M > maxc || M < k) {
+        if (tid == 0) over[q] = 1;
+        return;
+    }
+    int run = tsum[tid] - local;
+    for (int r = r0; r < r1; ++r) {
+        off[r] = run;
+        const int c = ccnt[q * SS + r];
+        run += c;
+    }
+    if (tid == 255) off[SS] = M;
+    const int cap = next_pow2(M < 2 ? 2 : M);
+    __syncthreads();
+    for (int i = tid; i < cap; i += 256) {
+        cand_t c = CAND_NONE;
+        if (i < M) {
+            int lo = 0, hi = SS;                               // last region with off[r] <= i
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (off[mid] <= i) lo = mid; else hi = mid;
+            }
+            c = cbuf[((size_t)q * SS + lo) * Cs + (i - off[lo])];
+        }
+        buf[i] = c;
+    }
+    __syncthreads();
+    block_bitonic_sort(buf, cap);
+    for (int i = tid; i < k; i += 256) emit_result(buf[i], q * k + i, q, ids, dists, qnorms, metric);
+    if (tid == 0) over[q] = 0;
 }
 
 // 64-bit minimum over the wave; every lane gets the result.
@@ -177,18 +251,7 @@ __global__ __launch_bounds__(256) void merge_sorted_kernel(
         if (lane == win) {
             if (out_lists) out_lists[q * k + r] = mn;
             if (seeds_out && r == k - 1) seeds_out[q] = mn;
-            if (ids) {
-                const int32_t key = cand_key(mn);
-                ids[q * k + r] = (mn == CAND_NONE) ? -1 : (int32_t)cand_id(mn);
-                int32_t v;
-                if (metric == MODE_I8_L2) v = key + qnorms[q];
-                else if (metric == MODE_I8_IP) v = -(key / 2);
-                else {
-                    const float f = sortable_to_float(key);
-                    v = __float_as_int(metric == MODE_F32_L2 ? f : -f);
-                }
-                dists[q * k + r] = v;
-            }
+            if (ids) emit_result(mn, q * k + r, q, ids, dists, qnorms, metric);
             if (lane < 4 && mn != CAND_NONE) {
                 ++p2;
                 best = (p2 < k) ? wres[lane * k + p2] : CAND_NONE;
@@ -231,25 +294,37 @@ namespace {
 
 int merge_max_lists(int k) { return 4096 / k - 1; }
 
+hipError_t launch_collect_select(const cand_t *cbuf, const int32_t *ccnt, int64_t nq, int SS, int Cs, int k,
+                                 int32_t *over, int32_t *ids, int32_t *dists, const int32_t *qnorms, int metric,
+                                 hipStream_t st)
+{
+    if (nq <= 0) return hipSuccess;
+    const int maxc = 4096;
+    if (SS < 1 || SS > 2048 || k > maxc) return hipErrorInvalidValue;
+    const size_t lds = (size_t)maxc * sizeof(cand_t) + (size_t)(SS + 1) * sizeof(int);
+    collect_select_kernel<<<(unsigned)nq, 256, lds, st>>>(cbuf, ccnt, SS, Cs, k, maxc, over, ids, dists, qnorms, metric);
+    return hipGetLastError();
+}
+
 hipError_t launch_search_generic(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds,
-                                 cand_t *lists, hipStream_t st)
+                                 cand_t *lists, hipStream_t st, const int32_t *only)
 {
     if (a.nq <= 0 || row1 <= row0) return hipSuccess;
     const int cap = next_pow2((2 * a.k > a.k + 2 * GEN_ROWS) ? 2 * a.k : a.k + 2 * GEN_ROWS);
     const int64_t split_rows = round_up(ceil_div(row1 - row0, S), GEN_ROWS);
     const size_t shmem = (size_t)cap * sizeof(cand_t) + (size_t)a.d_pad;
     search_generic_kernel<<<(unsigned)(a.nq * S), GEN_THREADS, shmem, st>>>(a, row0, row1, S, split_rows,
-                                                                              seeds, lists, cap);
+                                                                              seeds, lists, cap, only);
     return hipGetLastError();
 }
 
 hipError_t launch_merge(const cand_t *lists, int64_t nq, int P, int k, const cand_t *extra_lists,
                         cand_t *out_lists, cand_t *seeds_out, int32_t *ids, int32_t *dists,
-                        const int32_t *qnorms, int metric, hipStream_t st, bool sorted_lists)
+                        const int32_t *qnorms, int metric, hipStream_t st, bool sorted_lists, const int32_t *only)
 {
     if (nq <= 0) return hipSuccess;
     const int total = P * k + (extra_lists ? k : 0);
-    if (sorted_lists && k <= 32 && total >= 1024 && total <= 4096) {   // many short sorted lists
+    if (!only && sorted_lists && k <= 32 && total >= 1024 && total <= 4096) {   // many short sorted lists
         const int Pt = P + (extra_lists ? 1 : 0);
         const size_t lds = (size_t)(Pt + 4) * k * sizeof(cand_t) + (size_t)Pt * sizeof(int);
         merge_sorted_kernel<<<(unsigned)nq, 256, lds, st>>>(lists, P, k, extra_lists, out_lists, seeds_out, ids,
@@ -259,7 +334,7 @@ hipError_t launch_merge(const cand_t *lists, int64_t nq, int P, int k, const can
     const int cap = next_pow2(total < 2 ? 2 : total);
     if (cap > 4096) return hipErrorInvalidValue;
     merge_kernel<<<(unsigned)nq, 256, (size_t)cap * sizeof(cand_t), st>>>(
-        lists, P, k, extra_lists, cap, out_lists, seeds_out, ids, dists, qnorms, metric);
+        lists, P, k, extra_lists, cap, out_lists, seeds_out, ids, dists, qnorms, metric, only);
     return hipGetLastError();
 }
 

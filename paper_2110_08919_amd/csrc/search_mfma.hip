@@ -27,6 +27,13 @@
 // the lane that owns the query (lane q of the wave owns query q): the owner keeps the k best
 // in registers as a sorted list and inserts with one compare-exchange pass.
 //
+// Collecting mode (KCAP = 0, for k beyond what fits in registers).  The threshold of a query stays
+// at its seed for the whole scan and a drain appends every exact candidate that beats it to a
+// region of global memory owned by this (query, split[, wave]): no lists, no atomics outside the
+// wave's LDS counters.  The seed threshold is reached by at least k items, so the k best are among
+// the collected ones; a later kernel selects them (or hands a query whose region overflowed to the
+// generic kernel).
+//
 // Seeding pass (SEED = true).  The same pipeline with collection switched off: every lane
 // only tracks the maximum E it has seen per segment of its split.  Each (segment, lane half)
 // is a group of items disjoint from the others, so the k-th largest group maximum of a query
@@ -42,6 +49,18 @@ constexpr int NQW = 64;      // queries per wave = lanes per wave: lane q owns q
 constexpr int TRIG = 32;     // queue fill that asks for a joint drain at the next stage boundary
 constexpr int SVCAP = 128;   // compacted candidates buffered before they are handed to owners
 
+struct MfmaIo {     // what a launch reads and writes besides the corpus and the queries
+    const cand_t *seeds;   // [nq] starting thresholds, or null
+    cand_t *lists;         // list mode: [nq][S][k]
+    int32_t *gmax;         // seeding pass: [nq_pad][G] group maxima
+    int SEG;               // seeding pass: segments per split
+    cand_t *cbuf;          // collecting mode: [nq][SS][Cs] regions, SS = S (x waves when rows are split)
+    int32_t *ccnt;         // collecting mode: [nq][SS] candidates offered to each region (may exceed Cs)
+    int Cs;
+    int64_t split_stride;       // first row of split s is row0 + s * split_stride; 0: splits follow each other
+    int64_t split_stride_rows;  // with a stride: rows per split
+};
+
 struct WaveQ {      // pointers into the wave's private LDS region
     cand_t *thrC;   // [NQW] exact threshold candidate per query
     cand_t *svc;    // [SVCAP] compacted candidates
@@ -50,7 +69,7 @@ struct WaveQ {      // pointers into the wave's private LDS region
     unsigned *qpar; // [QCAP] parity word of that block
     int *qmeta;     // [QCAP] query slot | lane half << 8
     int *thrE;      // [NQW] conservative threshold on E
-    int *mbox;      // [NQW] lane whose candidate the owner takes this round, or -1
+    int *mbox;      // [NQW] lane whose candidate the owner takes this round, or -1 (collecting mode: region fill)
     int *svq;       // [SVCAP] query slot of each compacted candidate
 };
 
@@ -121,10 +140,28 @@ __device__ __forceinline__ void give_to_owners(const WaveQ &w, int svcnt, int la
     wave_lds_sync();
 }
 
+// Collecting mode: append the first `svcnt` compacted candidates to their queries' regions.
+// The stores stay in flight; they only make the counted waits for the ring more conservative.
+__device__ __forceinline__ void append_collected(const WaveQ &w, int svcnt, int lane, cand_t *cbase, size_t qstride,
+                                                 int Cs)
+{
+    wave_lds_sync();
+    for (int base = 0; base < svcnt; base += 64) {
+        const int idx = base + lane;
+        if (idx < svcnt) {
+            const cand_t c = w.svc[idx];
+            const int ql = w.svq[idx];
+            const int pos = atomicAdd(&w.mbox[ql], 1);
+            if (pos < Cs) cbase[(size_t)ql * qstride + pos] = c;
+        }
+    }
+    wave_lds_sync();
+}
+
 // Empty the wave's dump queue.  Wave-uniform control flow.
-template <bool L2, int KCAP>
+template <bool L2, int KCAP, int LK>
 __device__ __forceinline__ void drain_queue(const WaveQ &w, int qcnt, int64_t row_end, int lane,
-                                            cand_t (&lst)[KCAP], cand_t seedC)
+                                            cand_t (&lst)[LK], cand_t seedC, cand_t *cbase, size_t qstride, int Cs)
 {
     if (qcnt <= 0) return;
     wave_lds_sync();
@@ -162,21 +199,30 @@ __device__ __forceinline__ void drain_queue(const WaveQ &w, int qcnt, int64_t ro
             if (pass) { w.svc[pos] = c; w.svq[pos] = ql; }
             svcnt += __popcll(mask);
             if (svcnt > SVCAP - 64) {
-                give_to_owners<KCAP>(w, svcnt, lane, lst, seedC);
+                if constexpr (KCAP > 0) give_to_owners<KCAP>(w, svcnt, lane, lst, seedC);
+                else append_collected(w, svcnt, lane, cbase, qstride, Cs);
                 svcnt = 0;
             }
         }
     }
-    if (svcnt) give_to_owners<KCAP>(w, svcnt, lane, lst, seedC);
+    if (svcnt) {
+        if constexpr (KCAP > 0) give_to_owners<KCAP>(w, svcnt, lane, lst, seedC);
+        else append_collected(w, svcnt, lane, cbase, qstride, Cs);
+    }
 }
 
 template <int KS, bool L2, int KCAP, bool SEED, int NW, bool RSPLIT>
 __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
-    SearchArgs a, int64_t row0, int64_t row1, int S, int64_t split_rows, int qtiles,
-    const cand_t *__restrict__ seeds, cand_t *__restrict__ lists_out, int32_t *__restrict__ gmax, int SEG)
+    SearchArgs a, int64_t row0, int64_t row1, int S, int64_t split_rows, int qtiles, MfmaIo o)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int NB = 2;
+    constexpr bool COLLECT = !SEED && KCAP == 0;
+    constexpr int LK = KCAP > 0 ? KCAP : 1;
+    const cand_t *__restrict__ seeds = o.seeds;
+    cand_t *__restrict__ lists_out = o.lists;
+    int32_t *__restrict__ gmax = o.gmax;
+    const int SEG = o.SEG;
     // RSPLIT (few queries): the waves of a workgroup share ONE 64-query tile and split the rows of
     // a stage between them (one 32-row block each), so no matrix work is spent on padding queries.
     // Every wave then copies, waits for and reads only its own quarter of each stage: the waves run
@@ -207,7 +253,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     const int b = blockIdx.x;
     const int wk = (b < per * 8) ? (b % 8) * per + b / 8 : b;
     const int s = wk / qtiles, qt = wk % qtiles;
-    const int64_t rs = row0 + (int64_t)s * split_rows;
+    const int64_t rs = row0 + (int64_t)s * o.split_stride;
     const int64_t re = (rs + split_rows < row1) ? rs + split_rows : row1;
 
     unsigned char *ring = smem;
@@ -218,17 +264,21 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     const int64_t q_first = (int64_t)qt * QT + (RSPLIT ? 0 : wave * NQW);
 
     // ---- owner state (lane q owns query q of this wave) ------------------------------
-    cand_t lst[KCAP];
+    cand_t lst[LK];
     cand_t seedC = 0;
+    // collecting mode: this wave's regions are cbase + query slot * qstride
+    const int SS = S * (RSPLIT ? NW : 1), sub = s * (RSPLIT ? NW : 1) + (RSPLIT ? wave : 0);
+    cand_t *cbase = COLLECT ? o.cbuf + ((size_t)q_first * SS + sub) * o.Cs : nullptr;
+    const size_t qstride = (size_t)SS * o.Cs;
     if (!SEED) {
         const int64_t gq = q_first + lane;
         seedC = (gq < a.nq && a.dry_run == 0) ? (seeds ? seeds[gq] : CAND_NONE) : 0;
         // slots beyond k are pinned to the smallest candidate, so lst[KCAP-1] is the k-th best
 #pragma unroll
-        for (int i = 0; i < KCAP; ++i) lst[i] = (i < KCAP - k) ? 0 : CAND_NONE;
+        for (int i = 0; i < LK; ++i) lst[i] = (i < KCAP - k) ? 0 : CAND_NONE;
         w.thrC[lane] = seedC;
         w.thrE[lane] = thr_e(seedC);
-        w.mbox[lane] = -1;
+        w.mbox[lane] = COLLECT ? 0 : -1;
     }
     wave_lds_sync();
 
@@ -332,7 +382,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
             unsigned long long mask = __ballot(trip);                                                   \
             if (mask) {                                                                                 \
                 if (qcnt + __popcll(mask) > QCAP) { /* no room: this wave drains alone */               \
-                    drain_queue<L2, KCAP>(w, qcnt, re, lane, lst, seedC);                               \
+                    drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);                               \
                     qcnt = 0;                                                                           \
                     _Pragma("unroll") for (int j = 0; j < NB; ++j) thr[j] = w.thrE[j * 32 + col];       \
                     trip = m >= thr[nb];                                                                \
@@ -435,7 +485,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
                     any |= g[0] | g[1] | g[2] | g[3];
                 }
                 if (any) {   // same answer in every wave of the workgroup: drain together
-                    drain_queue<L2, KCAP>(w, qcnt, re, lane, lst, seedC);
+                    drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
                     qcnt = 0;
 #pragma unroll
                     for (int j = 0; j < NB; ++j) thr[j] = w.thrE[j * 32 + col];
@@ -458,36 +508,42 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
 #undef LPQ_BLOCK
 #undef LPQ_FLUSH_SEGMENT
 
-    if (!SEED) {
-        drain_queue<L2, KCAP>(w, qcnt, re, lane, lst, seedC);
-        if constexpr (RSPLIT) {
+    if (COLLECT) {
+        drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
+        wave_lds_sync();
+        const int64_t gq = q_first + lane;
+        if (gq < a.nq) o.ccnt[(size_t)gq * SS + sub] = w.mbox[lane];
+    } else if (!SEED) {
+        drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
+        if constexpr (RSPLIT && KCAP > 0) {
             // The waves hold lists of the SAME 64 queries over different rows: waves 1.. publish
             // theirs in the (now idle) ring and wave 0 folds them into its own.
             cand_t *xl = reinterpret_cast<cand_t *>(ring);
             __syncthreads();
             if (wave > 0) {
 #pragma unroll
-                for (int i = 0; i < KCAP; ++i) xl[((wave - 1) * KCAP + i) * 64 + lane] = lst[i];
+                for (int i = 0; i < LK; ++i) xl[((wave - 1) * LK + i) * 64 + lane] = lst[i];
             }
             __syncthreads();
             if (wave == 0) {
-                for (int i = 0; i < (NW - 1) * KCAP; ++i)   // pinned slots (index % KCAP < KCAP - k) are not candidates
-                    reglist_insert<KCAP>(lst, xl[i * 64 + lane], i % KCAP >= KCAP - k);
+                for (int i = 0; i < (NW - 1) * LK; ++i)   // pinned slots (index % KCAP < KCAP - k) are not candidates
+                    reglist_insert<LK>(lst, xl[i * 64 + lane], i % LK >= LK - k);
             }
         }
         const int64_t gq = q_first + lane;
         if (gq < a.nq && (!RSPLIT || wave == 0)) {
             cand_t *out = lists_out + ((size_t)gq * S + s) * k;
 #pragma unroll
-            for (int i = 0; i < KCAP; ++i)
-                if (i >= KCAP - k) out[i - (KCAP - k)] = lst[i];   // pinned slots are skipped; empty ones are CAND_NONE
+            for (int i = 0; i < LK; ++i)
+                if (i >= LK - k) out[i - (LK - k)] = lst[i];   // pinned slots are skipped; empty ones are CAND_NONE
         }
     }
 }
 
 // One wave per query: the k-th largest of its G group maxima (duplicates counted) becomes the
-// seed threshold.  Each lane keeps E of the values in registers; k times the wave takes the
-// largest value left and the first lane holding it drops one copy.
+// seed threshold.  Each lane keeps E of the values in registers.  Small k: k times the wave takes
+// the largest value left and the first lane holding it drops one copy.  Larger k: bisection on
+// the value with wave-wide counts.
 template <int E>
 __global__ __launch_bounds__(256) void seed_finalize_kernel(const int32_t *__restrict__ gmax, int64_t nq, int G, int k,
                                                             cand_t *__restrict__ seeds)
@@ -502,25 +558,50 @@ __global__ __launch_bounds__(256) void seed_finalize_kernel(const int32_t *__res
         v[e] = (i < G) ? gmax[q * G + i] : INT32_MIN;
     }
     int kth = INT32_MIN;
-    for (int r = 0; r < k; ++r) {
-        int mx = v[0];
+    if (k <= 24) {
+        for (int r = 0; r < k; ++r) {
+            int mx = v[0];
 #pragma unroll
-        for (int e = 1; e < E; ++e) mx = v[e] > mx ? v[e] : mx;
-        int wmx = mx;
+            for (int e = 1; e < E; ++e) mx = v[e] > mx ? v[e] : mx;
+            int wmx = mx;
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                const int t = __shfl_xor(wmx, o, 64);
+                wmx = t > wmx ? t : wmx;
+            }
+            kth = wmx;
+            const int win = __ffsll((unsigned long long)__ballot(mx == wmx)) - 1;
+            bool done = lane != win;
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                const bool hit = !done && v[e] == wmx;
+                v[e] = hit ? INT32_MIN : v[e];
+                done = done || hit;
+            }
+        }
+    } else if (G >= k) {
+        // larger k: bisection on the value; the answer is the largest t with #{v >= t} >= k
+        int mn = v[0], mx = v[0];
+#pragma unroll
+        for (int e = 1; e < E; ++e) {
+            mn = v[e] < mn ? v[e] : mn;
+            mx = v[e] > mx ? v[e] : mx;
+        }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {
-            const int t = __shfl_xor(wmx, o, 64);
-            wmx = t > wmx ? t : wmx;
+            const int a = __shfl_xor(mn, o, 64), b = __shfl_xor(mx, o, 64);
+            mn = a < mn ? a : mn;
+            mx = b > mx ? b : mx;
         }
-        kth = wmx;
-        const int win = __ffsll((unsigned long long)__ballot(mx == wmx)) - 1;
-        bool done = lane != win;
+        long long lo = mn, hi = mx;        // #{v >= lo} = all >= k; the answer lies in [lo, hi]
+        while (lo < hi) {                  // wave-uniform
+            const long long mid = lo + (hi - lo + 1) / 2;
+            int cnt = 0;
 #pragma unroll
-        for (int e = 0; e < E; ++e) {
-            const bool hit = !done && v[e] == wmx;
-            v[e] = hit ? INT32_MIN : v[e];
-            done = done || hit;
+            for (int e = 0; e < E; ++e) cnt += __popcll(__ballot(v[e] >= (int)mid));
+            if (cnt >= k) lo = mid; else hi = mid - 1;
         }
+        kth = (int)lo;
     }
     // at least k items have E >= kth, hence key <= -2 kth
     if (lane == 0) seeds[q] = (G < k || kth == INT32_MIN) ? CAND_NONE : make_cand(-2 * kth, 0xFFFFFFFFu);
@@ -536,11 +617,9 @@ size_t lds_bytes(int ks, bool seed, int nw, bool rsplit)
 }
 
 template <int KS, bool L2, int KCAP, bool SEED, int NW, bool RSPLIT>
-hipError_t launch_nw(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds, cand_t *lists,
-                     int32_t *gmax, int SEG, hipStream_t st)
+hipError_t launch_nw(const SearchArgs &a, int64_t row0, int64_t row1, int S, int64_t split_rows, MfmaIo o, hipStream_t st)
 {
     const int qtiles = (int)ceil_div(a.nq, RSPLIT ? NQW : NW * NQW);
-    const int64_t split_rows = round_up(ceil_div(row1 - row0, S), RSPLIT ? 32 * NW : 64);
     const size_t lds = lds_bytes(KS, SEED, NW, RSPLIT);
     auto kern = search_mfma_kernel<KS, L2, KCAP, SEED, NW, RSPLIT>;
     static bool attr_set = false;  // per instantiation
@@ -550,7 +629,7 @@ hipError_t launch_nw(const SearchArgs &a, int64_t row0, int64_t row1, int S, con
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    kern<<<(unsigned)(qtiles * S), NW * 64, lds, st>>>(a, row0, row1, S, split_rows, qtiles, seeds, lists, gmax, SEG);
+    kern<<<(unsigned)(qtiles * S), NW * 64, lds, st>>>(a, row0, row1, S, split_rows, qtiles, o);
     return hipGetLastError();
 }
 
@@ -558,41 +637,44 @@ hipError_t launch_nw(const SearchArgs &a, int64_t row0, int64_t row1, int S, con
 // CU, half the corpus bytes per contraction) measured slower: the wider barrier costs more than
 // the saved L1 traffic.
 template <int KS, bool L2, int KCAP, bool SEED>
-hipError_t launch_one(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds, cand_t *lists,
-                      int32_t *gmax, int SEG, hipStream_t st)
+hipError_t launch_one(const SearchArgs &a, int64_t row0, int64_t row1, int S, MfmaIo o, hipStream_t st)
 {
+    // rows of a split: a whole number of stages; splits follow each other unless a stride is given
+    const int64_t split_rows = o.split_stride ? o.split_stride_rows : round_up(ceil_div(row1 - row0, S), a.rsplit ? 128 : 64);
+    if (!o.split_stride) o.split_stride = split_rows;
     if constexpr (KS <= 4) {
-        if (a.rsplit) return launch_nw<KS, L2, KCAP, SEED, 4, true>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
+        if (a.rsplit) return launch_nw<KS, L2, KCAP, SEED, 4, true>(a, row0, row1, S, split_rows, o, st);
     }
-    return launch_nw<KS, L2, KCAP, SEED, 4, false>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
+    return launch_nw<KS, L2, KCAP, SEED, 4, false>(a, row0, row1, S, split_rows, o, st);
 }
 
 template <int KS>
-hipError_t launch_ks(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds, cand_t *lists,
-                     int32_t *gmax, int SEG, hipStream_t st)
+hipError_t launch_ks(const SearchArgs &a, int64_t row0, int64_t row1, int S, const MfmaIo &o, hipStream_t st)
 {
     const bool l2 = a.metric == LPQ_METRIC_L2SQ;
-    if (gmax)
-        return l2 ? launch_one<KS, true, 1, true>(a, row0, row1, S, seeds, lists, gmax, SEG, st)
-                  : launch_one<KS, false, 1, true>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
+    if (o.gmax)
+        return l2 ? launch_one<KS, true, 1, true>(a, row0, row1, S, o, st)
+                  : launch_one<KS, false, 1, true>(a, row0, row1, S, o, st);
+    if (o.cbuf)
+        return l2 ? launch_one<KS, true, 0, false>(a, row0, row1, S, o, st)
+                  : launch_one<KS, false, 0, false>(a, row0, row1, S, o, st);
     if (a.k <= 10)
-        return l2 ? launch_one<KS, true, 10, false>(a, row0, row1, S, seeds, lists, gmax, SEG, st)
-                  : launch_one<KS, false, 10, false>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
-    return l2 ? launch_one<KS, true, 16, false>(a, row0, row1, S, seeds, lists, gmax, SEG, st)
-              : launch_one<KS, false, 16, false>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
+        return l2 ? launch_one<KS, true, 10, false>(a, row0, row1, S, o, st)
+                  : launch_one<KS, false, 10, false>(a, row0, row1, S, o, st);
+    return l2 ? launch_one<KS, true, 16, false>(a, row0, row1, S, o, st)
+              : launch_one<KS, false, 16, false>(a, row0, row1, S, o, st);
 }
 
-hipError_t launch_any(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds, cand_t *lists,
-                      int32_t *gmax, int SEG, hipStream_t st)
+hipError_t launch_any(const SearchArgs &a, int64_t row0, int64_t row1, int S, const MfmaIo &o, hipStream_t st)
 {
     if (a.nq <= 0 || row1 <= row0) return hipSuccess;
-    if (row0 % 128) return hipErrorInvalidValue;  // stages and parity words cover aligned blocks
+    if (row0 % 128 || o.split_stride % 128) return hipErrorInvalidValue;  // stages and parity words cover aligned blocks
     switch (a.d_pad / 32) {
-    case 2: return launch_ks<2>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
-    case 3: return launch_ks<3>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
-    case 4: return launch_ks<4>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
-    case 6: return launch_ks<6>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
-    case 8: return launch_ks<8>(a, row0, row1, S, seeds, lists, gmax, SEG, st);
+    case 2: return launch_ks<2>(a, row0, row1, S, o, st);
+    case 3: return launch_ks<3>(a, row0, row1, S, o, st);
+    case 4: return launch_ks<4>(a, row0, row1, S, o, st);
+    case 6: return launch_ks<6>(a, row0, row1, S, o, st);
+    case 8: return launch_ks<8>(a, row0, row1, S, o, st);
     default: return hipErrorInvalidValue;
     }
 }
@@ -612,14 +694,31 @@ bool mfma_row_split(int64_t nq, int d_pad) { return nq <= 64 && d_pad <= 128; }
 
 bool mfma_reg_supported(int d_pad, int k) { return shape_ok(d_pad) && k >= 1 && k <= 16; }
 
+bool mfma_collect_supported(int d_pad, int k) { return shape_ok(d_pad) && k >= 1 && k <= 128; }
+
 bool mfma_supported(int d_pad, int k) { return mfma_reg_supported(d_pad, k) || mfma_lds_supported(d_pad, k); }
 
 hipError_t launch_search_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds,
                               cand_t *lists, hipStream_t st)
 {
-    if (mfma_reg_supported(a.d_pad, a.k)) return launch_any(a, row0, row1, S, seeds, lists, nullptr, 0, st);
+    if (mfma_reg_supported(a.d_pad, a.k)) {
+        MfmaIo o = {};
+        o.seeds = seeds; o.lists = lists;
+        return launch_any(a, row0, row1, S, o, st);
+    }
     return launch_search_mfma_lds(a, row0, row1, S, seeds, lists, st);
 }
+
+hipError_t launch_collect_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds,
+                               cand_t *cbuf, int32_t *ccnt, int Cs, hipStream_t st)
+{
+    if (!mfma_collect_supported(a.d_pad, a.k) || !seeds || !cbuf || !ccnt || Cs < 1) return hipErrorInvalidValue;
+    MfmaIo o = {};
+    o.seeds = seeds; o.cbuf = cbuf; o.ccnt = ccnt; o.Cs = Cs;
+    return launch_any(a, row0, row1, S, o, st);
+}
+
+int mfma_collect_regions(int S, bool rsplit) { return S * (rsplit ? 4 : 1); }
 
 int mfma_seed_groups(int S, int SEG, bool rsplit) { return 2 * S * SEG * (rsplit ? 4 : 1); }
 
@@ -632,11 +731,19 @@ int mfma_seed_segments(int S, int k, bool rsplit)
     return seg;
 }
 
+// The seeding pass reads S chunks of `chunk_rows` rows whose first rows are `stride` apart
+// (stride = 0: one contiguous range), so the sample is spread over the corpus.
 hipError_t launch_seed_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S, int SEG, int32_t *gmax,
-                            hipStream_t st)
+                            hipStream_t st, int64_t stride, int64_t chunk_rows)
 {
-    if (!mfma_reg_supported(a.d_pad, a.k) || !gmax) return hipErrorInvalidValue;
-    return launch_any(a, row0, row1, S, nullptr, nullptr, gmax, SEG, st);
+    if (!mfma_collect_supported(a.d_pad, a.k) || !gmax) return hipErrorInvalidValue;
+    MfmaIo o = {};
+    o.gmax = gmax; o.SEG = SEG;
+    if (stride) {
+        if (chunk_rows <= 0 || chunk_rows > stride || chunk_rows % 128) return hipErrorInvalidValue;
+        o.split_stride = stride; o.split_stride_rows = chunk_rows;
+    }
+    return launch_any(a, row0, row1, S, o, st);
 }
 
 hipError_t launch_seed_finalize(const int32_t *gmax, int64_t nq, int G, int k, cand_t *seeds, hipStream_t st)

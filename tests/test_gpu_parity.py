@@ -138,7 +138,10 @@ def _run_search_case(lpq, oracle, w, k, metric, mode, scope, path, nq=None, thre
     return idx, gq, ids, dists
 
 
-PATHS = [1, 2]   # generic kernel, matrix-core kernel (falls back when a shape is unsupported)
+# generic kernel; matrix-core kernels (built-in choice of variant); collecting variant wherever it
+# applies; matrix-core kernels without the collecting variant.  Each falls back when a shape is
+# unsupported.
+PATHS = [1, 2, 3, 4]
 
 
 @pytest.mark.parametrize("path", PATHS)
@@ -161,6 +164,51 @@ def test_search_parity_shapes(lpq, oracle, path, name, n, nq, k, metric, mode, s
     base = {"skewed": synth.SKEWED_1M, "aniso": synth.ANISO_1M2, "scaled": synth.SCALED_10M,
             "product": synth.PRODUCT_100M, "tiny": synth.TINY}[name]
     _run_search_case(lpq, oracle, base.scaled(n=n, nq=nq), k, metric, mode, scope, path)
+
+
+@pytest.mark.parametrize("path", [2, 3])
+@pytest.mark.parametrize("name,n,nq,k,metric,mode,scope", [
+    ("skewed", 200_003, 300, 100, "l2sq", "minmax", "global"),        # d = 128, ragged tail
+    ("skewed", 150_000, 5, 17, "l2sq", "minmax", "per_feature"),      # few queries: row-split workgroups
+    ("aniso", 160_000, 70, 128, "ip", "absmax", "global"),            # d = 100, largest k of the variant
+    ("scaled", 140_000, 257, 50, "l2sq", "absmax", "global"),         # d = 96
+    ("product", 135_000, 33, 100, "ip", "absmax", "per_feature"),     # d = 256
+    ("skewed", 131_072, 64, 10, "l2sq", "minmax", "global"),          # small k through the same variant
+])
+def test_search_collecting_variant(lpq, oracle, path, name, n, nq, k, metric, mode, scope):
+    """Corpora large enough for a seeding sample: larger k goes through the collecting scan
+    (fixed per-query thresholds, candidates gathered in global memory, one selection per query)."""
+    base = {"skewed": synth.SKEWED_1M, "aniso": synth.ANISO_1M2, "scaled": synth.SCALED_10M,
+            "product": synth.PRODUCT_100M}[name]
+    _run_search_case(lpq, oracle, base.scaled(n=n, nq=nq), k, metric, mode, scope, path)
+
+
+def test_search_collecting_variant_overflow_is_redone_exactly(lpq, oracle):
+    """A seeding sample far too small for k = 100 lets more candidates through than a query's
+    regions hold; those queries must come back exact from the generic kernel."""
+    lpq.set_tuning(lpq.TUNE_SEED_ROWS, 8192)
+    try:
+        _run_search_case(lpq, oracle, synth.SKEWED_1M.scaled(n=400_000, nq=40), 100, "l2sq", "minmax", "global", 3)
+        _run_search_case(lpq, oracle, synth.ANISO_1M2.scaled(n=400_000, nq=300), 100, "ip", "absmax", "global", 3)
+    finally:
+        lpq.set_tuning(lpq.TUNE_SEED_ROWS, 0)
+
+
+def test_search_collecting_variant_ties_at_the_threshold(lpq, oracle):
+    """4-bit codes in 32 dimensions: many items share the threshold distance and all of them are
+    collected; the selection must still order by (distance, id)."""
+    w = synth.SKEWED_1M.scaled(n=200_000, nq=70)
+    x, q = w.corpus("cuda")[:, :32].contiguous(), w.queries("cuda")[:, :32].contiguous()
+    # d = 32 is padded to 64
+    gq = lpq.Quantizer(32, 4).calibrate(x, "minmax", "global")
+    idx = lpq.Index(gq, w.n).add_f32(x)
+    oq = _oracle_quant(oracle, gq)
+    oc, oqc = oq.encode(x.cpu().numpy()), oq.encode(q.cpu().numpy())
+    for metric in ("l2sq", "ip"):
+        ids, dists = idx.search(q, 100, metric)
+        oids, odists = oracle.search_i8(oc, oqc, 100, metric, threads=16)
+        assert np.array_equal(dists.cpu().numpy(), odists)
+        assert np.array_equal(ids.cpu().numpy(), oids)
 
 
 @pytest.mark.parametrize("nq", [1, 7, 64, 65])
