@@ -79,7 +79,7 @@ def test_config2_skewed_1m_x128_k10(lpq, oracle):
 
 
 def test_config2_skewed_1m_x128_k100_per_feature(lpq, oracle):
-    _full_case(lpq, oracle, synth.SKEWED_1M.scaled(nq=2000), 100, "minmax", "per_feature", sample=32)
+    _full_case(lpq, oracle, synth.SKEWED_1M.scaled(nq=2000), 100, "minmax", "per_feature", sample=32, batches=(1, 16, 300))
 
 
 def test_config3_aniso_1m2_x100_ip(lpq, oracle):
