@@ -156,8 +156,12 @@ int lpq_search_f32(const float *x_dev, int64_t n, int64_t ldx, const float *q_de
  *                        -1 = no seeding pass)
  *   LPQ_TUNE_DRY_RUN     1 = the matrix-core kernel never collects a candidate (timing of
  *                        the bare contraction only; the results are then meaningless)
- * Results never depend on the first three. */
-enum { LPQ_TUNE_PATH = 0, LPQ_TUNE_SPLITS = 1, LPQ_TUNE_SEED_ROWS = 2, LPQ_TUNE_DRY_RUN = 3, LPQ_TUNE_COUNT_ = 4 };
+ *   LPQ_TUNE_WORK_ORDER  how workgroups of the matrix-core kernel are dealt to (split, query tile)
+ *                        pairs: 0 built-in, 1 each XCD takes whole splits, 2 each XCD takes whole
+ *                        query tiles, 3 plain block order
+ * Results never depend on PATH, SPLITS, SEED_ROWS or WORK_ORDER. */
+enum { LPQ_TUNE_PATH = 0, LPQ_TUNE_SPLITS = 1, LPQ_TUNE_SEED_ROWS = 2, LPQ_TUNE_DRY_RUN = 3, LPQ_TUNE_WORK_ORDER = 4,
+       LPQ_TUNE_COUNT_ = 5 };
 int lpq_set_tuning(int key, int64_t value);
 
 /* Kernel timing for benchmarks.  While enabled, every launch of the contraction/top-k

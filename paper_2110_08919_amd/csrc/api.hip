@@ -34,7 +34,7 @@ static int fail(int code, const char *fmt, ...)
 extern "C" const char *lpq_last_error(void) { return g_err; }
 
 // ------------------------------------------------------------------------ tuning ----
-static int64_t g_tune[LPQ_TUNE_COUNT_] = {0, 0, 0, 0};
+static int64_t g_tune[LPQ_TUNE_COUNT_] = {0, 0, 0, 0, 0};
 
 extern "C" int lpq_set_tuning(int key, int64_t value)
 {
@@ -362,13 +362,16 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     int64_t seed = 0;
     if (g_tune[LPQ_TUNE_SEED_ROWS] > 0) seed = g_tune[LPQ_TUNE_SEED_ROWS];
     else if (g_tune[LPQ_TUNE_SEED_ROWS] == 0 && p.mode != PLAN_GENERIC) {
-        seed = gm ? n / 16 : n / 64;
-        if (p.mode == PLAN_MFMA_COLLECT) {   // measured optimum: the sample grows with k, n/16 .. n/4
-            const int64_t by_k = n / 400 * k;
-            seed = by_k < n / 16 ? n / 16 : (by_k > n / 4 ? n / 4 : by_k);
-        }
-        const int64_t lo = gm ? 8192 : 4096, hi = p.mode == PLAN_MFMA_COLLECT ? n : (gm ? 65536 : 32768);
+        // Few queries: the scan is bound by corpus bytes, so the sample stays small.  Otherwise a
+        // larger sample pays for itself through fewer candidates in the main pass (measured).
+        const bool few = gm && mfma_row_split(nq, idx->d_pad);
+        seed = gm ? (few ? n / 16 : n / 8) : n / 64;
+        const int64_t lo = gm ? 8192 : 4096, hi = p.mode == PLAN_MFMA_COLLECT ? n : (gm ? (few ? 65536 : 131072) : 32768);
         seed = seed < lo ? lo : (seed > hi ? hi : seed);
+        if (p.mode == PLAN_MFMA_COLLECT) {   // no tightening during the scan: the sample grows with k, n/8 .. n/4
+            const int64_t by_k = n / 400 * k, least = few ? n / 16 : n / 8, most = few ? n / 8 : n / 4;
+            seed = by_k < least ? least : (by_k > most ? most : by_k);
+        }
     }
     seed = seed / 256 * 256;
     if (seed < 64 * k || seed * 4 > n) seed = 0;
@@ -473,6 +476,7 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k
     a.qcodes = reinterpret_cast<const int8_t *>(ws + p.off_qcodes);
     a.nq = nq; a.k = k; a.metric = metric;
     a.dry_run = (int)g_tune[LPQ_TUNE_DRY_RUN];
+    a.work_order = (int)g_tune[LPQ_TUNE_WORK_ORDER];
     a.rsplit = p.rsplit;
     const int32_t *qnorms = reinterpret_cast<const int32_t *>(ws + p.off_qnorms);
     cand_t *lists1 = reinterpret_cast<cand_t *>(ws + p.off_lists1);

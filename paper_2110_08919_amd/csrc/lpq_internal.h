@@ -102,6 +102,7 @@ struct SearchArgs {
     int metric;
     bool rsplit;            // register variant: row-split workgroups (set from mfma_row_split)
     int dry_run;            // timing experiments: != 0 never collects a candidate (2..4: ablations)
+    int work_order = 0;     // matrix-core kernels: block -> (split, query tile) mapping (0 = built-in)
 };
 
 // Generic kernel: one workgroup per (query, corpus split); any d_pad (multiple of 32), any k.

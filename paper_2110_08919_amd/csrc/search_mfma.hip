@@ -64,16 +64,14 @@ struct MfmaIo {     // what a launch reads and writes besides the corpus and the
 struct WaveQ {      // pointers into the wave's private LDS region
     cand_t *thrC;   // [NQW] exact threshold candidate per query
     cand_t *svc;    // [SVCAP] compacted candidates
-    int *qvals;     // [16][QCAP] accumulator r of dump s at qvals[r * QCAP + s]
-    int *qrow;      // [QCAP] first row of the 32-row block the dump came from
-    unsigned *qpar; // [QCAP] parity word of that block
-    int *qmeta;     // [QCAP] query slot | lane half << 8
+    int *qvals;     // [QCAP][16] the 16 accumulators of dump s at qvals[16 s ..]
+    v4i *qmeta;     // [QCAP] (first row of the dump's 32-row block, its parity word, query slot | lane half << 8, -)
     int *thrE;      // [NQW] conservative threshold on E
     int *mbox;      // [NQW] lane whose candidate the owner takes this round, or -1 (collecting mode: region fill)
     int *svq;       // [SVCAP] query slot of each compacted candidate
 };
 
-constexpr size_t WAVEQ_BYTES = NQW * 8 + SVCAP * 8 + QCAP * 16 * 4 + QCAP * 12 + NQW * 8 + SVCAP * 4;
+constexpr size_t WAVEQ_BYTES = NQW * 8 + SVCAP * 8 + QCAP * 16 * 4 + QCAP * 16 + NQW * 8 + SVCAP * 4;
 
 __device__ __forceinline__ WaveQ carve_waveq(unsigned char *p)
 {
@@ -81,9 +79,7 @@ __device__ __forceinline__ WaveQ carve_waveq(unsigned char *p)
     w.thrC = (cand_t *)p;    p += NQW * 8;
     w.svc = (cand_t *)p;     p += SVCAP * 8;
     w.qvals = (int *)p;      p += QCAP * 16 * 4;
-    w.qrow = (int *)p;       p += QCAP * 4;
-    w.qpar = (unsigned *)p;  p += QCAP * 4;
-    w.qmeta = (int *)p;      p += QCAP * 4;
+    w.qmeta = (v4i *)p;      p += QCAP * 16;
     w.thrE = (int *)p;       p += NQW * 4;
     w.mbox = (int *)p;       p += NQW * 4;
     w.svq = (int *)p;
@@ -172,17 +168,22 @@ __device__ __forceinline__ void drain_queue(const WaveQ &w, int qcnt, int64_t ro
     if (lg > 6) lg = 6;
     const int d = lane & ((1 << lg) - 1), rsub = lane >> lg, rstep = 64 >> lg;
     const bool live = d < qcnt;
-    const int meta = live ? w.qmeta[d] : 0;
+    v4i m4 = {0, 0, 0, 0};
+    if (live) m4 = w.qmeta[d];
+    const int meta = m4[2];
     const int ql = meta & 255, hf = meta >> 8;
-    const int rbase = live ? w.qrow[d] : 0;
-    const unsigned pw = (L2 && live) ? w.qpar[d] : 0u;
+    const int rbase = m4[0];
+    const unsigned pw = L2 ? (unsigned)m4[1] : 0u;
+    // A lane walks the accumulators of its dump starting from a dump-dependent index, so that the
+    // lanes of one step (dumps 64 bytes apart) fall on different banks.
+    const int rot = (d >> 2) * rstep;
     int svcnt = 0;
     for (int r0 = 0; r0 < 16; r0 += rstep) {
-        const int r = r0 + rsub;
-        bool pass = live && r < 16;
+        const int r = (r0 + rsub + rot) & 15;
+        bool pass = live && rsub < 16;
         cand_t c = 0;
         if (pass) {
-            const int e = w.qvals[r * QCAP + d];
+            const int e = w.qvals[d * 16 + r];
             pass = e >= w.thrE[ql];
             if (pass) {
                 const int off = 8 * (r >> 2) + 4 * hf + (r & 3);
@@ -251,8 +252,9 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     const int total = qtiles * S;
     const int per = total / 8;
     const int b = blockIdx.x;
-    const int wk = (b < per * 8) ? (b % 8) * per + b / 8 : b;
-    const int s = wk / qtiles, qt = wk % qtiles;
+    const int wk = (a.work_order != 3 && b < per * 8) ? (b % 8) * per + b / 8 : b;
+    const int s = (a.work_order == 2) ? wk % S : wk / qtiles;
+    const int qt = (a.work_order == 2) ? wk / S : wk % qtiles;
     const int64_t rs = row0 + (int64_t)s * o.split_stride;
     const int64_t re = (rs + split_rows < row1) ? rs + split_rows : row1;
 
@@ -272,7 +274,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     const size_t qstride = (size_t)SS * o.Cs;
     if (!SEED) {
         const int64_t gq = q_first + lane;
-        seedC = (gq < a.nq && a.dry_run == 0) ? (seeds ? seeds[gq] : CAND_NONE) : 0;
+        seedC = (gq < a.nq && (a.dry_run == 0 || a.dry_run >= 5)) ? (seeds ? seeds[gq] : CAND_NONE) : 0;
         // slots beyond k are pinned to the smallest candidate, so lst[KCAP-1] is the k-th best
 #pragma unroll
         for (int i = 0; i < LK; ++i) lst[i] = (i < KCAP - k) ? 0 : CAND_NONE;
@@ -382,7 +384,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
             unsigned long long mask = __ballot(trip);                                                   \
             if (mask) {                                                                                 \
                 if (qcnt + __popcll(mask) > QCAP) { /* no room: this wave drains alone */               \
-                    drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);                               \
+                    if (a.dry_run < 5) drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs); \
                     qcnt = 0;                                                                           \
                     _Pragma("unroll") for (int j = 0; j < NB; ++j) thr[j] = w.thrE[j * 32 + col];       \
                     trip = m >= thr[nb];                                                                \
@@ -391,12 +393,12 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
                 if (mask) {                                                                             \
                     const int below = __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),                 \
                                                                 __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u)); \
-                    if (trip) {                                                                         \
+                    if (trip && a.dry_run != 5) {   /* 5: trips are counted but nothing is stored */    \
                         const int slot = qcnt + below;                                                  \
-                        _Pragma("unroll") for (int r = 0; r < 16; ++r) w.qvals[r * QCAP + slot] = v[r]; \
-                        w.qrow[slot] = rowbase;                                                         \
-                        w.qpar[slot] = PREG;                                                            \
-                        w.qmeta[slot] = (nb * 32 + col) | (half << 8);                                  \
+                        v4i *dst_ = reinterpret_cast<v4i *>(w.qvals + slot * 16);                       \
+                        _Pragma("unroll") for (int g = 0; g < 4; ++g)                                   \
+                            dst_[g] = v4i{v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};          \
+                        w.qmeta[slot] = v4i{rowbase, (int)PREG, (nb * 32 + col) | (half << 8), 0};      \
                     }                                                                                   \
                     qcnt += __popcll(mask);                                                             \
                 }                                                                                       \
@@ -456,7 +458,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
         v4i A0[KS], A1[KS];
         v16i C0, C1;
         unsigned P0 = 0, P1 = 0;
-        const bool abl_nodma = a.dry_run >= 3, abl_nobar = a.dry_run == 2 || a.dry_run == 4;   // timing ablations
+        const bool abl_nodma = a.dry_run == 3 || a.dry_run == 4, abl_nobar = a.dry_run == 2 || a.dry_run == 4;   // timing ablations
         const int primed = T < NST ? T : NST;
         if (!abl_nodma) for (int st = 0; st < primed; ++st) LPQ_ISSUE(st);
         if (T > 0) {
@@ -485,7 +487,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
                     any |= g[0] | g[1] | g[2] | g[3];
                 }
                 if (any) {   // same answer in every wave of the workgroup: drain together
-                    drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
+                    if (a.dry_run < 5) drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
                     qcnt = 0;
 #pragma unroll
                     for (int j = 0; j < NB; ++j) thr[j] = w.thrE[j * 32 + col];
@@ -509,12 +511,12 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
 #undef LPQ_FLUSH_SEGMENT
 
     if (COLLECT) {
-        drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
+        if (a.dry_run < 5) drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
         wave_lds_sync();
         const int64_t gq = q_first + lane;
         if (gq < a.nq) o.ccnt[(size_t)gq * SS + sub] = w.mbox[lane];
     } else if (!SEED) {
-        drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
+        if (a.dry_run < 5) drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
         if constexpr (RSPLIT && KCAP > 0) {
             // The waves hold lists of the SAME 64 queries over different rows: waves 1.. publish
             // theirs in the (now idle) ring and wave 0 folds them into its own.
