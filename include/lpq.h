@@ -155,7 +155,11 @@ int lpq_search_f32(const float *x_dev, int64_t n, int64_t ldx, const float *q_de
  *   LPQ_TUNE_SEED_ROWS   rows of the threshold-seeding pass (0 = built-in choice,
  *                        -1 = no seeding pass)
  *   LPQ_TUNE_DRY_RUN     1 = the matrix-core kernel never collects a candidate (timing of
- *                        the bare contraction only; the results are then meaningless)
+ *                        the bare contraction only; the results are then meaningless).
+ *                        Further timing ablations, results equally meaningless: 2 no workgroup
+ *                        barrier, 3 no corpus copies, 4 neither, 5 candidates are detected but
+ *                        neither queued nor processed, 6 queued but not processed.  Meant for
+ *                        k <= 16 (for larger k every query then falls to the generic kernel).
  *   LPQ_TUNE_WORK_ORDER  how workgroups of the matrix-core kernel are dealt to (split, query tile)
  *                        pairs: 0 built-in, 1 each XCD takes whole splits, 2 each XCD takes whole
  *                        query tiles, 3 plain block order
@@ -165,11 +169,15 @@ enum { LPQ_TUNE_PATH = 0, LPQ_TUNE_SPLITS = 1, LPQ_TUNE_SEED_ROWS = 2, LPQ_TUNE_
 int lpq_set_tuning(int key, int64_t value);
 
 /* Kernel timing for benchmarks.  While enabled, every launch of the contraction/top-k
- * kernel of lpq_search* is bracketed by a pair of HIP events on the launch stream.
+ * kernel of lpq_search* (LPQ_PROFILE_SCAN) and of its threshold-seeding pass
+ * (LPQ_PROFILE_SEED) is bracketed by a pair of HIP events on the launch stream.
  * lpq_profile_read synchronises those events and returns the number of bracketed
- * launches and their summed duration in milliseconds since the last enable. */
+ * launches and their summed duration in milliseconds since the last enable;
+ * lpq_profile_read_kind does the same for one kind of launch. */
+enum { LPQ_PROFILE_SCAN = 0, LPQ_PROFILE_SEED = 1 };
 int lpq_profile_enable(int on);
 int lpq_profile_read(int64_t *launches, double *total_ms);
+int lpq_profile_read_kind(int kind, int64_t *launches, double *total_ms);
 
 /* Message of the last error on the calling thread ("" if none). */
 const char *lpq_last_error(void);

@@ -48,19 +48,21 @@ namespace {
 struct Profile {
     std::mutex mu;
     bool on = false;
-    std::vector<std::pair<hipEvent_t, hipEvent_t>> spans;
+    struct Span { hipEvent_t a, b; int kind; };
+    std::vector<Span> spans;
     void clear()
     {
-        for (auto &s : spans) { (void)hipEventDestroy(s.first); (void)hipEventDestroy(s.second); }
+        for (auto &s : spans) { (void)hipEventDestroy(s.a); (void)hipEventDestroy(s.b); }
         spans.clear();
     }
 };
 Profile g_prof;
 
-struct KernelSpan {  // brackets the main search kernel with two events while profiling is on
+struct KernelSpan {  // brackets one kernel launch with two events while profiling is on
     hipEvent_t a = nullptr, b = nullptr;
     hipStream_t st;
-    explicit KernelSpan(hipStream_t s) : st(s)
+    int kind;
+    explicit KernelSpan(hipStream_t s, int kind_ = LPQ_PROFILE_SCAN) : st(s), kind(kind_)
     {
         std::lock_guard<std::mutex> l(g_prof.mu);
         if (!g_prof.on) return;
@@ -72,7 +74,7 @@ struct KernelSpan {  // brackets the main search kernel with two events while pr
         if (!a) return;
         (void)hipEventRecord(b, st);
         std::lock_guard<std::mutex> l(g_prof.mu);
-        g_prof.spans.emplace_back(a, b);
+        g_prof.spans.push_back({a, b, kind});
     }
 };
 }  // namespace
@@ -85,20 +87,31 @@ extern "C" int lpq_profile_enable(int on)
     return LPQ_OK;
 }
 
-extern "C" int lpq_profile_read(int64_t *launches, double *total_ms)
+static int profile_sum(int kind, int64_t *launches, double *total_ms)
 {
     if (!launches || !total_ms) return fail(LPQ_EINVAL, "null output");
     std::lock_guard<std::mutex> l(g_prof.mu);
     double tot = 0.0;
+    int64_t cnt = 0;
     for (auto &s : g_prof.spans) {
-        HIP_TRY(hipEventSynchronize(s.second));
+        if (kind >= 0 && s.kind != kind) continue;
+        HIP_TRY(hipEventSynchronize(s.b));
         float ms = 0.f;
-        HIP_TRY(hipEventElapsedTime(&ms, s.first, s.second));
+        HIP_TRY(hipEventElapsedTime(&ms, s.a, s.b));
         tot += ms;
+        ++cnt;
     }
-    *launches = (int64_t)g_prof.spans.size();
+    *launches = cnt;
     *total_ms = tot;
     return LPQ_OK;
+}
+
+extern "C" int lpq_profile_read(int64_t *launches, double *total_ms) { return profile_sum(-1, launches, total_ms); }
+
+extern "C" int lpq_profile_read_kind(int kind, int64_t *launches, double *total_ms)
+{
+    if (kind != LPQ_PROFILE_SCAN && kind != LPQ_PROFILE_SEED) return fail(LPQ_EINVAL, "unknown kernel kind %d", kind);
+    return profile_sum(kind, launches, total_ms);
 }
 
 // --------------------------------------------------------------------- quantizer ----
@@ -503,7 +516,7 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k
     };
     auto seed_pass = [&]() -> hipError_t {
         {
-            KernelSpan span(st);
+            KernelSpan span(st, LPQ_PROFILE_SEED);
             hipError_t e = p.seed_stride ? launch_seed_mfma(a, 0, a.n, p.S1, p.SEG, gmax, st, p.seed_stride, p.seed_chunk)
                                          : launch_seed_mfma(a, 0, p.seed_rows, p.S1, p.SEG, gmax, st);
             if (e != hipSuccess) return e;

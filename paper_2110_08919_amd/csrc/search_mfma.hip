@@ -466,6 +466,10 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
             __syncthreads();
             LPQ_LOAD_BLOCK(0, 0, A0, C0, P0);
         }
+        // Drain requests are acted on one stage late: the flags written before the barrier of
+        // stage t are read right after it, but only looked at after the barrier of stage t + 1, so
+        // the LDS round trip is off the critical path (the queue keeps room for that extra stage).
+        v4i fl0 = {0, 0, 0, 0}, fl1 = {0, 0, 0, 0};
         for (int t = 0; t < T; ++t) {
             LPQ_LOAD_BLOCK(t, 1, A1, C1, P1);
             LPQ_BLOCK(t, 0, A0, C0, P0);
@@ -480,12 +484,10 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
             if (!abl_nobar) __syncthreads();
             if (t + NST < T && !abl_nodma) LPQ_ISSUE(t + NST);   // refills the slot of stage t
             if (!SEED) {
-                const v4i f = *reinterpret_cast<const v4i *>(flags + (t & 1) * 8);
-                int any = f[0] | f[1] | f[2] | f[3];
-                if (NW > 4) {
-                    const v4i g = *reinterpret_cast<const v4i *>(flags + (t & 1) * 8 + 4);
-                    any |= g[0] | g[1] | g[2] | g[3];
-                }
+                int any = fl0[0] | fl0[1] | fl0[2] | fl0[3];
+                if (NW > 4) any |= fl1[0] | fl1[1] | fl1[2] | fl1[3];
+                fl0 = *reinterpret_cast<const v4i *>(flags + (t & 1) * 8);
+                if (NW > 4) fl1 = *reinterpret_cast<const v4i *>(flags + (t & 1) * 8 + 4);
                 if (any) {   // same answer in every wave of the workgroup: drain together
                     if (a.dry_run < 5) drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
                     qcnt = 0;

@@ -67,6 +67,7 @@ def lib() -> C.CDLL:
             "lpq_set_tuning": (i32, [i32, i64]),
             "lpq_profile_enable": (i32, [i32]),
             "lpq_profile_read": (i32, [C.POINTER(i64), C.POINTER(C.c_double)]),
+            "lpq_profile_read_kind": (i32, [i32, C.POINTER(i64), C.POINTER(C.c_double)]),
             "lpq_last_error": (C.c_char_p, []),
         }
         for name, (res, args) in sig.items():
@@ -103,9 +104,16 @@ def profile_enable(on: bool):
     _check(lib().lpq_profile_enable(1 if on else 0))
 
 
-def profile_read():
+PROFILE_SCAN, PROFILE_SEED = 0, 1
+
+
+def profile_read(kind=None):
+    """(launches, total ms) of all bracketed launches, or of one kind (PROFILE_SCAN / PROFILE_SEED)."""
     n, ms = C.c_int64(0), C.c_double(0.0)
-    _check(lib().lpq_profile_read(C.byref(n), C.byref(ms)))
+    if kind is None:
+        _check(lib().lpq_profile_read(C.byref(n), C.byref(ms)))
+    else:
+        _check(lib().lpq_profile_read_kind(kind, C.byref(n), C.byref(ms)))
     return n.value, ms.value
 
 
