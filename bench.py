@@ -20,10 +20,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_INT8_OPS = 5.0e15      # MI355X dense int8 matrix peak, op/s
 PEAK_HBM = 8.0e12           # MI355X HBM3E, B/s
-# HBM bytes of one search of the default workload (seeding pass + main scan), from the rocprofv3
+# HBM bytes of one launch of the main scan kernel on the default workload, from the rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/search_mfma_kernel_skewed_int_1m_x128_pmc.txt
-# (FETCH_SIZE scaled by 2.000, WRITE_SIZE by 1.000 against a 512 MiB copy in the same run).
-TRAFFIC_BYTES_DEFAULT_WORKLOAD = 273.5e6
+# (FETCH_SIZE scaled by 2.000, WRITE_SIZE by 1.000 against device copies of known size in the same run).
+TRAFFIC_BYTES_DEFAULT_WORKLOAD = 227.2e6
 
 
 def cpu_baseline(oracle, x_host, q_host, params, k, metric, gpu_ids, gpu_dists, sample):
