@@ -22,6 +22,7 @@ int calib_blocks(int d)
 struct CalibScratch {
     float *pmn, *pmx;   // [G][d]
     double *psum;       // [G][d]  (pass 1: sum x; pass 2: sum (x - mu)^2)
+    double *csum, *css; // [d] column totals of the two passes
     double *mu;         // [d]
     float *mn, *mx;     // [d]
 };
@@ -32,6 +33,8 @@ CalibScratch carve(void *scratch, int d)
     char *p = (char *)scratch;
     CalibScratch s;
     s.psum = (double *)p; p += sizeof(double) * G * d;
+    s.csum = (double *)p; p += sizeof(double) * d;
+    s.css = (double *)p;  p += sizeof(double) * d;
     s.mu = (double *)p;   p += sizeof(double) * d;
     s.pmn = (float *)p;   p += sizeof(float) * G * d;
     s.pmx = (float *)p;   p += sizeof(float) * G * d;
@@ -130,44 +133,67 @@ __device__ inline float block_min(float v, float *sh)
     return r;
 }
 
-// Pass-1 finalisation: reduce the block partials per column; GLOBAL scope pools all columns.
+// Column totals of the G block partials: one workgroup per 64 columns, its 16 waves share the
+// G partial rows and combine through LDS.  pmn / pmx may be null (second pass: sums only).
+constexpr int COL_WAVES = 16;
+__global__ __launch_bounds__(COL_WAVES * 64) void calib_colreduce_kernel(
+    int G, int d, const float *__restrict__ pmn, const float *__restrict__ pmx, const double *__restrict__ psum,
+    float *__restrict__ mn_out, float *__restrict__ mx_out, double *__restrict__ sum_out)
+{
+    __shared__ float s_mn[COL_WAVES][64], s_mx[COL_WAVES][64];
+    __shared__ double s_sum[COL_WAVES][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + lane;
+    float mn = INFINITY, mx = -INFINITY;
+    double sum = 0.0;
+    if (c < d) {
+        for (int g = wave; g < G; g += COL_WAVES) {
+            const int64_t o = (int64_t)g * d + c;
+            if (pmn) { mn = fminf(mn, pmn[o]); mx = fmaxf(mx, pmx[o]); }
+            sum += psum[o];
+        }
+    }
+    s_mn[wave][lane] = mn;
+    s_mx[wave][lane] = mx;
+    s_sum[wave][lane] = sum;
+    __syncthreads();
+    if (wave == 0 && c < d) {
+        for (int w = 1; w < COL_WAVES; ++w) {
+            mn = fminf(mn, s_mn[w][lane]);
+            mx = fmaxf(mx, s_mx[w][lane]);
+            sum += s_sum[w][lane];
+        }
+        if (mn_out) { mn_out[c] = mn; mx_out[c] = mx; }
+        sum_out[c] = sum;
+    }
+}
+
+// Pass-1 finalisation from the column totals; GLOBAL scope pools all columns.  In place on mn / mx.
 __global__ __launch_bounds__(CAL_THREADS) void calib_stats_kernel(
-    int G, int d, int64_t n, int scope, const float *__restrict__ pmn, const float *__restrict__ pmx,
-    const double *__restrict__ psum, float *__restrict__ mn_out, float *__restrict__ mx_out,
-    double *__restrict__ mu_out)
+    int d, int64_t n, int scope, float *__restrict__ mn_io, float *__restrict__ mx_io,
+    const double *__restrict__ csum, double *__restrict__ mu_out)
 {
     __shared__ double shd[CAL_THREADS];
     __shared__ float shf[CAL_THREADS];
+    if (scope == LPQ_SCOPE_PER_FEATURE) {
+        for (int c = threadIdx.x; c < d; c += CAL_THREADS) mu_out[c] = csum[c] / (double)n;
+        return;
+    }
     float gmn = INFINITY, gmx = -INFINITY;
     double gsum = 0.0;
     for (int c = threadIdx.x; c < d; c += CAL_THREADS) {
-        float mn = INFINITY, mx = -INFINITY;
-        double sum = 0.0;
-        for (int g = 0; g < G; ++g) {
-            const int64_t o = (int64_t)g * d + c;
-            mn = fminf(mn, pmn[o]);
-            mx = fmaxf(mx, pmx[o]);
-            sum += psum[o];
-        }
-        if (scope == LPQ_SCOPE_PER_FEATURE) {
-            mn_out[c] = mn;
-            mx_out[c] = mx;
-            mu_out[c] = sum / (double)n;
-        }
-        gmn = fminf(gmn, mn);
-        gmx = fmaxf(gmx, mx);
-        gsum += sum;
+        gmn = fminf(gmn, mn_io[c]);
+        gmx = fmaxf(gmx, mx_io[c]);
+        gsum += csum[c];
     }
-    if (scope == LPQ_SCOPE_GLOBAL) {
-        gmn = block_min(gmn, shf);
-        gmx = -block_min(-gmx, shf);
-        gsum = block_sum(gsum, shd);
-        const double mu = gsum / ((double)n * (double)d);
-        for (int c = threadIdx.x; c < d; c += CAL_THREADS) {
-            mn_out[c] = gmn;
-            mx_out[c] = gmx;
-            mu_out[c] = mu;
-        }
+    gmn = block_min(gmn, shf);
+    gmx = -block_min(-gmx, shf);
+    gsum = block_sum(gsum, shd);
+    const double mu = gsum / ((double)n * (double)d);
+    for (int c = threadIdx.x; c < d; c += CAL_THREADS) {
+        mn_io[c] = gmn;
+        mx_io[c] = gmx;
+        mu_out[c] = mu;
     }
 }
 
@@ -179,15 +205,14 @@ __device__ inline float derive_m(float sb, float se, int bits)
 
 // Constants of Equation 1 from the statistics (Sections 3.2, 4.1, 4.2).
 __global__ __launch_bounds__(CAL_THREADS) void calib_params_kernel(
-    int G, int d, int64_t n, int bits, int mode, int scope, double sigma_mult,
+    int d, int64_t n, int bits, int mode, int scope, double sigma_mult,
     const float *__restrict__ mn, const float *__restrict__ mx, const double *__restrict__ mu,
-    const double *__restrict__ pss, float *__restrict__ params)
+    const double *__restrict__ css, float *__restrict__ params)
 {
     __shared__ double shd[CAL_THREADS];
     double gss = 0.0;
     if (mode == LPQ_CALIB_GAUSS && scope == LPQ_SCOPE_GLOBAL) {
-        for (int c = threadIdx.x; c < d; c += CAL_THREADS)
-            for (int g = 0; g < G; ++g) gss += pss[(int64_t)g * d + c];
+        for (int c = threadIdx.x; c < d; c += CAL_THREADS) gss += css[c];
         gss = block_sum(gss, shd);
     }
     for (int c = threadIdx.x; c < d; c += CAL_THREADS) {
@@ -195,8 +220,7 @@ __global__ __launch_bounds__(CAL_THREADS) void calib_params_kernel(
         if (mode == LPQ_CALIB_GAUSS) {
             double ss = gss, cnt = (double)n * (double)d;
             if (scope == LPQ_SCOPE_PER_FEATURE) {
-                ss = 0.0;
-                for (int g = 0; g < G; ++g) ss += pss[(int64_t)g * d + c];
+                ss = css[c];
                 cnt = (double)n;
             }
             const double sigma = sqrt(ss / cnt);
@@ -387,7 +411,7 @@ __global__ __launch_bounds__(256) void item_aux_kernel(
 size_t calib_scratch_bytes(int d)
 {
     const size_t G = calib_blocks(d);
-    return G * d * (sizeof(double) + 2 * sizeof(float)) + (size_t)d * (sizeof(double) + 2 * sizeof(float)) + 256;
+    return G * d * (sizeof(double) + 2 * sizeof(float)) + (size_t)d * (3 * sizeof(double) + 2 * sizeof(float)) + 256;
 }
 
 hipError_t launch_calibrate(const float *x, int64_t n, int64_t ld, int d, int bits, int mode, int scope,
@@ -401,12 +425,17 @@ hipError_t launch_calibrate(const float *x, int64_t n, int64_t ld, int d, int bi
     if (e != hipSuccess) return e;
     calib_reduce_kernel<1><<<G, CAL_THREADS, 0, st>>>(x, n, ld, d, rpb, nullptr, s.pmn, s.pmx, s.psum,
                                                       nonfinite_flag);
-    calib_stats_kernel<<<1, CAL_THREADS, 0, st>>>(G, d, n, scope, s.pmn, s.pmx, s.psum, s.mn, s.mx, s.mu);
-    if (mode == LPQ_CALIB_GAUSS)
+    const int cblocks = (d + 63) / 64;
+    calib_colreduce_kernel<<<cblocks, COL_WAVES * 64, 0, st>>>(G, d, s.pmn, s.pmx, s.psum, s.mn, s.mx, s.csum);
+    calib_stats_kernel<<<1, CAL_THREADS, 0, st>>>(d, n, scope, s.mn, s.mx, s.csum, s.mu);
+    if (mode == LPQ_CALIB_GAUSS) {
         calib_reduce_kernel<2><<<G, CAL_THREADS, 0, st>>>(x, n, ld, d, rpb, s.mu, nullptr, nullptr, s.psum,
                                                           nonfinite_flag);
-    calib_params_kernel<<<1, CAL_THREADS, 0, st>>>(G, d, n, bits, mode, scope, sigma_mult, s.mn, s.mx, s.mu,
-                                                   s.psum, params_out);
+        calib_colreduce_kernel<<<cblocks, COL_WAVES * 64, 0, st>>>(G, d, nullptr, nullptr, s.psum, nullptr, nullptr,
+                                                                  s.css);
+    }
+    calib_params_kernel<<<1, CAL_THREADS, 0, st>>>(d, n, bits, mode, scope, sigma_mult, s.mn, s.mx, s.mu, s.css,
+                                                   params_out);
     return hipGetLastError();
 }
 
