@@ -34,7 +34,7 @@ static int fail(int code, const char *fmt, ...)
 extern "C" const char *lpq_last_error(void) { return g_err; }
 
 // ------------------------------------------------------------------------ tuning ----
-static int64_t g_tune[LPQ_TUNE_COUNT_] = {0, 0, 0, 0, 0};
+static int64_t g_tune[LPQ_TUNE_COUNT_] = {0, 0, 0, 0, 0, 0};
 
 extern "C" int lpq_set_tuning(int key, int64_t value)
 {
@@ -342,6 +342,8 @@ struct Plan {
     int64_t seed_stride = 0, seed_chunk = 0;   // seeding pass over S1 chunks spread over the corpus
     int SS = 0, Cs = 0;     // PLAN_MFMA_COLLECT: regions per query, capacity of a region
     int Sg = 0;             // PLAN_MFMA_COLLECT: splits of the generic kernel for overflowed queries
+    int wave_queries = 64;  // PLAN_MFMA_COLLECT: queries per wave of the scan
+    int expect = 0;         // PLAN_MFMA_COLLECT: expected candidates per query
     size_t off_qcodes = 0, off_qnorms = 0, off_lists1 = 0, off_seedlist = 0, off_seeds = 0, off_lists2 = 0,
            off_gmax = 0, off_merge_tmp = 0, off_cbuf = 0, off_ccnt = 0, off_over = 0, total = 0;
 };
@@ -354,7 +356,11 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     const int64_t n = idx->size;
     const int64_t want = g_tune[LPQ_TUNE_PATH];
     const bool regs = mfma_reg_supported(idx->d_pad, k), coll = mfma_collect_supported(idx->d_pad, k);
+    // Large batches of short rows: the collecting variant with 128 queries per wave beats the
+    // register lists at any k it takes (fewer LDS reads and less per-stage overhead per contraction).
+    const bool wide = coll && mfma_collect_wide(nq, idx->d_pad) && g_tune[LPQ_TUNE_WAVE_QUERIES] != 64;
     if (want == 3 && coll) p.mode = PLAN_MFMA_COLLECT;
+    else if (want != 1 && want != 4 && wide) p.mode = PLAN_MFMA_COLLECT;
     else if (want != 1 && regs) p.mode = PLAN_MFMA_REG;
     else if (want != 1 && want != 4 && coll) p.mode = PLAN_MFMA_COLLECT;
     else if (want != 1 && mfma_lds_supported(idx->d_pad, k)) p.mode = PLAN_MFMA_LDS;
@@ -406,8 +412,10 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     int64_t qt = (p.mode == PLAN_MFMA_LDS && k > 16) ? 128 : 256;   // queries per workgroup
     int64_t slots_now = slots;
     if (gmode) {
-        qt = mfma_queries_per_workgroup(nq, idx->d_pad);
         p.rsplit = mfma_row_split(nq, idx->d_pad);
+        if (p.mode == PLAN_MFMA_COLLECT && mfma_collect_wide(nq, idx->d_pad) && g_tune[LPQ_TUNE_WAVE_QUERIES] != 64)
+            p.wave_queries = 128;
+        qt = mfma_queries_per_workgroup(nq, idx->d_pad, p.wave_queries == 128);
     }
     const int64_t tiles_q = ceil_div(nq > 0 ? nq : 1, qt);
     const int64_t min_rows = p.mode == PLAN_GENERIC ? 2048 : 512;
@@ -433,6 +441,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
         // three times its share (at least 32).  Overflow is caught per query and redone exactly.
         p.SS = mfma_collect_regions(p.S2, p.rsplit);
         const double per_region = 1.15 * (double)k * (double)n / (double)seed / p.SS;
+        p.expect = (int)(per_region * p.SS + 1.0);
         int64_t cs = 32;
         while ((double)cs < 3.0 * per_region && cs < 4096) cs <<= 1;
         p.Cs = (int)cs;
@@ -490,6 +499,7 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k
     a.nq = nq; a.k = k; a.metric = metric;
     a.dry_run = (int)g_tune[LPQ_TUNE_DRY_RUN];
     a.work_order = (int)g_tune[LPQ_TUNE_WORK_ORDER];
+    a.wave_queries = 64;
     a.rsplit = p.rsplit;
     const int32_t *qnorms = reinterpret_cast<const int32_t *>(ws + p.off_qnorms);
     cand_t *lists1 = reinterpret_cast<cand_t *>(ws + p.off_lists1);
@@ -517,8 +527,10 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k
     auto seed_pass = [&]() -> hipError_t {
         {
             KernelSpan span(st, LPQ_PROFILE_SEED);
+            a.wave_queries = p.wave_queries;   // same query tiling as the scan it seeds
             hipError_t e = p.seed_stride ? launch_seed_mfma(a, 0, a.n, p.S1, p.SEG, gmax, st, p.seed_stride, p.seed_chunk)
                                          : launch_seed_mfma(a, 0, p.seed_rows, p.S1, p.SEG, gmax, st);
+            a.wave_queries = 64;
             if (e != hipSuccess) return e;
         }
         return launch_seed_finalize(gmax, nq, p.G, k, seeds, st);
@@ -530,9 +542,12 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k
         HIP_TRY(seed_pass());
         {
             KernelSpan span(st);
-            HIP_TRY(launch_collect_mfma(a, 0, a.n, p.S2, seeds, cbuf, ccnt, p.Cs, st));
+            a.wave_queries = p.wave_queries;
+            hipError_t e = launch_collect_mfma(a, 0, a.n, p.S2, seeds, cbuf, ccnt, p.Cs, st);
+            a.wave_queries = 64;
+            HIP_TRY(e);
         }
-        HIP_TRY(launch_collect_select(cbuf, ccnt, nq, p.SS, p.Cs, k, over, ids, dist, qnorms, metric, st));
+        HIP_TRY(launch_collect_select(cbuf, ccnt, nq, p.SS, p.Cs, k, over, ids, dist, qnorms, metric, st, p.expect));
         // queries whose candidates did not fit are searched again by the generic kernel
         HIP_TRY(launch_search_generic(a, 0, a.n, p.Sg, nullptr, lists2, st, over));
         HIP_TRY(launch_merge(lists2, nq, p.Sg, k, nullptr, nullptr, nullptr, ids, dist, qnorms, metric, st, false, over));

@@ -103,6 +103,7 @@ struct SearchArgs {
     bool rsplit;            // register variant: row-split workgroups (set from mfma_row_split)
     int dry_run;            // timing experiments: != 0 never collects a candidate (2..4: ablations)
     int work_order = 0;     // matrix-core kernels: block -> (split, query tile) mapping (0 = built-in)
+    int wave_queries = 64;  // collecting mode: queries per wave (64 or 128)
 };
 
 // Generic kernel: one workgroup per (query, corpus split); any d_pad (multiple of 32), any k.
@@ -125,7 +126,8 @@ hipError_t launch_search_mfma_lds(const SearchArgs &a, int64_t row0, int64_t row
 // [row0, row1) (all of them real items), then seeds[q] = bound from the k-th largest.
 int mfma_seed_segments(int S, int k, bool rsplit);
 int mfma_seed_groups(int S, int SEG, bool rsplit);        // = G, entries per query in gmax
-int mfma_queries_per_workgroup(int64_t nq, int d_pad);   // query tile of the register variant
+int mfma_queries_per_workgroup(int64_t nq, int d_pad, bool wide = false);   // query tile; wide: 128 queries per wave
+bool mfma_collect_wide(int64_t nq, int d_pad);           // collecting mode may use 128 queries per wave
 bool mfma_row_split(int64_t nq, int d_pad);              // few queries: waves split rows, share queries
 // With stride > 0 the pass reads S chunks of chunk_rows rows (a multiple of 128, <= stride) whose
 // first rows are row0, row0 + stride, ...: a sample spread over the corpus.
@@ -140,9 +142,11 @@ hipError_t launch_collect_mfma(const SearchArgs &a, int64_t row0, int64_t row1, 
                                cand_t *cbuf, int32_t *ccnt, int Cs, hipStream_t st);
 // Per query: if no region overflowed and at most 4096 candidates were collected, sort them, write
 // the k best as the final result and set over[q] = 0; otherwise set over[q] = 1 and write nothing.
+// expected_candidates (per query, 0 = unknown) picks the one-wave-per-query kernel when small; that
+// kernel flags queries with more than 256 candidates as well.
 hipError_t launch_collect_select(const cand_t *cbuf, const int32_t *ccnt, int64_t nq, int SS, int Cs, int k,
                                  int32_t *over, int32_t *ids, int32_t *dists, const int32_t *qnorms, int metric,
-                                 hipStream_t st);
+                                 hipStream_t st, int expected_candidates = 0);
 hipError_t launch_seed_finalize(const int32_t *gmax, int64_t nq, int G, int k, cand_t *seeds, hipStream_t st);
 
 // Merge P lists of k candidates per query into one (merge.hip).  If ids/dists are given the

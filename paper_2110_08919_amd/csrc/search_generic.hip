@@ -73,6 +73,17 @@ __global__ __launch_bounds__(GEN_THREADS) void search_generic_kernel(
     for (int i = threadIdx.x; i < a.k; i += GEN_THREADS) out[i] = buf[i];
 }
 
+// 64-bit minimum over the wave; every lane gets the result.
+__device__ __forceinline__ cand_t wave_min_cand(cand_t c)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const cand_t t = __shfl_xor(c, o, 64);
+        c = t < c ? t : c;
+    }
+    return c;
+}
+
 // Final id and distance of candidate c of query q, written at position `at`.
 __device__ __forceinline__ void emit_result(cand_t c, int64_t at, int64_t q, int32_t *__restrict__ ids,
                                             int32_t *__restrict__ dists, const int32_t *__restrict__ qnorms, int metric)
@@ -114,6 +125,63 @@ __global__ __launch_bounds__(256) void merge_kernel(
         if (ids) emit_result(c, q * k + i, q, ids, dists, qnorms, metric);
     }
     if (seeds_out && threadIdx.x == 0) seeds_out[q] = buf[k - 1];
+}
+
+// Last step of the collecting scan for small k and few candidates, one WAVE per query (no
+// workgroup barriers): lane r gathers region r into the wave's LDS buffer, every lane then keeps
+// up to 4 candidates in registers and the wave takes the smallest k times.  A query with an
+// overflowed region, more than 256 candidates or fewer than k is flagged in over[] instead.
+constexpr int WSEL_CAP = 256;
+__global__ __launch_bounds__(256) void collect_select_wave_kernel(
+    const cand_t *__restrict__ cbuf, const int32_t *__restrict__ ccnt, int64_t nq, int SS, int Cs, int k,
+    int32_t *__restrict__ over, int32_t *__restrict__ ids, int32_t *__restrict__ dists,
+    const int32_t *__restrict__ qnorms, int metric)
+{
+    __shared__ cand_t sbuf[4][WSEL_CAP];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t q = (int64_t)blockIdx.x * 4 + wave;
+    if (q >= nq) return;                                   // wave-uniform
+    cand_t *wbuf = sbuf[wave];
+    const int c = (lane < SS) ? ccnt[q * SS + lane] : 0;
+    const bool bad = c > Cs || c < 0;
+    const int cl = bad ? 0 : c;
+    int incl = cl;                                         // inclusive prefix sum over the lanes
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += t;
+    }
+    const int M = __shfl(incl, 63, 64);
+    if (__ballot(bad) || M > WSEL_CAP || M < k) {
+        if (lane == 0) over[q] = 1;
+        return;
+    }
+    const int off = incl - cl;
+    for (int j = 0; j < cl; ++j) wbuf[off + j] = cbuf[((size_t)q * SS + lane) * Cs + j];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    cand_t v[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = (e * 64 + lane < M) ? wbuf[e * 64 + lane] : CAND_NONE;
+    for (int r = 0; r < k; ++r) {
+        cand_t mine = v[0];
+#pragma unroll
+        for (int e = 1; e < 4; ++e) mine = v[e] < mine ? v[e] : mine;
+        const cand_t mn = wave_min_cand(mine);
+        const int win = __ffsll((unsigned long long)__ballot(mine == mn)) - 1;
+        if (lane == win) {
+            emit_result(mn, q * k + r, q, ids, dists, qnorms, metric);
+            bool done = false;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool hit = !done && v[e] == mn;
+                v[e] = hit ? CAND_NONE : v[e];
+                done = done || hit;
+            }
+        }
+    }
+    if (lane == 0) over[q] = 0;
 }
 
 // Last step of the collecting scan, one workgroup per query: gather the query's regions into LDS,
@@ -181,17 +249,6 @@ __global__ __launch_bounds__(256) void collect_select_kernel(
     block_bitonic_sort(buf, cap);
     for (int i = tid; i < k; i += 256) emit_result(buf[i], q * k + i, q, ids, dists, qnorms, metric);
     if (tid == 0) over[q] = 0;
-}
-
-// 64-bit minimum over the wave; every lane gets the result.
-__device__ __forceinline__ cand_t wave_min_cand(cand_t c)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        const cand_t t = __shfl_xor(c, o, 64);
-        c = t < c ? t : c;
-    }
-    return c;
 }
 
 // Merge of lists that are each sorted ascending, for small k and many lists: one workgroup per
@@ -296,11 +353,16 @@ int merge_max_lists(int k) { return 4096 / k - 1; }
 
 hipError_t launch_collect_select(const cand_t *cbuf, const int32_t *ccnt, int64_t nq, int SS, int Cs, int k,
                                  int32_t *over, int32_t *ids, int32_t *dists, const int32_t *qnorms, int metric,
-                                 hipStream_t st)
+                                 hipStream_t st, int expected_candidates)
 {
     if (nq <= 0) return hipSuccess;
     const int maxc = 4096;
     if (SS < 1 || SS > 2048 || k > maxc) return hipErrorInvalidValue;
+    if (expected_candidates > 0 && expected_candidates <= WSEL_CAP / 2 && SS <= 64 && k <= 32) {
+        collect_select_wave_kernel<<<(unsigned)ceil_div(nq, (int64_t)4), 256, 0, st>>>(cbuf, ccnt, nq, SS, Cs, k, over, ids,
+                                                                                 dists, qnorms, metric);
+        return hipGetLastError();
+    }
     const size_t lds = (size_t)maxc * sizeof(cand_t) + (size_t)(SS + 1) * sizeof(int);
     collect_select_kernel<<<(unsigned)nq, 256, lds, st>>>(cbuf, ccnt, SS, Cs, k, maxc, over, ids, dists, qnorms, metric);
     return hipGetLastError();

@@ -45,7 +45,8 @@ namespace lpq {
 
 namespace {
 
-constexpr int NQW = 64;      // queries per wave = lanes per wave: lane q owns query q
+constexpr int NQW = 64;      // queries per wave in list mode = lanes per wave: lane q owns query q
+constexpr int MAXQW = 128;   // most queries a wave handles (collecting mode with four query blocks)
 constexpr int TRIG = 32;     // queue fill that asks for a joint drain at the next stage boundary
 constexpr int SVCAP = 128;   // compacted candidates buffered before they are handed to owners
 
@@ -71,17 +72,17 @@ struct WaveQ {      // pointers into the wave's private LDS region
     int *svq;       // [SVCAP] query slot of each compacted candidate
 };
 
-constexpr size_t WAVEQ_BYTES = NQW * 8 + SVCAP * 8 + QCAP * 16 * 4 + QCAP * 16 + NQW * 8 + SVCAP * 4;
+constexpr size_t WAVEQ_BYTES = MAXQW * 8 + SVCAP * 8 + QCAP * 16 * 4 + QCAP * 16 + MAXQW * 8 + SVCAP * 4;
 
 __device__ __forceinline__ WaveQ carve_waveq(unsigned char *p)
 {
     WaveQ w;
-    w.thrC = (cand_t *)p;    p += NQW * 8;
+    w.thrC = (cand_t *)p;    p += MAXQW * 8;
     w.svc = (cand_t *)p;     p += SVCAP * 8;
     w.qvals = (int *)p;      p += QCAP * 16 * 4;
     w.qmeta = (v4i *)p;      p += QCAP * 16;
-    w.thrE = (int *)p;       p += NQW * 4;
-    w.mbox = (int *)p;       p += NQW * 4;
+    w.thrE = (int *)p;       p += MAXQW * 4;
+    w.mbox = (int *)p;       p += MAXQW * 4;
     w.svq = (int *)p;
     return w;
 }
@@ -212,12 +213,15 @@ __device__ __forceinline__ void drain_queue(const WaveQ &w, int qcnt, int64_t ro
     }
 }
 
-template <int KS, bool L2, int KCAP, bool SEED, int NW, bool RSPLIT>
+template <int KS, bool L2, int KCAP, bool SEED, int NW, bool RSPLIT, int NB>
 __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     SearchArgs a, int64_t row0, int64_t row1, int S, int64_t split_rows, int qtiles, MfmaIo o)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    constexpr int NB = 2;
+    // NB blocks of 32 queries per wave: 2, or 4 (128 queries per wave, 512 per workgroup) in the
+    // collecting mode of large batches and its seeding pass, where no lane owns a list.
+    static_assert(NB == 2 || (NB == 4 && (KCAP == 0 || SEED) && !RSPLIT), "four query blocks: no register lists");
+    constexpr int QW = NB * 32;            // queries per wave
     constexpr bool COLLECT = !SEED && KCAP == 0;
     constexpr int LK = KCAP > 0 ? KCAP : 1;
     const cand_t *__restrict__ seeds = o.seeds;
@@ -228,7 +232,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     // a stage between them (one 32-row block each), so no matrix work is spent on padding queries.
     // Every wave then copies, waits for and reads only its own quarter of each stage: the waves run
     // without any workgroup barrier and the path is bound by how fast the corpus streams in.
-    constexpr int QT = RSPLIT ? NQW : NW * NQW;   // queries per workgroup
+    constexpr int QT = RSPLIT ? QW : NW * QW;   // queries per workgroup
     constexpr int CPR = 2 * KS;            // 16-byte chunks per corpus row
     constexpr int SLOTS = CPR <= 2 ? 2 : (CPR <= 4 ? 4 : (CPR <= 8 ? 8 : 16));  // LDS slots per row
     constexpr int RS = RSPLIT ? 32 * NW : 64;   // corpus rows per stage
@@ -263,7 +267,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     int *flags = aux + NST * AUX_INTS;           // [2][8] joint-drain requests, double buffered
     const WaveQ w = carve_waveq((unsigned char *)(flags + 16) + (size_t)wave * WAVEQ_BYTES);
 
-    const int64_t q_first = (int64_t)qt * QT + (RSPLIT ? 0 : wave * NQW);
+    const int64_t q_first = (int64_t)qt * QT + (RSPLIT ? 0 : wave * QW);
 
     // ---- owner state (lane q owns query q of this wave) ------------------------------
     cand_t lst[LK];
@@ -281,6 +285,13 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
         w.thrC[lane] = seedC;
         w.thrE[lane] = thr_e(seedC);
         w.mbox[lane] = COLLECT ? 0 : -1;
+        if constexpr (QW > 64) {   // the second 64 queries of the wave
+            const int64_t gq2 = gq + 64;
+            const cand_t s2 = (gq2 < a.nq && (a.dry_run == 0 || a.dry_run >= 5)) ? (seeds ? seeds[gq2] : CAND_NONE) : 0;
+            w.thrC[64 + lane] = s2;
+            w.thrE[64 + lane] = thr_e(s2);
+            w.mbox[64 + lane] = 0;
+        }
     }
     wave_lds_sync();
 
@@ -515,8 +526,10 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     if (COLLECT) {
         if (a.dry_run < 5) drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
         wave_lds_sync();
-        const int64_t gq = q_first + lane;
-        if (gq < a.nq) o.ccnt[(size_t)gq * SS + sub] = w.mbox[lane];
+        for (int i = lane; i < QW; i += 64) {
+            const int64_t gq = q_first + i;
+            if (gq < a.nq) o.ccnt[(size_t)gq * SS + sub] = w.mbox[i];
+        }
     } else if (!SEED) {
         if (a.dry_run < 5) drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
         if constexpr (RSPLIT && KCAP > 0) {
@@ -620,12 +633,12 @@ size_t lds_bytes(int ks, bool seed, int nw, bool rsplit)
     return (size_t)nst * rs * slots * 16 + (size_t)nst * (rs + 4) * 4 + 64 + (seed ? 0 : nw * WAVEQ_BYTES);
 }
 
-template <int KS, bool L2, int KCAP, bool SEED, int NW, bool RSPLIT>
+template <int KS, bool L2, int KCAP, bool SEED, int NW, bool RSPLIT, int NB = 2>
 hipError_t launch_nw(const SearchArgs &a, int64_t row0, int64_t row1, int S, int64_t split_rows, MfmaIo o, hipStream_t st)
 {
-    const int qtiles = (int)ceil_div(a.nq, RSPLIT ? NQW : NW * NQW);
+    const int qtiles = (int)ceil_div(a.nq, RSPLIT ? NQW : NW * NB * 32);
     const size_t lds = lds_bytes(KS, SEED, NW, RSPLIT);
-    auto kern = search_mfma_kernel<KS, L2, KCAP, SEED, NW, RSPLIT>;
+    auto kern = search_mfma_kernel<KS, L2, KCAP, SEED, NW, RSPLIT, NB>;
     static bool attr_set = false;  // per instantiation
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -648,6 +661,9 @@ hipError_t launch_one(const SearchArgs &a, int64_t row0, int64_t row1, int S, Mf
     if (!o.split_stride) o.split_stride = split_rows;
     if constexpr (KS <= 4) {
         if (a.rsplit) return launch_nw<KS, L2, KCAP, SEED, 4, true>(a, row0, row1, S, split_rows, o, st);
+        if constexpr (KCAP == 0 || SEED) {
+            if (a.wave_queries == 128) return launch_nw<KS, L2, KCAP, SEED, 4, false, 4>(a, row0, row1, S, split_rows, o, st);
+        }
     }
     return launch_nw<KS, L2, KCAP, SEED, 4, false>(a, row0, row1, S, split_rows, o, st);
 }
@@ -691,7 +707,10 @@ bool shape_ok(int d_pad)
 
 }  // namespace
 
-int mfma_queries_per_workgroup(int64_t nq, int d_pad) { return mfma_row_split(nq, d_pad) ? 64 : 256; }
+int mfma_queries_per_workgroup(int64_t nq, int d_pad, bool wide) { return mfma_row_split(nq, d_pad) ? 64 : (wide ? 512 : 256); }
+
+// Collecting mode: 128 queries per wave when the rows are short enough for the registers to hold them.
+bool mfma_collect_wide(int64_t nq, int d_pad) { return !mfma_row_split(nq, d_pad) && d_pad <= 128 && nq > 256; }
 
 // Few queries: the waves of a workgroup share them and split the rows instead.
 bool mfma_row_split(int64_t nq, int d_pad) { return nq <= 64 && d_pad <= 128; }

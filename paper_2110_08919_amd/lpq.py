@@ -19,7 +19,7 @@ OK, EINVAL, ERANGE, ENOMEM, EDEVICE, ENONFINITE, ESTATE = range(7)
 CALIB_MINMAX, CALIB_ABSMAX, CALIB_GAUSS = 0, 1, 2
 SCOPE_PER_FEATURE, SCOPE_GLOBAL = 0, 1
 METRIC_L2SQ, METRIC_IP = 0, 1
-TUNE_PATH, TUNE_SPLITS, TUNE_SEED_ROWS, TUNE_DRY_RUN, TUNE_WORK_ORDER = 0, 1, 2, 3, 4
+TUNE_PATH, TUNE_SPLITS, TUNE_SEED_ROWS, TUNE_DRY_RUN, TUNE_WORK_ORDER, TUNE_WAVE_QUERIES = 0, 1, 2, 3, 4, 5
 
 CALIB = {"minmax": CALIB_MINMAX, "absmax": CALIB_ABSMAX, "gauss": CALIB_GAUSS}
 SCOPE = {"per_feature": SCOPE_PER_FEATURE, "global": SCOPE_GLOBAL}
