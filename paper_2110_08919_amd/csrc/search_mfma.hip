@@ -46,7 +46,6 @@ namespace lpq {
 namespace {
 
 constexpr int NQW = 64;      // queries per wave in list mode = lanes per wave: lane q owns query q
-constexpr int MAXQW = 128;   // most queries a wave handles (collecting mode with four query blocks)
 constexpr int TRIG = 32;     // queue fill that asks for a joint drain at the next stage boundary
 constexpr int SVCAP = 128;   // compacted candidates buffered before they are handed to owners
 
@@ -72,17 +71,18 @@ struct WaveQ {      // pointers into the wave's private LDS region
     int *svq;       // [SVCAP] query slot of each compacted candidate
 };
 
-constexpr size_t WAVEQ_BYTES = MAXQW * 8 + SVCAP * 8 + QCAP * 16 * 4 + QCAP * 16 + MAXQW * 8 + SVCAP * 4;
+// bytes of a wave's region, for qw queries per wave (LDS is what limits two workgroups per CU)
+constexpr size_t waveq_bytes(int qw) { return (size_t)qw * 8 + SVCAP * 8 + QCAP * 16 * 4 + QCAP * 16 + (size_t)qw * 8 + SVCAP * 4; }
 
-__device__ __forceinline__ WaveQ carve_waveq(unsigned char *p)
+__device__ __forceinline__ WaveQ carve_waveq(unsigned char *p, int qw)
 {
     WaveQ w;
-    w.thrC = (cand_t *)p;    p += MAXQW * 8;
+    w.thrC = (cand_t *)p;    p += qw * 8;
     w.svc = (cand_t *)p;     p += SVCAP * 8;
     w.qvals = (int *)p;      p += QCAP * 16 * 4;
     w.qmeta = (v4i *)p;      p += QCAP * 16;
-    w.thrE = (int *)p;       p += MAXQW * 4;
-    w.mbox = (int *)p;       p += MAXQW * 4;
+    w.thrE = (int *)p;       p += qw * 4;
+    w.mbox = (int *)p;       p += qw * 4;
     w.svq = (int *)p;
     return w;
 }
@@ -265,7 +265,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     unsigned char *ring = smem;
     int *aux = (int *)(smem + NST * STAGE_BYTES);
     int *flags = aux + NST * AUX_INTS;           // [2][8] joint-drain requests, double buffered
-    const WaveQ w = carve_waveq((unsigned char *)(flags + 16) + (size_t)wave * WAVEQ_BYTES);
+    const WaveQ w = carve_waveq((unsigned char *)(flags + 16) + (size_t)wave * waveq_bytes(NB * 32), NB * 32);
 
     const int64_t q_first = (int64_t)qt * QT + (RSPLIT ? 0 : wave * QW);
 
@@ -624,20 +624,20 @@ __global__ __launch_bounds__(256) void seed_finalize_kernel(const int32_t *__res
     if (lane == 0) seeds[q] = (G < k || kth == INT32_MIN) ? CAND_NONE : make_cand(-2 * kth, 0xFFFFFFFFu);
 }
 
-size_t lds_bytes(int ks, bool seed, int nw, bool rsplit)
+size_t lds_bytes(int ks, bool seed, int nw, bool rsplit, int nb)
 {
     const int cpr = 2 * ks;
     const int slots = cpr <= 2 ? 2 : (cpr <= 4 ? 4 : (cpr <= 8 ? 8 : 16));
     const int nst = (ks <= 4 && !rsplit) ? 4 : 3;
     const int rs = rsplit ? 32 * nw : 64;
-    return (size_t)nst * rs * slots * 16 + (size_t)nst * (rs + 4) * 4 + 64 + (seed ? 0 : nw * WAVEQ_BYTES);
+    return (size_t)nst * rs * slots * 16 + (size_t)nst * (rs + 4) * 4 + 64 + (seed ? 0 : nw * waveq_bytes(nb * 32));
 }
 
 template <int KS, bool L2, int KCAP, bool SEED, int NW, bool RSPLIT, int NB = 2>
 hipError_t launch_nw(const SearchArgs &a, int64_t row0, int64_t row1, int S, int64_t split_rows, MfmaIo o, hipStream_t st)
 {
     const int qtiles = (int)ceil_div(a.nq, RSPLIT ? NQW : NW * NB * 32);
-    const size_t lds = lds_bytes(KS, SEED, NW, RSPLIT);
+    const size_t lds = lds_bytes(KS, SEED, NW, RSPLIT, NB);
     auto kern = search_mfma_kernel<KS, L2, KCAP, SEED, NW, RSPLIT, NB>;
     static bool attr_set = false;  // per instantiation
     if (!attr_set) {
