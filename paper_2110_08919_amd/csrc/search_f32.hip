@@ -1,7 +1,7 @@
 // Exact search on the original fp32 vectors: the reference set S_E of the recall definition
 // (Section 5.3).  The squared distance is summed directly as (q - x)^2 in fp32 (fused
 // multiply-add, partial sums per lane combined by a tree), never through the norm identity,
-// so near neighbours keep their relative accuracy.  One workgroup per (query, corpus split);
+// so near neighbours keep their relative accuracy.  One workgroup per (query tile, corpus split);
 // selection and merge are the ones of the integer path, on an order-preserving integer image
 // of the float.
 #include "block_select.h"
@@ -14,105 +14,182 @@ namespace {
 constexpr int F32_THREADS = 256;
 constexpr int F32_ROWS = F32_THREADS / 8;  // 8 lanes share a row, 4 floats each per step
 
-template <bool VEC>
+// QT queries share one pass over the rows of a split and every lane group works on F32_R rows at
+// once: the corpus is read once per QT queries, and a query value fetched from LDS feeds F32_R
+// subtract/multiply-add pairs (with one row per group the LDS pipe, not the VALU, was the limit).
+constexpr int F32_R = 4;
+constexpr int F32_STEP = F32_ROWS * F32_R;   // rows per step of a workgroup
+
+template <bool VEC, int QT>
 __global__ __launch_bounds__(F32_THREADS) void search_f32_kernel(
-    const float *__restrict__ x, int64_t n, int64_t ldx, const float *__restrict__ qv, int64_t ldq, int d,
-    int k, int mode, int S, int64_t split_rows, cand_t *__restrict__ lists, int cap)
+    const float *__restrict__ x, int64_t n, int64_t ldx, const float *__restrict__ qv, int64_t ldq, int64_t nq,
+    int d, int k, int mode, int S, int64_t split_rows, cand_t *__restrict__ lists, int cap)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    cand_t *buf = reinterpret_cast<cand_t *>(smem);
-    float *qs = reinterpret_cast<float *>(buf + cap);
-    __shared__ int s_count;
-    __shared__ cand_t s_thr;
+    cand_t *buf = reinterpret_cast<cand_t *>(smem);                 // [QT][cap]
+    float *qs = reinterpret_cast<float *>(buf + (size_t)QT * cap);  // [QT][dp]
+    __shared__ int s_count[QT];
+    __shared__ cand_t s_thr[QT];
 
-    const int64_t q = blockIdx.x / S;
-    const int s = blockIdx.x % S;
-    const int chunks = (d + 3) >> 2;
+    // Workgroups are dealt round-robin to the 8 XCDs: give each XCD a contiguous range of (split,
+    // query tile) pairs, split-major, so the query tiles that stream one split share that XCD's L2.
+    const int tiles = gridDim.x / S, per = gridDim.x / 8, b = blockIdx.x;
+    const int wk = (b < per * 8) ? (b % 8) * per + b / 8 : b;
+    const int64_t q0 = (int64_t)(wk % tiles) * QT;
+    const int s = wk / tiles;
+    const int chunks = (d + 3) >> 2, dp = 4 * chunks;
     const int64_t rs = (int64_t)s * split_rows;
     const int64_t re = (rs + split_rows < n) ? rs + split_rows : n;
     const bool l2 = mode == MODE_F32_L2;
 
-    for (int c = threadIdx.x; c < 4 * chunks; c += F32_THREADS) qs[c] = (c < d) ? qv[q * ldq + c] : 0.0f;
-    for (int i = threadIdx.x; i < cap; i += F32_THREADS) buf[i] = CAND_NONE;
-    if (threadIdx.x == 0) { s_count = 0; s_thr = CAND_NONE; }
+    for (int i = threadIdx.x; i < QT * dp; i += F32_THREADS) {
+        const int j = i / dp, c = i % dp;
+        qs[i] = (c < d && q0 + j < nq) ? qv[(q0 + j) * ldq + c] : 0.0f;
+    }
+    for (int i = threadIdx.x; i < QT * cap; i += F32_THREADS) buf[i] = CAND_NONE;
+    if (threadIdx.x < QT) { s_count[threadIdx.x] = 0; s_thr[threadIdx.x] = CAND_NONE; }
     __syncthreads();
 
     const int sub = threadIdx.x & 7, grp = threadIdx.x >> 3;
-    for (int64_t base = rs; base < re; base += F32_ROWS) {
-        const int64_t row = base + grp;
-        float acc = 0.0f;
-        if (row < re) {
-            const float *xr = x + row * ldx;
-            for (int c = sub; c < chunks; c += 8) {
-                float xv[4];
-                if (VEC && 4 * c + 3 < d) {
-                    const float4 t = *reinterpret_cast<const float4 *>(xr + 4 * c);
-                    xv[0] = t.x; xv[1] = t.y; xv[2] = t.z; xv[3] = t.w;
-                } else {
+    for (int64_t base = rs; base < re; base += F32_STEP) {
+        float acc[QT][F32_R];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) xv[j] = (4 * c + j < d) ? xr[4 * c + j] : 0.0f;
+        for (int j = 0; j < QT; ++j)
+#pragma unroll
+            for (int r = 0; r < F32_R; ++r) acc[j][r] = 0.0f;
+        // Four column chunks (of 4 floats) per lane at a time: all their loads are issued before the
+        // arithmetic starts, so one memory round trip covers 16 loads per lane.
+        for (int cb = sub; cb < chunks; cb += 32) {
+            float xv[4][F32_R][4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int c = cb + 8 * i;
+#pragma unroll
+                for (int r = 0; r < F32_R; ++r) {
+                    const int64_t row = base + r * F32_ROWS + grp;
+                    const float *xr = x + row * ldx;
+                    if (row >= re || c >= chunks) {
+                        xv[i][r][0] = xv[i][r][1] = xv[i][r][2] = xv[i][r][3] = 0.0f;
+                    } else if (VEC && 4 * c + 3 < d) {
+                        const float4 t = *reinterpret_cast<const float4 *>(xr + 4 * c);
+                        xv[i][r][0] = t.x; xv[i][r][1] = t.y; xv[i][r][2] = t.z; xv[i][r][3] = t.w;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) xv[i][r][e] = (4 * c + e < d) ? xr[4 * c + e] : 0.0f;
+                    }
                 }
+            }
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float qq = qs[4 * c + j];
-                    if (l2) { const float t = qq - xv[j]; acc = fmaf(t, t, acc); }
-                    else acc = fmaf(qq, xv[j], acc);
+            for (int i = 0; i < 4; ++i) {
+                const int c = cb + 8 * i;
+                if (c < chunks) {
+#pragma unroll
+                    for (int j = 0; j < QT; ++j) {
+                        const float4 qq = *reinterpret_cast<const float4 *>(qs + j * dp + 4 * c);
+                        const float qa[4] = {qq.x, qq.y, qq.z, qq.w};
+#pragma unroll
+                        for (int r = 0; r < F32_R; ++r)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                if (l2) { const float t = qa[e] - xv[i][r][e]; acc[j][r] = fmaf(t, t, acc[j][r]); }
+                                else acc[j][r] = fmaf(qa[e], xv[i][r][e], acc[j][r]);
+                            }
+                    }
                 }
             }
         }
-        acc += __shfl_xor(acc, 4, 64);
-        acc += __shfl_xor(acc, 2, 64);
-        acc += __shfl_xor(acc, 1, 64);
-        if (sub == 0 && row < re) {
-            const cand_t c = make_cand(float_to_sortable(l2 ? acc : -acc), (uint32_t)row);
-            if (c < s_thr) {
-                const int pos = atomicAdd(&s_count, 1);
-                buf[pos] = c;
+#pragma unroll
+        for (int j = 0; j < QT; ++j)
+#pragma unroll
+            for (int r = 0; r < F32_R; ++r) {
+                float a = acc[j][r];
+                a += __shfl_xor(a, 4, 64);
+                a += __shfl_xor(a, 2, 64);
+                a += __shfl_xor(a, 1, 64);
+                const int64_t row = base + r * F32_ROWS + grp;
+                if (sub == 0 && row < re) {
+                    const cand_t c = make_cand(float_to_sortable(l2 ? a : -a), (uint32_t)row);
+                    if (c < s_thr[j]) {
+                        const int pos = atomicAdd(&s_count[j], 1);
+                        buf[(size_t)j * cap + pos] = c;
+                    }
+                }
             }
-        }
         __syncthreads();
-        block_compact_if_full(buf, cap, k, F32_ROWS, &s_count, &s_thr);
+#pragma unroll
+        for (int j = 0; j < QT; ++j) block_compact_if_full(buf + (size_t)j * cap, cap, k, F32_STEP, &s_count[j], &s_thr[j]);
     }
-    block_bitonic_sort(buf, cap);
-    cand_t *out = lists + ((int64_t)q * S + s) * k;
-    for (int i = threadIdx.x; i < k; i += F32_THREADS) out[i] = buf[i];
+    for (int j = 0; j < QT; ++j) {
+        block_bitonic_sort(buf + (size_t)j * cap, cap);
+        if (q0 + j < nq) {
+            cand_t *out = lists + ((q0 + j) * S + s) * k;
+            for (int i = threadIdx.x; i < k; i += F32_THREADS) out[i] = buf[(size_t)j * cap + i];
+        }
+    }
 }
 
-int f32_splits(int64_t n, int64_t nq, int k)
+int f32_cap(int k) { return next_pow2((2 * k > k + 2 * F32_STEP) ? 2 * k : k + 2 * F32_STEP); }
+
+// queries per workgroup: as many as fit in 48 KB of LDS with their candidate buffers, at most 8
+int f32_query_tile(int d, int k)
 {
-    int64_t s = ceil_div(2048, nq > 0 ? nq : 1);
+    const size_t per = (size_t)f32_cap(k) * sizeof(cand_t) + (size_t)((d + 3) / 4) * 16;
+    int qt = 8;
+    while (qt > 1 && qt * per > 48 * 1024) qt >>= 1;
+    return qt;
+}
+
+int f32_splits(int64_t n, int64_t nq, int d, int k)
+{
+    const int64_t tiles = ceil_div(nq > 0 ? nq : 1, f32_query_tile(d, k));
+    int64_t s = ceil_div(2048, tiles);
     const int64_t by_rows = n / 2048 > 0 ? n / 2048 : 1;
     if (s > by_rows) s = by_rows;
     if (s > merge_max_lists(k)) s = merge_max_lists(k);
     return (int)(s < 1 ? 1 : s);
 }
 
+template <int QT>
+hipError_t launch_f32_tile(bool vec, unsigned blocks, size_t shmem, hipStream_t st, const float *x, int64_t n,
+                           int64_t ldx, const float *q, int64_t ldq, int64_t nq, int d, int k, int mode, int S,
+                           int64_t split_rows, cand_t *lists, int cap)
+{
+    if (vec)
+        search_f32_kernel<true, QT><<<blocks, F32_THREADS, shmem, st>>>(x, n, ldx, q, ldq, nq, d, k, mode, S, split_rows,
+                                                                          lists, cap);
+    else
+        search_f32_kernel<false, QT><<<blocks, F32_THREADS, shmem, st>>>(x, n, ldx, q, ldq, nq, d, k, mode, S, split_rows,
+                                                                           lists, cap);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 size_t f32_workspace_bytes(int64_t n, int64_t nq, int d, int k)
 {
-    (void)d;
-    return (size_t)nq * f32_splits(n, nq, k) * k * sizeof(cand_t);
+    return (size_t)nq * f32_splits(n, nq, d, k) * k * sizeof(cand_t);
 }
 
 hipError_t launch_search_f32(const float *x, int64_t n, int64_t ldx, const float *q, int64_t nq, int64_t ldq,
                              int d, int k, int metric, int32_t *ids, float *dists, void *ws, hipStream_t st)
 {
-    const int S = f32_splits(n, nq, k);
+    const int S = f32_splits(n, nq, d, k);
+    const int qt = f32_query_tile(d, k);
     const int mode = metric == LPQ_METRIC_L2SQ ? MODE_F32_L2 : MODE_F32_IP;
-    const int cap = next_pow2((2 * k > k + 2 * F32_ROWS) ? 2 * k : k + 2 * F32_ROWS);
-    const int64_t split_rows = round_up(ceil_div(n, S), F32_ROWS);
-    const size_t shmem = (size_t)cap * sizeof(cand_t) + (size_t)((d + 3) / 4) * 16;
+    const int cap = f32_cap(k);
+    const int64_t split_rows = round_up(ceil_div(n, S), F32_STEP);
+    const size_t shmem = (size_t)qt * ((size_t)cap * sizeof(cand_t) + (size_t)((d + 3) / 4) * 16);
     if (shmem > 64 * 1024) return hipErrorInvalidValue;
     cand_t *lists = reinterpret_cast<cand_t *>(ws);
     const bool vec = ((uintptr_t)x % 16 == 0) && (ldx % 4 == 0);
-    if (vec)
-        search_f32_kernel<true><<<(unsigned)(nq * S), F32_THREADS, shmem, st>>>(x, n, ldx, q, ldq, d, k, mode, S,
-                                                                                 split_rows, lists, cap);
-    else
-        search_f32_kernel<false><<<(unsigned)(nq * S), F32_THREADS, shmem, st>>>(x, n, ldx, q, ldq, d, k, mode, S,
-                                                                                  split_rows, lists, cap);
-    hipError_t e = hipGetLastError();
+    const unsigned blocks = (unsigned)(ceil_div(nq, qt) * S);
+    hipError_t e;
+    switch (qt) {
+    case 8: e = launch_f32_tile<8>(vec, blocks, shmem, st, x, n, ldx, q, ldq, nq, d, k, mode, S, split_rows, lists, cap); break;
+    case 4: e = launch_f32_tile<4>(vec, blocks, shmem, st, x, n, ldx, q, ldq, nq, d, k, mode, S, split_rows, lists, cap); break;
+    case 2: e = launch_f32_tile<2>(vec, blocks, shmem, st, x, n, ldx, q, ldq, nq, d, k, mode, S, split_rows, lists, cap); break;
+    default: e = launch_f32_tile<1>(vec, blocks, shmem, st, x, n, ldx, q, ldq, nq, d, k, mode, S, split_rows, lists, cap); break;
+    }
     if (e != hipSuccess) return e;
     return launch_merge(lists, nq, S, k, nullptr, nullptr, nullptr, ids, reinterpret_cast<int32_t *>(dists),
                         nullptr, mode, st, true);
