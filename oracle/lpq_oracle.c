@@ -31,6 +31,9 @@
  *   exact search  the S_E of Section 5.3: the same on the fp32 vectors, with the
  *                 sums accumulated in binary64.
  *   recall        |S_E intersect S_A| / |S_E| of Section 5.3.
+ *   gather        phi between a query and the items of an id list (the routine
+ *                 Section 5.2 replaces inside graph indexes).
+ *   re-rank       exact distances of a candidate list on the fp32 vectors, sorted.
  */
 #include <math.h>
 #include <stdint.h>
@@ -255,6 +258,61 @@ int lpqo_search_f32(const float *x, int64_t n, int64_t ldx, const float *q, int6
         free(p);
     }
     return fail;
+}
+
+/* Integer distances between each query and the items its list names (the distance
+ * routine that Section 5.2 swaps into graph indexes: phi(Q(q), Q(x_id)) for given ids).
+ * out[i][j] = phi(query i, item ids[i][j]); a negative id gives INT32_MAX (L2SQ) or
+ * INT32_MIN (IP), i.e. "infinitely far". */
+void lpqo_gather_dist(const int8_t *codes, int64_t ldc, const int8_t *q, int64_t nq, int64_t ldq,
+                      int d, const int32_t *ids, int m, int metric, int32_t *out)
+{
+    for (int64_t i = 0; i < nq; ++i)
+        for (int j = 0; j < m; ++j) {
+            int32_t id = ids[i * m + j];
+            if (id < 0) out[i * m + j] = (metric == LPQO_L2SQ) ? INT32_MAX : INT32_MIN;
+            else out[i * m + j] = (metric == LPQO_L2SQ) ? lpqo_dist_l2sq(q + i * ldq, codes + (int64_t)id * ldc, d)
+                                                        : lpqo_dist_ip(q + i * ldq, codes + (int64_t)id * ldc, d);
+        }
+}
+
+/* Re-rank of a candidate list on the original vectors (second stage that recovers the
+ * recall lost to quantization, Section 5.3's 2-6 % loss): for each query the exact
+ * distance (binary64 sums) to each of its kc candidates, sorted by (nearness, id),
+ * the first k reported (distance rounded to binary32).  Negative ids are skipped;
+ * missing results are id -1 with distance +inf (L2SQ) / -inf (IP). */
+int lpqo_rerank_f32(const float *x, int64_t ldx, const float *q, int64_t nq, int64_t ldq, int d,
+                    const int32_t *cand, int kc, int k, int metric, int32_t *ids, float *dists)
+{
+    dpair_t *p = (dpair_t *)malloc((size_t)(kc > 0 ? kc : 1) * sizeof(dpair_t));
+    if (!p) return 1;
+    for (int64_t i = 0; i < nq; ++i) {
+        int cnt = 0;
+        for (int j = 0; j < kc; ++j) {
+            int32_t id = cand[i * kc + j];
+            if (id < 0) continue;
+            double s = 0.0;
+            for (int t = 0; t < d; ++t) {
+                double a = (double)q[i * ldq + t], b = (double)x[(int64_t)id * ldx + t];
+                if (metric == LPQO_L2SQ) s += (a - b) * (a - b); else s += a * b;
+            }
+            p[cnt].key = (metric == LPQO_L2SQ) ? s : -s;
+            p[cnt].id = id;
+            ++cnt;
+        }
+        qsort(p, (size_t)cnt, sizeof(dpair_t), dpair_cmp);
+        for (int r = 0; r < k; ++r) {
+            if (r < cnt) {
+                ids[i * k + r] = p[r].id;
+                dists[i * k + r] = (float)((metric == LPQO_L2SQ) ? p[r].key : -p[r].key);
+            } else {
+                ids[i * k + r] = -1;
+                dists[i * k + r] = (metric == LPQO_L2SQ) ? INFINITY : -INFINITY;
+            }
+        }
+    }
+    free(p);
+    return 0;
 }
 
 /* Mean over queries of |approx intersect exact| / k (Section 5.3). */

@@ -172,6 +172,43 @@ def search_f32(x, q, k, metric="l2sq", threads=1):
     return ids, dists
 
 
+def gather_dist(codes, qcodes, ids, metric="l2sq"):
+    """int32 [nq, m]: integer distance between query i and item ids[i, j] (negative id: +-INT32 extreme)."""
+    codes, ldc = _mat(codes, np.int8)
+    qcodes, ldq = _mat(qcodes, np.int8)
+    ids = np.ascontiguousarray(ids, np.int32)
+    nq, m = ids.shape
+    assert qcodes.shape[0] == nq and qcodes.shape[1] == codes.shape[1]
+    assert ids.max(initial=-1) < codes.shape[0]
+    out = np.zeros((nq, m), np.int32)
+    lib = _load()
+    lib.lpqo_gather_dist.restype = None
+    lib.lpqo_gather_dist(_p(codes, C.c_int8), C.c_int64(ldc), _p(qcodes, C.c_int8), C.c_int64(nq), C.c_int64(ldq),
+                         C.c_int(codes.shape[1]), _p(ids, C.c_int32), C.c_int(m), C.c_int(_METRIC[metric]),
+                         _p(out, C.c_int32))
+    return out
+
+
+def rerank_f32(x, q, cand_ids, k, metric="l2sq"):
+    """Exact re-rank of candidate lists [nq, kc] on the fp32 vectors: (ids int32, dists fp32) [nq, k]."""
+    x, ldx = _mat(x, np.float32)
+    q, ldq = _mat(q, np.float32)
+    cand = np.ascontiguousarray(cand_ids, np.int32)
+    nq, kc = cand.shape
+    assert q.shape[0] == nq and q.shape[1] == x.shape[1] and k >= 1
+    assert cand.max(initial=-1) < x.shape[0]
+    ids = np.zeros((nq, k), np.int32)
+    dists = np.zeros((nq, k), np.float32)
+    lib = _load()
+    lib.lpqo_rerank_f32.restype = C.c_int
+    rc = lib.lpqo_rerank_f32(_p(x, C.c_float), C.c_int64(ldx), _p(q, C.c_float), C.c_int64(nq), C.c_int64(ldq),
+                             C.c_int(x.shape[1]), _p(cand, C.c_int32), C.c_int(kc), C.c_int(k),
+                             C.c_int(_METRIC[metric]), _p(ids, C.c_int32), _p(dists, C.c_float))
+    if rc:
+        raise MemoryError("oracle rerank")
+    return ids, dists
+
+
 def recall(approx_ids, exact_ids) -> float:
     a = np.ascontiguousarray(approx_ids, np.int32)
     e = np.ascontiguousarray(exact_ids, np.int32)

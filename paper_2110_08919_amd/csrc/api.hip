@@ -358,7 +358,9 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     const bool regs = mfma_reg_supported(idx->d_pad, k), coll = mfma_collect_supported(idx->d_pad, k);
     // Large batches of short rows: the collecting variant with 128 queries per wave beats the
     // register lists at any k it takes (fewer LDS reads and less per-stage overhead per contraction).
-    const bool wide = coll && mfma_collect_wide(nq, idx->d_pad) && g_tune[LPQ_TUNE_WAVE_QUERIES] != 64;
+    // (Not for codes of fewer than 8 bits: there many items tie at the seed threshold, all of them
+    // are collected, and queries spill to the exact redo.)
+    const bool wide = coll && idx->bits == 8 && mfma_collect_wide(nq, idx->d_pad) && g_tune[LPQ_TUNE_WAVE_QUERIES] != 64;
     if (want == 3 && coll) p.mode = PLAN_MFMA_COLLECT;
     else if (want != 1 && want != 4 && wide) p.mode = PLAN_MFMA_COLLECT;
     else if (want != 1 && regs) p.mode = PLAN_MFMA_REG;

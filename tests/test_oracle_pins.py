@@ -319,3 +319,50 @@ def test_tiny_workload_recall_is_plausible(oracle):
     ids, _ = oracle.search_i8(quant.encode(x), quant.encode(q), 10, "l2sq", threads=4)
     eids, _ = oracle.search_f32(x, q, 10, "l2sq", threads=4)
     assert oracle.recall(ids, eids) > 0.9
+
+
+# ---------------------------------------------------------------- candidate lists (gather, re-rank)
+def test_gather_distances_match_numpy_and_the_search(oracle):
+    """phi between a query and listed items: against numpy's direct sums, and consistent with the
+    exhaustive search (the distances the search reports are the gathered ones at its ids)."""
+    rng = np.random.default_rng(5)
+    codes = rng.integers(-128, 128, (300, 37), dtype=np.int8)
+    q = rng.integers(-128, 128, (9, 37), dtype=np.int8)
+    ids = rng.integers(0, 300, (9, 17)).astype(np.int32)
+    ids[2, 5] = -1
+    for metric in ("l2sq", "ip"):
+        got = oracle.gather_dist(codes, q, ids, metric)
+        c = codes[np.maximum(ids, 0)].astype(np.int64)
+        qq = q.astype(np.int64)[:, None, :]
+        ref = ((c - qq) ** 2).sum(-1) if metric == "l2sq" else (c * qq).sum(-1)
+        ok = ids >= 0
+        assert np.array_equal(got[ok], ref[ok])
+        assert got[2, 5] == (np.iinfo(np.int32).max if metric == "l2sq" else np.iinfo(np.int32).min)
+        sids, sd = oracle.search_i8(codes, q, 12, metric)
+        assert np.array_equal(oracle.gather_dist(codes, q, sids, metric), sd)
+
+
+def test_rerank_matches_numpy_sort_and_full_candidate_list_is_exact_search(oracle):
+    """Re-rank = exact fp64 distances of the listed items, sorted by (distance, id): against numpy
+    lexsort on float64 sums; with every item listed it must return the exact search of cdist."""
+    from scipy.spatial.distance import cdist
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal((200, 11)).astype(np.float32)
+    q = rng.standard_normal((7, 11)).astype(np.float32)
+    cand = np.stack([rng.permutation(200)[:40] for _ in range(7)]).astype(np.int32)
+    cand[3, 7] = -1
+    for metric in ("l2sq", "ip"):
+        ids, d = oracle.rerank_f32(x, q, cand, 10, metric)
+        for i in range(7):
+            c = cand[i][cand[i] >= 0]
+            xs, qs = x[c].astype(np.float64), q[i].astype(np.float64)
+            val = ((xs - qs) ** 2).sum(1) if metric == "l2sq" else -(xs @ qs)
+            order = np.lexsort((c, val))[:10]
+            assert np.array_equal(ids[i], c[order])
+            np.testing.assert_allclose(d[i], (val[order] if metric == "l2sq" else -val[order]).astype(np.float32), rtol=1e-6)
+    allc = np.tile(np.arange(200, dtype=np.int32), (7, 1))
+    ids, d = oracle.rerank_f32(x, q, allc, 5, "l2sq")
+    full = cdist(q.astype(np.float64), x.astype(np.float64), "sqeuclidean")
+    assert np.array_equal(ids, np.argsort(full, axis=1, kind="stable")[:, :5])
+    short, sd = oracle.rerank_f32(x, q, cand[:, :3], 5, "ip")      # fewer candidates than k
+    assert np.all(short[:, 3:] == -1) and np.all(np.isneginf(sd[:, 3:]))
