@@ -59,6 +59,9 @@ def main():
     ap.add_argument("--seed-rows", type=int, default=0)
     ap.add_argument("--workload", default="skewed_1m", choices=["tiny", "skewed_1m", "aniso_1m2", "scaled_10m", "product_100m"],
                     help="synthetic workload shape (default: the benchmark configuration)")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the candidate-list calls (gathered distances, fp32 re-rank) and report recall "
+                         "before / after the re-rank for a per-feature 6-bit quantizer")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 512 MiB device copy (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -159,6 +162,38 @@ def main():
         a, e = ids[:rq].cpu().numpy(), eids.cpu().numpy()
         recall = float(np.mean([len(set(a[i]) & set(e[i])) / k for i in range(rq)]))
 
+    # ---- candidate-list calls (not part of the timed step) ---------------------------------
+    extras = None
+    if args.extras:
+        def timed(fn, reps=10):
+            fn()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                out = fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps, out
+        m = 100
+        gen = torch.Generator(device="cuda").manual_seed(1)
+        gids = torch.randint(0, w.n, (w.nq, m), generator=gen, device="cuda", dtype=torch.int32)
+        qcodes = quant.encode(q).contiguous()
+        g_ms, _ = timed(lambda: index.gather_dist(qcodes, gids, metric))
+        rq2 = min(1000, w.nq)
+        q6 = lpq.Quantizer(w.d, 6).calibrate(x, "minmax", "per_feature")
+        i6 = lpq.Index(q6, w.n).add_f32(x)
+        ex, _ = lpq.search_f32(x, q[:rq2], k, metric)
+        c_ids, _ = i6.search(q[:rq2], k, metric)
+        w_ids, _ = i6.search(q[:rq2], 4 * k, metric)
+        r_ms, (f_ids, _) = timed(lambda: lpq.rerank_f32(x, q[:rq2], w_ids, k, metric))
+        def rec(a_, e_):
+            a_, e_ = a_.cpu().numpy(), e_.cpu().numpy()
+            return float(np.mean([len(set(a_[i]) & set(e_[i])) / k for i in range(a_.shape[0])]))
+        extras = {"gather_dist": {"pairs": w.nq * m, "ms": g_ms, "Mpairs_per_s": w.nq * m / g_ms / 1e3,
+                                  "GBps_rows": w.nq * m * (w.d + 4) / g_ms / 1e6},
+                  "rerank_f32": {"queries": rq2, "candidates": 4 * k, "ms": r_ms,
+                                 "recall_6bit_per_feature": rec(c_ids, ex), "recall_after_rerank": rec(f_ids, ex)}}
+
     # ---- CPU baseline: the oracle, on a bounded sample -----------------------------------
     cpu = None
     if args.cpu_sample > 0:
@@ -191,6 +226,8 @@ def main():
                         "encode_GBps": w.n * w.d * 5 / t_enc / 1e9},
         "wall_s_timed_region": wall,
     }
+    if extras:
+        out["extras"] = extras
     print(json.dumps(out))
 
 

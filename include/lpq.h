@@ -144,6 +144,31 @@ int lpq_search_f32(const float *x_dev, int64_t n, int64_t ldx, const float *q_de
                    int64_t ldq, int d, int k, int metric, int32_t *ids_dev, float *dist_dev,
                    void *workspace_dev, size_t workspace_bytes, void *stream);
 
+/* ------------------------------------------------------------ candidate lists ---- */
+
+/* Integer distances between each query and the items its id list names: the distance
+ * routine that Section 5.2 swaps into graph indexes, phi(Q(q), Q(x_id)), as one batched
+ * call.  qcodes_dev int8 [nq][ld] are codes of the index's quantizer (lpq_encode), ld >= d;
+ * ids_dev int32 [nq][m]; dist_dev int32 [nq][m] receives sum (cq - cx)^2 (L2SQ) or
+ * sum cq cx (IP).  An id outside [0, size) means "no item" and gives INT32_MAX (L2SQ) /
+ * INT32_MIN (IP).  All buffers are the caller's device memory; asynchronous on stream.
+ * LPQ_EINVAL: null argument, m < 1, ld < d, unknown metric; LPQ_ESTATE: empty index. */
+int lpq_gather_dist_i8(const lpq_index *idx, const int8_t *qcodes_dev, int64_t nq, int64_t ld,
+                       const int32_t *ids_dev, int m, int metric, int32_t *dist_dev, void *stream);
+
+/* Second stage on the original vectors, recovering the recall that quantization costs
+ * (the 2-6 % of Section 5.3): for each query the exact distance (binary64 sums) to each of
+ * its kc candidates cand_ids_dev [nq][kc] (e.g. the ids of an int8 search with k' > k),
+ * the k best sorted by (distance, id): ids_dev int32 [nq][k], dist_dev fp32 [nq][k]
+ * (L2SQ ascending / IP descending).  Candidate ids outside [0, n) are skipped; if fewer
+ * than k remain the row is completed with id -1 and distance +inf (L2SQ) / -inf (IP).
+ * 1 <= kc <= 4096, k >= 1.  Asynchronous on stream; no workspace.
+ * LPQ_EINVAL: null argument, d < 1, ldx/ldq < d, kc or k < 1, unknown metric; LPQ_ERANGE:
+ * kc > 4096. */
+int lpq_rerank_f32(const float *x_dev, int64_t n, int64_t ldx, const float *q_dev, int64_t nq,
+                   int64_t ldq, int d, const int32_t *cand_ids_dev, int kc, int k, int metric,
+                   int32_t *ids_dev, float *dist_dev, void *stream);
+
 /* ---------------------------------------------------------------- diagnostics ---- */
 
 /* Process-wide tuning knobs for measurements; 0 restores the built-in choice.

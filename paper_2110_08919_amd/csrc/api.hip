@@ -325,6 +325,36 @@ extern "C" int lpq_index_data(const lpq_index *idx, const int8_t **codes_dev, in
     return LPQ_OK;
 }
 
+// -------------------------------------------------------------- candidate lists ----
+extern "C" int lpq_gather_dist_i8(const lpq_index *idx, const int8_t *qcodes_dev, int64_t nq, int64_t ld,
+                                  const int32_t *ids_dev, int m, int metric, int32_t *dist_dev, void *stream)
+{
+    if (!idx) return fail(LPQ_EINVAL, "null index");
+    if (nq < 0 || m < 1) return fail(LPQ_EINVAL, "nq < 0 or m < 1");
+    if (metric != LPQ_METRIC_L2SQ && metric != LPQ_METRIC_IP) return fail(LPQ_EINVAL, "unknown metric %d", metric);
+    if (idx->size < 1) return fail(LPQ_ESTATE, "gather on an empty index");
+    if (nq > 0 && (!qcodes_dev || !ids_dev || !dist_dev)) return fail(LPQ_EINVAL, "null argument");
+    if (nq > 0 && ld < idx->d) return fail(LPQ_EINVAL, "ld < d");
+    HIP_TRY(launch_gather_dist(idx->codes, idx->norms, idx->size, idx->d, idx->d_pad, qcodes_dev, nq, ld, ids_dev, m,
+                               metric, dist_dev, (hipStream_t)stream));
+    return LPQ_OK;
+}
+
+extern "C" int lpq_rerank_f32(const float *x_dev, int64_t n, int64_t ldx, const float *q_dev, int64_t nq, int64_t ldq,
+                              int d, const int32_t *cand_ids_dev, int kc, int k, int metric, int32_t *ids_dev,
+                              float *dist_dev, void *stream)
+{
+    if (d < 1 || n < 1 || nq < 0 || kc < 1 || k < 1) return fail(LPQ_EINVAL, "bad size");
+    if (metric != LPQ_METRIC_L2SQ && metric != LPQ_METRIC_IP) return fail(LPQ_EINVAL, "unknown metric %d", metric);
+    if (kc > 4096) return fail(LPQ_ERANGE, "kc = %d > 4096", kc);
+    if (k > 4096) return fail(LPQ_ERANGE, "k = %d > 4096", k);
+    if (ldx < d || (nq > 0 && ldq < d)) return fail(LPQ_EINVAL, "row stride < d");
+    if (!x_dev || (nq > 0 && (!q_dev || !cand_ids_dev || !ids_dev || !dist_dev))) return fail(LPQ_EINVAL, "null argument");
+    HIP_TRY(launch_rerank_f32(x_dev, n, ldx, q_dev, nq, ldq, d, cand_ids_dev, kc, k, metric, ids_dev, dist_dev,
+                              (hipStream_t)stream));
+    return LPQ_OK;
+}
+
 // ------------------------------------------------------------------------ search ----
 namespace {
 

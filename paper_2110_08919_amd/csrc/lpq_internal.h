@@ -164,6 +164,17 @@ int merge_max_lists(int k);
 hipError_t launch_merge_groups(const cand_t *lists, int64_t nq, int P, int group, int k, cand_t *out_lists,
                                hipStream_t st);
 
+// ---- candidate lists (candidates.hip) -------------------------------------------------
+// out[i][j] = integer distance between query i (int8 codes, stride ldq) and item ids[i][j];
+// ids outside [0, n) give INT32_MAX (L2SQ) / INT32_MIN (IP).
+hipError_t launch_gather_dist(const int8_t *codes, const int32_t *norms, int64_t n, int d, int d_pad, const int8_t *q,
+                              int64_t nq, int64_t ldq, const int32_t *ids, int m, int metric, int32_t *out,
+                              hipStream_t st);
+// Exact distances (binary64 sums) of each query's kc <= 4096 candidates on the fp32 vectors, the k
+// best sorted by (distance, id); ids outside [0, n) are skipped, missing results are id -1.
+hipError_t launch_rerank_f32(const float *x, int64_t n, int64_t ldx, const float *q, int64_t nq, int64_t ldq, int d,
+                             const int32_t *cand, int kc, int k, int metric, int32_t *ids, float *dists, hipStream_t st);
+
 // ---- fp32 exact search (search_f32.hip) ---------------------------------------------
 size_t f32_workspace_bytes(int64_t n, int64_t nq, int d, int k);
 hipError_t launch_search_f32(const float *x, int64_t n, int64_t ldx, const float *q, int64_t nq,

@@ -64,6 +64,8 @@ def lib() -> C.CDLL:
             "lpq_search_i8": (i32, [vp, vp, i64, i64, i32, i32, vp, vp, vp, C.c_size_t, vp]),
             "lpq_search_f32_workspace_bytes": (C.c_size_t, [i64, i64, i32, i32]),
             "lpq_search_f32": (i32, [vp, i64, i64, vp, i64, i64, i32, i32, i32, vp, vp, vp, C.c_size_t, vp]),
+            "lpq_gather_dist_i8": (i32, [vp, vp, i64, i64, vp, i32, i32, vp, vp]),
+            "lpq_rerank_f32": (i32, [vp, i64, i64, vp, i64, i64, i32, vp, i32, i32, i32, vp, vp, vp]),
             "lpq_set_tuning": (i32, [i32, i64]),
             "lpq_profile_enable": (i32, [i32]),
             "lpq_profile_read": (i32, [C.POINTER(i64), C.POINTER(C.c_double)]),
@@ -201,6 +203,16 @@ class Index:
             self._ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
         return self._ws
 
+    def gather_dist(self, qcodes: torch.Tensor, ids: torch.Tensor, metric="l2sq"):
+        """int32 [nq, m]: integer distance between query i (int8 codes) and item ids[i, j]."""
+        qp, nq, ld = _dev_matrix(qcodes, torch.int8)
+        ip, ni, ldi = _dev_matrix(ids, torch.int32)
+        assert ni == nq and ldi == ids.shape[1]
+        out = torch.empty(ids.shape, dtype=torch.int32, device=ids.device)
+        _check(lib().lpq_gather_dist_i8(self._h, qp, nq, ld, ip, ids.shape[1], METRIC[metric], out.data_ptr(),
+                                        _stream()))
+        return out
+
     def search(self, q: torch.Tensor, k: int, metric="l2sq", out=None, workspace=None):
         """q fp32 [nq, d] or int8 codes [nq, d] on the device -> (ids int32, dists int32) [nq, k]."""
         is_codes = q.dtype == torch.int8
@@ -214,6 +226,19 @@ class Index:
         _check(fn(self._h, p, nq, ld, k, METRIC[metric], ids.data_ptr(), dists.data_ptr(),
                   ws.data_ptr(), ws.numel(), _stream()))
         return ids, dists
+
+
+def rerank_f32(x: torch.Tensor, q: torch.Tensor, cand_ids: torch.Tensor, k: int, metric="l2sq"):
+    """Exact re-rank of candidate lists int32 [nq, kc] on the fp32 vectors: (ids int32, dists fp32) [nq, k]."""
+    xp, n, ldx = _dev_matrix(x, torch.float32)
+    qp, nq, ldq = _dev_matrix(q, torch.float32)
+    cp, nc, ldc = _dev_matrix(cand_ids, torch.int32)
+    assert nc == nq and ldc == cand_ids.shape[1] and q.shape[1] == x.shape[1]
+    ids = torch.empty((nq, k), dtype=torch.int32, device=x.device)
+    dists = torch.empty((nq, k), dtype=torch.float32, device=x.device)
+    _check(lib().lpq_rerank_f32(xp, n, ldx, qp, nq, ldq, x.shape[1], cp, cand_ids.shape[1], k, METRIC[metric],
+                                ids.data_ptr(), dists.data_ptr(), _stream()))
+    return ids, dists
 
 
 def search_f32(x: torch.Tensor, q: torch.Tensor, k: int, metric="l2sq"):
