@@ -449,3 +449,43 @@ def test_rerank_recovers_recall(lpq, oracle):
     r0 = oracle.recall(coarse.cpu().numpy(), exact.cpu().numpy())
     r1 = oracle.recall(fine.cpu().numpy(), exact.cpu().numpy())
     assert r0 < 0.97 and r1 > r0 and r1 > 0.99
+
+
+# ------------------------------------------------------------------ stream capture
+@pytest.mark.parametrize("name,n,nq,k", [("skewed", 150_000, 300, 10), ("scaled", 140_000, 5, 10), ("tiny", 5000, 40, 100)])
+def test_search_can_be_captured_in_a_graph(lpq, oracle, name, n, nq, k):
+    """lpq_search enqueues kernels only (no allocation, no memset, no synchronisation), so a caller
+    may capture it in a HIP graph: every replay, with eager work in between, gives the eager result."""
+    base = {"skewed": synth.SKEWED_1M, "scaled": synth.SCALED_10M, "tiny": synth.TINY}[name]
+    w = base.scaled(n=n, nq=nq)
+    x, q = w.corpus("cuda"), w.queries("cuda")
+    quant = lpq.Quantizer(w.d, 8).calibrate(x, w.calib, w.scope)
+    index = lpq.Index(quant, w.n).add_f32(x)
+    ids = torch.empty((nq, k), dtype=torch.int32, device="cuda")
+    dists = torch.empty_like(ids)
+    ws = torch.empty(index.workspace_bytes(nq, k, w.metric) + 256, dtype=torch.uint8, device="cuda")
+
+    def step():
+        index.search(q, k, w.metric, out=(ids, dists), workspace=ws)
+    step()
+    torch.cuda.synchronize()
+    ref_ids, ref_d = ids.clone(), dists.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        ids.fill_(-5)
+        dists.fill_(-5)
+        ws.random_(0, 255)                      # whatever an earlier call left in the workspace must not matter
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ids, ref_ids) and torch.equal(dists, ref_d)
+        step()                                   # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(ids, ref_ids) and torch.equal(dists, ref_d)
