@@ -369,13 +369,14 @@ struct Plan {
     int G = 0;              // PLAN_MFMA_REG: group maxima per query
     bool rsplit = false;    // PLAN_MFMA_REG: row-split workgroups (few queries)
     int merge_group = 0;    // lists merged per workgroup in the first merge pass (0 = single pass)
-    int64_t seed_stride = 0, seed_chunk = 0;   // seeding pass over S1 chunks spread over the corpus
+    int64_t seed_stride = 0;   // seeding pass: one stage every seed_stride rows (systematic sample)
+    int seed_stages = 0;       // ... seed_stages of them per split
     int SS = 0, Cs = 0;     // PLAN_MFMA_COLLECT: regions per query, capacity of a region
     int Sg = 0;             // PLAN_MFMA_COLLECT: splits of the generic kernel for overflowed queries
     int wave_queries = 64;  // PLAN_MFMA_COLLECT: queries per wave of the scan
     int expect = 0;         // PLAN_MFMA_COLLECT: expected candidates per query
     size_t off_qcodes = 0, off_qnorms = 0, off_lists1 = 0, off_seedlist = 0, off_seeds = 0, off_lists2 = 0,
-           off_gmax = 0, off_merge_tmp = 0, off_cbuf = 0, off_ccnt = 0, off_over = 0, total = 0;
+           off_gmax = 0, off_merge_tmp = 0, off_cbuf = 0, off_ccnt = 0, off_over = 0, off_qlist = 0, total = 0;
 };
 
 size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
@@ -457,11 +458,13 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
         if (gmode) {
             p.SEG = mfma_seed_segments(p.S1, k, p.rsplit);
             p.G = mfma_seed_groups(p.S1, p.SEG, p.rsplit);
-            // S1 chunks of seed / S1 rows, first rows n / S1 apart (both whole 128-row blocks)
-            p.seed_chunk = seed / p.S1 / 128 * 128;
-            p.seed_stride = n / p.S1 / 128 * 128;
-            if (p.seed_chunk < 128 || p.seed_stride < p.seed_chunk) { p.seed_chunk = 0; p.seed_stride = 0; }
-            else seed = p.seed_chunk * p.S1;
+            // systematic sample: one stage every seed_stride rows, shared out over the S1 splits
+            const int64_t stage_rows = p.rsplit ? 128 : 64;
+            const int64_t stages = seed / stage_rows;
+            p.seed_stages = (int)ceil_div(stages, p.S1);
+            p.seed_stride = n / ((int64_t)p.seed_stages * p.S1) / 128 * 128;
+            if (p.seed_stages < 1 || p.seed_stride < stage_rows) { p.seed_stages = 0; p.seed_stride = 0; }
+            else seed = (int64_t)p.seed_stages * p.S1 * stage_rows;
         }
     }
     p.seed_rows = seed;
@@ -469,15 +472,20 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
                       p.mode == PLAN_MFMA_COLLECT ? (p.rsplit ? 512 : 2048)
                                                   : (p.rsplit ? merge_max_lists(k) : max_lists));   // few queries: one merge pass
     if (p.mode == PLAN_MFMA_COLLECT) {
-        // expected candidates per query ~ k n / seed_rows, spread over SS regions; a region holds
-        // three times its share (at least 32).  Overflow is caught per query and redone exactly.
+        // expected candidates per query ~ k n / seed_rows, spread evenly over SS regions (the scan
+        // deals its stages round-robin to the splits); a region holds three times its share, at
+        // least 64, which leaves room for bounds several times looser than expected (a corpus stored
+        // in sorted order).  Overflow is caught per query and redone exactly.
         p.SS = mfma_collect_regions(p.S2, p.rsplit);
         const double per_region = 1.15 * (double)k * (double)n / (double)seed / p.SS;
         p.expect = (int)(per_region * p.SS + 1.0);
-        int64_t cs = 32;
+        int64_t cs = 64;
         while ((double)cs < 3.0 * per_region && cs < 4096) cs <<= 1;
         p.Cs = (int)cs;
-        p.Sg = 4;
+        // splits of the redo scan: many, so that a few queries spread over the chip; bounded by the
+        // single merge pass and by 256 MB of lists
+        p.Sg = merge_max_lists(k) < 128 ? merge_max_lists(k) : 128;
+        while (p.Sg > 4 && (size_t)nq * p.Sg * k * sizeof(cand_t) > (size_t(256) << 20)) p.Sg /= 2;
     }
 
     size_t o = 0;
@@ -499,6 +507,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
         p.off_cbuf = o; o = align256(o + (size_t)nq * p.SS * p.Cs * sizeof(cand_t));
         p.off_ccnt = o; o = align256(o + (size_t)nq * p.SS * sizeof(int32_t));
         p.off_over = o; o = align256(o + (size_t)nq * sizeof(int32_t));
+        p.off_qlist = o; o = align256(o + ((size_t)nq + 1) * sizeof(int32_t));   // redo list, then its counter
     }
     p.total = o;
     return p;
@@ -560,12 +569,13 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k
         {
             KernelSpan span(st, LPQ_PROFILE_SEED);
             a.wave_queries = p.wave_queries;   // same query tiling as the scan it seeds
-            hipError_t e = p.seed_stride ? launch_seed_mfma(a, 0, a.n, p.S1, p.SEG, gmax, st, p.seed_stride, p.seed_chunk)
+            hipError_t e = p.seed_stride ? launch_seed_mfma(a, 0, a.n, p.S1, p.SEG, gmax, st, p.seed_stride, p.seed_stages)
                                          : launch_seed_mfma(a, 0, p.seed_rows, p.S1, p.SEG, gmax, st);
             a.wave_queries = 64;
             if (e != hipSuccess) return e;
         }
-        return launch_seed_finalize(gmax, nq, p.G, k, seeds, st);
+        return launch_seed_finalize(gmax, nq, p.G, k, seeds, st,
+                                    p.mode == PLAN_MFMA_COLLECT ? reinterpret_cast<int32_t *>(ws + p.off_qlist) + nq : nullptr);
     };
     if (p.mode == PLAN_MFMA_COLLECT) {
         cand_t *cbuf = reinterpret_cast<cand_t *>(ws + p.off_cbuf);
@@ -579,9 +589,11 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k
             a.wave_queries = 64;
             HIP_TRY(e);
         }
-        HIP_TRY(launch_collect_select(cbuf, ccnt, nq, p.SS, p.Cs, k, over, ids, dist, qnorms, metric, st, p.expect));
+        int32_t *qlist = reinterpret_cast<int32_t *>(ws + p.off_qlist), *qcount = qlist + nq;
+        HIP_TRY(launch_collect_select(cbuf, ccnt, nq, p.SS, p.Cs, k, over, qlist, qcount, ids, dist, qnorms, metric, st,
+                                      p.expect));
         // queries whose candidates did not fit are searched again by the generic kernel
-        HIP_TRY(launch_search_generic(a, 0, a.n, p.Sg, nullptr, lists2, st, over));
+        HIP_TRY(launch_search_generic_list(a, 0, a.n, p.Sg, qlist, qcount, lists2, st));
         HIP_TRY(launch_merge(lists2, nq, p.Sg, k, nullptr, nullptr, nullptr, ids, dist, qnorms, metric, st, false, over));
     } else if (p.mode == PLAN_MFMA_REG) {
         const cand_t *sd = nullptr;
@@ -629,6 +641,25 @@ extern "C" int lpq_search(const lpq_index *idx, const float *q_dev, int64_t nq, 
                           reinterpret_cast<int8_t *>(ws + p.off_qcodes), idx->d_pad, idx->d_pad,
                           reinterpret_cast<int32_t *>(ws + p.off_qnorms), st, p.nq_pad));
     return search_core(idx, p, ws, nq, k, metric, ids_dev, dist_dev, st);
+}
+
+extern "C" int lpq_search_overflow_stats(const lpq_index *idx, int64_t nq, int k, int metric, const void *workspace_dev,
+                                         int64_t *redone_queries, int64_t *max_region_fill)
+{
+    (void)metric;
+    if (!idx || !workspace_dev || !redone_queries || !max_region_fill || nq < 1 || k < 1) return fail(LPQ_EINVAL, "bad argument");
+    *redone_queries = 0;
+    *max_region_fill = 0;
+    const Plan p = make_plan(idx, nq, k);
+    if (p.mode != PLAN_MFMA_COLLECT) return LPQ_OK;
+    HIP_TRY(hipDeviceSynchronize());
+    std::vector<int32_t> over((size_t)nq), cnt((size_t)nq * p.SS);
+    const char *ws = static_cast<const char *>(workspace_dev);
+    HIP_TRY(hipMemcpy(over.data(), ws + p.off_over, over.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(cnt.data(), ws + p.off_ccnt, cnt.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+    for (int32_t v : over) *redone_queries += v != 0;
+    for (int32_t v : cnt) if (v > *max_region_fill) *max_region_fill = v;
+    return LPQ_OK;
 }
 
 extern "C" int lpq_search_i8(const lpq_index *idx, const int8_t *qcodes_dev, int64_t nq, int64_t ld, int k,

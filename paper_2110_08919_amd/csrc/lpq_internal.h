@@ -108,9 +108,12 @@ struct SearchArgs {
 
 // Generic kernel: one workgroup per (query, corpus split); any d_pad (multiple of 32), any k.
 // Writes lists[(q * S + s) * k + r], sorted ascending, CAND_NONE-filled.
-// only (optional): int[nq]; workgroups of queries with only[q] == 0 return at once.
 hipError_t launch_search_generic(const SearchArgs &a, int64_t row0, int64_t row1, int S,
-                                 const cand_t *seeds, cand_t *lists, hipStream_t st, const int32_t *only = nullptr);
+                                 const cand_t *seeds, cand_t *lists, hipStream_t st);
+// The same for the *qcount queries listed in qlist (device memory, written by an earlier kernel):
+// a fixed grid shares out the (query, split) pairs; lists of other queries are left untouched.
+hipError_t launch_search_generic_list(const SearchArgs &a, int64_t row0, int64_t row1, int S, const int32_t *qlist,
+                                      const int32_t *qcount, cand_t *lists, hipStream_t st);
 
 // Matrix-core kernels.  search_mfma.hip keeps the k best of a query in registers (k <= 16) and
 // has a seeding pass; search_mfma_lds.hip keeps them in LDS (larger k).  launch_search_mfma
@@ -122,17 +125,17 @@ hipError_t launch_search_mfma(const SearchArgs &a, int64_t row0, int64_t row1, i
                               cand_t *lists, hipStream_t st);
 hipError_t launch_search_mfma_lds(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds,
                                   cand_t *lists, hipStream_t st);
-// Seeding pass of the register variant: group maxima gmax[nq_pad][2*S*SEG] over rows
-// [row0, row1) (all of them real items), then seeds[q] = bound from the k-th largest.
+// Seeding pass: group maxima gmax[nq_pad][G], G = mfma_seed_groups(S, SEG, rsplit), over the sampled
+// rows (all of them real items), then seeds[q] = bound from the k-th largest group maximum.
 int mfma_seed_segments(int S, int k, bool rsplit);
 int mfma_seed_groups(int S, int SEG, bool rsplit);        // = G, entries per query in gmax
 int mfma_queries_per_workgroup(int64_t nq, int d_pad, bool wide = false);   // query tile; wide: 128 queries per wave
 bool mfma_collect_wide(int64_t nq, int d_pad);           // collecting mode may use 128 queries per wave
 bool mfma_row_split(int64_t nq, int d_pad);              // few queries: waves split rows, share queries
-// With stride > 0 the pass reads S chunks of chunk_rows rows (a multiple of 128, <= stride) whose
-// first rows are row0, row0 + stride, ...: a sample spread over the corpus.
+// With stage_stride > 0 (a multiple of 128) the pass is a systematic sample of [row0, row1): one
+// stage (64 rows; 128 in row-split launches) every stage_stride rows, stages_per_split per split.
 hipError_t launch_seed_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S, int SEG, int32_t *gmax,
-                            hipStream_t st, int64_t stride = 0, int64_t chunk_rows = 0);
+                            hipStream_t st, int64_t stage_stride = 0, int stages_per_split = 0);
 // Collecting scan (k <= 128): thresholds stay at seeds[q] (required); every candidate beating its
 // query's seed is appended to cbuf[(q * SS + region) * Cs + ...], SS = mfma_collect_regions(S, rsplit),
 // and ccnt[q * SS + region] = number offered (entries beyond Cs were dropped).
@@ -142,12 +145,15 @@ hipError_t launch_collect_mfma(const SearchArgs &a, int64_t row0, int64_t row1, 
                                cand_t *cbuf, int32_t *ccnt, int Cs, hipStream_t st);
 // Per query: if no region overflowed and at most 4096 candidates were collected, sort them, write
 // the k best as the final result and set over[q] = 0; otherwise set over[q] = 1 and write nothing.
-// expected_candidates (per query, 0 = unknown) picks the one-wave-per-query kernel when small; that
-// kernel flags queries with more than 256 candidates as well.
+// expected_candidates (per query, 0 = unknown) picks the one-wave-per-query kernel when small (k <= 32,
+// SS <= 64); that kernel takes any number of candidates the regions hold.
+// Flagged queries are also appended to qlist[atomicAdd(qcount, 1)] (qcount must be zero before).
 hipError_t launch_collect_select(const cand_t *cbuf, const int32_t *ccnt, int64_t nq, int SS, int Cs, int k,
-                                 int32_t *over, int32_t *ids, int32_t *dists, const int32_t *qnorms, int metric,
-                                 hipStream_t st, int expected_candidates = 0);
-hipError_t launch_seed_finalize(const int32_t *gmax, int64_t nq, int G, int k, cand_t *seeds, hipStream_t st);
+                                 int32_t *over, int32_t *qlist, int32_t *qcount, int32_t *ids, int32_t *dists,
+                                 const int32_t *qnorms, int metric, hipStream_t st, int expected_candidates = 0);
+// zero_word (optional): one int the kernel also sets to 0 (the counter of the redo list).
+hipError_t launch_seed_finalize(const int32_t *gmax, int64_t nq, int G, int k, cand_t *seeds, hipStream_t st,
+                                int32_t *zero_word = nullptr);
 
 // Merge P lists of k candidates per query into one (merge.hip).  If ids/dists are given the
 // result is final: ids, and dist = key + qnorm (L2SQ) or -key/2 (IP).  Otherwise the merged
@@ -157,7 +163,7 @@ hipError_t launch_seed_finalize(const int32_t *gmax, int64_t nq, int G, int k, c
 hipError_t launch_merge(const cand_t *lists, int64_t nq, int P, int k, const cand_t *extra_lists,
                         cand_t *out_lists, cand_t *seeds_out, int32_t *ids, int32_t *dists,
                         const int32_t *qnorms, int metric, hipStream_t st, bool sorted_lists = false,
-                        const int32_t *only = nullptr);   // only: as in launch_search_generic
+                        const int32_t *only = nullptr);   // only (optional): int[nq]; queries with only[q] == 0 are skipped
 int merge_max_lists(int k);
 // First pass of a two-pass merge: groups of `group` consecutive lists of each query are merged
 // into out_lists[q][ceil(P/group)][k].

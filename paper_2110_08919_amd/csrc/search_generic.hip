@@ -13,30 +13,18 @@ namespace {
 constexpr int GEN_THREADS = 256;
 constexpr int GEN_ROWS = GEN_THREADS / 8;  // rows per step: 8 lanes share a row
 
-__global__ __launch_bounds__(GEN_THREADS) void search_generic_kernel(
-    SearchArgs a, int64_t row0, int64_t row1, int S, int64_t split_rows, const cand_t *__restrict__ seeds,
-    cand_t *__restrict__ lists, int cap, const int32_t *__restrict__ only)
+// One (query, corpus split) pair by the whole workgroup; must be reached by all its threads.
+__device__ __forceinline__ void generic_scan(const SearchArgs &a, int64_t rs, int64_t re, int64_t q, const cand_t *seeds,
+                                             cand_t *out, int cap, cand_t *buf, uint4 *qs, int *s_count, cand_t *s_thr)
 {
-    extern __shared__ __align__(16) unsigned char smem[];
-    cand_t *buf = reinterpret_cast<cand_t *>(smem);
-    uint4 *qs = reinterpret_cast<uint4 *>(buf + cap);
-    __shared__ int s_count;
-    __shared__ cand_t s_thr;
-
-    const int64_t q = blockIdx.x / S;
-    if (only && !only[q]) return;   // same for the whole workgroup
-    const int s = blockIdx.x % S;
     const int chunks = a.d_pad >> 4;  // 16-byte chunks per row
-    const int64_t rs = row0 + (int64_t)s * split_rows;
-    const int64_t re = (rs + split_rows < row1) ? rs + split_rows : row1;
     const bool l2 = a.metric == LPQ_METRIC_L2SQ;
-
     for (int c = threadIdx.x; c < chunks; c += GEN_THREADS)
         qs[c] = reinterpret_cast<const uint4 *>(a.qcodes + q * a.d_pad)[c];
     for (int i = threadIdx.x; i < cap; i += GEN_THREADS) buf[i] = CAND_NONE;
     if (threadIdx.x == 0) {
-        s_count = 0;
-        s_thr = seeds ? seeds[q] : CAND_NONE;
+        *s_count = 0;
+        *s_thr = seeds ? seeds[q] : CAND_NONE;
     }
     __syncthreads();
 
@@ -60,17 +48,55 @@ __global__ __launch_bounds__(GEN_THREADS) void search_generic_kernel(
         if (sub == 0 && row < re) {
             const int32_t key = (l2 ? a.norms[row] : 0) - 2 * dot;  // see cand_t
             const cand_t c = make_cand(key, (uint32_t)row);
-            if (c < s_thr) {
-                const int pos = atomicAdd(&s_count, 1);
+            if (c < *s_thr) {
+                const int pos = atomicAdd(s_count, 1);
                 buf[pos] = c;
             }
         }
         __syncthreads();
-        block_compact_if_full(buf, cap, a.k, GEN_ROWS, &s_count, &s_thr);
+        block_compact_if_full(buf, cap, a.k, GEN_ROWS, s_count, s_thr);
     }
     block_bitonic_sort(buf, cap);
-    cand_t *out = lists + ((int64_t)q * S + s) * a.k;
     for (int i = threadIdx.x; i < a.k; i += GEN_THREADS) out[i] = buf[i];
+    __syncthreads();   // buf and qs are free again
+}
+
+__global__ __launch_bounds__(GEN_THREADS) void search_generic_kernel(
+    SearchArgs a, int64_t row0, int64_t row1, int S, int64_t split_rows, const cand_t *__restrict__ seeds,
+    cand_t *__restrict__ lists, int cap)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    cand_t *buf = reinterpret_cast<cand_t *>(smem);
+    uint4 *qs = reinterpret_cast<uint4 *>(buf + cap);
+    __shared__ int s_count;
+    __shared__ cand_t s_thr;
+    const int64_t q = blockIdx.x / S;
+    const int s = blockIdx.x % S;
+    const int64_t rs = row0 + (int64_t)s * split_rows;
+    const int64_t re = (rs + split_rows < row1) ? rs + split_rows : row1;
+    generic_scan(a, rs, re, q, seeds, lists + ((int64_t)q * S + s) * a.k, cap, buf, qs, &s_count, &s_thr);
+}
+
+// The same scan for a LIST of queries (the ones a collecting scan could not finish): the
+// workgroups of a fixed-size grid share out the (listed query, split) pairs, so a handful of
+// queries is spread over the whole chip and an empty list costs one tiny launch.
+__global__ __launch_bounds__(GEN_THREADS) void search_generic_list_kernel(
+    SearchArgs a, int64_t row0, int64_t row1, int S, int64_t split_rows, const int32_t *__restrict__ qlist,
+    const int32_t *__restrict__ qcount, cand_t *__restrict__ lists, int cap)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    cand_t *buf = reinterpret_cast<cand_t *>(smem);
+    uint4 *qs = reinterpret_cast<uint4 *>(buf + cap);
+    __shared__ int s_count;
+    __shared__ cand_t s_thr;
+    const int64_t items = (int64_t)(*qcount) * S;           // same for every thread of the grid
+    for (int64_t item = blockIdx.x; item < items; item += gridDim.x) {
+        const int64_t q = qlist[item / S];
+        const int s = (int)(item % S);
+        const int64_t rs = row0 + (int64_t)s * split_rows;
+        const int64_t re = (rs + split_rows < row1) ? rs + split_rows : row1;
+        generic_scan(a, rs, re, q, nullptr, lists + ((int64_t)q * S + s) * a.k, cap, buf, qs, &s_count, &s_thr);
+    }
 }
 
 // 64-bit minimum over the wave; every lane gets the result.
@@ -127,60 +153,60 @@ __global__ __launch_bounds__(256) void merge_kernel(
     if (seeds_out && threadIdx.x == 0) seeds_out[q] = buf[k - 1];
 }
 
-// Last step of the collecting scan for small k and few candidates, one WAVE per query (no
-// workgroup barriers): lane r gathers region r into the wave's LDS buffer, every lane then keeps
-// up to 4 candidates in registers and the wave takes the smallest k times.  A query with an
-// overflowed region, more than 256 candidates or fewer than k is flagged in over[] instead.
-constexpr int WSEL_CAP = 256;
+// Last step of the collecting scan for small k (<= 32) and at most 64 regions, one WAVE per query
+// and no LDS: lane r owns region r.  In each pass every lane loads up to 8 more candidates of its
+// region into registers; together with the k best kept so far (lane i keeps the i-th best) the
+// wave takes the smallest k times, which become the kept ones of the next pass.  Any number of
+// candidates the regions can hold is handled; a query with an overflowed region or fewer than k
+// candidates is flagged in over[] instead.
 __global__ __launch_bounds__(256) void collect_select_wave_kernel(
     const cand_t *__restrict__ cbuf, const int32_t *__restrict__ ccnt, int64_t nq, int SS, int Cs, int k,
-    int32_t *__restrict__ over, int32_t *__restrict__ ids, int32_t *__restrict__ dists,
-    const int32_t *__restrict__ qnorms, int metric)
+    int32_t *__restrict__ over, int32_t *__restrict__ qlist, int32_t *__restrict__ qcount,
+    int32_t *__restrict__ ids, int32_t *__restrict__ dists, const int32_t *__restrict__ qnorms, int metric)
 {
-    __shared__ cand_t sbuf[4][WSEL_CAP];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t q = (int64_t)blockIdx.x * 4 + wave;
     if (q >= nq) return;                                   // wave-uniform
-    cand_t *wbuf = sbuf[wave];
     const int c = (lane < SS) ? ccnt[q * SS + lane] : 0;
     const bool bad = c > Cs || c < 0;
-    const int cl = bad ? 0 : c;
-    int incl = cl;                                         // inclusive prefix sum over the lanes
+    int total = bad ? 0 : c, most = total;
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int t = __shfl_up(incl, o, 64);
-        if (lane >= o) incl += t;
+    for (int o = 32; o > 0; o >>= 1) {
+        total += __shfl_xor(total, o, 64);
+        const int t = __shfl_xor(most, o, 64);
+        most = t > most ? t : most;
     }
-    const int M = __shfl(incl, 63, 64);
-    if (__ballot(bad) || M > WSEL_CAP || M < k) {
-        if (lane == 0) over[q] = 1;
+    if (__ballot(bad) || total < k) {
+        if (lane == 0) { over[q] = 1; qlist[atomicAdd(qcount, 1)] = (int32_t)q; }
         return;
     }
-    const int off = incl - cl;
-    for (int j = 0; j < cl; ++j) wbuf[off + j] = cbuf[((size_t)q * SS + lane) * Cs + j];
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    cand_t v[4];
+    const cand_t *mine = cbuf + ((size_t)q * SS + (lane < SS ? lane : 0)) * Cs;
+    cand_t keep = CAND_NONE;                               // lane i: the i-th best so far
+    constexpr int E = 8;                                   // candidates a lane takes per pass
+    for (int p0 = 0; p0 < most; p0 += E) {                 // wave-uniform trip count
+        cand_t v[E + 1];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] = (e * 64 + lane < M) ? wbuf[e * 64 + lane] : CAND_NONE;
-    for (int r = 0; r < k; ++r) {
-        cand_t mine = v[0];
+        for (int e = 0; e < E; ++e) v[e] = (p0 + e < c && !bad) ? mine[p0 + e] : CAND_NONE;
+        v[E] = keep;
+        cand_t next = CAND_NONE;
+        for (int r = 0; r < k; ++r) {
+            cand_t m = v[0];
 #pragma unroll
-        for (int e = 1; e < 4; ++e) mine = v[e] < mine ? v[e] : mine;
-        const cand_t mn = wave_min_cand(mine);
-        const int win = __ffsll((unsigned long long)__ballot(mine == mn)) - 1;
-        if (lane == win) {
-            emit_result(mn, q * k + r, q, ids, dists, qnorms, metric);
-            bool done = false;
+            for (int e = 1; e <= E; ++e) m = v[e] < m ? v[e] : m;
+            const cand_t mn = wave_min_cand(m);
+            if (lane == r) next = mn;
+            const int win = __ffsll((unsigned long long)__ballot(m == mn)) - 1;
+            bool done = lane != win || mn == CAND_NONE;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
+            for (int e = 0; e <= E; ++e) {
                 const bool hit = !done && v[e] == mn;
                 v[e] = hit ? CAND_NONE : v[e];
                 done = done || hit;
             }
         }
+        keep = next;
     }
+    if (lane < k) emit_result(keep, q * k + lane, q, ids, dists, qnorms, metric);
     if (lane == 0) over[q] = 0;
 }
 
@@ -189,8 +215,8 @@ __global__ __launch_bounds__(256) void collect_select_wave_kernel(
 // than k is flagged in over[] instead and left to the generic kernel.
 __global__ __launch_bounds__(256) void collect_select_kernel(
     const cand_t *__restrict__ cbuf, const int32_t *__restrict__ ccnt, int SS, int Cs, int k, int maxc,
-    int32_t *__restrict__ over, int32_t *__restrict__ ids, int32_t *__restrict__ dists,
-    const int32_t *__restrict__ qnorms, int metric)
+    int32_t *__restrict__ over, int32_t *__restrict__ qlist, int32_t *__restrict__ qcount,
+    int32_t *__restrict__ ids, int32_t *__restrict__ dists, const int32_t *__restrict__ qnorms, int metric)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     cand_t *buf = reinterpret_cast<cand_t *>(smem);            // [maxc]
@@ -221,7 +247,7 @@ __global__ __launch_bounds__(256) void collect_select_kernel(
     }
     const int M = tsum[255];
     if (s_bad || M > maxc || M < k) {
-        if (tid == 0) over[q] = 1;
+        if (tid == 0) { over[q] = 1; qlist[atomicAdd(qcount, 1)] = (int32_t)q; }
         return;
     }
     int run = tsum[tid] - local;
@@ -352,31 +378,43 @@ namespace {
 int merge_max_lists(int k) { return 4096 / k - 1; }
 
 hipError_t launch_collect_select(const cand_t *cbuf, const int32_t *ccnt, int64_t nq, int SS, int Cs, int k,
-                                 int32_t *over, int32_t *ids, int32_t *dists, const int32_t *qnorms, int metric,
-                                 hipStream_t st, int expected_candidates)
+                                 int32_t *over, int32_t *qlist, int32_t *qcount, int32_t *ids, int32_t *dists,
+                                 const int32_t *qnorms, int metric, hipStream_t st, int expected_candidates)
 {
     if (nq <= 0) return hipSuccess;
     const int maxc = 4096;
     if (SS < 1 || SS > 2048 || k > maxc) return hipErrorInvalidValue;
-    if (expected_candidates > 0 && expected_candidates <= WSEL_CAP / 2 && SS <= 64 && k <= 32) {
-        collect_select_wave_kernel<<<(unsigned)ceil_div(nq, (int64_t)4), 256, 0, st>>>(cbuf, ccnt, nq, SS, Cs, k, over, ids,
-                                                                                 dists, qnorms, metric);
+    if (expected_candidates > 0 && expected_candidates <= 256 && SS <= 64 && k <= 32) {
+        collect_select_wave_kernel<<<(unsigned)ceil_div(nq, (int64_t)4), 256, 0, st>>>(cbuf, ccnt, nq, SS, Cs, k, over, qlist,
+                                                                                 qcount, ids, dists, qnorms, metric);
         return hipGetLastError();
     }
     const size_t lds = (size_t)maxc * sizeof(cand_t) + (size_t)(SS + 1) * sizeof(int);
-    collect_select_kernel<<<(unsigned)nq, 256, lds, st>>>(cbuf, ccnt, SS, Cs, k, maxc, over, ids, dists, qnorms, metric);
+    collect_select_kernel<<<(unsigned)nq, 256, lds, st>>>(cbuf, ccnt, SS, Cs, k, maxc, over, qlist, qcount, ids, dists,
+                                                          qnorms, metric);
     return hipGetLastError();
 }
 
 hipError_t launch_search_generic(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds,
-                                 cand_t *lists, hipStream_t st, const int32_t *only)
+                                 cand_t *lists, hipStream_t st)
 {
     if (a.nq <= 0 || row1 <= row0) return hipSuccess;
     const int cap = next_pow2((2 * a.k > a.k + 2 * GEN_ROWS) ? 2 * a.k : a.k + 2 * GEN_ROWS);
     const int64_t split_rows = round_up(ceil_div(row1 - row0, S), GEN_ROWS);
     const size_t shmem = (size_t)cap * sizeof(cand_t) + (size_t)a.d_pad;
     search_generic_kernel<<<(unsigned)(a.nq * S), GEN_THREADS, shmem, st>>>(a, row0, row1, S, split_rows,
-                                                                              seeds, lists, cap, only);
+                                                                              seeds, lists, cap);
+    return hipGetLastError();
+}
+
+hipError_t launch_search_generic_list(const SearchArgs &a, int64_t row0, int64_t row1, int S, const int32_t *qlist,
+                                      const int32_t *qcount, cand_t *lists, hipStream_t st)
+{
+    if (a.nq <= 0 || row1 <= row0) return hipSuccess;
+    const int cap = next_pow2((2 * a.k > a.k + 2 * GEN_ROWS) ? 2 * a.k : a.k + 2 * GEN_ROWS);
+    const int64_t split_rows = round_up(ceil_div(row1 - row0, S), GEN_ROWS);
+    const size_t shmem = (size_t)cap * sizeof(cand_t) + (size_t)a.d_pad;
+    search_generic_list_kernel<<<2048, GEN_THREADS, shmem, st>>>(a, row0, row1, S, split_rows, qlist, qcount, lists, cap);
     return hipGetLastError();
 }
 

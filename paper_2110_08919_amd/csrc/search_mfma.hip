@@ -59,6 +59,7 @@ struct MfmaIo {     // what a launch reads and writes besides the corpus and the
     int Cs;
     int64_t split_stride;       // first row of split s is row0 + s * split_stride; 0: splits follow each other
     int64_t split_stride_rows;  // with a stride: rows per split
+    int64_t stage_stride;       // seeding pass: first rows of consecutive stages are this far apart (0: adjacent)
 };
 
 struct WaveQ {      // pointers into the wave's private LDS region
@@ -259,8 +260,15 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     const int wk = (a.work_order != 3 && b < per * 8) ? (b % 8) * per + b / 8 : b;
     const int s = (a.work_order == 2) ? wk % S : wk / qtiles;
     const int qt = (a.work_order == 2) ? wk / S : wk % qtiles;
-    const int64_t rs = row0 + (int64_t)s * o.split_stride;
-    const int64_t re = (rs + split_rows < row1) ? rs + split_rows : row1;
+    // Stage st of this split starts at row rs + st * sstride.  Splits are contiguous row ranges with
+    // adjacent stages, except: a collecting scan deals the stages of the corpus round-robin to its
+    // splits (ILV), so that the candidates of a query spread evenly over the splits' regions however
+    // the corpus is ordered; and the seeding pass may sample one stage every stage_stride rows.
+    constexpr bool ILV = !SEED && KCAP == 0;
+    constexpr int RS_ = RSPLIT ? 32 * NW : 64;
+    const int64_t rs = ILV ? row0 + (int64_t)s * RS_ : row0 + (int64_t)s * o.split_stride;
+    const int64_t re = ILV ? row1 : ((rs + split_rows < row1) ? rs + split_rows : row1);
+    const int64_t sstride = ILV ? (int64_t)S * RS_ : ((SEED && o.stage_stride) ? o.stage_stride : RS_);
 
     unsigned char *ring = smem;
     int *aux = (int *)(smem + NST * STAGE_BYTES);
@@ -301,11 +309,17 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
             B[nb][ks] = *reinterpret_cast<const v4i *>(a.qcodes + (q_first + nb * 32 + col) * a.d_pad + ks * 32 + half * 16);
-    int thr[NB], gm[NB];
+    // Seeding pass: running maxima per group of rows, GR groups per lane.  GR = 16 (one group per
+    // accumulator, so that neighbouring rows fall into different groups) gives tighter bounds on a
+    // corpus stored in sorted order but measured 50 % slower overall on the benchmark workload (the
+    // extra registers spill in the 128-queries-per-wave kernel), so one group per lane half it is.
+    constexpr int GR = 1;
+    int thr[NB], gm[NB][GR];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         thr[nb] = SEED ? INT32_MAX : w.thrE[nb * 32 + col];
-        gm[nb] = INT32_MIN;
+#pragma unroll
+        for (int r = 0; r < GR; ++r) gm[nb][r] = INT32_MIN;
     }
     int qcnt = 0;
     int a_off[KS];   // byte offset of this lane's A chunk of k-step ks inside a 32-row block of a stage
@@ -330,7 +344,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
 #define LPQ_ISSUE(ST)                                                                                   \
     do {                                                                                                \
         const int st_ = (ST);                                                                           \
-        const int64_t r0_ = rs + (int64_t)st_ * RS;                                                     \
+        const int64_t r0_ = rs + (int64_t)st_ * sstride;                                                \
         const int ring_slot_ = st_ % NST;                                                               \
         const int8_t *src_ = a.codes + r0_ * (32 * KS);                                                 \
         _Pragma("unroll") for (int j = 0; j < IPW; ++j)                                                 \
@@ -376,9 +390,13 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
         _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                               \
             _Pragma("unroll") for (int nb = 0; nb < NB; ++nb)                                           \
                 acc[nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(AREG[ks], B[nb][ks], ks == 0 ? CREG : acc[nb], 0, 0, 0); \
-        const int rowbase = (int)(rs + (int64_t)(TT) * RS + (BLK) * 32);                                \
+        const int rowbase = (int)(rs + (int64_t)(TT) * sstride + (BLK) * 32);                           \
         _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) {                                             \
             const v16i v = acc[nb];                                                                     \
+            if (SEED && GR == 16) {                                                                     \
+                _Pragma("unroll") for (int r = 0; r < GR; ++r) gm[nb][r] = max(gm[nb][r], v[r]);        \
+                continue;                                                                               \
+            }                                                                                           \
             int m = max(max(v[0], v[1]), v[2]);                                                         \
             m = max(max(m, v[3]), v[4]);                                                                \
             m = max(max(m, v[5]), v[6]);                                                                \
@@ -388,7 +406,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
             m = max(max(m, v[13]), v[14]);                                                              \
             m = max(m, v[15]);                                                                          \
             if (SEED) {                                                                                 \
-                gm[nb] = max(gm[nb], m);                                                                \
+                gm[nb][0] = max(gm[nb][0], m);                                                          \
                 continue;                                                                               \
             }                                                                                           \
             bool trip = m >= thr[nb];                                                                   \
@@ -417,16 +435,27 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
         }                                                                                               \
     } while (0)
 
-    const int T = (re > rs) ? (int)((re - rs + RS - 1) / RS) : 0;
+    int T = (re > rs) ? (int)((re - rs + RS - 1) / RS) : 0;
+    if (ILV) {   // stages s, s + S, s + 2S, ... of the ceil(rows / RS) stages of the corpus
+        const int64_t all = (row1 - row0 + RS - 1) / RS;
+        T = (all > s) ? (int)((all - s + S - 1) / S) : 0;
+    } else if (SEED && o.stage_stride) {   // split_rows / RS stages, as far as their first rows are real items
+        const int64_t left = (row1 > rs) ? (row1 - rs + sstride - 1) / sstride : 0;
+        T = (int)(left < split_rows / RS ? left : split_rows / RS);
+    }
 
-    // Seeding pass: group maxima of segment g of this split go to gmax[q][(s*SEG + g)*2 + half].
-    const int G = S * SEG * 2 * (RSPLIT ? NW : 1);
+    // Seeding pass: the GR group maxima of (segment g of this split, lane half) go to
+    // gmax[q][(((s*SEG + g) [* NW + wave]) * 2 + half) * GR + r].
+    const int G = S * SEG * 2 * GR * (RSPLIT ? NW : 1);
 #define LPQ_FLUSH_SEGMENT(SEGIDX)                                                                       \
     do {                                                                                                \
         _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) {                                             \
-            gmax[(size_t)(q_first + nb * 32 + col) * G +                                                \
-                 (((size_t)s * SEG + (SEGIDX)) * (RSPLIT ? NW : 1) + (RSPLIT ? wave : 0)) * 2 + half] = gm[nb]; \
-            gm[nb] = INT32_MIN;                                                                         \
+            int32_t *dst_ = gmax + (size_t)(q_first + nb * 32 + col) * G +                              \
+                ((((size_t)s * SEG + (SEGIDX)) * (RSPLIT ? NW : 1) + (RSPLIT ? wave : 0)) * 2 + half) * GR; \
+            _Pragma("unroll") for (int r = 0; r < GR; ++r) {                                            \
+                dst_[r] = gm[nb][r];                                                                    \
+                gm[nb][r] = INT32_MIN;                                                                  \
+            }                                                                                           \
         }                                                                                               \
     } while (0)
     if (SEED) {   // segments this split never reaches keep the neutral value
@@ -563,9 +592,10 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
 // the value with wave-wide counts.
 template <int E>
 __global__ __launch_bounds__(256) void seed_finalize_kernel(const int32_t *__restrict__ gmax, int64_t nq, int G, int k,
-                                                            cand_t *__restrict__ seeds)
+                                                            cand_t *__restrict__ seeds, int32_t *__restrict__ zero_word)
 {
     const int lane = threadIdx.x & 63;
+    if (zero_word && blockIdx.x == 0 && threadIdx.x == 0) *zero_word = 0;
     const int64_t q = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (q >= nq) return;                                   // wave-uniform
     int v[E];
@@ -743,7 +773,7 @@ hipError_t launch_collect_mfma(const SearchArgs &a, int64_t row0, int64_t row1, 
 
 int mfma_collect_regions(int S, bool rsplit) { return S * (rsplit ? 4 : 1); }
 
-int mfma_seed_groups(int S, int SEG, bool rsplit) { return 2 * S * SEG * (rsplit ? 4 : 1); }
+int mfma_seed_groups(int S, int SEG, bool rsplit) { return S * SEG * (rsplit ? 8 : 2); }
 
 int mfma_seed_segments(int S, int k, bool rsplit)
 {
@@ -754,30 +784,35 @@ int mfma_seed_segments(int S, int k, bool rsplit)
     return seg;
 }
 
-// The seeding pass reads S chunks of `chunk_rows` rows whose first rows are `stride` apart
-// (stride = 0: one contiguous range), so the sample is spread over the corpus.
+// With stage_stride > 0 the seeding pass is a systematic sample: it reads one stage (64 rows, 128
+// in row-split launches) every stage_stride rows, stages_per_split of them per split, so a corpus
+// stored in some order (by cluster, by norm) is sampled evenly.  stage_stride = 0: rows [row0, row1).
 hipError_t launch_seed_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S, int SEG, int32_t *gmax,
-                            hipStream_t st, int64_t stride, int64_t chunk_rows)
+                            hipStream_t st, int64_t stage_stride, int stages_per_split)
 {
     if (!mfma_collect_supported(a.d_pad, a.k) || !gmax) return hipErrorInvalidValue;
     MfmaIo o = {};
     o.gmax = gmax; o.SEG = SEG;
-    if (stride) {
-        if (chunk_rows <= 0 || chunk_rows > stride || chunk_rows % 128) return hipErrorInvalidValue;
-        o.split_stride = stride; o.split_stride_rows = chunk_rows;
+    if (stage_stride) {
+        const int rs_rows = a.rsplit ? 128 : 64;
+        if (stages_per_split < 1 || stage_stride < rs_rows || stage_stride % 128) return hipErrorInvalidValue;
+        o.stage_stride = stage_stride;
+        o.split_stride = stage_stride * stages_per_split;
+        o.split_stride_rows = (int64_t)rs_rows * stages_per_split;
     }
     return launch_any(a, row0, row1, S, o, st);
 }
 
-hipError_t launch_seed_finalize(const int32_t *gmax, int64_t nq, int G, int k, cand_t *seeds, hipStream_t st)
+hipError_t launch_seed_finalize(const int32_t *gmax, int64_t nq, int G, int k, cand_t *seeds, hipStream_t st,
+                                int32_t *zero_word)
 {
     if (nq <= 0) return hipSuccess;
     if (G > 2048) return hipErrorInvalidValue;
     const unsigned blocks = (unsigned)ceil_div(nq, (int64_t)4);
-    if (G <= 256) seed_finalize_kernel<4><<<blocks, 256, 0, st>>>(gmax, nq, G, k, seeds);
-    else if (G <= 512) seed_finalize_kernel<8><<<blocks, 256, 0, st>>>(gmax, nq, G, k, seeds);
-    else if (G <= 1024) seed_finalize_kernel<16><<<blocks, 256, 0, st>>>(gmax, nq, G, k, seeds);
-    else seed_finalize_kernel<32><<<blocks, 256, 0, st>>>(gmax, nq, G, k, seeds);
+    if (G <= 256) seed_finalize_kernel<4><<<blocks, 256, 0, st>>>(gmax, nq, G, k, seeds, zero_word);
+    else if (G <= 512) seed_finalize_kernel<8><<<blocks, 256, 0, st>>>(gmax, nq, G, k, seeds, zero_word);
+    else if (G <= 1024) seed_finalize_kernel<16><<<blocks, 256, 0, st>>>(gmax, nq, G, k, seeds, zero_word);
+    else seed_finalize_kernel<32><<<blocks, 256, 0, st>>>(gmax, nq, G, k, seeds, zero_word);
     return hipGetLastError();
 }
 

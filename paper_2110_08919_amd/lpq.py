@@ -66,6 +66,7 @@ def lib() -> C.CDLL:
             "lpq_search_f32": (i32, [vp, i64, i64, vp, i64, i64, i32, i32, i32, vp, vp, vp, C.c_size_t, vp]),
             "lpq_gather_dist_i8": (i32, [vp, vp, i64, i64, vp, i32, i32, vp, vp]),
             "lpq_rerank_f32": (i32, [vp, i64, i64, vp, i64, i64, i32, vp, i32, i32, i32, vp, vp, vp]),
+            "lpq_search_overflow_stats": (i32, [vp, i64, i32, i32, vp, C.POINTER(i64), C.POINTER(i64)]),
             "lpq_set_tuning": (i32, [i32, i64]),
             "lpq_profile_enable": (i32, [i32]),
             "lpq_profile_read": (i32, [C.POINTER(i64), C.POINTER(C.c_double)]),
@@ -212,6 +213,12 @@ class Index:
         _check(lib().lpq_gather_dist_i8(self._h, qp, nq, ld, ip, ids.shape[1], METRIC[metric], out.data_ptr(),
                                         _stream()))
         return out
+
+    def overflow_stats(self, nq: int, k: int, metric, workspace: torch.Tensor):
+        """(queries redone by the generic kernel, largest region fill) of the last search in `workspace`."""
+        a, b = C.c_int64(0), C.c_int64(0)
+        _check(lib().lpq_search_overflow_stats(self._h, nq, k, METRIC[metric], workspace.data_ptr(), C.byref(a), C.byref(b)))
+        return a.value, b.value
 
     def search(self, q: torch.Tensor, k: int, metric="l2sq", out=None, workspace=None):
         """q fp32 [nq, d] or int8 codes [nq, d] on the device -> (ids int32, dists int32) [nq, k]."""

@@ -489,3 +489,25 @@ def test_search_can_be_captured_in_a_graph(lpq, oracle, name, n, nq, k):
         step()                                   # eager work between the replays
         torch.cuda.synchronize()
         assert torch.equal(ids, ref_ids) and torch.equal(dists, ref_d)
+
+
+@pytest.mark.parametrize("order", ["norm", "first_dims"])
+def test_collecting_scan_on_a_corpus_stored_in_sorted_order(lpq, oracle, order):
+    """Similar items next to each other (sorted by norm, or lexicographically): the sampled bound is
+    looser and candidates bunch up, but the scan deals its stages round-robin to the splits, so
+    the regions fill evenly; results stay exact and at most a few queries need the exact redo."""
+    w = synth.SKEWED_1M.scaled(n=300_000, nq=600)
+    x, q = w.corpus("cuda"), w.queries("cuda")
+    key = (x * x).sum(1) if order == "norm" else x[:, 0] * 1000 + x[:, 1]
+    x = x[torch.argsort(key, stable=True)].contiguous()
+    quant = lpq.Quantizer(w.d, 8).calibrate(x, "minmax", "global")
+    index = lpq.Index(quant, w.n).add_f32(x)
+    ws = torch.empty(index.workspace_bytes(w.nq, 10, "l2sq") + 256, dtype=torch.uint8, device="cuda")
+    ids, dists = index.search(q, 10, "l2sq", workspace=ws)
+    torch.cuda.synchronize()
+    redone, fill = index.overflow_stats(w.nq, 10, "l2sq", ws)
+    oq = _oracle_quant(oracle, quant)
+    oids, od = oracle.search_i8(oq.encode(x.cpu().numpy()), oq.encode(q.cpu().numpy()), 10, "l2sq", threads=16)
+    assert np.array_equal(dists.cpu().numpy(), od) and np.array_equal(ids.cpu().numpy(), oids)
+    assert fill > 0, "the collecting variant was expected to run here"
+    assert redone <= w.nq // 10
