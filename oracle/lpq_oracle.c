@@ -44,7 +44,7 @@
 #include <omp.h>
 #endif
 
-enum { LPQO_MINMAX = 0, LPQO_ABSMAX = 1, LPQO_GAUSS = 2 };
+enum { LPQO_MINMAX = 0, LPQO_ABSMAX = 1, LPQO_GAUSS = 2, LPQO_QUANTILE = 3 };
 enum { LPQO_PER_FEATURE = 0, LPQO_GLOBAL = 1 };
 enum { LPQO_L2SQ = 0, LPQO_IP = 1 };
 
@@ -100,8 +100,31 @@ static void constants_from(int mode, double sigma_mult, double mn, double mx, do
     }
 }
 
+static int float_cmp(const void *a, const void *b)
+{
+    const float x = *(const float *)a, y = *(const float *)b;
+    return (x > y) - (x < y);
+}
+
+/* Outlier discard of Section 4.2 as a two-sided quantile clip: of the cnt values, sorted
+ * ascending, S_b is the one of rank floor(p (cnt-1)) and S_e the one of rank
+ * ceil((1-p)(cnt-1)) (ranks from 0; p = 0 gives the minimum and the maximum). */
+static void quantile_range(float *vals, int64_t cnt, double p, double *lo, double *hi)
+{
+    qsort(vals, (size_t)cnt, sizeof(float), float_cmp);
+    int64_t rl = (int64_t)floor(p * (double)(cnt - 1));
+    int64_t rh = (int64_t)ceil((1.0 - p) * (double)(cnt - 1));
+    if (rl < 0) rl = 0;
+    if (rh > cnt - 1) rh = cnt - 1;
+    *lo = (double)vals[rl];
+    *hi = (double)vals[rh];
+}
+
 /* Learn (k, S_b, S_e) and m for each of d features from n vectors x[j*ld + i].
- * Returns 0, or 1 if the data held a NaN/infinity (outputs then unspecified). */
+ * sigma_mult is the sigma multiplier of LPQO_GAUSS and the clipped fraction p per side
+ * (0 <= p < 0.5) of LPQO_QUANTILE, whose constants are then formed as for the [min, max]
+ * range.  Returns 0, or 1 if the data held a NaN/infinity or an allocation failed
+ * (outputs then unspecified). */
 int lpqo_calibrate(const float *x, int64_t n, int64_t ld, int d, int bits, int mode, int scope,
                    double sigma_mult, float *k, float *sb, float *se, float *m)
 {
@@ -113,6 +136,13 @@ int lpqo_calibrate(const float *x, int64_t n, int64_t ld, int d, int bits, int m
             double mu = s.sum / (double)n, ss = 0.0;
             for (int64_t j = 0; j < n; ++j) { double c = (double)x[j * ld + i] - mu; ss += c * c; }
             double sigma = sqrt(ss / (double)n);   /* maximum likelihood: divide by n */
+            if (mode == LPQO_QUANTILE) {
+                float *col = (float *)malloc((size_t)n * sizeof(float));
+                if (!col) return 1;
+                for (int64_t j = 0; j < n; ++j) col[j] = x[j * ld + i];
+                quantile_range(col, n, sigma_mult, &s.mn, &s.mx);
+                free(col);
+            }
             constants_from(mode, sigma_mult, s.mn, s.mx, s.amax, mu, sigma, &k[i], &sb[i], &se[i]);
         }
     } else {                                       /* Section 4.1: one mu, sigma for all dimensions */
@@ -124,6 +154,14 @@ int lpqo_calibrate(const float *x, int64_t n, int64_t ld, int d, int bits, int m
         for (int64_t j = 0; j < n; ++j)
             for (int i = 0; i < d; ++i) { double c = (double)x[j * ld + i] - mu; ss += c * c; }
         double sigma = sqrt(ss / cnt);
+        if (mode == LPQO_QUANTILE) {
+            float *all = (float *)malloc((size_t)n * (size_t)d * sizeof(float));
+            if (!all) return 1;
+            for (int64_t j = 0; j < n; ++j)
+                for (int i = 0; i < d; ++i) all[j * d + i] = x[j * ld + i];
+            quantile_range(all, n * (int64_t)d, sigma_mult, &s.mn, &s.mx);
+            free(all);
+        }
         float k0, sb0, se0;
         constants_from(mode, sigma_mult, s.mn, s.mx, s.amax, mu, sigma, &k0, &sb0, &se0);
         for (int i = 0; i < d; ++i) { k[i] = k0; sb[i] = sb0; se[i] = se0; }

@@ -21,7 +21,7 @@ MINMAX, ABSMAX, GAUSS = 0, 1, 2
 PER_FEATURE, GLOBAL = 0, 1
 L2SQ, IP = 0, 1
 
-_CALIB = {"minmax": MINMAX, "absmax": ABSMAX, "gauss": GAUSS}
+_CALIB = {"minmax": MINMAX, "absmax": ABSMAX, "gauss": GAUSS, "quantile": 3}
 _SCOPE = {"per_feature": PER_FEATURE, "global": GLOBAL}
 _METRIC = {"l2sq": L2SQ, "ip": IP}
 

@@ -366,3 +366,26 @@ def test_rerank_matches_numpy_sort_and_full_candidate_list_is_exact_search(oracl
     assert np.array_equal(ids, np.argsort(full, axis=1, kind="stable")[:, :5])
     short, sd = oracle.rerank_f32(x, q, cand[:, :3], 5, "ip")      # fewer candidates than k
     assert np.all(short[:, 3:] == -1) and np.all(np.isneginf(sd[:, 3:]))
+
+
+# ---------------------------------------------------------------- quantile clip (Section 4.2, outliers)
+@pytest.mark.parametrize("scope", ["per_feature", "global"])
+def test_quantile_clip_matches_numpy_order_statistics(oracle, scope):
+    """S_b / S_e of the quantile mode are order statistics: against numpy's sort; p = 0 is [min, max]."""
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((501, 7)).astype(np.float32)
+    x[3, 2] = 1e6                       # an outlier the clip must drop
+    x[:50, 5] = 0.25                    # duplicates
+    for p in (0.0, 0.01, 0.1, 0.25):
+        q = oracle.Quantizer(7, 8).calibrate(x, "quantile", scope, sigma_mult=p)
+        cols = [np.sort(x[:, i]) for i in range(7)] if scope == "per_feature" else [np.sort(x.ravel())] * 7
+        for i, c in enumerate(cols):
+            n = c.size
+            lo, hi = c[int(np.floor(p * (n - 1)))], c[int(np.ceil((1.0 - p) * (n - 1)))]
+            assert q.sb[i] == lo and q.se[i] == hi
+            assert q.k[i] == np.float32((np.float64(lo) + np.float64(hi)) / 2.0)
+        if p == 0.0:
+            mm = oracle.Quantizer(7, 8).calibrate(x, "minmax", scope)
+            assert np.array_equal(q.sb, mm.sb) and np.array_equal(q.se, mm.se) and np.array_equal(q.m, mm.m)
+    q = oracle.Quantizer(7, 8).calibrate(x, "quantile", "per_feature", sigma_mult=0.01)
+    assert q.se[2] < 10.0               # the outlier no longer sets the range
