@@ -52,8 +52,13 @@ enum {
  *           dimension (Section 4.2).
  *   GAUSS   S_b = mu - c sigma, S_e = mu + c sigma, k = mu, with the maximum-likelihood
  *           (1/n) estimates of a normal law per dimension; the paper uses c = 1
- *           (Section 3.2). */
-enum { LPQ_CALIB_MINMAX = 0, LPQ_CALIB_ABSMAX = 1, LPQ_CALIB_GAUSS = 2 };
+ *           (Section 3.2).
+ *   QUANTILE  the observed range with outliers discarded (Section 4.2 leaves the technique
+ *           open; here a two-sided quantile clip): of the values of the dimension sorted
+ *           ascending, S_b is the one of rank floor(p (n-1)) and S_e the one of rank
+ *           ceil((1-p)(n-1)) (ranks from 0), k = (S_b + S_e) / 2; p = 0 is MINMAX.  Exact
+ *           order statistics (radix selection), not estimates. */
+enum { LPQ_CALIB_MINMAX = 0, LPQ_CALIB_ABSMAX = 1, LPQ_CALIB_GAUSS = 2, LPQ_CALIB_QUANTILE = 3 };
 
 /* PER_FEATURE: constants per dimension (the superscripts i of Equation 1).
  * GLOBAL: one set of constants from all n*d values, for all dimensions (Section 4.1). */
@@ -73,7 +78,8 @@ int lpq_quantizer_create(lpq_quantizer **out, int d, int bits);
 void lpq_quantizer_destroy(lpq_quantizer *q);
 
 /* Learn the constants from n >= 1 vectors x_dev[n][ld] (fp32, device).  sigma_mult is c
- * above (GAUSS only; must be > 0).  Statistics are exact for MINMAX/ABSMAX; GAUSS sums in
+ * above (GAUSS; must be > 0) or the clipped fraction p per side (QUANTILE; 0 <= p < 0.5).
+ * Statistics are exact for MINMAX/ABSMAX/QUANTILE; GAUSS sums in
  * fp64 (two passes: mean, then centred second moment).  This call SYNCHRONISES `stream`
  * before returning, because its status depends on the data: LPQ_ENONFINITE if a NaN or
  * an infinity was seen (the quantizer then keeps its previous state). */

@@ -25,6 +25,10 @@ struct CalibScratch {
     double *csum, *css; // [d] column totals of the two passes
     double *mu;         // [d]
     float *mn, *mx;     // [d]
+    // quantile selection: per column (one column when pooled) and per target (low, high rank)
+    unsigned long long *qhist;   // [d][2][256] counts of the current byte among the still matching values
+    unsigned long long *qrank;   // [2][d] rank still to go inside the matching values
+    uint32_t *qprefix;           // [2][d] the bytes of the answer decided so far (sortable image)
 };
 
 CalibScratch carve(void *scratch, int d)
@@ -39,7 +43,11 @@ CalibScratch carve(void *scratch, int d)
     s.pmn = (float *)p;   p += sizeof(float) * G * d;
     s.pmx = (float *)p;   p += sizeof(float) * G * d;
     s.mn = (float *)p;    p += sizeof(float) * d;
-    s.mx = (float *)p;
+    s.mx = (float *)p;    p += sizeof(float) * d;
+    p = (char *)(((uintptr_t)p + 15) & ~uintptr_t(15));
+    s.qhist = (unsigned long long *)p;  p += sizeof(unsigned long long) * 512 * (size_t)d;
+    s.qrank = (unsigned long long *)p;  p += sizeof(unsigned long long) * 2 * (size_t)d;
+    s.qprefix = (uint32_t *)p;
     return s;
 }
 
@@ -194,6 +202,95 @@ __global__ __launch_bounds__(CAL_THREADS) void calib_stats_kernel(
         mn_io[c] = gmn;
         mx_io[c] = gmx;
         mu_out[c] = mu;
+    }
+}
+
+// ------------------------------------------------------------- quantile selection --
+// Exact order statistics by radix selection on an order-preserving 32-bit image of the floats:
+// four passes from the most significant byte; each pass counts, per column and per target
+// rank, the values that still match the bytes decided so far, then the bin holding the rank
+// fixes the next byte.
+__device__ __forceinline__ uint32_t float_sortable_u32(float f)
+{
+    const uint32_t u = (uint32_t)__float_as_int(f);
+    return (u >> 31) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float sortable_u32_float(uint32_t u)
+{
+    return __int_as_float((int)((u >> 31) ? (u & 0x7fffffffu) : ~u));
+}
+
+constexpr int QH_COLS = 16;   // columns per workgroup; 16 row lanes share them
+
+__global__ void quantile_init_kernel(int cols, unsigned long long rank_lo, unsigned long long rank_hi,
+                                     unsigned long long *qrank, uint32_t *qprefix, unsigned long long *qhist)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < cols) {
+        qrank[i] = rank_lo; qrank[cols + i] = rank_hi;
+        qprefix[i] = 0u; qprefix[cols + i] = 0u;
+    }
+    for (int j = i; j < cols * 512; j += gridDim.x * blockDim.x) qhist[j] = 0ull;
+}
+
+// pooled: all d columns count into column 0 (one set of constants for all dimensions).
+__global__ __launch_bounds__(256) void quantile_hist_kernel(
+    const float *__restrict__ x, int64_t n, int64_t ld, int d, int64_t rows_per_block, int shift, int first,
+    int pooled, int cols, const uint32_t *__restrict__ qprefix, unsigned long long *__restrict__ qhist)
+{
+    __shared__ uint32_t h[QH_COLS][2][256];
+    for (int i = threadIdx.x; i < QH_COLS * 512; i += 256) (&h[0][0][0])[i] = 0u;
+    __syncthreads();
+    const int cl = threadIdx.x & (QH_COLS - 1), rl = threadIdx.x / QH_COLS;
+    const int c = blockIdx.y * QH_COLS + cl;
+    const int cg = pooled ? 0 : c;
+    const uint32_t keep = first ? 0u : (0xFFFFFFFFu << (shift + 8));   // the bytes already decided
+    if (c < d) {
+        const uint32_t p0 = qprefix[cg], p1 = qprefix[cols + cg];
+        const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
+        const int64_t r1 = (r0 + rows_per_block < n) ? r0 + rows_per_block : n;
+        for (int64_t r = r0 + rl; r < r1; r += 256 / QH_COLS) {
+            const uint32_t key = float_sortable_u32(x[r * ld + c]);
+            const int b = (int)((key >> shift) & 255u);
+            if (((key ^ p0) & keep) == 0u) atomicAdd(&h[cl][0][b], 1u);
+            if (((key ^ p1) & keep) == 0u) atomicAdd(&h[cl][1][b], 1u);
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < QH_COLS * 512; i += 256) {
+        const uint32_t v = (&h[0][0][0])[i];
+        const int col = blockIdx.y * QH_COLS + i / 512;
+        if (v && col < d) atomicAdd(&qhist[(size_t)(pooled ? 0 : col) * 512 + (i % 512)], (unsigned long long)v);
+    }
+}
+
+// One thread per (column, target): the bin that holds the rank decides the next byte.
+__global__ void quantile_pick_kernel(int cols, int shift, unsigned long long *qrank, uint32_t *qprefix,
+                                     unsigned long long *qhist)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= cols * 2) return;
+    const int c = i >> 1, t = i & 1;
+    unsigned long long *hh = qhist + ((size_t)c * 2 + t) * 256;
+    unsigned long long rank = qrank[t * cols + c], before = 0ull;
+    int bin = 255;
+    for (int b = 0; b < 256; ++b) {
+        const unsigned long long v = hh[b];
+        if (rank < before + v) { bin = b; break; }
+        before += v;
+    }
+    for (int b = 0; b < 256; ++b) hh[b] = 0ull;
+    qrank[t * cols + c] = rank - before;
+    qprefix[t * cols + c] |= (uint32_t)bin << shift;
+}
+
+__global__ void quantile_finish_kernel(int d, int pooled, int cols, const uint32_t *qprefix, float *mn, float *mx)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c < d) {
+        const int cg = pooled ? 0 : c;
+        mn[c] = sortable_u32_float(qprefix[cg]);
+        mx[c] = sortable_u32_float(qprefix[cols + cg]);
     }
 }
 
@@ -411,7 +508,8 @@ __global__ __launch_bounds__(256) void item_aux_kernel(
 size_t calib_scratch_bytes(int d)
 {
     const size_t G = calib_blocks(d);
-    return G * d * (sizeof(double) + 2 * sizeof(float)) + (size_t)d * (3 * sizeof(double) + 2 * sizeof(float)) + 256;
+    return G * d * (sizeof(double) + 2 * sizeof(float)) + (size_t)d * (3 * sizeof(double) + 2 * sizeof(float)) + 256 +
+           (size_t)d * (512 * sizeof(unsigned long long) + 2 * sizeof(unsigned long long) + 2 * sizeof(uint32_t));
 }
 
 hipError_t launch_calibrate(const float *x, int64_t n, int64_t ld, int d, int bits, int mode, int scope,
@@ -428,6 +526,24 @@ hipError_t launch_calibrate(const float *x, int64_t n, int64_t ld, int d, int bi
     const int cblocks = (d + 63) / 64;
     calib_colreduce_kernel<<<cblocks, COL_WAVES * 64, 0, st>>>(G, d, s.pmn, s.pmx, s.psum, s.mn, s.mx, s.csum);
     calib_stats_kernel<<<1, CAL_THREADS, 0, st>>>(d, n, scope, s.mn, s.mx, s.csum, s.mu);
+    if (mode == LPQ_CALIB_QUANTILE) {
+        // the min/max pass above has checked the data; now the two order statistics per column
+        const int pooled = scope == LPQ_SCOPE_GLOBAL, cols = pooled ? 1 : d;
+        const double cnt = pooled ? (double)n * (double)d : (double)n;
+        double rl = floor(sigma_mult * (cnt - 1.0)), rh = ceil((1.0 - sigma_mult) * (cnt - 1.0));
+        if (rl < 0.0) rl = 0.0;
+        if (rh > cnt - 1.0) rh = cnt - 1.0;
+        quantile_init_kernel<<<(cols * 512 + 255) / 256, 256, 0, st>>>(cols, (unsigned long long)rl, (unsigned long long)rh,
+                                                                       s.qrank, s.qprefix, s.qhist);
+        const int64_t qrpb = rpb < 4096 ? 4096 : rpb;   // rows per workgroup: enough to amortise the LDS histograms
+        const dim3 grid((unsigned)ceil_div(n, qrpb), (unsigned)((d + QH_COLS - 1) / QH_COLS));
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = 24 - 8 * pass;
+            quantile_hist_kernel<<<grid, 256, 0, st>>>(x, n, ld, d, qrpb, shift, pass == 0, pooled, cols, s.qprefix, s.qhist);
+            quantile_pick_kernel<<<(cols * 2 + 255) / 256, 256, 0, st>>>(cols, shift, s.qrank, s.qprefix, s.qhist);
+        }
+        quantile_finish_kernel<<<(d + 255) / 256, 256, 0, st>>>(d, pooled, cols, s.qprefix, s.mn, s.mx);
+    }
     if (mode == LPQ_CALIB_GAUSS) {
         calib_reduce_kernel<2><<<G, CAL_THREADS, 0, st>>>(x, n, ld, d, rpb, s.mu, nullptr, nullptr, s.psum,
                                                           nonfinite_flag);

@@ -66,6 +66,24 @@ def test_calibrate_gauss_within_tolerance_then_codes_exact(lpq, oracle, scope):
     assert np.array_equal(norms.cpu().numpy(), onorms)
 
 
+@pytest.mark.parametrize("scope", ["per_feature", "global"])
+@pytest.mark.parametrize("wl,n", [("tiny", 10000), ("skewed", 30011), ("aniso", 7000)])
+def test_calibrate_quantile_clip_bit_exact(lpq, oracle, wl, n, scope):
+    """Outlier-discarding calibration: the GPU's radix selection returns exactly the oracle's order
+    statistics (duplicates, negative values, an injected outlier), for several clip fractions."""
+    base = {"tiny": synth.TINY, "skewed": synth.SKEWED_1M, "aniso": synth.ANISO_1M2}[wl]
+    x = base.scaled(n=n, nq=1).corpus().clone()
+    x[5, 3] = 1e7
+    x[6, 0] = -1e7
+    for p in (0.0, 0.001, 0.02, 0.3):
+        gq = lpq.Quantizer(x.shape[1], 8).calibrate(x.cuda(), "quantile", scope, sigma_mult=p)
+        oq = oracle.Quantizer(x.shape[1], 8).calibrate(x.numpy(), "quantile", scope, sigma_mult=p)
+        k, sb, se, m = gq.get_params()
+        assert np.array_equal(sb, oq.sb) and np.array_equal(se, oq.se)
+        assert np.array_equal(k, oq.k) and np.array_equal(m, oq.m)
+    assert float(se.max()) < 1e6 and float(sb.min()) > -1e6     # the outliers no longer set the range
+
+
 def test_calibrate_rejects_non_finite(lpq):
     x = synth.TINY.scaled(n=1000).corpus()
     gq = lpq.Quantizer(128, 8).calibrate(x.cuda(), "minmax", "per_feature")
