@@ -106,6 +106,20 @@ int lpq_encode(const lpq_quantizer *q, const float *x_dev, int64_t n, int64_t ld
  * hipMalloc, the int8 codes (rows padded to a multiple of 32 bytes) and the integer norms.
  * d <= 32 768 keeps every integer distance inside int32. */
 int lpq_index_create(lpq_index **out, const lpq_quantizer *q, int64_t capacity);
+
+/* The same index with two codes per byte, for quantizers of B <= 4 bits (the memory saving
+ * that Section 1 names as the first gain of a compact representation, taken below one byte per
+ * feature; Section 3.1 asks for the lowest precision that keeps relative positions):
+ * code c is stored as the nibble c + 8, feature 2j in the low and 2j + 1 in the high half
+ * of byte j, rows padded with code 0 to 64, 96, 128, 192 or 256 features.  A nibble holds
+ * -8 .. 7, so at B = 4 the top code +8 is stored as 7, for items and for queries alike (the
+ * way +128 becomes 127 at B = 8); distances and norms are those of the stored codes.
+ * Searches (lpq_search, lpq_search_i8) unpack in registers and give bit-identical results to
+ * an unpacked index holding the same saturated codes; they take k <= 16 and run the scan
+ * once per 64 queries, so they suit the small batches whose time is the corpus read.
+ * lpq_index_data returns the packed rows (*ld_codes = bytes per row); lpq_gather_dist_i8 does
+ * not take a packed index (LPQ_EINVAL).  LPQ_EINVAL: B > 4; LPQ_ERANGE: d > 256. */
+int lpq_index_create_packed(lpq_index **out, const lpq_quantizer *q, int64_t capacity);
 void lpq_index_destroy(lpq_index *idx);
 
 /* Append n items: fp32 vectors (encoded with the index's quantizer, Equation 1) or codes

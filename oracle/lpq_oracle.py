@@ -214,3 +214,27 @@ def recall(approx_ids, exact_ids) -> float:
     e = np.ascontiguousarray(exact_ids, np.int32)
     assert a.shape == e.shape and a.ndim == 2
     return float(_load().lpqo_recall(_p(a, C.c_int32), _p(e, C.c_int32), a.shape[0], a.shape[1]))
+
+
+def nibble_codes(codes):
+    """Codes as a 4-bit two's-complement field can hold them: values above 7 become 7, values
+    below -8 become -8 (Equation 1 at B = 4 reaches +8, one more than a nibble's range; the top
+    code is stored as the largest value that fits, as +128 is stored as 127 at B = 8)."""
+    c = np.asarray(codes, np.int8).astype(np.int32)
+    return np.minimum(np.maximum(c, -8), 7).astype(np.int8)
+
+
+def pack_nibbles(codes, d_pad):
+    """Rows of nibble codes as bytes, written out from the storage definition: byte j of a row
+    holds feature 2j in bits 0-3 and feature 2j + 1 in bits 4-7, each as code + 8; features
+    beyond the row's d count as code 0 up to d_pad features.  Plain loops."""
+    c = nibble_codes(codes)
+    n, d = c.shape
+    assert d_pad % 2 == 0 and d_pad >= d
+    out = np.zeros((n, d_pad // 2), np.uint8)
+    for r in range(n):
+        for j in range(d_pad // 2):
+            lo = int(c[r, 2 * j]) if 2 * j < d else 0
+            hi = int(c[r, 2 * j + 1]) if 2 * j + 1 < d else 0
+            out[r, j] = (lo + 8) | ((hi + 8) << 4)
+    return out

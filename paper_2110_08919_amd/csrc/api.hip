@@ -227,13 +227,16 @@ extern "C" int lpq_encode(const lpq_quantizer *q, const float *x_dev, int64_t n,
 // ------------------------------------------------------------------------- index ----
 struct lpq_index {
     int d = 0, d_pad = 0, bits = 0;
+    bool packed = false;         // two 4-bit codes per byte: rows of d_pad / 2 bytes
     int64_t capacity = 0, cap_rows = 0, size = 0;
     float *params = nullptr;     // device copy of the quantizer constants
     int8_t *codes = nullptr;     // [cap_rows][d_pad], zero padded
     int32_t *norms = nullptr;    // [cap_rows]
     int32_t *cinit = nullptr;    // [cap_rows]   accumulator seeds of the matrix-core kernel
     uint32_t *parity = nullptr;  // [cap_rows/32]
+    int8_t *stage = nullptr;     // packed only: [PACK_STAGE_ROWS][d_pad] int8 codes on their way to nibbles
 };
+constexpr int64_t PACK_STAGE_ROWS = 65536;
 
 extern "C" void lpq_index_destroy(lpq_index *idx)
 {
@@ -242,30 +245,38 @@ extern "C" void lpq_index_destroy(lpq_index *idx)
     (void)hipFree(idx->codes);
     (void)hipFree(idx->norms);
     (void)hipFree(idx->cinit);
+    (void)hipFree(idx->stage);
     (void)hipFree(idx->parity);
     delete idx;
 }
 
-extern "C" int lpq_index_create(lpq_index **out, const lpq_quantizer *q, int64_t capacity)
+static int index_create_impl(lpq_index **out, const lpq_quantizer *q, int64_t capacity, bool packed)
 {
     if (!out || !q) return fail(LPQ_EINVAL, "null argument");
     if (!q->ready) return fail(LPQ_ESTATE, "quantizer has no constants yet");
+    if (packed && q->bits > 4) return fail(LPQ_EINVAL, "packed storage needs a quantizer of at most 4 bits (has %d)", q->bits);
+    if (packed && q->d > MAX_D_PACKED)
+        return fail(LPQ_ERANGE, "packed storage is searched for at most %d features (has %d)", (int)MAX_D_PACKED, q->d);
     if (capacity < 1) return fail(LPQ_EINVAL, "capacity < 1");
     if (capacity >= (int64_t(1) << 31) - 1024) return fail(LPQ_ERANGE, "capacity must stay below 2^31 - 1024");
     lpq_index *idx = new (std::nothrow) lpq_index;
     if (!idx) return fail(LPQ_ENOMEM, "host allocation failed");
     idx->d = q->d; idx->bits = q->bits;
+    idx->packed = packed;
     idx->d_pad = (int)round_up(q->d, 32);
+    if (packed)   // only the matrix-core scan reads packed rows: pad to a row length it has
+        idx->d_pad = q->d <= 64 ? 64 : q->d <= 96 ? 96 : q->d <= 128 ? 128 : q->d <= 192 ? 192 : 256;
     idx->capacity = capacity;
     idx->cap_rows = round_up(capacity, 256) + 256;  // whole tiles may be read past the last item
-    const size_t code_bytes = (size_t)idx->cap_rows * idx->d_pad;
+    const size_t code_bytes = (size_t)idx->cap_rows * idx->d_pad / (packed ? 2 : 1);
     hipError_t e = hipMalloc(&idx->params, sizeof(float) * 4 * idx->d);
     if (e == hipSuccess) e = hipMalloc(&idx->codes, code_bytes);
+    if (e == hipSuccess && packed) e = hipMalloc(&idx->stage, (size_t)PACK_STAGE_ROWS * idx->d_pad);
     if (e == hipSuccess) e = hipMalloc(&idx->norms, sizeof(int32_t) * idx->cap_rows);
     if (e == hipSuccess) e = hipMalloc(&idx->cinit, sizeof(int32_t) * idx->cap_rows);
     if (e == hipSuccess) e = hipMalloc(&idx->parity, sizeof(uint32_t) * (idx->cap_rows / 32));
     if (e == hipSuccess) e = hipMemcpy(idx->params, q->params, sizeof(float) * 4 * idx->d, hipMemcpyDeviceToDevice);
-    if (e == hipSuccess) e = hipMemset(idx->codes, 0, code_bytes);
+    if (e == hipSuccess) e = hipMemset(idx->codes, packed ? 0x88 : 0, code_bytes);   // code 0 everywhere
     if (e == hipSuccess) e = hipMemset(idx->norms, 0, sizeof(int32_t) * idx->cap_rows);
     if (e == hipSuccess) e = hipMemset(idx->parity, 0, sizeof(uint32_t) * (idx->cap_rows / 32));
     if (e == hipSuccess) e = hipMemsetD32((hipDeviceptr_t)idx->cinit, CINIT_PAD, (size_t)idx->cap_rows);
@@ -275,6 +286,24 @@ extern "C" int lpq_index_create(lpq_index **out, const lpq_quantizer *q, int64_t
         return fail(e == hipErrorOutOfMemory ? LPQ_ENOMEM : LPQ_EDEVICE, "index allocation: %s", hipGetErrorString(e));
     }
     *out = idx;
+    return LPQ_OK;
+}
+
+extern "C" int lpq_index_create(lpq_index **out, const lpq_quantizer *q, int64_t capacity)
+{
+    return index_create_impl(out, q, capacity, false);
+}
+
+extern "C" int lpq_index_create_packed(lpq_index **out, const lpq_quantizer *q, int64_t capacity)
+{
+    return index_create_impl(out, q, capacity, true);
+}
+
+// Packed index: rows [size, size + n) from int8 codes (device), through the nibble packer.
+static int index_pack_rows(lpq_index *idx, const int8_t *codes, int64_t n, int64_t ld, hipStream_t st)
+{
+    HIP_TRY(launch_pack4(codes, n, ld, idx->d, reinterpret_cast<uint8_t *>(idx->codes) + (size_t)idx->size * (idx->d_pad / 2),
+                         idx->d_pad, idx->norms + idx->size, st));
     return LPQ_OK;
 }
 
@@ -295,6 +324,18 @@ extern "C" int lpq_index_add_f32(lpq_index *idx, const float *x_dev, int64_t n, 
     if (idx->size + n > idx->capacity) return fail(LPQ_ERANGE, "index capacity %lld exceeded", (long long)idx->capacity);
     if (n == 0) return LPQ_OK;
     hipStream_t st = (hipStream_t)stream;
+    if (idx->packed) {   // encode a chunk into the staging rows, pack it, next chunk
+        for (int64_t r = 0; r < n; r += PACK_STAGE_ROWS) {
+            const int64_t m = n - r < PACK_STAGE_ROWS ? n - r : PACK_STAGE_ROWS;
+            HIP_TRY(launch_encode(view(idx->params, idx->d, idx->bits), x_dev + r * ld, m, ld, idx->stage, idx->d_pad,
+                                  idx->d_pad, nullptr, st));
+            int rc = index_pack_rows(idx, idx->stage, m, idx->d_pad, st);
+            if (rc) return rc;
+            rc = index_after_add(idx, m, st);
+            if (rc) return rc;
+        }
+        return LPQ_OK;
+    }
     HIP_TRY(launch_encode(view(idx->params, idx->d, idx->bits), x_dev, n, ld,
                           idx->codes + (size_t)idx->size * idx->d_pad, idx->d_pad, idx->d_pad,
                           idx->norms + idx->size, st));
@@ -309,6 +350,10 @@ extern "C" int lpq_index_add_i8(lpq_index *idx, const int8_t *codes_dev, int64_t
     if (idx->size + n > idx->capacity) return fail(LPQ_ERANGE, "index capacity %lld exceeded", (long long)idx->capacity);
     if (n == 0) return LPQ_OK;
     hipStream_t st = (hipStream_t)stream;
+    if (idx->packed) {
+        const int rc = index_pack_rows(idx, codes_dev, n, ld, st);
+        return rc ? rc : index_after_add(idx, n, st);
+    }
     HIP_TRY(launch_repack_i8(codes_dev, n, ld, idx->d, idx->codes + (size_t)idx->size * idx->d_pad, idx->d_pad,
                              idx->d_pad, idx->norms + idx->size, st));
     return index_after_add(idx, n, st);
@@ -321,7 +366,7 @@ extern "C" int lpq_index_data(const lpq_index *idx, const int8_t **codes_dev, in
 {
     if (!idx) return fail(LPQ_EINVAL, "null index");
     if (codes_dev) *codes_dev = idx->codes;
-    if (ld_codes) *ld_codes = idx->d_pad;
+    if (ld_codes) *ld_codes = idx->packed ? idx->d_pad / 2 : idx->d_pad;
     if (norms_dev) *norms_dev = idx->norms;
     return LPQ_OK;
 }
@@ -334,6 +379,7 @@ extern "C" int lpq_gather_dist_i8(const lpq_index *idx, const int8_t *qcodes_dev
     if (nq < 0 || m < 1) return fail(LPQ_EINVAL, "nq < 0 or m < 1");
     if (metric != LPQ_METRIC_L2SQ && metric != LPQ_METRIC_IP) return fail(LPQ_EINVAL, "unknown metric %d", metric);
     if (idx->size < 1) return fail(LPQ_ESTATE, "gather on an empty index");
+    if (idx->packed) return fail(LPQ_EINVAL, "gather is not available on a packed index");
     if (nq > 0 && (!qcodes_dev || !ids_dev || !dist_dev)) return fail(LPQ_EINVAL, "null argument");
     if (nq > 0 && ld < idx->d) return fail(LPQ_EINVAL, "ld < d");
     HIP_TRY(launch_gather_dist(idx->codes, idx->norms, idx->size, idx->d, idx->d_pad, qcodes_dev, nq, ld, ids_dev, m,
@@ -393,7 +439,8 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     // (Not for codes of fewer than 8 bits: there many items tie at the seed threshold, all of them
     // are collected, and queries spill to the exact redo.)
     const bool wide = coll && idx->bits == 8 && mfma_collect_wide(nq, idx->d_pad) && g_tune[LPQ_TUNE_WAVE_QUERIES] != 64;
-    if (want == 3 && coll) p.mode = PLAN_MFMA_COLLECT;
+    if (idx->packed) p.mode = PLAN_MFMA_REG;   // packed rows: row-split register-list kernel only (callers tile the queries)
+    else if (want == 3 && coll) p.mode = PLAN_MFMA_COLLECT;
     else if (want != 1 && want != 4 && wide) p.mode = PLAN_MFMA_COLLECT;
     else if (want != 1 && regs) p.mode = PLAN_MFMA_REG;
     else if (want != 1 && want != 4 && coll) p.mode = PLAN_MFMA_COLLECT;
@@ -417,7 +464,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     else if (g_tune[LPQ_TUNE_SEED_ROWS] == 0 && p.mode != PLAN_GENERIC) {
         // Few queries: the scan is bound by corpus bytes, so the sample stays small.  Otherwise a
         // larger sample pays for itself through fewer candidates in the main pass (measured).
-        const bool few = gm && mfma_row_split(nq, idx->d_pad);
+        const bool few = gm && mfma_row_split(nq, idx->d_pad, idx->packed);
         seed = gm ? (few ? n / 16 : n / 8) : n / 64;
         const int64_t lo = gm ? 8192 : 4096, hi = p.mode == PLAN_MFMA_COLLECT ? n : (gm ? (few ? 65536 : 131072) : 32768);
         seed = seed < lo ? lo : (seed > hi ? hi : seed);
@@ -446,7 +493,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     int64_t qt = (p.mode == PLAN_MFMA_LDS && k > 16) ? 128 : 256;   // queries per workgroup
     int64_t slots_now = slots;
     if (gmode) {
-        p.rsplit = mfma_row_split(nq, idx->d_pad);
+        p.rsplit = mfma_row_split(nq, idx->d_pad, idx->packed);
         if (p.mode == PLAN_MFMA_COLLECT && mfma_collect_wide(nq, idx->d_pad) && g_tune[LPQ_TUNE_WAVE_QUERIES] != 64)
             p.wave_queries = 128;
         qt = mfma_queries_per_workgroup(nq, idx->d_pad, p.wave_queries == 128);
@@ -524,6 +571,8 @@ int check_search_args(const lpq_index *idx, const void *q, int64_t nq, int64_t l
     if (idx->size < 1) return fail(LPQ_ESTATE, "search on an empty index");
     if (k > idx->size) return fail(LPQ_ERANGE, "k = %d > number of items %lld", k, (long long)idx->size);
     if (k > MAX_K) return fail(LPQ_ERANGE, "k = %d > %d", k, (int)MAX_K);
+    if (idx->packed && k > MAX_K_PACKED)
+        return fail(LPQ_ERANGE, "k = %d > %d, the most a packed index is searched for", k, (int)MAX_K_PACKED);
     if (nq > 0 && (!q || !ids || !dist)) return fail(LPQ_EINVAL, "null argument");
     if (nq > 0 && ld < idx->d) return fail(LPQ_EINVAL, "ld < d");
     if (nq * (int64_t)k >= (int64_t(1) << 40)) return fail(LPQ_ERANGE, "nq too large");
@@ -531,19 +580,22 @@ int check_search_args(const lpq_index *idx, const void *q, int64_t nq, int64_t l
 }
 
 // Everything after the queries are codes in the workspace.
-int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k, int metric, int32_t *ids,
-                int32_t *dist, hipStream_t st)
+// qcodes / qnorms: the nq queries' codes (rows of d_pad bytes, zero rows up to a multiple of 512
+// readable behind them) and the per-query term of the final distance; emit_mode: how the merge
+// turns a key into a distance.
+int search_core(const lpq_index *idx, const Plan &p, char *ws, const int8_t *qcodes, const int32_t *qnorms, int64_t nq,
+                int k, int metric, int emit_mode, int32_t *ids, int32_t *dist, hipStream_t st)
 {
     SearchArgs a;
     a.codes = idx->codes; a.norms = idx->norms; a.cinit = idx->cinit; a.parity = idx->parity;
     a.n = idx->size; a.d_pad = idx->d_pad;
-    a.qcodes = reinterpret_cast<const int8_t *>(ws + p.off_qcodes);
+    a.packed = idx->packed;
+    a.qcodes = qcodes;
     a.nq = nq; a.k = k; a.metric = metric;
     a.dry_run = (int)g_tune[LPQ_TUNE_DRY_RUN];
     a.work_order = (int)g_tune[LPQ_TUNE_WORK_ORDER];
     a.wave_queries = 64;
     a.rsplit = p.rsplit;
-    const int32_t *qnorms = reinterpret_cast<const int32_t *>(ws + p.off_qnorms);
     cand_t *lists1 = reinterpret_cast<cand_t *>(ws + p.off_lists1);
     cand_t *seedlist = reinterpret_cast<cand_t *>(ws + p.off_seedlist);
     cand_t *seeds = reinterpret_cast<cand_t *>(ws + p.off_seeds);
@@ -555,11 +607,11 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k
     const bool sorted = p.mode != PLAN_MFMA_LDS;   // that scan's lists come out in arrival order
     auto final_merge = [&](const cand_t *extra) -> hipError_t {
         if (!p.merge_group)
-            return launch_merge(lists2, nq, p.S2, k, extra, nullptr, nullptr, ids, dist, qnorms, metric, st, sorted);
+            return launch_merge(lists2, nq, p.S2, k, extra, nullptr, nullptr, ids, dist, qnorms, emit_mode, st, sorted);
         const int groups = (int)ceil_div(p.S2, p.merge_group);
         hipError_t e = launch_merge_groups(lists2, nq, p.S2, p.merge_group, k, merge_tmp, st);
         if (e != hipSuccess) return e;
-        return launch_merge(merge_tmp, nq, groups, k, extra, nullptr, nullptr, ids, dist, qnorms, metric, st, true);
+        return launch_merge(merge_tmp, nq, groups, k, extra, nullptr, nullptr, ids, dist, qnorms, emit_mode, st, true);
     };
     auto scan = [&](int64_t r0, int64_t r1, int S, const cand_t *sd, cand_t *out) -> hipError_t {
         KernelSpan span(st);
@@ -591,11 +643,11 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k
             HIP_TRY(e);
         }
         int32_t *qlist = reinterpret_cast<int32_t *>(ws + p.off_qlist), *qcount = qlist + nq;
-        HIP_TRY(launch_collect_select(cbuf, ccnt, nq, p.SS, p.Cs, k, over, qlist, qcount, ids, dist, qnorms, metric, st,
+        HIP_TRY(launch_collect_select(cbuf, ccnt, nq, p.SS, p.Cs, k, over, qlist, qcount, ids, dist, qnorms, emit_mode, st,
                                       p.expect));
         // queries whose candidates did not fit are searched again by the generic kernel
         HIP_TRY(launch_search_generic_list(a, 0, a.n, p.Sg, qlist, qcount, lists2, st));
-        HIP_TRY(launch_merge(lists2, nq, p.Sg, k, nullptr, nullptr, nullptr, ids, dist, qnorms, metric, st, false, over));
+        HIP_TRY(launch_merge(lists2, nq, p.Sg, k, nullptr, nullptr, nullptr, ids, dist, qnorms, emit_mode, st, false, over));
     } else if (p.mode == PLAN_MFMA_REG) {
         const cand_t *sd = nullptr;
         if (p.seed_rows) {
@@ -616,12 +668,62 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, int64_t nq, int k
     return LPQ_OK;
 }
 
+// A packed index is searched in tiles of at most 64 queries by the row-split kernel; the workspace
+// holds all queries' codes, their permuted copy and per-query terms, then one tile's plan.
+struct PackedPlan {
+    int64_t nq_pad;
+    size_t off_qcodes, off_qnorms, off_qperm, off_qadj, off_tile, total;
+};
+constexpr int64_t PACKED_TILE = 64;
+
+PackedPlan make_packed_plan(const lpq_index *idx, int64_t nq, int k)
+{
+    PackedPlan pp;
+    const int64_t full = nq < PACKED_TILE ? nq : PACKED_TILE, last = nq % PACKED_TILE;
+    const Plan a = make_plan(idx, full, k);
+    size_t tile = a.total;
+    int64_t tail = a.nq_pad;
+    if (last) {
+        const Plan b = make_plan(idx, last, k);
+        if (b.total > tile) tile = b.total;
+        if (b.nq_pad > tail) tail = b.nq_pad;
+    }
+    pp.nq_pad = ceil_div(nq, PACKED_TILE) * PACKED_TILE + tail;   // every tile may read a whole padded tile
+    size_t o = 0;
+    pp.off_qcodes = o; o = align256(o + (size_t)pp.nq_pad * idx->d_pad);
+    pp.off_qnorms = o; o = align256(o + (size_t)pp.nq_pad * sizeof(int32_t));
+    pp.off_qperm = o;  o = align256(o + (size_t)pp.nq_pad * idx->d_pad);
+    pp.off_qadj = o;   o = align256(o + (size_t)pp.nq_pad * sizeof(int32_t));
+    pp.off_tile = o;   o = align256(o + tile);
+    pp.total = o;
+    return pp;
+}
+
+int search_packed(const lpq_index *idx, const PackedPlan &pp, char *ws, int64_t nq, int k, int metric, int32_t *ids,
+                  int32_t *dist, hipStream_t st)
+{
+    int8_t *qperm = reinterpret_cast<int8_t *>(ws + pp.off_qperm);
+    int32_t *qadj = reinterpret_cast<int32_t *>(ws + pp.off_qadj);
+    HIP_TRY(launch_permute_queries(reinterpret_cast<const int8_t *>(ws + pp.off_qcodes), pp.nq_pad, idx->d_pad,
+                                   metric == LPQ_METRIC_L2SQ, qperm, qadj, st));
+    const int emit = metric == LPQ_METRIC_L2SQ ? MODE_I8_L2 : MODE_I8_IP_ADJ;
+    for (int64_t q0 = 0; q0 < nq; q0 += PACKED_TILE) {
+        const int64_t nt = nq - q0 < PACKED_TILE ? nq - q0 : PACKED_TILE;
+        const Plan pt = make_plan(idx, nt, k);
+        int rc = search_core(idx, pt, ws + pp.off_tile, qperm + q0 * idx->d_pad, qadj + q0, nt, k, metric, emit,
+                             ids + q0 * k, dist + q0 * k, st);
+        if (rc) return rc;
+    }
+    return LPQ_OK;
+}
+
 }  // namespace
 
 extern "C" size_t lpq_search_workspace_bytes(const lpq_index *idx, int64_t nq, int k, int metric)
 {
     if (!idx || nq < 0 || k < 1 || k > MAX_K || idx->size < 1 || k > idx->size) return 0;
     (void)metric;
+    if (idx->packed) return k > MAX_K_PACKED ? 0 : make_packed_plan(idx, nq, k).total + 256;
     return make_plan(idx, nq, k).total + 256;
 }
 
@@ -632,16 +734,25 @@ extern "C" int lpq_search(const lpq_index *idx, const float *q_dev, int64_t nq, 
     int rc = check_search_args(idx, q_dev, nq, ld, k, metric, ids_dev, dist_dev);
     if (rc) return rc;
     if (nq == 0) return LPQ_OK;
-    const Plan p = make_plan(idx, nq, k);
-    if (!workspace_dev || workspace_bytes < p.total) return fail(LPQ_ERANGE, "workspace of %zu bytes needed", p.total);
-    if ((uintptr_t)workspace_dev % 256) return fail(LPQ_EINVAL, "workspace must be 256-byte aligned");
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace_dev;
+    if ((uintptr_t)workspace_dev % 256) return fail(LPQ_EINVAL, "workspace must be 256-byte aligned");
+    if (idx->packed) {
+        const PackedPlan pp = make_packed_plan(idx, nq, k);
+        if (!workspace_dev || workspace_bytes < pp.total) return fail(LPQ_ERANGE, "workspace of %zu bytes needed", pp.total);
+        HIP_TRY(launch_encode(view(idx->params, idx->d, idx->bits), q_dev, nq, ld,
+                              reinterpret_cast<int8_t *>(ws + pp.off_qcodes), idx->d_pad, idx->d_pad,
+                              reinterpret_cast<int32_t *>(ws + pp.off_qnorms), st, pp.nq_pad));
+        return search_packed(idx, pp, ws, nq, k, metric, ids_dev, dist_dev, st);
+    }
+    const Plan p = make_plan(idx, nq, k);
+    if (!workspace_dev || workspace_bytes < p.total) return fail(LPQ_ERANGE, "workspace of %zu bytes needed", p.total);
     // Padding query rows [nq, nq_pad) are written as zero codes; their results are never written out.
     HIP_TRY(launch_encode(view(idx->params, idx->d, idx->bits), q_dev, nq, ld,
                           reinterpret_cast<int8_t *>(ws + p.off_qcodes), idx->d_pad, idx->d_pad,
                           reinterpret_cast<int32_t *>(ws + p.off_qnorms), st, p.nq_pad));
-    return search_core(idx, p, ws, nq, k, metric, ids_dev, dist_dev, st);
+    return search_core(idx, p, ws, reinterpret_cast<const int8_t *>(ws + p.off_qcodes),
+                       reinterpret_cast<const int32_t *>(ws + p.off_qnorms), nq, k, metric, metric, ids_dev, dist_dev, st);
 }
 
 extern "C" int lpq_search_overflow_stats(const lpq_index *idx, int64_t nq, int k, int metric, const void *workspace_dev,
@@ -670,14 +781,22 @@ extern "C" int lpq_search_i8(const lpq_index *idx, const int8_t *qcodes_dev, int
     int rc = check_search_args(idx, qcodes_dev, nq, ld, k, metric, ids_dev, dist_dev);
     if (rc) return rc;
     if (nq == 0) return LPQ_OK;
-    const Plan p = make_plan(idx, nq, k);
-    if (!workspace_dev || workspace_bytes < p.total) return fail(LPQ_ERANGE, "workspace of %zu bytes needed", p.total);
-    if ((uintptr_t)workspace_dev % 256) return fail(LPQ_EINVAL, "workspace must be 256-byte aligned");
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace_dev;
+    if ((uintptr_t)workspace_dev % 256) return fail(LPQ_EINVAL, "workspace must be 256-byte aligned");
+    if (idx->packed) {
+        const PackedPlan pp = make_packed_plan(idx, nq, k);
+        if (!workspace_dev || workspace_bytes < pp.total) return fail(LPQ_ERANGE, "workspace of %zu bytes needed", pp.total);
+        HIP_TRY(launch_repack_i8(qcodes_dev, nq, ld, idx->d, reinterpret_cast<int8_t *>(ws + pp.off_qcodes), idx->d_pad,
+                                 idx->d_pad, reinterpret_cast<int32_t *>(ws + pp.off_qnorms), st, pp.nq_pad));
+        return search_packed(idx, pp, ws, nq, k, metric, ids_dev, dist_dev, st);
+    }
+    const Plan p = make_plan(idx, nq, k);
+    if (!workspace_dev || workspace_bytes < p.total) return fail(LPQ_ERANGE, "workspace of %zu bytes needed", p.total);
     HIP_TRY(launch_repack_i8(qcodes_dev, nq, ld, idx->d, reinterpret_cast<int8_t *>(ws + p.off_qcodes), idx->d_pad,
                              idx->d_pad, reinterpret_cast<int32_t *>(ws + p.off_qnorms), st, p.nq_pad));
-    return search_core(idx, p, ws, nq, k, metric, ids_dev, dist_dev, st);
+    return search_core(idx, p, ws, reinterpret_cast<const int8_t *>(ws + p.off_qcodes),
+                       reinterpret_cast<const int32_t *>(ws + p.off_qnorms), nq, k, metric, metric, ids_dev, dist_dev, st);
 }
 
 // -------------------------------------------------------------------- fp32 exact ----

@@ -30,7 +30,8 @@ __host__ __device__ inline uint32_t cand_id(cand_t c) { return (uint32_t)c; }
 // Ranking modes of the merge kernel: the two integer metrics (same values as the public
 // LPQ_METRIC_* constants) and the two fp32 ones, whose keys are order-preserving integer
 // images of the float distance (L2) or of minus the inner product (IP).
-enum { MODE_I8_L2 = 0, MODE_I8_IP = 1, MODE_F32_L2 = 2, MODE_F32_IP = 3 };
+enum { MODE_I8_L2 = 0, MODE_I8_IP = 1, MODE_F32_L2 = 2, MODE_F32_IP = 3,
+       MODE_I8_IP_ADJ = 4 };   // inner product plus a per-query term (packed corpus codes are stored + 8)
 
 // Order-preserving map between finite floats and int32 (its own inverse); -0 is folded into +0.
 __host__ __device__ inline int32_t float_to_sortable(float f)
@@ -57,7 +58,7 @@ __host__ __device__ static inline int next_pow2(int v)
 static inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-enum { MAX_K = 1024, MAX_D = 32768 };
+enum { MAX_K = 1024, MAX_D = 32768, MAX_K_PACKED = 16, MAX_D_PACKED = 256 };
 
 // Per-feature constants on the device: four arrays of d floats, [k | S_b | S_e | m].
 struct QuantParams {
@@ -84,7 +85,15 @@ hipError_t launch_repack_i8(const int8_t *src, int64_t n, int64_t ld, int d, int
 // Derived per-item arrays used by the matrix-core kernel: cinit_j = -ceil(nx_j / 2) and one
 // word of 32 parity bits (bit r = nx_{32w+r} & 1) per 32 items; rows >= n of the last word's
 // block get cinit = CINIT_PAD.  use_norms = false (IP) gives cinit = 0 and parity = 0.
-hipError_t launch_zero_bytes(void *p, size_t bytes, hipStream_t st);  // bytes % 4 == 0, p 4-byte aligned
+hipError_t launch_zero_bytes(void *p, size_t bytes, hipStream_t st);
+// Sub-byte packing: int8 codes [n][ld] -> two codes per byte (stored + 8, clamped to [-8, 7]),
+// rows of d_pad / 2 bytes, and the norms of the stored codes.
+hipError_t launch_pack4(const int8_t *src, int64_t n, int64_t ld, int d, uint8_t *dst, int d_pad, int32_t *norms,
+                        hipStream_t st);
+// Queries for the packed scan: codes permuted inside every group of 16 to match the operand
+// unpacking, and qadj[q] = |cq|^2 + 16 sum(cq) (L2SQ) or -8 sum(cq) (IP).
+hipError_t launch_permute_queries(const int8_t *q, int64_t nq_pad, int d_pad, bool l2, int8_t *qperm, int32_t *qadj,
+                                  hipStream_t st);  // bytes % 4 == 0, p 4-byte aligned
 hipError_t launch_item_aux(const int32_t *norms, int64_t row0, int64_t n_total, int32_t *cinit,
                            uint32_t *parity, hipStream_t st);
 
@@ -104,6 +113,7 @@ struct SearchArgs {
     int dry_run;            // timing experiments: != 0 never collects a candidate (2..4: ablations)
     int work_order = 0;     // matrix-core kernels: block -> (split, query tile) mapping (0 = built-in)
     int wave_queries = 64;  // collecting mode: queries per wave (64 or 128)
+    bool packed = false;    // codes holds two 4-bit codes (stored + 8) per byte, rows of d_pad / 2 bytes; qcodes permuted to match
 };
 
 // Generic kernel: one workgroup per (query, corpus split); any d_pad (multiple of 32), any k.
@@ -131,7 +141,7 @@ int mfma_seed_segments(int S, int k, bool rsplit);
 int mfma_seed_groups(int S, int SEG, bool rsplit);        // = G, entries per query in gmax
 int mfma_queries_per_workgroup(int64_t nq, int d_pad, bool wide = false);   // query tile; wide: 128 queries per wave
 bool mfma_collect_wide(int64_t nq, int d_pad);           // collecting mode may use 128 queries per wave
-bool mfma_row_split(int64_t nq, int d_pad);              // few queries: waves split rows, share queries
+bool mfma_row_split(int64_t nq, int d_pad, bool packed = false);   // few queries: waves split rows, share queries
 // With stage_stride > 0 (a multiple of 128) the pass is a systematic sample of [row0, row1): one
 // stage (64 rows; 128 in row-split launches) every stage_stride rows, stages_per_split per split.
 hipError_t launch_seed_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S, int SEG, int32_t *gmax,

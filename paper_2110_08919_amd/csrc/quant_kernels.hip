@@ -476,6 +476,58 @@ __global__ __launch_bounds__(256) void repack_i8_kernel(
     if (r < n_out && sub == 0 && norms) norms[r] = s;
 }
 
+// Two 4-bit codes per byte (sub-byte packing for B <= 4): byte j of a row holds code 2j in its low
+// nibble and code 2j+1 in its high nibble, each stored as u = code + 8.  A nibble cannot hold +8,
+// so the upper clamp value of B = 4 is stored as 7 (as a byte stores +128 as 127 at B = 8); the
+// norm is that of the stored codes.  Columns d .. d_pad-1 hold code 0.  16 lanes per row.
+__global__ __launch_bounds__(256) void pack4_kernel(const int8_t *__restrict__ src, int64_t n, int64_t ld, int d,
+                                                    uint8_t *__restrict__ dst, int d_pad, int32_t *__restrict__ norms)
+{
+    const int sub = threadIdx.x & 15;
+    const int64_t r = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 4;
+    int s = 0;
+    if (r < n) {
+        for (int j = sub; j < d_pad / 2; j += 16) {
+            int c0 = (2 * j < d) ? (int)src[r * ld + 2 * j] : 0;
+            int c1 = (2 * j + 1 < d) ? (int)src[r * ld + 2 * j + 1] : 0;
+            c0 = c0 > 7 ? 7 : (c0 < -8 ? -8 : c0);
+            c1 = c1 > 7 ? 7 : (c1 < -8 ? -8 : c1);
+            dst[r * (d_pad / 2) + j] = (uint8_t)((c0 + 8) | ((c1 + 8) << 4));
+            s += c0 * c0 + c1 * c1;
+        }
+    }
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (r < n && sub == 0) norms[r] = s;
+}
+
+// Query codes in the order the packed scan's operand unpacking produces (inside every group of 16
+// codes: 0 2 4 6 1 3 5 7 8 10 12 14 9 11 13 15), and the per-query term that takes the + 8 offset
+// of the stored corpus codes out of the result: L2SQ |cq|^2 + 16 sum(cq), IP -8 sum(cq).  Codes are
+// saturated to the nibble range [-8, 7] first.
+__global__ __launch_bounds__(256) void permute_queries_kernel(const int8_t *__restrict__ q, int64_t nq_pad, int d_pad,
+                                                              int l2, int8_t *__restrict__ qperm, int32_t *__restrict__ qadj)
+{
+    const int sub = threadIdx.x & 15;
+    const int64_t r = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 4;
+    int sum = 0, sq = 0;
+    if (r < nq_pad) {
+        for (int c = sub; c < d_pad; c += 16) {
+            const int i = c & 15, g = c & ~15;
+            const int h = i & 7;                                  // position inside a half of 8
+            const int srci = (i & 8) | (h < 4 ? 2 * h : 2 * (h - 4) + 1);
+            int v = (int)q[r * d_pad + g + srci];
+            v = v > 7 ? 7 : (v < -8 ? -8 : v);   // queries saturate like the stored items
+            qperm[r * d_pad + c] = (int8_t)v;
+            sum += v;
+            sq += v * v;
+        }
+    }
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) { sum += __shfl_xor(sum, o, 64); sq += __shfl_xor(sq, o, 64); }
+    if (r < nq_pad && sub == 0) qadj[r] = l2 ? sq + 16 * sum : -8 * sum;
+}
+
 __global__ __launch_bounds__(256) void zero_words_kernel(uint32_t *p, size_t words)
 {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words; i += (size_t)gridDim.x * 256) p[i] = 0u;
@@ -605,6 +657,22 @@ hipError_t launch_repack_i8(const int8_t *src, int64_t n, int64_t ld, int d, int
     if (n_out <= 0) return hipSuccess;
     const int64_t blocks = ceil_div(n_out * 16, 256);
     repack_i8_kernel<<<(unsigned)blocks, 256, 0, st>>>(src, n, ld, d, dst, ldd, d_pad, norms, n_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack4(const int8_t *src, int64_t n, int64_t ld, int d, uint8_t *dst, int d_pad, int32_t *norms,
+                        hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    pack4_kernel<<<(unsigned)ceil_div(n * 16, 256), 256, 0, st>>>(src, n, ld, d, dst, d_pad, norms);
+    return hipGetLastError();
+}
+
+hipError_t launch_permute_queries(const int8_t *q, int64_t nq_pad, int d_pad, bool l2, int8_t *qperm, int32_t *qadj,
+                                  hipStream_t st)
+{
+    if (nq_pad <= 0) return hipSuccess;
+    permute_queries_kernel<<<(unsigned)ceil_div(nq_pad * 16, 256), 256, 0, st>>>(q, nq_pad, d_pad, l2 ? 1 : 0, qperm, qadj);
     return hipGetLastError();
 }
 

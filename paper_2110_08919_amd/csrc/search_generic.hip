@@ -119,6 +119,7 @@ __device__ __forceinline__ void emit_result(cand_t c, int64_t at, int64_t q, int
     int32_t v;
     if (metric == MODE_I8_L2) v = key + qnorms[q];
     else if (metric == MODE_I8_IP) v = -(key / 2);
+    else if (metric == MODE_I8_IP_ADJ) v = -(key / 2) + qnorms[q];
     else {
         const float f = sortable_to_float(key);
         v = __float_as_int(metric == MODE_F32_L2 ? f : -f);

@@ -214,7 +214,7 @@ __device__ __forceinline__ void drain_queue(const WaveQ &w, int qcnt, int64_t ro
     }
 }
 
-template <int KS, bool L2, int KCAP, bool SEED, int NW, bool RSPLIT, int NB>
+template <int KS, bool L2, int KCAP, bool SEED, int NW, bool RSPLIT, int NB, bool PACK>
 __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     SearchArgs a, int64_t row0, int64_t row1, int S, int64_t split_rows, int qtiles, MfmaIo o)
 {
@@ -234,11 +234,19 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     // Every wave then copies, waits for and reads only its own quarter of each stage: the waves run
     // without any workgroup barrier and the path is bound by how fast the corpus streams in.
     constexpr int QT = RSPLIT ? QW : NW * QW;   // queries per workgroup
-    constexpr int CPR = 2 * KS;            // 16-byte chunks per corpus row
+    // PACK: the corpus holds two 4-bit codes per byte, stored as u = code + 8 (0..15): rows are half
+    // as long in HBM and in LDS; a lane reads 8 bytes per k-step and spreads the nibbles over its
+    // four operand registers (low nibbles of a dword, then its high nibbles), which permutes the
+    // 16 codes of the lane inside the k-step; the caller hands in query codes permuted the same
+    // way.  The matrix core then delivers dot(u, q) = dot(code, q) + 8 sum(q): a constant per query,
+    // which shifts every key of a query alike and is taken out when the result is written.
+    static_assert(!PACK || RSPLIT, "packed rows: row-split launches only");
+    constexpr int CPR = PACK ? KS : 2 * KS;   // 16-byte chunks per corpus row
+    constexpr int ROWB = 16 * CPR;            // bytes per corpus row
     constexpr int SLOTS = CPR <= 2 ? 2 : (CPR <= 4 ? 4 : (CPR <= 8 ? 8 : 16));  // LDS slots per row
     constexpr int RS = RSPLIT ? 32 * NW : 64;   // corpus rows per stage
     constexpr int NST = (KS <= 4 && !RSPLIT) ? 4 : 3;   // LDS ring depth (a deeper ring measured slower for RSPLIT)
-    static_assert(!RSPLIT || KS <= 4, "row-split staging is sized for rows of up to 128 bytes");
+    static_assert(!RSPLIT || ROWB <= 128, "row-split staging is sized for rows of up to 128 bytes");
     constexpr int STAGE_BYTES = RS * SLOTS * 16;
     constexpr int IPW = RS * SLOTS / 64 / NW;   // async copy instructions per wave and stage
     constexpr int AUX_INTS = RS + 4;       // cinit[RS] then parity words
@@ -324,7 +332,9 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     int qcnt = 0;
     int a_off[KS];   // byte offset of this lane's A chunk of k-step ks inside a 32-row block of a stage
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) a_off[ks] = col * (SLOTS * 16) + ((2 * ks + half) ^ swz<SLOTS>(col)) * 16;
+    for (int ks = 0; ks < KS; ++ks)
+        a_off[ks] = PACK ? col * (SLOTS * 16) + (ks ^ swz<SLOTS>(col)) * 16 + half * 8
+                         : col * (SLOTS * 16) + ((2 * ks + half) ^ swz<SLOTS>(col)) * 16;
 
     // ---- stage loader -----------------------------------------------------------------
     // Position p of a stage = LDS bytes [16p, 16p+16) = (row p / SLOTS, slot p % SLOTS).  Wave
@@ -339,14 +349,14 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
         const int r = p / SLOTS, sl = p % SLOTS;
         int c = sl ^ swz<SLOTS>(r & 31);
         c = c < CPR ? c : CPR - 1;          // padding slots of non-power-of-two rows: any valid chunk
-        src_off[j] = r * (32 * KS) + c * 16;
+        src_off[j] = r * ROWB + c * 16;
     }
 #define LPQ_ISSUE(ST)                                                                                   \
     do {                                                                                                \
         const int st_ = (ST);                                                                           \
         const int64_t r0_ = rs + (int64_t)st_ * sstride;                                                \
         const int ring_slot_ = st_ % NST;                                                               \
-        const int8_t *src_ = a.codes + r0_ * (32 * KS);                                                 \
+        const int8_t *src_ = a.codes + r0_ * ROWB;                                                      \
         _Pragma("unroll") for (int j = 0; j < IPW; ++j)                                                 \
             async_copy16(src_ + src_off[j], ring_lds + ring_slot_ * STAGE_BYTES + (wave * IPW + j) * 1024); \
         if (L2 && RSPLIT) { /* each wave brings the seeds and the parity word of its own block */       \
@@ -368,8 +378,15 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     do {                                                                                                \
         const unsigned char *sb_ = ring + (size_t)((TT) % NST) * STAGE_BYTES + (BLK) * 32 * (SLOTS * 16); \
         const int *cb_ = aux + ((TT) % NST) * AUX_INTS;                                                 \
-        _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                               \
-            AREG[ks] = *reinterpret_cast<const v4i *>(sb_ + a_off[ks]);                                 \
+        _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                             \
+            if (PACK) {                                                                                 \
+                const v2i w_ = *reinterpret_cast<const v2i *>(sb_ + a_off[ks]);                         \
+                AREG[ks] = v4i{w_[0] & 0x0F0F0F0F, (int)(((unsigned)w_[0] >> 4) & 0x0F0F0F0Fu),         \
+                               w_[1] & 0x0F0F0F0F, (int)(((unsigned)w_[1] >> 4) & 0x0F0F0F0Fu)};        \
+            } else {                                                                                    \
+                AREG[ks] = *reinterpret_cast<const v4i *>(sb_ + a_off[ks]);                             \
+            }                                                                                           \
+        }                                                                                               \
         if (L2) {                                                                                       \
             _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                             \
                 const v4i v_ = *reinterpret_cast<const v4i *>(cb_ + (BLK) * 32 + 8 * g + 4 * half);     \
@@ -654,21 +671,21 @@ __global__ __launch_bounds__(256) void seed_finalize_kernel(const int32_t *__res
     if (lane == 0) seeds[q] = (G < k || kth == INT32_MIN) ? CAND_NONE : make_cand(-2 * kth, 0xFFFFFFFFu);
 }
 
-size_t lds_bytes(int ks, bool seed, int nw, bool rsplit, int nb)
+size_t lds_bytes(int ks, bool seed, int nw, bool rsplit, int nb, bool pack)
 {
-    const int cpr = 2 * ks;
+    const int cpr = pack ? ks : 2 * ks;
     const int slots = cpr <= 2 ? 2 : (cpr <= 4 ? 4 : (cpr <= 8 ? 8 : 16));
     const int nst = (ks <= 4 && !rsplit) ? 4 : 3;
     const int rs = rsplit ? 32 * nw : 64;
     return (size_t)nst * rs * slots * 16 + (size_t)nst * (rs + 4) * 4 + 64 + (seed ? 0 : nw * waveq_bytes(nb * 32));
 }
 
-template <int KS, bool L2, int KCAP, bool SEED, int NW, bool RSPLIT, int NB = 2>
+template <int KS, bool L2, int KCAP, bool SEED, int NW, bool RSPLIT, int NB = 2, bool PACK = false>
 hipError_t launch_nw(const SearchArgs &a, int64_t row0, int64_t row1, int S, int64_t split_rows, MfmaIo o, hipStream_t st)
 {
     const int qtiles = (int)ceil_div(a.nq, RSPLIT ? NQW : NW * NB * 32);
-    const size_t lds = lds_bytes(KS, SEED, NW, RSPLIT, NB);
-    auto kern = search_mfma_kernel<KS, L2, KCAP, SEED, NW, RSPLIT, NB>;
+    const size_t lds = lds_bytes(KS, SEED, NW, RSPLIT, NB, PACK);
+    auto kern = search_mfma_kernel<KS, L2, KCAP, SEED, NW, RSPLIT, NB, PACK>;
     static bool attr_set = false;  // per instantiation
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -689,6 +706,14 @@ hipError_t launch_one(const SearchArgs &a, int64_t row0, int64_t row1, int S, Mf
     // rows of a split: a whole number of stages; splits follow each other unless a stride is given
     const int64_t split_rows = o.split_stride ? o.split_stride_rows : round_up(ceil_div(row1 - row0, S), a.rsplit ? 128 : 64);
     if (!o.split_stride) o.split_stride = split_rows;
+    if constexpr (KCAP != 0) {   // packed rows: row-split launches with register lists (and their seeding pass)
+        if (a.packed) {
+            if (!a.rsplit) return hipErrorInvalidValue;
+            return launch_nw<KS, L2, KCAP, SEED, 4, true, 2, true>(a, row0, row1, S, split_rows, o, st);
+        }
+    } else if (a.packed) {
+        return hipErrorInvalidValue;
+    }
     if constexpr (KS <= 4) {
         if (a.rsplit) return launch_nw<KS, L2, KCAP, SEED, 4, true>(a, row0, row1, S, split_rows, o, st);
         if constexpr (KCAP == 0 || SEED) {
@@ -743,7 +768,7 @@ int mfma_queries_per_workgroup(int64_t nq, int d_pad, bool wide) { return mfma_r
 bool mfma_collect_wide(int64_t nq, int d_pad) { return !mfma_row_split(nq, d_pad) && d_pad <= 128 && nq > 256; }
 
 // Few queries: the waves of a workgroup share them and split the rows instead.
-bool mfma_row_split(int64_t nq, int d_pad) { return nq <= 64 && d_pad <= 128; }
+bool mfma_row_split(int64_t nq, int d_pad, bool packed) { return nq <= 64 && d_pad <= (packed ? 256 : 128); }
 
 bool mfma_reg_supported(int d_pad, int k) { return shape_ok(d_pad) && k >= 1 && k <= 16; }
 

@@ -54,6 +54,7 @@ def lib() -> C.CDLL:
             "lpq_quantizer_get_params": (i32, [vp, vp, vp, vp, vp]),
             "lpq_encode": (i32, [vp, vp, i64, i64, vp, i64, vp, vp]),
             "lpq_index_create": (i32, [C.POINTER(vp), vp, i64]),
+            "lpq_index_create_packed": (i32, [C.POINTER(vp), vp, i64]),
             "lpq_index_destroy": (None, [vp]),
             "lpq_index_add_f32": (i32, [vp, vp, i64, i64, vp]),
             "lpq_index_add_i8": (i32, [vp, vp, i64, i64, vp]),
@@ -163,10 +164,11 @@ class Quantizer:
 class Index:
     """lpq_index_* and lpq_search*: the flat int8 corpus and exhaustive top-k search."""
 
-    def __init__(self, quantizer: Quantizer, capacity: int):
+    def __init__(self, quantizer: Quantizer, capacity: int, packed: bool = False):
         h = C.c_void_p()
-        _check(lib().lpq_index_create(C.byref(h), quantizer._h, capacity))
-        self._h, self.d, self.capacity = h, quantizer.d, capacity
+        create = lib().lpq_index_create_packed if packed else lib().lpq_index_create
+        _check(create(C.byref(h), quantizer._h, capacity))
+        self._h, self.d, self.capacity, self.packed = h, quantizer.d, capacity, packed
         self._ws = None
 
     def __del__(self):
@@ -195,6 +197,23 @@ class Index:
         cp, ld, npn = C.c_void_p(), C.c_int64(), C.c_void_p()
         _check(lib().lpq_index_data(self._h, C.byref(cp), C.byref(ld), C.byref(npn)))
         return cp.value, ld.value, npn.value
+
+    def storage(self):
+        """Host copies (numpy) of the stored rows, uint8 [size, ld_codes] as they lie in device memory
+        (int8 codes, or two nibbles per byte for a packed index), and of the norms int32 [size]."""
+        import numpy as np
+        cp, ld, npn = self.data()
+        torch.cuda.synchronize()
+        n = self.size
+        rows = torch.empty((n, ld), dtype=torch.uint8, device="cuda")
+        norms = torch.empty((n,), dtype=torch.int32, device="cuda")
+        hip = C.CDLL("libamdhip64.so")
+        hip.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
+        for dst, src, nb in ((rows, cp, n * ld), (norms, npn, n * 4)):
+            rc = hip.hipMemcpy(dst.data_ptr(), src, nb, 3)   # device to device
+            if rc:
+                raise LpqError(-1, f"hipMemcpy failed with {rc}")
+        return np.asarray(rows.cpu()), np.asarray(norms.cpu())
 
     def workspace_bytes(self, nq: int, k: int, metric="l2sq") -> int:
         return lib().lpq_search_workspace_bytes(self._h, nq, k, METRIC[metric])

@@ -1,0 +1,135 @@
+"""Parity of the packed (two codes per byte) index against the CPU oracle, through the C ABI:
+stored bytes and norms bit-exact against the storage definition, search results bit-exact
+against the oracle's exhaustive search over the saturated codes.  Needs a real MI355X."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2110_08919_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+BASES = {"skewed": synth.SKEWED_1M, "aniso": synth.ANISO_1M2, "scaled": synth.SCALED_10M,
+         "product": synth.PRODUCT_100M, "tiny": synth.TINY}
+
+
+@pytest.fixture(scope="module")
+def lpq():
+    from paper_2110_08919_amd import lpq as m
+    assert torch.cuda.is_available(), "no GPU visible"
+    m.lib()
+    return m
+
+
+def _oracle_quant(oracle, gq):
+    k, sb, se, m = gq.get_params()
+    oq = oracle.Quantizer(gq.d, gq.bits).set_params(k, sb, se)
+    assert np.array_equal(oq.m, m)
+    return oq
+
+
+def _padded_features(d):
+    return next(p for p in (64, 96, 128, 192, 256) if d <= p)
+
+
+def _build(lpq, oracle, w, bits, mode, scope):
+    x, q = w.corpus(), w.queries()
+    xd = x.cuda()
+    gq = lpq.Quantizer(w.d, bits).calibrate(xd, mode, scope)
+    idx = lpq.Index(gq, w.n, packed=True).add_f32(xd)
+    assert idx.size == w.n
+    oq = _oracle_quant(oracle, gq)
+    ocodes = oracle.nibble_codes(oq.encode(x.numpy()))
+    oqcodes = oracle.nibble_codes(oq.encode(q.numpy()))
+    return idx, gq, q, ocodes, oqcodes
+
+
+@pytest.mark.parametrize("name,n,bits,mode,scope", [
+    ("tiny", 3001, 4, "minmax", "per_feature"),      # d = 128; min/max calibration reaches the top code + 8
+    ("aniso", 2050, 4, "absmax", "global"),          # d = 100 -> 128 features per row
+    ("scaled", 1000, 3, "absmax", "global"),         # d = 96
+    ("product", 777, 2, "absmax", "per_feature"),    # d = 256
+])
+def test_packed_rows_and_norms_bit_exact(lpq, oracle, name, n, bits, mode, scope):
+    w = BASES[name].scaled(n=n, nq=4)
+    idx, gq, q, ocodes, _ = _build(lpq, oracle, w, bits, mode, scope)
+    rows, norms = idx.storage()
+    d_pad = _padded_features(w.d)
+    assert rows.shape == (n, d_pad // 2)
+    assert np.array_equal(rows, oracle.pack_nibbles(ocodes, d_pad))
+    assert np.array_equal(norms, (ocodes.astype(np.int64) ** 2).sum(axis=1).astype(np.int32))
+    if bits == 4 and mode == "minmax":
+        # the case the saturation exists for is present in the data
+        raw = _oracle_quant(oracle, gq).encode(w.corpus().numpy())
+        assert int(raw.max()) == 8 and int(ocodes.max()) == 7
+
+
+@pytest.mark.parametrize("name,n,nq,k,metric,bits,mode,scope", [
+    ("tiny", 10000, 100, 10, "l2sq", 4, "minmax", "per_feature"),     # two query tiles, the second ragged
+    ("skewed", 70001, 16, 10, "l2sq", 4, "minmax", "global"),         # ragged last stage, seeding pass
+    ("skewed", 140000, 5, 16, "l2sq", 4, "minmax", "per_feature"),    # largest k; three staging chunks on add
+    ("aniso", 66000, 64, 10, "ip", 4, "absmax", "global"),            # d = 100, inner product: per-query term
+    ("aniso", 12345, 130, 1, "ip", 3, "absmax", "global"),            # three tiles
+    ("scaled", 90000, 33, 10, "l2sq", 4, "absmax", "global"),         # d = 96
+    ("product", 50000, 20, 10, "ip", 4, "absmax", "per_feature"),     # d = 256: 128-byte rows
+    ("product", 9000, 70, 16, "l2sq", 2, "absmax", "per_feature"),    # 2 bits: ties everywhere
+    ("tiny", 40, 3, 1, "ip", 4, "absmax", "global"),                  # fewer items than one stage
+    ("tiny", 300, 200, 16, "l2sq", 4, "minmax", "global"),
+])
+def test_packed_search_bit_exact(lpq, oracle, name, n, nq, k, metric, bits, mode, scope):
+    w = BASES[name].scaled(n=n, nq=nq)
+    idx, gq, q, ocodes, oqcodes = _build(lpq, oracle, w, bits, mode, scope)
+    ids, dists = idx.search(q.cuda(), k, metric)
+    torch.cuda.synchronize()
+    oids, odists = oracle.search_i8(ocodes, oqcodes, k, metric, threads=16)
+    assert np.array_equal(dists.cpu().numpy(), odists)
+    assert np.array_equal(ids.cpu().numpy(), oids)
+    # the same through the entry point that takes codes (unsaturated ones: the library saturates)
+    raw_q = _oracle_quant(oracle, gq).encode(q.numpy())
+    ids2, dists2 = idx.search(torch.from_numpy(raw_q).cuda(), k, metric)
+    torch.cuda.synchronize()
+    assert torch.equal(ids2, ids) and torch.equal(dists2, dists)
+
+
+def test_packed_equals_unpacked_index_of_saturated_codes_and_incremental_add(lpq, oracle):
+    w = synth.SKEWED_1M.scaled(n=100_000, nq=48)
+    x, q = w.corpus().cuda(), w.queries().cuda()
+    gq = lpq.Quantizer(w.d, 4).calibrate(x, "minmax", "global")
+    codes = gq.encode(x)
+    sat = codes.clamp(-8, 7)
+    plain = lpq.Index(gq, w.n).add_i8(sat)
+    packed = lpq.Index(gq, w.n, packed=True)
+    packed.add_i8(codes[:33_333]).add_f32(x[33_333:70_000]).add_i8(sat[70_000:])
+    assert packed.size == w.n
+    qc = gq.encode(q).clamp(-8, 7)
+    for metric in ("l2sq", "ip"):
+        a = plain.search(qc, 10, metric)
+        b = packed.search(q, 10, metric)
+        torch.cuda.synchronize()
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    # half the bytes per row
+    assert packed.data()[1] * 2 == plain.data()[1]
+
+
+def test_packed_error_codes(lpq):
+    w = synth.TINY.scaled(n=500, nq=4)
+    x, q = w.corpus().cuda(), w.queries().cuda()
+    g8 = lpq.Quantizer(w.d, 8).calibrate(x, "minmax", "per_feature")
+    with pytest.raises(lpq.LpqError) as e:
+        lpq.Index(g8, 500, packed=True)
+    assert e.value.code == lpq.EINVAL                     # more than 4 bits
+    wide = torch.randn(64, 300, device="cuda")
+    gw = lpq.Quantizer(300, 4).calibrate(wide, "minmax", "per_feature")
+    with pytest.raises(lpq.LpqError) as e:
+        lpq.Index(gw, 64, packed=True)
+    assert e.value.code == lpq.ERANGE                     # more than 256 features
+    g4 = lpq.Quantizer(w.d, 4).calibrate(x, "minmax", "per_feature")
+    idx = lpq.Index(g4, 500, packed=True).add_f32(x)
+    with pytest.raises(lpq.LpqError) as e:
+        idx.search(q, 17, "l2sq")
+    assert e.value.code == lpq.ERANGE                     # k beyond the packed scan's lists
+    assert idx.workspace_bytes(4, 17) == 0
+    with pytest.raises(lpq.LpqError) as e:
+        idx.gather_dist(torch.zeros((4, w.d), dtype=torch.int8, device="cuda"),
+                        torch.zeros((4, 3), dtype=torch.int32, device="cuda"))
+    assert e.value.code == lpq.EINVAL

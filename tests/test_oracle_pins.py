@@ -389,3 +389,24 @@ def test_quantile_clip_matches_numpy_order_statistics(oracle, scope):
             assert np.array_equal(q.sb, mm.sb) and np.array_equal(q.se, mm.se) and np.array_equal(q.m, mm.m)
     q = oracle.Quantizer(7, 8).calibrate(x, "quantile", "per_feature", sigma_mult=0.01)
     assert q.se[2] < 10.0               # the outlier no longer sets the range
+
+
+# ---------------------------------------------------------------- nibble storage (B <= 4)
+def test_nibble_saturation_and_packing_by_hand(oracle):
+    # every int8 value: only those outside [-8, 7] change, and they move to the nearer end
+    allv = np.arange(-128, 128).astype(np.int8)
+    sat = oracle.nibble_codes(allv)
+    for v, s in zip(allv.tolist(), sat.tolist()):
+        assert s == (7 if v > 7 else -8 if v < -8 else v)
+    # bytes written out by hand: (-8, 7) -> 0x0 | 0xF << 4; (0, 0) -> 0x88; (8 -> 7, -1) -> 0xF | 0x7 << 4;
+    # an odd feature count leaves the high nibble at code 0 (= 8), padding bytes are 0x88
+    rows = np.array([[-8, 7, 0, 0, 8, -1, 3]], np.int8)
+    packed = oracle.pack_nibbles(rows, 10)
+    assert packed.tolist() == [[0xF0, 0x88, 0x7F, 0x8B, 0x88]]
+    # unpacking with shifts and masks gives the saturated codes back
+    rng = np.random.default_rng(5)
+    c = rng.integers(-9, 10, size=(7, 13)).astype(np.int8)
+    p = oracle.pack_nibbles(c, 16).astype(np.int32)
+    un = np.stack([(p & 15) - 8, (p >> 4) - 8], axis=2).reshape(7, 16)
+    assert np.array_equal(un[:, :13], oracle.nibble_codes(c))
+    assert np.all(un[:, 13:] == 0)
