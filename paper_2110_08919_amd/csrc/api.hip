@@ -479,6 +479,8 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
         p.mode = (regs && want != 1) ? PLAN_MFMA_REG : (mfma_lds_supported(idx->d_pad, k) ? PLAN_MFMA_LDS : PLAN_GENERIC);
     }
 
+    // lists one merge launch takes: the register-list scan's come out sorted, which allows more of them
+    const int one_pass = p.mode == PLAN_MFMA_REG ? merge_max_sorted_lists(k) : merge_max_lists(k);
     auto splits_for = [&](int64_t rows, int64_t tiles_q, int64_t min_rows, int64_t slots, int64_t cap) {
         int64_t s;
         if (p.mode != PLAN_GENERIC) s = g_tune[LPQ_TUNE_SPLITS] > 0 ? g_tune[LPQ_TUNE_SPLITS] : slots / (tiles_q > 0 ? tiles_q : 1);
@@ -518,7 +520,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     p.seed_rows = seed;
     p.S2 = splits_for(gmode ? n : n - seed, tiles_q, min_rows, slots_now,
                       p.mode == PLAN_MFMA_COLLECT ? (p.rsplit ? 512 : 2048)
-                                                  : (p.rsplit ? merge_max_lists(k) : max_lists));   // few queries: one merge pass
+                                                  : (p.rsplit ? one_pass : max_lists));   // few queries: one merge pass
     if (p.mode == PLAN_MFMA_COLLECT) {
         // expected candidates per query ~ k n / seed_rows, spread evenly over SS regions (the scan
         // deals its stages round-robin to the splits); a region holds three times its share, at
@@ -547,7 +549,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     p.off_gmax = o;
     if (gmode && seed) o = align256(o + (size_t)p.nq_pad * p.G * sizeof(int32_t));
     p.off_merge_tmp = o;
-    if (p.mode != PLAN_MFMA_COLLECT && p.S2 > merge_max_lists(k)) {
+    if (p.mode != PLAN_MFMA_COLLECT && p.S2 > one_pass) {
         p.merge_group = merge_max_lists(k);
         o = align256(o + (size_t)nq * ceil_div(p.S2, p.merge_group) * k * sizeof(cand_t));
     }

@@ -175,6 +175,7 @@ hipError_t launch_merge(const cand_t *lists, int64_t nq, int P, int k, const can
                         const int32_t *qnorms, int metric, hipStream_t st, bool sorted_lists = false,
                         const int32_t *only = nullptr);   // only (optional): int[nq]; queries with only[q] == 0 are skipped
 int merge_max_lists(int k);
+int merge_max_sorted_lists(int k);   // same for lists that are each sorted (k <= 32: more of them)
 // First pass of a two-pass merge: groups of `group` consecutive lists of each query are merged
 // into out_lists[q][ceil(P/group)][k].
 hipError_t launch_merge_groups(const cand_t *lists, int64_t nq, int P, int group, int k, cand_t *out_lists,

@@ -41,28 +41,23 @@ __device__ __forceinline__ unsigned lds_offset(const void *p)
     return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
 }
 
-// s_waitcnt vmcnt(n) with n a run-time value in 0..15 (other counters untouched).
+// s_waitcnt vmcnt(n) with n a run-time value in 0..63 (other counters untouched).  The count is
+// an immediate, split over bits 3:0 and 15:14 of the operand.
+#define LPQ_WAITCNT_CASE(N) case N: __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14)); break;
+#define LPQ_WAITCNT_CASES8(B) LPQ_WAITCNT_CASE(B) LPQ_WAITCNT_CASE(B + 1) LPQ_WAITCNT_CASE(B + 2) LPQ_WAITCNT_CASE(B + 3) \
+    LPQ_WAITCNT_CASE(B + 4) LPQ_WAITCNT_CASE(B + 5) LPQ_WAITCNT_CASE(B + 6) LPQ_WAITCNT_CASE(B + 7)
 __device__ __forceinline__ void wait_vmcnt(int n)
 {
     switch (n) {
-    case 0: __builtin_amdgcn_s_waitcnt(0x0F70); break;
-    case 1: __builtin_amdgcn_s_waitcnt(0x0F71); break;
-    case 2: __builtin_amdgcn_s_waitcnt(0x0F72); break;
-    case 3: __builtin_amdgcn_s_waitcnt(0x0F73); break;
-    case 4: __builtin_amdgcn_s_waitcnt(0x0F74); break;
-    case 5: __builtin_amdgcn_s_waitcnt(0x0F75); break;
-    case 6: __builtin_amdgcn_s_waitcnt(0x0F76); break;
-    case 7: __builtin_amdgcn_s_waitcnt(0x0F77); break;
-    case 8: __builtin_amdgcn_s_waitcnt(0x0F78); break;
-    case 9: __builtin_amdgcn_s_waitcnt(0x0F79); break;
-    case 10: __builtin_amdgcn_s_waitcnt(0x0F7A); break;
-    case 11: __builtin_amdgcn_s_waitcnt(0x0F7B); break;
-    case 12: __builtin_amdgcn_s_waitcnt(0x0F7C); break;
-    case 13: __builtin_amdgcn_s_waitcnt(0x0F7D); break;
-    case 14: __builtin_amdgcn_s_waitcnt(0x0F7E); break;
-    default: __builtin_amdgcn_s_waitcnt(0x0F7F); break;
+    LPQ_WAITCNT_CASES8(0) LPQ_WAITCNT_CASES8(8) LPQ_WAITCNT_CASES8(16) LPQ_WAITCNT_CASES8(24)
+    LPQ_WAITCNT_CASES8(32) LPQ_WAITCNT_CASES8(40) LPQ_WAITCNT_CASES8(48)
+    LPQ_WAITCNT_CASE(56) LPQ_WAITCNT_CASE(57) LPQ_WAITCNT_CASE(58) LPQ_WAITCNT_CASE(59) LPQ_WAITCNT_CASE(60)
+    LPQ_WAITCNT_CASE(61) LPQ_WAITCNT_CASE(62)
+    default: __builtin_amdgcn_s_waitcnt(0xCF7F); break;   // 63: the counter's maximum
     }
 }
+#undef LPQ_WAITCNT_CASES8
+#undef LPQ_WAITCNT_CASE
 
 // A candidate can only beat the threshold candidate c if its E is >= thr_e(c).
 __device__ inline int thr_e(cand_t c)

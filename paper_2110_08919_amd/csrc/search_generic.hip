@@ -378,6 +378,16 @@ namespace {
 
 int merge_max_lists(int k) { return 4096 / k - 1; }
 
+// Lists of k that are each sorted and short (k <= 32) merge by repeated extraction, which needs
+// no power-of-two buffer: as many lists as 128 KB of LDS hold, at most 1024.
+static size_t merge_sorted_lds(int lists, int k) { return (size_t)(lists + 4) * k * sizeof(cand_t) + (size_t)lists * sizeof(int); }
+int merge_max_sorted_lists(int k)
+{
+    if (k > 32) return merge_max_lists(k);
+    int p = (int)((131072 - 32 * (size_t)k) / (8 * (size_t)k + 4)) - 1;   // one spare for an extra list
+    return p > 1024 ? 1024 : p;
+}
+
 hipError_t launch_collect_select(const cand_t *cbuf, const int32_t *ccnt, int64_t nq, int SS, int Cs, int k,
                                  int32_t *over, int32_t *qlist, int32_t *qcount, int32_t *ids, int32_t *dists,
                                  const int32_t *qnorms, int metric, hipStream_t st, int expected_candidates)
@@ -425,9 +435,16 @@ hipError_t launch_merge(const cand_t *lists, int64_t nq, int P, int k, const can
 {
     if (nq <= 0) return hipSuccess;
     const int total = P * k + (extra_lists ? k : 0);
-    if (!only && sorted_lists && k <= 32 && total >= 1024 && total <= 4096) {   // many short sorted lists
+    if (!only && sorted_lists && k <= 32 && total >= 1024 && P <= merge_max_sorted_lists(k)) {   // many short sorted lists
         const int Pt = P + (extra_lists ? 1 : 0);
-        const size_t lds = (size_t)(Pt + 4) * k * sizeof(cand_t) + (size_t)Pt * sizeof(int);
+        const size_t lds = merge_sorted_lds(Pt, k);
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(merge_sorted_kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
         merge_sorted_kernel<<<(unsigned)nq, 256, lds, st>>>(lists, P, k, extra_lists, out_lists, seeds_out, ids,
                                                            dists, qnorms, metric);
         return hipGetLastError();

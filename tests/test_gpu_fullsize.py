@@ -97,3 +97,29 @@ def test_config5_product_x256_ip_k100(lpq, oracle):
     (25.6 GB of codes; the oracle then needs several minutes and ~60 GB of host memory)."""
     n = 100_000_000 if os.environ.get("LPQ_TEST_FULL_100M") == "1" else 8_000_000
     _full_case(lpq, oracle, synth.PRODUCT_100M.scaled(n=n, nq=1000), 100, "absmax", "per_feature", sample=4)
+
+
+def test_config4_scaled_10m_x96_packed_4bit(lpq, oracle):
+    """The small-batch workload with two 4-bit codes per byte (quantile-clip calibration): batches of
+    1, 16 and 100 queries against the oracle's search over the saturated codes."""
+    w = synth.SCALED_10M.scaled(nq=100)
+    x, q = w.corpus("cuda"), w.queries("cuda")
+    quant = lpq.Quantizer(w.d, 4).calibrate(x, "quantile", "global", 0.001)
+    index = lpq.Index(quant, w.n, packed=True).add_f32(x)
+    kq, sb, se, m = quant.get_params()
+    oq = oracle.Quantizer(w.d, 4).set_params(kq, sb, se)
+    assert np.array_equal(oq.m, m)
+    codes = oracle.nibble_codes(oq.encode(x.cpu().numpy()))
+    qcodes = oracle.nibble_codes(oq.encode(q.cpu().numpy()))
+    del x
+    ids, dists = index.search(q, 10, "l2sq")
+    torch.cuda.synchronize()
+    ids, dists = ids.cpu().numpy(), dists.cpu().numpy()
+    _check_properties(ids, dists, codes, qcodes, "l2sq")
+    pick = np.array([0, 1, 15, 16, 63, 64, 65, 99])
+    oids, odists = oracle.search_i8(codes, qcodes[pick], 10, "l2sq", threads=16)
+    assert np.array_equal(dists[pick], odists)
+    assert np.array_equal(ids[pick], oids)
+    for nb in (1, 16):
+        bi, bd = index.search(q[:nb], 10, "l2sq")
+        assert np.array_equal(bi.cpu().numpy(), ids[:nb]) and np.array_equal(bd.cpu().numpy(), dists[:nb])
