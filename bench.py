@@ -60,8 +60,9 @@ def main():
     ap.add_argument("--workload", default="skewed_1m", choices=["tiny", "skewed_1m", "aniso_1m2", "scaled_10m", "product_100m"],
                     help="synthetic workload shape (default: the benchmark configuration)")
     ap.add_argument("--extras", action="store_true",
-                    help="also time the candidate-list calls (gathered distances, fp32 re-rank) and report recall "
-                         "before / after the re-rank for a per-feature 6-bit quantizer")
+                    help="also time the candidate-list calls (gathered distances, fp32 re-rank), report recall "
+                         "before / after the re-rank for a per-feature 6-bit quantizer, and time a small batch on "
+                         "4-bit codes stored one and two per byte")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 512 MiB device copy (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -193,6 +194,20 @@ def main():
                                   "GBps_rows": w.nq * m * (w.d + 4) / g_ms / 1e6},
                   "rerank_f32": {"queries": rq2, "candidates": 4 * k, "ms": r_ms,
                                  "recall_6bit_per_feature": rec(c_ids, ex), "recall_after_rerank": rec(f_ids, ex)}}
+
+        # 4-bit codes, one per byte against two per byte: the byte-bound small batch
+        if k <= 16 and w.d <= 256:
+            q4 = lpq.Quantizer(w.d, 4).calibrate(x, "quantile", w.scope, 0.001)
+            nb = min(16, w.nq)
+            packed = {}
+            for name, pk in (("one_code_per_byte", False), ("two_codes_per_byte", True)):
+                i4 = lpq.Index(q4, w.n, packed=pk).add_f32(x)
+                p_ids, _ = i4.search(q[:rq2], k, metric)
+                p_ms, _ = timed(lambda: i4.search(q[:nb], k, metric), reps=20)
+                packed[name] = {"ms": p_ms, "batch": nb, "recall": rec(p_ids, ex),
+                                "GBps_rows": w.n * (i4.data()[1] + 4) / p_ms / 1e6}
+                del i4
+            extras["four_bit_quantile_clip"] = packed
 
     # ---- CPU baseline: the oracle, on a bounded sample -----------------------------------
     cpu = None
