@@ -49,11 +49,13 @@ def _full_case(lpq, oracle, w, k, mode, scope, sample, batches=None, threads=16)
     kq, sb, se, m = quant.get_params()
     oq = oracle.Quantizer(w.d, 8).set_params(kq, sb, se)
     assert np.array_equal(oq.m, m)
+    print(f"[{w.name}] index built, {w.n} rows; oracle encodes", flush=True)
     xh, qh = x.cpu().numpy(), q.cpu().numpy()
     codes, qcodes = oq.encode(xh), oq.encode(qh)
+    print(f"[{w.name}] oracle codes ready", flush=True)
     del xh
     # the encode kernel gives exactly the oracle's codes and norms (spot rows)
-    probe = torch.linspace(0, w.n - 1, 4000).long().cuda()
+    probe = torch.linspace(0, w.n - 1, 4000, dtype=torch.float64).long().clamp_(0, w.n - 1).cuda()   # binary32 would round n - 1 up to n beyond 2^24 rows
     pc, pn = quant.encode(x[probe].contiguous(), with_norms=True)
     assert np.array_equal(pc.cpu().numpy(), codes[probe.cpu().numpy()])
     assert np.array_equal(pn.cpu().numpy(), (codes[probe.cpu().numpy()].astype(np.int64) ** 2).sum(1))
@@ -64,6 +66,7 @@ def _full_case(lpq, oracle, w, k, mode, scope, sample, batches=None, threads=16)
     ids, dists = ids.cpu().numpy(), dists.cpu().numpy()
     _check_properties(ids, dists, codes, qcodes, w.metric)
     pick = np.unique(np.linspace(0, w.nq - 1, sample).astype(np.int64))
+    print(f"[{w.name}] properties hold for all queries; oracle searches {len(pick)} of them", flush=True)
     oids, odists = oracle.search_i8(codes, qcodes[pick], k, w.metric, threads=threads)
     assert np.array_equal(dists[pick], odists)
     assert np.array_equal(ids[pick], oids)
@@ -93,9 +96,10 @@ def test_config4_scaled_10m_x96_batch_sweep(lpq, oracle):
 
 def test_config5_product_x256_ip_k100(lpq, oracle):
     """d = 256, inner product, k = 100 on the bimodal product-embedding recipe.  The corpus is
-    8M rows by default (about a minute with the oracle); LPQ_TEST_FULL_100M=1 runs all 100M rows
-    (25.6 GB of codes; the oracle then needs several minutes and ~60 GB of host memory)."""
-    n = 100_000_000 if os.environ.get("LPQ_TEST_FULL_100M") == "1" else 8_000_000
+    8M rows by default (about a minute with the oracle); LPQ_TEST_CONFIG5_ROWS sets another size
+    (from 17M rows on, byte offsets into the codes pass 2^32); LPQ_TEST_FULL_100M=1 runs all 100M
+    rows (25.6 GB of codes; the oracle then needs several minutes and ~130 GB of host memory)."""
+    n = 100_000_000 if os.environ.get("LPQ_TEST_FULL_100M") == "1" else int(os.environ.get("LPQ_TEST_CONFIG5_ROWS", 8_000_000))
     _full_case(lpq, oracle, synth.PRODUCT_100M.scaled(n=n, nq=1000), 100, "absmax", "per_feature", sample=4)
 
 
