@@ -5,6 +5,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <cmath>
 #include <vector>
 
 #include "lpq_internal.h"
@@ -468,9 +469,18 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
         seed = gm ? (few ? n / 16 : n / 8) : n / 64;
         const int64_t lo = gm ? 8192 : 4096, hi = p.mode == PLAN_MFMA_COLLECT ? n : (gm ? (few ? 65536 : 131072) : 32768);
         seed = seed < lo ? lo : (seed > hi ? hi : seed);
-        if (p.mode == PLAN_MFMA_COLLECT) {   // no tightening during the scan: the sample grows with k, n/8 .. n/4
-            const int64_t by_k = n / 400 * k, least = few ? n / 16 : n / 8, most = few ? n / 8 : n / 4;
+        if (p.mode == PLAN_MFMA_COLLECT && few) {   // no tightening during the scan: the sample grows with k
+            const int64_t by_k = n / 400 * k, least = n / 16, most = n / 8;
             seed = by_k < least ? least : (by_k > most ? most : by_k);
+        } else if (p.mode == PLAN_MFMA_COLLECT) {
+            // The sample costs time in proportion to its rows, the candidates it lets through in
+            // proportion to k n / rows: the sum is least at rows ~ sqrt(k n) (coefficient measured:
+            // 125 000 rows at n = 1M, k = 10).  At least k n / 1500, so that the ~1.15 k n / rows
+            // candidates of a query stay well inside the 4096 the selection kernel sorts; at most n / 4.
+            const double by_cost = 125000.0 * std::sqrt((double)n / 1e6 * (double)k / 10.0);
+            const double by_room = (double)k * (double)n / 1500.0;
+            const double want_rows = by_cost > by_room ? by_cost : by_room;
+            seed = want_rows > (double)(n / 4) ? n / 4 : (int64_t)want_rows;
         }
     }
     seed = seed / 256 * 256;
