@@ -61,8 +61,16 @@ enum {
 enum { LPQ_CALIB_MINMAX = 0, LPQ_CALIB_ABSMAX = 1, LPQ_CALIB_GAUSS = 2, LPQ_CALIB_QUANTILE = 3 };
 
 /* PER_FEATURE: constants per dimension (the superscripts i of Equation 1).
- * GLOBAL: one set of constants from all n*d values, for all dimensions (Section 4.1). */
-enum { LPQ_SCOPE_PER_FEATURE = 0, LPQ_SCOPE_GLOBAL = 1 };
+ * GLOBAL: one set of constants from all n*d values, for all dimensions (Section 4.1).
+ * SHARED_WIDTH: an offset per dimension and one scale for all of them - the "normalization
+ *   constants for both scale and offset" that the end of Section 3.2 asks for when dimensions
+ *   differ.  The PER_FEATURE constants are learned first; then every range keeps its centre
+ *   (S_b + S_e) / 2 and takes the half-width of the widest range, H = max_i (S_e - S_b) / 2
+ *   (binary64 on the binary32 constants): S_b = fl32(centre - H), S_e = fl32(centre + H),
+ *   k unchanged.  One code step then has the same length in every dimension, so L2SQ on codes
+ *   weighs all dimensions alike (PER_FEATURE turns it into a weighted distance) while offsets
+ *   between dimensions cost no code range (as they do under GLOBAL). */
+enum { LPQ_SCOPE_PER_FEATURE = 0, LPQ_SCOPE_GLOBAL = 1, LPQ_SCOPE_SHARED_WIDTH = 2 };
 
 /* L2SQ: sum_i (a_i - b_i)^2 on codes, smaller = nearer.
  * IP:   sum_i a_i b_i on codes, LARGER = nearer (maximum inner product search, Section

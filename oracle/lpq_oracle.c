@@ -16,7 +16,10 @@
  *                 S_e = mu + sigma, k = mu), Section 4.1 (one mu, sigma for all
  *                 dimensions), Section 4.2 (absolute maximum per dimension),
  *                 plus the [min, max] reading of "the range of values that appear
- *                 in practice" (Section 1).
+ *                 in practice" (Section 1); and, for the closing remark of Section
+ *                 3.2 (data with high interdimensional variance need constants for
+ *                 both scale and offset), a scope with one offset per dimension and
+ *                 one range width for all of them.
  *   encode        Equation 1, evaluated in IEEE binary32 as two rounded
  *                 operations t = (x - k) * m with m = fl32(2^B / (S_e - S_b)),
  *                 then floor; the result +2^(B-1) of the upper clamp is kept for
@@ -45,7 +48,7 @@
 #endif
 
 enum { LPQO_MINMAX = 0, LPQO_ABSMAX = 1, LPQO_GAUSS = 2, LPQO_QUANTILE = 3 };
-enum { LPQO_PER_FEATURE = 0, LPQO_GLOBAL = 1 };
+enum { LPQO_PER_FEATURE = 0, LPQO_GLOBAL = 1, LPQO_SHARED_WIDTH = 2 };
 enum { LPQO_L2SQ = 0, LPQO_IP = 1 };
 
 /* m = fl32( 2^B / (S_e - S_b) ), the multiplier of Equation 1; 0 marks a feature
@@ -128,7 +131,7 @@ static void quantile_range(float *vals, int64_t cnt, double p, double *lo, doubl
 int lpqo_calibrate(const float *x, int64_t n, int64_t ld, int d, int bits, int mode, int scope,
                    double sigma_mult, float *k, float *sb, float *se, float *m)
 {
-    if (scope == LPQO_PER_FEATURE) {
+    if (scope == LPQO_PER_FEATURE || scope == LPQO_SHARED_WIDTH) {
         for (int i = 0; i < d; ++i) {
             stat_t s; stat_init(&s);
             for (int64_t j = 0; j < n; ++j) stat_add(&s, x[j * ld + i]);
@@ -165,6 +168,21 @@ int lpqo_calibrate(const float *x, int64_t n, int64_t ld, int d, int bits, int m
         float k0, sb0, se0;
         constants_from(mode, sigma_mult, s.mn, s.mx, s.amax, mu, sigma, &k0, &sb0, &se0);
         for (int i = 0; i < d; ++i) { k[i] = k0; sb[i] = sb0; se[i] = se0; }
+    }
+    if (scope == LPQO_SHARED_WIDTH) {
+        /* Offsets stay per dimension, the scale becomes common: every range keeps its centre
+         * and takes the half-width of the widest one, so that one code step is the same length
+         * in every dimension and the squared distance of codes weighs all of them alike. */
+        double half = 0.0;
+        for (int i = 0; i < d; ++i) {
+            double h = ((double)se[i] - (double)sb[i]) / 2.0;
+            if (h > half) half = h;
+        }
+        for (int i = 0; i < d; ++i) {
+            double centre = ((double)sb[i] + (double)se[i]) / 2.0;
+            sb[i] = (float)(centre - half);
+            se[i] = (float)(centre + half);
+        }
     }
     lpqo_derive_m(sb, se, d, bits, m);
     return 0;

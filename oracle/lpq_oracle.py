@@ -18,11 +18,11 @@ _SRC = os.path.join(_HERE, "lpq_oracle.c")
 _LIB = os.path.join(_HERE, "liblpq_oracle.so")
 
 MINMAX, ABSMAX, GAUSS = 0, 1, 2
-PER_FEATURE, GLOBAL = 0, 1
+PER_FEATURE, GLOBAL, SHARED_WIDTH = 0, 1, 2
 L2SQ, IP = 0, 1
 
 _CALIB = {"minmax": MINMAX, "absmax": ABSMAX, "gauss": GAUSS, "quantile": 3}
-_SCOPE = {"per_feature": PER_FEATURE, "global": GLOBAL}
+_SCOPE = {"per_feature": PER_FEATURE, "global": GLOBAL, "shared_width": SHARED_WIDTH}
 _METRIC = {"l2sq": L2SQ, "ip": IP}
 
 

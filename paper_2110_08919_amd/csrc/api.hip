@@ -172,7 +172,7 @@ extern "C" int lpq_quantizer_calibrate(lpq_quantizer *q, const float *x_dev, int
     if (ld < q->d) return fail(LPQ_EINVAL, "ld = %lld < d = %d", (long long)ld, q->d);
     if (mode < LPQ_CALIB_MINMAX || mode > LPQ_CALIB_QUANTILE) return fail(LPQ_EINVAL, "unknown calibration mode %d", mode);
     if (mode == LPQ_CALIB_QUANTILE && !(sigma_mult >= 0.0f && sigma_mult < 0.5f)) return fail(LPQ_EINVAL, "clip fraction must be in [0, 0.5)");
-    if (scope != LPQ_SCOPE_PER_FEATURE && scope != LPQ_SCOPE_GLOBAL) return fail(LPQ_EINVAL, "unknown scope %d", scope);
+    if (scope != LPQ_SCOPE_PER_FEATURE && scope != LPQ_SCOPE_GLOBAL && scope != LPQ_SCOPE_SHARED_WIDTH) return fail(LPQ_EINVAL, "unknown scope %d", scope);
     if (mode == LPQ_CALIB_GAUSS && !(sigma_mult > 0.0f)) return fail(LPQ_EINVAL, "sigma_mult must be > 0");
     hipStream_t st = (hipStream_t)stream;
     HIP_TRY(launch_calibrate(x_dev, n, ld, q->d, q->bits, mode, scope, (double)sigma_mult, q->scratch,

@@ -128,6 +128,18 @@ __device__ inline double block_sum(double v, double *sh)
     __syncthreads();
     return r;
 }
+__device__ inline double block_max(double v, double *sh)
+{
+    sh[threadIdx.x] = v;
+    __syncthreads();
+    for (int s = CAL_THREADS / 2; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) sh[threadIdx.x] = fmax(sh[threadIdx.x], sh[threadIdx.x + s]);
+        __syncthreads();
+    }
+    const double r = sh[0];
+    __syncthreads();
+    return r;
+}
 __device__ inline float block_min(float v, float *sh)
 {
     sh[threadIdx.x] = v;
@@ -183,7 +195,7 @@ __global__ __launch_bounds__(CAL_THREADS) void calib_stats_kernel(
 {
     __shared__ double shd[CAL_THREADS];
     __shared__ float shf[CAL_THREADS];
-    if (scope == LPQ_SCOPE_PER_FEATURE) {
+    if (scope != LPQ_SCOPE_GLOBAL) {
         for (int c = threadIdx.x; c < d; c += CAL_THREADS) mu_out[c] = csum[c] / (double)n;
         return;
     }
@@ -316,7 +328,7 @@ __global__ __launch_bounds__(CAL_THREADS) void calib_params_kernel(
         float k, sb, se;
         if (mode == LPQ_CALIB_GAUSS) {
             double ss = gss, cnt = (double)n * (double)d;
-            if (scope == LPQ_SCOPE_PER_FEATURE) {
+            if (scope != LPQ_SCOPE_GLOBAL) {
                 ss = css[c];
                 cnt = (double)n;
             }
@@ -335,6 +347,21 @@ __global__ __launch_bounds__(CAL_THREADS) void calib_params_kernel(
             k = (float)(((double)mn[c] + (double)mx[c]) / 2.0);
         }
         params[c] = k;
+        params[d + c] = sb;
+        params[2 * d + c] = se;
+        params[3 * d + c] = derive_m(sb, se, bits);
+    }
+    if (scope != LPQ_SCOPE_SHARED_WIDTH) return;
+    // One width for all dimensions: every range keeps its centre and takes the half-width of
+    // the widest one (binary64 arithmetic on the binary32 constants just written).
+    __syncthreads();
+    double half = 0.0;
+    for (int c = threadIdx.x; c < d; c += CAL_THREADS)
+        half = fmax(half, ((double)params[2 * d + c] - (double)params[d + c]) / 2.0);
+    half = block_max(half, shd);
+    for (int c = threadIdx.x; c < d; c += CAL_THREADS) {
+        const double centre = ((double)params[d + c] + (double)params[2 * d + c]) / 2.0;
+        const float sb = (float)(centre - half), se = (float)(centre + half);
         params[d + c] = sb;
         params[2 * d + c] = se;
         params[3 * d + c] = derive_m(sb, se, bits);

@@ -35,7 +35,8 @@ def _oracle_quant(oracle, gq):
 
 # ------------------------------------------------------------------ calibrate + encode
 @pytest.mark.parametrize("mode,scope", [("minmax", "per_feature"), ("minmax", "global"),
-                                        ("absmax", "per_feature"), ("absmax", "global")])
+                                        ("absmax", "per_feature"), ("absmax", "global"),
+                                        ("minmax", "shared_width"), ("absmax", "shared_width")])
 @pytest.mark.parametrize("wl", ["tiny", "skewed", "aniso"])
 def test_calibrate_range_modes_bit_exact(lpq, oracle, wl, mode, scope):
     w = {"tiny": synth.TINY.scaled(n=5000), "skewed": synth.SKEWED_1M.scaled(n=7001),
@@ -48,7 +49,7 @@ def test_calibrate_range_modes_bit_exact(lpq, oracle, wl, mode, scope):
     assert np.array_equal(se, oq.se) and np.array_equal(m, oq.m)
 
 
-@pytest.mark.parametrize("scope", ["per_feature", "global"])
+@pytest.mark.parametrize("scope", ["per_feature", "global", "shared_width"])
 def test_calibrate_gauss_within_tolerance_then_codes_exact(lpq, oracle, scope):
     w = synth.SCALED_10M.scaled(n=20011)
     x = w.corpus()
@@ -66,7 +67,7 @@ def test_calibrate_gauss_within_tolerance_then_codes_exact(lpq, oracle, scope):
     assert np.array_equal(norms.cpu().numpy(), onorms)
 
 
-@pytest.mark.parametrize("scope", ["per_feature", "global"])
+@pytest.mark.parametrize("scope", ["per_feature", "global", "shared_width"])
 @pytest.mark.parametrize("wl,n", [("tiny", 10000), ("skewed", 30011), ("aniso", 7000)])
 def test_calibrate_quantile_clip_bit_exact(lpq, oracle, wl, n, scope):
     """Outlier-discarding calibration: the GPU's radix selection returns exactly the oracle's order
@@ -357,6 +358,30 @@ def test_search_error_codes(lpq):
     assert int(ids.min()) == -7 and int(dists.max()) == -7            # outputs untouched on error
     e_ids, e_d = idx.search(q[:0], 10, "l2sq")                        # nq = 0: no-op
     assert e_ids.shape == (0, 10)
+
+
+def test_shared_width_scope_on_dimensions_with_offsets(lpq, oracle):
+    """Dimensions with different offsets and spreads: constants bit-exact against the oracle, search
+    bit-exact, and the scope does what it is for (recall against fp32 above both other scopes)."""
+    g = torch.Generator().manual_seed(21)
+    d, n, nq, k = 64, 60000, 200, 10
+    mu, sg = torch.rand(d, generator=g) * 2 - 1, torch.rand(d, generator=g) * 0.18 + 0.02
+    x = torch.randn(n, d, generator=g) * sg + mu
+    q = torch.randn(nq, d, generator=g) * sg + mu
+    xd, qd = x.cuda(), q.cuda()
+    eids, _ = lpq.search_f32(xd, qd, k, "l2sq")
+    rec = {}
+    for scope in ("per_feature", "global", "shared_width"):
+        gq = lpq.Quantizer(d, 6).calibrate(xd, "quantile", scope, 0.001)
+        oq = oracle.Quantizer(d, 6).calibrate(x.numpy(), "quantile", scope, 0.001)
+        ks, sb, se, m = gq.get_params()
+        assert np.array_equal(sb, oq.sb) and np.array_equal(se, oq.se)
+        assert np.array_equal(ks, oq.k) and np.array_equal(m, oq.m)
+        ids, dists = lpq.Index(gq, n).add_f32(xd).search(qd, k, "l2sq")
+        oids, odists = oracle.search_i8(oq.encode(x.numpy()), oq.encode(q.numpy()), k, "l2sq", threads=16)
+        assert np.array_equal(ids.cpu().numpy(), oids) and np.array_equal(dists.cpu().numpy(), odists)
+        rec[scope] = oracle.recall(oids, eids.cpu().numpy())
+    assert rec["shared_width"] > rec["global"] + 0.05 and rec["shared_width"] > rec["per_feature"] + 0.2, rec
 
 
 # ------------------------------------------------------------------ fp32 exact search

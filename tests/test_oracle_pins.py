@@ -410,3 +410,75 @@ def test_nibble_saturation_and_packing_by_hand(oracle):
     un = np.stack([(p & 15) - 8, (p >> 4) - 8], axis=2).reshape(7, 16)
     assert np.array_equal(un[:, :13], oracle.nibble_codes(c))
     assert np.all(un[:, 13:] == 0)
+
+
+# ---------------------------------------------------------------- shared-width scope (Section 3.2, last sentence)
+def _offset_data(rng, n, d):
+    """Dimensions with different offsets AND different spreads."""
+    mu, sg = rng.uniform(-1, 1, d), rng.uniform(0.02, 0.2, d)
+    return (rng.normal(size=(n, d)) * sg + mu).astype(np.float32)
+
+
+@pytest.mark.parametrize("mode,arg", [("minmax", 1.0), ("quantile", 0.01), ("gauss", 2.0)])
+def test_shared_width_keeps_centres_and_gives_every_dimension_the_widest_range(oracle, mode, arg):
+    x = _offset_data(np.random.default_rng(11), 2000, 24)
+    pf = oracle.Quantizer(24, 8).calibrate(x, mode, "per_feature", arg)
+    sh = oracle.Quantizer(24, 8).calibrate(x, mode, "shared_width", arg)
+    w_pf = pf.se.astype(np.float64) - pf.sb.astype(np.float64)
+    w_sh = sh.se.astype(np.float64) - sh.sb.astype(np.float64)
+    widest = int(np.argmax(w_pf))
+    assert np.array_equal(sh.k, pf.k)                                       # offsets stay per dimension
+    assert sh.sb[widest] == pf.sb[widest] and sh.se[widest] == pf.se[widest]  # the widest range is unchanged
+    np.testing.assert_allclose(w_sh, w_pf.max(), rtol=1e-6)                 # one width (up to binary32 endpoints)
+    c_pf = (pf.sb.astype(np.float64) + pf.se.astype(np.float64)) / 2
+    c_sh = (sh.sb.astype(np.float64) + sh.se.astype(np.float64)) / 2
+    np.testing.assert_allclose(c_sh, c_pf, atol=1e-6)                       # centres stay
+    np.testing.assert_allclose(sh.m, sh.m[0], rtol=1e-6)                    # hence one scale
+
+
+def test_shared_width_with_absmax_is_the_global_absmax(oracle):
+    x = _offset_data(np.random.default_rng(12), 1500, 10)
+    sh = oracle.Quantizer(10, 8).calibrate(x, "absmax", "shared_width")
+    gl = oracle.Quantizer(10, 8).calibrate(x, "absmax", "global")
+    assert np.array_equal(sh.sb, gl.sb) and np.array_equal(sh.se, gl.se)
+    assert np.array_equal(sh.k, gl.k) and np.array_equal(sh.m, gl.m)
+
+
+def test_shared_width_on_offset_integer_data_reduces_to_exact_search(oracle):
+    """Integer data, dimension i spanning [o_i, o_i + r_i] with r_i odd and the widest r = 255: the
+    common scale is fl32(256/255), centres are half-integers, and every code is the value shifted by
+    a per-dimension integer - so integer distances equal the exact ones and the int8 search IS the
+    exact search, although offsets differ by thousands.  (Per-feature scales do not have this property.)"""
+    rng = np.random.default_rng(13)
+    d, n, nq, k = 12, 600, 40, 7
+    r = np.concatenate([[255], rng.integers(0, 127, d - 1) * 2 + 1])
+    off = rng.integers(-3000, 3000, d)
+    x = off + rng.integers(0, r + 1, size=(n, d))
+    x[0], x[1] = off, off + r                                  # both ends observed in every dimension
+    q = off + rng.integers(0, r + 1, size=(nq, d))
+    xf, qf = x.astype(np.float32), q.astype(np.float32)
+    qz = oracle.Quantizer(d, 8).calibrate(xf, "minmax", "shared_width")
+    assert np.all(qz.m == np.float32(256.0 / 255.0))
+    ids, dists = oracle.search_i8(qz.encode(xf), qz.encode(qf), k, "l2sq")
+    exact = ((q[:, None, :] - x[None, :, :]) ** 2).sum(-1)     # int64, no rounding anywhere
+    for i in range(nq):
+        order = np.lexsort((np.arange(n), exact[i]))[:k]
+        assert np.array_equal(ids[i], order)
+        assert np.array_equal(dists[i], exact[i][order])
+    pf = oracle.Quantizer(d, 8).calibrate(xf, "minmax", "per_feature")
+    _, d_pf = oracle.search_i8(pf.encode(xf), pf.encode(qf), k, "l2sq")
+    assert not np.array_equal(d_pf, dists)                     # the pin can tell the scopes apart
+
+
+def test_shared_width_preserves_l2_up_to_one_step_per_dimension(oracle):
+    """With one scale m the code distance tracks the real one: | sqrt(D_int) - m |a - b| | <= sqrt(d)
+    for in-range points (each coordinate difference is off by less than one step)."""
+    rng = np.random.default_rng(14)
+    x = _offset_data(rng, 800, 16)
+    qz = oracle.Quantizer(16, 8).calibrate(x, "minmax", "shared_width")
+    c = qz.encode(x).astype(np.int64)
+    m = float(qz.m.astype(np.float64).mean())
+    a, b = rng.integers(0, 800, 300), rng.integers(0, 800, 300)
+    d_int = np.sqrt(((c[a] - c[b]) ** 2).sum(1))
+    d_real = np.sqrt(((x[a].astype(np.float64) - x[b].astype(np.float64)) ** 2).sum(1))
+    assert np.all(np.abs(d_int - m * d_real) <= np.sqrt(16) * (1 + 1e-5))
