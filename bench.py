@@ -23,17 +23,19 @@ PEAK_HBM = 8.0e12           # MI355X HBM3E, B/s
 # HBM bytes of one launch of the main scan kernel on the default workload, from the rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/search_mfma_kernel_skewed_int_1m_x128_pmc.txt
 # (FETCH_SIZE scaled by 2.000, WRITE_SIZE by 1.000 against device copies of known size in the same run).
-TRAFFIC_BYTES_DEFAULT_WORKLOAD = 243.5e6
+TRAFFIC_BYTES_DEFAULT_WORKLOAD = 244.5e6
 
 
-def cpu_baseline(oracle, x_host, q_host, params, k, metric, gpu_ids, gpu_dists, sample):
+def cpu_baseline(oracle, x_host, q_host, params, k, metric, gpu_ids, gpu_dists, sample, bits=8, packed=False):
     """The oracle as it stands, timed on the host cores on `sample` queries; also checks the
     GPU result of those queries bit for bit."""
     import numpy as np
     kq, sb, se, _ = params
-    oq = oracle.Quantizer(x_host.shape[1], 8).set_params(kq, sb, se)
+    oq = oracle.Quantizer(x_host.shape[1], bits).set_params(kq, sb, se)
     codes = oq.encode(x_host)
     qcodes = oq.encode(q_host[:sample])
+    if packed:   # two codes per byte hold -8 .. 7
+        codes, qcodes = oracle.nibble_codes(codes), oracle.nibble_codes(qcodes)
     threads = max(1, min(16, oracle.max_threads(), os.cpu_count() or 1))
     t0 = time.perf_counter()
     oids, odists = oracle.search_i8(codes, qcodes, k, metric, threads=threads)
@@ -66,6 +68,11 @@ def main():
     ap.add_argument("--seed-rows", type=int, default=0)
     ap.add_argument("--workload", default="skewed_1m", choices=["tiny", "skewed_1m", "aniso_1m2", "scaled_10m", "product_100m"],
                     help="synthetic workload shape (default: the benchmark configuration)")
+    ap.add_argument("--bits", type=int, default=8, help="bits per code B of Equation 1 (default 8)")
+    ap.add_argument("--packed", action="store_true", help="store two codes per byte (needs --bits <= 4, k <= 16)")
+    ap.add_argument("--calib", default="", help="calibration mode instead of the workload's (minmax, absmax, gauss, quantile)")
+    ap.add_argument("--scope", default="", help="calibration scope instead of the workload's (per_feature, global, shared_width)")
+    ap.add_argument("--calib-arg", type=float, default=1.0, help="sigma multiplier (gauss) or clipped fraction (quantile)")
     ap.add_argument("--extras", action="store_true",
                     help="also time the candidate-list calls (gathered distances, fp32 re-rank), report recall "
                          "before / after the re-rank for a per-feature 6-bit quantizer, and time a small batch on "
@@ -95,10 +102,11 @@ def main():
     q = w.queries("cuda")
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    quant = lpq.Quantizer(w.d, 8).calibrate(x, w.calib, w.scope)
+    calib, scope = args.calib or w.calib, args.scope or w.scope
+    quant = lpq.Quantizer(w.d, args.bits).calibrate(x, calib, scope, args.calib_arg)
     torch.cuda.synchronize()
     t_cal = time.perf_counter() - t0
-    index = lpq.Index(quant, w.n)
+    index = lpq.Index(quant, w.n, packed=args.packed)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     index.add_f32(x)
@@ -144,7 +152,8 @@ def main():
     launches_per_step = launches / args.steps
     kern_ms_per_launch = kern_ms / max(launches, 1)
     ops_per_launch = 2.0 * w.nq * w.n * w.d / launches_per_step      # true d, not the padded one
-    bytes_per_launch = float(w.n) * (w.d + 4) / launches_per_step    # corpus codes + norms, streamed once
+    code_bytes = w.d / 2.0 if args.packed else float(w.d)
+    bytes_per_launch = float(w.n) * (code_bytes + 4) / launches_per_step   # corpus codes + norms, streamed once
     mfma_frac = ops_per_launch / (kern_ms_per_launch * 1e-3) / PEAK_INT8_OPS
     hbm_frac = bytes_per_launch / (kern_ms_per_launch * 1e-3) / PEAK_HBM
     if mfma_frac >= hbm_frac:
@@ -154,7 +163,8 @@ def main():
         roofline = {"bound": "hbm", "achieved": bytes_per_launch / (kern_ms_per_launch * 1e-3) / 1e9,
                     "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": hbm_frac, "traffic": None}
     default_workload = (args.workload == "skewed_1m" and args.n == 0 and args.nq == 0 and args.k == 10 and args.path == 0
-                        and args.splits == 0 and args.seed_rows == 0)
+                        and args.splits == 0 and args.seed_rows == 0 and args.bits == 8 and not args.packed
+                        and not args.calib and not args.scope)
     roofline["traffic"] = TRAFFIC_BYTES_DEFAULT_WORKLOAD if default_workload else None
     roofline["kernel"] = "search_mfma_kernel, main scan (contraction + top-k over all corpus rows)"
     roofline["kernel_ms_per_launch"] = kern_ms_per_launch
@@ -172,7 +182,7 @@ def main():
 
     # ---- candidate-list calls (not part of the timed step) ---------------------------------
     extras = None
-    if args.extras:
+    if args.extras and not args.packed:   # (the gathered-distance call takes unpacked indexes only)
         def timed(fn, reps=10):
             fn()
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -222,7 +232,7 @@ def main():
         from oracle import lpq_oracle as oracle
         sample = min(args.cpu_sample, w.nq)
         cpu = cpu_baseline(oracle, x.cpu().numpy(), q[:sample].cpu().numpy(), quant.get_params(), k, metric,
-                           ids.cpu().numpy(), dists.cpu().numpy(), sample)
+                           ids.cpu().numpy(), dists.cpu().numpy(), sample, args.bits, args.packed)
 
     out = {
         "metric": "queries/sec, int8 brute-force top-%d, %s" % (k, "1M x 128" if args.workload == "skewed_1m" and not args.n else f"{w.n} x {w.d}"),
@@ -235,10 +245,10 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "int8",
+        "dtype": "int4 (two per byte, int8 matrix core)" if args.packed else "int8",
         "data": "synthetic",
         "config": {"workload": w.name, "n": w.n, "d": w.d, "nq": w.nq, "k": k, "metric": metric,
-                   "calibration": f"{w.calib}/{w.scope}", "seed": w.seed,
+                   "calibration": f"{calib}/{scope}", "bits": args.bits, "packed": bool(args.packed), "seed": w.seed,
                    "path": {0: "auto", 1: "generic", 2: "matrix-core"}[args.path]},
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -300,11 +300,11 @@ extern "C" int lpq_index_create_packed(lpq_index **out, const lpq_quantizer *q, 
     return index_create_impl(out, q, capacity, true);
 }
 
-// Packed index: rows [size, size + n) from int8 codes (device), through the nibble packer.
-static int index_pack_rows(lpq_index *idx, const int8_t *codes, int64_t n, int64_t ld, hipStream_t st)
+// Packed index: rows [row0, row0 + n) from int8 codes (device), through the nibble packer.
+static int index_pack_rows(lpq_index *idx, int64_t row0, const int8_t *codes, int64_t n, int64_t ld, hipStream_t st)
 {
-    HIP_TRY(launch_pack4(codes, n, ld, idx->d, reinterpret_cast<uint8_t *>(idx->codes) + (size_t)idx->size * (idx->d_pad / 2),
-                         idx->d_pad, idx->norms + idx->size, st));
+    HIP_TRY(launch_pack4(codes, n, ld, idx->d, reinterpret_cast<uint8_t *>(idx->codes) + (size_t)row0 * (idx->d_pad / 2),
+                         idx->d_pad, idx->norms + row0, st));
     return LPQ_OK;
 }
 
@@ -330,12 +330,10 @@ extern "C" int lpq_index_add_f32(lpq_index *idx, const float *x_dev, int64_t n, 
             const int64_t m = n - r < PACK_STAGE_ROWS ? n - r : PACK_STAGE_ROWS;
             HIP_TRY(launch_encode(view(idx->params, idx->d, idx->bits), x_dev + r * ld, m, ld, idx->stage, idx->d_pad,
                                   idx->d_pad, nullptr, st));
-            int rc = index_pack_rows(idx, idx->stage, m, idx->d_pad, st);
-            if (rc) return rc;
-            rc = index_after_add(idx, m, st);
+            const int rc = index_pack_rows(idx, idx->size + r, idx->stage, m, idx->d_pad, st);
             if (rc) return rc;
         }
-        return LPQ_OK;
+        return index_after_add(idx, n, st);
     }
     HIP_TRY(launch_encode(view(idx->params, idx->d, idx->bits), x_dev, n, ld,
                           idx->codes + (size_t)idx->size * idx->d_pad, idx->d_pad, idx->d_pad,
@@ -352,7 +350,7 @@ extern "C" int lpq_index_add_i8(lpq_index *idx, const int8_t *codes_dev, int64_t
     if (n == 0) return LPQ_OK;
     hipStream_t st = (hipStream_t)stream;
     if (idx->packed) {
-        const int rc = index_pack_rows(idx, codes_dev, n, ld, st);
+        const int rc = index_pack_rows(idx, idx->size, codes_dev, n, ld, st);
         return rc ? rc : index_after_add(idx, n, st);
     }
     HIP_TRY(launch_repack_i8(codes_dev, n, ld, idx->d, idx->codes + (size_t)idx->size * idx->d_pad, idx->d_pad,
