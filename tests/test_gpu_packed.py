@@ -91,6 +91,28 @@ def test_packed_search_bit_exact(lpq, oracle, name, n, nq, k, metric, bits, mode
     assert torch.equal(ids2, ids) and torch.equal(dists2, dists)
 
 
+@pytest.mark.parametrize("d,metric,bits", [(33, "l2sq", 4), (64, "ip", 4), (65, "l2sq", 3), (129, "ip", 4),
+                                           (200, "l2sq", 4), (256, "l2sq", 4), (1, "l2sq", 4)])
+def test_packed_search_every_row_length(lpq, oracle, d, metric, bits):
+    """Feature counts on both sides of every padded row length (64, 96, 128, 192, 256 features)."""
+    g = torch.Generator().manual_seed(d)
+    n, nq, k = 30011, 70, 10
+    x = torch.randn(n, d, generator=g)
+    q = torch.randn(nq, d, generator=g)
+    gq = lpq.Quantizer(d, bits).calibrate(x.cuda(), "absmax", "global")
+    idx = lpq.Index(gq, n, packed=True).add_f32(x.cuda())
+    oq = _oracle_quant(oracle, gq)
+    ocodes = oracle.nibble_codes(oq.encode(x.numpy()))
+    oqcodes = oracle.nibble_codes(oq.encode(q.numpy()))
+    rows, norms = idx.storage()
+    assert np.array_equal(rows, oracle.pack_nibbles(ocodes, _padded_features(d)))
+    ids, dists = idx.search(q.cuda(), k, metric)
+    torch.cuda.synchronize()
+    oids, odists = oracle.search_i8(ocodes, oqcodes, k, metric, threads=16)
+    assert np.array_equal(dists.cpu().numpy(), odists)
+    assert np.array_equal(ids.cpu().numpy(), oids)
+
+
 def test_packed_equals_unpacked_index_of_saturated_codes_and_incremental_add(lpq, oracle):
     w = synth.SKEWED_1M.scaled(n=100_000, nq=48)
     x, q = w.corpus().cuda(), w.queries().cuda()
