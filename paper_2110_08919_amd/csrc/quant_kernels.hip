@@ -376,16 +376,32 @@ __global__ void derive_m_kernel(float *params, int d, int bits)
 
 // ------------------------------------------------------------------------- encode --
 // Equation 1 for one value, in binary32 with separately rounded subtract and multiply.
-__device__ inline int quantize_one(float x, float k, float sb, float se, float m, int half)
+// lo = -2^(B-1) and top = min(2^(B-1), 127) as floats; an empty range (S_e <= S_b) arrives here
+// as sb = -inf, se = +inf, m = 0 (see column_constants), which yields 0 for every x.
+__device__ inline int quantize_one(float x, float k, float sb, float se, float m, float lo, float top)
 {
     const float t = __fmul_rn(__fsub_rn(x, k), m);
-    const float f = floorf(t);
-    int r = (f >= (float)half) ? half : (f <= (float)(-half)) ? -half : (f == f) ? (int)f : 0;
-    r = (x > se) ? half : r;
-    r = (x < sb) ? -half : r;
-    r = (x != x) ? 0 : r;
-    r = (se > sb) ? r : 0;
-    return r < 127 ? r : 127;
+    // floor, clamp to the code range (the stored top code included), convert: the clamp keeps the
+    // conversion in range; a NaN (from x, or from inf * 0) is replaced below
+    float f = __builtin_amdgcn_fmed3f(floorf(t), lo, top);
+    f = (x > se) ? top : f;
+    f = (x < sb) ? lo : f;
+    f = (t != t) ? 0.0f : f;
+    return (int)f;
+}
+
+// Constants of column c as the encoder uses them.
+__device__ inline void column_constants(const QuantParams &qp, int c, bool in, float &k, float &sb, float &se, float &m)
+{
+    k = in ? qp.k[c] : 0.f;
+    sb = in ? qp.sb[c] : 0.f;
+    se = in ? qp.se[c] : 0.f;
+    m = in ? qp.m[c] : 0.f;
+    if (!(se > sb)) {   // empty range: code 0 everywhere
+        sb = -INFINITY;
+        se = INFINITY;
+        m = 0.f;
+    }
 }
 
 constexpr int ENC_THREADS = 256;
@@ -404,6 +420,7 @@ __global__ __launch_bounds__(ENC_THREADS) void encode_kernel(
     const int lane = threadIdx.x & 63;
     const int sub = lane % TPR, rsel = lane / TPR;
     const int d = qp.d, half = 1 << (qp.bits - 1);
+    const float lo = (float)(-half), top = (float)(half < 127 ? half : 127);
     const int ngroups = (d + 3) >> 2;              // 4-column groups holding data
     const int pgroups = (zero_pad_to > d) ? ((zero_pad_to + 3) >> 2) : ngroups;
     const int64_t wave_id = ((int64_t)blockIdx.x * ENC_THREADS + threadIdx.x) >> 6;
@@ -413,10 +430,7 @@ __global__ __launch_bounds__(ENC_THREADS) void encode_kernel(
     float ck[4] = {0, 0, 0, 0}, cb[4] = {0, 0, 0, 0}, ce[4] = {0, 0, 0, 0}, cm[4] = {0, 0, 0, 0};
     if (single) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int c = 4 * sub + j;
-            if (c < d) { ck[j] = qp.k[c]; cb[j] = qp.sb[c]; ce[j] = qp.se[c]; cm[j] = qp.m[c]; }
-        }
+        for (int j = 0; j < 4; ++j) column_constants(qp, 4 * sub + j, 4 * sub + j < d, ck[j], cb[j], ce[j], cm[j]);
     }
     for (int64_t base = wave_id * RPW * ENC_UNROLL; base < n_out; base += nwaves * RPW * ENC_UNROLL) {
         int acc[ENC_UNROLL];
@@ -427,12 +441,7 @@ __global__ __launch_bounds__(ENC_THREADS) void encode_kernel(
             const int c0 = 4 * g;
             if (!single) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int c = c0 + j;
-                    const bool in = c < d;
-                    ck[j] = in ? qp.k[c] : 0.f; cb[j] = in ? qp.sb[c] : 0.f;
-                    ce[j] = in ? qp.se[c] : 0.f; cm[j] = in ? qp.m[c] : 0.f;
-                }
+                for (int j = 0; j < 4; ++j) column_constants(qp, c0 + j, c0 + j < d, ck[j], cb[j], ce[j], cm[j]);
             }
             float v[ENC_UNROLL][4];
 #pragma unroll
@@ -454,7 +463,7 @@ __global__ __launch_bounds__(ENC_THREADS) void encode_kernel(
                     int q[4];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        q[j] = (c0 + j < d && r < n) ? quantize_one(v[u][j], ck[j], cb[j], ce[j], cm[j], half) : 0;
+                        q[j] = (c0 + j < d && r < n) ? quantize_one(v[u][j], ck[j], cb[j], ce[j], cm[j], lo, top) : 0;
                         acc[u] += q[j] * q[j];
                     }
                     const int lim = (zero_pad_to > d) ? zero_pad_to : d;
