@@ -9,6 +9,7 @@ namespace {
 
 constexpr int CAL_THREADS = 256;
 constexpr int CAL_WAVES = CAL_THREADS / 64;
+constexpr int CAL_EXTRA_ROWS = 16;   // partial rows beyond the per-block ones: the first level of the column reduction
 
 int calib_blocks(int d)
 {
@@ -20,8 +21,8 @@ int calib_blocks(int d)
 
 // Scratch: per-block partial results and the reduced per-column statistics.
 struct CalibScratch {
-    float *pmn, *pmx;   // [G][d]
-    double *psum;       // [G][d]  (pass 1: sum x; pass 2: sum (x - mu)^2)
+    float *pmn, *pmx;   // [G + CAL_EXTRA_ROWS][d]
+    double *psum;       // [G + CAL_EXTRA_ROWS][d]  (pass 1: sum x; pass 2: sum (x - mu)^2)
     double *csum, *css; // [d] column totals of the two passes
     double *mu;         // [d]
     float *mn, *mx;     // [d]
@@ -36,12 +37,12 @@ CalibScratch carve(void *scratch, int d)
     const int64_t G = calib_blocks(d);
     char *p = (char *)scratch;
     CalibScratch s;
-    s.psum = (double *)p; p += sizeof(double) * G * d;
+    s.psum = (double *)p; p += sizeof(double) * (G + CAL_EXTRA_ROWS) * d;
     s.csum = (double *)p; p += sizeof(double) * d;
     s.css = (double *)p;  p += sizeof(double) * d;
     s.mu = (double *)p;   p += sizeof(double) * d;
-    s.pmn = (float *)p;   p += sizeof(float) * G * d;
-    s.pmx = (float *)p;   p += sizeof(float) * G * d;
+    s.pmn = (float *)p;   p += sizeof(float) * (G + CAL_EXTRA_ROWS) * d;
+    s.pmx = (float *)p;   p += sizeof(float) * (G + CAL_EXTRA_ROWS) * d;
     s.mn = (float *)p;    p += sizeof(float) * d;
     s.mx = (float *)p;    p += sizeof(float) * d;
     p = (char *)(((uintptr_t)p + 15) & ~uintptr_t(15));
@@ -116,6 +117,91 @@ __global__ __launch_bounds__(CAL_THREADS) void calib_reduce_kernel(
     }
 }
 
+// The same reduction with 16-byte loads, for rows that allow them (d and the row stride multiples
+// of 4 floats, 16-byte aligned base): LPR lanes share a row, each owning 4 consecutive columns, so a
+// wave reads 64 / LPR rows per load and four such loads are in flight per lane (64 bytes).
+template <int PASS>
+__global__ __launch_bounds__(CAL_THREADS) void calib_reduce_vec_kernel(
+    const float *__restrict__ x, int64_t n, int64_t ld, int d, int lpr, int64_t rows_per_block,
+    const double *__restrict__ mu, float *__restrict__ pmn, float *__restrict__ pmx,
+    double *__restrict__ psum, int *__restrict__ nonfinite)
+{
+    __shared__ float s_mn[CAL_WAVES][64][4], s_mx[CAL_WAVES][64][4];
+    __shared__ double s_sum[CAL_WAVES][64][4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int cg = lane % lpr, rsel = lane / lpr, rpw = 64 / lpr;   // column group, row slot, rows per wave and load
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t r1 = (r0 + rows_per_block < n) ? r0 + rows_per_block : n;
+    const int64_t rstep = (int64_t)CAL_WAVES * rpw;
+    for (int c0 = 0; c0 < d; c0 += 4 * lpr) {
+        const int c = c0 + 4 * cg;
+        const bool live = c < d;   // d is a multiple of 4: a live lane owns 4 real columns
+        float mn[4], mx[4];
+        double sum[4], m[4];
+        bool bad = false;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            mn[e] = INFINITY; mx[e] = -INFINITY; sum[e] = 0.0;
+            m[e] = (PASS == 2 && live) ? mu[c + e] : 0.0;
+        }
+        for (int64_t r = r0 + (int64_t)wave * rpw + rsel; r < r1; r += 4 * rstep) {
+            float4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t rr = r + u * rstep;
+                v[u] = (live && rr < r1) ? *reinterpret_cast<const float4 *>(x + rr * ld + c) : float4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t rr = r + u * rstep;
+                if (live && rr < r1) {
+                    const float a[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (PASS == 1) {
+                            if (!isfinite(a[e])) {
+                                bad = true;
+                            } else {
+                                mn[e] = fminf(mn[e], a[e]);
+                                mx[e] = fmaxf(mx[e], a[e]);
+                                sum[e] += (double)a[e];
+                            }
+                        } else {
+                            const double t = (double)a[e] - m[e];
+                            sum[e] += t * t;
+                        }
+                    }
+                }
+            }
+        }
+        if (PASS == 1 && bad) atomicOr(nonfinite, 1);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            s_mn[wave][lane][e] = mn[e];
+            s_mx[wave][lane][e] = mx[e];
+            s_sum[wave][lane][e] = sum[e];
+        }
+        __syncthreads();
+        if (wave == 0 && rsel == 0 && live) {   // fixed order: waves, then row slots
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float a = INFINITY, b = -INFINITY;
+                double t = 0.0;
+                for (int w = 0; w < CAL_WAVES; ++w)
+                    for (int rs = 0; rs < rpw; ++rs) {
+                        a = fminf(a, s_mn[w][rs * lpr + cg][e]);
+                        b = fmaxf(b, s_mx[w][rs * lpr + cg][e]);
+                        t += s_sum[w][rs * lpr + cg][e];
+                    }
+                const int64_t o = (int64_t)blockIdx.x * d + c + e;
+                if (PASS == 1) { pmn[o] = a; pmx[o] = b; }
+                psum[o] = t;
+            }
+        }
+        __syncthreads();
+    }
+}
+
 __device__ inline double block_sum(double v, double *sh)
 {
     sh[threadIdx.x] = v;
@@ -153,21 +239,28 @@ __device__ inline float block_min(float v, float *sh)
     return r;
 }
 
-// Column totals of the G block partials: one workgroup per 64 columns, its 16 waves share the
-// G partial rows and combine through LDS.  pmn / pmx may be null (second pass: sums only).
+// Column totals of partial rows [g_begin, g_begin + count): workgroup (x, y) takes 64 columns and
+// the y-th of gridDim.y equal slices of the rows; its 16 waves share the slice and combine through
+// LDS; the result goes to row y of the outputs.  Two levels (COL_PARTS slices, then their COL_PARTS
+// results) keep the summation order fixed while spreading the G x d partials over 16 times as many
+// workgroups.  pmn / pmx may be null (second pass: sums only).
 constexpr int COL_WAVES = 16;
+constexpr int COL_PARTS = 16;
 __global__ __launch_bounds__(COL_WAVES * 64) void calib_colreduce_kernel(
-    int G, int d, const float *__restrict__ pmn, const float *__restrict__ pmx, const double *__restrict__ psum,
-    float *__restrict__ mn_out, float *__restrict__ mx_out, double *__restrict__ sum_out)
+    int g_begin, int count, int d, const float *__restrict__ pmn, const float *__restrict__ pmx,
+    const double *__restrict__ psum, float *__restrict__ mn_out, float *__restrict__ mx_out, double *__restrict__ sum_out)
 {
     __shared__ float s_mn[COL_WAVES][64], s_mx[COL_WAVES][64];
     __shared__ double s_sum[COL_WAVES][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = blockIdx.x * 64 + lane;
+    const int per = (count + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int g0 = g_begin + (int)blockIdx.y * per;
+    const int g1 = (g0 + per < g_begin + count) ? g0 + per : g_begin + count;
     float mn = INFINITY, mx = -INFINITY;
     double sum = 0.0;
     if (c < d) {
-        for (int g = wave; g < G; g += COL_WAVES) {
+        for (int g = g0 + wave; g < g1; g += COL_WAVES) {
             const int64_t o = (int64_t)g * d + c;
             if (pmn) { mn = fminf(mn, pmn[o]); mx = fmaxf(mx, pmx[o]); }
             sum += psum[o];
@@ -183,8 +276,9 @@ __global__ __launch_bounds__(COL_WAVES * 64) void calib_colreduce_kernel(
             mx = fmaxf(mx, s_mx[w][lane]);
             sum += s_sum[w][lane];
         }
-        if (mn_out) { mn_out[c] = mn; mx_out[c] = mx; }
-        sum_out[c] = sum;
+        const int64_t o = (int64_t)blockIdx.y * d + c;
+        if (mn_out) { mn_out[o] = mn; mx_out[o] = mx; }
+        sum_out[o] = sum;
     }
 }
 
@@ -595,7 +689,7 @@ __global__ __launch_bounds__(256) void item_aux_kernel(
 
 size_t calib_scratch_bytes(int d)
 {
-    const size_t G = calib_blocks(d);
+    const size_t G = calib_blocks(d) + CAL_EXTRA_ROWS;
     return G * d * (sizeof(double) + 2 * sizeof(float)) + (size_t)d * (3 * sizeof(double) + 2 * sizeof(float)) + 256 +
            (size_t)d * (512 * sizeof(unsigned long long) + 2 * sizeof(unsigned long long) + 2 * sizeof(uint32_t));
 }
@@ -609,10 +703,23 @@ hipError_t launch_calibrate(const float *x, int64_t n, int64_t ld, int d, int bi
     const int64_t rpb = ceil_div(n, G);
     hipError_t e = hipMemsetAsync(nonfinite_flag, 0, sizeof(int), st);
     if (e != hipSuccess) return e;
-    calib_reduce_kernel<1><<<G, CAL_THREADS, 0, st>>>(x, n, ld, d, rpb, nullptr, s.pmn, s.pmx, s.psum,
-                                                      nonfinite_flag);
+    // 16-byte loads when the rows allow them; lanes per row: the power of two that covers d / 4
+    const bool vec = d % 4 == 0 && ld % 4 == 0 && (uintptr_t)x % 16 == 0;
+    int lpr = 1;
+    while (lpr < d / 4 && lpr < 64) lpr <<= 1;
+    if (vec)
+        calib_reduce_vec_kernel<1><<<G, CAL_THREADS, 0, st>>>(x, n, ld, d, lpr, rpb, nullptr, s.pmn, s.pmx, s.psum,
+                                                              nonfinite_flag);
+    else
+        calib_reduce_kernel<1><<<G, CAL_THREADS, 0, st>>>(x, n, ld, d, rpb, nullptr, s.pmn, s.pmx, s.psum,
+                                                          nonfinite_flag);
     const int cblocks = (d + 63) / 64;
-    calib_colreduce_kernel<<<cblocks, COL_WAVES * 64, 0, st>>>(G, d, s.pmn, s.pmx, s.psum, s.mn, s.mx, s.csum);
+    static_assert(COL_PARTS <= CAL_EXTRA_ROWS, "the first level writes COL_PARTS partial rows behind the G block rows");
+    const size_t lvl = (size_t)G * d;   // first-level results live in rows G .. G + COL_PARTS - 1
+    calib_colreduce_kernel<<<dim3(cblocks, COL_PARTS), COL_WAVES * 64, 0, st>>>(0, G, d, s.pmn, s.pmx, s.psum, s.pmn + lvl,
+                                                                               s.pmx + lvl, s.psum + lvl);
+    calib_colreduce_kernel<<<dim3(cblocks, 1), COL_WAVES * 64, 0, st>>>(G, COL_PARTS, d, s.pmn, s.pmx, s.psum, s.mn, s.mx,
+                                                                       s.csum);
     calib_stats_kernel<<<1, CAL_THREADS, 0, st>>>(d, n, scope, s.mn, s.mx, s.csum, s.mu);
     if (mode == LPQ_CALIB_QUANTILE) {
         // the min/max pass above has checked the data; now the two order statistics per column
@@ -633,10 +740,16 @@ hipError_t launch_calibrate(const float *x, int64_t n, int64_t ld, int d, int bi
         quantile_finish_kernel<<<(d + 255) / 256, 256, 0, st>>>(d, pooled, cols, s.qprefix, s.mn, s.mx);
     }
     if (mode == LPQ_CALIB_GAUSS) {
-        calib_reduce_kernel<2><<<G, CAL_THREADS, 0, st>>>(x, n, ld, d, rpb, s.mu, nullptr, nullptr, s.psum,
-                                                          nonfinite_flag);
-        calib_colreduce_kernel<<<cblocks, COL_WAVES * 64, 0, st>>>(G, d, nullptr, nullptr, s.psum, nullptr, nullptr,
-                                                                  s.css);
+        if (vec)
+            calib_reduce_vec_kernel<2><<<G, CAL_THREADS, 0, st>>>(x, n, ld, d, lpr, rpb, s.mu, nullptr, nullptr, s.psum,
+                                                                  nonfinite_flag);
+        else
+            calib_reduce_kernel<2><<<G, CAL_THREADS, 0, st>>>(x, n, ld, d, rpb, s.mu, nullptr, nullptr, s.psum,
+                                                              nonfinite_flag);
+        calib_colreduce_kernel<<<dim3(cblocks, COL_PARTS), COL_WAVES * 64, 0, st>>>(0, G, d, nullptr, nullptr, s.psum, nullptr,
+                                                                                   nullptr, s.psum + lvl);
+        calib_colreduce_kernel<<<dim3(cblocks, 1), COL_WAVES * 64, 0, st>>>(G, COL_PARTS, d, nullptr, nullptr, s.psum, nullptr,
+                                                                           nullptr, s.css);
     }
     calib_params_kernel<<<1, CAL_THREADS, 0, st>>>(d, n, bits, mode, scope, sigma_mult, s.mn, s.mx, s.mu, s.css,
                                                    params_out);
