@@ -234,9 +234,10 @@ int lpq_profile_read(int64_t *launches, double *total_ms);
 int lpq_profile_read_kind(int kind, int64_t *launches, double *total_ms);
 
 /* Diagnostics of the collecting variant: after a search with the same (idx, nq, k, metric) and
- * workspace has finished, the number of queries whose candidates did not fit and that were redone
- * by the generic kernel (0 when the search did not use the collecting variant) and the largest
- * number of candidates any region received.  Synchronises the device. */
+ * workspace has finished, the number of queries whose candidates did not fit and that were
+ * searched again exactly (up to 64 by the generic kernel, more by a pass of the register-list
+ * matrix-core kernel when k <= 16; 0 when the search did not use the collecting variant) and the
+ * largest number of candidates any region received.  Synchronises the device. */
 int lpq_search_overflow_stats(const lpq_index *idx, int64_t nq, int k, int metric, const void *workspace_dev,
                               int64_t *redone_queries, int64_t *max_region_fill);
 

@@ -419,10 +419,11 @@ struct Plan {
     int seed_stages = 0;       // ... seed_stages of them per split
     int SS = 0, Cs = 0;     // PLAN_MFMA_COLLECT: regions per query, capacity of a region
     int Sg = 0;             // PLAN_MFMA_COLLECT: splits of the generic kernel for overflowed queries
+    int Sr = 0;             // PLAN_MFMA_COLLECT: splits of the register-list kernel for many overflowed queries (0 = none)
     int wave_queries = 64;  // PLAN_MFMA_COLLECT: queries per wave of the scan
     int expect = 0;         // PLAN_MFMA_COLLECT: expected candidates per query
     size_t off_qcodes = 0, off_qnorms = 0, off_lists1 = 0, off_seedlist = 0, off_seeds = 0, off_lists2 = 0,
-           off_gmax = 0, off_merge_tmp = 0, off_cbuf = 0, off_ccnt = 0, off_over = 0, off_qlist = 0, total = 0;
+           off_gmax = 0, off_merge_tmp = 0, off_cbuf = 0, off_ccnt = 0, off_over = 0, off_qlist = 0, off_redo = 0, total = 0;
 };
 
 size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
@@ -566,6 +567,15 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
         p.off_ccnt = o; o = align256(o + (size_t)nq * p.SS * sizeof(int32_t));
         p.off_over = o; o = align256(o + (size_t)nq * sizeof(int32_t));
         p.off_qlist = o; o = align256(o + ((size_t)nq + 1) * sizeof(int32_t));   // redo list, then its counter
+        // redo of many queries by the register-list kernel (k <= 16, 256 queries per workgroup): one
+        // list per query and split, few enough splits for a single merge pass
+        if (!p.rsplit && regs) {
+            int64_t sr = slots / ceil_div(nq, 256);
+            if (sr > merge_max_lists(k)) sr = merge_max_lists(k);
+            if (sr > n / 512) sr = n / 512;
+            p.Sr = (int)(sr < 1 ? 1 : sr);
+            p.off_redo = o; o = align256(o + (size_t)nq * p.Sr * k * sizeof(cand_t));
+        }
     }
     p.total = o;
     return p;
@@ -655,9 +665,23 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, const int8_t *qco
         int32_t *qlist = reinterpret_cast<int32_t *>(ws + p.off_qlist), *qcount = qlist + nq;
         HIP_TRY(launch_collect_select(cbuf, ccnt, nq, p.SS, p.Cs, k, over, qlist, qcount, ids, dist, qnorms, emit_mode, st,
                                       p.expect));
-        // queries whose candidates did not fit are searched again by the generic kernel
-        HIP_TRY(launch_search_generic_list(a, 0, a.n, p.Sg, qlist, qcount, lists2, st));
-        HIP_TRY(launch_merge(lists2, nq, p.Sg, k, nullptr, nullptr, nullptr, ids, dist, qnorms, emit_mode, st, false, over));
+        // Queries whose candidates did not fit are searched again, exactly: a few by the generic kernel;
+        // many (a corpus full of duplicates or ties) by a pass of the register-list kernel over the
+        // query tiles that hold one.  Both are launched; the count on the device decides which works.
+        const int few = p.Sr ? REDO_GENERIC_MAX : INT32_MAX;
+        HIP_TRY(launch_search_generic_list(a, 0, a.n, p.Sg, qlist, qcount, lists2, st, few));
+        HIP_TRY(launch_merge(lists2, nq, p.Sg, k, nullptr, nullptr, nullptr, ids, dist, qnorms, emit_mode, st, false, over,
+                             p.Sr ? qcount : nullptr, 0, few));
+        if (p.Sr) {
+            cand_t *lists_r = reinterpret_cast<cand_t *>(ws + p.off_redo);
+            SearchArgs ar = a;
+            ar.rsplit = false;
+            ar.wave_queries = 64;
+            ar.redo_flags = over; ar.redo_count = qcount; ar.redo_min = REDO_GENERIC_MAX;
+            HIP_TRY(launch_search_mfma(ar, 0, a.n, p.Sr, seeds, lists_r, st));
+            HIP_TRY(launch_merge(lists_r, nq, p.Sr, k, nullptr, nullptr, nullptr, ids, dist, qnorms, emit_mode, st, false,
+                                 over, qcount, REDO_GENERIC_MAX + 1, INT32_MAX));
+        }
     } else if (p.mode == PLAN_MFMA_REG) {
         const cand_t *sd = nullptr;
         if (p.seed_rows) {

@@ -114,7 +114,17 @@ struct SearchArgs {
     int work_order = 0;     // matrix-core kernels: block -> (split, query tile) mapping (0 = built-in)
     int wave_queries = 64;  // collecting mode: queries per wave (64 or 128)
     bool packed = false;    // codes holds two 4-bit codes (stored + 8) per byte, rows of d_pad / 2 bytes; qcodes permuted to match
+    // Redo pass of the register-list kernel (device memory written by an earlier kernel): a workgroup
+    // works only if more than redo_min queries are flagged in all and one of its own queries is.
+    const int32_t *redo_flags = nullptr;   // [nq] non-zero = search this query again
+    const int32_t *redo_count = nullptr;   // number of flagged queries
+    int redo_min = 0;
 };
+
+// Queries of the collecting scan that must be searched again: up to this many go through the
+// generic kernel (a fixed grid shares them out), more through a pass of the register-list kernel
+// whose workgroups skip query tiles without a flagged query.
+constexpr int REDO_GENERIC_MAX = 64;
 
 // Generic kernel: one workgroup per (query, corpus split); any d_pad (multiple of 32), any k.
 // Writes lists[(q * S + s) * k + r], sorted ascending, CAND_NONE-filled.
@@ -122,8 +132,9 @@ hipError_t launch_search_generic(const SearchArgs &a, int64_t row0, int64_t row1
                                  const cand_t *seeds, cand_t *lists, hipStream_t st);
 // The same for the *qcount queries listed in qlist (device memory, written by an earlier kernel):
 // a fixed grid shares out the (query, split) pairs; lists of other queries are left untouched.
+// Does nothing if more than max_listed queries are listed.
 hipError_t launch_search_generic_list(const SearchArgs &a, int64_t row0, int64_t row1, int S, const int32_t *qlist,
-                                      const int32_t *qcount, cand_t *lists, hipStream_t st);
+                                      const int32_t *qcount, cand_t *lists, hipStream_t st, int max_listed = INT32_MAX);
 
 // Matrix-core kernels.  search_mfma.hip keeps the k best of a query in registers (k <= 16) and
 // has a seeding pass; search_mfma_lds.hip keeps them in LDS (larger k).  launch_search_mfma
@@ -173,7 +184,9 @@ hipError_t launch_seed_finalize(const int32_t *gmax, int64_t nq, int G, int k, c
 hipError_t launch_merge(const cand_t *lists, int64_t nq, int P, int k, const cand_t *extra_lists,
                         cand_t *out_lists, cand_t *seeds_out, int32_t *ids, int32_t *dists,
                         const int32_t *qnorms, int metric, hipStream_t st, bool sorted_lists = false,
-                        const int32_t *only = nullptr);   // only (optional): int[nq]; queries with only[q] == 0 are skipped
+                        const int32_t *only = nullptr,   // only (optional): int[nq]; queries with only[q] == 0 are skipped
+                        const int32_t *gate_count = nullptr, int gate_lo = 0,   // gate (optional): nothing is done
+                        int gate_hi = INT32_MAX);                               // unless gate_lo <= *gate_count <= gate_hi
 int merge_max_lists(int k);
 int merge_max_sorted_lists(int k);   // same for lists that are each sorted (k <= 32: more of them)
 // First pass of a two-pass merge: groups of `group` consecutive lists of each query are merged

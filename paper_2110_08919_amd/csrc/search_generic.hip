@@ -82,13 +82,14 @@ __global__ __launch_bounds__(GEN_THREADS) void search_generic_kernel(
 // queries is spread over the whole chip and an empty list costs one tiny launch.
 __global__ __launch_bounds__(GEN_THREADS) void search_generic_list_kernel(
     SearchArgs a, int64_t row0, int64_t row1, int S, int64_t split_rows, const int32_t *__restrict__ qlist,
-    const int32_t *__restrict__ qcount, cand_t *__restrict__ lists, int cap)
+    const int32_t *__restrict__ qcount, cand_t *__restrict__ lists, int cap, int max_listed)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     cand_t *buf = reinterpret_cast<cand_t *>(smem);
     uint4 *qs = reinterpret_cast<uint4 *>(buf + cap);
     __shared__ int s_count;
     __shared__ cand_t s_thr;
+    if (*qcount > max_listed) return;                       // too many for this path: another kernel takes them
     const int64_t items = (int64_t)(*qcount) * S;           // same for every thread of the grid
     for (int64_t item = blockIdx.x; item < items; item += gridDim.x) {
         const int64_t q = qlist[item / S];
@@ -131,12 +132,17 @@ __device__ __forceinline__ void emit_result(cand_t c, int64_t at, int64_t q, int
 __global__ __launch_bounds__(256) void merge_kernel(
     const cand_t *__restrict__ lists, int P, int k, const cand_t *__restrict__ extra, int cap,
     cand_t *__restrict__ out_lists, cand_t *__restrict__ seeds_out, int32_t *__restrict__ ids,
-    int32_t *__restrict__ dists, const int32_t *__restrict__ qnorms, int metric, const int32_t *__restrict__ only)
+    int32_t *__restrict__ dists, const int32_t *__restrict__ qnorms, int metric, const int32_t *__restrict__ only,
+    const int32_t *__restrict__ gate_count, int gate_lo, int gate_hi)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     cand_t *buf = reinterpret_cast<cand_t *>(smem);
     const int64_t q = blockIdx.x;
     if (only && !only[q]) return;   // same for the whole workgroup
+    if (gate_count) {               // this merge belongs to one of two alternative redo paths
+        const int c = *gate_count;
+        if (c < gate_lo || c > gate_hi) return;
+    }
     const int m = P * k;
     for (int i = threadIdx.x; i < cap; i += 256) {
         cand_t c = CAND_NONE;
@@ -419,23 +425,25 @@ hipError_t launch_search_generic(const SearchArgs &a, int64_t row0, int64_t row1
 }
 
 hipError_t launch_search_generic_list(const SearchArgs &a, int64_t row0, int64_t row1, int S, const int32_t *qlist,
-                                      const int32_t *qcount, cand_t *lists, hipStream_t st)
+                                      const int32_t *qcount, cand_t *lists, hipStream_t st, int max_listed)
 {
     if (a.nq <= 0 || row1 <= row0) return hipSuccess;
     const int cap = next_pow2((2 * a.k > a.k + 2 * GEN_ROWS) ? 2 * a.k : a.k + 2 * GEN_ROWS);
     const int64_t split_rows = round_up(ceil_div(row1 - row0, S), GEN_ROWS);
     const size_t shmem = (size_t)cap * sizeof(cand_t) + (size_t)a.d_pad;
-    search_generic_list_kernel<<<2048, GEN_THREADS, shmem, st>>>(a, row0, row1, S, split_rows, qlist, qcount, lists, cap);
+    search_generic_list_kernel<<<2048, GEN_THREADS, shmem, st>>>(a, row0, row1, S, split_rows, qlist, qcount, lists, cap,
+                                                                 max_listed);
     return hipGetLastError();
 }
 
 hipError_t launch_merge(const cand_t *lists, int64_t nq, int P, int k, const cand_t *extra_lists,
                         cand_t *out_lists, cand_t *seeds_out, int32_t *ids, int32_t *dists,
-                        const int32_t *qnorms, int metric, hipStream_t st, bool sorted_lists, const int32_t *only)
+                        const int32_t *qnorms, int metric, hipStream_t st, bool sorted_lists, const int32_t *only,
+                        const int32_t *gate_count, int gate_lo, int gate_hi)
 {
     if (nq <= 0) return hipSuccess;
     const int total = P * k + (extra_lists ? k : 0);
-    if (!only && sorted_lists && k <= 32 && total >= 1024 && P <= merge_max_sorted_lists(k)) {   // many short sorted lists
+    if (!only && !gate_count && sorted_lists && k <= 32 && total >= 1024 && P <= merge_max_sorted_lists(k)) {   // many short sorted lists
         const int Pt = P + (extra_lists ? 1 : 0);
         const size_t lds = merge_sorted_lds(Pt, k);
         static bool attr_set = false;
@@ -452,7 +460,7 @@ hipError_t launch_merge(const cand_t *lists, int64_t nq, int P, int k, const can
     const int cap = next_pow2(total < 2 ? 2 : total);
     if (cap > 4096) return hipErrorInvalidValue;
     merge_kernel<<<(unsigned)nq, 256, (size_t)cap * sizeof(cand_t), st>>>(
-        lists, P, k, extra_lists, cap, out_lists, seeds_out, ids, dists, qnorms, metric, only);
+        lists, P, k, extra_lists, cap, out_lists, seeds_out, ids, dists, qnorms, metric, only, gate_count, gate_lo, gate_hi);
     return hipGetLastError();
 }
 

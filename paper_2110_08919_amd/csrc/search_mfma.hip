@@ -291,6 +291,25 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
 
     const int64_t q_first = (int64_t)qt * QT + (RSPLIT ? 0 : wave * QW);
 
+    if constexpr (!SEED && KCAP > 0 && !RSPLIT) {
+        if (a.redo_flags) {   // redo pass: only if the flagged queries are many, and only tiles that hold one
+            if (*a.redo_count <= a.redo_min) return;
+            const int64_t t0 = (int64_t)qt * QT;
+            int mine = 0;
+            for (int64_t qq = t0 + tid; qq < t0 + QT && qq < a.nq; qq += NW * 64) mine |= a.redo_flags[qq];
+            // workgroup-wide OR through the (still unused) first word of the ring: the kernel has no
+            // static LDS, which the 160 KB dynamic limit set at launch leaves no room for
+            int *vote = reinterpret_cast<int *>(ring);
+            if (tid == 0) *vote = 0;
+            __syncthreads();
+            if (mine) atomicOr(vote, 1);
+            __syncthreads();
+            const int any = *vote;
+            __syncthreads();   // everyone has read the vote before the ring is filled
+            if (!any) return;  // the same answer in every thread of the workgroup
+        }
+    }
+
     // ---- owner state (lane q owns query q of this wave) ------------------------------
     cand_t lst[LK];
     cand_t seedC = 0;

@@ -233,8 +233,10 @@ class Index:
                                         _stream()))
         return out
 
-    def overflow_stats(self, nq: int, k: int, metric, workspace: torch.Tensor):
-        """(queries redone by the generic kernel, largest region fill) of the last search in `workspace`."""
+    def overflow_stats(self, nq: int, k: int, metric, workspace: torch.Tensor = None):
+        """(queries searched again exactly, largest region fill) of the last search in `workspace`
+        (default: the index's own workspace, used when search() was given none)."""
+        workspace = self._ws if workspace is None else workspace
         a, b = C.c_int64(0), C.c_int64(0)
         _check(lib().lpq_search_overflow_stats(self._h, nq, k, METRIC[metric], workspace.data_ptr(), C.byref(a), C.byref(b)))
         return a.value, b.value

@@ -213,6 +213,49 @@ def test_search_collecting_variant_overflow_is_redone_exactly(lpq, oracle):
         lpq.set_tuning(lpq.TUNE_SEED_ROWS, 0)
 
 
+@pytest.mark.parametrize("nq,clusters,expect_many", [(700, 250, True), (300, 200, True), (300, 500, None), (300, 0, False)])
+@pytest.mark.parametrize("k", [10, 16])
+def test_search_corpus_stored_cluster_by_cluster(lpq, oracle, nq, clusters, expect_many, k):
+    """A corpus stored cluster by cluster (tight clusters, contiguous rows) with queries near the
+    cluster centres: all near neighbours of a query sit in one run of rows, so they share a few groups
+    of the seeding pass, the bound comes from farther clusters and whole clusters pass it - far more
+    candidates than a query's regions hold, for most queries.  Those are searched again exactly: by
+    the register-list matrix-core kernel when they are many, by the generic kernel when they are few
+    (third case: the plain corpus, where a tiny seeding sample makes at most a few queries overflow)."""
+    w = synth.SKEWED_1M.scaled(n=250_000, nq=nq)
+    g = torch.Generator().manual_seed(clusters + k)
+    if clusters:
+        centres = w.corpus()[:clusters]
+        member = torch.arange(w.n) // (w.n // clusters)
+        x = (centres[member] + torch.randint(-2, 3, (w.n, w.d), generator=g).float()).clamp_(0, 255).contiguous()
+        pick = torch.randint(0, clusters, (nq,), generator=g)
+        q = (centres[pick] + torch.randint(-2, 3, (nq, w.d), generator=g).float()).clamp_(0, 255).contiguous()
+    else:
+        x, q = w.corpus(), w.queries()
+    xd, qd = x.cuda(), q.cuda()
+    gq = lpq.Quantizer(w.d, 8).calibrate(xd, "minmax", "global")
+    idx = lpq.Index(gq, w.n).add_f32(xd)
+    oq = _oracle_quant(oracle, gq)
+    oids, odists = oracle.search_i8(oq.encode(x.numpy()), oq.encode(q.numpy()), k, "l2sq", threads=16)
+    lpq.set_tuning(lpq.TUNE_PATH, 3)
+    if expect_many is False:
+        lpq.set_tuning(lpq.TUNE_SEED_ROWS, 8192)
+    try:
+        ids, dists = idx.search(qd, k, "l2sq")
+        torch.cuda.synchronize()
+        redone, fill = idx.overflow_stats(nq, k, "l2sq")
+    finally:
+        lpq.set_tuning(lpq.TUNE_PATH, 0)
+        lpq.set_tuning(lpq.TUNE_SEED_ROWS, 0)
+    assert np.array_equal(dists.cpu().numpy(), odists)
+    assert np.array_equal(ids.cpu().numpy(), oids)
+    print("queries searched again:", redone, "largest region fill:", fill)
+    if expect_many is True:
+        assert redone > 64, (redone, fill)      # the matrix-core redo took them
+    elif expect_many is False:
+        assert redone <= 64, (redone, fill)     # the generic redo (or none at all)
+
+
 def test_search_collecting_variant_ties_at_the_threshold(lpq, oracle):
     """4-bit codes in 32 dimensions: many items share the threshold distance and all of them are
     collected; the selection must still order by (distance, id)."""
