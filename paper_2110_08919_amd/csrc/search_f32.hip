@@ -20,7 +20,28 @@ constexpr int F32_ROWS = F32_THREADS / 8;  // 8 lanes share a row, 4 floats each
 constexpr int F32_R = 4;
 constexpr int F32_STEP = F32_ROWS * F32_R;   // rows per step of a workgroup
 
-template <bool VEC, int QT>
+// One step of the halving butterfly over lane pairs (lane, lane ^ m): of its first CNT partial
+// sums a lane keeps one half (the upper one if `upper`), adds the partner's partial sums of that
+// half and leaves the results in red[0 .. CNT/2).  With a single sum left it is a plain exchange.
+template <int CNT, int N>
+__device__ __forceinline__ void halve_sums(float (&red)[N], int m, bool upper)
+{
+    if constexpr (CNT > 1) {
+        constexpr int H = CNT / 2;
+#pragma unroll
+        for (int i = 0; i < H; ++i) {
+            const float mine = upper ? red[H + i] : red[i];
+            const float theirs = upper ? red[i] : red[H + i];
+            red[i] = mine + __shfl_xor(theirs, m, 64);
+        }
+    } else {
+        red[0] += __shfl_xor(red[0], m, 64);
+    }
+}
+
+// L2 is a template parameter: as a run-time flag the compiler computed both metrics for every pair
+// and selected one (four vector operations per pair instead of two).
+template <bool VEC, int QT, bool L2>
 __global__ __launch_bounds__(F32_THREADS) void search_f32_kernel(
     const float *__restrict__ x, int64_t n, int64_t ldx, const float *__restrict__ qv, int64_t ldq, int64_t nq,
     int d, int k, int mode, int S, int64_t split_rows, cand_t *__restrict__ lists, int cap)
@@ -40,7 +61,8 @@ __global__ __launch_bounds__(F32_THREADS) void search_f32_kernel(
     const int chunks = (d + 3) >> 2, dp = 4 * chunks;
     const int64_t rs = (int64_t)s * split_rows;
     const int64_t re = (rs + split_rows < n) ? rs + split_rows : n;
-    const bool l2 = mode == MODE_F32_L2;
+    constexpr bool l2 = L2;
+    (void)mode;
 
     for (int i = threadIdx.x; i < QT * dp; i += F32_THREADS) {
         const int j = i / dp, c = i % dp;
@@ -61,6 +83,17 @@ __global__ __launch_bounds__(F32_THREADS) void search_f32_kernel(
         // arithmetic starts, so one memory round trip covers 16 loads per lane.
         for (int cb = sub; cb < chunks; cb += 32) {
             float xv[4][F32_R][4];
+            // whole step inside the split and whole 16-byte chunks: plain loads, no per-value selects
+            const bool plain = VEC && base + F32_STEP <= re && cb + 24 < chunks && 4 * (cb + 24) + 3 < d;
+            if (plain) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int r = 0; r < F32_R; ++r) {
+                        const float4 t = *reinterpret_cast<const float4 *>(x + (base + r * F32_ROWS + grp) * ldx + 4 * (cb + 8 * i));
+                        xv[i][r][0] = t.x; xv[i][r][1] = t.y; xv[i][r][2] = t.z; xv[i][r][3] = t.w;
+                    }
+            } else
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int c = cb + 8 * i;
@@ -98,23 +131,38 @@ __global__ __launch_bounds__(F32_THREADS) void search_f32_kernel(
                 }
             }
         }
+        // Sum over the 8 lanes of a row group by a halving butterfly: at each step a lane keeps one
+        // half of its partial sums and receives the partner's partial sums of that half, so the
+        // exchange costs QT * F32_R - 1 shuffles in all (not 3 per sum) and the finished sums end up
+        // spread over the lanes: lane `sub` owns sums [sub * PER, sub * PER + PER) in (query, row)
+        // order, and tests them against its queries' thresholds.
+        constexpr int NACC = QT * F32_R;
+        constexpr int PER = NACC >= 8 ? NACC / 8 : 1;
+        float red[NACC];
 #pragma unroll
         for (int j = 0; j < QT; ++j)
 #pragma unroll
-            for (int r = 0; r < F32_R; ++r) {
-                float a = acc[j][r];
-                a += __shfl_xor(a, 4, 64);
-                a += __shfl_xor(a, 2, 64);
-                a += __shfl_xor(a, 1, 64);
-                const int64_t row = base + r * F32_ROWS + grp;
-                if (sub == 0 && row < re) {
-                    const cand_t c = make_cand(float_to_sortable(l2 ? a : -a), (uint32_t)row);
-                    if (c < s_thr[j]) {
-                        const int pos = atomicAdd(&s_count[j], 1);
-                        buf[(size_t)j * cap + pos] = c;
-                    }
+            for (int r = 0; r < F32_R; ++r) red[j * F32_R + r] = acc[j][r];
+        halve_sums<NACC>(red, 4, (sub & 4) != 0);
+        halve_sums<(NACC > 1 ? NACC / 2 : 1)>(red, 2, (sub & 2) != 0);
+        halve_sums<(NACC > 3 ? NACC / 4 : 1)>(red, 1, (sub & 1) != 0);
+        // NACC >= 8: lane sub holds sums sub * PER + i.  NACC = 4 (one query): after the two halving
+        // steps lanes 2p and 2p + 1 both hold sum p; the even lane acts.
+        const int first = NACC >= 8 ? sub * PER : (sub >> 1);
+        const bool acts = NACC >= 8 || (sub & 1) == 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int idx = first + i, j = idx / F32_R, r = idx % F32_R;
+            const int64_t row = base + r * F32_ROWS + grp;
+            if (acts && row < re) {
+                const float a = red[i];
+                const cand_t c = make_cand(float_to_sortable(l2 ? a : -a), (uint32_t)row);
+                if (c < s_thr[j]) {
+                    const int pos = atomicAdd(&s_count[j], 1);
+                    buf[(size_t)j * cap + pos] = c;
                 }
             }
+        }
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < QT; ++j) block_compact_if_full(buf + (size_t)j * cap, cap, k, F32_STEP, &s_count[j], &s_thr[j]);
@@ -154,12 +202,10 @@ hipError_t launch_f32_tile(bool vec, unsigned blocks, size_t shmem, hipStream_t 
                            int64_t ldx, const float *q, int64_t ldq, int64_t nq, int d, int k, int mode, int S,
                            int64_t split_rows, cand_t *lists, int cap)
 {
-    if (vec)
-        search_f32_kernel<true, QT><<<blocks, F32_THREADS, shmem, st>>>(x, n, ldx, q, ldq, nq, d, k, mode, S, split_rows,
-                                                                          lists, cap);
-    else
-        search_f32_kernel<false, QT><<<blocks, F32_THREADS, shmem, st>>>(x, n, ldx, q, ldq, nq, d, k, mode, S, split_rows,
-                                                                           lists, cap);
+    const bool l2 = mode == MODE_F32_L2;
+    auto kern = vec ? (l2 ? search_f32_kernel<true, QT, true> : search_f32_kernel<true, QT, false>)
+                    : (l2 ? search_f32_kernel<false, QT, true> : search_f32_kernel<false, QT, false>);
+    kern<<<blocks, F32_THREADS, shmem, st>>>(x, n, ldx, q, ldq, nq, d, k, mode, S, split_rows, lists, cap);
     return hipGetLastError();
 }
 
