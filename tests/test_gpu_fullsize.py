@@ -127,3 +127,9 @@ def test_config4_scaled_10m_x96_packed_4bit(lpq, oracle):
     for nb in (1, 16):
         bi, bd = index.search(q[:nb], 10, "l2sq")
         assert np.array_equal(bi.cpu().numpy(), ids[:nb]) and np.array_equal(bd.cpu().numpy(), dists[:nb])
+
+
+def test_config2_with_200_000_queries_in_one_call(lpq, oracle):
+    """Twenty times the benchmark batch in one call (391 query tiles, gigabytes of workspace): offsets
+    into the per-query buffers pass 2^31."""
+    _full_case(lpq, oracle, synth.SKEWED_1M.scaled(nq=200_000), 10, "minmax", "global", sample=24)
