@@ -131,7 +131,10 @@ int lpq_index_create_packed(lpq_index **out, const lpq_quantizer *q, int64_t cap
 void lpq_index_destroy(lpq_index *idx);
 
 /* Append n items: fp32 vectors (encoded with the index's quantizer, Equation 1) or codes
- * produced earlier by lpq_encode with the same constants (row stride ld bytes). */
+ * produced earlier by lpq_encode with the same constants (row stride ld bytes).  Item ids are
+ * the positions in add order.  Results never depend on the order of the items, but large-batch
+ * search time does when near neighbours sit in adjacent rows (a corpus stored cluster by cluster:
+ * up to ~5x slower, see lpq_search_overflow_stats); adding the items in shuffled order avoids it. */
 int lpq_index_add_f32(lpq_index *idx, const float *x_dev, int64_t n, int64_t ld, void *stream);
 int lpq_index_add_i8(lpq_index *idx, const int8_t *codes_dev, int64_t n, int64_t ld, void *stream);
 int64_t lpq_index_size(const lpq_index *idx);  /* items added so far; -1 for NULL */
