@@ -220,9 +220,11 @@ int lpq_rerank_f32(const float *x_dev, int64_t n, int64_t ldx, const float *q_de
  *                        pairs: 0 built-in, 1 each XCD takes whole splits, 2 each XCD takes whole
  *                        query tiles, 3 plain block order
  *   LPQ_TUNE_WAVE_QUERIES queries per wave of the collecting variant: 64 or 128 (0 = built-in)
- * Results never depend on PATH, SPLITS, SEED_ROWS, WORK_ORDER or WAVE_QUERIES. */
+ *   LPQ_TUNE_REGION_CAP  candidates a region of the collecting variant holds (0 = built-in); a tiny
+ *                        value makes most queries overflow and go through the exact redo paths
+ * Results never depend on PATH, SPLITS, SEED_ROWS, WORK_ORDER, WAVE_QUERIES or REGION_CAP. */
 enum { LPQ_TUNE_PATH = 0, LPQ_TUNE_SPLITS = 1, LPQ_TUNE_SEED_ROWS = 2, LPQ_TUNE_DRY_RUN = 3, LPQ_TUNE_WORK_ORDER = 4,
-       LPQ_TUNE_WAVE_QUERIES = 5, LPQ_TUNE_COUNT_ = 6 };
+       LPQ_TUNE_WAVE_QUERIES = 5, LPQ_TUNE_REGION_CAP = 6, LPQ_TUNE_COUNT_ = 7 };
 int lpq_set_tuning(int key, int64_t value);
 
 /* Kernel timing for benchmarks.  While enabled, every launch of the contraction/top-k

@@ -155,8 +155,12 @@ bool mfma_collect_wide(int64_t nq, int d_pad);           // collecting mode may 
 bool mfma_row_split(int64_t nq, int d_pad, bool packed = false);   // few queries: waves split rows, share queries
 // With stage_stride > 0 (a multiple of 128) the pass is a systematic sample of [row0, row1): one
 // stage (64 rows; 128 in row-split launches) every stage_stride rows, stages_per_split per split.
+// With piece_stride > 0 instead (not for row-split launches; row0 = 0): a finer systematic sample,
+// runs of 8 rows every piece_stride rows, dealt round-robin to the splits, eight runs to a stage,
+// piece_stages stages per split - neighbouring rows of the corpus then fall into different groups.
 hipError_t launch_seed_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S, int SEG, int32_t *gmax,
-                            hipStream_t st, int64_t stage_stride = 0, int stages_per_split = 0);
+                            hipStream_t st, int64_t stage_stride = 0, int stages_per_split = 0,
+                            int64_t piece_stride = 0, int piece_stages = 0);
 // Collecting scan (k <= 128): thresholds stay at seeds[q] (required); every candidate beating its
 // query's seed is appended to cbuf[(q * SS + region) * Cs + ...], SS = mfma_collect_regions(S, rsplit),
 // and ccnt[q * SS + region] = number offered (entries beyond Cs were dropped).

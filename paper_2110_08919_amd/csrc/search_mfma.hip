@@ -39,6 +39,8 @@
 // is a group of items disjoint from the others, so the k-th largest group maximum of a query
 // is a value that at least k items reach: an upper bound on the k-th best key that costs
 // nothing but the contraction itself.  The main pass starts from it.
+#include <type_traits>
+
 #include "mfma_common.h"
 
 namespace lpq {
@@ -60,6 +62,11 @@ struct MfmaIo {     // what a launch reads and writes besides the corpus and the
     int64_t split_stride;       // first row of split s is row0 + s * split_stride; 0: splits follow each other
     int64_t split_stride_rows;  // with a stride: rows per split
     int64_t stage_stride;       // seeding pass: first rows of consecutive stages are this far apart (0: adjacent)
+    // Seeding pass over a finer systematic sample (not for row-split launches): piece P = rows
+    // [P * piece_stride, + 8); split s takes pieces s, s + S, s + 2S, ..., eight to a stage,
+    // piece_stages stages.  0: stages of 64 consecutive rows as above.
+    int64_t piece_stride;
+    int piece_stages;
 };
 
 struct WaveQ {      // pointers into the wave's private LDS region
@@ -367,7 +374,13 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     // is the chunk that belongs in its slot, so every instruction reads whole rows.
     const unsigned ring_lds = lds_offset(ring), aux_lds = lds_offset(aux);
     const int lpt = IPW + (!L2 ? 0 : (RSPLIT ? 2 : (wave < RS / 64 + 1 ? 1 : 0)));   // copies this wave issues per stage
-    int src_off[IPW];   // byte offset of the lane's source chunk inside a stage of corpus rows
+    // Seeding pass by pieces: the 64 rows of a stage are eight runs of 8 rows taken S * piece_stride
+    // rows apart, so that neighbouring rows of the corpus fall into different splits (and groups).
+    constexpr bool CAN_PIECES = SEED && !RSPLIT;
+    const bool pieces = CAN_PIECES && o.piece_stride > 0;
+    const int64_t piece_gap = pieces ? (int64_t)S * o.piece_stride : 0;   // rows between the pieces of a stage
+    using src_off_t = typename std::conditional<CAN_PIECES, int64_t, int>::type;
+    src_off_t src_off[IPW];   // byte offset of the lane's source chunk relative to the first row of a stage
 #pragma unroll
     for (int j = 0; j < IPW; ++j) {
         const int p = (wave * IPW + j) * 64 + lane;
@@ -375,11 +388,17 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
         int c = sl ^ swz<SLOTS>(r & 31);
         c = c < CPR ? c : CPR - 1;          // padding slots of non-power-of-two rows: any valid chunk
         src_off[j] = r * ROWB + c * 16;
+        if constexpr (CAN_PIECES) {
+            if (pieces) src_off[j] = ((r & 7) + (int64_t)(r >> 3) * piece_gap) * ROWB + c * 16;
+        }
     }
+    // row of the accumulator seed that wave 0's lane brings (non-row-split launches)
+    const int64_t cin_off = pieces ? (int64_t)(lane >> 3) * piece_gap + (lane & 7) : (int64_t)wave * 64 + lane;
 #define LPQ_ISSUE(ST)                                                                                   \
     do {                                                                                                \
         const int st_ = (ST);                                                                           \
-        const int64_t r0_ = rs + (int64_t)st_ * sstride;                                                \
+        const int64_t r0_ = pieces ? ((int64_t)s + (int64_t)S * 8 * st_) * o.piece_stride                \
+                                   : rs + (int64_t)st_ * sstride;                                       \
         const int ring_slot_ = st_ % NST;                                                               \
         const int8_t *src_ = a.codes + r0_ * ROWB;                                                      \
         _Pragma("unroll") for (int j = 0; j < IPW; ++j)                                                 \
@@ -390,7 +409,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
             if (lane < 1)                                                                               \
                 async_copy4(a.parity + r0_ / 32 + wave, aux_lds + (ring_slot_ * AUX_INTS + RS + wave) * 4); \
         } else if (L2 && wave < RS / 64) {                                                              \
-            async_copy4(a.cinit + r0_ + wave * 64 + lane, aux_lds + (ring_slot_ * AUX_INTS + wave * 64) * 4); \
+            async_copy4(a.cinit + r0_ + cin_off, aux_lds + (ring_slot_ * AUX_INTS + wave * 64) * 4);     \
         } else if (L2 && wave == RS / 64) {                                                             \
             if (lane < RS / 32)                                                                         \
                 async_copy4(a.parity + r0_ / 32 + lane, aux_lds + (ring_slot_ * AUX_INTS + RS) * 4);    \
@@ -478,7 +497,9 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     } while (0)
 
     int T = (re > rs) ? (int)((re - rs + RS - 1) / RS) : 0;
-    if (ILV) {   // stages s, s + S, s + 2S, ... of the ceil(rows / RS) stages of the corpus
+    if (pieces) {
+        T = o.piece_stages;
+    } else if (ILV) {   // stages s, s + S, s + 2S, ... of the ceil(rows / RS) stages of the corpus
         const int64_t all = (row1 - row0 + RS - 1) / RS;
         T = (all > s) ? (int)((all - s + S - 1) / S) : 0;
     } else if (SEED && o.stage_stride) {   // split_rows / RS stages, as far as their first rows are real items
@@ -838,12 +859,20 @@ int mfma_seed_segments(int S, int k, bool rsplit)
 // in row-split launches) every stage_stride rows, stages_per_split of them per split, so a corpus
 // stored in some order (by cluster, by norm) is sampled evenly.  stage_stride = 0: rows [row0, row1).
 hipError_t launch_seed_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S, int SEG, int32_t *gmax,
-                            hipStream_t st, int64_t stage_stride, int stages_per_split)
+                            hipStream_t st, int64_t stage_stride, int stages_per_split, int64_t piece_stride,
+                            int piece_stages)
 {
     if (!mfma_collect_supported(a.d_pad, a.k) || !gmax) return hipErrorInvalidValue;
     MfmaIo o = {};
     o.gmax = gmax; o.SEG = SEG;
-    if (stage_stride) {
+    if (piece_stride) {
+        // every piece lies inside [row0, row1): the last one starts at (S * 8 * piece_stages - 1) * piece_stride
+        if (a.rsplit || row0 != 0 || piece_stages < 1 || piece_stride < 8 ||
+            ((int64_t)S * 8 * piece_stages - 1) * piece_stride + 8 > row1)
+            return hipErrorInvalidValue;
+        o.piece_stride = piece_stride;
+        o.piece_stages = piece_stages;
+    } else if (stage_stride) {
         const int rs_rows = a.rsplit ? 128 : 64;
         if (stages_per_split < 1 || stage_stride < rs_rows || stage_stride % 128) return hipErrorInvalidValue;
         o.stage_stride = stage_stride;

@@ -19,7 +19,7 @@ OK, EINVAL, ERANGE, ENOMEM, EDEVICE, ENONFINITE, ESTATE = range(7)
 CALIB_MINMAX, CALIB_ABSMAX, CALIB_GAUSS, CALIB_QUANTILE = 0, 1, 2, 3
 SCOPE_PER_FEATURE, SCOPE_GLOBAL, SCOPE_SHARED_WIDTH = 0, 1, 2
 METRIC_L2SQ, METRIC_IP = 0, 1
-TUNE_PATH, TUNE_SPLITS, TUNE_SEED_ROWS, TUNE_DRY_RUN, TUNE_WORK_ORDER, TUNE_WAVE_QUERIES = 0, 1, 2, 3, 4, 5
+TUNE_PATH, TUNE_SPLITS, TUNE_SEED_ROWS, TUNE_DRY_RUN, TUNE_WORK_ORDER, TUNE_WAVE_QUERIES, TUNE_REGION_CAP = 0, 1, 2, 3, 4, 5, 6
 
 CALIB = {"minmax": CALIB_MINMAX, "absmax": CALIB_ABSMAX, "gauss": CALIB_GAUSS, "quantile": CALIB_QUANTILE}
 SCOPE = {"per_feature": SCOPE_PER_FEATURE, "global": SCOPE_GLOBAL, "shared_width": SCOPE_SHARED_WIDTH}

@@ -213,15 +213,18 @@ def test_search_collecting_variant_overflow_is_redone_exactly(lpq, oracle):
         lpq.set_tuning(lpq.TUNE_SEED_ROWS, 0)
 
 
-@pytest.mark.parametrize("nq,clusters,expect_many", [(700, 250, True), (300, 200, True), (300, 500, None), (300, 0, False)])
+@pytest.mark.parametrize("nq,clusters,seed_rows,region_cap,expect", [
+    (700, 250, 0, 0, "none"), (700, 250, 8192, 0, "any"), (700, 250, 0, 2, "many"), (300, 0, 0, 1, "many"),
+    (300, 0, 8192, 0, "few")])
 @pytest.mark.parametrize("k", [10, 16])
-def test_search_corpus_stored_cluster_by_cluster(lpq, oracle, nq, clusters, expect_many, k):
+def test_search_corpus_stored_cluster_by_cluster(lpq, oracle, nq, clusters, seed_rows, region_cap, expect, k):
     """A corpus stored cluster by cluster (tight clusters, contiguous rows) with queries near the
-    cluster centres: all near neighbours of a query sit in one run of rows, so they share a few groups
-    of the seeding pass, the bound comes from farther clusters and whole clusters pass it - far more
-    candidates than a query's regions hold, for most queries.  Those are searched again exactly: by
-    the register-list matrix-core kernel when they are many, by the generic kernel when they are few
-    (third case: the plain corpus, where a tiny seeding sample makes at most a few queries overflow)."""
+    cluster centres: all near neighbours of a query sit in one run of rows.  The seeding pass samples
+    runs of 8 rows dealt round-robin to its splits, so such a run still lands in many groups and the
+    bound stays tight: no query overflows ("none"); with a sample far too small for that (forced
+    here) a few dozen do.  Queries that overflow are searched again exactly - by the generic kernel
+    when they are few, by the register-list matrix-core kernel when they are many (forced here by
+    regions that hold only one or two candidates)."""
     w = synth.SKEWED_1M.scaled(n=250_000, nq=nq)
     g = torch.Generator().manual_seed(clusters + k)
     if clusters:
@@ -238,8 +241,8 @@ def test_search_corpus_stored_cluster_by_cluster(lpq, oracle, nq, clusters, expe
     oq = _oracle_quant(oracle, gq)
     oids, odists = oracle.search_i8(oq.encode(x.numpy()), oq.encode(q.numpy()), k, "l2sq", threads=16)
     lpq.set_tuning(lpq.TUNE_PATH, 3)
-    if expect_many is False:
-        lpq.set_tuning(lpq.TUNE_SEED_ROWS, 8192)
+    lpq.set_tuning(lpq.TUNE_SEED_ROWS, seed_rows)
+    lpq.set_tuning(lpq.TUNE_REGION_CAP, region_cap)
     try:
         ids, dists = idx.search(qd, k, "l2sq")
         torch.cuda.synchronize()
@@ -247,13 +250,16 @@ def test_search_corpus_stored_cluster_by_cluster(lpq, oracle, nq, clusters, expe
     finally:
         lpq.set_tuning(lpq.TUNE_PATH, 0)
         lpq.set_tuning(lpq.TUNE_SEED_ROWS, 0)
+        lpq.set_tuning(lpq.TUNE_REGION_CAP, 0)
     assert np.array_equal(dists.cpu().numpy(), odists)
     assert np.array_equal(ids.cpu().numpy(), oids)
     print("queries searched again:", redone, "largest region fill:", fill)
-    if expect_many is True:
+    if expect == "many":
         assert redone > 64, (redone, fill)      # the matrix-core redo took them
-    elif expect_many is False:
+    elif expect == "few":
         assert redone <= 64, (redone, fill)     # the generic redo (or none at all)
+    elif expect == "none":
+        assert redone == 0, (redone, fill)
 
 
 def test_search_collecting_variant_ties_at_the_threshold(lpq, oracle):
