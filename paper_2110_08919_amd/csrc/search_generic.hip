@@ -5,6 +5,7 @@
 // not take and an independent second implementation of the same result.
 #include "block_select.h"
 #include "lpq_internal.h"
+#include "wave_ops.h"
 
 namespace lpq {
 
@@ -101,15 +102,7 @@ __global__ __launch_bounds__(GEN_THREADS) void search_generic_list_kernel(
 }
 
 // 64-bit minimum over the wave; every lane gets the result.
-__device__ __forceinline__ cand_t wave_min_cand(cand_t c)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        const cand_t t = __shfl_xor(c, o, 64);
-        c = t < c ? t : c;
-    }
-    return c;
-}
+__device__ __forceinline__ cand_t wave_min_cand(cand_t c) { return wave_min_u64(c); }
 
 // Final id and distance of candidate c of query q, written at position `at`.
 __device__ __forceinline__ void emit_result(cand_t c, int64_t at, int64_t q, int32_t *__restrict__ ids,

@@ -42,6 +42,7 @@
 #include <type_traits>
 
 #include "mfma_common.h"
+#include "wave_ops.h"
 
 namespace lpq {
 
@@ -673,12 +674,7 @@ __global__ __launch_bounds__(256) void seed_finalize_kernel(const int32_t *__res
             int mx = v[0];
 #pragma unroll
             for (int e = 1; e < E; ++e) mx = v[e] > mx ? v[e] : mx;
-            int wmx = mx;
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) {
-                const int t = __shfl_xor(wmx, o, 64);
-                wmx = t > wmx ? t : wmx;
-            }
+            const int wmx = wave_max_i32(mx);
             kth = wmx;
             const int win = __ffsll((unsigned long long)__ballot(mx == wmx)) - 1;
             bool done = lane != win;
