@@ -6,6 +6,7 @@
 // of the float.
 #include "block_select.h"
 #include "lpq_internal.h"
+#include "wave_ops.h"
 
 namespace lpq {
 
@@ -20,11 +21,13 @@ constexpr int F32_ROWS = F32_THREADS / 8;  // 8 lanes share a row, 4 floats each
 constexpr int F32_R = 4;
 constexpr int F32_STEP = F32_ROWS * F32_R;   // rows per step of a workgroup
 
-// One step of the halving butterfly over lane pairs (lane, lane ^ m): of its first CNT partial
-// sums a lane keeps one half (the upper one if `upper`), adds the partner's partial sums of that
-// half and leaves the results in red[0 .. CNT/2).  With a single sum left it is a plain exchange.
-template <int CNT, int N>
-__device__ __forceinline__ void halve_sums(float (&red)[N], int m, bool upper)
+// One step of the halving butterfly over lane pairs: of its first CNT partial sums a lane keeps
+// one half (the upper one if `upper`), adds the partner's partial sums of that half and leaves the
+// results in red[0 .. CNT/2).  With a single sum left it is a plain exchange.  The partner is given
+// by a DPP control (no LDS round trip): it must differ from the lane in the bit that `upper` tests
+// and lie in the same group of 8 lanes; which other bits differ does not matter for the sums.
+template <int CNT, int CTRL, int N>
+__device__ __forceinline__ void halve_sums(float (&red)[N], bool upper)
 {
     if constexpr (CNT > 1) {
         constexpr int H = CNT / 2;
@@ -32,10 +35,10 @@ __device__ __forceinline__ void halve_sums(float (&red)[N], int m, bool upper)
         for (int i = 0; i < H; ++i) {
             const float mine = upper ? red[H + i] : red[i];
             const float theirs = upper ? red[i] : red[H + i];
-            red[i] = mine + __shfl_xor(theirs, m, 64);
+            red[i] = mine + __int_as_float(dpp_move<CTRL>(__float_as_int(theirs)));
         }
     } else {
-        red[0] += __shfl_xor(red[0], m, 64);
+        red[0] += __int_as_float(dpp_move<CTRL>(__float_as_int(red[0])));
     }
 }
 
@@ -143,9 +146,9 @@ __global__ __launch_bounds__(F32_THREADS) void search_f32_kernel(
         for (int j = 0; j < QT; ++j)
 #pragma unroll
             for (int r = 0; r < F32_R; ++r) red[j * F32_R + r] = acc[j][r];
-        halve_sums<NACC>(red, 4, (sub & 4) != 0);
-        halve_sums<(NACC > 1 ? NACC / 2 : 1)>(red, 2, (sub & 2) != 0);
-        halve_sums<(NACC > 3 ? NACC / 4 : 1)>(red, 1, (sub & 1) != 0);
+        halve_sums<NACC, DPP_HALF_MIRROR>(red, (sub & 4) != 0);               // partner 7 - sub: bit 2 differs
+        halve_sums<(NACC > 1 ? NACC / 2 : 1), DPP_XOR2>(red, (sub & 2) != 0);
+        halve_sums<(NACC > 3 ? NACC / 4 : 1), DPP_XOR1>(red, (sub & 1) != 0);
         // NACC >= 8: lane sub holds sums sub * PER + i.  NACC = 4 (one query): after the two halving
         // steps lanes 2p and 2p + 1 both hold sum p; the even lane acts.
         const int first = NACC >= 8 ? sub * PER : (sub >> 1);
