@@ -365,6 +365,28 @@ def test_search_extreme_codes_no_overflow(lpq, oracle):
         assert np.array_equal(ids.cpu().numpy(), oids) and np.array_equal(dists.cpu().numpy(), odists)
 
 
+def test_search_largest_d_and_largest_k(lpq, oracle):
+    """d = 32 768 with codes at the ends of the range: the largest integer distance the interface
+    promises to hold in int32 (255^2 * 32 768 = 2 130 739 200); and k = 1024, the largest k."""
+    d, n = 32768, 150
+    rng = np.random.default_rng(13)
+    c = rng.choice(np.array([-128, 127], np.int8), size=(n, d))
+    q = rng.choice(np.array([-128, 127], np.int8), size=(3, d))
+    c[7] = 127
+    q[1] = -128                                       # pair (1, 7): every feature differs by 255
+    gq = lpq.Quantizer(d, 8).set_params(np.zeros(d), np.full(d, -128.0), np.full(d, 128.0))
+    idx = lpq.Index(gq, n).add_i8(dev(c))
+    for metric in ("l2sq", "ip"):
+        ids, dists = idx.search(dev(q), n, metric)
+        oids, odists = oracle.search_i8(c, q, n, metric, threads=4)
+        assert np.array_equal(ids.cpu().numpy(), oids) and np.array_equal(dists.cpu().numpy(), odists)
+    ids, dists = idx.search(dev(q), n, "l2sq")
+    assert int(dists[1].max()) == 255 * 255 * d
+    w = synth.SKEWED_1M.scaled(n=6000, nq=7)
+    _run_search_case(lpq, oracle, w, 1024, "l2sq", "minmax", "global", 0)
+    _run_search_case(lpq, oracle, w, 1024, "ip", "absmax", "global", 2)
+
+
 def test_incremental_add_and_determinism(lpq, oracle):
     w = synth.SKEWED_1M.scaled(n=5003, nq=50)
     x, q = w.corpus().cuda(), w.queries().cuda()
