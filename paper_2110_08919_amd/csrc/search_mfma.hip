@@ -31,14 +31,23 @@
 // at its seed for the whole scan and a drain appends every exact candidate that beats it to a
 // region of global memory owned by this (query, split[, wave]): no lists, no atomics outside the
 // wave's LDS counters.  The seed threshold is reached by at least k items, so the k best are among
-// the collected ones; a later kernel selects them (or hands a query whose region overflowed to the
-// generic kernel).
+// the collected ones; a later kernel selects them (or flags a query whose region overflowed for an
+// exact redo: by the generic kernel, or, when many are flagged, by a launch of this kernel in list
+// mode that skips query tiles without a flagged query).  With short rows and many queries a wave
+// holds 128 queries (NB = 4 blocks of 32) instead of 64.
+//
+// Row-split launches (RSPLIT, at most 64 queries).  The four waves share the 64 queries and split
+// the rows of a 128-row stage; each wave copies, waits for and reads only its own 32 rows, so there
+// is no workgroup barrier and the launch runs at the speed the corpus streams in.  PACK: the rows
+// hold two 4-bit codes per byte and are spread over the operand registers after the LDS read.
 //
 // Seeding pass (SEED = true).  The same pipeline with collection switched off: every lane
 // only tracks the maximum E it has seen per segment of its split.  Each (segment, lane half)
 // is a group of items disjoint from the others, so the k-th largest group maximum of a query
 // is a value that at least k items reach: an upper bound on the k-th best key that costs
-// nothing but the contraction itself.  The main pass starts from it.
+// nothing but the contraction itself.  The main pass starts from it.  The pass reads a systematic
+// sample of the corpus: whole stages at a stride, or (k <= 16) runs of 8 rows gathered from places
+// far apart, so that rows stored next to each other fall into different groups.
 #include <type_traits>
 
 #include "mfma_common.h"
