@@ -57,6 +57,17 @@ def test_argument_checks_without_device(L):
     assert L.lpq_set_tuning(99, 0) == lpq.EINVAL
     assert L.lpq_set_tuning(lpq.TUNE_SPLITS, 0) == lpq.OK
     assert L.lpq_profile_read(None, None) == lpq.EINVAL
+    assert L.lpq_index_create_packed(None, None, 10) == lpq.EINVAL
+    assert L.lpq_gather_dist_i8(None, None, 1, 4, None, 3, 0, None, None) == lpq.EINVAL
+    assert L.lpq_search_overflow_stats(None, 1, 1, 0, None, None, None) == lpq.EINVAL
+    one = C.c_int(1)
+    p1 = C.addressof(one)                                     # any non-null address: checks come before any use
+    assert L.lpq_rerank_f32(p1, 10, 4, p1, 1, 4, 4, p1, 5000, 5, 0, p1, p1, None) == lpq.ERANGE   # kc > 4096
+    assert L.lpq_rerank_f32(p1, 10, 4, p1, 1, 4, 4, p1, 8, 0, 0, p1, p1, None) == lpq.EINVAL      # k < 1
+    assert L.lpq_rerank_f32(None, 10, 4, p1, 1, 4, 4, p1, 8, 5, 0, p1, p1, None) == lpq.EINVAL    # null corpus
+    # workspace of the fp32 search: host arithmetic only, grows with the batch
+    small, large = L.lpq_search_f32_workspace_bytes(1_000_000, 10, 128, 10), L.lpq_search_f32_workspace_bytes(1_000_000, 1000, 128, 10)
+    assert 0 < small <= large
     L.lpq_quantizer_destroy(None)
     L.lpq_index_destroy(None)
 
