@@ -3,6 +3,8 @@ oracle: dimensions on both sides of every row length, corpora from one row to a 
 a split boundary, query batches across the tile sizes of every kernel variant, every k the list
 and collecting variants take, few-bit codes (ties everywhere), every tuning path, packed and
 unpacked storage.  Bit-exact ids and distances.  Needs a real MI355X."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -54,7 +56,7 @@ def _data(c):
     return x, q
 
 
-@pytest.mark.parametrize("seed", range(160))
+@pytest.mark.parametrize("seed", range(int(os.environ.get("LPQ_TEST_RANDOM_CASES", "160"))))   # more cases on request
 def test_random_configuration_bit_exact(lpq, oracle, seed):
     c = _case(seed)
     print(c, flush=True)
