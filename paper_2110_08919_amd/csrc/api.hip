@@ -264,9 +264,11 @@ static int index_create_impl(lpq_index **out, const lpq_quantizer *q, int64_t ca
     if (!idx) return fail(LPQ_ENOMEM, "host allocation failed");
     idx->d = q->d; idx->bits = q->bits;
     idx->packed = packed;
-    idx->d_pad = (int)round_up(q->d, 32);
-    if (packed)   // only the matrix-core scan reads packed rows: pad to a row length it has
-        idx->d_pad = q->d <= 64 ? 64 : q->d <= 96 ? 96 : q->d <= 128 ? 128 : q->d <= 192 ? 192 : 256;
+    // Rows are zero padded to a length the matrix-core scans have (64, 96, 128, 192 or 256 bytes):
+    // up to 256 features never fall back to the generic kernel, which is ~100x slower on large
+    // batches; the price is up to 2x the row bytes for d <= 32 and 20 % for 129..160.
+    idx->d_pad = q->d <= 64 ? 64 : q->d <= 96 ? 96 : q->d <= 128 ? 128 : q->d <= 192 ? 192 :
+                 q->d <= 256 ? 256 : (int)round_up(q->d, 32);
     idx->capacity = capacity;
     idx->cap_rows = round_up(capacity, 256) + 256;  // whole tiles may be read past the last item
     const size_t code_bytes = (size_t)idx->cap_rows * idx->d_pad / (packed ? 2 : 1);
@@ -430,6 +432,8 @@ struct Plan {
 
 size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 
+constexpr int WIDE_MIN_BITS = 2;   // narrowest codes that take the 128-queries-per-wave collecting scan
+
 Plan make_plan(const lpq_index *idx, int64_t nq, int k)
 {
     Plan p;
@@ -438,16 +442,20 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     const bool regs = mfma_reg_supported(idx->d_pad, k), coll = mfma_collect_supported(idx->d_pad, k);
     // Large batches of short rows: the collecting variant with 128 queries per wave beats the
     // register lists at any k it takes (fewer LDS reads and less per-stage overhead per contraction).
-    // (Not for codes of fewer than 8 bits: there many items tie at the seed threshold, all of them
-    // are collected, and queries spill to the exact redo.)
-    const bool wide = coll && idx->bits == 8 && mfma_collect_wide(nq, idx->d_pad) && g_tune[LPQ_TUNE_WAVE_QUERIES] != 64;
+    // (Not for codes of fewer than WIDE_MIN_BITS bits: there many items tie at the seed
+    // threshold, all of them are collected, and queries spill to the exact redo.)
+    const bool wide = coll && idx->bits >= WIDE_MIN_BITS && mfma_collect_wide(nq, idx->d_pad) &&
+                      g_tune[LPQ_TUNE_WAVE_QUERIES] != 64;
     // Rows longer than 128 bytes: the register-list kernels hold 6 or 8 operand registers per query
     // block on top of the lists and spill; the collecting variant measured 1.6x (10 000 queries) to
-    // 3.5x (16 queries) faster at d = 256 for every batch size.
-    const bool long_rows = coll && idx->bits == 8 && idx->d_pad > 128;
+    // 3.5x (16 queries) faster at d = 256 for every batch size and code width.
+    const bool long_rows = coll && idx->d_pad > 128;
+    // Lists of 11 to 16 entries: the 16-entry register lists cost more per accepted candidate than
+    // collecting does; collecting measured 11 to 40 % faster at every batch size (d = 64 to 128).
+    const bool long_lists = coll && k > 10;
     if (idx->packed) p.mode = PLAN_MFMA_REG;   // packed rows: row-split register-list kernel only (callers tile the queries)
     else if (want == 3 && coll) p.mode = PLAN_MFMA_COLLECT;
-    else if (want != 1 && want != 4 && (wide || long_rows)) p.mode = PLAN_MFMA_COLLECT;
+    else if (want != 1 && want != 4 && (wide || long_rows || long_lists)) p.mode = PLAN_MFMA_COLLECT;
     else if (want != 1 && regs) p.mode = PLAN_MFMA_REG;
     else if (want != 1 && want != 4 && coll) p.mode = PLAN_MFMA_COLLECT;
     else if (want != 1 && mfma_lds_supported(idx->d_pad, k)) p.mode = PLAN_MFMA_LDS;
