@@ -135,7 +135,7 @@ void lpq_index_destroy(lpq_index *idx);
  * produced earlier by lpq_encode with the same constants (row stride ld bytes).  Item ids are
  * the positions in add order.  Results never depend on the order of the items, but large-batch
  * search time does when near neighbours sit in adjacent rows (a corpus stored cluster by cluster:
- * up to ~5x slower, see lpq_search_overflow_stats); adding the items in shuffled order avoids it. */
+ * up to ~2x slower, see lpq_search_overflow_stats); adding the items in shuffled order avoids it. */
 int lpq_index_add_f32(lpq_index *idx, const float *x_dev, int64_t n, int64_t ld, void *stream);
 int lpq_index_add_i8(lpq_index *idx, const int8_t *codes_dev, int64_t n, int64_t ld, void *stream);
 int64_t lpq_index_size(const lpq_index *idx);  /* items added so far; -1 for NULL */
@@ -241,11 +241,20 @@ int lpq_profile_read_kind(int kind, int64_t *launches, double *total_ms);
 
 /* Diagnostics of the collecting variant: after a search with the same (idx, nq, k, metric) and
  * workspace has finished, the number of queries whose candidates did not fit and that were
- * searched again exactly (up to 64 by the generic kernel, more by a pass of the register-list
+ * searched again (up to 64 by the generic kernel, more by a pass of the register-list
  * matrix-core kernel when k <= 16; 0 when the search did not use the collecting variant) and the
- * largest number of candidates any region received.  Synchronises the device. */
+ * largest number of candidates any region received in the last round of the scan.  Synchronises
+ * the device. */
 int lpq_search_overflow_stats(const lpq_index *idx, int64_t nq, int k, int metric, const void *workspace_dev,
                               int64_t *redone_queries, int64_t *max_region_fill);
+
+/* For 16 < k <= 128 more than 16 such queries are not searched again exactly at once: the scan
+ * runs again (up to two more rounds) over the query tiles that hold one, with bounds taken from
+ * the candidates the round before did collect, and only queries that overflow every time go
+ * through the generic kernel.  *left_queries = their number after the last search (0 when the
+ * plan has no further rounds or they did not run).  Same arguments and synchronisation as above. */
+int lpq_search_overflow_left(const lpq_index *idx, int64_t nq, int k, int metric, const void *workspace_dev,
+                             int64_t *left_queries);
 
 /* Message of the last error on the calling thread ("" if none). */
 const char *lpq_last_error(void);

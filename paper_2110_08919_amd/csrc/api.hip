@@ -424,15 +424,19 @@ struct Plan {
     int SS = 0, Cs = 0;     // PLAN_MFMA_COLLECT: regions per query, capacity of a region
     int Sg = 0;             // PLAN_MFMA_COLLECT: splits of the generic kernel for overflowed queries
     int Sr = 0;             // PLAN_MFMA_COLLECT: splits of the register-list kernel for many overflowed queries (0 = none)
+    bool refine = false;    // PLAN_MFMA_COLLECT: many overflowed queries take a second collecting scan with tighter bounds
     int wave_queries = 64;  // PLAN_MFMA_COLLECT: queries per wave of the scan
     int expect = 0;         // PLAN_MFMA_COLLECT: expected candidates per query
     size_t off_qcodes = 0, off_qnorms = 0, off_lists1 = 0, off_seedlist = 0, off_seeds = 0, off_lists2 = 0,
-           off_gmax = 0, off_merge_tmp = 0, off_cbuf = 0, off_ccnt = 0, off_over = 0, off_qlist = 0, off_redo = 0, total = 0;
+           off_gmax = 0, off_merge_tmp = 0, off_cbuf = 0, off_ccnt = 0, off_over = 0, off_qlist = 0, off_redo = 0, off_bounds2 = 0, off_over2 = 0,
+           off_qlist2 = 0, total = 0;
 };
 
 size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 
-constexpr int WIDE_MIN_BITS = 2;   // narrowest codes that take the 128-queries-per-wave collecting scan
+constexpr int WIDE_MIN_BITS = 2;
+constexpr int REFINE_ROUNDS = 2;        // further rounds of the collecting scan for queries that overflowed (k > 16)
+constexpr int REFINE_GENERIC_MAX = 16;  // ... unless the first round flags no more than this many (generic kernel then)   // narrowest codes that take the 128-queries-per-wave collecting scan
 
 Plan make_plan(const lpq_index *idx, int64_t nq, int k)
 {
@@ -541,9 +545,9 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
             // Finer still (not for row-split launches): runs of 8 rows every piece_stride rows, dealt
             // round-robin to the splits, so that a run of neighbouring rows - a cluster stored
             // contiguously - is spread over many splits and hence over many groups of the pass.
-            // (For k > 16 it measured worse on a corpus sorted by norm - 3.4 -> 28 ms per 10 000
-            // queries at k = 100 - because a split's groups then span wide slices of the order.)
-            if (!p.rsplit && k <= 16) {
+            // (For k > 16 on a corpus sorted by norm a split's groups then span wide slices of the order
+            // and up to a tenth of the queries overflow; the further rounds of the scan take those.)
+            if (!p.rsplit) {
                 const int64_t pstages = ceil_div(stages, p.S1);                 // as many rows as the stage-wise sample
                 const int64_t pstride = pstages > 0 ? n / (8 * pstages * p.S1) : 0;   // all pieces inside the corpus
                 if (pstride >= 16 && pstages >= 1) {
@@ -604,6 +608,13 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
             if (sr > n / 512) sr = n / 512;
             p.Sr = (int)(sr < 1 ? 1 : sr);
             p.off_redo = o; o = align256(o + (size_t)nq * p.Sr * k * sizeof(cand_t));
+        }
+        // longer lists: a second collecting scan of the flagged queries, bounded by what the first collected
+        if (!p.rsplit && !p.Sr) {
+            p.refine = true;
+            p.off_bounds2 = o; o = align256(o + (size_t)p.nq_pad * sizeof(cand_t));
+            p.off_over2 = o;   o = align256(o + (size_t)REFINE_ROUNDS * nq * sizeof(int32_t));
+            p.off_qlist2 = o;  o = align256(o + (size_t)REFINE_ROUNDS * (nq + 1) * sizeof(int32_t));   // per round: list, then its counter
         }
     }
     p.total = o;
@@ -698,10 +709,41 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, const int8_t *qco
         // Queries whose candidates did not fit are searched again, exactly: a few by the generic kernel;
         // many (a corpus full of duplicates or ties) by a pass of the register-list kernel over the
         // query tiles that hold one.  Both are launched; the count on the device decides which works.
-        const int few = p.Sr ? REDO_GENERIC_MAX : INT32_MAX;
+        const int few = p.Sr ? REDO_GENERIC_MAX : (p.refine ? REFINE_GENERIC_MAX : INT32_MAX);
         HIP_TRY(launch_search_generic_list(a, 0, a.n, p.Sg, qlist, qcount, lists2, st, few));
         HIP_TRY(launch_merge(lists2, nq, p.Sg, k, nullptr, nullptr, nullptr, ids, dist, qnorms, emit_mode, st, false, over,
-                             p.Sr ? qcount : nullptr, 0, few));
+                             (p.Sr || p.refine) ? qcount : nullptr, 0, few));
+        if (p.refine) {
+            // Lists too long for the register-list kernel: the flagged queries get bounds from what the
+            // scan collected for them and the scan runs again over the query tiles that hold one, up to
+            // REFINE_ROUNDS times (what a round collects is the FIRST candidates of each region in scan
+            // order, not the best, so one round may still leave too many: each round cuts the number
+            // that pass by about k / (candidates the regions hold)).  What overflows even then goes
+            // through the generic kernel.  Every launch is gated on the device by the count of queries
+            // the round before flagged: more than `few` for the first round, any for the later ones.
+            cand_t *bounds2 = reinterpret_cast<cand_t *>(ws + p.off_bounds2);
+            const int32_t *over_prev = over, *count_prev = qcount;
+            int min_prev = few;
+            const cand_t *bounds_prev = seeds;
+            for (int r = 0; r < REFINE_ROUNDS; ++r) {
+                int32_t *over_r = reinterpret_cast<int32_t *>(ws + p.off_over2) + (size_t)r * nq;
+                int32_t *qlist_r = reinterpret_cast<int32_t *>(ws + p.off_qlist2) + (size_t)r * (nq + 1), *count_r = qlist_r + nq;
+                HIP_TRY(launch_collect_refine(cbuf, ccnt, nq, p.SS, p.Cs, k, over_prev, count_prev, min_prev, bounds_prev,
+                                              bounds2, count_r, st));
+                SearchArgs ar = a;
+                ar.wave_queries = p.wave_queries;
+                ar.redo_flags = over_prev; ar.redo_count = count_prev; ar.redo_min = min_prev;
+                HIP_TRY(launch_collect_mfma(ar, 0, a.n, p.S2, bounds2, cbuf, ccnt, p.Cs, st));
+                HIP_TRY(launch_collect_select(cbuf, ccnt, nq, p.SS, p.Cs, k, over_r, qlist_r, count_r, ids, dist, qnorms,
+                                              emit_mode, st, 0, over_prev, count_prev, min_prev));
+                over_prev = over_r; count_prev = count_r; min_prev = 0; bounds_prev = bounds2;
+                if (r + 1 == REFINE_ROUNDS) {
+                    HIP_TRY(launch_search_generic_list(a, 0, a.n, p.Sg, qlist_r, count_r, lists2, st, INT32_MAX));
+                    HIP_TRY(launch_merge(lists2, nq, p.Sg, k, nullptr, nullptr, nullptr, ids, dist, qnorms, emit_mode, st,
+                                         false, over_r));
+                }
+            }
+        }
         if (p.Sr) {
             cand_t *lists_r = reinterpret_cast<cand_t *>(ws + p.off_redo);
             SearchArgs ar = a;
@@ -835,6 +877,23 @@ extern "C" int lpq_search_overflow_stats(const lpq_index *idx, int64_t nq, int k
     HIP_TRY(hipMemcpy(cnt.data(), ws + p.off_ccnt, cnt.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
     for (int32_t v : over) *redone_queries += v != 0;
     for (int32_t v : cnt) if (v > *max_region_fill) *max_region_fill = v;
+    return LPQ_OK;
+}
+
+extern "C" int lpq_search_overflow_left(const lpq_index *idx, int64_t nq, int k, int metric, const void *workspace_dev,
+                                        int64_t *left_queries)
+{
+    (void)metric;
+    if (!idx || !workspace_dev || !left_queries || nq < 1 || k < 1) return fail(LPQ_EINVAL, "bad argument");
+    *left_queries = 0;
+    const Plan p = make_plan(idx, nq, k);
+    if (p.mode != PLAN_MFMA_COLLECT || !p.refine) return LPQ_OK;
+    HIP_TRY(hipDeviceSynchronize());
+    std::vector<int32_t> over2((size_t)nq);
+    const char *ws = static_cast<const char *>(workspace_dev);
+    HIP_TRY(hipMemcpy(over2.data(), ws + p.off_over2 + (size_t)(REFINE_ROUNDS - 1) * nq * sizeof(int32_t),
+                      over2.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+    for (int32_t v : over2) *left_queries += v != 0;
     return LPQ_OK;
 }
 

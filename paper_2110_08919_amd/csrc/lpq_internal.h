@@ -175,7 +175,16 @@ hipError_t launch_collect_mfma(const SearchArgs &a, int64_t row0, int64_t row1, 
 // Flagged queries are also appended to qlist[atomicAdd(qcount, 1)] (qcount must be zero before).
 hipError_t launch_collect_select(const cand_t *cbuf, const int32_t *ccnt, int64_t nq, int SS, int Cs, int k,
                                  int32_t *over, int32_t *qlist, int32_t *qcount, int32_t *ids, int32_t *dists,
-                                 const int32_t *qnorms, int metric, hipStream_t st, int expected_candidates = 0);
+                                 const int32_t *qnorms, int metric, hipStream_t st, int expected_candidates = 0,
+                                 const int32_t *only = nullptr,   // only (optional): int[nq]; other queries just get over[q] = 0,
+                                 const int32_t *gate_count = nullptr, int gate_min = 0);   // and so do all unless *gate_count > gate_min
+// Second round of the collecting scan for queries flagged by launch_collect_select: bounds_out[q] =
+// the k-th best of what the first round collected for q (a bound on its final k-th best), or
+// bounds_in[q] if that was fewer than k; queries not flagged, and all of them unless
+// *qcount > min_flagged, get the bound that nothing passes.  zero_word (optional) is set to 0.
+hipError_t launch_collect_refine(const cand_t *cbuf, const int32_t *ccnt, int64_t nq, int SS, int Cs, int k,
+                                 const int32_t *over, const int32_t *qcount, int min_flagged, const cand_t *bounds_in,
+                                 cand_t *bounds_out, int32_t *zero_word, hipStream_t st);
 // zero_word (optional): one int the kernel also sets to 0 (the counter of the redo list).
 hipError_t launch_seed_finalize(const int32_t *gmax, int64_t nq, int G, int k, cand_t *seeds, hipStream_t st,
                                 int32_t *zero_word = nullptr);

@@ -216,7 +216,8 @@ __global__ __launch_bounds__(256) void collect_select_wave_kernel(
 __global__ __launch_bounds__(256) void collect_select_kernel(
     const cand_t *__restrict__ cbuf, const int32_t *__restrict__ ccnt, int SS, int Cs, int k, int maxc,
     int32_t *__restrict__ over, int32_t *__restrict__ qlist, int32_t *__restrict__ qcount,
-    int32_t *__restrict__ ids, int32_t *__restrict__ dists, const int32_t *__restrict__ qnorms, int metric)
+    int32_t *__restrict__ ids, int32_t *__restrict__ dists, const int32_t *__restrict__ qnorms, int metric,
+    const int32_t *__restrict__ only, const int32_t *__restrict__ gate_count, int gate_min)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     cand_t *buf = reinterpret_cast<cand_t *>(smem);            // [maxc]
@@ -225,6 +226,12 @@ __global__ __launch_bounds__(256) void collect_select_kernel(
     __shared__ int s_bad;
     const int64_t q = blockIdx.x;
     const int tid = threadIdx.x;
+    if (only) {   // second round: queries flagged in the first one, if they were more than gate_min
+        if (*gate_count <= gate_min || !only[q]) {
+            if (tid == 0) over[q] = 0;
+            return;
+        }
+    }
     const int per = (SS + 255) / 256;                          // consecutive regions per thread
     const int r0 = tid * per, r1 = (r0 + per < SS) ? r0 + per : SS;
     if (tid == 0) s_bad = 0;
@@ -275,6 +282,48 @@ __global__ __launch_bounds__(256) void collect_select_kernel(
     block_bitonic_sort(buf, cap);
     for (int i = tid; i < k; i += 256) emit_result(buf[i], q * k + i, q, ids, dists, qnorms, metric);
     if (tid == 0) over[q] = 0;
+}
+
+// Tighter bounds for queries whose regions overflowed.  Whatever the scan did collect for such a
+// query are real items, so the k-th best of them bounds the query's final k-th best from above -
+// and far more closely than the seeding pass did, since they all passed its bound.  One workgroup
+// per query: every region gives its first min(count, Cs, maxc / SS) candidates, the workgroup
+// sorts them and writes bounds_out[q] = (key of the k-th best, largest id): items with that key
+// or a smaller one pass.  With fewer than k collected the old bound is kept.  Queries that are
+// not flagged get the bound nothing passes (candidate 0), and so does every query when no more
+// than min_flagged are flagged (then the second scan does not run at all).  Also clears *zero_word.
+__global__ __launch_bounds__(256) void collect_refine_kernel(
+    const cand_t *__restrict__ cbuf, const int32_t *__restrict__ ccnt, int SS, int Cs, int k, int maxc,
+    const int32_t *__restrict__ over, const int32_t *__restrict__ qcount, int min_flagged,
+    const cand_t *bounds_in, cand_t *bounds_out /* may be the same array */, int32_t *__restrict__ zero_word)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    cand_t *buf = reinterpret_cast<cand_t *>(smem);            // [maxc]
+    const int64_t q = blockIdx.x;
+    const int tid = threadIdx.x;
+    if (q == 0 && tid == 0 && zero_word) *zero_word = 0;
+    if (*qcount <= min_flagged || !over[q]) {
+        if (tid == 0) bounds_out[q] = 0;
+        return;
+    }
+    const int per = maxc / SS < Cs ? maxc / SS : Cs;           // slots per region, >= 1
+    const int used = SS * per;
+    const int cap = next_pow2(used < 2 ? 2 : used);
+    for (int i = tid; i < cap; i += 256) {
+        cand_t c = CAND_NONE;
+        if (i < used) {
+            const int r = i / per, j = i - r * per;
+            const int cnt = ccnt[q * SS + r];
+            if (j < cnt) c = cbuf[((size_t)q * SS + r) * Cs + j];   // cnt > Cs: the region holds Cs, and j < per <= Cs
+        }
+        buf[i] = c;
+    }
+    __syncthreads();
+    block_bitonic_sort(buf, cap);
+    if (tid == 0) {
+        const cand_t kth = (k <= cap) ? buf[k - 1] : CAND_NONE;
+        bounds_out[q] = (kth == CAND_NONE) ? bounds_in[q] : make_cand(cand_key(kth), 0xFFFFFFFFu);
+    }
 }
 
 // Merge of lists that are each sorted ascending, for small k and many lists: one workgroup per
@@ -387,21 +436,34 @@ int merge_max_sorted_lists(int k)
     return p > 1024 ? 1024 : p;
 }
 
+hipError_t launch_collect_refine(const cand_t *cbuf, const int32_t *ccnt, int64_t nq, int SS, int Cs, int k,
+                                 const int32_t *over, const int32_t *qcount, int min_flagged, const cand_t *bounds_in,
+                                 cand_t *bounds_out, int32_t *zero_word, hipStream_t st)
+{
+    if (nq <= 0) return hipSuccess;
+    const int maxc = 4096;
+    if (SS < 1 || SS > 2048 || Cs < 1 || k > maxc) return hipErrorInvalidValue;
+    collect_refine_kernel<<<(unsigned)nq, 256, (size_t)maxc * sizeof(cand_t), st>>>(cbuf, ccnt, SS, Cs, k, maxc, over, qcount,
+                                                                                   min_flagged, bounds_in, bounds_out, zero_word);
+    return hipGetLastError();
+}
+
 hipError_t launch_collect_select(const cand_t *cbuf, const int32_t *ccnt, int64_t nq, int SS, int Cs, int k,
                                  int32_t *over, int32_t *qlist, int32_t *qcount, int32_t *ids, int32_t *dists,
-                                 const int32_t *qnorms, int metric, hipStream_t st, int expected_candidates)
+                                 const int32_t *qnorms, int metric, hipStream_t st, int expected_candidates,
+                                 const int32_t *only, const int32_t *gate_count, int gate_min)
 {
     if (nq <= 0) return hipSuccess;
     const int maxc = 4096;
     if (SS < 1 || SS > 2048 || k > maxc) return hipErrorInvalidValue;
-    if (expected_candidates > 0 && expected_candidates <= 256 && SS <= 64 && k <= 32) {
+    if (!only && expected_candidates > 0 && expected_candidates <= 256 && SS <= 64 && k <= 32) {
         collect_select_wave_kernel<<<(unsigned)ceil_div(nq, (int64_t)4), 256, 0, st>>>(cbuf, ccnt, nq, SS, Cs, k, over, qlist,
                                                                                  qcount, ids, dists, qnorms, metric);
         return hipGetLastError();
     }
     const size_t lds = (size_t)maxc * sizeof(cand_t) + (size_t)(SS + 1) * sizeof(int);
     collect_select_kernel<<<(unsigned)nq, 256, lds, st>>>(cbuf, ccnt, SS, Cs, k, maxc, over, qlist, qcount, ids, dists,
-                                                          qnorms, metric);
+                                                          qnorms, metric, only, gate_count, gate_min);
     return hipGetLastError();
 }
 

@@ -308,7 +308,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
 
     const int64_t q_first = (int64_t)qt * QT + (RSPLIT ? 0 : wave * QW);
 
-    if constexpr (!SEED && KCAP > 0 && !RSPLIT) {
+    if constexpr (!SEED && !RSPLIT) {
         if (a.redo_flags) {   // redo pass: only if the flagged queries are many, and only tiles that hold one
             if (*a.redo_count <= a.redo_min) return;
             const int64_t t0 = (int64_t)qt * QT;

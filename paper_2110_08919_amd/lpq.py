@@ -68,6 +68,7 @@ def lib() -> C.CDLL:
             "lpq_gather_dist_i8": (i32, [vp, vp, i64, i64, vp, i32, i32, vp, vp]),
             "lpq_rerank_f32": (i32, [vp, i64, i64, vp, i64, i64, i32, vp, i32, i32, i32, vp, vp, vp]),
             "lpq_search_overflow_stats": (i32, [vp, i64, i32, i32, vp, C.POINTER(i64), C.POINTER(i64)]),
+            "lpq_search_overflow_left": (i32, [vp, i64, i32, i32, vp, C.POINTER(i64)]),
             "lpq_set_tuning": (i32, [i32, i64]),
             "lpq_profile_enable": (i32, [i32]),
             "lpq_profile_read": (i32, [C.POINTER(i64), C.POINTER(C.c_double)]),
@@ -240,6 +241,14 @@ class Index:
         a, b = C.c_int64(0), C.c_int64(0)
         _check(lib().lpq_search_overflow_stats(self._h, nq, k, METRIC[metric], workspace.data_ptr(), C.byref(a), C.byref(b)))
         return a.value, b.value
+
+    def overflow_left(self, nq: int, k: int, metric, workspace: torch.Tensor = None):
+        """Queries that overflowed again in the second round of the collecting scan of the last search
+        (they went through the generic kernel); 0 when there was no second round."""
+        workspace = self._ws if workspace is None else workspace
+        a = C.c_int64(0)
+        _check(lib().lpq_search_overflow_left(self._h, nq, k, METRIC[metric], workspace.data_ptr(), C.byref(a)))
+        return a.value
 
     def search(self, q: torch.Tensor, k: int, metric="l2sq", out=None, workspace=None):
         """q fp32 [nq, d] or int8 codes [nq, d] on the device -> (ids int32, dists int32) [nq, k]."""

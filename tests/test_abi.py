@@ -60,6 +60,7 @@ def test_argument_checks_without_device(L):
     assert L.lpq_index_create_packed(None, None, 10) == lpq.EINVAL
     assert L.lpq_gather_dist_i8(None, None, 1, 4, None, 3, 0, None, None) == lpq.EINVAL
     assert L.lpq_search_overflow_stats(None, 1, 1, 0, None, None, None) == lpq.EINVAL
+    assert L.lpq_search_overflow_left(None, 1, 1, 0, None, None) == lpq.EINVAL
     one = C.c_int(1)
     p1 = C.addressof(one)                                     # any non-null address: checks come before any use
     assert L.lpq_rerank_f32(p1, 10, 4, p1, 1, 4, 4, p1, 5000, 5, 0, p1, p1, None) == lpq.ERANGE   # kc > 4096

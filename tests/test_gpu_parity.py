@@ -262,6 +262,49 @@ def test_search_corpus_stored_cluster_by_cluster(lpq, oracle, nq, clusters, seed
         assert redone == 0, (redone, fill)
 
 
+@pytest.mark.parametrize("k,nq,clusters,seed_rows,region_cap,expect", [
+    (32, 700, 250, 8192, 0, "second"), (100, 700, 250, 8192, 0, "second"), (128, 300, 100, 8192, 0, "second"),
+    (100, 700, 250, 0, 0, "any"), (32, 700, 250, 0, 2, "generic"), (100, 12, 250, 8192, 0, "few")])
+def test_search_long_lists_on_a_corpus_stored_cluster_by_cluster(lpq, oracle, k, nq, clusters, seed_rows, region_cap,
+                                                                 expect):
+    """k > 16 on the cluster-by-cluster corpus: a sample far too small (forced) gives loose bounds
+    there and most queries overflow their regions.  More than 16 of them go through further
+    rounds of the scan with bounds from what the round before collected ("second": nearly all
+    succeed there); regions of two candidates (forced) overflow in every round and everything ends
+    in the generic kernel ("generic"); 16 or fewer go to the generic kernel at once ("few")."""
+    w = synth.SKEWED_1M.scaled(n=250_000, nq=nq)
+    g = torch.Generator().manual_seed(clusters + k)
+    centres = w.corpus()[:clusters]
+    member = torch.arange(w.n) // (w.n // clusters)
+    x = (centres[member] + torch.randint(-2, 3, (w.n, w.d), generator=g).float()).clamp_(0, 255).contiguous()
+    pick = torch.randint(0, clusters, (nq,), generator=g)
+    q = (centres[pick] + torch.randint(-2, 3, (nq, w.d), generator=g).float()).clamp_(0, 255).contiguous()
+    xd, qd = x.cuda(), q.cuda()
+    gq = lpq.Quantizer(w.d, 8).calibrate(xd, "minmax", "global")
+    idx = lpq.Index(gq, w.n).add_f32(xd)
+    oq = _oracle_quant(oracle, gq)
+    oids, odists = oracle.search_i8(oq.encode(x.numpy()), oq.encode(q.numpy()), k, "l2sq", threads=16)
+    lpq.set_tuning(lpq.TUNE_REGION_CAP, region_cap)
+    lpq.set_tuning(lpq.TUNE_SEED_ROWS, seed_rows)
+    try:
+        ids, dists = idx.search(qd, k, "l2sq")
+        torch.cuda.synchronize()
+        redone, fill = idx.overflow_stats(nq, k, "l2sq")
+        left = idx.overflow_left(nq, k, "l2sq")
+    finally:
+        lpq.set_tuning(lpq.TUNE_REGION_CAP, 0)
+        lpq.set_tuning(lpq.TUNE_SEED_ROWS, 0)
+    assert np.array_equal(dists.cpu().numpy(), odists)
+    assert np.array_equal(ids.cpu().numpy(), oids)
+    print("flagged in the first round:", redone, "left after the last:", left, "largest region fill:", fill)
+    if expect == "second":
+        assert redone > 16 and left < redone // 4, (redone, left, fill)
+    elif expect == "generic":
+        assert redone > 16 and left == redone, (redone, left, fill)
+    elif expect == "few":
+        assert 0 < redone <= 16 and left == 0, (redone, left, fill)
+
+
 def test_search_collecting_variant_ties_at_the_threshold(lpq, oracle):
     """4-bit codes in 32 dimensions: many items share the threshold distance and all of them are
     collected; the selection must still order by (distance, id)."""
