@@ -424,7 +424,7 @@ struct Plan {
     int SS = 0, Cs = 0;     // PLAN_MFMA_COLLECT: regions per query, capacity of a region
     int Sg = 0;             // PLAN_MFMA_COLLECT: splits of the generic kernel for overflowed queries
     int Sr = 0;             // PLAN_MFMA_COLLECT: splits of the register-list kernel for many overflowed queries (0 = none)
-    bool refine = false;    // PLAN_MFMA_COLLECT: many overflowed queries take a second collecting scan with tighter bounds
+    int rounds = 0;         // PLAN_MFMA_COLLECT: further rounds of the collecting scan, with tighter bounds, for overflowed queries
     int wave_queries = 64;  // PLAN_MFMA_COLLECT: queries per wave of the scan
     int expect = 0;         // PLAN_MFMA_COLLECT: expected candidates per query
     size_t off_qcodes = 0, off_qnorms = 0, off_lists1 = 0, off_seedlist = 0, off_seeds = 0, off_lists2 = 0,
@@ -610,11 +610,11 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
             p.off_redo = o; o = align256(o + (size_t)nq * p.Sr * k * sizeof(cand_t));
         }
         // longer lists: a second collecting scan of the flagged queries, bounded by what the first collected
-        if (!p.rsplit && !p.Sr) {
-            p.refine = true;
+        if (!p.Sr) {
+            p.rounds = p.rsplit ? 1 : REFINE_ROUNDS;   // few queries: every launch counts, and their many regions rarely overflow twice
             p.off_bounds2 = o; o = align256(o + (size_t)p.nq_pad * sizeof(cand_t));
-            p.off_over2 = o;   o = align256(o + (size_t)REFINE_ROUNDS * nq * sizeof(int32_t));
-            p.off_qlist2 = o;  o = align256(o + (size_t)REFINE_ROUNDS * (nq + 1) * sizeof(int32_t));   // per round: list, then its counter
+            p.off_over2 = o;   o = align256(o + (size_t)p.rounds * nq * sizeof(int32_t));
+            p.off_qlist2 = o;  o = align256(o + (size_t)p.rounds * (nq + 1) * sizeof(int32_t));   // per round: list, then its counter
         }
     }
     p.total = o;
@@ -709,23 +709,27 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, const int8_t *qco
         // Queries whose candidates did not fit are searched again, exactly: a few by the generic kernel;
         // many (a corpus full of duplicates or ties) by a pass of the register-list kernel over the
         // query tiles that hold one.  Both are launched; the count on the device decides which works.
-        const int few = p.Sr ? REDO_GENERIC_MAX : (p.refine ? REFINE_GENERIC_MAX : INT32_MAX);
-        HIP_TRY(launch_search_generic_list(a, 0, a.n, p.Sg, qlist, qcount, lists2, st, few));
-        HIP_TRY(launch_merge(lists2, nq, p.Sg, k, nullptr, nullptr, nullptr, ids, dist, qnorms, emit_mode, st, false, over,
-                             (p.Sr || p.refine) ? qcount : nullptr, 0, few));
-        if (p.refine) {
+        // (row-split plans - up to 64 queries - never start with the generic kernel: one query there
+        // takes longer than a round of the scan for all of them)
+        const int few = p.Sr ? REDO_GENERIC_MAX : (p.rounds ? (p.rsplit ? -1 : REFINE_GENERIC_MAX) : INT32_MAX);
+        if (few >= 0) {
+            HIP_TRY(launch_search_generic_list(a, 0, a.n, p.Sg, qlist, qcount, lists2, st, few));
+            HIP_TRY(launch_merge(lists2, nq, p.Sg, k, nullptr, nullptr, nullptr, ids, dist, qnorms, emit_mode, st, false, over,
+                                 (p.Sr || p.rounds) ? qcount : nullptr, 0, few));
+        }
+        if (p.rounds) {
             // Lists too long for the register-list kernel: the flagged queries get bounds from what the
             // scan collected for them and the scan runs again over the query tiles that hold one, up to
-            // REFINE_ROUNDS times (what a round collects is the FIRST candidates of each region in scan
+            // p.rounds times (what a round collects is the FIRST candidates of each region in scan
             // order, not the best, so one round may still leave too many: each round cuts the number
             // that pass by about k / (candidates the regions hold)).  What overflows even then goes
             // through the generic kernel.  Every launch is gated on the device by the count of queries
             // the round before flagged: more than `few` for the first round, any for the later ones.
             cand_t *bounds2 = reinterpret_cast<cand_t *>(ws + p.off_bounds2);
             const int32_t *over_prev = over, *count_prev = qcount;
-            int min_prev = few;
+            int min_prev = few < 0 ? 0 : few;
             const cand_t *bounds_prev = seeds;
-            for (int r = 0; r < REFINE_ROUNDS; ++r) {
+            for (int r = 0; r < p.rounds; ++r) {
                 int32_t *over_r = reinterpret_cast<int32_t *>(ws + p.off_over2) + (size_t)r * nq;
                 int32_t *qlist_r = reinterpret_cast<int32_t *>(ws + p.off_qlist2) + (size_t)r * (nq + 1), *count_r = qlist_r + nq;
                 HIP_TRY(launch_collect_refine(cbuf, ccnt, nq, p.SS, p.Cs, k, over_prev, count_prev, min_prev, bounds_prev,
@@ -737,7 +741,7 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, const int8_t *qco
                 HIP_TRY(launch_collect_select(cbuf, ccnt, nq, p.SS, p.Cs, k, over_r, qlist_r, count_r, ids, dist, qnorms,
                                               emit_mode, st, 0, over_prev, count_prev, min_prev));
                 over_prev = over_r; count_prev = count_r; min_prev = 0; bounds_prev = bounds2;
-                if (r + 1 == REFINE_ROUNDS) {
+                if (r + 1 == p.rounds) {
                     HIP_TRY(launch_search_generic_list(a, 0, a.n, p.Sg, qlist_r, count_r, lists2, st, INT32_MAX));
                     HIP_TRY(launch_merge(lists2, nq, p.Sg, k, nullptr, nullptr, nullptr, ids, dist, qnorms, emit_mode, st,
                                          false, over_r));
@@ -887,11 +891,11 @@ extern "C" int lpq_search_overflow_left(const lpq_index *idx, int64_t nq, int k,
     if (!idx || !workspace_dev || !left_queries || nq < 1 || k < 1) return fail(LPQ_EINVAL, "bad argument");
     *left_queries = 0;
     const Plan p = make_plan(idx, nq, k);
-    if (p.mode != PLAN_MFMA_COLLECT || !p.refine) return LPQ_OK;
+    if (p.mode != PLAN_MFMA_COLLECT || !p.rounds) return LPQ_OK;
     HIP_TRY(hipDeviceSynchronize());
     std::vector<int32_t> over2((size_t)nq);
     const char *ws = static_cast<const char *>(workspace_dev);
-    HIP_TRY(hipMemcpy(over2.data(), ws + p.off_over2 + (size_t)(REFINE_ROUNDS - 1) * nq * sizeof(int32_t),
+    HIP_TRY(hipMemcpy(over2.data(), ws + p.off_over2 + (size_t)(p.rounds - 1) * nq * sizeof(int32_t),
                       over2.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
     for (int32_t v : over2) *left_queries += v != 0;
     return LPQ_OK;

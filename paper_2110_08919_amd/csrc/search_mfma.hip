@@ -310,7 +310,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
 
     if constexpr (!SEED && !RSPLIT) {
         if (a.redo_flags) {   // redo pass: only if the flagged queries are many, and only tiles that hold one
-            if (*a.redo_count <= a.redo_min) return;
+            if (*a.redo_count <= a.redo_min) return;   // the same answer in every thread of the grid
             const int64_t t0 = (int64_t)qt * QT;
             int mine = 0;
             for (int64_t qq = t0 + tid; qq < t0 + QT && qq < a.nq; qq += NW * 64) mine |= a.redo_flags[qq];
@@ -325,6 +325,9 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
             __syncthreads();   // everyone has read the vote before the ring is filled
             if (!any) return;  // the same answer in every thread of the workgroup
         }
+    }
+    if constexpr (!SEED && RSPLIT) {   // row-split launches hold one tile of queries: the count alone decides
+        if (a.redo_flags && *a.redo_count <= a.redo_min) return;
     }
 
     // ---- owner state (lane q owns query q of this wave) ------------------------------
