@@ -435,6 +435,7 @@ struct Plan {
 size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 
 constexpr int WIDE_MIN_BITS = 2;
+constexpr int64_t PACKED_BATCH_MIN = 128;  // packed index: larger batches take one collecting scan instead of tiles of 64 queries
 constexpr int REFINE_ROUNDS = 2;        // further rounds of the collecting scan for queries that overflowed (k > 16)
 constexpr int REFINE_GENERIC_MAX = 16;  // ... unless the first round flags no more than this many (generic kernel then)   // narrowest codes that take the 128-queries-per-wave collecting scan
 
@@ -457,7 +458,10 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     // Lists of 11 to 16 entries: the 16-entry register lists cost more per accepted candidate than
     // collecting does; collecting measured 11 to 40 % faster at every batch size (d = 64 to 128).
     const bool long_lists = coll && k > 10;
-    if (idx->packed) p.mode = PLAN_MFMA_REG;   // packed rows: row-split register-list kernel only (callers tile the queries)
+    // Packed rows: the row-split register-list kernel (callers tile the queries by 64), or for large
+    // batches the collecting scan over all queries at once; the generic kernel on request.
+    const bool packed_batch = idx->packed && coll && nq > PACKED_BATCH_MIN && idx->d_pad >= 96;
+    if (idx->packed) p.mode = want == 1 ? PLAN_GENERIC : (packed_batch ? PLAN_MFMA_COLLECT : PLAN_MFMA_REG);
     else if (want == 3 && coll) p.mode = PLAN_MFMA_COLLECT;
     else if (want != 1 && want != 4 && (wide || long_rows || long_lists)) p.mode = PLAN_MFMA_COLLECT;
     else if (want != 1 && regs) p.mode = PLAN_MFMA_REG;
@@ -525,6 +529,8 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
         p.rsplit = mfma_row_split(nq, idx->d_pad, idx->packed);
         if (p.mode == PLAN_MFMA_COLLECT && mfma_collect_wide(nq, idx->d_pad) && g_tune[LPQ_TUNE_WAVE_QUERIES] != 64)
             p.wave_queries = 128;
+        if (p.mode == PLAN_MFMA_COLLECT && idx->packed)   // the packed scan has one variant per row length
+            p.wave_queries = idx->d_pad <= 128 ? 128 : 64;
         qt = mfma_queries_per_workgroup(nq, idx->d_pad, p.wave_queries == 128);
     }
     const int64_t tiles_q = ceil_div(nq > 0 ? nq : 1, qt);
@@ -602,7 +608,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
         p.off_qlist = o; o = align256(o + ((size_t)nq + 1) * sizeof(int32_t));   // redo list, then its counter
         // redo of many queries by the register-list kernel (k <= 16, 256 queries per workgroup): one
         // list per query and split, few enough splits for a single merge pass
-        if (!p.rsplit && regs) {
+        if (!p.rsplit && regs && !idx->packed) {
             int64_t sr = slots / ceil_div(nq, 256);
             if (sr > merge_max_lists(k)) sr = merge_max_lists(k);
             if (sr > n / 512) sr = n / 512;
@@ -799,6 +805,11 @@ PackedPlan make_packed_plan(const lpq_index *idx, int64_t nq, int k)
         if (b.nq_pad > tail) tail = b.nq_pad;
     }
     pp.nq_pad = ceil_div(nq, PACKED_TILE) * PACKED_TILE + tail;   // every tile may read a whole padded tile
+    const Plan whole = make_plan(idx, nq, k);
+    if (whole.mode == PLAN_MFMA_COLLECT) {   // large batch: one scan over all queries
+        tile = whole.total;
+        if (whole.nq_pad > pp.nq_pad) pp.nq_pad = whole.nq_pad;
+    }
     size_t o = 0;
     pp.off_qcodes = o; o = align256(o + (size_t)pp.nq_pad * idx->d_pad);
     pp.off_qnorms = o; o = align256(o + (size_t)pp.nq_pad * sizeof(int32_t));
@@ -817,6 +828,9 @@ int search_packed(const lpq_index *idx, const PackedPlan &pp, char *ws, int64_t 
     HIP_TRY(launch_permute_queries(reinterpret_cast<const int8_t *>(ws + pp.off_qcodes), pp.nq_pad, idx->d_pad,
                                    metric == LPQ_METRIC_L2SQ, qperm, qadj, st));
     const int emit = metric == LPQ_METRIC_L2SQ ? MODE_I8_L2 : MODE_I8_IP_ADJ;
+    const Plan whole = make_plan(idx, nq, k);
+    if (whole.mode == PLAN_MFMA_COLLECT)
+        return search_core(idx, whole, ws + pp.off_tile, qperm, qadj, nq, k, metric, emit, ids, dist, st);
     for (int64_t q0 = 0; q0 < nq; q0 += PACKED_TILE) {
         const int64_t nt = nq - q0 < PACKED_TILE ? nq - q0 : PACKED_TILE;
         const Plan pt = make_plan(idx, nt, k);
@@ -876,7 +890,7 @@ extern "C" int lpq_search_overflow_stats(const lpq_index *idx, int64_t nq, int k
     if (p.mode != PLAN_MFMA_COLLECT) return LPQ_OK;
     HIP_TRY(hipDeviceSynchronize());
     std::vector<int32_t> over((size_t)nq), cnt((size_t)nq * p.SS);
-    const char *ws = static_cast<const char *>(workspace_dev);
+    const char *ws = static_cast<const char *>(workspace_dev) + (idx->packed ? make_packed_plan(idx, nq, k).off_tile : 0);
     HIP_TRY(hipMemcpy(over.data(), ws + p.off_over, over.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
     HIP_TRY(hipMemcpy(cnt.data(), ws + p.off_ccnt, cnt.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
     for (int32_t v : over) *redone_queries += v != 0;
@@ -894,7 +908,7 @@ extern "C" int lpq_search_overflow_left(const lpq_index *idx, int64_t nq, int k,
     if (p.mode != PLAN_MFMA_COLLECT || !p.rounds) return LPQ_OK;
     HIP_TRY(hipDeviceSynchronize());
     std::vector<int32_t> over2((size_t)nq);
-    const char *ws = static_cast<const char *>(workspace_dev);
+    const char *ws = static_cast<const char *>(workspace_dev) + (idx->packed ? make_packed_plan(idx, nq, k).off_tile : 0);
     HIP_TRY(hipMemcpy(over2.data(), ws + p.off_over2 + (size_t)(p.rounds - 1) * nq * sizeof(int32_t),
                       over2.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
     for (int32_t v : over2) *left_queries += v != 0;

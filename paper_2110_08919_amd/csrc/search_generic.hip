@@ -18,10 +18,15 @@ constexpr int GEN_ROWS = GEN_THREADS / 8;  // rows per step: 8 lanes share a row
 __device__ __forceinline__ void generic_scan(const SearchArgs &a, int64_t rs, int64_t re, int64_t q, const cand_t *seeds,
                                              cand_t *out, int cap, cand_t *buf, uint4 *qs, int *s_count, cand_t *s_thr)
 {
-    const int chunks = a.d_pad >> 4;  // 16-byte chunks per row
+    const int chunks = a.d_pad >> 4;  // 16-byte chunks per row of int8 codes
     const bool l2 = a.metric == LPQ_METRIC_L2SQ;
     for (int c = threadIdx.x; c < chunks; c += GEN_THREADS)
         qs[c] = reinterpret_cast<const uint4 *>(a.qcodes + q * a.d_pad)[c];
+    // Packed rows: a 16-byte chunk holds 32 codes, two to a byte, stored + 8; the low nibbles of a
+    // dword meet one dword of the (permuted) query codes and its high nibbles the next one, as in
+    // the matrix-core scan.  The result is dot(code + 8, q): the same key that scan produces.
+    const int xchunks = a.packed ? chunks >> 1 : chunks;
+    const int64_t row_bytes = a.packed ? a.d_pad >> 1 : a.d_pad;
     for (int i = threadIdx.x; i < cap; i += GEN_THREADS) buf[i] = CAND_NONE;
     if (threadIdx.x == 0) {
         *s_count = 0;
@@ -34,13 +39,28 @@ __device__ __forceinline__ void generic_scan(const SearchArgs &a, int64_t rs, in
         const int64_t row = base + grp;
         int dot = 0;
         if (row < re) {
-            const uint4 *xr = reinterpret_cast<const uint4 *>(a.codes + row * a.d_pad);
-            for (int c = sub; c < chunks; c += 8) {
-                const uint4 xv = xr[c], qv = qs[c];
-                dot = __builtin_amdgcn_sdot4((int)xv.x, (int)qv.x, dot, false);
-                dot = __builtin_amdgcn_sdot4((int)xv.y, (int)qv.y, dot, false);
-                dot = __builtin_amdgcn_sdot4((int)xv.z, (int)qv.z, dot, false);
-                dot = __builtin_amdgcn_sdot4((int)xv.w, (int)qv.w, dot, false);
+            const uint4 *xr = reinterpret_cast<const uint4 *>(a.codes + row * row_bytes);
+            if (a.packed) {
+                for (int c = sub; c < xchunks; c += 8) {
+                    const uint4 xv = xr[c], q0 = qs[2 * c], q1 = qs[2 * c + 1];
+                    const unsigned m = 0x0F0F0F0Fu;
+                    dot = __builtin_amdgcn_sdot4((int)(xv.x & m), (int)q0.x, dot, false);
+                    dot = __builtin_amdgcn_sdot4((int)((xv.x >> 4) & m), (int)q0.y, dot, false);
+                    dot = __builtin_amdgcn_sdot4((int)(xv.y & m), (int)q0.z, dot, false);
+                    dot = __builtin_amdgcn_sdot4((int)((xv.y >> 4) & m), (int)q0.w, dot, false);
+                    dot = __builtin_amdgcn_sdot4((int)(xv.z & m), (int)q1.x, dot, false);
+                    dot = __builtin_amdgcn_sdot4((int)((xv.z >> 4) & m), (int)q1.y, dot, false);
+                    dot = __builtin_amdgcn_sdot4((int)(xv.w & m), (int)q1.z, dot, false);
+                    dot = __builtin_amdgcn_sdot4((int)((xv.w >> 4) & m), (int)q1.w, dot, false);
+                }
+            } else {
+                for (int c = sub; c < chunks; c += 8) {
+                    const uint4 xv = xr[c], qv = qs[c];
+                    dot = __builtin_amdgcn_sdot4((int)xv.x, (int)qv.x, dot, false);
+                    dot = __builtin_amdgcn_sdot4((int)xv.y, (int)qv.y, dot, false);
+                    dot = __builtin_amdgcn_sdot4((int)xv.z, (int)qv.z, dot, false);
+                    dot = __builtin_amdgcn_sdot4((int)xv.w, (int)qv.w, dot, false);
+                }
             }
         }
         dot += __shfl_xor(dot, 4, 64);

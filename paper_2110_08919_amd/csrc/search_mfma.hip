@@ -39,7 +39,8 @@
 // Row-split launches (RSPLIT, at most 64 queries).  The four waves share the 64 queries and split
 // the rows of a 128-row stage; each wave copies, waits for and reads only its own 32 rows, so there
 // is no workgroup barrier and the launch runs at the speed the corpus streams in.  PACK: the rows
-// hold two 4-bit codes per byte and are spread over the operand registers after the LDS read.
+// hold two 4-bit codes per byte and are spread over the operand registers after the LDS read
+// (row-split launches, and the collecting scan and seeding pass of large batches).
 //
 // Seeding pass (SEED = true).  The same pipeline with collection switched off: every lane
 // only tracks the maximum E it has seen per segment of its split.  Each (segment, lane half)
@@ -259,7 +260,8 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     // 16 codes of the lane inside the k-step; the caller hands in query codes permuted the same
     // way.  The matrix core then delivers dot(u, q) = dot(code, q) + 8 sum(q): a constant per query,
     // which shifts every key of a query alike and is taken out when the result is written.
-    static_assert(!PACK || RSPLIT, "packed rows: row-split launches only");
+    static_assert(!PACK || RSPLIT || ((KCAP == 0 || SEED) && KS >= 3),
+                  "packed rows: row-split launches, or the collecting scan and its seeding pass on rows of 48 bytes or more");
     constexpr int CPR = PACK ? KS : 2 * KS;   // 16-byte chunks per corpus row
     constexpr int ROWB = 16 * CPR;            // bytes per corpus row
     constexpr int SLOTS = CPR <= 2 ? 2 : (CPR <= 4 ? 4 : (CPR <= 8 ? 8 : 16));  // LDS slots per row
@@ -760,12 +762,23 @@ hipError_t launch_one(const SearchArgs &a, int64_t row0, int64_t row1, int S, Mf
     // rows of a split: a whole number of stages; splits follow each other unless a stride is given
     const int64_t split_rows = o.split_stride ? o.split_stride_rows : round_up(ceil_div(row1 - row0, S), a.rsplit ? 128 : 64);
     if (!o.split_stride) o.split_stride = split_rows;
-    if constexpr (KCAP != 0) {   // packed rows: row-split launches with register lists (and their seeding pass)
-        if (a.packed) {
-            if (!a.rsplit) return hipErrorInvalidValue;
-            return launch_nw<KS, L2, KCAP, SEED, 4, true, 2, true>(a, row0, row1, S, split_rows, o, st);
+    if (a.packed) {
+        // packed rows: row-split launches with register lists (and their seeding pass) for up to 64
+        // queries; large batches: the collecting scan (and its seeding pass), 128 queries per wave
+        // on rows of up to 64 bytes, 64 on longer ones
+        if (a.rsplit) {
+            if constexpr (KCAP != 0) return launch_nw<KS, L2, KCAP, SEED, 4, true, 2, true>(a, row0, row1, S, split_rows, o, st);
+            return hipErrorInvalidValue;
         }
-    } else if (a.packed) {
+        if constexpr ((KCAP == 0 || SEED) && KS >= 3) {
+            if constexpr (KS <= 4) {
+                if (a.wave_queries != 128) return hipErrorInvalidValue;
+                return launch_nw<KS, L2, KCAP, SEED, 4, false, 4, true>(a, row0, row1, S, split_rows, o, st);
+            } else {
+                if (a.wave_queries != 64) return hipErrorInvalidValue;
+                return launch_nw<KS, L2, KCAP, SEED, 4, false, 2, true>(a, row0, row1, S, split_rows, o, st);
+            }
+        }
         return hipErrorInvalidValue;
     }
     if constexpr (KS <= 4) {

@@ -113,6 +113,43 @@ def test_packed_search_every_row_length(lpq, oracle, d, metric, bits):
     assert np.array_equal(ids.cpu().numpy(), oids)
 
 
+@pytest.mark.parametrize("name,n,nq,k,metric,bits,mode,scope,path,region_cap", [
+    ("skewed", 150_001, 700, 10, "l2sq", 4, "minmax", "global", 0, 0),       # d = 128: 128 queries per wave, ragged tiles
+    ("skewed", 100_000, 300, 16, "l2sq", 4, "minmax", "per_feature", 0, 0),  # largest k
+    ("aniso", 120_000, 513, 10, "ip", 4, "absmax", "global", 0, 0),          # d = 100, inner product: per-query term
+    ("scaled", 90_000, 129, 1, "l2sq", 3, "absmax", "global", 0, 0),         # d = 96: three 16-byte chunks per row; smallest batch
+    ("product", 80_000, 400, 10, "ip", 4, "absmax", "per_feature", 0, 0),    # d = 256: 64 queries per wave
+    ("product", 70_000, 300, 10, "l2sq", 2, "absmax", "per_feature", 0, 0),  # 2 bits: ties everywhere
+    ("skewed", 100_000, 300, 10, "l2sq", 4, "minmax", "global", 0, 2),       # regions of two: further rounds, then the generic kernel
+    ("aniso", 66_000, 300, 10, "ip", 4, "absmax", "global", 1, 0),           # the generic kernel on packed rows
+    ("skewed", 30_000, 40, 10, "l2sq", 4, "minmax", "global", 1, 0),
+])
+def test_packed_search_large_batches(lpq, oracle, name, n, nq, k, metric, bits, mode, scope, path, region_cap):
+    """More than 128 queries on a packed index take ONE collecting scan over all queries instead of
+    tiles of 64 (rows of 48 bytes or more); the generic kernel reads packed rows too (forced here,
+    and the last resort of the collecting scan)."""
+    w = BASES[name].scaled(n=n, nq=nq)
+    idx, gq, q, ocodes, oqcodes = _build(lpq, oracle, w, bits, mode, scope)
+    lpq.set_tuning(lpq.TUNE_PATH, path)
+    lpq.set_tuning(lpq.TUNE_REGION_CAP, region_cap)
+    try:
+        ids, dists = idx.search(q.cuda(), k, metric)
+        torch.cuda.synchronize()
+        redone, fill = idx.overflow_stats(nq, k, metric)
+        left = idx.overflow_left(nq, k, metric)
+    finally:
+        lpq.set_tuning(lpq.TUNE_PATH, 0)
+        lpq.set_tuning(lpq.TUNE_REGION_CAP, 0)
+    oids, odists = oracle.search_i8(ocodes, oqcodes, k, metric, threads=16)
+    assert np.array_equal(dists.cpu().numpy(), odists)
+    assert np.array_equal(ids.cpu().numpy(), oids)
+    print("flagged:", redone, "left for the generic kernel:", left, "largest region fill:", fill)
+    if region_cap:
+        assert redone > 16 and left > 0, (redone, left, fill)
+    elif path == 0 and nq > 128:
+        assert fill > 0      # the collecting scan ran
+
+
 def test_packed_equals_unpacked_index_of_saturated_codes_and_incremental_add(lpq, oracle):
     w = synth.SKEWED_1M.scaled(n=100_000, nq=48)
     x, q = w.corpus().cuda(), w.queries().cuda()
