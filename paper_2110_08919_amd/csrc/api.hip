@@ -415,7 +415,8 @@ struct Plan {
     int S1 = 0, S2 = 0;     // corpus splits of the seeding pass and of the main pass
     int SEG = 0;            // PLAN_MFMA_REG: segments per split in the seeding pass
     int G = 0;              // PLAN_MFMA_REG: group maxima per query
-    bool rsplit = false;    // PLAN_MFMA_REG: row-split workgroups (few queries)
+    bool rsplit = false;    // PLAN_MFMA_REG, PLAN_MFMA_COLLECT: row-split workgroups (few queries)
+    int rs_waves = 0;       // ... of this many waves (0 when not row-split)
     int merge_group = 0;    // lists merged per workgroup in the first merge pass (0 = single pass)
     int64_t seed_stride = 0;   // seeding pass: one stage every seed_stride rows (systematic sample)
     int seed_stages = 0;       // ... seed_stages of them per split
@@ -526,7 +527,10 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     int64_t qt = (p.mode == PLAN_MFMA_LDS && k > 16) ? 128 : 256;   // queries per workgroup
     int64_t slots_now = slots;
     if (gmode) {
-        p.rsplit = mfma_row_split(nq, idx->d_pad, idx->packed);
+        // (rows of more than 128 bytes: the collecting scan only - the register lists do not fit beside them)
+        const int waves = mfma_row_split_waves(idx->d_pad, idx->packed);
+        p.rsplit = mfma_row_split(nq, idx->d_pad, idx->packed) && (waves == 4 || p.mode == PLAN_MFMA_COLLECT);
+        p.rs_waves = p.rsplit ? waves : 0;
         if (p.mode == PLAN_MFMA_COLLECT && mfma_collect_wide(nq, idx->d_pad) && g_tune[LPQ_TUNE_WAVE_QUERIES] != 64)
             p.wave_queries = 128;
         if (p.mode == PLAN_MFMA_COLLECT && idx->packed)   // the packed scan has one variant per row length
@@ -539,10 +543,10 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
         // group maxima per query: 2 per split and segment (8 when rows are split), at most 2048
         p.S1 = splits_for(seed, tiles_q, min_rows, slots_now, gmode ? (p.rsplit ? 256 : 1024) : merge_max_lists(k));
         if (gmode) {
-            p.SEG = mfma_seed_segments(p.S1, k, p.rsplit);
-            p.G = mfma_seed_groups(p.S1, p.SEG, p.rsplit);
+            p.SEG = mfma_seed_segments(p.S1, k, p.rs_waves);
+            p.G = mfma_seed_groups(p.S1, p.SEG, p.rs_waves);
             // systematic sample: one stage every seed_stride rows, shared out over the S1 splits
-            const int64_t stage_rows = p.rsplit ? 128 : 64;
+            const int64_t stage_rows = p.rsplit ? 32 * p.rs_waves : 64;
             const int64_t stages = seed / stage_rows;
             p.seed_stages = (int)ceil_div(stages, p.S1);
             p.seed_stride = n / ((int64_t)p.seed_stages * p.S1) / 128 * 128;
@@ -573,7 +577,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
         // deals its stages round-robin to the splits); a region holds three times its share, at
         // least 64, which leaves room for bounds several times looser than expected (a corpus stored
         // in sorted order).  Overflow is caught per query and redone exactly.
-        p.SS = mfma_collect_regions(p.S2, p.rsplit);
+        p.SS = mfma_collect_regions(p.S2, p.rs_waves);
         const double per_region = 1.15 * (double)k * (double)n / (double)seed / p.SS;
         p.expect = (int)(per_region * p.SS + 1.0);
         int64_t cs = 64;
@@ -662,6 +666,7 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, const int8_t *qco
     a.work_order = (int)g_tune[LPQ_TUNE_WORK_ORDER];
     a.wave_queries = 64;
     a.rsplit = p.rsplit;
+    a.rs_waves = p.rsplit ? p.rs_waves : 4;
     cand_t *lists1 = reinterpret_cast<cand_t *>(ws + p.off_lists1);
     cand_t *seedlist = reinterpret_cast<cand_t *>(ws + p.off_seedlist);
     cand_t *seeds = reinterpret_cast<cand_t *>(ws + p.off_seeds);

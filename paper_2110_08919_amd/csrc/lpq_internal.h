@@ -110,6 +110,7 @@ struct SearchArgs {
     int k;
     int metric;
     bool rsplit;            // register variant: row-split workgroups (set from mfma_row_split)
+    int rs_waves = 4;       // ... of this many waves (mfma_row_split_waves): a stage holds 32 rows per wave
     int dry_run;            // timing experiments: != 0 never collects a candidate (2..4: ablations)
     int work_order = 0;     // matrix-core kernels: block -> (split, query tile) mapping (0 = built-in)
     int wave_queries = 64;  // collecting mode: queries per wave (64 or 128)
@@ -148,11 +149,12 @@ hipError_t launch_search_mfma_lds(const SearchArgs &a, int64_t row0, int64_t row
                                   cand_t *lists, hipStream_t st);
 // Seeding pass: group maxima gmax[nq_pad][G], G = mfma_seed_groups(S, SEG, rsplit), over the sampled
 // rows (all of them real items), then seeds[q] = bound from the k-th largest group maximum.
-int mfma_seed_segments(int S, int k, bool rsplit);
-int mfma_seed_groups(int S, int SEG, bool rsplit);        // = G, entries per query in gmax
+int mfma_seed_segments(int S, int k, int rs_waves);   // rs_waves: waves of a row-split workgroup, 0 = not row-split
+int mfma_seed_groups(int S, int SEG, int rs_waves);      // = G, entries per query in gmax
 int mfma_queries_per_workgroup(int64_t nq, int d_pad, bool wide = false);   // query tile; wide: 128 queries per wave
 bool mfma_collect_wide(int64_t nq, int d_pad);           // collecting mode may use 128 queries per wave
 bool mfma_row_split(int64_t nq, int d_pad, bool packed = false);   // few queries: waves split rows, share queries
+int mfma_row_split_waves(int d_pad, bool packed);   // 4 on rows of up to 128 bytes, 2 on longer ones (collecting scan and seeding pass only)
 // With stage_stride > 0 (a multiple of 128) the pass is a systematic sample of [row0, row1): one
 // stage (64 rows; 128 in row-split launches) every stage_stride rows, stages_per_split per split.
 // With piece_stride > 0 instead (not for row-split launches; row0 = 0): a finer systematic sample,
@@ -165,7 +167,7 @@ hipError_t launch_seed_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int
 // query's seed is appended to cbuf[(q * SS + region) * Cs + ...], SS = mfma_collect_regions(S, rsplit),
 // and ccnt[q * SS + region] = number offered (entries beyond Cs were dropped).
 bool mfma_collect_supported(int d_pad, int k);
-int mfma_collect_regions(int S, bool rsplit);
+int mfma_collect_regions(int S, int rs_waves);
 hipError_t launch_collect_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S, const cand_t *seeds,
                                cand_t *cbuf, int32_t *ccnt, int Cs, hipStream_t st);
 // Per query: if no region overflowed and at most 4096 candidates were collected, sort them, write

@@ -36,9 +36,10 @@
 // mode that skips query tiles without a flagged query).  With short rows and many queries a wave
 // holds 128 queries (NB = 4 blocks of 32) instead of 64.
 //
-// Row-split launches (RSPLIT, at most 64 queries).  The four waves share the 64 queries and split
-// the rows of a 128-row stage; each wave copies, waits for and reads only its own 32 rows, so there
-// is no workgroup barrier and the launch runs at the speed the corpus streams in.  PACK: the rows
+// Row-split launches (RSPLIT, at most 64 queries).  The four waves (two on rows of more than 128
+// bytes) share the 64 queries and split the rows of a stage, 32 rows per wave; each wave copies,
+// waits for and reads only its own 32 rows, so there is no workgroup barrier and the launch runs at
+// the speed the corpus streams in.  PACK: the rows
 // hold two 4-bit codes per byte and are spread over the operand registers after the LDS read
 // (row-split launches, and the collecting scan and seeding pass of large batches).
 //
@@ -269,7 +270,8 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     // LDS ring depth.  Row-split launches: 3, or 4 for the half-size packed stages (2.5 % faster);
     // rings of 6 and 8 packed stages measured 55 % slower, as deeper rings did for unpacked rows.
     constexpr int NST = ring_depth(KS, RSPLIT, PACK);
-    static_assert(!RSPLIT || ROWB <= 128, "row-split staging is sized for rows of up to 128 bytes");
+    static_assert(!RSPLIT || ROWB <= 128 || (NW == 2 && (KCAP == 0 || SEED)),
+                  "row-split staging: four waves on rows of up to 128 bytes, two on longer ones (no register lists there)");
     constexpr int STAGE_BYTES = RS * SLOTS * 16;
     constexpr int IPW = RS * SLOTS / 64 / NW;   // async copy instructions per wave and stage
     constexpr int AUX_INTS = RS + 4;       // cinit[RS] then parity words
@@ -767,6 +769,7 @@ hipError_t launch_one(const SearchArgs &a, int64_t row0, int64_t row1, int S, Mf
         // queries; large batches: the collecting scan (and its seeding pass), 128 queries per wave
         // on rows of up to 64 bytes, 64 on longer ones
         if (a.rsplit) {
+            if (a.rs_waves != 4) return hipErrorInvalidValue;
             if constexpr (KCAP != 0) return launch_nw<KS, L2, KCAP, SEED, 4, true, 2, true>(a, row0, row1, S, split_rows, o, st);
             return hipErrorInvalidValue;
         }
@@ -782,10 +785,19 @@ hipError_t launch_one(const SearchArgs &a, int64_t row0, int64_t row1, int S, Mf
         return hipErrorInvalidValue;
     }
     if constexpr (KS <= 4) {
-        if (a.rsplit) return launch_nw<KS, L2, KCAP, SEED, 4, true>(a, row0, row1, S, split_rows, o, st);
+        if (a.rsplit) {
+            if (a.rs_waves != 4) return hipErrorInvalidValue;
+            return launch_nw<KS, L2, KCAP, SEED, 4, true>(a, row0, row1, S, split_rows, o, st);
+        }
         if constexpr (KCAP == 0 || SEED) {
             if (a.wave_queries == 128) return launch_nw<KS, L2, KCAP, SEED, 4, false, 4>(a, row0, row1, S, split_rows, o, st);
         }
+    } else if (a.rsplit) {   // rows of 192 or 256 bytes: two waves per workgroup, 64-row stages (collecting scan and seeding pass)
+        if constexpr (KCAP == 0 || SEED) {
+            if (a.rs_waves != 2) return hipErrorInvalidValue;
+            return launch_nw<KS, L2, KCAP, SEED, 2, true>(a, row0, row1, S, split_rows, o, st);
+        }
+        return hipErrorInvalidValue;
     }
     return launch_nw<KS, L2, KCAP, SEED, 4, false>(a, row0, row1, S, split_rows, o, st);
 }
@@ -835,7 +847,9 @@ int mfma_queries_per_workgroup(int64_t nq, int d_pad, bool wide) { return mfma_r
 bool mfma_collect_wide(int64_t nq, int d_pad) { return !mfma_row_split(nq, d_pad) && d_pad <= 128 && nq > 256; }
 
 // Few queries: the waves of a workgroup share them and split the rows instead.
-bool mfma_row_split(int64_t nq, int d_pad, bool packed) { return nq <= 64 && d_pad <= (packed ? 256 : 128); }
+bool mfma_row_split(int64_t nq, int d_pad, bool packed) { (void)packed; return nq <= 64 && d_pad <= 256; }
+
+int mfma_row_split_waves(int d_pad, bool packed) { return (packed ? d_pad / 2 : d_pad) <= 128 ? 4 : 2; }
 
 bool mfma_reg_supported(int d_pad, int k) { return shape_ok(d_pad) && k >= 1 && k <= 16; }
 
@@ -863,13 +877,13 @@ hipError_t launch_collect_mfma(const SearchArgs &a, int64_t row0, int64_t row1, 
     return launch_any(a, row0, row1, S, o, st);
 }
 
-int mfma_collect_regions(int S, bool rsplit) { return S * (rsplit ? 4 : 1); }
+int mfma_collect_regions(int S, int rs_waves) { return S * (rs_waves ? rs_waves : 1); }
 
-int mfma_seed_groups(int S, int SEG, bool rsplit) { return S * SEG * (rsplit ? 8 : 2); }
+int mfma_seed_groups(int S, int SEG, int rs_waves) { return S * SEG * (rs_waves ? 2 * rs_waves : 2); }
 
-int mfma_seed_segments(int S, int k, bool rsplit)
+int mfma_seed_segments(int S, int k, int rs_waves)
 {
-    const int per = rsplit ? 8 : 2;            // groups a split contributes per segment
+    const int per = rs_waves ? 2 * rs_waves : 2;   // groups a split contributes per segment
     int seg = (int)ceil_div(6 * k, per * S);   // >= 6k groups: the k-th largest is then close to
     if (seg < 1) seg = 1;                      // the k-th best item of the seeded rows
     while (per * S * seg > 2048 && seg > 1) --seg;
@@ -894,7 +908,7 @@ hipError_t launch_seed_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int
         o.piece_stride = piece_stride;
         o.piece_stages = piece_stages;
     } else if (stage_stride) {
-        const int rs_rows = a.rsplit ? 128 : 64;
+        const int rs_rows = a.rsplit ? 32 * a.rs_waves : 64;
         if (stages_per_split < 1 || stage_stride < rs_rows || stage_stride % 128) return hipErrorInvalidValue;
         o.stage_stride = stage_stride;
         o.split_stride = stage_stride * stages_per_split;
