@@ -308,8 +308,10 @@ __global__ __launch_bounds__(256) void collect_select_kernel(
 // query are real items, so the k-th best of them bounds the query's final k-th best from above -
 // and far more closely than the seeding pass did, since they all passed its bound.  One workgroup
 // per query: every region gives its first min(count, Cs, maxc / SS) candidates, the workgroup
-// sorts them and writes bounds_out[q] = (key of the k-th best, largest id): items with that key
-// or a smaller one pass.  With fewer than k collected the old bound is kept.  Queries that are
+// sorts them and writes bounds_out[q] = the candidate right after the k-th best in (key, id)
+// order: the k-th best and everything before it pass, so ties of its key with larger ids do not
+// (a region keeps its FIRST arrivals, the lowest ids among equal keys, which is what makes this
+// converge on codes of few bits).  With fewer than k collected the old bound is kept.  Queries that are
 // not flagged get the bound nothing passes (candidate 0), and so does every query when no more
 // than min_flagged are flagged (then the second scan does not run at all).  Also clears *zero_word.
 __global__ __launch_bounds__(256) void collect_refine_kernel(
@@ -342,7 +344,8 @@ __global__ __launch_bounds__(256) void collect_refine_kernel(
     block_bitonic_sort(buf, cap);
     if (tid == 0) {
         const cand_t kth = (k <= cap) ? buf[k - 1] : CAND_NONE;
-        bounds_out[q] = (kth == CAND_NONE) ? bounds_in[q] : make_cand(cand_key(kth), 0xFFFFFFFFu);
+        // the scan passes candidates strictly below its bound: kth itself must pass, later ids with its key need not
+        bounds_out[q] = (kth == CAND_NONE) ? bounds_in[q] : kth + 1;
     }
 }
 
