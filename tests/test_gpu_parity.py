@@ -305,6 +305,41 @@ def test_search_long_lists_on_a_corpus_stored_cluster_by_cluster(lpq, oracle, k,
         assert 0 < redone <= 16 and left == 0, (redone, left, fill)
 
 
+@pytest.mark.parametrize("nq,k", [(16, 10), (700, 10), (300, 32)])
+def test_search_captured_in_a_graph_replays_exactly(lpq, oracle, nq, k):
+    """A search only launches kernels on the caller's stream (no allocation, no host round trip, no
+    memset), so it can be captured in a HIP graph.  Every replay - with new queries in the same
+    buffers, and eager searches between the replays - must equal the oracle."""
+    w = synth.SKEWED_1M.scaled(n=200_000, nq=2 * nq)
+    x, qall = w.corpus(), w.queries()
+    xd = x.cuda()
+    gq = lpq.Quantizer(w.d, 8).calibrate(xd, "minmax", "global")
+    idx = lpq.Index(gq, w.n).add_f32(xd)
+    oq = _oracle_quant(oracle, gq)
+    ocodes = oq.encode(x.numpy())
+    q = qall[:nq].cuda().clone()
+    ids = torch.empty((nq, k), dtype=torch.int32, device="cuda")
+    dists = torch.empty_like(ids)
+    ws = torch.empty(idx.workspace_bytes(nq, k, "l2sq") + 256, dtype=torch.uint8, device="cuda")
+    idx.search(q, k, "l2sq", out=(ids, dists), workspace=ws)      # first launches happen outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        idx.search(q, k, "l2sq", out=(ids, dists), workspace=ws)
+    for rep in range(3):
+        src = qall[:nq] if rep % 2 == 0 else qall[nq:]
+        q.copy_(src.cuda())
+        ids.zero_(); dists.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        oids, odists = oracle.search_i8(ocodes, oq.encode(src.numpy()), k, "l2sq", threads=16)
+        assert np.array_equal(ids.cpu().numpy(), oids), rep
+        assert np.array_equal(dists.cpu().numpy(), odists), rep
+        e_ids, e_dists = idx.search(q, k, "l2sq")                  # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(e_ids, ids) and torch.equal(e_dists, dists)
+
+
 def test_search_collecting_variant_ties_at_the_threshold(lpq, oracle):
     """4-bit codes in 32 dimensions: many items share the threshold distance and all of them are
     collected; the selection must still order by (distance, id)."""
