@@ -124,7 +124,7 @@ int lpq_index_create(lpq_index **out, const lpq_quantizer *q, int64_t capacity);
  * -8 .. 7, so at B = 4 the top code +8 is stored as 7, for items and for queries alike (the
  * way +128 becomes 127 at B = 8); distances and norms are those of the stored codes.
  * Searches (lpq_search, lpq_search_i8) unpack in registers and give bit-identical results to
- * an unpacked index holding the same saturated codes; they take k <= 16.  Up to 128 queries run
+ * an unpacked index holding the same saturated codes; they take k <= 128.  Up to 128 queries run
  * the scan once per 64 queries (the small batches whose time is the corpus read: half the bytes);
  * larger batches take one scan over all queries at about the speed of an unpacked index.
  * lpq_index_data returns the packed rows (*ld_codes = bytes per row); lpq_gather_dist_i8 does

@@ -461,8 +461,12 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     const bool long_lists = coll && k > 10;
     // Packed rows: the row-split register-list kernel (callers tile the queries by 64), or for large
     // batches the collecting scan over all queries at once; the generic kernel on request.
-    const bool packed_batch = idx->packed && coll && nq > PACKED_BATCH_MIN && idx->d_pad >= 96;
-    if (idx->packed) p.mode = want == 1 ? PLAN_GENERIC : (packed_batch ? PLAN_MFMA_COLLECT : PLAN_MFMA_REG);
+    // (lists of more than 16 entries: the collecting scan at every batch size; rows of 32 packed
+    // bytes have no scan over more than 64 queries, their callers tile)
+    const bool packed_batch = idx->packed && coll && idx->d_pad >= 96 && (nq > PACKED_BATCH_MIN || (!regs && nq > 64));
+    const bool packed_collect = packed_batch || (idx->packed && coll && !regs && nq <= 64);
+    if (idx->packed) p.mode = want == 1 ? PLAN_GENERIC : (packed_collect ? PLAN_MFMA_COLLECT
+                                                          : (regs ? PLAN_MFMA_REG : PLAN_GENERIC));
     else if (want == 3 && coll) p.mode = PLAN_MFMA_COLLECT;
     else if (want != 1 && want != 4 && (wide || long_rows || long_lists)) p.mode = PLAN_MFMA_COLLECT;
     else if (want != 1 && regs) p.mode = PLAN_MFMA_REG;
@@ -508,7 +512,8 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     seed = seed / 256 * 256;
     if (seed < 64 * k || seed * 4 > n) seed = 0;
     if (p.mode == PLAN_MFMA_COLLECT && !seed) {   // too few items to sample: exact paths
-        p.mode = (regs && want != 1) ? PLAN_MFMA_REG : (mfma_lds_supported(idx->d_pad, k) ? PLAN_MFMA_LDS : PLAN_GENERIC);
+        p.mode = (regs && want != 1) ? PLAN_MFMA_REG
+                 : (mfma_lds_supported(idx->d_pad, k) && !idx->packed ? PLAN_MFMA_LDS : PLAN_GENERIC);
     }
 
     // lists one merge launch takes: the register-list scan's come out sorted, which allows more of them
@@ -811,7 +816,7 @@ PackedPlan make_packed_plan(const lpq_index *idx, int64_t nq, int k)
     }
     pp.nq_pad = ceil_div(nq, PACKED_TILE) * PACKED_TILE + tail;   // every tile may read a whole padded tile
     const Plan whole = make_plan(idx, nq, k);
-    if (whole.mode == PLAN_MFMA_COLLECT) {   // large batch: one scan over all queries
+    if (whole.mode == PLAN_MFMA_COLLECT && !whole.rsplit) {   // large batch: one scan over all queries
         tile = whole.total;
         if (whole.nq_pad > pp.nq_pad) pp.nq_pad = whole.nq_pad;
     }
@@ -834,7 +839,7 @@ int search_packed(const lpq_index *idx, const PackedPlan &pp, char *ws, int64_t 
                                    metric == LPQ_METRIC_L2SQ, qperm, qadj, st));
     const int emit = metric == LPQ_METRIC_L2SQ ? MODE_I8_L2 : MODE_I8_IP_ADJ;
     const Plan whole = make_plan(idx, nq, k);
-    if (whole.mode == PLAN_MFMA_COLLECT)
+    if (whole.mode == PLAN_MFMA_COLLECT && !whole.rsplit)
         return search_core(idx, whole, ws + pp.off_tile, qperm, qadj, nq, k, metric, emit, ids, dist, st);
     for (int64_t q0 = 0; q0 < nq; q0 += PACKED_TILE) {
         const int64_t nt = nq - q0 < PACKED_TILE ? nq - q0 : PACKED_TILE;

@@ -58,7 +58,7 @@ __host__ __device__ static inline int next_pow2(int v)
 static inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-enum { MAX_K = 1024, MAX_D = 32768, MAX_K_PACKED = 16, MAX_D_PACKED = 256 };
+enum { MAX_K = 1024, MAX_D = 32768, MAX_K_PACKED = 128, MAX_D_PACKED = 256 };
 
 // Per-feature constants on the device: four arrays of d floats, [k | S_b | S_e | m].
 struct QuantParams {

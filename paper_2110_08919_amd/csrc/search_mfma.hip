@@ -765,13 +765,12 @@ hipError_t launch_one(const SearchArgs &a, int64_t row0, int64_t row1, int S, Mf
     const int64_t split_rows = o.split_stride ? o.split_stride_rows : round_up(ceil_div(row1 - row0, S), a.rsplit ? 128 : 64);
     if (!o.split_stride) o.split_stride = split_rows;
     if (a.packed) {
-        // packed rows: row-split launches with register lists (and their seeding pass) for up to 64
-        // queries; large batches: the collecting scan (and its seeding pass), 128 queries per wave
-        // on rows of up to 64 bytes, 64 on longer ones
+        // packed rows: row-split launches (register lists, or the collecting scan for longer lists,
+        // and their seeding pass) for up to 64 queries; large batches: the collecting scan (and its
+        // seeding pass), 128 queries per wave on rows of up to 64 bytes, 64 on longer ones
         if (a.rsplit) {
             if (a.rs_waves != 4) return hipErrorInvalidValue;
-            if constexpr (KCAP != 0) return launch_nw<KS, L2, KCAP, SEED, 4, true, 2, true>(a, row0, row1, S, split_rows, o, st);
-            return hipErrorInvalidValue;
+            return launch_nw<KS, L2, KCAP, SEED, 4, true, 2, true>(a, row0, row1, S, split_rows, o, st);
         }
         if constexpr ((KCAP == 0 || SEED) && KS >= 3) {
             if constexpr (KS <= 4) {

@@ -150,6 +150,41 @@ def test_packed_search_large_batches(lpq, oracle, name, n, nq, k, metric, bits, 
         assert fill > 0      # the collecting scan ran
 
 
+@pytest.mark.parametrize("name,n,nq,k,metric,bits", [
+    ("skewed", 120_000, 5, 17, "l2sq", 4),       # one row-split tile, collecting scan
+    ("skewed", 200_000, 64, 100, "l2sq", 4),
+    ("aniso", 150_000, 100, 32, "ip", 4),        # 65 .. 128 queries: one scan over all of them
+    ("product", 100_000, 300, 128, "ip", 3),     # d = 256, largest k
+    ("tiny", 9_000, 130, 50, "l2sq", 4),         # too few items to sample: generic kernel on packed rows
+])
+def test_packed_search_long_lists(lpq, oracle, name, n, nq, k, metric, bits):
+    """k > 16 on a packed index: the collecting scan at every batch size."""
+    w = BASES[name].scaled(n=n, nq=nq)
+    idx, gq, q, ocodes, oqcodes = _build(lpq, oracle, w, bits, "absmax" if metric == "ip" else "minmax", "global")
+    ids, dists = idx.search(q.cuda(), k, metric)
+    torch.cuda.synchronize()
+    oids, odists = oracle.search_i8(ocodes, oqcodes, k, metric, threads=16)
+    assert np.array_equal(dists.cpu().numpy(), odists)
+    assert np.array_equal(ids.cpu().numpy(), oids)
+
+
+def test_packed_search_long_lists_on_short_rows_in_tiles(lpq, oracle):
+    """d <= 64 (32 packed bytes per row) has no scan over more than 64 queries: tiles of 64, each a
+    row-split collecting scan."""
+    g = torch.Generator().manual_seed(5)
+    n, nq, k, d = 150_000, 150, 40, 50
+    x, q = torch.randn(n, d, generator=g), torch.randn(nq, d, generator=g)
+    gq = lpq.Quantizer(d, 4).calibrate(x.cuda(), "absmax", "global")
+    idx = lpq.Index(gq, n, packed=True).add_f32(x.cuda())
+    oq = _oracle_quant(oracle, gq)
+    ocodes, oqcodes = oracle.nibble_codes(oq.encode(x.numpy())), oracle.nibble_codes(oq.encode(q.numpy()))
+    ids, dists = idx.search(q.cuda(), k, "l2sq")
+    torch.cuda.synchronize()
+    oids, odists = oracle.search_i8(ocodes, oqcodes, k, "l2sq", threads=16)
+    assert np.array_equal(dists.cpu().numpy(), odists)
+    assert np.array_equal(ids.cpu().numpy(), oids)
+
+
 def test_packed_equals_unpacked_index_of_saturated_codes_and_incremental_add(lpq, oracle):
     w = synth.SKEWED_1M.scaled(n=100_000, nq=48)
     x, q = w.corpus().cuda(), w.queries().cuda()
@@ -185,9 +220,9 @@ def test_packed_error_codes(lpq):
     g4 = lpq.Quantizer(w.d, 4).calibrate(x, "minmax", "per_feature")
     idx = lpq.Index(g4, 500, packed=True).add_f32(x)
     with pytest.raises(lpq.LpqError) as e:
-        idx.search(q, 17, "l2sq")
-    assert e.value.code == lpq.ERANGE                     # k beyond the packed scan's lists
-    assert idx.workspace_bytes(4, 17) == 0
+        idx.search(q, 129, "l2sq")
+    assert e.value.code == lpq.ERANGE                     # k beyond what the packed scans collect
+    assert idx.workspace_bytes(4, 129) == 0
     with pytest.raises(lpq.LpqError) as e:
         idx.gather_dist(torch.zeros((4, w.d), dtype=torch.int8, device="cuda"),
                         torch.zeros((4, 3), dtype=torch.int32, device="cuda"))

@@ -36,7 +36,7 @@ def _case(seed):
     mode, arg = MODES[int(r.integers(len(MODES)))]
     scope = str(r.choice(SCOPES))
     path = int(r.choice([0, 0, 1, 2, 3, 4]))
-    packed = bool(bits <= 4 and d <= 256 and k <= 16 and r.random() < 0.7)
+    packed = bool(bits <= 4 and d <= 256 and k <= 128 and r.random() < 0.7)
     kind = str(r.choice(["normal", "offsets", "small_integers"]))
     return dict(seed=seed, d=d, nq=nq, n=n, k=k, bits=bits, metric=metric, mode=mode, arg=arg, scope=scope,
                 path=path, packed=packed, kind=kind)
