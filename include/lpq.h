@@ -127,8 +127,8 @@ int lpq_index_create(lpq_index **out, const lpq_quantizer *q, int64_t capacity);
  * an unpacked index holding the same saturated codes; they take k <= 128.  Up to 128 queries run
  * the scan once per 64 queries (the small batches whose time is the corpus read: half the bytes);
  * larger batches take one scan over all queries at about the speed of an unpacked index.
- * lpq_index_data returns the packed rows (*ld_codes = bytes per row); lpq_gather_dist_i8 does
- * not take a packed index (LPQ_EINVAL).  LPQ_EINVAL: B > 4; LPQ_ERANGE: d > 256. */
+ * lpq_index_data returns the packed rows (*ld_codes = bytes per row); lpq_gather_dist_i8
+ * saturates the query codes the same way.  LPQ_EINVAL: B > 4; LPQ_ERANGE: d > 256. */
 int lpq_index_create_packed(lpq_index **out, const lpq_quantizer *q, int64_t capacity);
 void lpq_index_destroy(lpq_index *idx);
 
@@ -184,7 +184,9 @@ int lpq_search_f32(const float *x_dev, int64_t n, int64_t ldx, const float *q_de
  * call.  qcodes_dev int8 [nq][ld] are codes of the index's quantizer (lpq_encode), ld >= d;
  * ids_dev int32 [nq][m]; dist_dev int32 [nq][m] receives sum (cq - cx)^2 (L2SQ) or
  * sum cq cx (IP).  An id outside [0, size) means "no item" and gives INT32_MAX (L2SQ) /
- * INT32_MIN (IP).  All buffers are the caller's device memory; asynchronous on stream.
+ * INT32_MIN (IP).  On a packed index the distances are those of the stored (saturated) codes
+ * and of the query codes saturated to -8 .. 7.  All buffers are the caller's device memory;
+ * asynchronous on stream.
  * LPQ_EINVAL: null argument, m < 1, ld < d, unknown metric; LPQ_ESTATE: empty index. */
 int lpq_gather_dist_i8(const lpq_index *idx, const int8_t *qcodes_dev, int64_t nq, int64_t ld,
                        const int32_t *ids_dev, int m, int metric, int32_t *dist_dev, void *stream);

@@ -380,11 +380,10 @@ extern "C" int lpq_gather_dist_i8(const lpq_index *idx, const int8_t *qcodes_dev
     if (nq < 0 || m < 1) return fail(LPQ_EINVAL, "nq < 0 or m < 1");
     if (metric != LPQ_METRIC_L2SQ && metric != LPQ_METRIC_IP) return fail(LPQ_EINVAL, "unknown metric %d", metric);
     if (idx->size < 1) return fail(LPQ_ESTATE, "gather on an empty index");
-    if (idx->packed) return fail(LPQ_EINVAL, "gather is not available on a packed index");
     if (nq > 0 && (!qcodes_dev || !ids_dev || !dist_dev)) return fail(LPQ_EINVAL, "null argument");
     if (nq > 0 && ld < idx->d) return fail(LPQ_EINVAL, "ld < d");
     HIP_TRY(launch_gather_dist(idx->codes, idx->norms, idx->size, idx->d, idx->d_pad, qcodes_dev, nq, ld, ids_dev, m,
-                               metric, dist_dev, (hipStream_t)stream));
+                               metric, dist_dev, (hipStream_t)stream, idx->packed));
     return LPQ_OK;
 }
 

@@ -20,14 +20,25 @@ constexpr int GD_ITEMS = 256;   // items of one query per workgroup (8 passes of
 __global__ __launch_bounds__(GD_THREADS) void gather_dist_kernel(
     const int8_t *__restrict__ codes, const int32_t *__restrict__ norms, int64_t n, int d, int d_pad,
     const int8_t *__restrict__ q, int64_t ldq, const int32_t *__restrict__ ids, int m, int blocks_per_query,
-    int metric, int32_t *__restrict__ out)
+    int metric, int32_t *__restrict__ out, bool packed)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     uint4 *qs = reinterpret_cast<uint4 *>(smem);   // the query's codes, zero padded to d_pad
     const int64_t qi = blockIdx.x / blocks_per_query;
     const int j0 = (blockIdx.x % blocks_per_query) * GD_ITEMS;
     int8_t *qb = reinterpret_cast<int8_t *>(smem);
-    for (int c = threadIdx.x; c < d_pad; c += GD_THREADS) qb[c] = (c < d) ? q[qi * ldq + c] : (int8_t)0;
+    // Packed rows (two codes per byte, stored + 8): the query saturates to -8 .. 7 like the items,
+    // and each group of 8 of its codes is stored evens first (0 2 4 6 1 3 5 7), so that the low
+    // nibbles of a packed dword meet one query dword and its high nibbles the next.
+    for (int c = threadIdx.x; c < d_pad; c += GD_THREADS) {
+        int v = (c < d) ? (int)q[qi * ldq + c] : 0;
+        int at = c;
+        if (packed) {
+            v = v < -8 ? -8 : (v > 7 ? 7 : v);
+            at = (c & ~7) + ((c & 1) ? 4 : 0) + ((c & 7) >> 1);
+        }
+        qb[at] = (int8_t)v;
+    }
     __syncthreads();
     const int sub = threadIdx.x & 7, grp = threadIdx.x >> 3;
     const int chunks = d_pad >> 4;
@@ -37,7 +48,29 @@ __global__ __launch_bounds__(GD_THREADS) void gather_dist_kernel(
         const int32_t id = (j < m) ? ids[qi * m + j] : -1;
         const bool live = id >= 0 && (int64_t)id < n;
         int dot = 0, qq = 0;
-        if (live) {
+        if (live && packed) {
+            const uint4 *xr = reinterpret_cast<const uint4 *>(codes + (int64_t)id * (d_pad >> 1));
+            const unsigned mk = 0x0F0F0F0Fu;
+            int sq = 0;
+            for (int c = sub; c < (chunks >> 1); c += 8) {
+                const uint4 xv = xr[c], q0 = qs[2 * c], q1 = qs[2 * c + 1];
+                dot = __builtin_amdgcn_sdot4((int)(xv.x & mk), (int)q0.x, dot, false);
+                dot = __builtin_amdgcn_sdot4((int)((xv.x >> 4) & mk), (int)q0.y, dot, false);
+                dot = __builtin_amdgcn_sdot4((int)(xv.y & mk), (int)q0.z, dot, false);
+                dot = __builtin_amdgcn_sdot4((int)((xv.y >> 4) & mk), (int)q0.w, dot, false);
+                dot = __builtin_amdgcn_sdot4((int)(xv.z & mk), (int)q1.x, dot, false);
+                dot = __builtin_amdgcn_sdot4((int)((xv.z >> 4) & mk), (int)q1.y, dot, false);
+                dot = __builtin_amdgcn_sdot4((int)(xv.w & mk), (int)q1.z, dot, false);
+                dot = __builtin_amdgcn_sdot4((int)((xv.w >> 4) & mk), (int)q1.w, dot, false);
+                const unsigned qv[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    qq = __builtin_amdgcn_sdot4((int)qv[t], (int)qv[t], qq, false);
+                    sq = __builtin_amdgcn_sdot4((int)qv[t], 0x01010101, sq, false);
+                }
+            }
+            dot -= 8 * sq;   // the stored nibbles are code + 8
+        } else if (live) {
             const uint4 *xr = reinterpret_cast<const uint4 *>(codes + (int64_t)id * d_pad);
             for (int c = sub; c < chunks; c += 8) {
                 const uint4 xv = xr[c], qv = qs[c];
@@ -137,13 +170,13 @@ __global__ __launch_bounds__(RR_THREADS) void rerank_f32_kernel(
 
 hipError_t launch_gather_dist(const int8_t *codes, const int32_t *norms, int64_t n, int d, int d_pad, const int8_t *q,
                               int64_t nq, int64_t ldq, const int32_t *ids, int m, int metric, int32_t *out,
-                              hipStream_t st)
+                              hipStream_t st, bool packed)
 {
     if (nq <= 0 || m <= 0) return hipSuccess;
     const int bpq = (int)ceil_div(m, GD_ITEMS);
     if (nq * bpq >= (int64_t(1) << 31)) return hipErrorInvalidValue;
     gather_dist_kernel<<<(unsigned)(nq * bpq), GD_THREADS, (size_t)d_pad, st>>>(codes, norms, n, d, d_pad, q, ldq, ids, m,
-                                                                               bpq, metric, out);
+                                                                               bpq, metric, out, packed);
     return hipGetLastError();
 }
 

@@ -214,7 +214,7 @@ hipError_t launch_merge_groups(const cand_t *lists, int64_t nq, int P, int group
 // ids outside [0, n) give INT32_MAX (L2SQ) / INT32_MIN (IP).
 hipError_t launch_gather_dist(const int8_t *codes, const int32_t *norms, int64_t n, int d, int d_pad, const int8_t *q,
                               int64_t nq, int64_t ldq, const int32_t *ids, int m, int metric, int32_t *out,
-                              hipStream_t st);
+                              hipStream_t st, bool packed = false);   // packed: rows of d_pad / 2 bytes, two codes per byte stored + 8; queries saturate to -8 .. 7
 // Exact distances (binary64 sums) of each query's kc <= 4096 candidates on the fp32 vectors, the k
 // best sorted by (distance, id); ids outside [0, n) are skipped, missing results are id -1.
 hipError_t launch_rerank_f32(const float *x, int64_t n, int64_t ldx, const float *q, int64_t nq, int64_t ldq, int d,

@@ -185,6 +185,22 @@ def test_packed_search_long_lists_on_short_rows_in_tiles(lpq, oracle):
     assert np.array_equal(ids.cpu().numpy(), oids)
 
 
+@pytest.mark.parametrize("name,n,nq,m,metric,bits", [
+    ("skewed", 50_000, 37, 100, "l2sq", 4), ("aniso", 20_000, 64, 7, "ip", 4), ("product", 9_000, 5, 300, "l2sq", 3),
+    ("scaled", 30_000, 20, 33, "ip", 4)])
+def test_packed_gather_distances_bit_exact(lpq, oracle, name, n, nq, m, metric, bits):
+    """Distances to listed items on a packed index: those of the stored nibble codes and of the
+    query codes saturated the same way (handed in unsaturated), including absent ids."""
+    w = BASES[name].scaled(n=n, nq=nq)
+    idx, gq, q, ocodes, oqcodes = _build(lpq, oracle, w, bits, "absmax" if metric == "ip" else "minmax", "per_feature")
+    r = np.random.default_rng(n + m)
+    ids = r.integers(0, n, size=(nq, m), dtype=np.int32)
+    ids[0, 0], ids[-1, -1] = -1, n            # "no item"
+    raw_q = _oracle_quant(oracle, gq).encode(q.numpy())
+    got = idx.gather_dist(torch.from_numpy(raw_q).cuda(), torch.from_numpy(ids).cuda(), metric).cpu().numpy()
+    assert np.array_equal(got, oracle.gather_dist(ocodes, oqcodes, np.where(ids >= n, -1, ids), metric))
+
+
 def test_packed_equals_unpacked_index_of_saturated_codes_and_incremental_add(lpq, oracle):
     w = synth.SKEWED_1M.scaled(n=100_000, nq=48)
     x, q = w.corpus().cuda(), w.queries().cuda()
@@ -223,7 +239,3 @@ def test_packed_error_codes(lpq):
         idx.search(q, 129, "l2sq")
     assert e.value.code == lpq.ERANGE                     # k beyond what the packed scans collect
     assert idx.workspace_bytes(4, 129) == 0
-    with pytest.raises(lpq.LpqError) as e:
-        idx.gather_dist(torch.zeros((4, w.d), dtype=torch.int8, device="cuda"),
-                        torch.zeros((4, 3), dtype=torch.int32, device="cuda"))
-    assert e.value.code == lpq.EINVAL
