@@ -461,20 +461,14 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
         }                                                                                               \
     } while (0)
 
-    // Contraction of one block against the wave's 64 queries, then the filter epilogue.
-#define LPQ_BLOCK(TT, BLK, AREG, CREG, PREG)                                                            \
+    // Filter epilogue of one block of 32 queries x 32 rows (accumulators VEC).
+#define LPQ_EPI(VEC, NBI, ROWBASE, PWORD)                                                               \
     do {                                                                                                \
-        v16i acc[NB];                                                                                   \
-        _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                               \
-            _Pragma("unroll") for (int nb = 0; nb < NB; ++nb)                                           \
-                acc[nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(AREG[ks], B[nb][ks], ks == 0 ? CREG : acc[nb], 0, 0, 0); \
-        const int rowbase = (int)(rs + (int64_t)(TT) * sstride + (BLK) * 32);                           \
-        _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) {                                             \
-            const v16i v = acc[nb];                                                                     \
-            if (SEED && GR == 16) {                                                                     \
-                _Pragma("unroll") for (int r = 0; r < GR; ++r) gm[nb][r] = max(gm[nb][r], v[r]);        \
-                continue;                                                                               \
-            }                                                                                           \
+        const int nb = (NBI);                                                                           \
+        const v16i v = (VEC);                                                                           \
+        if (SEED && GR == 16) {                                                                         \
+            _Pragma("unroll") for (int r = 0; r < GR; ++r) gm[nb][r] = max(gm[nb][r], v[r]);            \
+        } else {                                                                                        \
             int m = max(max(v[0], v[1]), v[2]);                                                         \
             m = max(max(m, v[3]), v[4]);                                                                \
             m = max(max(m, v[5]), v[6]);                                                                \
@@ -485,31 +479,65 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
             m = max(m, v[15]);                                                                          \
             if (SEED) {                                                                                 \
                 gm[nb][0] = max(gm[nb][0], m);                                                          \
-                continue;                                                                               \
-            }                                                                                           \
-            bool trip = m >= thr[nb];                                                                   \
-            unsigned long long mask = __ballot(trip);                                                   \
-            if (mask) {                                                                                 \
-                if (qcnt + __popcll(mask) > QCAP) { /* no room: this wave drains alone */               \
-                    if (a.dry_run < 5) drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs); \
-                    qcnt = 0;                                                                           \
-                    _Pragma("unroll") for (int j = 0; j < NB; ++j) thr[j] = w.thrE[j * 32 + col];       \
-                    trip = m >= thr[nb];                                                                \
-                    mask = __ballot(trip);                                                              \
-                }                                                                                       \
+            } else {                                                                                    \
+                bool trip = m >= thr[nb];                                                               \
+                unsigned long long mask = __ballot(trip);                                               \
                 if (mask) {                                                                             \
-                    const int below = __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),                 \
-                                                                __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u)); \
-                    if (trip && a.dry_run != 5) {   /* 5: trips are counted but nothing is stored */    \
-                        const int slot = qcnt + below;                                                  \
-                        v4i *dst_ = reinterpret_cast<v4i *>(w.qvals + slot * 16);                       \
-                        _Pragma("unroll") for (int g = 0; g < 4; ++g)                                   \
-                            dst_[g] = v4i{v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};          \
-                        w.qmeta[slot] = v4i{rowbase, (int)PREG, (nb * 32 + col) | (half << 8), 0};      \
+                    if (qcnt + __popcll(mask) > QCAP) { /* no room: this wave drains alone */           \
+                        if (a.dry_run < 5) drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs); \
+                        qcnt = 0;                                                                       \
+                        _Pragma("unroll") for (int j = 0; j < NB; ++j) thr[j] = w.thrE[j * 32 + col];   \
+                        trip = m >= thr[nb];                                                            \
+                        mask = __ballot(trip);                                                          \
                     }                                                                                   \
-                    qcnt += __popcll(mask);                                                             \
+                    if (mask) {                                                                         \
+                        const int below = __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),             \
+                                                                    __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u)); \
+                        if (trip && a.dry_run != 5) {                                                   \
+                            const int slot = qcnt + below;                                              \
+                            v4i *dst_ = reinterpret_cast<v4i *>(w.qvals + slot * 16);                   \
+                            _Pragma("unroll") for (int g = 0; g < 4; ++g)                               \
+                                dst_[g] = v4i{v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};      \
+                            w.qmeta[slot] = v4i{(ROWBASE), (int)(PWORD), (nb * 32 + col) | (half << 8), 0}; \
+                        }                                                                               \
+                        qcnt += __popcll(mask);                                                         \
+                    }                                                                                   \
                 }                                                                                       \
             }                                                                                           \
+        }                                                                                               \
+    } while (0)
+
+#define LPQ_CHAIN(NBI, AREG, CREG)                                                                      \
+    _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                                   \
+        acc[NBI] = __builtin_amdgcn_mfma_i32_32x32x32_i8(AREG[ks], B[NBI][ks], ks == 0 ? CREG : acc[NBI], 0, 0, 0)
+
+    // Order of the contraction and of the filter epilogue.  Each block of 32 queries gets its KS
+    // matrix instructions as one chain (dependent instructions of a chain issue back to back), and
+    // the epilogue of a block is placed one chain later, so that its vector instructions run while
+    // the next chain is in the matrix core; the last block's accumulators are carried over and
+    // tested after the first chain of the NEXT 32-row block.  Against k-step-major order with the
+    // four epilogues at the end this measured 5.4 % faster on the benchmark workload (1.347 ->
+    // 1.274 ms per 10 000 queries) and needs 29 fewer registers (accumulators live shorter).  The
+    // seeding pass tests the last block at once: its segment maxima are flushed at stage boundaries.
+    v16i carry_acc = {};
+    int carry_rowbase = 0;
+    unsigned carry_p = 0;
+    bool have_carry = false;
+#define LPQ_BLOCK(TT, BLK, AREG, CREG, PREG)                                                            \
+    do {                                                                                                \
+        v16i acc[NB];                                                                                   \
+        const unsigned PREG_ = (PREG);                                                                  \
+        const int rowbase = (int)(rs + (int64_t)(TT) * sstride + (BLK) * 32);                           \
+        LPQ_CHAIN(0, AREG, CREG);                                                                       \
+        if (have_carry) LPQ_EPI(carry_acc, NB - 1, carry_rowbase, carry_p);                             \
+        _Pragma("unroll") for (int nbi = 1; nbi < NB; ++nbi) {                                          \
+            LPQ_CHAIN(nbi, AREG, CREG);                                                                 \
+            LPQ_EPI(acc[nbi - 1], nbi - 1, rowbase, PREG_);                                             \
+        }                                                                                               \
+        if (SEED) {                                                                                     \
+            LPQ_EPI(acc[NB - 1], NB - 1, rowbase, PREG_);                                               \
+        } else {                                                                                        \
+            carry_acc = acc[NB - 1]; carry_rowbase = rowbase; carry_p = PREG_; have_carry = true;       \
         }                                                                                               \
     } while (0)
 
@@ -627,7 +655,10 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
             }
         }
     }
+    if (!SEED && have_carry) LPQ_EPI(carry_acc, NB - 1, carry_rowbase, carry_p);
 #undef LPQ_ISSUE
+#undef LPQ_EPI
+#undef LPQ_CHAIN
 #undef LPQ_LOAD_BLOCK
 #undef LPQ_BLOCK
 #undef LPQ_FLUSH_SEGMENT
