@@ -233,7 +233,7 @@ __device__ __forceinline__ void drain_queue(const WaveQ &w, int qcnt, int64_t ro
     }
 }
 
-constexpr bool big_stage(int kcap, bool seed, bool rsplit, int nb, bool pack) { return kcap == 0 && !seed && !rsplit && nb == 4 && !pack; }
+constexpr bool big_stage(int kcap, bool seed, bool rsplit, int nb, bool pack, int ks = 4) { return !seed && !rsplit && !pack && ks <= 4; }
 constexpr int ring_depth(int ks, bool rsplit, bool pack, bool big = false) { return big ? 2 : (rsplit ? (pack ? 4 : 3) : (ks <= 4 ? 4 : 3)); }
 
 template <int KS, bool L2, int KCAP, bool SEED, int NW, bool RSPLIT, int NB, bool PACK>
@@ -267,11 +267,13 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     constexpr int CPR = PACK ? KS : 2 * KS;   // 16-byte chunks per corpus row
     constexpr int ROWB = 16 * CPR;            // bytes per corpus row
     constexpr int SLOTS = CPR <= 2 ? 2 : (CPR <= 4 ? 4 : (CPR <= 8 ? 8 : 16));  // LDS slots per row
-    // The collecting scan of large batches takes stages of 128 rows through a two-deep ring (the
-    // same 32 KB of LDS as four stages of 64): half as many workgroup barriers and copy waits per
-    // row.  Measured on the benchmark workload: 1.283 -> 1.171 ms per 10 000 queries (k = 100:
-    // 2.06 -> 1.82; 10M x 96: 10.0 -> 8.7 ms).
-    constexpr bool BIG = big_stage(KCAP, SEED, RSPLIT, NB, PACK);
+    // Scans of rows of up to 128 bytes whose waves share a stage (all but the row-split launches,
+    // the seeding pass and packed rows) take stages of 128 rows through a two-deep ring (the same
+    // 32 KB of LDS as four stages of 64): half as many workgroup barriers and copy waits per row.
+    // Measured on the benchmark workload: 1.283 -> 1.171 ms per 10 000 queries (k = 100: 2.06 ->
+    // 1.82; 10M x 96: 10.0 -> 8.7 ms; 256 queries on 10M x 96: 0.394 -> 0.333 ms).  Longer rows
+    // would need 64 KB for such a ring, which no longer fits two workgroups per CU.
+    constexpr bool BIG = big_stage(KCAP, SEED, RSPLIT, NB, PACK, KS);
     constexpr int RS = RSPLIT ? 32 * NW : (BIG ? 128 : 64);   // corpus rows per stage
     // LDS ring depth.  Row-split launches: 3, or 4 for the half-size packed stages (2.5 % faster);
     // rings of 6 and 8 packed stages measured 55 % slower, as deeper rings did for unpacked rows.
@@ -785,7 +787,7 @@ template <int KS, bool L2, int KCAP, bool SEED, int NW, bool RSPLIT, int NB = 2,
 hipError_t launch_nw(const SearchArgs &a, int64_t row0, int64_t row1, int S, int64_t split_rows, MfmaIo o, hipStream_t st)
 {
     const int qtiles = (int)ceil_div(a.nq, RSPLIT ? NQW : NW * NB * 32);
-    const size_t lds = lds_bytes(KS, SEED, NW, RSPLIT, NB, PACK, big_stage(KCAP, SEED, RSPLIT, NB, PACK));
+    const size_t lds = lds_bytes(KS, SEED, NW, RSPLIT, NB, PACK, big_stage(KCAP, SEED, RSPLIT, NB, PACK, KS));
     auto kern = search_mfma_kernel<KS, L2, KCAP, SEED, NW, RSPLIT, NB, PACK>;
     static bool attr_set = false;  // per instantiation
     if (!attr_set) {
@@ -805,7 +807,7 @@ template <int KS, bool L2, int KCAP, bool SEED>
 hipError_t launch_one(const SearchArgs &a, int64_t row0, int64_t row1, int S, MfmaIo o, hipStream_t st)
 {
     // rows of a split: a whole number of stages; splits follow each other unless a stride is given
-    const int64_t split_rows = o.split_stride ? o.split_stride_rows : round_up(ceil_div(row1 - row0, S), a.rsplit ? 128 : 64);
+    const int64_t split_rows = o.split_stride ? o.split_stride_rows : round_up(ceil_div(row1 - row0, S), 128);
     if (!o.split_stride) o.split_stride = split_rows;
     if (a.packed) {
         // packed rows: row-split launches (register lists, or the collecting scan for longer lists,
