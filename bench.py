@@ -23,7 +23,7 @@ PEAK_HBM = 8.0e12           # MI355X HBM3E, B/s
 # HBM bytes of one launch of the main scan kernel on the default workload, from the rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/search_mfma_kernel_skewed_int_1m_x128_pmc.txt
 # (FETCH_SIZE scaled by 2.000, WRITE_SIZE by 1.000 against device copies of known size in the same run).
-TRAFFIC_BYTES_DEFAULT_WORKLOAD = 244.5e6
+TRAFFIC_BYTES_DEFAULT_WORKLOAD = 264.0e6
 
 
 def cpu_baseline(oracle, x_host, q_host, params, k, metric, gpu_ids, gpu_dists, sample, bits=8, packed=False):
