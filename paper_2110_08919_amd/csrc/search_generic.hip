@@ -342,11 +342,39 @@ __global__ __launch_bounds__(256) void collect_refine_kernel(
     }
     __syncthreads();
     block_bitonic_sort(buf, cap);
-    if (tid == 0) {
-        const cand_t kth = (k <= cap) ? buf[k - 1] : CAND_NONE;
-        // the scan passes candidates strictly below its bound: kth itself must pass, later ids with its key need not
-        bounds_out[q] = (kth == CAND_NONE) ? bounds_in[q] : kth + 1;
+    cand_t kth = (k <= cap) ? buf[k - 1] : CAND_NONE;   // the same value in every thread
+    __syncthreads();
+    // Second pass when the regions hold more than the sort does (per < Cs): every collected
+    // candidate that is no worse than that k-th best goes into the buffer - about k Cs / per of
+    // them - and the k-th best of ALL collected candidates comes out.  (If even those do not fit,
+    // the first estimate stands: it is a valid bound either way.)
+    if (per < Cs && kth != CAND_NONE) {
+        __shared__ int s_n;
+        if (tid == 0) s_n = 0;
+        __syncthreads();
+        for (int r = 0; r < SS; ++r) {
+            int cnt = ccnt[q * SS + r];
+            cnt = cnt > Cs ? Cs : cnt;
+            for (int j = tid; j < cnt; j += 256) {
+                const cand_t c = cbuf[((size_t)q * SS + r) * Cs + j];
+                if (c <= kth) {
+                    const int at = atomicAdd(&s_n, 1);
+                    if (at < maxc) buf[at] = c;
+                }
+            }
+        }
+        __syncthreads();
+        const int m = s_n;
+        if (m >= k && m <= maxc) {
+            const int cap2 = next_pow2(m < 2 ? 2 : m);
+            for (int i = m + tid; i < cap2; i += 256) buf[i] = CAND_NONE;
+            __syncthreads();
+            block_bitonic_sort(buf, cap2);
+            kth = buf[k - 1];
+        }
     }
+    // the scan passes candidates strictly below its bound: kth itself must pass, later ids with its key need not
+    if (tid == 0) bounds_out[q] = (kth == CAND_NONE) ? bounds_in[q] : kth + 1;
 }
 
 // Merge of lists that are each sorted ascending, for small k and many lists: one workgroup per

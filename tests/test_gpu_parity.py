@@ -269,8 +269,8 @@ def test_search_long_lists_on_a_corpus_stored_cluster_by_cluster(lpq, oracle, k,
                                                                  expect):
     """k > 16 on the cluster-by-cluster corpus: a sample far too small (forced) gives loose bounds
     there and most queries overflow their regions.  More than 16 of them go through further
-    rounds of the scan with bounds from what the round before collected ("second": some to nearly
-    all succeed there, the rest ends in the generic kernel); regions of two candidates (forced) overflow in every round and everything ends
+    rounds of the scan with bounds from what the round before collected ("second": nearly all
+    succeed there); regions of two candidates (forced) overflow in every round and everything ends
     in the generic kernel ("generic"); 16 or fewer go to the generic kernel at once ("few")."""
     w = synth.SKEWED_1M.scaled(n=250_000, nq=nq)
     g = torch.Generator().manual_seed(clusters + k)
@@ -297,8 +297,8 @@ def test_search_long_lists_on_a_corpus_stored_cluster_by_cluster(lpq, oracle, k,
     assert np.array_equal(dists.cpu().numpy(), odists)
     assert np.array_equal(ids.cpu().numpy(), oids)
     print("flagged in the first round:", redone, "left after the last:", left, "largest region fill:", fill)
-    if expect == "second":     # (how many succeed depends on how the forced bound falls: all that is asked is progress)
-        assert redone > 16 and left <= redone, (redone, left, fill)
+    if expect == "second":
+        assert redone > 16 and left < redone // 4, (redone, left, fill)
     elif expect == "generic":
         assert redone > 16 and left == redone, (redone, left, fill)
     elif expect == "few":
