@@ -3,11 +3,15 @@
 //
 // Work split.  A workgroup of 4 waves owns one query tile (256 queries, 64 per wave) and one
 // corpus split.  Each wave keeps the codes of its 64 queries in registers for the whole
-// kernel (B operands); corpus rows stream through an LDS ring of NSTG stages shared by the
-// four waves (A operands).  The ring is filled by asynchronous global->LDS loads
-// (global_load_lds_dwordx4) issued NSTG-1 stages ahead; rows sit in LDS row-major with an XOR
-// swizzle of their 16-byte chunks, which keeps the global side fully coalesced and the
-// ds_read_b128 of the A operands free of bank conflicts.
+// kernel (B operands); corpus rows stream through an LDS ring of NST stages shared by the
+// four waves (A operands): two stages of 128 rows for rows of up to 128 bytes, three or four of
+// 64 rows otherwise.  The ring is filled by asynchronous global->LDS loads
+// (global_load_lds_dwordx4) issued NST-1 stages ahead, one workgroup barrier per stage; rows sit
+// in LDS row-major with an XOR swizzle of their 16-byte chunks, which keeps the global side fully
+// coalesced and the ds_read_b128 of the A operands free of bank conflicts.  Inside a 32-row block
+// each block of 32 queries gets its matrix instructions as one chain, and the filter epilogue of
+// a block runs one chain later (the last one after the first chain of the next row block), so the
+// epilogue issues while the matrix core is busy.
 //
 // The corpus is the M side on purpose: the 16 accumulators of a lane then belong to ONE
 // query (column = lane % 32) and 16 different items, so the common-case epilogue is a max
@@ -39,17 +43,17 @@
 // Row-split launches (RSPLIT, at most 64 queries).  The four waves (two on rows of more than 128
 // bytes) share the 64 queries and split the rows of a stage, 32 rows per wave; each wave copies,
 // waits for and reads only its own 32 rows, so there is no workgroup barrier and the launch runs at
-// the speed the corpus streams in.  PACK: the rows
-// hold two 4-bit codes per byte and are spread over the operand registers after the LDS read
-// (row-split launches, and the collecting scan and seeding pass of large batches).
+// the speed the corpus streams in.  PACK: the rows hold two 4-bit codes per byte and are spread over
+// the operand registers after the LDS read (row-split launches, and the collecting scan and seeding
+// pass of large batches).
 //
 // Seeding pass (SEED = true).  The same pipeline with collection switched off: every lane
 // only tracks the maximum E it has seen per segment of its split.  Each (segment, lane half)
 // is a group of items disjoint from the others, so the k-th largest group maximum of a query
 // is a value that at least k items reach: an upper bound on the k-th best key that costs
 // nothing but the contraction itself.  The main pass starts from it.  The pass reads a systematic
-// sample of the corpus: whole stages at a stride, or (k <= 16) runs of 8 rows gathered from places
-// far apart, so that rows stored next to each other fall into different groups.
+// sample of the corpus: whole stages at a stride, or runs of 8 rows gathered from places far
+// apart, so that rows stored next to each other fall into different groups.
 #include <type_traits>
 
 #include "mfma_common.h"
