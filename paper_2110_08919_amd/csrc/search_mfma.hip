@@ -4,7 +4,7 @@
 // Work split.  A workgroup of 4 waves owns one query tile (256 queries, 64 per wave) and one
 // corpus split.  Each wave keeps the codes of its 64 queries in registers for the whole
 // kernel (B operands); corpus rows stream through an LDS ring of NST stages shared by the
-// four waves (A operands): two stages of 128 rows for rows of up to 128 bytes, three or four of
+// four waves (A operands): two stages of 128 rows for rows of up to 128 bytes, two or four of
 // 64 rows otherwise.  The ring is filled by asynchronous global->LDS loads
 // (global_load_lds_dwordx4) issued NST-1 stages ahead, one workgroup barrier per stage; rows sit
 // in LDS row-major with an XOR swizzle of their 16-byte chunks, which keeps the global side fully
@@ -238,7 +238,7 @@ __device__ __forceinline__ void drain_queue(const WaveQ &w, int qcnt, int64_t ro
 }
 
 constexpr bool big_stage(int kcap, bool seed, bool rsplit, int nb, bool pack, int ks = 4) { return !seed && !rsplit && !pack && ks <= 4; }
-constexpr int ring_depth(int ks, bool rsplit, bool pack, bool big = false) { return big ? 2 : (rsplit ? (pack ? 4 : 3) : (ks <= 4 ? 4 : 3)); }
+constexpr int ring_depth(int ks, bool rsplit, bool pack, bool big = false) { return big ? 2 : (rsplit ? (pack ? 4 : 3) : (ks <= 4 ? 4 : 2)); }
 
 template <int KS, bool L2, int KCAP, bool SEED, int NW, bool RSPLIT, int NB, bool PACK>
 __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
@@ -281,6 +281,9 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     constexpr int RS = RSPLIT ? 32 * NW : (BIG ? 128 : 64);   // corpus rows per stage
     // LDS ring depth.  Row-split launches: 3, or 4 for the half-size packed stages (2.5 % faster);
     // rings of 6 and 8 packed stages measured 55 % slower, as deeper rings did for unpacked rows.
+    // Shared stages: 2 for the 128-row stages and for rows of more than 128 bytes (3 measured 36 %
+    // and 1.8 % slower there), 4 for the 64-row stages of the seeding pass on short rows, whose
+    // stages are gathered from far apart and need the lead (3: 1.5 % slower, 2: 4 %).
     constexpr int NST = ring_depth(KS, RSPLIT, PACK, BIG);
     static_assert(!RSPLIT || ROWB <= 128 || (NW == 2 && (KCAP == 0 || SEED)),
                   "row-split staging: four waves on rows of up to 128 bytes, two on longer ones (no register lists there)");
