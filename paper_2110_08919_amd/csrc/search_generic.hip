@@ -230,6 +230,106 @@ __global__ __launch_bounds__(256) void collect_select_wave_kernel(
     if (lane == 0) over[q] = 0;
 }
 
+// 64-bit value of lane `src` (any lane), through two 32-bit shuffles.
+__device__ __forceinline__ cand_t shfl_u64(cand_t v, int src)
+{
+    const unsigned lo = (unsigned)__shfl((int)(uint32_t)v, src, 64), hi = (unsigned)__shfl((int)(uint32_t)(v >> 32), src, 64);
+    return ((cand_t)hi << 32) | lo;
+}
+
+// Ascending bitonic sort of 512 candidates held 8 per lane by one wave, element e = 8 * lane + slot.
+// Strides 1, 2, 4 exchange registers of a lane, larger strides exchange with lane ^ (stride / 8).
+__device__ __forceinline__ void wave_sort512(cand_t (&v)[8], int lane)
+{
+#pragma unroll
+    for (int size = 2; size <= 512; size <<= 1) {
+#pragma unroll
+        for (int stride = size >> 1; stride >= 1; stride >>= 1) {
+            if (stride >= 8) {
+                const int lx = stride >> 3;
+                const bool up = ((lane * 8) & size) == 0;          // this run of `size` elements sorts ascending
+                const bool low = (lane & lx) == 0;                 // this lane holds the lower element of each pair
+                const bool take_min = up == low;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const cand_t o = shfl_u64(v[j], lane ^ lx);
+                    v[j] = take_min ? (o < v[j] ? o : v[j]) : (o > v[j] ? o : v[j]);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    if ((j & stride) == 0) {
+                        const bool up = ((lane * 8 + j) & size) == 0;
+                        const cand_t a = v[j], b = v[j | stride];
+                        const bool swap = up ? (b < a) : (a < b);
+                        v[j] = swap ? b : a;
+                        v[j | stride] = swap ? a : b;
+                    }
+                }
+            }
+        }
+    }
+}
+
+// Last step of the collecting scan for k <= 128 and at most 64 regions, one WAVE per query and no
+// LDS: lane r holds the count of region r; the wave loads up to 512 candidates (8 per lane, each
+// found by a search over the prefix counts), sorts them in registers and keeps the best 128 in its
+// first 16 lanes; further candidates come in 384 at a time through the other 48 lanes.  Any number
+// of candidates the regions hold is handled; a query with an overflowed region or fewer than k
+// candidates is flagged in over[] instead.
+__global__ __launch_bounds__(256) void collect_select_sort_kernel(
+    const cand_t *__restrict__ cbuf, const int32_t *__restrict__ ccnt, int64_t nq, int SS, int Cs, int k,
+    int32_t *__restrict__ over, int32_t *__restrict__ qlist, int32_t *__restrict__ qcount,
+    int32_t *__restrict__ ids, int32_t *__restrict__ dists, const int32_t *__restrict__ qnorms, int metric)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t q = (int64_t)blockIdx.x * 4 + wave;
+    if (q >= nq) return;                                   // wave-uniform
+    const int c = (lane < SS) ? ccnt[q * SS + lane] : 0;
+    const bool bad = c > Cs || c < 0;
+    int incl = bad ? 0 : c;                                // inclusive prefix sum of the counts over the lanes
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += t;
+    }
+    const int total = __shfl(incl, 63, 64);
+    if (__ballot(bad) || total < k) {
+        if (lane == 0) { over[q] = 1; qlist[atomicAdd(qcount, 1)] = (int32_t)q; }
+        return;
+    }
+    const int excl = incl - c;                             // index of the first candidate of this lane's region
+    const cand_t *base = cbuf + (size_t)q * SS * Cs;
+    // candidate number i of the query sits in the first region whose inclusive count exceeds i
+    auto fetch = [&](int i) -> cand_t {
+        int r = 0;
+#pragma unroll
+        for (int step = 32; step >= 1; step >>= 1)
+            if (__shfl(incl, r + step - 1, 64) <= i) r += step;
+        r = r > 63 ? 63 : r;
+        const int first = __shfl(excl, r, 64);
+        return i < total ? base[(size_t)r * Cs + (i - first)] : CAND_NONE;
+    };
+    cand_t v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = fetch(j * 64 + lane);
+    wave_sort512(v, lane);
+    for (int done = 512; done < total; done += 384) {      // wave-uniform: the best 128 stay in lanes 0 .. 15
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const cand_t n = fetch(done + j * 48 + (lane - 16));   // (every lane takes part in the shuffles)
+            if (lane >= 16) v[j] = n;
+        }
+        wave_sort512(v, lane);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int e = lane * 8 + j;
+        if (e < k) emit_result(v[j], q * k + e, q, ids, dists, qnorms, metric);
+    }
+    if (lane == 0) over[q] = 0;
+}
+
 // Last step of the collecting scan, one workgroup per query: gather the query's regions into LDS,
 // sort, write the k best.  A query with an overflowed region, more than `maxc` candidates or fewer
 // than k is flagged in over[] instead and left to the generic kernel.
@@ -509,6 +609,11 @@ hipError_t launch_collect_select(const cand_t *cbuf, const int32_t *ccnt, int64_
     if (SS < 1 || SS > 2048 || k > maxc) return hipErrorInvalidValue;
     if (!only && expected_candidates > 0 && expected_candidates <= 256 && SS <= 64 && k <= 32) {
         collect_select_wave_kernel<<<(unsigned)ceil_div(nq, (int64_t)4), 256, 0, st>>>(cbuf, ccnt, nq, SS, Cs, k, over, qlist,
+                                                                                 qcount, ids, dists, qnorms, metric);
+        return hipGetLastError();
+    }
+    if (!only && SS <= 64 && k <= 128) {   // one wave per query, sorted in registers
+        collect_select_sort_kernel<<<(unsigned)ceil_div(nq, (int64_t)4), 256, 0, st>>>(cbuf, ccnt, nq, SS, Cs, k, over, qlist,
                                                                                  qcount, ids, dists, qnorms, metric);
         return hipGetLastError();
     }
