@@ -3,6 +3,8 @@
 // beat the running k-th best in an LDS buffer and compacts the buffer by a bitonic sort
 // whenever it could overflow.  It is the fallback for shapes the matrix-core kernel does
 // not take and an independent second implementation of the same result.
+#include <type_traits>
+
 #include "block_select.h"
 #include "lpq_internal.h"
 #include "wave_ops.h"
@@ -237,29 +239,30 @@ __device__ __forceinline__ cand_t shfl_u64(cand_t v, int src)
     return ((cand_t)hi << 32) | lo;
 }
 
-// Ascending bitonic sort of 512 candidates held 8 per lane by one wave, element e = 8 * lane + slot.
-// Strides 1, 2, 4 exchange registers of a lane, larger strides exchange with lane ^ (stride / 8).
-__device__ __forceinline__ void wave_sort512(cand_t (&v)[8], int lane)
+// Ascending bitonic sort of 64 E candidates held E per lane by one wave, element e = E * lane + slot.
+// Strides below E exchange registers of a lane, larger strides exchange with lane ^ (stride / E).
+template <int E>
+__device__ __forceinline__ void wave_sort(cand_t (&v)[E], int lane)
 {
 #pragma unroll
-    for (int size = 2; size <= 512; size <<= 1) {
+    for (int size = 2; size <= 64 * E; size <<= 1) {
 #pragma unroll
         for (int stride = size >> 1; stride >= 1; stride >>= 1) {
-            if (stride >= 8) {
-                const int lx = stride >> 3;
-                const bool up = ((lane * 8) & size) == 0;          // this run of `size` elements sorts ascending
+            if (stride >= E) {
+                const int lx = stride / E;
+                const bool up = ((lane * E) & size) == 0;          // this run of `size` elements sorts ascending
                 const bool low = (lane & lx) == 0;                 // this lane holds the lower element of each pair
                 const bool take_min = up == low;
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
+                for (int j = 0; j < E; ++j) {
                     const cand_t o = shfl_u64(v[j], lane ^ lx);
                     v[j] = take_min ? (o < v[j] ? o : v[j]) : (o > v[j] ? o : v[j]);
                 }
             } else {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
+                for (int j = 0; j < E; ++j) {
                     if ((j & stride) == 0) {
-                        const bool up = ((lane * 8 + j) & size) == 0;
+                        const bool up = ((lane * E + j) & size) == 0;
                         const cand_t a = v[j], b = v[j | stride];
                         const bool swap = up ? (b < a) : (a < b);
                         v[j] = swap ? b : a;
@@ -272,9 +275,9 @@ __device__ __forceinline__ void wave_sort512(cand_t (&v)[8], int lane)
 }
 
 // Last step of the collecting scan for k <= 128 and at most 64 regions, one WAVE per query and no
-// LDS: lane r holds the count of region r; the wave loads up to 512 candidates (8 per lane, each
-// found by a search over the prefix counts), sorts them in registers and keeps the best 128 in its
-// first 16 lanes; further candidates come in 384 at a time through the other 48 lanes.  Any number
+// LDS: lane r holds the count of region r; the wave loads up to 512 candidates (2, 4 or 8 per lane
+// as needed, each found by a search over the prefix counts), sorts them in registers and keeps the
+// best 128 in its first 16 lanes; further candidates come in 384 at a time through the other 48 lanes.  Any number
 // of candidates the regions hold is handled; a query with an overflowed region or fewer than k
 // candidates is flagged in over[] instead.
 __global__ __launch_bounds__(256) void collect_select_sort_kernel(
@@ -310,22 +313,41 @@ __global__ __launch_bounds__(256) void collect_select_sort_kernel(
         const int first = __shfl(excl, r, 64);
         return i < total ? base[(size_t)r * Cs + (i - first)] : CAND_NONE;
     };
-    cand_t v[8];
+    // few candidates: a smaller network (2 or 4 per lane) does
+    auto small = [&](auto tag) {
+        constexpr int E = decltype(tag)::value;
+        cand_t v[E];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) v[j] = fetch(j * 64 + lane);
-    wave_sort512(v, lane);
-    for (int done = 512; done < total; done += 384) {      // wave-uniform: the best 128 stay in lanes 0 .. 15
+        for (int j = 0; j < E; ++j) v[j] = fetch(j * 64 + lane);
+        wave_sort<E>(v, lane);
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+            const int e = lane * E + j;
+            if (e < k) emit_result(v[j], q * k + e, q, ids, dists, qnorms, metric);
+        }
+    };
+    if (total <= 128) {                                    // wave-uniform
+        small(std::integral_constant<int, 2>{});
+    } else if (total <= 256) {
+        small(std::integral_constant<int, 4>{});
+    } else {
+        cand_t v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = fetch(j * 64 + lane);
+        wave_sort<8>(v, lane);
+        for (int done = 512; done < total; done += 384) {  // wave-uniform: the best 128 stay in lanes 0 .. 15
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const cand_t n = fetch(done + j * 48 + (lane - 16));   // (every lane takes part in the shuffles)
+                if (lane >= 16) v[j] = n;
+            }
+            wave_sort<8>(v, lane);
+        }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const cand_t n = fetch(done + j * 48 + (lane - 16));   // (every lane takes part in the shuffles)
-            if (lane >= 16) v[j] = n;
+            const int e = lane * 8 + j;
+            if (e < k) emit_result(v[j], q * k + e, q, ids, dists, qnorms, metric);
         }
-        wave_sort512(v, lane);
-    }
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int e = lane * 8 + j;
-        if (e < k) emit_result(v[j], q * k + e, q, ids, dists, qnorms, metric);
     }
     if (lane == 0) over[q] = 0;
 }
@@ -607,7 +629,9 @@ hipError_t launch_collect_select(const cand_t *cbuf, const int32_t *ccnt, int64_
     if (nq <= 0) return hipSuccess;
     const int maxc = 4096;
     if (SS < 1 || SS > 2048 || k > maxc) return hipErrorInvalidValue;
-    if (!only && expected_candidates > 0 && expected_candidates <= 256 && SS <= 64 && k <= 32) {
+    // (k rounds of "smallest in the wave" beat the sorting network only for the shortest lists: k = 1
+    // 1.00 against 1.01 ms per search on the benchmark workload, k = 10 1.178 against 1.166, k = 32 1.446 against 1.375)
+    if (!only && expected_candidates > 0 && expected_candidates <= 256 && SS <= 64 && k <= 2) {
         collect_select_wave_kernel<<<(unsigned)ceil_div(nq, (int64_t)4), 256, 0, st>>>(cbuf, ccnt, nq, SS, Cs, k, over, qlist,
                                                                                  qcount, ids, dists, qnorms, metric);
         return hipGetLastError();
