@@ -471,6 +471,9 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     else if (want != 1 && regs) p.mode = PLAN_MFMA_REG;
     else if (want != 1 && want != 4 && coll) p.mode = PLAN_MFMA_COLLECT;
     else if (want != 1 && mfma_lds_supported(idx->d_pad, k)) p.mode = PLAN_MFMA_LDS;
+    // Corpora too small for any sample (below 4096 rows) and little work in all: the generic kernel
+    // (1000 x 128, 1000 queries, k = 10: 0.05 ms against 0.29 ms for an unseeded matrix-core scan).
+    if (want == 0 && n < 4096 && nq * n <= (int64_t(4) << 20)) p.mode = PLAN_GENERIC;
     p.nq_pad = round_up(nq > 0 ? nq : 1, 512);
     // A merge pass sorts up to 4096 candidates per workgroup; more lists than that are merged in
     // two passes, so the number of splits is bounded by max_lists^2 only.
@@ -515,8 +518,11 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     seed = seed / 256 * 256;
     if (seed < 64 * k || seed * 4 > n) seed = 0;
     if (p.mode == PLAN_MFMA_COLLECT && !seed) {   // too few items to sample: exact paths
+        // (longer lists without a sample: the generic kernel; the LDS-list matrix-core kernel measured
+        // 10 to 70x slower on the corpora this happens for - 1000 x 128, k = 100, 1000 queries: 4.3 ms
+        // against 0.06 ms - and stays reachable through LPQ_TUNE_PATH = 4)
         p.mode = (regs && want != 1) ? PLAN_MFMA_REG
-                 : (mfma_lds_supported(idx->d_pad, k) && !idx->packed ? PLAN_MFMA_LDS : PLAN_GENERIC);
+                 : (want == 4 && mfma_lds_supported(idx->d_pad, k) && !idx->packed ? PLAN_MFMA_LDS : PLAN_GENERIC);
     }
 
     // lists one merge launch takes: the register-list scan's come out sorted, which allows more of them
