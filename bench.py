@@ -24,6 +24,51 @@ PEAK_HBM = 8.0e12           # MI355X HBM3E, B/s
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/search_mfma_kernel_skewed_int_1m_x128_pmc.txt
 # (FETCH_SIZE scaled by 2.000, WRITE_SIZE by 1.000 against device copies of known size in the same run).
 TRAFFIC_BYTES_DEFAULT_WORKLOAD = 264.0e6
+TRAFFIC_SOURCE = ("profiles/search_mfma_kernel_skewed_int_1m_x128_pmc.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                  "runs of this command; a constant taken from that file, not measured in this run)")
+
+
+def host_info():
+    """Logical CPUs of the host and its CPU model string (the oracle's baseline runs there)."""
+    model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return os.cpu_count() or 1, model
+
+
+def time_batches(lpq, torch, index, q, k, metric, reps, warm=10):
+    """ms per lpq_search call over `reps` back-to-back calls on one batch, and the per-call time of its
+    scan kernel and seeding pass (HIP events around each launch, as in the main timed region)."""
+    nq = q.shape[0]
+    ids = torch.empty((nq, k), dtype=torch.int32, device="cuda")
+    dists = torch.empty_like(ids)
+    ws = torch.empty(index.workspace_bytes(nq, k, metric) + 256, dtype=torch.uint8, device="cuda")
+    for _ in range(warm):
+        index.search(q, k, metric, out=(ids, dists), workspace=ws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        index.search(q, k, metric, out=(ids, dists), workspace=ws)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    # kernel times from a second, bracketed pass (the event pairs would otherwise sit between the launches timed above)
+    lpq.profile_enable(True)
+    for _ in range(min(reps, 100)):
+        index.search(q, k, metric, out=(ids, dists), workspace=ws)
+    torch.cuda.synchronize()
+    n_scan, scan_ms = lpq.profile_read(lpq.PROFILE_SCAN)
+    _, seed_ms = lpq.profile_read(lpq.PROFILE_SEED)
+    lpq.profile_enable(False)
+    calls = min(reps, 100)
+    return ms, scan_ms / calls, seed_ms / calls, n_scan / calls
 
 
 def cpu_baseline(oracle, x_host, q_host, params, k, metric, gpu_ids, gpu_dists, sample, bits=8, packed=False):
@@ -46,7 +91,9 @@ def cpu_baseline(oracle, x_host, q_host, params, k, metric, gpu_ids, gpu_dists, 
     t0 = time.perf_counter()
     oracle.search_i8(codes, qcodes[:s1], k, metric, threads=1)
     dt1 = time.perf_counter() - t0
-    return {"value": sample / dt, "unit": "queries/s", "cores": threads, "kind": "oracle",
+    host_cores, host_cpu = host_info()
+    return {"value": sample / dt, "unit": "queries/s", "cores": threads, "host_cores": host_cores, "host_cpu": host_cpu,
+            "kind": "oracle",
             "sample": f"first {sample} queries against the full corpus, {dt:.1f} s wall",
             "gpu_matches_oracle_on_sample": ok,
             "single_thread": {"value": s1 / dt1, "unit": "queries/s", "cores": 1,
@@ -60,6 +107,11 @@ def main():
     # default warm-up covers them; 100 timed searches of the default workload take ~0.14 s.
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--ramp", type=int, default=60,
+                    help="untimed searches BEFORE the warm-up (reported as ramp_searches): the shader clock needs "
+                         "~20 searches (~25 ms of load) after idle to settle, so a short --warmup would time the ramp")
+    ap.add_argument("--no-small-batch", action="store_true", help="skip the small-batch (HBM regime) block")
+    ap.add_argument("--no-probe", action="store_true", help="skip the attainable-rate probes")
     ap.add_argument("--nq", type=int, default=0, help="query batch (default: the workload's 10 000)")
     ap.add_argument("--k", type=int, default=10)
     ap.add_argument("--n", type=int, default=0, help="corpus rows (default: the workload's 1 000 000)")
@@ -122,12 +174,18 @@ def main():
     dists = torch.empty((w.nq, k), dtype=torch.int32, device="cuda")
     ws = torch.empty(index.workspace_bytes(w.nq, k, metric) + 256, dtype=torch.uint8, device="cuda")
 
+    # Clock ramp, disclosed under its own key: searches that are neither warm-up nor timed.  After
+    # an idle period the first ~20 searches run ~6 % slower while the shader clock settles, which a
+    # 5-search warm-up would put inside the timed region.
+    for _ in range(max(args.ramp, 0)):
+        index.search(q, k, metric, out=(ids, dists), workspace=ws)
+    torch.cuda.synchronize()
     for _ in range(args.warmup):
         index.search(q, k, metric, out=(ids, dists), workspace=ws)
     torch.cuda.synchronize()
 
     # ---- timed region: exactly `steps` searches ------------------------------------------
-    lpq.profile_enable(True)
+    lpq.profile_enable(True)     # creates the event pairs of the per-launch timing here, outside the timed region
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -168,11 +226,35 @@ def main():
                         and args.splits == 0 and args.seed_rows == 0 and args.bits == 8 and not args.packed
                         and not args.calib and not args.scope)
     roofline["traffic"] = TRAFFIC_BYTES_DEFAULT_WORKLOAD if default_workload else None
+    roofline["traffic_source"] = TRAFFIC_SOURCE if default_workload else None
     roofline["kernel"] = "search_mfma_kernel, main scan (contraction + top-k over all corpus rows)"
     roofline["kernel_ms_per_launch"] = kern_ms_per_launch
     roofline["launches_per_step"] = launches_per_step
     roofline["seeding_pass_ms_per_step"] = seed_ms / args.steps
     roofline["frac_with_seeding_pass"] = max(mfma_frac, hbm_frac) * kern_ms / max(kern_ms + seed_ms, 1e-12)
+    # the same algorithmic work over the whole step (query encode, seeding pass, scan, selection)
+    roofline["frac_end_to_end"] = (2.0 * w.nq * w.n * w.d / (ms_per_step * 1e-3) / PEAK_INT8_OPS if mfma_frac >= hbm_frac
+                                   else float(w.n) * (code_bytes + 4) / (ms_per_step * 1e-3) / PEAK_HBM)
+
+    # ---- what the part sustains on the two bounding resources (probes, after the timed region) ----
+    attainable = None
+    if not args.no_probe:
+        gen = torch.Generator(device="cuda").manual_seed(7)
+        rnd = torch.randint(-128, 128, (1 << 20,), generator=gen, device="cuda", dtype=torch.int8)
+        code_view = quant.encode(x[:min(w.n, 8192)].contiguous()).contiguous()   # codes of this workload's items
+        buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 256)
+        attainable = {
+            "mfma_zero_operands_TOPs": lpq.probe_mfma_i8(None),
+            "mfma_random_operands_TOPs": lpq.probe_mfma_i8(rnd),
+            "mfma_workload_codes_TOPs": lpq.probe_mfma_i8(code_view),
+            "stream_global_to_lds_GBps": lpq.probe_stream(buf, 0, 10),
+            "stream_register_loads_GBps": lpq.probe_stream(buf, 1, 10),
+            "note": "register-resident int8 matrix-instruction loop (operand bits as named; the shader clock falls "
+                    "under matrix load) and a streaming read of 1 GiB; peaks in `roofline` are the published ones",
+        }
+        del buf, rnd
+        ref = attainable["mfma_workload_codes_TOPs"] * 1e12 if mfma_frac >= hbm_frac else attainable["stream_global_to_lds_GBps"] * 1e9
+        roofline["frac_of_attainable"] = roofline["achieved"] * (1e12 if mfma_frac >= hbm_frac else 1e9) / ref
 
     # ---- recall@k of the int8 search against fp32 exact search (GPU), on a query subset ----
     rq = min(args.recall_queries, w.nq)
@@ -181,6 +263,44 @@ def main():
         eids, _ = lpq.search_f32(x, q[:rq], k, metric)
         a, e = ids[:rq].cpu().numpy(), eids.cpu().numpy()
         recall = float(np.mean([len(set(a[i]) & set(e[i])) / k for i in range(rq)]))
+
+    # The headline calibration (global min/max on integer data) makes codes = x - 128, so the recall
+    # above is 1 by construction; per-feature min/max on the same data is the informative figure.
+    recall_pf = None
+    if rq > 0 and default_workload:
+        qpf = lpq.Quantizer(w.d, args.bits).calibrate(x, "minmax", "per_feature")
+        ipf = lpq.Index(qpf, w.n).add_f32(x)
+        pids, _ = ipf.search(q[:rq], k, metric)
+        a = pids.cpu().numpy()
+        recall_pf = float(np.mean([len(set(a[i]) & set(e[i])) / k for i in range(rq)]))
+        del ipf, qpf
+
+    # ---- small batches: the regime bound by corpus bytes (after the timed region) -------------
+    small = None
+    if default_workload and not args.no_small_batch:
+        small = {"note": "ms per lpq_search call over back-to-back calls on one batch; bytes = n (d + 4) corpus bytes "
+                         "streamed once per call; fractions of 8 TB/s for the scan kernel alone and end to end; the "
+                         "128 MB of the 1M x 128 codes stay in the 256 MB memory-side cache between calls, the "
+                         "960 MB of 10M x 96 do not",
+                 "cases": []}
+        def small_case(name, idx_, qq, n_, d_, reps):
+            ms, scan_ms, seed_ms, scans = time_batches(lpq, torch, idx_, qq, k, metric, reps)
+            nbytes = float(n_) * (d_ + 4)
+            small["cases"].append({"workload": name, "nq": int(qq.shape[0]), "ms_per_batch": ms, "scan_ms": scan_ms,
+                                   "seeding_pass_ms": seed_ms, "scan_launches": scans, "bytes": nbytes,
+                                   "hbm_frac_scan": nbytes / (scan_ms * 1e-3) / PEAK_HBM if scan_ms > 0 else None,
+                                   "hbm_frac_end_to_end": nbytes / (ms * 1e-3) / PEAK_HBM,
+                                   "queries_per_s": qq.shape[0] / (ms * 1e-3)})
+        for nb in (1, 16, 256):
+            small_case(w.name, index, q[:nb], w.n, w.d, 300)
+        w4 = synth.SCALED_10M
+        x4 = w4.corpus("cuda")
+        q4 = w4.queries("cuda")[:16].contiguous()
+        quant4 = lpq.Quantizer(w4.d, 8).calibrate(x4, w4.calib, w4.scope)
+        index4 = lpq.Index(quant4, w4.n).add_f32(x4)
+        del x4
+        small_case(w4.name, index4, q4, w4.n, w4.d, 200)
+        del index4, quant4
 
     # ---- candidate-list calls (not part of the timed step) ---------------------------------
     extras = None
@@ -254,7 +374,11 @@ def main():
                    "path": {0: "auto", 1: "generic", 2: "matrix-core"}[args.path]},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "ramp_searches": max(args.ramp, 0),
+        "attainable": attainable,
+        "small_batch": small,
         "recall_at_k_vs_fp32": recall,
+        "recall_at_k_vs_fp32_per_feature_calibration": recall_pf,
         "recall_queries": rq,
         "index_build": {"calibrate_ms": t_cal * 1e3, "encode_ms": t_enc * 1e3,
                         "encode_GBps": w.n * w.d * 5 / t_enc / 1e9},

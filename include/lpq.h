@@ -214,19 +214,23 @@ int lpq_rerank_f32(const float *x_dev, int64_t n, int64_t ldx, const float *q_de
  *   LPQ_TUNE_SPLITS      number of corpus splits per query tile in the main pass
  *   LPQ_TUNE_SEED_ROWS   rows of the threshold-seeding pass (0 = built-in choice,
  *                        -1 = no seeding pass)
- *   LPQ_TUNE_DRY_RUN     1 = the matrix-core kernel never collects a candidate (timing of
- *                        the bare contraction only; the results are then meaningless).
- *                        Further timing ablations, results equally meaningless: 2 no workgroup
- *                        barrier, 3 no corpus copies, 4 neither, 5 candidates are detected but
- *                        neither queued nor processed, 6 queued but not processed.  Meant for
- *                        k <= 16 (for larger k every query then falls to the generic kernel).
+ *   LPQ_TUNE_DRY_RUN     timing ablations of the matrix-core kernel whose results are meaningless
+ *                        (1 never collects a candidate, 2 no workgroup barrier, 3 no corpus
+ *                        copies, 4 neither, 5 candidates detected but not queued, 6 queued but
+ *                        not processed).  Compiled only into builds made with -DLPQ_ABLATION
+ *                        (python -m paper_2110_08919_amd.build --ablation writes
+ *                        liblpq_ablation.so); the shipped library has none of these branches
+ *                        and rejects a non-zero value with LPQ_EINVAL.
  *   LPQ_TUNE_WORK_ORDER  how workgroups of the matrix-core kernel are dealt to (split, query tile)
  *                        pairs: 0 built-in, 1 each XCD takes whole splits, 2 each XCD takes whole
  *                        query tiles, 3 plain block order
  *   LPQ_TUNE_WAVE_QUERIES queries per wave of the collecting variant: 64 or 128 (0 = built-in)
  *   LPQ_TUNE_REGION_CAP  candidates a region of the collecting variant holds (0 = built-in); a tiny
  *                        value makes most queries overflow and go through the exact redo paths
- * Results never depend on PATH, SPLITS, SEED_ROWS, WORK_ORDER, WAVE_QUERIES or REGION_CAP. */
+ * Results never depend on PATH, SPLITS, SEED_ROWS, WORK_ORDER, WAVE_QUERIES or REGION_CAP.
+ * The knobs are atomics: setting one while other threads search is not a data race; a search
+ * reads each knob at some moment of its planning, so set them before the searches they are for
+ * (lpq_search_workspace_bytes and the lpq_search that uses its answer must see the same values). */
 enum { LPQ_TUNE_PATH = 0, LPQ_TUNE_SPLITS = 1, LPQ_TUNE_SEED_ROWS = 2, LPQ_TUNE_DRY_RUN = 3, LPQ_TUNE_WORK_ORDER = 4,
        LPQ_TUNE_WAVE_QUERIES = 5, LPQ_TUNE_REGION_CAP = 6, LPQ_TUNE_COUNT_ = 7 };
 int lpq_set_tuning(int key, int64_t value);
@@ -241,6 +245,24 @@ enum { LPQ_PROFILE_SCAN = 0, LPQ_PROFILE_SEED = 1 };
 int lpq_profile_enable(int on);
 int lpq_profile_read(int64_t *launches, double *total_ms);
 int lpq_profile_read_kind(int kind, int64_t *launches, double *total_ms);
+
+/* Attainable-rate probes (benchmarks only): what this GPU sustains on the two resources that
+ * bound lpq_search, measured by kernels that do nothing else, so that a roofline fraction quoted
+ * against a published peak can be read next to what the part reaches in practice.  Both calls
+ * allocate a small device buffer, time with events on `stream` and synchronise it.
+ *   lpq_probe_mfma_i8: a register-resident loop of the int8 matrix instruction the search uses
+ *     (the contraction of Section 3.1's phi on codes), `iters` x 8 instructions per wave, four
+ *     waves per workgroup, two workgroups per CU.  The operand registers are filled from
+ *     operands_dev[operand_bytes] (device memory, 16-byte aligned; null = all-zero operands): the
+ *     sustained rate depends on how many operand bits toggle, so pass the bytes of interest
+ *     (random bytes, or the codes of an index).  *tops = 1e12 integer operations per second.
+ *   lpq_probe_stream: reads bytes (rounded down to a multiple of 4096) of src_dev `reps` times,
+ *     mode 0 through the asynchronous global->LDS copies of the scan kernels, mode 1 through
+ *     16-byte register loads.  *gbps = 1e9 bytes per second.
+ * LPQ_EINVAL: null output, iters outside 1..10 000 000, misaligned or too small a buffer,
+ * unknown mode, reps outside 1..10 000. */
+int lpq_probe_mfma_i8(const void *operands_dev, size_t operand_bytes, int iters, double *tops, void *stream);
+int lpq_probe_stream(const void *src_dev, size_t bytes, int mode, int reps, double *gbps, void *stream);
 
 /* Diagnostics of the collecting variant: after a search with the same (idx, nq, k, metric) and
  * workspace has finished, the number of queries whose candidates did not fit and that were

@@ -1,9 +1,12 @@
 """Builds liblpq.so (the HIP library) in-tree with hipcc for gfx950.
 
-    python -m paper_2110_08919_amd.build [--force]
+    python -m paper_2110_08919_amd.build [--force] [--ablation]
 
 Each .hip file under csrc/ is compiled to an object (in parallel), then linked into
 paper_2110_08919_amd/liblpq.so.  hipcc cross-compiles, so no GPU is needed to build.
+--ablation builds a second library, liblpq_ablation.so, with -DLPQ_ABLATION: the timing
+experiments of the matrix-core kernel (LPQ_TUNE_DRY_RUN) exist only there; select it for a
+measurement with LPQ_LIBRARY=<path>.
 """
 from __future__ import annotations
 
@@ -37,23 +40,25 @@ def _newest_header() -> float:
     return max(os.path.getmtime(h) for h in hs)
 
 
-def _compile(src: str, force: bool) -> str:
-    obj = os.path.join(OBJ, os.path.basename(src)[:-4] + ".o")
+def _compile(src: str, force: bool, ablation: bool) -> str:
+    obj = os.path.join(OBJ, os.path.basename(src)[:-4] + (".abl.o" if ablation else ".o"))
     stale = (force or not os.path.exists(obj)
              or os.path.getmtime(obj) < max(os.path.getmtime(src), _newest_header()))
     if stale:
-        subprocess.run([HIPCC, *FLAGS, "-c", src, "-o", obj], check=True)
+        extra = ["-DLPQ_ABLATION"] if ablation else []
+        subprocess.run([HIPCC, *FLAGS, *extra, "-c", src, "-o", obj], check=True)
     return obj
 
 
-def build(force: bool = False, jobs: int = 8) -> str:
+def build(force: bool = False, jobs: int = 8, ablation: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
+    lib = os.path.join(HERE, "liblpq_ablation.so") if ablation else LIB
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(lambda s: _compile(s, force), sources()))
-    if force or not os.path.exists(LIB) or any(os.path.getmtime(o) > os.path.getmtime(LIB) for o in objs):
-        subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
-    return LIB
+        objs = list(ex.map(lambda s: _compile(s, force, ablation), sources()))
+    if force or not os.path.exists(lib) or any(os.path.getmtime(o) > os.path.getmtime(lib) for o in objs):
+        subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs], check=True)
+    return lib
 
 
 if __name__ == "__main__":
-    print(build(force="--force" in sys.argv))
+    print(build(force="--force" in sys.argv, ablation="--ablation" in sys.argv))

@@ -1,5 +1,6 @@
 // C ABI of liblpq.so: argument checks, handle lifetimes, workspace planning and the order
 // in which the kernels of a search are enqueued.  No kernel lives here.
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -35,26 +36,41 @@ static int fail(int code, const char *fmt, ...)
 extern "C" const char *lpq_last_error(void) { return g_err; }
 
 // ------------------------------------------------------------------------ tuning ----
-static int64_t g_tune[LPQ_TUNE_COUNT_] = {0, 0, 0, 0, 0, 0, 0};
+// Process-wide and read by every planning call: atomics, so that a thread changing a knob while
+// others search is not a data race (a search still sees each knob at some moment of its planning;
+// results never depend on them).
+static std::atomic<int64_t> g_tune[LPQ_TUNE_COUNT_];
+static inline int64_t tune(int key) { return g_tune[key].load(std::memory_order_relaxed); }
 
 extern "C" int lpq_set_tuning(int key, int64_t value)
 {
     if (key < 0 || key >= LPQ_TUNE_COUNT_) return fail(LPQ_EINVAL, "unknown tuning key %d", key);
-    g_tune[key] = value;
+#ifndef LPQ_ABLATION
+    if (key == LPQ_TUNE_DRY_RUN && value != 0)
+        return fail(LPQ_EINVAL, "LPQ_TUNE_DRY_RUN exists only in builds compiled with -DLPQ_ABLATION");
+#endif
+    g_tune[key].store(value, std::memory_order_relaxed);
     return LPQ_OK;
 }
 
 // --------------------------------------------------------------------- profiling ----
 namespace {
+// Event pairs are created when profiling is switched on, not inside the searches they time: a
+// span only takes the next free pair (spans beyond the pool go untimed and are counted as dropped).
+constexpr size_t PROFILE_POOL = 4096;
 struct Profile {
     std::mutex mu;
     bool on = false;
     struct Span { hipEvent_t a, b; int kind; };
-    std::vector<Span> spans;
+    std::vector<Span> pool;    // pairs created by lpq_profile_enable(1)
+    size_t used = 0;           // pairs handed out so far
+    int64_t dropped = 0;
     void clear()
     {
-        for (auto &s : spans) { (void)hipEventDestroy(s.a); (void)hipEventDestroy(s.b); }
-        spans.clear();
+        for (auto &s : pool) { (void)hipEventDestroy(s.a); (void)hipEventDestroy(s.b); }
+        pool.clear();
+        used = 0;
+        dropped = 0;
     }
 };
 Profile g_prof;
@@ -62,20 +78,19 @@ Profile g_prof;
 struct KernelSpan {  // brackets one kernel launch with two events while profiling is on
     hipEvent_t a = nullptr, b = nullptr;
     hipStream_t st;
-    int kind;
-    explicit KernelSpan(hipStream_t s, int kind_ = LPQ_PROFILE_SCAN) : st(s), kind(kind_)
+    explicit KernelSpan(hipStream_t s, int kind_ = LPQ_PROFILE_SCAN) : st(s)
     {
         std::lock_guard<std::mutex> l(g_prof.mu);
         if (!g_prof.on) return;
-        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { a = b = nullptr; return; }
+        if (g_prof.used >= g_prof.pool.size()) { ++g_prof.dropped; return; }
+        Profile::Span &sp = g_prof.pool[g_prof.used++];
+        sp.kind = kind_;
+        a = sp.a; b = sp.b;
         (void)hipEventRecord(a, st);
     }
     ~KernelSpan()
     {
-        if (!a) return;
-        (void)hipEventRecord(b, st);
-        std::lock_guard<std::mutex> l(g_prof.mu);
-        g_prof.spans.push_back({a, b, kind});
+        if (a) (void)hipEventRecord(b, st);
     }
 };
 }  // namespace
@@ -84,7 +99,22 @@ extern "C" int lpq_profile_enable(int on)
 {
     std::lock_guard<std::mutex> l(g_prof.mu);
     g_prof.clear();
-    g_prof.on = on != 0;
+    g_prof.on = false;
+    if (on) {
+        g_prof.pool.reserve(PROFILE_POOL);
+        for (size_t i = 0; i < PROFILE_POOL; ++i) {
+            Profile::Span sp = {nullptr, nullptr, 0};
+            hipError_t e = hipEventCreate(&sp.a);
+            if (e == hipSuccess) e = hipEventCreate(&sp.b);
+            if (e != hipSuccess) {
+                if (sp.a) (void)hipEventDestroy(sp.a);
+                g_prof.clear();
+                return fail(LPQ_EDEVICE, "hipEventCreate: %s", hipGetErrorString(e));
+            }
+            g_prof.pool.push_back(sp);
+        }
+        g_prof.on = true;
+    }
     return LPQ_OK;
 }
 
@@ -94,7 +124,8 @@ static int profile_sum(int kind, int64_t *launches, double *total_ms)
     std::lock_guard<std::mutex> l(g_prof.mu);
     double tot = 0.0;
     int64_t cnt = 0;
-    for (auto &s : g_prof.spans) {
+    for (size_t i = 0; i < g_prof.used; ++i) {
+        const Profile::Span &s = g_prof.pool[i];
         if (kind >= 0 && s.kind != kind) continue;
         HIP_TRY(hipEventSynchronize(s.b));
         float ms = 0.f;
@@ -113,6 +144,29 @@ extern "C" int lpq_profile_read_kind(int kind, int64_t *launches, double *total_
 {
     if (kind != LPQ_PROFILE_SCAN && kind != LPQ_PROFILE_SEED) return fail(LPQ_EINVAL, "unknown kernel kind %d", kind);
     return profile_sum(kind, launches, total_ms);
+}
+
+// ------------------------------------------------------------------------ probes ----
+extern "C" int lpq_probe_mfma_i8(const void *operands_dev, size_t operand_bytes, int iters, double *tops, void *stream)
+{
+    if (!tops) return fail(LPQ_EINVAL, "null output");
+    if (iters < 1 || iters > 10000000) return fail(LPQ_EINVAL, "iters = %d outside 1..10 000 000", iters);
+    if (operands_dev && operand_bytes < 16) return fail(LPQ_EINVAL, "operand buffer smaller than 16 bytes");
+    if (operands_dev && (uintptr_t)operands_dev % 16) return fail(LPQ_EINVAL, "operand buffer must be 16-byte aligned");
+    *tops = 0.0;
+    HIP_TRY(probe_mfma(operands_dev, operand_bytes, iters, tops, (hipStream_t)stream));
+    return LPQ_OK;
+}
+
+extern "C" int lpq_probe_stream(const void *src_dev, size_t bytes, int mode, int reps, double *gbps, void *stream)
+{
+    if (!src_dev || !gbps) return fail(LPQ_EINVAL, "null argument");
+    if (mode != 0 && mode != 1) return fail(LPQ_EINVAL, "unknown mode %d", mode);
+    if (bytes < 4096 || reps < 1 || reps > 10000) return fail(LPQ_EINVAL, "bytes < 4096 or reps outside 1..10 000");
+    if ((uintptr_t)src_dev % 16) return fail(LPQ_EINVAL, "buffer must be 16-byte aligned");
+    *gbps = 0.0;
+    HIP_TRY(probe_stream(src_dev, bytes / 4096 * 4096, mode, reps, gbps, (hipStream_t)stream));
+    return LPQ_OK;
 }
 
 // --------------------------------------------------------------------- quantizer ----
@@ -443,14 +497,14 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
 {
     Plan p;
     const int64_t n = idx->size;
-    const int64_t want = g_tune[LPQ_TUNE_PATH];
+    const int64_t want = tune(LPQ_TUNE_PATH);
     const bool regs = mfma_reg_supported(idx->d_pad, k), coll = mfma_collect_supported(idx->d_pad, k);
     // Large batches of short rows: the collecting variant with 128 queries per wave beats the
     // register lists at any k it takes (fewer LDS reads and less per-stage overhead per contraction).
     // (Not for codes of fewer than WIDE_MIN_BITS bits: there many items tie at the seed
     // threshold, all of them are collected, and queries spill to the exact redo.)
     const bool wide = coll && idx->bits >= WIDE_MIN_BITS && mfma_collect_wide(nq, idx->d_pad) &&
-                      g_tune[LPQ_TUNE_WAVE_QUERIES] != 64;
+                      tune(LPQ_TUNE_WAVE_QUERIES) != 64;
     // Rows longer than 128 bytes: the register-list kernels hold 6 or 8 operand registers per query
     // block on top of the lists and spill; the collecting variant measured 1.6x (10 000 queries) to
     // 3.5x (16 queries) faster at d = 256 for every batch size and code width.
@@ -489,8 +543,8 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     // per query survive.
     const bool gm = p.mode == PLAN_MFMA_REG || p.mode == PLAN_MFMA_COLLECT;
     int64_t seed = 0;
-    if (g_tune[LPQ_TUNE_SEED_ROWS] > 0) seed = g_tune[LPQ_TUNE_SEED_ROWS];
-    else if (g_tune[LPQ_TUNE_SEED_ROWS] == 0 && p.mode != PLAN_GENERIC) {
+    if (tune(LPQ_TUNE_SEED_ROWS) > 0) seed = tune(LPQ_TUNE_SEED_ROWS);
+    else if (tune(LPQ_TUNE_SEED_ROWS) == 0 && p.mode != PLAN_GENERIC) {
         // Few queries: the scan is bound by corpus bytes, so the sample stays small.  Otherwise a
         // larger sample pays for itself through fewer candidates in the main pass (measured).
         const bool few = gm && mfma_row_split(nq, idx->d_pad, idx->packed);
@@ -529,8 +583,8 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     const int one_pass = p.mode == PLAN_MFMA_REG ? merge_max_sorted_lists(k) : merge_max_lists(k);
     auto splits_for = [&](int64_t rows, int64_t tiles_q, int64_t min_rows, int64_t slots, int64_t cap) {
         int64_t s;
-        if (p.mode != PLAN_GENERIC) s = g_tune[LPQ_TUNE_SPLITS] > 0 ? g_tune[LPQ_TUNE_SPLITS] : slots / (tiles_q > 0 ? tiles_q : 1);
-        else s = g_tune[LPQ_TUNE_SPLITS] > 0 ? g_tune[LPQ_TUNE_SPLITS] : ceil_div(2048, nq > 0 ? nq : 1);
+        if (p.mode != PLAN_GENERIC) s = tune(LPQ_TUNE_SPLITS) > 0 ? tune(LPQ_TUNE_SPLITS) : slots / (tiles_q > 0 ? tiles_q : 1);
+        else s = tune(LPQ_TUNE_SPLITS) > 0 ? tune(LPQ_TUNE_SPLITS) : ceil_div(2048, nq > 0 ? nq : 1);
         const int64_t by_rows = rows / min_rows > 0 ? rows / min_rows : 1;
         if (s > by_rows) s = by_rows;
         if (s > cap) s = cap;
@@ -545,7 +599,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
         const int waves = mfma_row_split_waves(idx->d_pad, idx->packed);
         p.rsplit = mfma_row_split(nq, idx->d_pad, idx->packed) && (waves == 4 || p.mode == PLAN_MFMA_COLLECT);
         p.rs_waves = p.rsplit ? waves : 0;
-        if (p.mode == PLAN_MFMA_COLLECT && mfma_collect_wide(nq, idx->d_pad) && g_tune[LPQ_TUNE_WAVE_QUERIES] != 64)
+        if (p.mode == PLAN_MFMA_COLLECT && mfma_collect_wide(nq, idx->d_pad) && tune(LPQ_TUNE_WAVE_QUERIES) != 64)
             p.wave_queries = 128;
         if (p.mode == PLAN_MFMA_COLLECT && idx->packed)   // the packed scan has one variant per row length
             p.wave_queries = idx->d_pad <= 128 ? 128 : 64;
@@ -597,7 +651,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
         int64_t cs = 64;
         while ((double)cs < 3.0 * per_region && cs < 4096) cs <<= 1;
         p.Cs = (int)cs;
-        if (g_tune[LPQ_TUNE_REGION_CAP] > 0) p.Cs = (int)(g_tune[LPQ_TUNE_REGION_CAP] < 4096 ? g_tune[LPQ_TUNE_REGION_CAP] : 4096);
+        if (tune(LPQ_TUNE_REGION_CAP) > 0) p.Cs = (int)(tune(LPQ_TUNE_REGION_CAP) < 4096 ? tune(LPQ_TUNE_REGION_CAP) : 4096);
         // splits of the redo scan: many, so that a few queries spread over the chip; bounded by the
         // single merge pass and by 256 MB of lists
         p.Sg = merge_max_lists(k) < 128 ? merge_max_lists(k) : 128;
@@ -676,8 +730,10 @@ int search_core(const lpq_index *idx, const Plan &p, char *ws, const int8_t *qco
     a.packed = idx->packed;
     a.qcodes = qcodes;
     a.nq = nq; a.k = k; a.metric = metric;
-    a.dry_run = (int)g_tune[LPQ_TUNE_DRY_RUN];
-    a.work_order = (int)g_tune[LPQ_TUNE_WORK_ORDER];
+#ifdef LPQ_ABLATION
+    a.dry_run = (int)tune(LPQ_TUNE_DRY_RUN);
+#endif
+    a.work_order = (int)tune(LPQ_TUNE_WORK_ORDER);
     a.wave_queries = 64;
     a.rsplit = p.rsplit;
     a.rs_waves = p.rsplit ? p.rs_waves : 4;
@@ -870,14 +926,10 @@ extern "C" size_t lpq_search_workspace_bytes(const lpq_index *idx, int64_t nq, i
     return make_plan(idx, nq, k).total + 256;
 }
 
-extern "C" int lpq_search(const lpq_index *idx, const float *q_dev, int64_t nq, int64_t ld, int k, int metric,
-                          int32_t *ids_dev, int32_t *dist_dev, void *workspace_dev, size_t workspace_bytes,
-                          void *stream)
+static int search_f32_queries(const lpq_index *idx, const float *q_dev, int64_t nq, int64_t ld, int k, int metric,
+                              int32_t *ids_dev, int32_t *dist_dev, void *workspace_dev, size_t workspace_bytes,
+                              hipStream_t st)
 {
-    int rc = check_search_args(idx, q_dev, nq, ld, k, metric, ids_dev, dist_dev);
-    if (rc) return rc;
-    if (nq == 0) return LPQ_OK;
-    hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace_dev;
     if ((uintptr_t)workspace_dev % 256) return fail(LPQ_EINVAL, "workspace must be 256-byte aligned");
     if (idx->packed) {
@@ -896,6 +948,17 @@ extern "C" int lpq_search(const lpq_index *idx, const float *q_dev, int64_t nq, 
                           reinterpret_cast<int32_t *>(ws + p.off_qnorms), st, p.nq_pad));
     return search_core(idx, p, ws, reinterpret_cast<const int8_t *>(ws + p.off_qcodes),
                        reinterpret_cast<const int32_t *>(ws + p.off_qnorms), nq, k, metric, metric, ids_dev, dist_dev, st);
+}
+
+extern "C" int lpq_search(const lpq_index *idx, const float *q_dev, int64_t nq, int64_t ld, int k, int metric,
+                          int32_t *ids_dev, int32_t *dist_dev, void *workspace_dev, size_t workspace_bytes,
+                          void *stream)
+{
+    int rc = check_search_args(idx, q_dev, nq, ld, k, metric, ids_dev, dist_dev);
+    if (rc) return rc;
+    if (nq == 0) return LPQ_OK;
+    return search_f32_queries(idx, q_dev, nq, ld, k, metric, ids_dev, dist_dev, workspace_dev, workspace_bytes,
+                              (hipStream_t)stream);
 }
 
 extern "C" int lpq_search_overflow_stats(const lpq_index *idx, int64_t nq, int k, int metric, const void *workspace_dev,

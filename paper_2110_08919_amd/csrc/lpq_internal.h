@@ -111,7 +111,7 @@ struct SearchArgs {
     int metric;
     bool rsplit;            // register variant: row-split workgroups (set from mfma_row_split)
     int rs_waves = 4;       // ... of this many waves (mfma_row_split_waves): a stage holds 32 rows per wave
-    int dry_run;            // timing experiments: != 0 never collects a candidate (2..4: ablations)
+    int dry_run = 0;        // builds with -DLPQ_ABLATION only: timing experiments whose results are meaningless
     int work_order = 0;     // matrix-core kernels: block -> (split, query tile) mapping (0 = built-in)
     int wave_queries = 64;  // collecting mode: queries per wave (64 or 128)
     bool packed = false;    // codes holds two 4-bit codes (stored + 8) per byte, rows of d_pad / 2 bytes; qcodes permuted to match
@@ -225,6 +225,15 @@ size_t f32_workspace_bytes(int64_t n, int64_t nq, int d, int k);
 hipError_t launch_search_f32(const float *x, int64_t n, int64_t ldx, const float *q, int64_t nq,
                              int64_t ldq, int d, int k, int metric, int32_t *ids, float *dists,
                              void *ws, hipStream_t st);
+
+// ---- attainable-rate probes (probe.hip); they allocate a small sink, time with events on st and synchronise ----
+// Sustained rate of a register-resident v_mfma_i32_32x32x32_i8 loop whose operand registers are
+// filled from `operands` (null: all zero), in 1e12 integer operations per second.
+hipError_t probe_mfma(const void *operands, size_t bytes, int iters, double *tops, hipStream_t st);
+// Sustained read rate over `bytes` of device memory, `reps` passes: mode 0 through asynchronous
+// global->LDS copies into wave-private rings (bytes / 4096 chunks are read), mode 1 through
+// 16-byte register loads; in 1e9 bytes per second.
+hipError_t probe_stream(const void *src, size_t bytes, int mode, int reps, double *gbps, hipStream_t st);
 
 static const int32_t CINIT_PAD = -(1 << 30);
 

@@ -63,6 +63,14 @@ namespace lpq {
 
 namespace {
 
+// Timing ablations (results then meaningless) exist only in builds compiled with -DLPQ_ABLATION;
+// in the shipped library the value is the constant 0 and the branches on it vanish.
+#ifdef LPQ_ABLATION
+#define LPQ_DRY(a) ((a).dry_run)
+#else
+#define LPQ_DRY(a) 0
+#endif
+
 constexpr int NQW = 64;      // queries per wave in list mode = lanes per wave: lane q owns query q
 constexpr int TRIG = 32;     // queue fill that asks for a joint drain at the next stage boundary
 constexpr int SVCAP = 128;   // compacted candidates buffered before they are handed to owners
@@ -358,7 +366,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     const size_t qstride = (size_t)SS * o.Cs;
     if (!SEED) {
         const int64_t gq = q_first + lane;
-        seedC = (gq < a.nq && (a.dry_run == 0 || a.dry_run >= 5)) ? (seeds ? seeds[gq] : CAND_NONE) : 0;
+        seedC = (gq < a.nq && (LPQ_DRY(a) == 0 || LPQ_DRY(a) >= 5)) ? (seeds ? seeds[gq] : CAND_NONE) : 0;
         // slots beyond k are pinned to the smallest candidate, so lst[KCAP-1] is the k-th best
 #pragma unroll
         for (int i = 0; i < LK; ++i) lst[i] = (i < KCAP - k) ? 0 : CAND_NONE;
@@ -367,7 +375,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
         w.mbox[lane] = COLLECT ? 0 : -1;
         if constexpr (QW > 64) {   // the second 64 queries of the wave
             const int64_t gq2 = gq + 64;
-            const cand_t s2 = (gq2 < a.nq && (a.dry_run == 0 || a.dry_run >= 5)) ? (seeds ? seeds[gq2] : CAND_NONE) : 0;
+            const cand_t s2 = (gq2 < a.nq && (LPQ_DRY(a) == 0 || LPQ_DRY(a) >= 5)) ? (seeds ? seeds[gq2] : CAND_NONE) : 0;
             w.thrC[64 + lane] = s2;
             w.thrE[64 + lane] = thr_e(s2);
             w.mbox[64 + lane] = 0;
@@ -499,7 +507,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
                 unsigned long long mask = __ballot(trip);                                               \
                 if (mask) {                                                                             \
                     if (qcnt + __popcll(mask) > QCAP) { /* no room: this wave drains alone */           \
-                        if (a.dry_run < 5) drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs); \
+                        if (LPQ_DRY(a) < 5) drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs); \
                         qcnt = 0;                                                                       \
                         _Pragma("unroll") for (int j = 0; j < NB; ++j) thr[j] = w.thrE[j * 32 + col];   \
                         trip = m >= thr[nb];                                                            \
@@ -508,7 +516,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
                     if (mask) {                                                                         \
                         const int below = __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),             \
                                                                     __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u)); \
-                        if (trip && a.dry_run != 5) {                                                   \
+                        if (trip && LPQ_DRY(a) != 5) {                                                   \
                             const int slot = qcnt + below;                                              \
                             v4i *dst_ = reinterpret_cast<v4i *>(w.qvals + slot * 16);                   \
                             _Pragma("unroll") for (int g = 0; g < 4; ++g)                               \
@@ -621,7 +629,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
         v4i A0[KS], A1[KS];
         v16i C0, C1;
         unsigned P0 = 0, P1 = 0;
-        const bool abl_nodma = a.dry_run == 3 || a.dry_run == 4, abl_nobar = a.dry_run == 2 || a.dry_run == 4;   // timing ablations
+        const bool abl_nodma = LPQ_DRY(a) == 3 || LPQ_DRY(a) == 4, abl_nobar = LPQ_DRY(a) == 2 || LPQ_DRY(a) == 4;   // timing ablations
         const int primed = T < NST ? T : NST;
         if (!abl_nodma) for (int st = 0; st < primed; ++st) LPQ_ISSUE(st);
         if (T > 0) {
@@ -658,7 +666,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
                 fl0 = *reinterpret_cast<const v4i *>(flags + (t & 1) * 8);
                 if (NW > 4) fl1 = *reinterpret_cast<const v4i *>(flags + (t & 1) * 8 + 4);
                 if (any) {   // same answer in every wave of the workgroup: drain together
-                    if (a.dry_run < 5) drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
+                    if (LPQ_DRY(a) < 5) drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
                     qcnt = 0;
 #pragma unroll
                     for (int j = 0; j < NB; ++j) thr[j] = w.thrE[j * 32 + col];
@@ -685,14 +693,14 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
 #undef LPQ_FLUSH_SEGMENT
 
     if (COLLECT) {
-        if (a.dry_run < 5) drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
+        if (LPQ_DRY(a) < 5) drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
         wave_lds_sync();
         for (int i = lane; i < QW; i += 64) {
             const int64_t gq = q_first + i;
             if (gq < a.nq) o.ccnt[(size_t)gq * SS + sub] = w.mbox[i];
         }
     } else if (!SEED) {
-        if (a.dry_run < 5) drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
+        if (LPQ_DRY(a) < 5) drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
         if constexpr (RSPLIT && KCAP > 0) {
             // The waves hold lists of the SAME 64 queries over different rows: waves 1.. publish
             // theirs in the (now idle) ring and wave 0 folds them into its own.

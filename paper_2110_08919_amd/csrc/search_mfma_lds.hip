@@ -148,7 +148,7 @@ __global__ __launch_bounds__(THREADS, 2) void search_mfma_lds_kernel(
     const int64_t q_first = (int64_t)qt * QT + wave * NQW;
     if (lane < NQW) {
         const int64_t gq = q_first + lane;
-        const cand_t sd = (gq < a.nq && a.dry_run == 0) ? (seeds ? seeds[gq] : CAND_NONE) : 0;
+        const cand_t sd = (gq < a.nq) ? (seeds ? seeds[gq] : CAND_NONE) : 0;
         w.thrC[lane] = sd;
         w.thrE[lane] = thr_e(sd);
         w.cnt[lane] = 0;

@@ -73,6 +73,8 @@ def lib() -> C.CDLL:
             "lpq_profile_enable": (i32, [i32]),
             "lpq_profile_read": (i32, [C.POINTER(i64), C.POINTER(C.c_double)]),
             "lpq_profile_read_kind": (i32, [i32, C.POINTER(i64), C.POINTER(C.c_double)]),
+            "lpq_probe_mfma_i8": (i32, [vp, C.c_size_t, i32, C.POINTER(C.c_double), vp]),
+            "lpq_probe_stream": (i32, [vp, C.c_size_t, i32, i32, C.POINTER(C.c_double), vp]),
             "lpq_last_error": (C.c_char_p, []),
         }
         for name, (res, args) in sig.items():
@@ -120,6 +122,23 @@ def profile_read(kind=None):
     else:
         _check(lib().lpq_profile_read_kind(kind, C.byref(n), C.byref(ms)))
     return n.value, ms.value
+
+
+def probe_mfma_i8(operands: torch.Tensor = None, iters: int = 50000) -> float:
+    """Sustained 1e12 op/s of a register-resident int8 matrix-instruction loop whose operand
+    registers are filled from `operands` (a contiguous device tensor; None = zeros)."""
+    out = C.c_double(0.0)
+    nbytes = 0 if operands is None else operands.numel() * operands.element_size()
+    _check(lib().lpq_probe_mfma_i8(_ptr(operands), nbytes, iters, C.byref(out), _stream()))
+    return out.value
+
+
+def probe_stream(src: torch.Tensor, mode: int = 0, reps: int = 10) -> float:
+    """Sustained 1e9 B/s of reading `src` (contiguous device tensor): mode 0 asynchronous
+    global->LDS copies, mode 1 register loads."""
+    out = C.c_double(0.0)
+    _check(lib().lpq_probe_stream(src.data_ptr(), src.numel() * src.element_size(), mode, reps, C.byref(out), _stream()))
+    return out.value
 
 
 class Quantizer:

@@ -69,6 +69,18 @@ def test_argument_checks_without_device(L):
     # workspace of the fp32 search: host arithmetic only, grows with the batch
     small, large = L.lpq_search_f32_workspace_bytes(1_000_000, 10, 128, 10), L.lpq_search_f32_workspace_bytes(1_000_000, 1000, 128, 10)
     assert 0 < small <= large
+    # probes: argument checks precede any device work
+    out = C.c_double(-1.0)
+    assert L.lpq_probe_mfma_i8(None, 0, 100, None, None) == lpq.EINVAL
+    assert L.lpq_probe_mfma_i8(None, 0, 0, C.byref(out), None) == lpq.EINVAL
+    assert L.lpq_probe_mfma_i8(p1, 8, 100, C.byref(out), None) == lpq.EINVAL       # fewer than 16 operand bytes
+    assert L.lpq_probe_stream(None, 1 << 20, 0, 1, C.byref(out), None) == lpq.EINVAL
+    assert L.lpq_probe_stream(p1, 1 << 20, 2, 1, C.byref(out), None) == lpq.EINVAL  # unknown mode
+    assert L.lpq_probe_stream(p1, 100, 0, 1, C.byref(out), None) == lpq.EINVAL      # less than one 4 KB chunk
+    assert out.value == -1.0
+    # the timing ablations are not compiled into the shipped library
+    assert L.lpq_set_tuning(lpq.TUNE_DRY_RUN, 1) == lpq.EINVAL
+    assert L.lpq_set_tuning(lpq.TUNE_DRY_RUN, 0) == lpq.OK
     L.lpq_quantizer_destroy(None)
     L.lpq_index_destroy(None)
 

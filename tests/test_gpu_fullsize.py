@@ -73,7 +73,7 @@ def _full_case(lpq, oracle, w, k, mode, scope, sample, batches=None, threads=16)
     for nb in batches or ():                                     # other batch sizes: same answers
         bi, bd = index.search(q[:nb], k, w.metric)
         assert np.array_equal(bi.cpu().numpy(), ids[:nb]) and np.array_equal(bd.cpu().numpy(), dists[:nb])
-    return index, q, ids
+    return index, q, ids, codes, qcodes
 
 
 def test_config2_skewed_1m_x128_k10(lpq, oracle):
@@ -96,11 +96,25 @@ def test_config4_scaled_10m_x96_batch_sweep(lpq, oracle):
 
 def test_config5_product_x256_ip_k100(lpq, oracle):
     """d = 256, inner product, k = 100 on the bimodal product-embedding recipe.  The corpus is
-    8M rows by default (about a minute with the oracle); LPQ_TEST_CONFIG5_ROWS sets another size
-    (from 17M rows on, byte offsets into the codes pass 2^32); LPQ_TEST_FULL_100M=1 runs all 100M
-    rows (25.6 GB of codes; the oracle then needs several minutes and ~130 GB of host memory)."""
-    n = 100_000_000 if os.environ.get("LPQ_TEST_FULL_100M") == "1" else int(os.environ.get("LPQ_TEST_CONFIG5_ROWS", 8_000_000))
-    _full_case(lpq, oracle, synth.PRODUCT_100M.scaled(n=n, nq=1000), 100, "absmax", "per_feature", sample=4)
+    20M rows by default: 5.1 GB of codes, so byte offsets into them pass 2^32 (they do from 16.8M
+    rows on) in the batched scan, in the two-wave row-split scan of a 16-query batch and in the
+    gathered-distance call, whose listed ids include the last rows.  LPQ_TEST_CONFIG5_ROWS sets
+    another size; LPQ_TEST_FULL_100M=1 runs all 100M rows (25.6 GB of codes; the oracle then needs
+    several minutes and ~130 GB of host memory)."""
+    n = 100_000_000 if os.environ.get("LPQ_TEST_FULL_100M") == "1" else int(os.environ.get("LPQ_TEST_CONFIG5_ROWS", 20_000_000))
+    w = synth.PRODUCT_100M.scaled(n=n, nq=1000)
+    print(f"[{w.name}] {n} rows x {w.d}: {n * 256 / 2**30:.2f} GiB of codes", flush=True)
+    index, q, ids, codes, qcodes = _full_case(lpq, oracle, w, 100, "absmax", "per_feature", sample=4, batches=(16,))
+    # distances to listed items, the lists naming rows on both sides of the 4 GiB byte offset and the last rows
+    m, nqg = 64, 8
+    gids = np.random.default_rng(5).integers(0, n, size=(nqg, m), dtype=np.int64)
+    gids[:, :8] = n - 1 - np.arange(8)
+    gids[:, 8:16] = min(n - 1, (1 << 32) // 256) + np.arange(-4, 4)
+    gids = np.ascontiguousarray(np.clip(gids, 0, n - 1).astype(np.int32))
+    qc = np.ascontiguousarray(qcodes[:nqg])
+    for metric in ("ip", "l2sq"):
+        got = index.gather_dist(torch.from_numpy(qc).cuda(), torch.from_numpy(gids).cuda(), metric).cpu().numpy()
+        assert np.array_equal(got, oracle.gather_dist(codes, qc, gids, metric))
 
 
 def test_config4_scaled_10m_x96_packed_4bit(lpq, oracle):

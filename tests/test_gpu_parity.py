@@ -545,11 +545,18 @@ def test_fp32_exact_search_within_tolerance(lpq, oracle, name, n, nq, k, metric)
     ids, dists = lpq.search_f32(x.cuda(), q.cuda(), k, metric)
     oids, odists = oracle.search_f32(x.numpy(), q.numpy(), k, metric, threads=16)
     ids, dists = ids.cpu().numpy(), dists.cpu().numpy()
-    # distances, rank by rank, within the stated relative tolerance; for the inner product
-    # "relative" is to |q||x| (= 1 for the unit-length vectors used here), since the sum cancels
-    scale = np.abs(odists) if metric == "l2sq" else np.maximum(np.abs(odists), 1.0)
-    assert np.all(np.abs(dists - odists) <= REL_TOL_F32 * scale)
-    # ids must agree wherever the neighbouring distances are separated by more than the tolerance
+    # distances, rank by rank, within the stated relative tolerance 1e-5 of the value itself; only
+    # inner products below 0.1 in magnitude (the sum cancels there) are held to 1e-5 of |q||x|
+    # instead (= 1 for the unit-length vectors used with that metric)
+    err = np.abs(dists.astype(np.float64) - odists.astype(np.float64))
+    mag = np.abs(odists.astype(np.float64))
+    strict = mag >= 0.1 if metric == "ip" else np.ones_like(mag, bool)
+    worst = float((err[strict] / mag[strict]).max()) if strict.any() else 0.0
+    print(f"[fp32 {name} {metric}] worst relative error on distances {worst:.3e} "
+          f"({int(strict.sum())} of {strict.size} held to the strict form)", flush=True)
+    assert worst <= REL_TOL_F32
+    assert np.all(err[~strict] <= REL_TOL_F32)
+    # every reported id has the reported distance, and ids are distinct
     xs, qs = x.numpy().astype(np.float64), q.numpy().astype(np.float64)
     for i in range(nq):
         if metric == "l2sq":
@@ -558,8 +565,17 @@ def test_fp32_exact_search_within_tolerance(lpq, oracle, name, n, nq, k, metric)
             mine = xs[ids[i]] @ qs[i]
         np.testing.assert_allclose(mine, odists[i], rtol=4 * REL_TOL_F32, atol=4 * REL_TOL_F32 * (metric == "ip"))
         assert len(set(ids[i].tolist())) == k
-    agree = (ids == oids).mean()
-    assert agree > 0.98
+    # ids equal the oracle's wherever its neighbouring binary64 distances are separated by more
+    # than 4e-5 relative (the reference set S_E is unique there)
+    od = odists.astype(np.float64)
+    gap = np.abs(np.diff(od, axis=1))
+    sep = gap > 4 * REL_TOL_F32 * np.maximum(np.maximum(np.abs(od[:, 1:]), np.abs(od[:, :-1])), 1e-30)
+    clear = np.ones_like(od, bool)
+    clear[:, 1:] &= sep
+    clear[:, :-1] &= sep
+    assert np.array_equal(ids[clear], oids[clear])
+    print(f"[fp32 {name} {metric}] ranks with separated neighbours: {clear.mean():.3f}", flush=True)
+    assert clear.mean() > 0.8                                    # and that covers most ranks
 
 
 def test_recall_of_int8_against_fp32_on_gpu(lpq, oracle):
