@@ -163,6 +163,22 @@ int lpq_search(const lpq_index *idx, const float *q_dev, int64_t nq, int64_t ld,
                int metric, int32_t *ids_dev, int32_t *dist_dev, void *workspace_dev,
                size_t workspace_bytes, void *stream);
 
+/* lpq_search for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results
+ * and errors as lpq_search, but the intermediates (query codes, group maxima, candidate lists or
+ * regions, counters) live in a device array that is part of the library: LPQ_STATIC_WORKSPACE_BYTES
+ * on every GPU the library is used on, held until the process ends.  The call allocates nothing
+ * (no hipMalloc / hipFree, no allocating library routine) and is kernel launches only, after one
+ * hipGetSymbolAddress per device on the first call there.  A search whose plan needs more than
+ * LPQ_STATIC_WORKSPACE_BYTES (lpq_search_workspace_bytes tells) returns LPQ_ERANGE and launches
+ * nothing: the limit is meant for small batches (e.g. 1M x 128: up to 256 queries at k = 10, 64 at
+ * k = 100).  All calls on one GPU share the array, which keeps the previous call's contents (every
+ * counter in it is cleared by the kernels that precede its use): calls that overlap on one GPU -
+ * different streams, or different threads - race; serialise them on one stream. */
+#define LPQ_STATIC_WORKSPACE_BYTES (64u << 20)
+int lpq_search_static(const lpq_index *idx, const float *q_dev, int64_t nq, int64_t ld, int k,
+                      int metric, int32_t *ids_dev, int32_t *dist_dev, void *stream);
+
 /* Same, for queries that are already codes (int8, row stride ld bytes). */
 int lpq_search_i8(const lpq_index *idx, const int8_t *qcodes_dev, int64_t nq, int64_t ld, int k,
                   int metric, int32_t *ids_dev, int32_t *dist_dev, void *workspace_dev,

@@ -961,6 +961,51 @@ extern "C" int lpq_search(const lpq_index *idx, const float *q_dev, int64_t nq, 
                               (hipStream_t)stream);
 }
 
+// ---- search without any allocation: the workspace is a device array of the library ----
+// One copy of the array exists on every GPU the library is loaded on, at that GPU's own address;
+// in host code the array's name is only a handle for hipGetSymbolAddress, never an address.
+static __device__ __align__(256) unsigned char scratch[LPQ_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[MAX_DEVICES];   // device address of `scratch` on device i, once looked up
+
+// Device address of `scratch` on the current device (looked up once per device, with that device current).
+int scratch_address(void **out)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(LPQ_EDEVICE, "device ordinal %d outside 0..%d", dev, MAX_DEVICES - 1);
+    std::lock_guard<std::mutex> l(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(LPQ_EDEVICE, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return LPQ_OK;
+}
+}  // namespace
+
+extern "C" int lpq_search_static(const lpq_index *idx, const float *q_dev, int64_t nq, int64_t ld, int k, int metric,
+                                 int32_t *ids_dev, int32_t *dist_dev, void *stream)
+{
+    int rc = check_search_args(idx, q_dev, nq, ld, k, metric, ids_dev, dist_dev);
+    if (rc) return rc;
+    if (nq == 0) return LPQ_OK;
+    const size_t need = idx->packed ? make_packed_plan(idx, nq, k).total : make_plan(idx, nq, k).total;
+    if (need > (size_t)LPQ_STATIC_WORKSPACE_BYTES)
+        return fail(LPQ_ERANGE, "this search needs %zu bytes of workspace, the built-in one holds %zu: use lpq_search",
+                    need, (size_t)LPQ_STATIC_WORKSPACE_BYTES);
+    void *ws = nullptr;
+    rc = scratch_address(&ws);
+    if (rc) return rc;
+    return search_f32_queries(idx, q_dev, nq, ld, k, metric, ids_dev, dist_dev, ws, (size_t)LPQ_STATIC_WORKSPACE_BYTES,
+                              (hipStream_t)stream);
+}
+
 extern "C" int lpq_search_overflow_stats(const lpq_index *idx, int64_t nq, int k, int metric, const void *workspace_dev,
                                          int64_t *redone_queries, int64_t *max_region_fill)
 {

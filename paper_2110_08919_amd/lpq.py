@@ -62,6 +62,7 @@ def lib() -> C.CDLL:
             "lpq_index_data": (i32, [vp, C.POINTER(vp), C.POINTER(i64), C.POINTER(vp)]),
             "lpq_search_workspace_bytes": (C.c_size_t, [vp, i64, i32, i32]),
             "lpq_search": (i32, [vp, vp, i64, i64, i32, i32, vp, vp, vp, C.c_size_t, vp]),
+            "lpq_search_static": (i32, [vp, vp, i64, i64, i32, i32, vp, vp, vp]),
             "lpq_search_i8": (i32, [vp, vp, i64, i64, i32, i32, vp, vp, vp, C.c_size_t, vp]),
             "lpq_search_f32_workspace_bytes": (C.c_size_t, [i64, i64, i32, i32]),
             "lpq_search_f32": (i32, [vp, i64, i64, vp, i64, i64, i32, i32, i32, vp, vp, vp, C.c_size_t, vp]),
@@ -282,6 +283,19 @@ class Index:
         _check(fn(self._h, p, nq, ld, k, METRIC[metric], ids.data_ptr(), dists.data_ptr(),
                   ws.data_ptr(), ws.numel(), _stream()))
         return ids, dists
+
+    def search_static(self, q: torch.Tensor, k: int, metric="l2sq", out=None):
+        """lpq_search_static: fp32 queries, the library's built-in workspace, no allocation inside the call
+        (pass `out` to keep this wrapper from allocating the result tensors either)."""
+        p, nq, ld = _dev_matrix(q, torch.float32)
+        ids, dists = out if out is not None else (
+            torch.empty((nq, k), dtype=torch.int32, device=q.device),
+            torch.empty((nq, k), dtype=torch.int32, device=q.device))
+        _check(lib().lpq_search_static(self._h, p, nq, ld, k, METRIC[metric], ids.data_ptr(), dists.data_ptr(), _stream()))
+        return ids, dists
+
+
+STATIC_WORKSPACE_BYTES = 64 << 20
 
 
 def rerank_f32(x: torch.Tensor, q: torch.Tensor, cand_ids: torch.Tensor, k: int, metric="l2sq"):
