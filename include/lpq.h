@@ -171,7 +171,7 @@ int lpq_search(const lpq_index *idx, const float *q_dev, int64_t nq, int64_t ld,
  * (no hipMalloc / hipFree, no allocating library routine) and is kernel launches only, after one
  * hipGetSymbolAddress per device on the first call there.  A search whose plan needs more than
  * LPQ_STATIC_WORKSPACE_BYTES (lpq_search_workspace_bytes tells) returns LPQ_ERANGE and launches
- * nothing: the limit is meant for small batches (e.g. 1M x 128: up to 256 queries at k = 10, 64 at
+ * nothing: the limit is meant for small batches (e.g. 1M x 128: up to 256 queries at k = 10, 48 at
  * k = 100).  All calls on one GPU share the array, which keeps the previous call's contents (every
  * counter in it is cleared by the kernels that precede its use): calls that overlap on one GPU -
  * different streams, or different threads - race; serialise them on one stream. */
@@ -233,7 +233,8 @@ int lpq_rerank_f32(const float *x_dev, int64_t n, int64_t ldx, const float *q_de
  *   LPQ_TUNE_DRY_RUN     timing ablations of the matrix-core kernel whose results are meaningless
  *                        (1 never collects a candidate, 2 no workgroup barrier, 3 no corpus
  *                        copies, 4 neither, 5 candidates detected but not queued, 6 queued but
- *                        not processed).  Compiled only into builds made with -DLPQ_ABLATION
+ *                        not processed, 7 every copy reads the first two stages of its split, which
+ *                        stay in L2).  Compiled only into builds made with -DLPQ_ABLATION
  *                        (python -m paper_2110_08919_amd.build --ablation writes
  *                        liblpq_ablation.so); the shipped library has none of these branches
  *                        and rejects a non-zero value with LPQ_EINVAL.
@@ -261,6 +262,30 @@ enum { LPQ_PROFILE_SCAN = 0, LPQ_PROFILE_SEED = 1 };
 int lpq_profile_enable(int on);
 int lpq_profile_read(int64_t *launches, double *total_ms);
 int lpq_profile_read_kind(int kind, int64_t *launches, double *total_ms);
+
+/* How lpq_search would run a search, computed on the host without any device or index: the plan
+ * for nq queries and k results on an index of n_items items of d features at `bits` bits (packed:
+ * two codes per byte).  For capacity planning (out[16] is what lpq_search_workspace_bytes would
+ * return less its 256 bytes of alignment slack) and for checking the planner itself.  out receives
+ * LPQ_PLAN_INFO_COUNT values:
+ *   [0] kernel family (0 generic dot-product kernel, 1 matrix-core with lists in LDS, 2 matrix-core
+ *       with lists in registers, 3 matrix-core collecting scan)   [1] row-split workgroups (0/1)
+ *   [2] waves of a row-split workgroup   [3] queries per wave of the collecting scan
+ *   [4] query rows the workspace holds (padded)   [5] rows of the threshold-seeding pass (0 = none)
+ *   [6] corpus splits of the seeding pass   [7] corpus splits of the main scan   [8] segments per split
+ *   and [9] group maxima per query of the seeding pass   [10] candidate regions per query and
+ *   [11] their capacity (collecting scan)   [12] splits of the generic redo   [13] splits of the
+ *   register-list redo   [14] further rounds of the collecting scan   [15] lists merged per workgroup
+ *   in a first merge pass (0 = one pass)   [16] workspace bytes   [17] offset of the per-tile plan
+ *   inside the workspace (packed index; else 0)
+ *   [18..33] byte offsets of the plan's buffers in the order they are laid out (0 = not used), [34]
+ *   their end.  Every offset is a multiple of 256 and the used ones never decrease.  (A packed
+ *   index is searched in tiles of 64 queries unless one collecting scan takes the whole batch: the
+ *   values then describe the plan of a full tile, [4], [16] and [17] the whole workspace.)
+ * LPQ_EINVAL / LPQ_ERANGE as for lpq_quantizer_create, lpq_index_create and lpq_search. */
+#define LPQ_PLAN_INFO_COUNT 35
+int lpq_search_plan_info(int d, int bits, int packed, int64_t n_items, int64_t nq, int k, int64_t *out,
+                         int out_count);
 
 /* Attainable-rate probes (benchmarks only): what this GPU sustains on the two resources that
  * bound lpq_search, measured by kernels that do nothing else, so that a roofline fraction quoted

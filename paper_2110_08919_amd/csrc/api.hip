@@ -305,6 +305,12 @@ extern "C" void lpq_index_destroy(lpq_index *idx)
     delete idx;
 }
 
+// Row length an index stores d features in: a length the matrix-core scans have where one exists.
+static int padded_row_length(int d)
+{
+    return d <= 64 ? 64 : d <= 96 ? 96 : d <= 128 ? 128 : d <= 192 ? 192 : d <= 256 ? 256 : (int)round_up(d, 32);
+}
+
 static int index_create_impl(lpq_index **out, const lpq_quantizer *q, int64_t capacity, bool packed)
 {
     if (!out || !q) return fail(LPQ_EINVAL, "null argument");
@@ -321,8 +327,7 @@ static int index_create_impl(lpq_index **out, const lpq_quantizer *q, int64_t ca
     // Rows are zero padded to a length the matrix-core scans have (64, 96, 128, 192 or 256 bytes):
     // up to 256 features never fall back to the generic kernel, which is ~100x slower on large
     // batches; the price is up to 2x the row bytes for d <= 32 and 20 % for 129..160.
-    idx->d_pad = q->d <= 64 ? 64 : q->d <= 96 ? 96 : q->d <= 128 ? 128 : q->d <= 192 ? 192 :
-                 q->d <= 256 ? 256 : (int)round_up(q->d, 32);
+    idx->d_pad = padded_row_length(q->d);
     idx->capacity = capacity;
     idx->cap_rows = round_up(capacity, 256) + 256;  // whole tiles may be read past the last item
     const size_t code_bytes = (size_t)idx->cap_rows * idx->d_pad / (packed ? 2 : 1);
@@ -917,6 +922,41 @@ int search_packed(const lpq_index *idx, const PackedPlan &pp, char *ws, int64_t 
 }
 
 }  // namespace
+
+extern "C" int lpq_search_plan_info(int d, int bits, int packed, int64_t n_items, int64_t nq, int k, int64_t *out,
+                                    int out_count)
+{
+    if (!out || out_count < LPQ_PLAN_INFO_COUNT) return fail(LPQ_EINVAL, "out must hold LPQ_PLAN_INFO_COUNT values");
+    if (d < 1 || bits < 1 || bits > 8) return fail(LPQ_EINVAL, "d < 1 or bits outside 1..8");
+    if (d > MAX_D) return fail(LPQ_ERANGE, "d = %d > %d", d, (int)MAX_D);
+    if (packed && (bits > 4 || d > MAX_D_PACKED)) return fail(LPQ_EINVAL, "packed storage: at most 4 bits and %d features", (int)MAX_D_PACKED);
+    if (n_items < 1 || n_items >= (int64_t(1) << 31) - 1024) return fail(LPQ_ERANGE, "n_items outside 1 .. 2^31 - 1025");
+    if (nq < 0 || k < 1) return fail(LPQ_EINVAL, "nq < 0 or k < 1");
+    if (k > MAX_K || k > n_items || (packed && k > MAX_K_PACKED)) return fail(LPQ_ERANGE, "k = %d out of range", k);
+    lpq_index shape;                     // a description only: no device memory behind it
+    shape.d = d; shape.bits = bits; shape.packed = packed != 0;
+    shape.d_pad = padded_row_length(d);
+    shape.capacity = shape.size = n_items;
+    Plan p = make_plan(&shape, nq, k);
+    size_t total = p.total, base = 0;
+    int64_t nq_rows = p.nq_pad;
+    if (shape.packed) {   // searched in tiles of 64 queries unless one collecting scan takes the whole batch
+        const PackedPlan pp = make_packed_plan(&shape, nq, k);
+        total = pp.total;
+        base = pp.off_tile;
+        nq_rows = pp.nq_pad;
+        if (!(p.mode == PLAN_MFMA_COLLECT && !p.rsplit)) p = make_plan(&shape, nq < PACKED_TILE ? nq : PACKED_TILE, k);
+    }
+    const int64_t v[LPQ_PLAN_INFO_COUNT] = {
+        p.mode, p.rsplit ? 1 : 0, p.rs_waves, p.wave_queries, nq_rows, p.seed_rows, p.S1, p.S2, p.SEG, p.G, p.SS, p.Cs,
+        p.Sg, p.Sr, p.rounds, p.merge_group, (int64_t)total, (int64_t)base,
+        (int64_t)p.off_qcodes, (int64_t)p.off_qnorms, (int64_t)p.off_lists1, (int64_t)p.off_seedlist, (int64_t)p.off_seeds,
+        (int64_t)p.off_lists2, (int64_t)p.off_gmax, (int64_t)p.off_merge_tmp, (int64_t)p.off_cbuf, (int64_t)p.off_ccnt,
+        (int64_t)p.off_over, (int64_t)p.off_qlist, (int64_t)p.off_redo, (int64_t)p.off_bounds2, (int64_t)p.off_over2,
+        (int64_t)p.off_qlist2, (int64_t)p.total};
+    for (int i = 0; i < LPQ_PLAN_INFO_COUNT; ++i) out[i] = v[i];
+    return LPQ_OK;
+}
 
 extern "C" size_t lpq_search_workspace_bytes(const lpq_index *idx, int64_t nq, int k, int metric)
 {

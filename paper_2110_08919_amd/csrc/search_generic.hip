@@ -503,6 +503,10 @@ __global__ __launch_bounds__(256) void collect_refine_kernel(
 // query; every wave takes k times the smallest head among its share of the lists (each lane owns
 // the lists first + lane, first + lane + 64, ...), then wave 0 does the same over the four wave
 // results.  Duplicated values come out once per copy, as a sort would give them.
+// A lane keeps the head and the position of each of its LPL lists in registers, so a round costs the
+// winner one LDS read (the next entry of the list it took from) instead of a walk over positions and
+// heads in LDS (512 lists of 10: 16.9 -> see the profile of the small-batch workload).
+template <int LPL>
 __global__ __launch_bounds__(256) void merge_sorted_kernel(
     const cand_t *__restrict__ lists, int P, int k, const cand_t *__restrict__ extra,
     cand_t *__restrict__ out_lists, cand_t *__restrict__ seeds_out, int32_t *__restrict__ ids,
@@ -512,44 +516,47 @@ __global__ __launch_bounds__(256) void merge_sorted_kernel(
     const int Pt = P + (extra ? 1 : 0);
     cand_t *buf = reinterpret_cast<cand_t *>(smem);     // [Pt][k]
     cand_t *wres = buf + (size_t)Pt * k;                // [4][k]
-    int *pos = reinterpret_cast<int *>(wres + 4 * k);   // [Pt] entries already taken from each list
     const int64_t q = blockIdx.x;
     const int m = P * k, mt = Pt * k;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int i = threadIdx.x; i < mt; i += 256) buf[i] = (i < m) ? lists[q * m + i] : extra[q * k + (i - m)];
-    for (int i = threadIdx.x; i < Pt; i += 256) pos[i] = 0;
     __syncthreads();
 
-    const int lpw = (Pt + 3) >> 2;
+    const int lpw = (Pt + 3) >> 2;                      // lists per wave, <= 64 LPL
     const int first = wave * lpw, last = (first + lpw < Pt) ? first + lpw : Pt;
-    cand_t best = CAND_NONE;
-    int bl = -1;
-    for (int l = first + lane; l < last; l += 64) {
-        const cand_t c = buf[(size_t)l * k];
-        if (bl < 0 || c < best) { best = c; bl = l; }
+    cand_t head[LPL];
+    int pos[LPL];
+#pragma unroll
+    for (int j = 0; j < LPL; ++j) {
+        const int l = first + lane + 64 * j;
+        pos[j] = 0;
+        head[j] = (l < last) ? buf[(size_t)l * k] : CAND_NONE;
     }
     for (int r = 0; r < k; ++r) {
+        cand_t best = head[0];
+#pragma unroll
+        for (int j = 1; j < LPL; ++j) best = head[j] < best ? head[j] : best;
         const cand_t mn = wave_min_cand(best);
         const int win = __ffsll((unsigned long long)__ballot(best == mn)) - 1;
         if (lane == win) {
             wres[wave * k + r] = mn;
-            if (bl >= 0 && mn != CAND_NONE) {
-                pos[bl] += 1;
-                best = CAND_NONE;
-                int nb = bl;
-                for (int l = first + lane; l < last; l += 64) {
-                    const int pp = pos[l];
-                    const cand_t c = (pp < k) ? buf[(size_t)l * k + pp] : CAND_NONE;
-                    if (c < best) { best = c; nb = l; }
+            if (mn != CAND_NONE) {
+                bool taken = false;                     // the first of my lists whose head is the minimum moves on
+#pragma unroll
+                for (int j = 0; j < LPL; ++j) {
+                    if (!taken && head[j] == mn) {
+                        taken = true;
+                        pos[j] += 1;
+                        head[j] = (pos[j] < k) ? buf[(size_t)(first + lane + 64 * j) * k + pos[j]] : CAND_NONE;
+                    }
                 }
-                bl = nb;
             }
         }
     }
     __syncthreads();
     if (wave != 0) return;
     int p2 = 0;
-    best = (lane < 4) ? wres[lane * k] : CAND_NONE;
+    cand_t best = (lane < 4) ? wres[lane * k] : CAND_NONE;
     for (int r = 0; r < k; ++r) {
         const cand_t mn = wave_min_cand(best);
         const int win = __ffsll((unsigned long long)__ballot(best == mn)) - 1;
@@ -601,7 +608,7 @@ int merge_max_lists(int k) { return 4096 / k - 1; }
 
 // Lists of k that are each sorted and short (k <= 32) merge by repeated extraction, which needs
 // no power-of-two buffer: as many lists as 128 KB of LDS hold, at most 1024.
-static size_t merge_sorted_lds(int lists, int k) { return (size_t)(lists + 4) * k * sizeof(cand_t) + (size_t)lists * sizeof(int); }
+static size_t merge_sorted_lds(int lists, int k) { return (size_t)(lists + 4) * k * sizeof(cand_t); }
 int merge_max_sorted_lists(int k)
 {
     if (k > 32) return merge_max_lists(k);
@@ -681,16 +688,23 @@ hipError_t launch_merge(const cand_t *lists, int64_t nq, int P, int k, const can
     if (!only && !gate_count && sorted_lists && k <= 32 && total >= 1024 && P <= merge_max_sorted_lists(k)) {   // many short sorted lists
         const int Pt = P + (extra_lists ? 1 : 0);
         const size_t lds = merge_sorted_lds(Pt, k);
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(merge_sorted_kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
-        merge_sorted_kernel<<<(unsigned)nq, 256, lds, st>>>(lists, P, k, extra_lists, out_lists, seeds_out, ids,
-                                                           dists, qnorms, metric);
-        return hipGetLastError();
+        const int lpl = (int)ceil_div(ceil_div(Pt, 4), 64);   // lists a lane owns
+        static bool attr_set[4] = {false, false, false, false};   // per instantiation
+        auto launch = [&](auto kern, int slot) -> hipError_t {
+            if (!attr_set[slot]) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                if (e != hipSuccess) return e;
+                attr_set[slot] = true;
+            }
+            kern<<<(unsigned)nq, 256, lds, st>>>(lists, P, k, extra_lists, out_lists, seeds_out, ids, dists, qnorms, metric);
+            return hipGetLastError();
+        };
+        if (lpl <= 1) return launch(merge_sorted_kernel<1>, 0);
+        if (lpl <= 2) return launch(merge_sorted_kernel<2>, 1);
+        if (lpl <= 4) return launch(merge_sorted_kernel<4>, 2);
+        if (lpl <= 8) return launch(merge_sorted_kernel<8>, 3);
+        return hipErrorInvalidValue;   // more than 2048 lists: merge_max_sorted_lists allows 1024
     }
     const int cap = next_pow2(total < 2 ? 2 : total);
     if (cap > 4096) return hipErrorInvalidValue;

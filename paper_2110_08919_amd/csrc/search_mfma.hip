@@ -71,6 +71,29 @@ namespace {
 #define LPQ_DRY(a) 0
 #endif
 
+// After the thresholds have been re-read from LDS on a rare path: wait for them there, as an
+// instruction the compiler's wait-count bookkeeping sees.  Otherwise the registers count as "load
+// pending" where the rare path rejoins the common one, and every later threshold compare of the
+// common path gets a "wait for all LDS loads" in front of it, also right after the operand loads of
+// the next row block were issued.  (Measured: the same time either way on the benchmark workload -
+// those loads have returned by then; kept so that the common path only waits where it consumes.)
+#define LPQ_LGKM_SETTLED() __builtin_amdgcn_s_waitcnt(0xC07F)   /* lgkmcnt(0); vmcnt, expcnt untouched */
+
+// Instruction order of one chain and the filter epilogue of the chain before it (one scheduling
+// region: it ends at the epilogue's branch): two matrix instructions first, then the max tree in the
+// shadow of the second one, then the remaining matrix instructions with the rest of the vector work
+// between them; without it the compiler puts seven of the nine vector instructions and the idle
+// cycles their operands need behind the first matrix instruction.  Measured on one box (main scan of
+// the benchmark workload): 0.934 -> 0.917 ms; 1.2M x 100, inner product: 1.101 -> 1.079 ms.
+#define LPQ_SCHED_CHAIN()                                                                               \
+    do {                                                                                                \
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   /* 2 matrix instructions */                \
+        __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);   /* 5 vector instructions */                \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                              \
+        __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);                                              \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                              \
+    } while (0)
+
 constexpr int NQW = 64;      // queries per wave in list mode = lanes per wave: lane q owns query q
 constexpr int TRIG = 32;     // queue fill that asks for a joint drain at the next stage boundary
 constexpr int SVCAP = 128;   // compacted candidates buffered before they are handed to owners
@@ -438,7 +461,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     do {                                                                                                \
         const int st_ = (ST);                                                                           \
         const int64_t r0_ = pieces ? ((int64_t)s + (int64_t)S * 8 * st_) * o.piece_stride                \
-                                   : rs + (int64_t)st_ * sstride;                                       \
+                                   : rs + (int64_t)(LPQ_DRY(a) == 7 ? (st_ & 1) : st_) * sstride;       \
         const int ring_slot_ = st_ % NST;                                                               \
         const int8_t *src_ = a.codes + r0_ * ROWB;                                                      \
         _Pragma("unroll") for (int j = 0; j < IPW; ++j)                                                 \
@@ -505,11 +528,13 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
             } else {                                                                                    \
                 bool trip = m >= thr[nb];                                                               \
                 unsigned long long mask = __ballot(trip);                                               \
-                if (mask) {                                                                             \
+                LPQ_SCHED_CHAIN();                                                                      \
+                if (__builtin_expect(mask != 0, 0)) {   /* rare: laid out off the hot path */           \
                     if (qcnt + __popcll(mask) > QCAP) { /* no room: this wave drains alone */           \
                         if (LPQ_DRY(a) < 5) drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs); \
                         qcnt = 0;                                                                       \
                         _Pragma("unroll") for (int j = 0; j < NB; ++j) thr[j] = w.thrE[j * 32 + col];   \
+                        LPQ_LGKM_SETTLED();                                                             \
                         trip = m >= thr[nb];                                                            \
                         mask = __ballot(trip);                                                          \
                     }                                                                                   \
@@ -670,6 +695,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
                     qcnt = 0;
 #pragma unroll
                     for (int j = 0; j < NB; ++j) thr[j] = w.thrE[j * 32 + col];
+                    LPQ_LGKM_SETTLED();
                 }
             }
             if (t + 1 < T) LPQ_LOAD_BLOCK(t + 1, 0, A0, C0, P0);

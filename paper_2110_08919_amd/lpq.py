@@ -74,6 +74,7 @@ def lib() -> C.CDLL:
             "lpq_profile_enable": (i32, [i32]),
             "lpq_profile_read": (i32, [C.POINTER(i64), C.POINTER(C.c_double)]),
             "lpq_profile_read_kind": (i32, [i32, C.POINTER(i64), C.POINTER(C.c_double)]),
+            "lpq_search_plan_info": (i32, [i32, i32, i32, i64, i64, i32, C.POINTER(i64), i32]),
             "lpq_probe_mfma_i8": (i32, [vp, C.c_size_t, i32, C.POINTER(C.c_double), vp]),
             "lpq_probe_stream": (i32, [vp, C.c_size_t, i32, i32, C.POINTER(C.c_double), vp]),
             "lpq_last_error": (C.c_char_p, []),
@@ -123,6 +124,16 @@ def profile_read(kind=None):
     else:
         _check(lib().lpq_profile_read_kind(kind, C.byref(n), C.byref(ms)))
     return n.value, ms.value
+
+
+PLAN_INFO_COUNT = 35
+
+
+def search_plan_info(d: int, bits: int, packed: bool, n_items: int, nq: int, k: int):
+    """lpq_search_plan_info: the plan of a search as a list of PLAN_INFO_COUNT integers (no device needed)."""
+    out = (C.c_int64 * PLAN_INFO_COUNT)()
+    _check(lib().lpq_search_plan_info(d, bits, 1 if packed else 0, n_items, nq, k, out, PLAN_INFO_COUNT))
+    return list(out)
 
 
 def probe_mfma_i8(operands: torch.Tensor = None, iters: int = 50000) -> float:
