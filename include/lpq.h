@@ -47,7 +47,7 @@ enum {
 
 /* How the range [S_b, S_e] and the offset k of Equation 1 are learned.
  *   MINMAX  S_b = min, S_e = max, k = (min + max) / 2: the observed range (Section 1,
- *           "the range of values that appear in practice").
+ *           the value range the data actually occupies).
  *   ABSMAX  S_b = -A, S_e = +A, k = 0 with A the absolute maximum observed in the
  *           dimension (Section 4.2).
  *   GAUSS   S_b = mu - c sigma, S_e = mu + c sigma, k = mu, with the maximum-likelihood
@@ -62,9 +62,9 @@ enum { LPQ_CALIB_MINMAX = 0, LPQ_CALIB_ABSMAX = 1, LPQ_CALIB_GAUSS = 2, LPQ_CALI
 
 /* PER_FEATURE: constants per dimension (the superscripts i of Equation 1).
  * GLOBAL: one set of constants from all n*d values, for all dimensions (Section 4.1).
- * SHARED_WIDTH: an offset per dimension and one scale for all of them - the "normalization
- *   constants for both scale and offset" that the end of Section 3.2 asks for when dimensions
- *   differ.  The PER_FEATURE constants are learned first; then every range keeps its centre
+ * SHARED_WIDTH: an offset per dimension and one scale for all of them - a reading of the end of
+ *   Section 3.2, which asks for extra per-dimension constants (scale as well as offset) when the
+ *   dimensions differ much.  The PER_FEATURE constants are learned first; then every range keeps its centre
  *   (S_b + S_e) / 2 and takes the half-width of the widest range, H = max_i (S_e - S_b) / 2
  *   (binary64 on the binary32 constants): S_b = fl32(centre - H), S_e = fl32(centre + H),
  *   k unchanged.  One code step then has the same length in every dimension, so L2SQ on codes
@@ -187,7 +187,11 @@ int lpq_search_i8(const lpq_index *idx, const int8_t *qcodes_dev, int64_t nq, in
 /* Exact search on the original fp32 vectors (the reference set S_E of the recall
  * definition, Section 5.3): x_dev[n][ldx], q_dev[nq][ldq], fp32 arithmetic (the squared
  * distance is summed directly as (q - x)^2, never through norms).  dist_dev [nq][k] fp32,
- * L2SQ ascending / IP descending, ties to the lower id.  1 <= k <= min(n, 1024). */
+ * L2SQ ascending / IP descending, ties to the lower id.  1 <= k <= min(n, 1024).  A workgroup keeps
+ * a query vector and its candidate buffer in 64 KB of LDS, which bounds d: at most 15 328 features
+ * for k <= 256, 12 256 for k = 1024 (in between: (65 408 - 8 c) / 4 rounded down to a multiple of 4,
+ * c = the power of two >= max(2 k, k + 256)); beyond that LPQ_ERANGE, and the workspace query
+ * returns 0. */
 size_t lpq_search_f32_workspace_bytes(int64_t n, int64_t nq, int d, int k);
 int lpq_search_f32(const float *x_dev, int64_t n, int64_t ldx, const float *q_dev, int64_t nq,
                    int64_t ldq, int d, int k, int metric, int32_t *ids_dev, float *dist_dev,

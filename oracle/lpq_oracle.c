@@ -15,11 +15,11 @@
  *   calibration   Section 3.2 (Gaussian maximum likelihood: S_b = mu - sigma,
  *                 S_e = mu + sigma, k = mu), Section 4.1 (one mu, sigma for all
  *                 dimensions), Section 4.2 (absolute maximum per dimension),
- *                 plus the [min, max] reading of "the range of values that appear
- *                 in practice" (Section 1); and, for the closing remark of Section
- *                 3.2 (data with high interdimensional variance need constants for
- *                 both scale and offset), a scope with one offset per dimension and
- *                 one range width for all of them.
+ *                 plus the [min, max] reading of Section 1 (the value range the
+ *                 data actually occupies); and, for the closing remark of Section
+ *                 3.2 (dimensions that differ much need extra per-dimension
+ *                 constants, for scale as well as offset), a scope with one offset
+ *                 per dimension and one range width for all of them.
  *   encode        Equation 1, evaluated in IEEE binary32 as two rounded
  *                 operations t = (x - k) * m with m = fl32(2^B / (S_e - S_b)),
  *                 then floor; the result +2^(B-1) of the upper clamp is kept for

@@ -1110,7 +1110,7 @@ extern "C" int lpq_search_i8(const lpq_index *idx, const int8_t *qcodes_dev, int
 // -------------------------------------------------------------------- fp32 exact ----
 extern "C" size_t lpq_search_f32_workspace_bytes(int64_t n, int64_t nq, int d, int k)
 {
-    if (n < 1 || nq < 0 || d < 1 || k < 1 || k > MAX_K || k > n) return 0;
+    if (n < 1 || nq < 0 || d < 1 || k < 1 || k > MAX_K || k > n || d > f32_max_d(k)) return 0;
     return f32_workspace_bytes(n, nq, d, k) + 256;
 }
 
@@ -1125,6 +1125,8 @@ extern "C" int lpq_search_f32(const float *x_dev, int64_t n, int64_t ldx, const 
     if (metric != LPQ_METRIC_L2SQ && metric != LPQ_METRIC_IP) return fail(LPQ_EINVAL, "unknown metric %d", metric);
     if (k > n || k > MAX_K) return fail(LPQ_ERANGE, "k = %d out of range", k);
     if (n >= (int64_t(1) << 31) - 1024) return fail(LPQ_ERANGE, "n must stay below 2^31 - 1024");
+    if (d > f32_max_d(k))
+        return fail(LPQ_ERANGE, "d = %d: the fp32 search takes at most %d features for k = %d", d, f32_max_d(k), k);
     if (nq == 0) return LPQ_OK;
     if (!x_dev || !q_dev || !ids_dev || !dist_dev) return fail(LPQ_EINVAL, "null argument");
     if (ldx < d || ldq < d) return fail(LPQ_EINVAL, "row stride smaller than d");

@@ -222,6 +222,7 @@ hipError_t launch_rerank_f32(const float *x, int64_t n, int64_t ldx, const float
 
 // ---- fp32 exact search (search_f32.hip) ---------------------------------------------
 size_t f32_workspace_bytes(int64_t n, int64_t nq, int d, int k);
+int f32_max_d(int k);   // largest d the fp32 search takes for k results (its LDS holds a query and its candidates)
 hipError_t launch_search_f32(const float *x, int64_t n, int64_t ldx, const float *q, int64_t nq,
                              int64_t ldq, int d, int k, int metric, int32_t *ids, float *dists,
                              void *ws, hipStream_t st);

@@ -214,6 +214,14 @@ hipError_t launch_f32_tile(bool vec, unsigned blocks, size_t shmem, hipStream_t 
 
 }  // namespace
 
+// Largest d a search for k results takes: one query's vector and candidate buffer, plus the kernel's
+// 96 bytes of static LDS, must fit the 64 KB a workgroup may use without opting in to more.
+int f32_max_d(int k)
+{
+    const int64_t room = 64 * 1024 - 128 - (int64_t)f32_cap(k) * (int64_t)sizeof(cand_t);
+    return room < 16 ? 0 : (int)(room / 16 * 4);
+}
+
 size_t f32_workspace_bytes(int64_t n, int64_t nq, int d, int k)
 {
     return (size_t)nq * f32_splits(n, nq, d, k) * k * sizeof(cand_t);
@@ -228,7 +236,7 @@ hipError_t launch_search_f32(const float *x, int64_t n, int64_t ldx, const float
     const int cap = f32_cap(k);
     const int64_t split_rows = round_up(ceil_div(n, S), F32_STEP);
     const size_t shmem = (size_t)qt * ((size_t)cap * sizeof(cand_t) + (size_t)((d + 3) / 4) * 16);
-    if (shmem > 64 * 1024) return hipErrorInvalidValue;
+    if (d > f32_max_d(k) || shmem + 128 > 64 * 1024) return hipErrorInvalidValue;   // callers check f32_max_d first
     cand_t *lists = reinterpret_cast<cand_t *>(ws);
     const bool vec = ((uintptr_t)x % 16 == 0) && (ldx % 4 == 0);
     const unsigned blocks = (unsigned)(ceil_div(nq, qt) * S);

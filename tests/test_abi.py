@@ -69,6 +69,18 @@ def test_argument_checks_without_device(L):
     # workspace of the fp32 search: host arithmetic only, grows with the batch
     small, large = L.lpq_search_f32_workspace_bytes(1_000_000, 10, 128, 10), L.lpq_search_f32_workspace_bytes(1_000_000, 1000, 128, 10)
     assert 0 < small <= large
+    # fp32 search: d beyond what a workgroup's LDS holds is refused, and the workspace query says so too
+    assert L.lpq_search_f32(p1, 100, 20000, p1, 1, 20000, 20000, 5, 0, p1, p1, p1, 1 << 20, None) == lpq.ERANGE
+    assert b"at most" in L.lpq_last_error()
+    assert L.lpq_search_f32_workspace_bytes(100, 1, 20000, 5) == 0
+    assert L.lpq_search_f32_workspace_bytes(100, 1, 15328, 5) > 0
+    assert L.lpq_search_f32_workspace_bytes(2000, 1, 12260, 1024) == 0
+    # the plan of a search, on the host: the benchmark shape takes the collecting scan with 128 queries per wave
+    info = lpq.search_plan_info(128, 8, False, 1_000_000, 10_000, 10)
+    assert info[0] == 3 and info[3] == 128 and info[5] > 0 and info[16] > 0
+    assert lpq.search_plan_info(128, 8, False, 1_000_000, 16, 10)[1] == 1          # few queries: row-split workgroups
+    out64 = (C.c_int64 * 35)()
+    assert L.lpq_search_plan_info(128, 8, 0, 1000, 10, 10, out64, 10) == lpq.EINVAL
     # probes: argument checks precede any device work
     out = C.c_double(-1.0)
     assert L.lpq_probe_mfma_i8(None, 0, 100, None, None) == lpq.EINVAL
