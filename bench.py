@@ -247,10 +247,13 @@ def main():
             "mfma_zero_operands_TOPs": lpq.probe_mfma_i8(None),
             "mfma_random_operands_TOPs": lpq.probe_mfma_i8(rnd),
             "mfma_workload_codes_TOPs": lpq.probe_mfma_i8(code_view),
+            "scan_core_loop_workload_codes_TOPs": lpq.probe_scan_core(code_view),
             "stream_global_to_lds_GBps": lpq.probe_stream(buf, 0, 10),
             "stream_register_loads_GBps": lpq.probe_stream(buf, 1, 10),
             "note": "register-resident int8 matrix-instruction loop (operand bits as named; the shader clock falls "
-                    "under matrix load) and a streaming read of 1 GiB; peaks in `roofline` are the published ones",
+                    "under matrix load: the part is power-limited there), the scan's inner loop alone (matrix "
+                    "instructions + filter epilogue + LDS operand reads; no copies, barrier, candidates or query "
+                    "padding) and a streaming read of 1 GiB; peaks in `roofline` are the published ones",
         }
         del buf, rnd
         ref = attainable["mfma_workload_codes_TOPs"] * 1e12 if mfma_frac >= hbm_frac else attainable["stream_global_to_lds_GBps"] * 1e9

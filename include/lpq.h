@@ -301,12 +301,19 @@ int lpq_search_plan_info(int d, int bits, int packed, int64_t n_items, int64_t n
  *     operands_dev[operand_bytes] (device memory, 16-byte aligned; null = all-zero operands): the
  *     sustained rate depends on how many operand bits toggle, so pass the bytes of interest
  *     (random bytes, or the codes of an index).  *tops = 1e12 integer operations per second.
+ *   lpq_probe_scan_core: the inner loop of the batched scan and nothing else - per 32 rows and 128
+ *     queries of a wave sixteen matrix instructions with the filter epilogue (maximum of the 16
+ *     accumulators of a lane, threshold compare, branch) and the row operands and accumulator seeds
+ *     read from LDS - without corpus copies, barriers or candidates; `stages` x 64 instructions
+ *     per wave.  LDS ring and query registers are filled from operands_dev as above.  *tops as
+ *     above: the ceiling of that loop on this GPU for such operand bits.
  *   lpq_probe_stream: reads bytes (rounded down to a multiple of 4096) of src_dev `reps` times,
  *     mode 0 through the asynchronous global->LDS copies of the scan kernels, mode 1 through
  *     16-byte register loads.  *gbps = 1e9 bytes per second.
- * LPQ_EINVAL: null output, iters outside 1..10 000 000, misaligned or too small a buffer,
+ * LPQ_EINVAL: null output, iters or stages outside 1..10 000 000, misaligned or too small a buffer,
  * unknown mode, reps outside 1..10 000. */
 int lpq_probe_mfma_i8(const void *operands_dev, size_t operand_bytes, int iters, double *tops, void *stream);
+int lpq_probe_scan_core(const void *operands_dev, size_t operand_bytes, int stages, double *tops, void *stream);
 int lpq_probe_stream(const void *src_dev, size_t bytes, int mode, int reps, double *gbps, void *stream);
 
 /* Diagnostics of the collecting variant: after a search with the same (idx, nq, k, metric) and

@@ -158,6 +158,17 @@ extern "C" int lpq_probe_mfma_i8(const void *operands_dev, size_t operand_bytes,
     return LPQ_OK;
 }
 
+extern "C" int lpq_probe_scan_core(const void *operands_dev, size_t operand_bytes, int stages, double *tops, void *stream)
+{
+    if (!tops) return fail(LPQ_EINVAL, "null output");
+    if (stages < 1 || stages > 10000000) return fail(LPQ_EINVAL, "stages = %d outside 1..10 000 000", stages);
+    if (operands_dev && operand_bytes < 16) return fail(LPQ_EINVAL, "operand buffer smaller than 16 bytes");
+    if (operands_dev && (uintptr_t)operands_dev % 16) return fail(LPQ_EINVAL, "operand buffer must be 16-byte aligned");
+    *tops = 0.0;
+    HIP_TRY(probe_scan_core(operands_dev, operand_bytes, stages, tops, (hipStream_t)stream));
+    return LPQ_OK;
+}
+
 extern "C" int lpq_probe_stream(const void *src_dev, size_t bytes, int mode, int reps, double *gbps, void *stream)
 {
     if (!src_dev || !gbps) return fail(LPQ_EINVAL, "null argument");

@@ -231,6 +231,9 @@ hipError_t launch_search_f32(const float *x, int64_t n, int64_t ldx, const float
 // Sustained rate of a register-resident v_mfma_i32_32x32x32_i8 loop whose operand registers are
 // filled from `operands` (null: all zero), in 1e12 integer operations per second.
 hipError_t probe_mfma(const void *operands, size_t bytes, int iters, double *tops, hipStream_t st);
+// Sustained rate of the wide collecting scan's inner loop alone (matrix instructions, filter epilogue,
+// operands from an LDS ring filled once from `operands`; no copies, barrier or candidates), in 1e12 op/s.
+hipError_t probe_scan_core(const void *operands, size_t bytes, int stages, double *tops, hipStream_t st);
 // Sustained read rate over `bytes` of device memory, `reps` passes: mode 0 through asynchronous
 // global->LDS copies into wave-private rings (bytes / 4096 chunks are read), mode 1 through
 // 16-byte register loads; in 1e9 bytes per second.

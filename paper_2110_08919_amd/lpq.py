@@ -76,6 +76,7 @@ def lib() -> C.CDLL:
             "lpq_profile_read_kind": (i32, [i32, C.POINTER(i64), C.POINTER(C.c_double)]),
             "lpq_search_plan_info": (i32, [i32, i32, i32, i64, i64, i32, C.POINTER(i64), i32]),
             "lpq_probe_mfma_i8": (i32, [vp, C.c_size_t, i32, C.POINTER(C.c_double), vp]),
+            "lpq_probe_scan_core": (i32, [vp, C.c_size_t, i32, C.POINTER(C.c_double), vp]),
             "lpq_probe_stream": (i32, [vp, C.c_size_t, i32, i32, C.POINTER(C.c_double), vp]),
             "lpq_last_error": (C.c_char_p, []),
         }
@@ -142,6 +143,15 @@ def probe_mfma_i8(operands: torch.Tensor = None, iters: int = 50000) -> float:
     out = C.c_double(0.0)
     nbytes = 0 if operands is None else operands.numel() * operands.element_size()
     _check(lib().lpq_probe_mfma_i8(_ptr(operands), nbytes, iters, C.byref(out), _stream()))
+    return out.value
+
+
+def probe_scan_core(operands: torch.Tensor = None, stages: int = 12000) -> float:
+    """Sustained 1e12 op/s of the batched scan's inner loop alone (no copies, barrier or candidates),
+    its LDS ring and query registers filled from `operands` (None = zeros)."""
+    out = C.c_double(0.0)
+    nbytes = 0 if operands is None else operands.numel() * operands.element_size()
+    _check(lib().lpq_probe_scan_core(_ptr(operands), nbytes, stages, C.byref(out), _stream()))
     return out.value
 
 
