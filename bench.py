@@ -23,7 +23,7 @@ PEAK_HBM = 8.0e12           # MI355X HBM3E, B/s
 # HBM bytes of one launch of the main scan kernel on the default workload, from the rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/search_mfma_kernel_skewed_int_1m_x128_pmc.txt
 # (FETCH_SIZE scaled by 2.000, WRITE_SIZE by 1.000 against device copies of known size in the same run).
-TRAFFIC_BYTES_DEFAULT_WORKLOAD = 264.0e6
+TRAFFIC_BYTES_DEFAULT_WORKLOAD = 266.7e6
 TRAFFIC_SOURCE = ("profiles/search_mfma_kernel_skewed_int_1m_x128_pmc.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
                   "runs of this command; a constant taken from that file, not measured in this run)")
 
@@ -40,6 +40,42 @@ def host_info():
     except OSError:
         pass
     return os.cpu_count() or 1, model
+
+
+class ClockSampler:
+    """Samples the shader clock (rocm-smi) from a thread while a GPU loop runs; mean over the samples
+    taken between start() and stop(), the first 0.4 s dropped (the clock is still settling)."""
+
+    def __init__(self):
+        import threading
+        self.samples, self._stop, self._t0 = [], False, 0.0
+        self._thread = threading.Thread(target=self._run, daemon=True)
+        self._thread.start()
+
+    def _run(self):
+        import re
+        import subprocess
+        while not self._stop:
+            t = time.time()
+            try:
+                out = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=5).stdout
+                m = re.search(r'sclk clock speed:"\s*:\s*"\((\d+)Mhz\)', out)
+                if m:
+                    self.samples.append((t, int(m.group(1))))
+            except Exception:
+                pass
+            time.sleep(0.1)
+
+    def start(self):
+        self._t0 = time.time()
+
+    def stop(self):
+        t1 = time.time()
+        v = [c for t, c in self.samples if self._t0 + 0.4 <= t <= t1 - 0.05]
+        return {"mean_mhz": sum(v) / len(v), "min_mhz": min(v), "max_mhz": max(v), "samples": len(v)} if v else None
+
+    def close(self):
+        self._stop = True
 
 
 def time_batches(lpq, torch, index, q, k, metric, reps, warm=10):
@@ -112,6 +148,9 @@ def main():
                          "~20 searches (~25 ms of load) after idle to settle, so a short --warmup would time the ramp")
     ap.add_argument("--no-small-batch", action="store_true", help="skip the small-batch (HBM regime) block")
     ap.add_argument("--no-probe", action="store_true", help="skip the attainable-rate probes")
+    ap.add_argument("--sample-clocks", action="store_true",
+                    help="after the timed region, run ~2 s of searches and ~1 s of each matrix probe while a thread "
+                         "samples the shader clock with rocm-smi; reported under `clocks` (evidence for the power limit)")
     ap.add_argument("--nq", type=int, default=0, help="query batch (default: the workload's 10 000)")
     ap.add_argument("--k", type=int, default=10)
     ap.add_argument("--n", type=int, default=0, help="corpus rows (default: the workload's 1 000 000)")
@@ -259,6 +298,30 @@ def main():
         ref = attainable["mfma_workload_codes_TOPs"] * 1e12 if mfma_frac >= hbm_frac else attainable["stream_global_to_lds_GBps"] * 1e9
         roofline["frac_of_attainable"] = roofline["achieved"] * (1e12 if mfma_frac >= hbm_frac else 1e9) / ref
 
+    # ---- shader clock under the search and under the probes (optional) ----------------------------
+    clocks = None
+    if args.sample_clocks:
+        sampler = ClockSampler()
+        clocks = {}
+        reps = max(200, int(2000.0 / max(ms_per_step, 1e-3)))
+        torch.cuda.synchronize()
+        sampler.start()
+        for _ in range(reps):
+            index.search(q, k, metric, out=(ids, dists), workspace=ws)
+        torch.cuda.synchronize()
+        clocks["search_loop"] = sampler.stop()
+        gen = torch.Generator(device="cuda").manual_seed(7)
+        rnd = torch.randint(-128, 128, (1 << 20,), generator=gen, device="cuda", dtype=torch.int8)
+        codes_ = quant.encode(x[:min(w.n, 8192)].contiguous()).contiguous()
+        for name, op in (("mfma_zero_operands", None), ("mfma_workload_codes", codes_), ("mfma_random_operands", rnd)):
+            sampler.start()
+            tops = [lpq.probe_mfma_i8(op, 1500000) for _ in range(2)]
+            clocks[name] = dict(sampler.stop() or {}, TOPs=tops[-1])
+        sampler.start()
+        tops = [lpq.probe_scan_core(codes_, 250000) for _ in range(2)]
+        clocks["scan_core_loop_workload_codes"] = dict(sampler.stop() or {}, TOPs=tops[-1])
+        sampler.close()
+
     # ---- recall@k of the int8 search against fp32 exact search (GPU), on a query subset ----
     rq = min(args.recall_queries, w.nq)
     recall = None
@@ -379,6 +442,7 @@ def main():
         "cpu_baseline": cpu,
         "ramp_searches": max(args.ramp, 0),
         "attainable": attainable,
+        "clocks": clocks,
         "small_batch": small,
         "recall_at_k_vs_fp32": recall,
         "recall_at_k_vs_fp32_per_feature_calibration": recall_pf,
