@@ -442,30 +442,42 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     constexpr bool CAN_PIECES = SEED && !RSPLIT;
     const bool pieces = CAN_PIECES && o.piece_stride > 0;
     const int64_t piece_gap = pieces ? (int64_t)S * o.piece_stride : 0;   // rows between the pieces of a stage
-    using src_off_t = typename std::conditional<CAN_PIECES, int64_t, int>::type;
-    src_off_t src_off[IPW];   // byte offset of the lane's source chunk relative to the first row of a stage
+    int src_off[IPW];   // byte offset of the lane's source chunk relative to the first row of a stage (of its piece)
 #pragma unroll
     for (int j = 0; j < IPW; ++j) {
         const int p = (wave * IPW + j) * 64 + lane;
         const int r = p / SLOTS, sl = p % SLOTS;
         int c = sl ^ swz<SLOTS>(r & 31);
         c = c < CPR ? c : CPR - 1;          // padding slots of non-power-of-two rows: any valid chunk
-        src_off[j] = r * ROWB + c * 16;
-        if constexpr (CAN_PIECES) {
-            if (pieces) src_off[j] = ((r & 7) + (int64_t)(r >> 3) * piece_gap) * ROWB + c * 16;
-        }
+        src_off[j] = (pieces ? (r & 7) : r) * ROWB + c * 16;
     }
-    // row of the accumulator seed that wave 0's lane brings (non-row-split launches)
-    const int64_t cin_off = pieces ? (int64_t)(lane >> 3) * piece_gap + (lane & 7) : (int64_t)wave * 64 + lane;
+    // Row of the accumulator seed that wave 0's lane brings (non-row-split launches).  It is worked
+    // out from the lane number where it is used, behind a barrier for the optimiser: kept in a
+    // register across the loop, the seeding pass of 128 queries per wave spills it, and a reload
+    // from scratch waits for every copy in flight (they share the vector-memory counter).
+    // (Only that kernel: where nothing spills, carrying the addresses measured 1 to 4 % faster.)
+    constexpr bool REFORM = CAN_PIECES && NB == 4 && KS == 4;
+#define LPQ_OPAQUE(X) asm volatile("" : "+v"(X))
 #define LPQ_ISSUE(ST)                                                                                   \
     do {                                                                                                \
         const int st_ = (ST);                                                                           \
+        int lane_ = lane;                                                                               \
+        if (REFORM) LPQ_OPAQUE(lane_);                                                                  \
+        const int64_t cin_off = pieces ? (int64_t)(lane_ >> 3) * piece_gap + (lane_ & 7) : (int64_t)wave * 64 + lane_; \
         const int64_t r0_ = pieces ? ((int64_t)s + (int64_t)S * 8 * st_) * o.piece_stride                \
                                    : rs + (int64_t)(LPQ_DRY(a) == 7 ? (st_ & 1) : st_) * sstride;       \
         const int ring_slot_ = st_ % NST;                                                               \
         const int8_t *src_ = a.codes + r0_ * ROWB;                                                      \
-        _Pragma("unroll") for (int j = 0; j < IPW; ++j)                                                 \
-            async_copy16(src_ + src_off[j], ring_lds + ring_slot_ * STAGE_BYTES + (wave * IPW + j) * 1024); \
+        _Pragma("unroll") for (int j = 0; j < IPW; ++j) {                                               \
+            /* pieces: the lane's row belongs to piece (row of the stage) / 8, which is the same for */ \
+            /* all lanes of the instruction when a row takes 8 slots or more                          */ \
+            const int piece_ = SLOTS >= 8 ? (((wave * IPW + j) * 64) / SLOTS) >> 3                      \
+                                          : (((wave * IPW + j) * 64 + lane_) / SLOTS) >> 3;             \
+            const int64_t far_ = pieces ? (int64_t)piece_ * piece_gap * ROWB : 0;                       \
+            int near_ = src_off[j];   /* stays one register: the 64-bit sum is formed here */           \
+            if (REFORM) LPQ_OPAQUE(near_);                                                              \
+            async_copy16(src_ + far_ + near_, ring_lds + ring_slot_ * STAGE_BYTES + (wave * IPW + j) * 1024); \
+        }                                                                                               \
         if (L2 && RSPLIT) { /* each wave brings the seeds and the parity word of its own block */       \
             if (lane < 32)                                                                              \
                 async_copy4(a.cinit + r0_ + wave * 32 + lane, aux_lds + (ring_slot_ * AUX_INTS + wave * 32) * 4); \
@@ -605,9 +617,11 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     const int G = S * SEG * 2 * GR * (RSPLIT ? NW : 1);
 #define LPQ_FLUSH_SEGMENT(SEGIDX)                                                                       \
     do {                                                                                                \
+        int lane_ = lane;   /* addresses are formed here, not carried through the loop in registers */ \
+        if (REFORM) LPQ_OPAQUE(lane_);                                                                  \
         _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) {                                             \
-            int32_t *dst_ = gmax + (size_t)(q_first + nb * 32 + col) * G +                              \
-                ((((size_t)s * SEG + (SEGIDX)) * (RSPLIT ? NW : 1) + (RSPLIT ? wave : 0)) * 2 + half) * GR; \
+            int32_t *dst_ = gmax + (size_t)(q_first + nb * 32 + (lane_ & 31)) * G +                     \
+                ((((size_t)s * SEG + (SEGIDX)) * (RSPLIT ? NW : 1) + (RSPLIT ? wave : 0)) * 2 + (lane_ >> 5)) * GR; \
             _Pragma("unroll") for (int r = 0; r < GR; ++r) {                                            \
                 dst_[r] = gm[nb][r];                                                                    \
                 gm[nb][r] = INT32_MIN;                                                                  \
@@ -717,6 +731,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
 #undef LPQ_LOAD_BLOCK
 #undef LPQ_BLOCK
 #undef LPQ_FLUSH_SEGMENT
+#undef LPQ_OPAQUE
 
     if (COLLECT) {
         if (LPQ_DRY(a) < 5) drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
