@@ -319,7 +319,9 @@ extern "C" void lpq_index_destroy(lpq_index *idx)
 // Row length an index stores d features in: a length the matrix-core scans have where one exists.
 static int padded_row_length(int d)
 {
-    return d <= 64 ? 64 : d <= 96 ? 96 : d <= 128 ? 128 : d <= 192 ? 192 : d <= 256 ? 256 : (int)round_up(d, 32);
+    // up to 1024 features: the row lengths the matrix-core kernels take; beyond: the generic kernel's
+    return d <= 64 ? 64 : d <= 96 ? 96 : d <= 128 ? 128 : d <= 192 ? 192 : d <= 256 ? 256
+           : d <= 384 ? 384 : d <= 512 ? 512 : d <= 768 ? 768 : d <= 1024 ? 1024 : (int)round_up(d, 32);
 }
 
 static int index_create_impl(lpq_index **out, const lpq_quantizer *q, int64_t capacity, bool packed)
@@ -619,6 +621,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
             p.wave_queries = 128;
         if (p.mode == PLAN_MFMA_COLLECT && idx->packed)   // the packed scan has one variant per row length
             p.wave_queries = idx->d_pad <= 128 ? 128 : 64;
+        if (mfma_long_rows(idx->d_pad)) p.wave_queries = mfma_long_wave_queries(idx->d_pad);
         qt = mfma_queries_per_workgroup(nq, idx->d_pad, p.wave_queries == 128);
     }
     const int64_t tiles_q = ceil_div(nq > 0 ? nq : 1, qt);
@@ -630,7 +633,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
             p.SEG = mfma_seed_segments(p.S1, k, p.rs_waves);
             p.G = mfma_seed_groups(p.S1, p.SEG, p.rs_waves);
             // systematic sample: one stage every seed_stride rows, shared out over the S1 splits
-            const int64_t stage_rows = p.rsplit ? 32 * p.rs_waves : 64;
+            const int64_t stage_rows = p.rsplit ? 32 * p.rs_waves : (mfma_long_rows(idx->d_pad) ? 32 : 64);
             const int64_t stages = seed / stage_rows;
             p.seed_stages = (int)ceil_div(stages, p.S1);
             p.seed_stride = n / ((int64_t)p.seed_stages * p.S1) / 128 * 128;
@@ -641,7 +644,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
             // contiguously - is spread over many splits and hence over many groups of the pass.
             // (For k > 16 on a corpus sorted by norm a split's groups then span wide slices of the order
             // and up to a tenth of the queries overflow; the further rounds of the scan take those.)
-            if (!p.rsplit) {
+            if (!p.rsplit && !mfma_long_rows(idx->d_pad)) {
                 const int64_t pstages = ceil_div(stages, p.S1);                 // as many rows as the stage-wise sample
                 const int64_t pstride = pstages > 0 ? n / (8 * pstages * p.S1) : 0;   // all pieces inside the corpus
                 if (pstride >= 16 && pstages >= 1) {

@@ -154,6 +154,8 @@ int mfma_seed_groups(int S, int SEG, int rs_waves);      // = G, entries per que
 int mfma_queries_per_workgroup(int64_t nq, int d_pad, bool wide = false);   // query tile; wide: 128 queries per wave
 bool mfma_collect_wide(int64_t nq, int d_pad);           // collecting mode may use 128 queries per wave
 bool mfma_row_split(int64_t nq, int d_pad, bool packed = false);   // few queries: waves split rows, share queries
+bool mfma_long_rows(int d_pad);            // rows of 384, 512, 768 or 1024 bytes: their own collecting scan and seeding pass
+int mfma_long_wave_queries(int d_pad);     // ... which keep 64 (up to 512 bytes) or 32 queries per wave
 int mfma_row_split_waves(int d_pad, bool packed);   // 4 on rows of up to 128 bytes, 2 on longer ones (collecting scan and seeding pass only)
 // With stage_stride > 0 (a multiple of 128) the pass is a systematic sample of [row0, row1): one
 // stage (64 rows; 128 in row-split launches) every stage_stride rows, stages_per_split per split.

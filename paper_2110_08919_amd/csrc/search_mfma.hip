@@ -767,6 +767,344 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     }
 }
 
+// ---- rows of 384 to 1024 bytes ----------------------------------------------------------------
+// The collecting scan and its seeding pass for rows whose operands no longer fit the scheme above
+// (query fragments AND two row blocks' worth of corpus fragments in registers).  What changes:
+//   - a wave holds the fragments of 32 queries (rows of 768 or 1024 bytes) or 64 (384 or 512 bytes):
+//     128 registers at most;
+//   - a stage is ONE block of 32 rows by one segment of the row (the whole row up to 512 bytes, else
+//     a half), 12 or 16 KB, in a ring of three; the accumulators of a row block live across its
+//     segments, are seeded when its first segment starts and filtered when its last one ends;
+//   - corpus fragments come from LDS four k-steps at a time, one group ahead of the matrix
+//     instructions that use them; the group that crosses into the next stage is read right after the
+//     workgroup barrier that says the stage has landed.
+// Chunks (16 bytes) of a row segment are swizzled inside aligned groups of 2^SWB chunks: with the
+// row stride of 512 bytes (a multiple of the 256 bytes the 64 banks cover) the low four bits of the
+// row number do it; with 384 bytes odd rows start half way round the banks, so three bits taken
+// from bit 1 up give 16 consecutive rows 16 different bank groups as well.
+template <int CPS>
+__device__ __forceinline__ int long_slot(int c, int r)
+{
+    constexpr int SWB = CPS == 32 ? 4 : 3, MASK = (1 << SWB) - 1;
+    const int sw = CPS == 32 ? (r & 15) : ((r >> 1) & 7);
+    return (c & ~MASK) | ((c ^ sw) & MASK);
+}
+
+constexpr int LONG_NST = 3;
+constexpr size_t long_lds_bytes(int kseg, int nb, bool seed)
+{
+    return (size_t)LONG_NST * 32 * kseg * 32 + (size_t)LONG_NST * (32 + 4) * 4 + 64 + (seed ? 0 : 4 * waveq_bytes(nb * 32));
+}
+
+template <int KSEG, int NSEG, bool L2, bool SEED>
+__global__ __launch_bounds__(256, 2) void search_long_kernel(
+    SearchArgs a, int64_t row0, int64_t row1, int S, int64_t split_rows, int qtiles, MfmaIo o)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    static_assert((KSEG == 12 || KSEG == 16) && (NSEG == 1 || NSEG == 2), "rows of 384, 512, 768 or 1024 bytes");
+    constexpr int NW = 4;
+    constexpr int NB = NSEG == 1 ? 2 : 1;      // blocks of 32 queries per wave
+    constexpr int QW = NB * 32, QT = NW * QW;
+    constexpr int KTOT = KSEG * NSEG;          // k-steps (32 bytes) per row
+    constexpr int ROWB = KTOT * 32, SEGB = KSEG * 32;
+    constexpr int CPS = SEGB / 16;             // chunks per row segment
+    constexpr int RS = 32;                     // rows per stage
+    constexpr int NST = LONG_NST;
+    constexpr int STAGE_BYTES = RS * SEGB;
+    constexpr int IPW = RS * CPS / 64 / NW;    // copy instructions per wave and stage
+    constexpr int AUX_INTS = RS + 4;           // accumulator seeds of the 32 rows, then their parity word
+    constexpr int NG = KSEG / 4;               // groups of four k-steps per segment
+    constexpr int PER = CPS == 32 ? 8 : 4;     // k-steps after which the swizzle pattern of a lane repeats
+    static_assert(RS * CPS % (64 * NW) == 0, "a stage splits evenly over the waves' copies");
+    static_assert((NST - 1) * (IPW + 1) <= 63, "wait_vmcnt covers 0..63");
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int col = lane & 31, half = lane >> 5;
+
+    // the same XCD-aware order of (split, query tile) pairs as the kernel above
+    const int total = qtiles * S;
+    const int per = total / 8;
+    const int b = blockIdx.x;
+    const int wk = (a.work_order != 3 && b < per * 8) ? (b % 8) * per + b / 8 : b;
+    const int s = (a.work_order == 2) ? wk % S : wk / qtiles;
+    const int qt = (a.work_order == 2) ? wk / S : wk % qtiles;
+
+    // Row blocks of this split.  Collecting scan: blocks s, s + S, s + 2S, ... of the corpus, so that
+    // a query's candidates spread evenly over the splits' regions.  Seeding pass: split_rows / 32
+    // blocks starting at row0 + s * split_stride, stage_stride rows apart (adjacent without a stride),
+    // as far as their first rows are real items.
+    int RB;
+    int64_t rs, bstride;
+    if (!SEED) {
+        const int64_t all = (row1 - row0 + RS - 1) / RS;
+        RB = (all > s) ? (int)((all - s + S - 1) / S) : 0;
+        rs = row0 + (int64_t)s * RS;
+        bstride = (int64_t)S * RS;
+    } else {
+        rs = row0 + (int64_t)s * o.split_stride;
+        bstride = o.stage_stride ? o.stage_stride : RS;
+        const int64_t left = (row1 > rs) ? (row1 - rs + bstride - 1) / bstride : 0;
+        RB = (int)(left < split_rows / RS ? left : split_rows / RS);
+    }
+    const int T = RB * NSEG;
+    const int64_t re = row1;
+
+    unsigned char *ring = smem;
+    int *aux = (int *)(smem + NST * STAGE_BYTES);
+    int *flags = aux + NST * AUX_INTS;           // [2][8] joint-drain requests, double buffered
+    const WaveQ w = carve_waveq((unsigned char *)(flags + 16) + (size_t)wave * waveq_bytes(QW), QW);
+    const int64_t q_first = (int64_t)qt * QT + wave * QW;
+
+    if constexpr (!SEED) {
+        if (a.redo_flags) {   // a further round: only if the flagged queries are many, and only tiles that hold one
+            if (*a.redo_count <= a.redo_min) return;   // the same answer in every thread of the grid
+            const int64_t t0 = (int64_t)qt * QT;
+            int mine = 0;
+            for (int64_t qq = t0 + tid; qq < t0 + QT && qq < a.nq; qq += NW * 64) mine |= a.redo_flags[qq];
+            int *vote = reinterpret_cast<int *>(ring);   // the ring is still unused
+            if (tid == 0) *vote = 0;
+            __syncthreads();
+            if (mine) atomicOr(vote, 1);
+            __syncthreads();
+            const int any = *vote;
+            __syncthreads();   // everyone has read the vote before the ring is filled
+            if (!any) return;  // the same answer in every thread of the workgroup
+        }
+    }
+
+    cand_t lst[1] = {0};
+    const cand_t seedC = 0;
+    cand_t *cbase = SEED ? nullptr : o.cbuf + ((size_t)q_first * S + s) * o.Cs;
+    const size_t qstride = (size_t)S * o.Cs;
+    if (!SEED) {
+        for (int i = lane; i < QW; i += 64) {
+            const int64_t gq = q_first + i;
+            const cand_t sc = gq < a.nq ? (o.seeds ? o.seeds[gq] : CAND_NONE) : 0;
+            w.thrC[i] = sc;
+            w.thrE[i] = thr_e(sc);
+            w.mbox[i] = 0;
+        }
+    }
+    wave_lds_sync();
+
+    v4i B[NB][KTOT];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int ks = 0; ks < KTOT; ++ks)
+            B[nb][ks] = *reinterpret_cast<const v4i *>(a.qcodes + (q_first + nb * 32 + col) * a.d_pad + ks * 32 + half * 16);
+    int thr[NB], gm[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        thr[nb] = SEED ? INT32_MAX : w.thrE[nb * 32 + col];
+        gm[nb] = INT32_MIN;
+    }
+    int qcnt = 0;
+    // byte offset, inside a stage, of this lane's fragment of k-step ks (of the segment) for ks < PER;
+    // k-step ks is a_off[ks % PER] + (ks / PER) * PER * 32
+    int a_off[PER];
+#pragma unroll
+    for (int ks = 0; ks < PER; ++ks) a_off[ks] = col * SEGB + long_slot<CPS>(2 * ks + half, col) * 16;
+
+    // Stage loader: LDS position p (16 bytes) of a stage = (row p / CPS, slot p % CPS); instruction j of
+    // a wave fills positions [(wave * IPW + j) * 64, + 64), each lane fetching the chunk that belongs
+    // in its slot.
+    const unsigned ring_lds = lds_offset(ring), aux_lds = lds_offset(aux);
+    const int lpt = IPW + ((L2 && wave < 2) ? 1 : 0);   // copies this wave issues per stage
+    int src_off[IPW];
+#pragma unroll
+    for (int j = 0; j < IPW; ++j) {
+        const int p = (wave * IPW + j) * 64 + lane;
+        const int r = p / CPS, sl = p % CPS;
+        src_off[j] = r * ROWB + long_slot<CPS>(sl, r) * 16;   // the swizzle is its own inverse
+    }
+#define LPQL_ISSUE(ST, SLOT)                                                                            \
+    do {                                                                                                \
+        const int st_ = (ST), slot_ = (SLOT);                                                           \
+        const int64_t r0_ = rs + (int64_t)(st_ / NSEG) * bstride;                                       \
+        const int8_t *src_ = a.codes + r0_ * ROWB + (st_ % NSEG) * SEGB;                                \
+        _Pragma("unroll") for (int j = 0; j < IPW; ++j)                                                 \
+            async_copy16(src_ + src_off[j], ring_lds + slot_ * STAGE_BYTES + (wave * IPW + j) * 1024);  \
+        if (L2 && wave == 0) {                                                                          \
+            if (lane < 32) async_copy4(a.cinit + r0_ + lane, aux_lds + slot_ * AUX_INTS * 4);           \
+        } else if (L2 && wave == 1) {                                                                   \
+            if (lane < 1) async_copy4(a.parity + r0_ / 32, aux_lds + (slot_ * AUX_INTS + RS) * 4);      \
+        }                                                                                               \
+    } while (0)
+
+    // fragments of group G (k-steps 4G .. 4G+3 of the segment) of the stage in ring slot SLOT
+#define LPQL_LOAD_GROUP(SLOT, G, AREG)                                                                  \
+    do {                                                                                                \
+        const unsigned char *sb_ = ring + (size_t)(SLOT) * STAGE_BYTES;                                 \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                 \
+            const int ks_ = (G) * 4 + i;                                                                \
+            AREG[i] = *reinterpret_cast<const v4i *>(sb_ + a_off[ks_ % PER] + (ks_ / PER) * (PER * 32)); \
+        }                                                                                               \
+    } while (0)
+    // accumulator seeds and parity word of the row block whose (first) stage sits in ring slot SLOT
+#define LPQL_LOAD_SEEDS(SLOT, CREG, PREG)                                                               \
+    do {                                                                                                \
+        if (L2) {                                                                                       \
+            const int *cb_ = aux + (SLOT) * AUX_INTS;                                                   \
+            _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                             \
+                const v4i v_ = *reinterpret_cast<const v4i *>(cb_ + 8 * g + 4 * half);                  \
+                CREG[4 * g + 0] = v_[0]; CREG[4 * g + 1] = v_[1];                                       \
+                CREG[4 * g + 2] = v_[2]; CREG[4 * g + 3] = v_[3];                                       \
+            }                                                                                           \
+            PREG = (unsigned)cb_[RS];                                                                   \
+        } else {                                                                                        \
+            _Pragma("unroll") for (int i = 0; i < 16; ++i) CREG[i] = 0;                                 \
+            PREG = 0u;                                                                                  \
+        }                                                                                               \
+    } while (0)
+
+    // filter epilogue of one block of 32 queries x 32 rows, as in the kernel above
+#define LPQL_EPI(VEC, NBI, ROWBASE, PWORD)                                                              \
+    do {                                                                                                \
+        const int nb = (NBI);                                                                           \
+        const v16i v = (VEC);                                                                           \
+        int m = max(max(v[0], v[1]), v[2]);                                                             \
+        m = max(max(m, v[3]), v[4]);                                                                    \
+        m = max(max(m, v[5]), v[6]);                                                                    \
+        m = max(max(m, v[7]), v[8]);                                                                    \
+        m = max(max(m, v[9]), v[10]);                                                                   \
+        m = max(max(m, v[11]), v[12]);                                                                  \
+        m = max(max(m, v[13]), v[14]);                                                                  \
+        m = max(m, v[15]);                                                                              \
+        if (SEED) {                                                                                     \
+            gm[nb] = max(gm[nb], m);                                                                    \
+        } else {                                                                                        \
+            bool trip = m >= thr[nb];                                                                   \
+            unsigned long long mask = __ballot(trip);                                                   \
+            if (__builtin_expect(mask != 0, 0)) {                                                       \
+                if (qcnt + __popcll(mask) > QCAP) {   /* no room: this wave drains alone */             \
+                    drain_queue<L2, 0, 1>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);         \
+                    qcnt = 0;                                                                           \
+                }                                                                                       \
+                const int below = __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),                     \
+                                                            __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u)); \
+                if (trip) {                                                                             \
+                    const int slot = qcnt + below;                                                      \
+                    v4i *dst_ = reinterpret_cast<v4i *>(w.qvals + slot * 16);                           \
+                    _Pragma("unroll") for (int g = 0; g < 4; ++g)                                       \
+                        dst_[g] = v4i{v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};              \
+                    w.qmeta[slot] = v4i{(ROWBASE), (int)(PWORD), (nb * 32 + col) | (half << 8), 0};     \
+                }                                                                                       \
+                qcnt += __popcll(mask);                                                                 \
+            }                                                                                           \
+        }                                                                                               \
+    } while (0)
+
+    // Seeding pass: the group maximum of (segment g of this split, lane half) goes to
+    // gmax[q][(s * SEG + g) * 2 + half], the layout the kernel above uses.
+    const int SEG = o.SEG;
+    const int G = S * SEG * 2;
+#define LPQL_FLUSH_SEGMENT(SEGIDX)                                                                      \
+    do {                                                                                                \
+        _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) {                                             \
+            o.gmax[(size_t)(q_first + nb * 32 + col) * G + ((size_t)s * SEG + (SEGIDX)) * 2 + half] = gm[nb]; \
+            gm[nb] = INT32_MIN;                                                                         \
+        }                                                                                               \
+    } while (0)
+    if (SEED) {   // segments this split never reaches keep the neutral value
+        for (int g = 0; g < SEG; ++g) LPQL_FLUSH_SEGMENT(g);
+    }
+
+    // Query fragments (and the stores above) have completed before any copy is issued, so from
+    // here on only async copies (and appended candidates) are outstanding on the vector-memory counter.
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+
+    v4i An[4];           // the group read ahead
+    v16i Cn;             // seeds and parity word of the row block that starts next
+    unsigned Pn = 0;
+    const int primed = T < NST ? T : NST;
+    for (int st = 0; st < primed; ++st) LPQL_ISSUE(st, st);
+    int slot = 0;        // ring slot of stage t
+    if (T > 0) {
+        wait_vmcnt((primed - 1) * lpt);
+        __syncthreads();
+        LPQL_LOAD_GROUP(0, 0, An);
+        LPQL_LOAD_SEEDS(0, Cn, Pn);
+    }
+    v4i fl0 = {0, 0, 0, 0};
+    int t = 0;
+    for (int rb = 0; rb < RB; ++rb) {
+        v16i acc[NB];
+        v16i Cc;
+        unsigned Pc = 0;
+#pragma unroll
+        for (int seg = 0; seg < NSEG; ++seg, ++t) {
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                v4i Ac[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) Ac[i] = An[i];
+                if (seg == 0 && g == 0) { Cc = Cn; Pc = Pn; }
+                if (g + 1 < NG) {
+                    LPQL_LOAD_GROUP(slot, g + 1, An);
+                } else {
+                    // the last group of stage t is in registers once the LDS counter is down: this wave
+                    // is done reading the stage
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    if (!SEED && lane == 0) flags[(t & 1) * 8 + wave] = qcnt >= TRIG;
+                    if (t + 1 < T) {
+                        // stages issued so far: 0 .. min(T-1, t+NST-1); stage t+1 must have landed
+                        const int last = T - 1 < t + NST - 1 ? T - 1 : t + NST - 1;
+                        wait_vmcnt((last - (t + 1)) * lpt);
+                    }
+                    __syncthreads();
+                    if (t + NST < T) LPQL_ISSUE(t + NST, slot);   // refills the slot of stage t
+                    if (!SEED) {   // drain requests of the stage before, acted on together
+                        const int any = fl0[0] | fl0[1] | fl0[2] | fl0[3];
+                        fl0 = *reinterpret_cast<const v4i *>(flags + (t & 1) * 8);
+                        if (any) {
+                            drain_queue<L2, 0, 1>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
+                            qcnt = 0;
+                        }
+                    }
+                    const int nslot = slot + 1 == NST ? 0 : slot + 1;
+                    if (t + 1 < T) {
+                        LPQL_LOAD_GROUP(nslot, 0, An);
+                        if (seg + 1 == NSEG) LPQL_LOAD_SEEDS(nslot, Cn, Pn);
+                    }
+                    slot = nslot;
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        acc[nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Ac[i], B[nb][seg * KSEG + g * 4 + i],
+                                                                        (seg == 0 && g == 0 && i == 0) ? Cc : acc[nb], 0, 0, 0);
+            }
+        }
+        const int rowbase = (int)(rs + (int64_t)rb * bstride);
+#pragma unroll
+        for (int nbi = 0; nbi < NB; ++nbi) LPQL_EPI(acc[nbi], nbi, rowbase, Pc);
+        if (SEED) {   // close a segment when the next row block belongs to the next one
+            const int sg = (int)((int64_t)rb * SEG / RB), sg_next = (int)((int64_t)(rb + 1) * SEG / RB);
+            if (rb + 1 == RB || sg_next != sg) {
+                LPQL_FLUSH_SEGMENT(sg);
+                __builtin_amdgcn_s_waitcnt(0x0F70);   // keep the counter to async copies only
+            }
+        }
+    }
+#undef LPQL_ISSUE
+#undef LPQL_LOAD_GROUP
+#undef LPQL_LOAD_SEEDS
+#undef LPQL_EPI
+#undef LPQL_FLUSH_SEGMENT
+
+    if (!SEED) {
+        drain_queue<L2, 0, 1>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
+        wave_lds_sync();
+        for (int i = lane; i < QW; i += 64) {
+            const int64_t gq = q_first + i;
+            if (gq < a.nq) o.ccnt[(size_t)gq * S + s] = w.mbox[i];
+        }
+    }
+}
+
 // One wave per query: the k-th largest of its G group maxima (duplicates counted) becomes the
 // seed threshold.  Each lane keeps E of the values in registers.  Small k: k times the wave takes
 // the largest value left and the first lane holding it drops one copy.  Larger k: bisection on
@@ -919,10 +1257,51 @@ hipError_t launch_ks(const SearchArgs &a, int64_t row0, int64_t row1, int S, con
               : launch_one<KS, false, 16, false>(a, row0, row1, S, o, st);
 }
 
+// Rows of 384 to 1024 bytes: the collecting scan (o.cbuf) or its seeding pass (o.gmax).
+template <int KSEG, int NSEG, bool L2, bool SEED>
+hipError_t launch_long_one(const SearchArgs &a, int64_t row0, int64_t row1, int S, MfmaIo o, hipStream_t st)
+{
+    constexpr int NB = NSEG == 1 ? 2 : 1;
+    if (a.rsplit || a.packed || a.wave_queries != NB * 32) return hipErrorInvalidValue;
+    const int64_t split_rows = o.split_stride ? o.split_stride_rows : round_up(ceil_div(row1 - row0, S), 128);
+    if (!o.split_stride) o.split_stride = split_rows;
+    const int qtiles = (int)ceil_div(a.nq, 4 * NB * 32);
+    auto kern = search_long_kernel<KSEG, NSEG, L2, SEED>;
+    static bool attr_set = false;  // per instantiation
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    kern<<<(unsigned)(qtiles * S), 256, long_lds_bytes(KSEG, NB, SEED), st>>>(a, row0, row1, S, split_rows, qtiles, o);
+    return hipGetLastError();
+}
+
+template <int KSEG, int NSEG>
+hipError_t launch_long(const SearchArgs &a, int64_t row0, int64_t row1, int S, const MfmaIo &o, hipStream_t st)
+{
+    const bool l2 = a.metric == LPQ_METRIC_L2SQ;
+    if (o.gmax)
+        return l2 ? launch_long_one<KSEG, NSEG, true, true>(a, row0, row1, S, o, st)
+                  : launch_long_one<KSEG, NSEG, false, true>(a, row0, row1, S, o, st);
+    if (o.cbuf)
+        return l2 ? launch_long_one<KSEG, NSEG, true, false>(a, row0, row1, S, o, st)
+                  : launch_long_one<KSEG, NSEG, false, false>(a, row0, row1, S, o, st);
+    return hipErrorInvalidValue;   // no register lists beside rows this long
+}
+
 hipError_t launch_any(const SearchArgs &a, int64_t row0, int64_t row1, int S, const MfmaIo &o, hipStream_t st)
 {
     if (a.nq <= 0 || row1 <= row0) return hipSuccess;
     if (row0 % 128 || o.split_stride % 128) return hipErrorInvalidValue;  // stages and parity words cover aligned blocks
+    switch (a.d_pad / 32) {
+    case 12: return launch_long<12, 1>(a, row0, row1, S, o, st);
+    case 16: return launch_long<16, 1>(a, row0, row1, S, o, st);
+    case 24: return launch_long<12, 2>(a, row0, row1, S, o, st);
+    case 32: return launch_long<16, 2>(a, row0, row1, S, o, st);
+    default: break;
+    }
     switch (a.d_pad / 32) {
     case 2: return launch_ks<2>(a, row0, row1, S, o, st);
     case 3: return launch_ks<3>(a, row0, row1, S, o, st);
@@ -939,9 +1318,20 @@ bool shape_ok(int d_pad)
     return d_pad % 32 == 0 && (ks == 2 || ks == 3 || ks == 4 || ks == 6 || ks == 8);
 }
 
+bool long_shape_ok(int d_pad) { return d_pad == 384 || d_pad == 512 || d_pad == 768 || d_pad == 1024; }
+
 }  // namespace
 
-int mfma_queries_per_workgroup(int64_t nq, int d_pad, bool wide) { return mfma_row_split(nq, d_pad) ? 64 : (wide ? 512 : 256); }
+int mfma_queries_per_workgroup(int64_t nq, int d_pad, bool wide)
+{
+    if (long_shape_ok(d_pad)) return 4 * mfma_long_wave_queries(d_pad);
+    return mfma_row_split(nq, d_pad) ? 64 : (wide ? 512 : 256);
+}
+
+// Rows of more than 256 bytes (384, 512, 768 or 1024: the collecting scan and its seeding pass only).
+bool mfma_long_rows(int d_pad) { return long_shape_ok(d_pad); }
+
+int mfma_long_wave_queries(int d_pad) { return d_pad <= 512 ? 64 : 32; }
 
 // Collecting mode: 128 queries per wave when the rows are short enough for the registers to hold them.
 bool mfma_collect_wide(int64_t nq, int d_pad) { return !mfma_row_split(nq, d_pad) && d_pad <= 128 && nq > 256; }
@@ -953,7 +1343,7 @@ int mfma_row_split_waves(int d_pad, bool packed) { return (packed ? d_pad / 2 : 
 
 bool mfma_reg_supported(int d_pad, int k) { return shape_ok(d_pad) && k >= 1 && k <= 16; }
 
-bool mfma_collect_supported(int d_pad, int k) { return shape_ok(d_pad) && k >= 1 && k <= 128; }
+bool mfma_collect_supported(int d_pad, int k) { return (shape_ok(d_pad) || long_shape_ok(d_pad)) && k >= 1 && k <= 128; }
 
 bool mfma_supported(int d_pad, int k) { return mfma_reg_supported(d_pad, k) || mfma_lds_supported(d_pad, k); }
 
@@ -1002,13 +1392,13 @@ hipError_t launch_seed_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int
     o.gmax = gmax; o.SEG = SEG;
     if (piece_stride) {
         // every piece lies inside [row0, row1): the last one starts at (S * 8 * piece_stages - 1) * piece_stride
-        if (a.rsplit || row0 != 0 || piece_stages < 1 || piece_stride < 8 ||
+        if (a.rsplit || long_shape_ok(a.d_pad) || row0 != 0 || piece_stages < 1 || piece_stride < 8 ||
             ((int64_t)S * 8 * piece_stages - 1) * piece_stride + 8 > row1)
             return hipErrorInvalidValue;
         o.piece_stride = piece_stride;
         o.piece_stages = piece_stages;
     } else if (stage_stride) {
-        const int rs_rows = a.rsplit ? 32 * a.rs_waves : 64;
+        const int rs_rows = a.rsplit ? 32 * a.rs_waves : (long_shape_ok(a.d_pad) ? 32 : 64);
         if (stages_per_split < 1 || stage_stride < rs_rows || stage_stride % 128) return hipErrorInvalidValue;
         o.stage_stride = stage_stride;
         o.split_stride = stage_stride * stages_per_split;

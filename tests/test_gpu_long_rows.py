@@ -1,0 +1,85 @@
+"""Rows of more than 256 features (up to 1024): the matrix-core collecting scan for long rows and its
+seeding pass against the CPU oracle, bit-exact on ids and int32 distances.  Needs a real MI355X."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2110_08919_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lpq():
+    from paper_2110_08919_amd import lpq as m
+    assert torch.cuda.is_available(), "no GPU visible"
+    m.lib()
+    return m
+
+
+def _workload(recipe, d, n, nq, metric):
+    return synth.Workload(f"{recipe}_x{d}", recipe, n, d, nq, metric, (10,), "minmax", "global", 3)
+
+
+def _case(lpq, oracle, w, k, metric, mode, scope, expect_collecting=True):
+    x, q = w.corpus("cuda"), w.queries("cuda")
+    gq = lpq.Quantizer(w.d, 8).calibrate(x, mode, scope)
+    index = lpq.Index(gq, w.n).add_f32(x)
+    ws = torch.empty(index.workspace_bytes(w.nq, k, metric) + 256, dtype=torch.uint8, device="cuda")
+    ids, dists = index.search(q, k, metric, workspace=ws)
+    torch.cuda.synchronize()
+    kk, sb, se, _ = gq.get_params()
+    oq = oracle.Quantizer(gq.d, gq.bits).set_params(kk, sb, se)
+    oids, odists = oracle.search_i8(oq.encode(x.cpu().numpy()), oq.encode(q.cpu().numpy()), k, metric, threads=16)
+    assert np.array_equal(dists.cpu().numpy(), odists)
+    assert np.array_equal(ids.cpu().numpy(), oids)
+    if expect_collecting:
+        _, fill = index.overflow_stats(w.nq, k, metric, ws)
+        assert fill > 0, "the collecting scan was expected to run here"
+    return index, ws
+
+
+@pytest.mark.parametrize("recipe,d,n,nq,k,metric,mode,scope", [
+    ("bimodal", 300, 70_003, 130, 10, "l2sq", "minmax", "per_feature"),   # padded to 384, ragged tail
+    ("scaled_unit", 384, 66_000, 5, 10, "ip", "absmax", "global"),
+    ("skewed_int", 500, 80_000, 257, 100, "l2sq", "minmax", "global"),    # padded to 512, k = 100
+    ("bimodal", 512, 90_011, 64, 10, "ip", "absmax", "per_feature"),
+    ("scaled_unit", 700, 70_000, 129, 17, "l2sq", "absmax", "global"),    # padded to 768
+    ("bimodal", 768, 100_000, 300, 10, "l2sq", "minmax", "per_feature"),
+    ("skewed_int", 960, 65_536, 33, 128, "l2sq", "minmax", "global"),     # padded to 1024, largest k of the scan
+    ("bimodal", 1024, 75_001, 1, 10, "ip", "absmax", "global"),
+])
+def test_search_long_rows(lpq, oracle, recipe, d, n, nq, k, metric, mode, scope):
+    _case(lpq, oracle, _workload(recipe, d, n, nq, metric), k, metric, mode, scope)
+
+
+@pytest.mark.parametrize("d", [384, 1024])
+def test_search_long_rows_overflow_is_redone_exactly(lpq, oracle, d):
+    """A sample far too small for k = 100: queries whose regions overflow go through the further
+    rounds of the scan (and what still overflows through the generic kernel) and come back exact."""
+    lpq.set_tuning(lpq.TUNE_SEED_ROWS, 8192)
+    try:
+        _case(lpq, oracle, _workload("skewed_int", d, 200_000, 70, "l2sq"), 100, "l2sq", "minmax", "global")
+    finally:
+        lpq.set_tuning(lpq.TUNE_SEED_ROWS, 0)
+
+
+def test_search_long_rows_extreme_codes(lpq, oracle):
+    """Codes at the ends of the range in 1024 dimensions: the largest dot products and norms the
+    long-row scan meets, on a corpus large enough for its seeding pass."""
+    d, n = 1024, 70_000
+    rng = np.random.default_rng(21)
+    c = rng.choice(np.array([-128, 127], np.int8), size=(n, d))
+    q = rng.choice(np.array([-128, 127], np.int8), size=(40, d))
+    gq = lpq.Quantizer(d, 8).set_params(np.zeros(d), np.full(d, -128.0), np.full(d, 128.0))
+    idx = lpq.Index(gq, n).add_i8(torch.as_tensor(c).cuda())
+    for metric in ("l2sq", "ip"):
+        ids, dists = idx.search(torch.as_tensor(q).cuda(), 20, metric)
+        oids, odists = oracle.search_i8(c, q, 20, metric, threads=16)
+        assert np.array_equal(ids.cpu().numpy(), oids) and np.array_equal(dists.cpu().numpy(), odists)
+
+
+def test_search_long_rows_small_corpus_and_large_k_take_the_generic_kernel(lpq, oracle):
+    """Below the smallest sample, and for k beyond 128, long rows are searched by the generic kernel."""
+    _case(lpq, oracle, _workload("bimodal", 768, 3000, 9, "l2sq"), 10, "l2sq", "minmax", "global", expect_collecting=False)
+    _case(lpq, oracle, _workload("bimodal", 600, 40_000, 3, "ip"), 200, "ip", "absmax", "global", expect_collecting=False)
