@@ -621,7 +621,10 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
             p.wave_queries = 128;
         if (p.mode == PLAN_MFMA_COLLECT && idx->packed)   // the packed scan has one variant per row length
             p.wave_queries = idx->d_pad <= 128 ? 128 : 64;
-        if (mfma_long_rows(idx->d_pad)) p.wave_queries = mfma_long_wave_queries(idx->d_pad);
+        if (mfma_long_rows(idx->d_pad)) {
+            p.wave_queries = mfma_long_wave_queries(idx->d_pad);
+            if (mfma_long_waves(idx->d_pad, nq) == 8) slots_now = 256;   // one workgroup per CU
+        }
         qt = mfma_queries_per_workgroup(nq, idx->d_pad, p.wave_queries == 128);
     }
     const int64_t tiles_q = ceil_div(nq > 0 ? nq : 1, qt);

@@ -155,6 +155,7 @@ int mfma_queries_per_workgroup(int64_t nq, int d_pad, bool wide = false);   // q
 bool mfma_collect_wide(int64_t nq, int d_pad);           // collecting mode may use 128 queries per wave
 bool mfma_row_split(int64_t nq, int d_pad, bool packed = false);   // few queries: waves split rows, share queries
 bool mfma_long_rows(int d_pad);            // rows of 384, 512, 768 or 1024 bytes: their own collecting scan and seeding pass
+int mfma_long_waves(int d_pad, int64_t nq);           // ... in workgroups of this many waves (4: two workgroups per CU, 8: one)
 int mfma_long_wave_queries(int d_pad);     // ... which keep 64 (up to 512 bytes) or 32 queries per wave
 int mfma_row_split_waves(int d_pad, bool packed);   // 4 on rows of up to 128 bytes, 2 on longer ones (collecting scan and seeding pass only)
 // With stage_stride > 0 (a multiple of 128) the pass is a systematic sample of [row0, row1): one

@@ -43,6 +43,7 @@ __device__ __forceinline__ unsigned lds_offset(const void *p)
 
 // s_waitcnt vmcnt(n) with n a run-time value in 0..63 (other counters untouched).  The count is
 // an immediate, split over bits 3:0 and 15:14 of the operand.
+constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }   // operand of s_waitcnt vmcnt(n)
 #define LPQ_WAITCNT_CASE(N) case N: __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14)); break;
 #define LPQ_WAITCNT_CASES8(B) LPQ_WAITCNT_CASE(B) LPQ_WAITCNT_CASE(B + 1) LPQ_WAITCNT_CASE(B + 2) LPQ_WAITCNT_CASE(B + 3) \
     LPQ_WAITCNT_CASE(B + 4) LPQ_WAITCNT_CASE(B + 5) LPQ_WAITCNT_CASE(B + 6) LPQ_WAITCNT_CASE(B + 7)

@@ -42,10 +42,11 @@ def _case(lpq, oracle, w, k, metric, mode, scope, expect_collecting=True):
 @pytest.mark.parametrize("recipe,d,n,nq,k,metric,mode,scope", [
     ("bimodal", 300, 70_003, 130, 10, "l2sq", "minmax", "per_feature"),   # padded to 384, ragged tail
     ("scaled_unit", 384, 66_000, 5, 10, "ip", "absmax", "global"),
-    ("skewed_int", 500, 80_000, 257, 100, "l2sq", "minmax", "global"),    # padded to 512, k = 100
+    ("skewed_int", 500, 80_000, 1030, 100, "l2sq", "minmax", "global"),   # padded to 512, k = 100; eight-wave workgroups
     ("bimodal", 512, 90_011, 64, 10, "ip", "absmax", "per_feature"),
     ("scaled_unit", 700, 70_000, 129, 17, "l2sq", "absmax", "global"),    # padded to 768
-    ("bimodal", 768, 100_000, 300, 10, "l2sq", "minmax", "per_feature"),
+    ("bimodal", 768, 100_000, 700, 10, "l2sq", "minmax", "per_feature"),  # eight-wave workgroups
+    ("scaled_unit", 1000, 66_000, 513, 10, "ip", "absmax", "global"),
     ("skewed_int", 960, 65_536, 33, 128, "l2sq", "minmax", "global"),     # padded to 1024, largest k of the scan
     ("bimodal", 1024, 75_001, 1, 10, "ip", "absmax", "global"),
 ])
@@ -59,7 +60,7 @@ def test_search_long_rows_overflow_is_redone_exactly(lpq, oracle, d):
     rounds of the scan (and what still overflows through the generic kernel) and come back exact."""
     lpq.set_tuning(lpq.TUNE_SEED_ROWS, 8192)
     try:
-        _case(lpq, oracle, _workload("skewed_int", d, 200_000, 70, "l2sq"), 100, "l2sq", "minmax", "global")
+        _case(lpq, oracle, _workload("skewed_int", d, 200_000, 70 if d == 384 else 600, "l2sq"), 100, "l2sq", "minmax", "global")
     finally:
         lpq.set_tuning(lpq.TUNE_SEED_ROWS, 0)
 
