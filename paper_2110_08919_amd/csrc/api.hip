@@ -612,6 +612,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     const bool gmode = p.mode == PLAN_MFMA_REG || p.mode == PLAN_MFMA_COLLECT;
     int64_t qt = (p.mode == PLAN_MFMA_LDS && k > 16) ? 128 : 256;   // queries per workgroup
     int64_t slots_now = slots;
+    bool long_scan = false;
     if (gmode) {
         // (rows of more than 128 bytes: the collecting scan only - the register lists do not fit beside them)
         const int waves = mfma_row_split_waves(idx->d_pad, idx->packed);
@@ -621,11 +622,13 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
             p.wave_queries = 128;
         if (p.mode == PLAN_MFMA_COLLECT && idx->packed)   // the packed scan has one variant per row length
             p.wave_queries = idx->d_pad <= 128 ? 128 : 64;
-        if (mfma_long_rows(idx->d_pad)) {
+        qt = mfma_queries_per_workgroup(nq, idx->d_pad, p.wave_queries == 128);
+        long_scan = p.mode == PLAN_MFMA_COLLECT && !idx->packed && !p.rsplit && mfma_long_rows(idx->d_pad, nq);
+        if (long_scan) {   // the scan for long rows and its seeding pass have their own tiles
             p.wave_queries = mfma_long_wave_queries(idx->d_pad);
+            qt = (int64_t)mfma_long_waves(idx->d_pad, nq) * p.wave_queries;
             if (mfma_long_waves(idx->d_pad, nq) == 8) slots_now = 256;   // one workgroup per CU
         }
-        qt = mfma_queries_per_workgroup(nq, idx->d_pad, p.wave_queries == 128);
     }
     const int64_t tiles_q = ceil_div(nq > 0 ? nq : 1, qt);
     const int64_t min_rows = p.mode == PLAN_GENERIC ? 2048 : 512;
@@ -636,7 +639,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
             p.SEG = mfma_seed_segments(p.S1, k, p.rs_waves);
             p.G = mfma_seed_groups(p.S1, p.SEG, p.rs_waves);
             // systematic sample: one stage every seed_stride rows, shared out over the S1 splits
-            const int64_t stage_rows = p.rsplit ? 32 * p.rs_waves : (mfma_long_rows(idx->d_pad) ? 32 : 64);
+            const int64_t stage_rows = p.rsplit ? 32 * p.rs_waves : (long_scan ? 32 : 64);
             const int64_t stages = seed / stage_rows;
             p.seed_stages = (int)ceil_div(stages, p.S1);
             p.seed_stride = n / ((int64_t)p.seed_stages * p.S1) / 128 * 128;
@@ -647,7 +650,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
             // contiguously - is spread over many splits and hence over many groups of the pass.
             // (For k > 16 on a corpus sorted by norm a split's groups then span wide slices of the order
             // and up to a tenth of the queries overflow; the further rounds of the scan take those.)
-            if (!p.rsplit && !mfma_long_rows(idx->d_pad)) {
+            if (!p.rsplit && !long_scan) {
                 const int64_t pstages = ceil_div(stages, p.S1);                 // as many rows as the stage-wise sample
                 const int64_t pstride = pstages > 0 ? n / (8 * pstages * p.S1) : 0;   // all pieces inside the corpus
                 if (pstride >= 16 && pstages >= 1) {

@@ -767,30 +767,34 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     }
 }
 
-// ---- rows of 384 to 1024 bytes ----------------------------------------------------------------
+// ---- rows of 384 to 1024 bytes, and large batches on rows of 192 and 256 bytes -----------------
 // The collecting scan and its seeding pass for rows whose operands no longer fit the scheme above
 // (query fragments AND two row blocks' worth of corpus fragments in registers).  What changes:
-//   - a wave holds the fragments of 32 queries (rows of 768 or 1024 bytes) or 64 (384 or 512 bytes):
-//     128 registers at most;
+//   - a wave holds the fragments of 32 queries (rows of 768 or 1024 bytes), 64 (384 or 512 bytes) or
+//     128 (192 or 256 bytes): 128 registers at most;
 //   - a stage is ONE block of 32 rows by one segment of the row (the whole row up to 512 bytes, else
 //     a half), 12 or 16 KB, in a ring of three; the accumulators of a row block live across its
 //     segments, are seeded when its first segment starts and filtered when its last one ends;
-//   - corpus fragments come from LDS four k-steps at a time, one group ahead of the matrix
+//   - corpus fragments come from LDS two to four k-steps at a time, one group ahead of the matrix
 //     instructions that use them; the group that crosses into the next stage is read right after the
 //     workgroup barrier that says the stage has landed.
 // Chunks (16 bytes) of a row segment are swizzled inside aligned groups of 2^SWB chunks: with the
 // row stride of 512 bytes (a multiple of the 256 bytes the 64 banks cover) the low four bits of the
 // row number do it; with 384 bytes odd rows start half way round the banks, so three bits taken
 // from bit 1 up give 16 consecutive rows 16 different bank groups as well.
+// (Segments of 256 bytes behave like 512, and with 192 bytes a row starts at one of four places
+// round the banks, so two bits taken from bit 2 up do it, in groups of four chunks.)
 template <int CPS>
 __device__ __forceinline__ int long_slot(int c, int r)
 {
-    constexpr int SWB = CPS == 32 ? 4 : 3, MASK = (1 << SWB) - 1;
-    const int sw = CPS == 32 ? (r & 15) : ((r >> 1) & 7);
+    constexpr int SWB = CPS % 16 == 0 ? 4 : (CPS % 8 == 0 ? 3 : 2), MASK = (1 << SWB) - 1;
+    const int sw = SWB == 4 ? (r & 15) : (SWB == 3 ? ((r >> 1) & 7) : ((r >> 2) & 3));
     return (c & ~MASK) | ((c ^ sw) & MASK);
 }
 
-constexpr int long_nst(int kseg, int nw) { return nw == 4 ? 3 : (kseg == 12 ? 6 : 5); }
+// blocks of 32 queries per wave: as many as 128 registers of query fragments allow
+constexpr int long_nb(int kseg, int nseg) { return nseg == 2 ? 1 : (kseg >= 12 ? 2 : 4); }
+constexpr int long_nst(int kseg, int nw) { return nw == 4 ? (kseg <= 8 ? 4 : 3) : (kseg <= 12 ? 6 : 5); }
 constexpr size_t long_lds_bytes(int kseg, int nb, bool seed, int nw)
 {
     return (size_t)long_nst(kseg, nw) * 32 * kseg * 32 + (size_t)long_nst(kseg, nw) * (32 + 4) * 4 + 64 +
@@ -802,9 +806,10 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void search_long_kernel(
     SearchArgs a, int64_t row0, int64_t row1, int S, int64_t split_rows, int qtiles, MfmaIo o)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    static_assert((KSEG == 12 || KSEG == 16) && (NSEG == 1 || NSEG == 2), "rows of 384, 512, 768 or 1024 bytes");
+    static_assert(((KSEG == 12 || KSEG == 16) && (NSEG == 1 || NSEG == 2)) || ((KSEG == 6 || KSEG == 8) && NSEG == 1),
+                  "rows of 192, 256, 384, 512, 768 or 1024 bytes");
     static_assert(NW == 4 || NW == 8, "four waves (two workgroups per CU) or eight (one)");
-    constexpr int NB = NSEG == 1 ? 2 : 1;      // blocks of 32 queries per wave
+    constexpr int NB = long_nb(KSEG, NSEG);    // blocks of 32 queries per wave
     constexpr int QW = NB * 32, QT = NW * QW;
     constexpr int KTOT = KSEG * NSEG;          // k-steps (32 bytes) per row
     constexpr int ROWB = KTOT * 32, SEGB = KSEG * 32;
@@ -815,8 +820,9 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void search_long_kernel(
     constexpr int NI = RS * CPS / 64;          // copy instructions per stage: wave w issues w, w + NW, ...
     constexpr int IPW = (NI + NW - 1) / NW;    // ... at most this many
     constexpr int AUX_INTS = RS + 4;           // accumulator seeds of the 32 rows, then their parity word
-    constexpr int NG = KSEG / 4;               // groups of four k-steps per segment
-    constexpr int PER = CPS == 32 ? 8 : 4;     // k-steps after which the swizzle pattern of a lane repeats
+    constexpr int GS = KSEG == 6 ? 3 : (KSEG == 8 ? 2 : 4);   // k-steps per group of fragments (each feeds NB matrix instructions)
+    constexpr int NG = KSEG / GS;              // groups per segment
+    constexpr int PER = CPS % 16 == 0 ? 8 : (CPS % 8 == 0 ? 4 : 2);   // k-steps after which a lane's swizzle pattern repeats
     static_assert((NST - 1) * (IPW + 1) <= 63, "wait_vmcnt covers 0..63");
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -902,11 +908,13 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void search_long_kernel(
         gm[nb] = INT32_MIN;
     }
     int qcnt = 0;
-    // byte offset, inside a stage, of this lane's fragment of k-step ks (of the segment) for ks < PER;
-    // k-step ks is a_off[ks % PER] + (ks / PER) * PER * 32
-    int a_off[PER];
-#pragma unroll
-    for (int ks = 0; ks < PER; ++ks) a_off[ks] = col * SEGB + long_slot<CPS>(2 * ks + half, col) * 16;
+    // Byte offset, inside a stage, of this lane's fragment of k-step ks (of the segment): the chunk
+    // 2 ks + half sits in slot long_slot(2 ks + half, col), which differs from the slot of k-step 0
+    // only in the bits ks % PER sets (the row's start has those address bits clear), so one register
+    // and an exclusive-or with a constant per read replace a table of PER offsets:
+    // offset(ks) = (a_base ^ ((ks % PER) << 5)) + (ks / PER) * PER * 32.
+    const int a_base = col * SEGB + long_slot<CPS>(half, col) * 16;
+    static_assert(SEGB % (PER * 32) == 0, "a row starts on a multiple of the swizzle group");
 
     // Stage loader: LDS position p (16 bytes) of a stage = (row p / CPS, slot p % CPS); instruction j of
     // a wave fills positions [(wave * IPW + j) * 64, + 64), each lane fetching the chunk that belongs
@@ -941,9 +949,9 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void search_long_kernel(
 #define LPQL_LOAD_GROUP(SLOT, G, AREG)                                                                  \
     do {                                                                                                \
         const unsigned char *sb_ = ring + (size_t)(SLOT) * STAGE_BYTES;                                 \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                 \
-            const int ks_ = (G) * 4 + i;                                                                \
-            AREG[i] = *reinterpret_cast<const v4i *>(sb_ + a_off[ks_ % PER] + (ks_ / PER) * (PER * 32)); \
+        _Pragma("unroll") for (int i = 0; i < GS; ++i) {                                                \
+            const int ks_ = (G) * GS + i;                                                               \
+            AREG[i] = *reinterpret_cast<const v4i *>(sb_ + (a_base ^ ((ks_ % PER) << 5)) + (ks_ / PER) * (PER * 32)); \
         }                                                                                               \
     } while (0)
     // accumulator seeds and parity word of the row block whose (first) stage sits in ring slot SLOT
@@ -1019,7 +1027,10 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void search_long_kernel(
     // here on only async copies (and appended candidates) are outstanding on the vector-memory counter.
     __builtin_amdgcn_s_waitcnt(0x0F70);
 
-    v4i An[4];           // the group read ahead
+    // Seeds and parity word of a row block are read one stage ahead, except with 128 queries per
+    // wave, where the 16 registers that takes are not there: the block then reads them as it starts.
+    constexpr bool SEEDS_AHEAD = NB < 4;
+    v4i An[GS];          // the group read ahead
     v16i Cn;             // seeds and parity word of the row block that starts next
     unsigned Pn = 0;
     const int primed = T < NST ? T : NST;
@@ -1029,7 +1040,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void search_long_kernel(
         wait_vmcnt((primed - 1) * lpt);
         __syncthreads();
         LPQL_LOAD_GROUP(0, 0, An);
-        LPQL_LOAD_SEEDS(0, Cn, Pn);
+        if (SEEDS_AHEAD) LPQL_LOAD_SEEDS(0, Cn, Pn);
     }
     int t = 0;
     for (int rb = 0; rb < RB; ++rb) {
@@ -1040,10 +1051,13 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void search_long_kernel(
         for (int seg = 0; seg < NSEG; ++seg, ++t) {
 #pragma unroll
             for (int g = 0; g < NG; ++g) {
-                v4i Ac[4];
+                v4i Ac[GS];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) Ac[i] = An[i];
-                if (seg == 0 && g == 0) { Cc = Cn; Pc = Pn; }
+                for (int i = 0; i < GS; ++i) Ac[i] = An[i];
+                if (seg == 0 && g == 0) {
+                    if (SEEDS_AHEAD) { Cc = Cn; Pc = Pn; }
+                    else LPQL_LOAD_SEEDS(slot, Cc, Pc);   // the stage's slot is refilled only after its last group
+                }
                 if (g + 1 < NG) {
                     LPQL_LOAD_GROUP(slot, g + 1, An);
                 } else {
@@ -1083,21 +1097,21 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void search_long_kernel(
                     const int nslot = slot + 1 == NST ? 0 : slot + 1;
                     if (t + 1 < T) {
                         LPQL_LOAD_GROUP(nslot, 0, An);
-                        if (seg + 1 == NSEG) LPQL_LOAD_SEEDS(nslot, Cn, Pn);
+                        if (SEEDS_AHEAD && seg + 1 == NSEG) LPQL_LOAD_SEEDS(nslot, Cn, Pn);
                     }
                     slot = nslot;
                 }
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < GS; ++i)
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb)
-                        acc[nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Ac[i], B[nb][seg * KSEG + g * 4 + i],
+                        acc[nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Ac[i], B[nb][seg * KSEG + g * GS + i],
                                                                         (seg == 0 && g == 0 && i == 0) ? Cc : acc[nb], 0, 0, 0);
                 // Keep the reads of the next group in front of this group's matrix instructions: left
                 // alone, the compiler moves each read down to the instruction that needs it and every
                 // matrix instruction then waits out a full LDS round trip.
-                __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);        // 4 LDS reads
-                __builtin_amdgcn_sched_group_barrier(0x008, 4 * NB, 0);   // 4 NB matrix instructions
+                __builtin_amdgcn_sched_group_barrier(0x100, GS, 0);        // the group's LDS reads
+                __builtin_amdgcn_sched_group_barrier(0x008, GS * NB, 0);   // GS * NB matrix instructions
             }
         }
         const int rowbase = (int)(rs + (int64_t)rb * bstride);
@@ -1279,11 +1293,17 @@ hipError_t launch_ks(const SearchArgs &a, int64_t row0, int64_t row1, int S, con
               : launch_one<KS, false, 16, false>(a, row0, row1, S, o, st);
 }
 
+// Launches the plan laid out for the long-row scan (its query tile says so).
+bool takes_long_scan(const SearchArgs &a)
+{
+    return mfma_long_rows(a.d_pad, a.nq) && !a.rsplit && !a.packed && a.wave_queries == mfma_long_wave_queries(a.d_pad);
+}
+
 // Rows of 384 to 1024 bytes: the collecting scan (o.cbuf) or its seeding pass (o.gmax).
 template <int KSEG, int NSEG, bool L2, bool SEED, int NW>
 hipError_t launch_long_nw(const SearchArgs &a, int64_t row0, int64_t row1, int S, MfmaIo o, hipStream_t st)
 {
-    constexpr int NB = NSEG == 1 ? 2 : 1;
+    constexpr int NB = long_nb(KSEG, NSEG);
     if (a.rsplit || a.packed || a.wave_queries != NB * 32) return hipErrorInvalidValue;
     const int64_t split_rows = o.split_stride ? o.split_stride_rows : round_up(ceil_div(row1 - row0, S), 128);
     if (!o.split_stride) o.split_stride = split_rows;
@@ -1324,12 +1344,16 @@ hipError_t launch_any(const SearchArgs &a, int64_t row0, int64_t row1, int S, co
 {
     if (a.nq <= 0 || row1 <= row0) return hipSuccess;
     if (row0 % 128 || o.split_stride % 128) return hipErrorInvalidValue;  // stages and parity words cover aligned blocks
-    switch (a.d_pad / 32) {
-    case 12: return launch_long<12, 1>(a, row0, row1, S, o, st);
-    case 16: return launch_long<16, 1>(a, row0, row1, S, o, st);
-    case 24: return launch_long<12, 2>(a, row0, row1, S, o, st);
-    case 32: return launch_long<16, 2>(a, row0, row1, S, o, st);
-    default: break;
+    if (takes_long_scan(a) && (o.gmax || o.cbuf)) {
+        switch (a.d_pad / 32) {
+        case 6: return launch_long<6, 1>(a, row0, row1, S, o, st);
+        case 8: return launch_long<8, 1>(a, row0, row1, S, o, st);
+        case 12: return launch_long<12, 1>(a, row0, row1, S, o, st);
+        case 16: return launch_long<16, 1>(a, row0, row1, S, o, st);
+        case 24: return launch_long<12, 2>(a, row0, row1, S, o, st);
+        case 32: return launch_long<16, 2>(a, row0, row1, S, o, st);
+        default: break;
+        }
     }
     switch (a.d_pad / 32) {
     case 2: return launch_ks<2>(a, row0, row1, S, o, st);
@@ -1358,15 +1382,25 @@ int mfma_queries_per_workgroup(int64_t nq, int d_pad, bool wide)
 }
 
 // Rows of more than 256 bytes (384, 512, 768 or 1024: the collecting scan and its seeding pass only).
-bool mfma_long_rows(int d_pad) { return long_shape_ok(d_pad); }
+bool mfma_long_rows(int d_pad, int64_t nq)
+{
+    // Rows of 192 and 256 bytes: the same scan with 128 queries per wave (eight-wave workgroups,
+    // tiles of 1024 queries) measured 9 to 15 % faster than the 64-queries-per-wave tile of the
+    // kernel above on large batches (4M x 256, 10 000 queries, k = 100: 11.2 -> 9.6 ms), half of that
+    // with four waves, and slower on partly filled tiles (256 queries: 0.13 -> 0.17 ms): taken when
+    // the padding of the batch to its tiles does not eat the gain.
+    if (d_pad == 192 || d_pad == 256)
+        return nq > 1024 && round_up(nq, 1024) * 87 <= round_up(nq, 256) * 100;
+    return long_shape_ok(d_pad);
+}
 
-int mfma_long_wave_queries(int d_pad) { return d_pad <= 512 ? 64 : 32; }
+int mfma_long_wave_queries(int d_pad) { return d_pad <= 256 ? 128 : (d_pad <= 512 ? 64 : 32); }
 
 // Eight waves per workgroup (one workgroup per CU, a ring of five or six stages) for large batches:
 // half the corpus bytes per contraction go through the L2, measured 4 to 14 % faster at 10 000
 // queries; four waves (two workgroups per CU) finish small batches sooner (16 queries on
 // 500K x 1024: 0.18 against 0.22 ms).
-int mfma_long_waves(int d_pad, int64_t nq) { (void)d_pad; return nq > 512 ? 8 : 4; }
+int mfma_long_waves(int d_pad, int64_t nq) { return (d_pad <= 256 || nq > 512) ? 8 : 4; }
 
 // Collecting mode: 128 queries per wave when the rows are short enough for the registers to hold them.
 bool mfma_collect_wide(int64_t nq, int d_pad) { return !mfma_row_split(nq, d_pad) && d_pad <= 128 && nq > 256; }
@@ -1427,13 +1461,13 @@ hipError_t launch_seed_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int
     o.gmax = gmax; o.SEG = SEG;
     if (piece_stride) {
         // every piece lies inside [row0, row1): the last one starts at (S * 8 * piece_stages - 1) * piece_stride
-        if (a.rsplit || long_shape_ok(a.d_pad) || row0 != 0 || piece_stages < 1 || piece_stride < 8 ||
+        if (a.rsplit || takes_long_scan(a) || row0 != 0 || piece_stages < 1 || piece_stride < 8 ||
             ((int64_t)S * 8 * piece_stages - 1) * piece_stride + 8 > row1)
             return hipErrorInvalidValue;
         o.piece_stride = piece_stride;
         o.piece_stages = piece_stages;
     } else if (stage_stride) {
-        const int rs_rows = a.rsplit ? 32 * a.rs_waves : (long_shape_ok(a.d_pad) ? 32 : 64);
+        const int rs_rows = a.rsplit ? 32 * a.rs_waves : (takes_long_scan(a) ? 32 : 64);
         if (stages_per_split < 1 || stage_stride < rs_rows || stage_stride % 128) return hipErrorInvalidValue;
         o.stage_stride = stage_stride;
         o.split_stride = stage_stride * stages_per_split;

@@ -97,14 +97,16 @@ def test_config4_scaled_10m_x96_batch_sweep(lpq, oracle):
 def test_config5_product_x256_ip_k100(lpq, oracle):
     """d = 256, inner product, k = 100 on the bimodal product-embedding recipe.  The corpus is
     20M rows by default: 5.1 GB of codes, so byte offsets into them pass 2^32 (they do from 16.8M
-    rows on) in the batched scan, in the two-wave row-split scan of a 16-query batch and in the
-    gathered-distance call, whose listed ids include the last rows.  LPQ_TEST_CONFIG5_ROWS sets
+    rows on) in the batched scan of 2000 queries (128 queries per wave), in that of its first 1000
+    (64 per wave), in the two-wave row-split scan of a 16-query batch and in the gathered-distance
+    call, whose listed ids include the last rows.  LPQ_TEST_CONFIG5_ROWS sets
     another size; LPQ_TEST_FULL_100M=1 runs all 100M rows (25.6 GB of codes; the oracle then needs
     several minutes and ~130 GB of host memory)."""
     n = 100_000_000 if os.environ.get("LPQ_TEST_FULL_100M") == "1" else int(os.environ.get("LPQ_TEST_CONFIG5_ROWS", 20_000_000))
-    w = synth.PRODUCT_100M.scaled(n=n, nq=1000)
+    w = synth.PRODUCT_100M.scaled(n=n, nq=2000)
     print(f"[{w.name}] {n} rows x {w.d}: {n * 256 / 2**30:.2f} GiB of codes", flush=True)
-    index, q, ids, codes, qcodes = _full_case(lpq, oracle, w, 100, "absmax", "per_feature", sample=4, batches=(16,))
+    index, q, ids, codes, qcodes = _full_case(lpq, oracle, w, 100, "absmax", "per_feature", sample=4, batches=(16, 1000))
+    assert lpq.search_plan_info(w.d, 8, 0, n, 2000, 100)[3] == 128 and lpq.search_plan_info(w.d, 8, 0, n, 1000, 100)[3] == 64
     # distances to listed items, the lists naming rows on both sides of the 4 GiB byte offset and the last rows
     m, nqg = 64, 8
     gids = np.random.default_rng(5).integers(0, n, size=(nqg, m), dtype=np.int64)

@@ -1,5 +1,6 @@
-"""Rows of more than 256 features (up to 1024): the matrix-core collecting scan for long rows and its
-seeding pass against the CPU oracle, bit-exact on ids and int32 distances.  Needs a real MI355X."""
+"""The matrix-core collecting scan for long rows and its seeding pass (rows of 257 to 1024 features,
+and large batches on rows of 192 and 256 bytes) against the CPU oracle, bit-exact on ids and int32
+distances.  Needs a real MI355X."""
 import numpy as np
 import pytest
 import torch
@@ -51,6 +52,19 @@ def _case(lpq, oracle, w, k, metric, mode, scope, expect_collecting=True):
     ("bimodal", 1024, 75_001, 1, 10, "ip", "absmax", "global"),
 ])
 def test_search_long_rows(lpq, oracle, recipe, d, n, nq, k, metric, mode, scope):
+    _case(lpq, oracle, _workload(recipe, d, n, nq, metric), k, metric, mode, scope)
+
+
+@pytest.mark.parametrize("recipe,d,n,nq,k,metric,mode,scope", [
+    ("bimodal", 256, 70_000, 2000, 100, "ip", "absmax", "per_feature"),
+    ("skewed_int", 256, 80_003, 1900, 10, "l2sq", "minmax", "global"),
+    ("scaled_unit", 180, 66_000, 2048, 16, "l2sq", "absmax", "global"),   # padded to 192
+    ("bimodal", 192, 90_000, 3000, 40, "ip", "absmax", "global"),
+])
+def test_search_large_batches_on_rows_of_192_and_256_bytes(lpq, oracle, recipe, d, n, nq, k, metric, mode, scope):
+    """Large batches on rows of 192 and 256 bytes take the same scan with 128 queries per wave."""
+    assert lpq.search_plan_info(d, 8, 0, n, nq, k)[3] == 128, "the 128-queries-per-wave tile was expected here"
+    assert lpq.search_plan_info(d, 8, 0, n, 1100, k)[3] == 64, "a batch that would mostly pad its tiles keeps the 64-query tile"
     _case(lpq, oracle, _workload(recipe, d, n, nq, metric), k, metric, mode, scope)
 
 
