@@ -161,6 +161,7 @@ def main():
     ap.add_argument("--seed-rows", type=int, default=0)
     ap.add_argument("--workload", default="skewed_1m", choices=["tiny", "skewed_1m", "aniso_1m2", "scaled_10m", "product_100m"],
                     help="synthetic workload shape (default: the benchmark configuration)")
+    ap.add_argument("--d", type=int, default=0, help="features per vector instead of the workload's (same recipe and seed)")
     ap.add_argument("--bits", type=int, default=8, help="bits per code B of Equation 1 (default 8)")
     ap.add_argument("--packed", action="store_true", help="store two codes per byte (needs --bits <= 4, k <= 16)")
     ap.add_argument("--calib", default="", help="calibration mode instead of the workload's (minmax, absmax, gauss, quantile)")
@@ -188,6 +189,8 @@ def main():
     base = {"tiny": synth.TINY, "skewed_1m": synth.SKEWED_1M, "aniso_1m2": synth.ANISO_1M2,
             "scaled_10m": synth.SCALED_10M, "product_100m": synth.PRODUCT_100M}[args.workload]
     w = base.scaled(n=args.n or None, nq=args.nq or None)
+    if args.d:
+        w = synth.Workload(f"{w.recipe}_{w.n}_x{args.d}", w.recipe, w.n, args.d, w.nq, w.metric, w.ks, w.calib, w.scope, w.seed)
     k, metric = args.k, w.metric
 
     # ---- inputs and index build (not part of the timed search step) -------------------
@@ -262,11 +265,14 @@ def main():
         roofline = {"bound": "hbm", "achieved": bytes_per_launch / (kern_ms_per_launch * 1e-3) / 1e9,
                     "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": hbm_frac, "traffic": None}
     default_workload = (args.workload == "skewed_1m" and args.n == 0 and args.nq == 0 and args.k == 10 and args.path == 0
-                        and args.splits == 0 and args.seed_rows == 0 and args.bits == 8 and not args.packed
+                        and args.splits == 0 and args.seed_rows == 0 and args.bits == 8 and not args.packed and args.d == 0
                         and not args.calib and not args.scope)
     roofline["traffic"] = TRAFFIC_BYTES_DEFAULT_WORKLOAD if default_workload else None
     roofline["traffic_source"] = TRAFFIC_SOURCE if default_workload else None
-    roofline["kernel"] = "search_mfma_kernel, main scan (contraction + top-k over all corpus rows)"
+    plan = lpq.search_plan_info(w.d, args.bits, int(args.packed), w.n, int(q.shape[0]), k)
+    long_scan = w.d > 256 or (w.d > 128 and plan[3] == 128)   # the scan for long rows (its query tile says so)
+    roofline["kernel"] = ("search_long_kernel" if long_scan else "search_mfma_kernel") + \
+        ", main scan (contraction + top-k over all corpus rows)"
     roofline["kernel_ms_per_launch"] = kern_ms_per_launch
     roofline["launches_per_step"] = launches_per_step
     roofline["seeding_pass_ms_per_step"] = seed_ms / args.steps
