@@ -773,8 +773,8 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
 //   - a wave holds the fragments of 32 queries (rows of 768 or 1024 bytes), 64 (384 or 512 bytes) or
 //     128 (192 or 256 bytes): 128 registers at most;
 //   - a stage is ONE block of 32 rows by one segment of the row (the whole row up to 512 bytes, else
-//     a half), 12 or 16 KB, in a ring of three; the accumulators of a row block live across its
-//     segments, are seeded when its first segment starts and filtered when its last one ends;
+//     a half), 6 to 16 KB, in a ring of three to six; the accumulators of a row block live across
+//     its segments, are seeded when its first segment starts and filtered when its last one ends;
 //   - corpus fragments come from LDS two to four k-steps at a time, one group ahead of the matrix
 //     instructions that use them; the group that crosses into the next stage is read right after the
 //     workgroup barrier that says the stage has landed.
@@ -859,7 +859,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void search_long_kernel(
 
     unsigned char *ring = smem;
     int *aux = (int *)(smem + NST * STAGE_BYTES);
-    int *flags = aux + NST * AUX_INTS;           // [2][8] joint-drain requests, double buffered
+    int *flags = aux + NST * AUX_INTS;           // [8] joint-drain requests, one per wave (16 words are set aside)
     const WaveQ w = carve_waveq((unsigned char *)(flags + 16) + (size_t)wave * waveq_bytes(QW), QW);
     const int64_t q_first = (int64_t)qt * QT + wave * QW;
 
@@ -916,9 +916,9 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void search_long_kernel(
     const int a_base = col * SEGB + long_slot<CPS>(half, col) * 16;
     static_assert(SEGB % (PER * 32) == 0, "a row starts on a multiple of the swizzle group");
 
-    // Stage loader: LDS position p (16 bytes) of a stage = (row p / CPS, slot p % CPS); instruction j of
-    // a wave fills positions [(wave * IPW + j) * 64, + 64), each lane fetching the chunk that belongs
-    // in its slot.
+    // Stage loader: LDS position p (16 bytes) of a stage = (row p / CPS, slot p % CPS); copy instruction
+    // i of a stage fills positions [64 i, 64 i + 64), each lane fetching the chunk that belongs in its
+    // slot, and wave w issues instructions w, w + NW, ...
     const unsigned ring_lds = lds_offset(ring), aux_lds = lds_offset(aux);
     const int mine = (NI - wave + NW - 1) / NW;         // copy instructions of this wave
     const int lpt = mine + ((L2 && wave < 2) ? 1 : 0);  // copies this wave issues per stage

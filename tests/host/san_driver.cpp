@@ -112,11 +112,11 @@ static void planner_checks(void *lib)
     plan_info_fn plan = (plan_info_fn)dlsym(lib, "lpq_search_plan_info");
     CHECK(plan != nullptr, "lpq_search_plan_info not exported");
     if (!plan) return;
-    const int ds[] = {1, 31, 32, 64, 65, 96, 100, 128, 129, 160, 192, 224, 256, 257, 1000, 32768};
+    const int ds[] = {1, 31, 32, 64, 65, 96, 100, 128, 129, 160, 192, 224, 256, 257, 384, 500, 512, 768, 1000, 1024, 1025, 32768};
     const int bitss[] = {1, 2, 4, 8};
     const int64_t ns[] = {1, 2, 63, 64, 511, 512, 1000, 4095, 4096, 10000, 65535, 65536, 262143, 1000000, 10000000,
                           100000000, (int64_t(1) << 31) - 1025};
-    const int64_t nqs[] = {0, 1, 2, 16, 63, 64, 65, 128, 129, 255, 256, 257, 511, 512, 513, 1000, 10000, 200000, 3000000};
+    const int64_t nqs[] = {0, 1, 2, 16, 63, 64, 65, 128, 129, 255, 256, 257, 511, 512, 513, 1000, 1025, 2000, 4097, 10000, 200000, 3000000};
     const int ks[] = {1, 2, 3, 10, 11, 16, 17, 24, 25, 32, 33, 100, 128, 129, 500, 1024};
     long calls = 0;
     for (int d : ds) for (int bits : bitss) for (int packed = 0; packed < 2; ++packed) {
@@ -131,6 +131,8 @@ static void planner_checks(void *lib)
             if (rc) continue;
 #define SHAPE "(d %d bits %d packed %d n %lld nq %lld k %d)", d, bits, packed, (long long)n, (long long)nq, k
             CHECK(v[0] >= 0 && v[0] <= 3, "mode " SHAPE);
+            CHECK(v[3] == 32 || v[3] == 64 || v[3] == 128, "queries per wave " SHAPE);
+            if (v[3] == 32) CHECK(d > 512 && d <= 1024 && v[0] == 3 && !packed, "32 queries per wave: rows of 768 or 1024 bytes only " SHAPE);
             CHECK(v[4] >= nq && v[4] >= 1, "query rows cover the batch " SHAPE);
             CHECK(v[5] >= 0 && v[5] <= n, "seeding rows within the corpus " SHAPE);
             CHECK(v[7] >= 1, "at least one split " SHAPE);
