@@ -639,7 +639,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
             p.SEG = mfma_seed_segments(p.S1, k, p.rs_waves);
             p.G = mfma_seed_groups(p.S1, p.SEG, p.rs_waves);
             // systematic sample: one stage every seed_stride rows, shared out over the S1 splits
-            const int64_t stage_rows = p.rsplit ? 32 * p.rs_waves : (long_scan ? 32 : 64);
+            const int64_t stage_rows = p.rsplit ? 32 * p.rs_waves : (long_scan ? mfma_long_stage_rows(idx->d_pad, nq) : 64);
             const int64_t stages = seed / stage_rows;
             p.seed_stages = (int)ceil_div(stages, p.S1);
             p.seed_stride = n / ((int64_t)p.seed_stages * p.S1) / 128 * 128;

@@ -156,6 +156,7 @@ bool mfma_collect_wide(int64_t nq, int d_pad);           // collecting mode may 
 bool mfma_row_split(int64_t nq, int d_pad, bool packed = false);   // few queries: waves split rows, share queries
 bool mfma_long_rows(int d_pad, int64_t nq);         // rows of 384 to 1024 bytes, and large batches on 192 and 256: their own collecting scan and seeding pass
 int mfma_long_waves(int d_pad, int64_t nq);           // ... in workgroups of this many waves (4: two workgroups per CU, 8: one)
+int mfma_long_stage_rows(int d_pad, int64_t nq);   // ... whose stages hold 32 or 64 rows (the unit of the seeding pass' sample)
 int mfma_long_wave_queries(int d_pad);     // ... which keep 64 (up to 512 bytes) or 32 queries per wave
 int mfma_row_split_waves(int d_pad, bool packed);   // 4 on rows of up to 128 bytes, 2 on longer ones (collecting scan and seeding pass only)
 // With stage_stride > 0 (a multiple of 128) the pass is a systematic sample of [row0, row1): one

@@ -772,9 +772,10 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
 // (query fragments AND two row blocks' worth of corpus fragments in registers).  What changes:
 //   - a wave holds the fragments of 32 queries (rows of 768 or 1024 bytes), 64 (384 or 512 bytes) or
 //     128 (192 or 256 bytes): 128 registers at most;
-//   - a stage is ONE block of 32 rows by one segment of the row (the whole row up to 512 bytes, else
-//     a half), 6 to 16 KB, in a ring of three to six; the accumulators of a row block live across
-//     its segments, are seeded when its first segment starts and filtered when its last one ends;
+//   - a stage is one block of 32 rows (two where an eight-wave workgroup has the LDS for it) by one
+//     segment of the row (the whole row up to 512 bytes, else a half), 6 to 32 KB, in a ring of three
+//     to six; the accumulators of a row block live across its segments, are seeded when its first
+//     segment starts and filtered when its last one ends;
 //   - corpus fragments come from LDS two to four k-steps at a time, one group ahead of the matrix
 //     instructions that use them; the group that crosses into the next stage is read right after the
 //     workgroup barrier that says the stage has landed.
@@ -794,10 +795,18 @@ __device__ __forceinline__ int long_slot(int c, int r)
 
 // blocks of 32 queries per wave: as many as 128 registers of query fragments allow
 constexpr int long_nb(int kseg, int nseg) { return nseg == 2 ? 1 : (kseg >= 12 ? 2 : 4); }
-constexpr int long_nst(int kseg, int nw) { return nw == 4 ? (kseg <= 8 ? 4 : 3) : (kseg <= 12 ? 6 : 5); }
-constexpr size_t long_lds_bytes(int kseg, int nb, bool seed, int nw)
+// rows per stage: two row blocks where one workgroup has the CU's LDS to itself and the queues of
+// at most 64 queries per wave leave room (batches of more than 512 queries on rows of 384 bytes
+// and more; the seeding pass samples the same stages): twice the matrix instructions per barrier,
+// copy wait and loop turn
+constexpr int long_rs(int kseg, int nseg, int nw) { return (nw == 8 && long_nb(kseg, nseg) <= 2) ? 64 : 32; }
+constexpr int long_nst(int kseg, int nw, int rs)
 {
-    return (size_t)long_nst(kseg, nw) * 32 * kseg * 32 + (size_t)long_nst(kseg, nw) * (32 + 4) * 4 + 64 +
+    return nw == 4 ? (kseg <= 8 ? 4 : 3) : (rs == 64 ? (kseg == 12 ? 4 : 3) : (kseg <= 12 ? 6 : 5));
+}
+constexpr size_t long_lds_bytes(int kseg, int nb, bool seed, int nw, int rs)
+{
+    return (size_t)long_nst(kseg, nw, rs) * rs * kseg * 32 + (size_t)long_nst(kseg, nw, rs) * (rs + 4) * 4 + 64 +
            (seed ? 0 : nw * waveq_bytes(nb * 32));
 }
 
@@ -814,8 +823,9 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void search_long_kernel(
     constexpr int KTOT = KSEG * NSEG;          // k-steps (32 bytes) per row
     constexpr int ROWB = KTOT * 32, SEGB = KSEG * 32;
     constexpr int CPS = SEGB / 16;             // chunks per row segment
-    constexpr int RS = 32;                     // rows per stage
-    constexpr int NST = long_nst(KSEG, NW);
+    constexpr int RS = long_rs(KSEG, NSEG, NW);   // rows per stage
+    constexpr int BPS = RS / 32;               // row blocks per stage
+    constexpr int NST = long_nst(KSEG, NW, RS);
     constexpr int STAGE_BYTES = RS * SEGB;
     constexpr int NI = RS * CPS / 64;          // copy instructions per stage: wave w issues w, w + NW, ...
     constexpr int IPW = (NI + NW - 1) / NW;    // ... at most this many
@@ -935,36 +945,39 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void search_long_kernel(
         const int64_t r0_ = rs + (int64_t)(st_ / NSEG) * bstride;                                       \
         const int8_t *src_ = a.codes + r0_ * ROWB + (st_ % NSEG) * SEGB;                                \
         _Pragma("unroll") for (int j = 0; j < IPW; ++j)                                                 \
-            if (NI % NW == 0 || j < mine)                                                               \
-                async_copy16(src_ + src_off[j],                                                         \
+            if (NI % NW == 0 || j < mine) {                                                             \
+                int near_ = src_off[j];   /* one register each: the 64-bit address is formed here, not */ \
+                asm volatile("" : "+v"(near_));   /* carried through the loop (and spilled) as a pair  */ \
+                async_copy16(src_ + near_,                                                              \
                              __builtin_amdgcn_readfirstlane(ring_lds + slot_ * STAGE_BYTES + (wave + j * NW) * 1024)); \
+            }                                                                                           \
         if (L2 && wave == 0) {                                                                          \
-            if (lane < 32) async_copy4(a.cinit + r0_ + lane, aux_lds + slot_ * AUX_INTS * 4);           \
+            if (lane < RS) async_copy4(a.cinit + r0_ + lane, aux_lds + slot_ * AUX_INTS * 4);           \
         } else if (L2 && wave == 1) {                                                                   \
-            if (lane < 1) async_copy4(a.parity + r0_ / 32, aux_lds + (slot_ * AUX_INTS + RS) * 4);      \
+            if (lane < BPS) async_copy4(a.parity + r0_ / 32 + lane, aux_lds + (slot_ * AUX_INTS + RS) * 4); \
         }                                                                                               \
     } while (0)
 
-    // fragments of group G (k-steps 4G .. 4G+3 of the segment) of the stage in ring slot SLOT
-#define LPQL_LOAD_GROUP(SLOT, G, AREG)                                                                  \
+    // fragments of group G (k-steps GS G .. GS G + GS - 1 of the segment) of row block BLK of the stage in ring slot SLOT
+#define LPQL_LOAD_GROUP(SLOT, BLK, G, AREG)                                                             \
     do {                                                                                                \
-        const unsigned char *sb_ = ring + (size_t)(SLOT) * STAGE_BYTES;                                 \
+        const unsigned char *sb_ = ring + (size_t)(SLOT) * STAGE_BYTES + (BLK) * 32 * SEGB;             \
         _Pragma("unroll") for (int i = 0; i < GS; ++i) {                                                \
             const int ks_ = (G) * GS + i;                                                               \
             AREG[i] = *reinterpret_cast<const v4i *>(sb_ + (a_base ^ ((ks_ % PER) << 5)) + (ks_ / PER) * (PER * 32)); \
         }                                                                                               \
     } while (0)
-    // accumulator seeds and parity word of the row block whose (first) stage sits in ring slot SLOT
-#define LPQL_LOAD_SEEDS(SLOT, CREG, PREG)                                                               \
+    // accumulator seeds and parity word of row block BLK of the stage in ring slot SLOT
+#define LPQL_LOAD_SEEDS(SLOT, BLK, CREG, PREG)                                                          \
     do {                                                                                                \
         if (L2) {                                                                                       \
             const int *cb_ = aux + (SLOT) * AUX_INTS;                                                   \
             _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                             \
-                const v4i v_ = *reinterpret_cast<const v4i *>(cb_ + 8 * g + 4 * half);                  \
+                const v4i v_ = *reinterpret_cast<const v4i *>(cb_ + (BLK) * 32 + 8 * g + 4 * half);     \
                 CREG[4 * g + 0] = v_[0]; CREG[4 * g + 1] = v_[1];                                       \
                 CREG[4 * g + 2] = v_[2]; CREG[4 * g + 3] = v_[3];                                       \
             }                                                                                           \
-            PREG = (unsigned)cb_[RS];                                                                   \
+            PREG = (unsigned)cb_[RS + (BLK)];                                                           \
         } else {                                                                                        \
             _Pragma("unroll") for (int i = 0; i < 16; ++i) CREG[i] = 0;                                 \
             PREG = 0u;                                                                                  \
@@ -1014,8 +1027,10 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void search_long_kernel(
     const int G = S * SEG * 2;
 #define LPQL_FLUSH_SEGMENT(SEGIDX)                                                                      \
     do {                                                                                                \
+        int lane_ = lane;   /* likewise: the addresses are formed when a segment closes */              \
+        asm volatile("" : "+v"(lane_));                                                                 \
         _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) {                                             \
-            o.gmax[(size_t)(q_first + nb * 32 + col) * G + ((size_t)s * SEG + (SEGIDX)) * 2 + half] = gm[nb]; \
+            o.gmax[(size_t)(q_first + nb * 32 + (lane_ & 31)) * G + ((size_t)s * SEG + (SEGIDX)) * 2 + (lane_ >> 5)] = gm[nb]; \
             gm[nb] = INT32_MIN;                                                                         \
         }                                                                                               \
     } while (0)
@@ -1027,9 +1042,10 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void search_long_kernel(
     // here on only async copies (and appended candidates) are outstanding on the vector-memory counter.
     __builtin_amdgcn_s_waitcnt(0x0F70);
 
-    // Seeds and parity word of a row block are read one stage ahead, except with 128 queries per
-    // wave, where the 16 registers that takes are not there: the block then reads them as it starts.
-    constexpr bool SEEDS_AHEAD = NB < 4;
+    // Seeds and parity word of a row block are read along with its first fragment group, one group
+    // ahead - except where the query fragments fill all 128 registers they may have and the 16 more
+    // are not there: the block then reads its seeds as it starts.
+    constexpr bool SEEDS_AHEAD = KTOT * NB * 4 < 128;
     v4i An[GS];          // the group read ahead
     v16i Cn;             // seeds and parity word of the row block that starts next
     unsigned Pn = 0;
@@ -1039,84 +1055,92 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void search_long_kernel(
     if (T > 0) {
         wait_vmcnt((primed - 1) * lpt);
         __syncthreads();
-        LPQL_LOAD_GROUP(0, 0, An);
-        if (SEEDS_AHEAD) LPQL_LOAD_SEEDS(0, Cn, Pn);
+        LPQL_LOAD_GROUP(0, 0, 0, An);
+        if (SEEDS_AHEAD) LPQL_LOAD_SEEDS(0, 0, Cn, Pn);
     }
     int t = 0;
-    for (int rb = 0; rb < RB; ++rb) {
-        v16i acc[NB];
+    for (int rb = 0; rb < RB; ++rb) {   // rb: a group of RS rows = BPS row blocks; its NSEG stages follow each other
+        v16i acc[BPS][NB];
         v16i Cc;
-        unsigned Pc = 0;
+        unsigned Pc[BPS];
 #pragma unroll
         for (int seg = 0; seg < NSEG; ++seg, ++t) {
 #pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                v4i Ac[GS];
+            for (int blk = 0; blk < BPS; ++blk) {
 #pragma unroll
-                for (int i = 0; i < GS; ++i) Ac[i] = An[i];
-                if (seg == 0 && g == 0) {
-                    if (SEEDS_AHEAD) { Cc = Cn; Pc = Pn; }
-                    else LPQL_LOAD_SEEDS(slot, Cc, Pc);   // the stage's slot is refilled only after its last group
-                }
-                if (g + 1 < NG) {
-                    LPQL_LOAD_GROUP(slot, g + 1, An);
-                } else {
-                    // the last group of stage t is in registers once the LDS counter is down: this wave
-                    // is done reading the stage
-                    // (the matrix instructions of the group before are issued first: they run meanwhile)
-                    __builtin_amdgcn_sched_barrier(0);
-                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                    // every fourth stage the waves tell each other whether a queue is half full, and
-                    // if one is, all drain together (a wave whose queue overflows in between drains alone)
-                    const bool xchg = !SEED && (t & 3) == 3;
-                    if (xchg && lane == 0) flags[wave] = qcnt >= TRIG;
-                    if (t + NST - 1 < T) {
-                        // stages 0 .. t+NST-1 have been issued and stage t+1 must have landed: all but
-                        // the copies of the NST-2 newest stages (a constant count per wave, without the
-                        // run-time dispatch of wait_vmcnt)
-                        if (lpt == IPW) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 2) * IPW));
-                        else if (lpt == IPW + 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 2) * (IPW + 1)));
-                        else wait_vmcnt((NST - 2) * lpt);
-                    } else if (t + 1 < T) {   // the tail: stages up to T-1 have been issued
-                        wait_vmcnt((T - 1 - (t + 1)) * lpt);
+                for (int g = 0; g < NG; ++g) {
+                    v4i Ac[GS];
+#pragma unroll
+                    for (int i = 0; i < GS; ++i) Ac[i] = An[i];
+                    if (seg == 0 && g == 0) {
+                        if (SEEDS_AHEAD) { Cc = Cn; Pc[blk] = Pn; }
+                        else LPQL_LOAD_SEEDS(slot, blk, Cc, Pc[blk]);   // the stage's slot is refilled only after its last group
                     }
-                    __syncthreads();
-                    if (t + NST < T) LPQL_ISSUE(t + NST, slot);   // refills the slot of stage t
-                    if (xchg) {   // (the next exchange is four barriers away: no wave can overwrite a flag early)
-                        const v4i fl0 = *reinterpret_cast<const v4i *>(flags);
-                        int any = fl0[0] | fl0[1] | fl0[2] | fl0[3];
-                        if (NW > 4) {
-                            const v4i fl1 = *reinterpret_cast<const v4i *>(flags + 4);
-                            any |= fl1[0] | fl1[1] | fl1[2] | fl1[3];
+                    if (g + 1 < NG) {
+                        LPQL_LOAD_GROUP(slot, blk, g + 1, An);
+                    } else if (blk + 1 < BPS) {   // on to the next row block of the same stage
+                        LPQL_LOAD_GROUP(slot, blk + 1, 0, An);
+                        if (SEEDS_AHEAD && seg == 0) LPQL_LOAD_SEEDS(slot, blk + 1, Cn, Pn);
+                    } else {
+                        // the last group of stage t is in registers once the LDS counter is down: this wave
+                        // is done reading the stage
+                        // (the matrix instructions of the group before are issued first: they run meanwhile)
+                        __builtin_amdgcn_sched_barrier(0);
+                        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                        // every fourth stage the waves tell each other whether a queue is half full, and
+                        // if one is, all drain together (a wave whose queue overflows in between drains alone)
+                        const bool xchg = !SEED && (t & 3) == 3;
+                        if (xchg && lane == 0) flags[wave] = qcnt >= TRIG;
+                        if (t + NST - 1 < T) {
+                            // stages 0 .. t+NST-1 have been issued and stage t+1 must have landed: all but
+                            // the copies of the NST-2 newest stages (a constant count per wave, without the
+                            // run-time dispatch of wait_vmcnt)
+                            if (lpt == IPW) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 2) * IPW));
+                            else if (lpt == IPW + 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 2) * (IPW + 1)));
+                            else wait_vmcnt((NST - 2) * lpt);
+                        } else if (t + 1 < T) {   // the tail: stages up to T-1 have been issued
+                            wait_vmcnt((T - 1 - (t + 1)) * lpt);
                         }
-                        if (any) {
-                            drain_queue<L2, 0, 1>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
-                            qcnt = 0;
+                        __syncthreads();
+                        if (t + NST < T) LPQL_ISSUE(t + NST, slot);   // refills the slot of stage t
+                        if (xchg) {   // (the next exchange is four barriers away: no wave can overwrite a flag early)
+                            const v4i fl0 = *reinterpret_cast<const v4i *>(flags);
+                            int any = fl0[0] | fl0[1] | fl0[2] | fl0[3];
+                            if (NW > 4) {
+                                const v4i fl1 = *reinterpret_cast<const v4i *>(flags + 4);
+                                any |= fl1[0] | fl1[1] | fl1[2] | fl1[3];
+                            }
+                            if (any) {
+                                drain_queue<L2, 0, 1>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs);
+                                qcnt = 0;
+                            }
                         }
+                        const int nslot = slot + 1 == NST ? 0 : slot + 1;
+                        if (t + 1 < T) {
+                            LPQL_LOAD_GROUP(nslot, 0, 0, An);
+                            if (SEEDS_AHEAD && seg + 1 == NSEG) LPQL_LOAD_SEEDS(nslot, 0, Cn, Pn);
+                        }
+                        slot = nslot;
                     }
-                    const int nslot = slot + 1 == NST ? 0 : slot + 1;
-                    if (t + 1 < T) {
-                        LPQL_LOAD_GROUP(nslot, 0, An);
-                        if (SEEDS_AHEAD && seg + 1 == NSEG) LPQL_LOAD_SEEDS(nslot, Cn, Pn);
+#pragma unroll
+                    for (int i = 0; i < GS; ++i)
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            acc[blk][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                                Ac[i], B[nb][seg * KSEG + g * GS + i], (seg == 0 && g == 0 && i == 0) ? Cc : acc[blk][nb], 0, 0, 0);
+                    // Keep the reads of the next group in front of this group's matrix instructions: left
+                    // alone, the compiler moves each read down to the instruction that needs it and every
+                    // matrix instruction then waits out a full LDS round trip.
+                    __builtin_amdgcn_sched_group_barrier(0x100, GS, 0);        // the group's LDS reads
+                    __builtin_amdgcn_sched_group_barrier(0x008, GS * NB, 0);   // GS * NB matrix instructions
+                    if (seg == NSEG - 1 && g == NG - 1) {   // the row block is complete
+                        const int rowbase = (int)(rs + (int64_t)rb * bstride) + blk * 32;
+#pragma unroll
+                        for (int nbi = 0; nbi < NB; ++nbi) LPQL_EPI(acc[blk][nbi], nbi, rowbase, Pc[blk]);
                     }
-                    slot = nslot;
                 }
-#pragma unroll
-                for (int i = 0; i < GS; ++i)
-#pragma unroll
-                    for (int nb = 0; nb < NB; ++nb)
-                        acc[nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Ac[i], B[nb][seg * KSEG + g * GS + i],
-                                                                        (seg == 0 && g == 0 && i == 0) ? Cc : acc[nb], 0, 0, 0);
-                // Keep the reads of the next group in front of this group's matrix instructions: left
-                // alone, the compiler moves each read down to the instruction that needs it and every
-                // matrix instruction then waits out a full LDS round trip.
-                __builtin_amdgcn_sched_group_barrier(0x100, GS, 0);        // the group's LDS reads
-                __builtin_amdgcn_sched_group_barrier(0x008, GS * NB, 0);   // GS * NB matrix instructions
             }
         }
-        const int rowbase = (int)(rs + (int64_t)rb * bstride);
-#pragma unroll
-        for (int nbi = 0; nbi < NB; ++nbi) LPQL_EPI(acc[nbi], nbi, rowbase, Pc);
         if (SEED) {   // close a segment when the next row block belongs to the next one
             const int sg = (int)((int64_t)rb * SEG / RB), sg_next = (int)((int64_t)(rb + 1) * SEG / RB);
             if (rb + 1 == RB || sg_next != sg) {
@@ -1316,7 +1340,8 @@ hipError_t launch_long_nw(const SearchArgs &a, int64_t row0, int64_t row1, int S
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    kern<<<(unsigned)(qtiles * S), NW * 64, long_lds_bytes(KSEG, NB, SEED, NW), st>>>(a, row0, row1, S, split_rows, qtiles, o);
+    kern<<<(unsigned)(qtiles * S), NW * 64, long_lds_bytes(KSEG, NB, SEED, NW, long_rs(KSEG, NSEG, NW)), st>>>(
+        a, row0, row1, S, split_rows, qtiles, o);
     return hipGetLastError();
 }
 
@@ -1396,6 +1421,8 @@ bool mfma_long_rows(int d_pad, int64_t nq)
 
 int mfma_long_wave_queries(int d_pad) { return d_pad <= 256 ? 128 : (d_pad <= 512 ? 64 : 32); }
 
+int mfma_long_stage_rows(int d_pad, int64_t nq) { return (mfma_long_waves(d_pad, nq) == 8 && d_pad > 256) ? 64 : 32; }
+
 // Eight waves per workgroup (one workgroup per CU, a ring of five or six stages) for large batches:
 // half the corpus bytes per contraction go through the L2, measured 4 to 14 % faster at 10 000
 // queries; four waves (two workgroups per CU) finish small batches sooner (16 queries on
@@ -1467,7 +1494,7 @@ hipError_t launch_seed_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int
         o.piece_stride = piece_stride;
         o.piece_stages = piece_stages;
     } else if (stage_stride) {
-        const int rs_rows = a.rsplit ? 32 * a.rs_waves : (takes_long_scan(a) ? 32 : 64);
+        const int rs_rows = a.rsplit ? 32 * a.rs_waves : (takes_long_scan(a) ? mfma_long_stage_rows(a.d_pad, a.nq) : 64);
         if (stages_per_split < 1 || stage_stride < rs_rows || stage_stride % 128) return hipErrorInvalidValue;
         o.stage_stride = stage_stride;
         o.split_stride = stage_stride * stages_per_split;
