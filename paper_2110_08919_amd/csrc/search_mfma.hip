@@ -795,14 +795,15 @@ __device__ __forceinline__ int long_slot(int c, int r)
 
 // blocks of 32 queries per wave: as many as 128 registers of query fragments allow
 constexpr int long_nb(int kseg, int nseg) { return nseg == 2 ? 1 : (kseg >= 12 ? 2 : 4); }
-// rows per stage: two row blocks where one workgroup has the CU's LDS to itself and the queues of
-// at most 64 queries per wave leave room (batches of more than 512 queries on rows of 384 bytes
-// and more; the seeding pass samples the same stages): twice the matrix instructions per barrier,
-// copy wait and loop turn
-constexpr int long_rs(int kseg, int nseg, int nw) { return (nw == 8 && long_nb(kseg, nseg) <= 2) ? 64 : 32; }
+// rows per stage: two row blocks where one workgroup has the CU's LDS to itself (eight waves; the
+// seeding pass samples the same stages): twice the matrix instructions per barrier, copy wait and
+// loop turn
+// (not the seeding pass of rows up to 256 bytes: with 128 queries per wave and no branch between
+// its row blocks the compiler schedules both as one region and spills 24 to 45 registers)
+constexpr int long_rs(int kseg, bool seed, int nw) { return (nw == 8 && !(seed && kseg <= 8)) ? 64 : 32; }
 constexpr int long_nst(int kseg, int nw, int rs)
 {
-    return nw == 4 ? (kseg <= 8 ? 4 : 3) : (rs == 64 ? (kseg == 12 ? 4 : 3) : (kseg <= 12 ? 6 : 5));
+    return nw == 4 ? (kseg <= 8 ? 4 : 3) : (rs == 64 ? (kseg == 6 ? 5 : (kseg == 16 ? 3 : 4)) : (kseg <= 12 ? 6 : 5));
 }
 constexpr size_t long_lds_bytes(int kseg, int nb, bool seed, int nw, int rs)
 {
@@ -823,7 +824,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void search_long_kernel(
     constexpr int KTOT = KSEG * NSEG;          // k-steps (32 bytes) per row
     constexpr int ROWB = KTOT * 32, SEGB = KSEG * 32;
     constexpr int CPS = SEGB / 16;             // chunks per row segment
-    constexpr int RS = long_rs(KSEG, NSEG, NW);   // rows per stage
+    constexpr int RS = long_rs(KSEG, SEED, NW);   // rows per stage
     constexpr int BPS = RS / 32;               // row blocks per stage
     constexpr int NST = long_nst(KSEG, NW, RS);
     constexpr int STAGE_BYTES = RS * SEGB;
@@ -1340,7 +1341,7 @@ hipError_t launch_long_nw(const SearchArgs &a, int64_t row0, int64_t row1, int S
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    kern<<<(unsigned)(qtiles * S), NW * 64, long_lds_bytes(KSEG, NB, SEED, NW, long_rs(KSEG, NSEG, NW)), st>>>(
+    kern<<<(unsigned)(qtiles * S), NW * 64, long_lds_bytes(KSEG, NB, SEED, NW, long_rs(KSEG, SEED, NW)), st>>>(
         a, row0, row1, S, split_rows, qtiles, o);
     return hipGetLastError();
 }
