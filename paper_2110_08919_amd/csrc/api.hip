@@ -627,6 +627,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
         if (long_scan) {   // the scan for long rows and its seeding pass have their own tiles
             p.wave_queries = mfma_long_wave_queries(idx->d_pad);
             qt = (int64_t)mfma_long_waves(idx->d_pad, nq) * p.wave_queries;
+            if (qt > 512) p.nq_pad = round_up(nq > 0 ? nq : 1, qt);   // query rows (codes, group maxima) cover whole tiles
             if (mfma_long_waves(idx->d_pad, nq) == 8) slots_now = 256;   // one workgroup per CU
         }
     }

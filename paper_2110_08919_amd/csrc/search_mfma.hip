@@ -1131,7 +1131,14 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void search_long_kernel(
                                 Ac[i], B[nb][seg * KSEG + g * GS + i], (seg == 0 && g == 0 && i == 0) ? Cc : acc[blk][nb], 0, 0, 0);
                     // Keep the reads of the next group in front of this group's matrix instructions: left
                     // alone, the compiler moves each read down to the instruction that needs it and every
-                    // matrix instruction then waits out a full LDS round trip.
+                    // matrix instruction then waits out a full LDS round trip.  The same two groups keep
+                    // ALL matrix instructions of the block in front of its first filter epilogue.  That
+                    // matters: with the completing group issued query block by query block and each
+                    // epilogue one chain later (as in the kernel above) the scheduler put the last
+                    // matrix instruction of a chain four instructions before the branch that ends the
+                    // epilogue before it, the next epilogue read that chain's first accumulators five
+                    // issue slots after it with no wait inserted, and candidates in those rows went
+                    // missing now and then (two runs of one binary disagreed).
                     __builtin_amdgcn_sched_group_barrier(0x100, GS, 0);        // the group's LDS reads
                     __builtin_amdgcn_sched_group_barrier(0x008, GS * NB, 0);   // GS * NB matrix instructions
                     if (seg == NSEG - 1 && g == NG - 1) {   // the row block is complete

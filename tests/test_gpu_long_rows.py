@@ -60,6 +60,7 @@ def test_search_long_rows(lpq, oracle, recipe, d, n, nq, k, metric, mode, scope)
     ("skewed_int", 256, 80_003, 1900, 10, "l2sq", "minmax", "global"),
     ("scaled_unit", 180, 66_000, 2048, 16, "l2sq", "absmax", "global"),   # padded to 192
     ("bimodal", 192, 90_000, 3000, 40, "ip", "absmax", "global"),
+    ("bimodal", 256, 66_000, 5200, 10, "l2sq", "minmax", "global"),       # six tiles of 1024: query rows padded beyond a multiple of 512
 ])
 def test_search_large_batches_on_rows_of_192_and_256_bytes(lpq, oracle, recipe, d, n, nq, k, metric, mode, scope):
     """Large batches on rows of 192 and 256 bytes take the same scan with 128 queries per wave."""
