@@ -40,13 +40,33 @@ def _newest_header() -> float:
     return max(os.path.getmtime(h) for h in hs)
 
 
+def device_asm(src: str) -> str:
+    """Where the compile of a matrix-core kernel file leaves its gfx950 assembly (a by-product kept
+    for tests/test_kernel_schedule.py, which checks the instruction order the compiler chose)."""
+    return os.path.join(OBJ, os.path.basename(src)[:-4] + "-hip-amdgcn-amd-amdhsa-gfx950.s")
+
+
+def keeps_asm(src: str) -> bool:
+    return os.path.basename(src).startswith("search_mfma")
+
+
 def _compile(src: str, force: bool, ablation: bool) -> str:
     obj = os.path.join(OBJ, os.path.basename(src)[:-4] + (".abl.o" if ablation else ".o"))
+    want_asm = keeps_asm(src) and not ablation
     stale = (force or not os.path.exists(obj)
-             or os.path.getmtime(obj) < max(os.path.getmtime(src), _newest_header()))
+             or os.path.getmtime(obj) < max(os.path.getmtime(src), _newest_header())
+             or (want_asm and not os.path.exists(device_asm(src))))
     if stale:
         extra = ["-DLPQ_ABLATION"] if ablation else []
+        if want_asm:
+            extra.append("-save-temps=obj")
         subprocess.run([HIPCC, *FLAGS, *extra, "-c", src, "-o", obj], check=True)
+        if want_asm:   # of the intermediate files only the device assembly is kept
+            stem = os.path.join(OBJ, os.path.basename(src)[:-4])
+            for f in os.listdir(OBJ):
+                full = os.path.join(OBJ, f)
+                if full.startswith(stem + "-h") and full != device_asm(src) or full == stem + ".hip-hip-amdgcn-amd-amdhsa.hipfb":
+                    os.remove(full)
     return obj
 
 

@@ -1142,6 +1142,8 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void search_long_kernel(
                     __builtin_amdgcn_sched_group_barrier(0x100, GS, 0);        // the group's LDS reads
                     __builtin_amdgcn_sched_group_barrier(0x008, GS * NB, 0);   // GS * NB matrix instructions
                     if (seg == NSEG - 1 && g == NG - 1) {   // the row block is complete
+                        // nothing of the contraction may drift down among the epilogues (see above)
+                        __builtin_amdgcn_sched_barrier(0);
                         const int rowbase = (int)(rs + (int64_t)rb * bstride) + blk * 32;
 #pragma unroll
                         for (int nbi = 0; nbi < NB; ++nbi) LPQL_EPI(acc[blk][nbi], nbi, rowbase, Pc[blk]);
