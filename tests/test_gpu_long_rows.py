@@ -99,3 +99,30 @@ def test_search_long_rows_small_corpus_and_large_k_take_the_generic_kernel(lpq, 
     """Below the smallest sample, and for k beyond 128, long rows are searched by the generic kernel."""
     _case(lpq, oracle, _workload("bimodal", 768, 3000, 9, "l2sq"), 10, "l2sq", "minmax", "global", expect_collecting=False)
     _case(lpq, oracle, _workload("bimodal", 600, 40_000, 3, "ip"), 200, "ip", "absmax", "global", expect_collecting=False)
+
+
+def _random_case(seed):
+    """A random shape that the long-row scan takes: rows of 192 bytes and more, corpora large enough
+    for a seeding sample, batches on both sides of the workgroup sizes and of the 1024-query tiles."""
+    r = np.random.default_rng(7000 + seed)
+    d = int(r.choice([180, 192, 256, 257, 300, 384, 400, 512, 513, 700, 768, 900, 1000, 1024]))
+    nq = int(r.choice([1, 33, 64, 300, 512, 513, 700, 1100, 2100, 3000]))
+    n = int(r.choice([33_000, 40_001, 66_000, 70_003, 100_000]))
+    if d * nq * n > 8e10:                       # keep the oracle to a few seconds
+        nq = max(1, int(8e10 / (d * n)))
+    k = int(r.choice([1, 10, 16, 17, 40, 100, 128]))
+    metric = str(r.choice(["l2sq", "ip"]))
+    recipe = str(r.choice(["bimodal", "skewed_int", "scaled_unit"]))
+    mode, scope = [("minmax", "per_feature"), ("minmax", "global"), ("absmax", "global")][int(r.integers(3))]
+    return recipe, d, n, nq, k, metric, mode, scope
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_random_long_row_configuration_bit_exact(lpq, oracle, seed):
+    recipe, d, n, nq, k, metric, mode, scope = _random_case(seed)
+    print(dict(recipe=recipe, d=d, n=n, nq=nq, k=k, metric=metric, mode=mode, scope=scope), flush=True)
+    w = synth.Workload(f"{recipe}_x{d}", recipe, n, d, nq, metric, (10,), "minmax", "global", 100 + seed)
+    index, ws = _case(lpq, oracle, w, k, metric, mode, scope, expect_collecting=False)
+    ids2, dists2 = index.search(w.queries("cuda"), k, metric, workspace=ws)      # the same call again: the same answer
+    ids1, dists1 = index.search(w.queries("cuda"), k, metric)
+    assert torch.equal(ids1, ids2) and torch.equal(dists1, dists2)
