@@ -574,7 +574,9 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
         const int64_t lo = gm ? lo_gm : 4096, hi = p.mode == PLAN_MFMA_COLLECT ? n : (gm ? (few ? 65536 : 131072) : 32768);
         seed = seed < lo ? lo : (seed > hi ? hi : seed);
         if (p.mode == PLAN_MFMA_COLLECT && few) {   // no tightening during the scan: the sample grows with k
-            const int64_t by_k = n / 400 * k, least = n / 16, most = n / 8;
+            // (beyond k = 256 a quarter: an eighth would let about 9 k candidates through, more than the
+            // 4096 the selection sorts)
+            const int64_t by_k = n / 400 * k, least = n / 16, most = k > 256 ? n / 4 : n / 8;
             seed = by_k < least ? least : (by_k > most ? most : by_k);
         } else if (p.mode == PLAN_MFMA_COLLECT) {
             // The sample costs time in proportion to its rows, the candidates it lets through in
