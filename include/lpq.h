@@ -229,7 +229,7 @@ int lpq_rerank_f32(const float *x_dev, int64_t n, int64_t ldx, const float *q_de
 /* Process-wide tuning knobs for measurements; 0 restores the built-in choice.
  *   LPQ_TUNE_PATH        1 = generic dot-product kernel, 2 = matrix-core kernels (built-in
  *                        choice of variant), 3 = the collecting matrix-core variant for every
- *                        k it takes (k <= 512), 4 = matrix-core kernels without the
+ *                        k it takes, 4 = matrix-core kernels without the
  *                        collecting variant
  *   LPQ_TUNE_SPLITS      number of corpus splits per query tile in the main pass
  *   LPQ_TUNE_SEED_ROWS   rows of the threshold-seeding pass (0 = built-in choice,
@@ -325,7 +325,7 @@ int lpq_probe_stream(const void *src_dev, size_t bytes, int mode, int reps, doub
 int lpq_search_overflow_stats(const lpq_index *idx, int64_t nq, int k, int metric, const void *workspace_dev,
                               int64_t *redone_queries, int64_t *max_region_fill);
 
-/* For 16 < k <= 512 more than 16 such queries are not searched again exactly at once: the scan
+/* For k > 16 more than 16 such queries are not searched again exactly at once: the scan
  * runs again (up to two more rounds) over the query tiles that hold one, with bounds taken from
  * the candidates the round before did collect, and only queries that overflow every time go
  * through the generic kernel.  *left_queries = their number after the last search (0 when the

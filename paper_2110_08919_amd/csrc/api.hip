@@ -576,7 +576,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
         if (p.mode == PLAN_MFMA_COLLECT && few) {   // no tightening during the scan: the sample grows with k
             // (beyond k = 256 a quarter: an eighth would let about 9 k candidates through, more than the
             // 4096 the selection sorts)
-            const int64_t by_k = n / 400 * k, least = n / 16, most = k > 256 ? n / 4 : n / 8;
+            const int64_t by_k = n / 400 * k, least = n / 16, most = k > 512 ? n / 2 : (k > 256 ? n / 4 : n / 8);
             seed = by_k < least ? least : (by_k > most ? most : by_k);
         } else if (p.mode == PLAN_MFMA_COLLECT) {
             // The sample costs time in proportion to its rows, the candidates it lets through in
@@ -586,11 +586,13 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
             const double by_cost = 125000.0 * std::sqrt((double)n / 1e6 * (double)k / 10.0);
             const double by_room = (double)k * (double)n / 1500.0;
             const double want_rows = by_cost > by_room ? by_cost : by_room;
-            seed = want_rows > (double)(n / 4) ? n / 4 : (int64_t)want_rows;
+            // (k beyond 512: half the corpus, or the ~4.6 k candidates a quarter lets through would not fit)
+            const int64_t most = k > 512 ? n / 2 : n / 4;
+            seed = want_rows > (double)most ? most : (int64_t)want_rows;
         }
     }
     seed = seed / 256 * 256;
-    if (seed < 64 * k || seed * 4 > n) seed = 0;
+    if (seed < 64 * k || seed * (k > 512 ? 2 : 4) > n) seed = 0;
     if (p.mode == PLAN_MFMA_COLLECT && !seed) {   // too few items to sample: exact paths
         // (longer lists without a sample: the generic kernel; the LDS-list matrix-core kernel measured
         // 10 to 70x slower on the corpora this happens for - 1000 x 128, k = 100, 1000 queries: 4.3 ms

@@ -167,7 +167,7 @@ int mfma_row_split_waves(int d_pad, bool packed);   // 4 on rows of up to 128 by
 hipError_t launch_seed_mfma(const SearchArgs &a, int64_t row0, int64_t row1, int S, int SEG, int32_t *gmax,
                             hipStream_t st, int64_t stage_stride = 0, int stages_per_split = 0,
                             int64_t piece_stride = 0, int piece_stages = 0);
-// Collecting scan (k <= 512): thresholds stay at seeds[q] (required); every candidate beating its
+// Collecting scan (any k up to MAX_K): thresholds stay at seeds[q] (required); every candidate beating its
 // query's seed is appended to cbuf[(q * SS + region) * Cs + ...], SS = mfma_collect_regions(S, rsplit),
 // and ccnt[q * SS + region] = number offered (entries beyond Cs were dropped).
 bool mfma_collect_supported(int d_pad, int k);

@@ -1449,9 +1449,9 @@ int mfma_row_split_waves(int d_pad, bool packed) { return (packed ? d_pad / 2 : 
 
 bool mfma_reg_supported(int d_pad, int k) { return shape_ok(d_pad) && k >= 1 && k <= 16; }
 
-// (k up to 512: about 4.6 k candidates per query survive a sample of a quarter of the corpus, and
-// the selection sorts up to 4096)
-bool mfma_collect_supported(int d_pad, int k) { return (shape_ok(d_pad) || long_shape_ok(d_pad)) && k >= 1 && k <= 512; }
+// (any k the interface takes: about 4.6 k candidates per query survive a sample of a quarter of
+// the corpus, 2.8 k a sample of half of it - taken beyond k = 512 - and the selection sorts up to 4096)
+bool mfma_collect_supported(int d_pad, int k) { return (shape_ok(d_pad) || long_shape_ok(d_pad)) && k >= 1 && k <= 1024; }
 
 bool mfma_supported(int d_pad, int k) { return mfma_reg_supported(d_pad, k) || mfma_lds_supported(d_pad, k); }
 

@@ -208,14 +208,16 @@ def test_search_collecting_variant(lpq, oracle, path, name, n, nq, k, metric, mo
     ("aniso", 160_000, 700, 300, "ip", "absmax", "global"),            # d = 100
     ("scaled", 140_000, 257, 512, "l2sq", "absmax", "global"),         # d = 96, largest k of the variant
     ("product", 135_000, 1100, 200, "ip", "absmax", "per_feature"),    # d = 256
+    ("skewed", 300_000, 300, 1024, "l2sq", "minmax", "global"),        # the largest k: half the corpus is sampled; many queries overflow and are redone
+    ("aniso", 200_000, 40, 1024, "ip", "absmax", "global"),
+    ("product", 150_000, 600, 700, "ip", "absmax", "per_feature"),
 ])
 def test_search_collecting_variant_long_lists(lpq, oracle, name, n, nq, k, metric, mode, scope):
-    """k from 129 to 512 goes through the collecting scan too (a workgroup per query selects from up to
-    4096 collected candidates); beyond 512 the generic kernel."""
+    """k from 129 to 1024 goes through the collecting scan too (a workgroup per query selects from up
+    to 4096 collected candidates; beyond k = 512 the seeding pass samples half the corpus)."""
     base = {"skewed": synth.SKEWED_1M, "aniso": synth.ANISO_1M2, "scaled": synth.SCALED_10M,
             "product": synth.PRODUCT_100M}[name]
     assert lpq.search_plan_info(base.d, 8, 0, n, nq, k)[0] == 3, "the collecting scan was expected to take this k"
-    assert lpq.search_plan_info(base.d, 8, 0, n, nq, 513)[0] != 3
     _run_search_case(lpq, oracle, base.scaled(n=n, nq=nq), k, metric, mode, scope, 0)
 
 
