@@ -111,8 +111,8 @@ int lpq_encode(const lpq_quantizer *q, const float *x_dev, int64_t n, int64_t ld
 
 /* Flat index for up to `capacity` items (1 <= capacity < 2^31).  The index takes a copy
  * of the quantizer's constants (later changes to q do not affect it) and allocates, with
- * hipMalloc, the int8 codes (rows zero padded to 64, 96, 128, 192, 256, 384, 512, 768 or 1024
- * bytes, beyond 1024 features to a multiple of 32 bytes) and the integer norms.
+ * hipMalloc, the int8 codes (rows zero padded to 64, 96, 128, 192, 256, 384, 512, 768, 1024 or
+ * 1536 bytes, beyond 1536 features to a multiple of 32 bytes) and the integer norms.
  * d <= 32 768 keeps every integer distance inside int32. */
 int lpq_index_create(lpq_index **out, const lpq_quantizer *q, int64_t capacity);
 

@@ -319,9 +319,9 @@ extern "C" void lpq_index_destroy(lpq_index *idx)
 // Row length an index stores d features in: a length the matrix-core scans have where one exists.
 static int padded_row_length(int d)
 {
-    // up to 1024 features: the row lengths the matrix-core kernels take; beyond: the generic kernel's
+    // up to 1536 features: the row lengths the matrix-core kernels take; beyond: the generic kernel's
     return d <= 64 ? 64 : d <= 96 ? 96 : d <= 128 ? 128 : d <= 192 ? 192 : d <= 256 ? 256
-           : d <= 384 ? 384 : d <= 512 ? 512 : d <= 768 ? 768 : d <= 1024 ? 1024 : (int)round_up(d, 32);
+           : d <= 384 ? 384 : d <= 512 ? 512 : d <= 768 ? 768 : d <= 1024 ? 1024 : d <= 1536 ? 1536 : (int)round_up(d, 32);
 }
 
 static int index_create_impl(lpq_index **out, const lpq_quantizer *q, int64_t capacity, bool packed)

@@ -794,7 +794,7 @@ __device__ __forceinline__ int long_slot(int c, int r)
 }
 
 // blocks of 32 queries per wave: as many as 128 registers of query fragments allow
-constexpr int long_nb(int kseg, int nseg) { return nseg == 2 ? 1 : (kseg >= 12 ? 2 : 4); }
+constexpr int long_nb(int kseg, int nseg) { return nseg >= 2 ? 1 : (kseg >= 12 ? 2 : 4); }
 // rows per stage: two row blocks where one workgroup has the CU's LDS to itself (eight waves; the
 // seeding pass samples the same stages): twice the matrix instructions per barrier, copy wait and
 // loop turn
@@ -816,8 +816,8 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void search_long_kernel(
     SearchArgs a, int64_t row0, int64_t row1, int S, int64_t split_rows, int qtiles, MfmaIo o)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    static_assert(((KSEG == 12 || KSEG == 16) && (NSEG == 1 || NSEG == 2)) || ((KSEG == 6 || KSEG == 8) && NSEG == 1),
-                  "rows of 192, 256, 384, 512, 768 or 1024 bytes");
+    static_assert(((KSEG == 12 || KSEG == 16) && (NSEG == 1 || NSEG == 2)) || ((KSEG == 6 || KSEG == 8) && NSEG == 1) ||
+                  (KSEG == 16 && NSEG == 3), "rows of 192, 256, 384, 512, 768, 1024 or 1536 bytes");
     static_assert(NW == 4 || NW == 8, "four waves (two workgroups per CU) or eight (one)");
     constexpr int NB = long_nb(KSEG, NSEG);    // blocks of 32 queries per wave
     constexpr int QW = NB * 32, QT = NW * QW;
@@ -831,7 +831,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void search_long_kernel(
     constexpr int NI = RS * CPS / 64;          // copy instructions per stage: wave w issues w, w + NW, ...
     constexpr int IPW = (NI + NW - 1) / NW;    // ... at most this many
     constexpr int AUX_INTS = RS + 4;           // accumulator seeds of the 32 rows, then their parity word
-    constexpr int GS = KSEG == 6 ? 3 : (KSEG == 8 ? 2 : 4);   // k-steps per group of fragments (each feeds NB matrix instructions)
+    constexpr int GS = KSEG == 6 ? 3 : ((KSEG == 8 || NSEG == 3) ? 2 : 4);   // k-steps per group of fragments (each feeds NB matrix instructions)
     constexpr int NG = KSEG / GS;              // groups per segment
     constexpr int PER = CPS % 16 == 0 ? 8 : (CPS % 8 == 0 ? 4 : 2);   // k-steps after which a lane's swizzle pattern repeats
     static_assert((NST - 1) * (IPW + 1) <= 63, "wait_vmcnt covers 0..63");
@@ -1358,8 +1358,10 @@ hipError_t launch_long_nw(const SearchArgs &a, int64_t row0, int64_t row1, int S
 template <int KSEG, int NSEG, bool L2, bool SEED>
 hipError_t launch_long_one(const SearchArgs &a, int64_t row0, int64_t row1, int S, const MfmaIo &o, hipStream_t st)
 {
-    return mfma_long_waves(a.d_pad, a.nq) == 8 ? launch_long_nw<KSEG, NSEG, L2, SEED, 8>(a, row0, row1, S, o, st)
-                                         : launch_long_nw<KSEG, NSEG, L2, SEED, 4>(a, row0, row1, S, o, st);
+    if constexpr (NSEG < 3) {
+        if (mfma_long_waves(a.d_pad, a.nq) == 8) return launch_long_nw<KSEG, NSEG, L2, SEED, 8>(a, row0, row1, S, o, st);
+    }
+    return launch_long_nw<KSEG, NSEG, L2, SEED, 4>(a, row0, row1, S, o, st);
 }
 
 template <int KSEG, int NSEG>
@@ -1387,6 +1389,7 @@ hipError_t launch_any(const SearchArgs &a, int64_t row0, int64_t row1, int S, co
         case 16: return launch_long<16, 1>(a, row0, row1, S, o, st);
         case 24: return launch_long<12, 2>(a, row0, row1, S, o, st);
         case 32: return launch_long<16, 2>(a, row0, row1, S, o, st);
+        case 48: return launch_long<16, 3>(a, row0, row1, S, o, st);
         default: break;
         }
     }
@@ -1406,7 +1409,7 @@ bool shape_ok(int d_pad)
     return d_pad % 32 == 0 && (ks == 2 || ks == 3 || ks == 4 || ks == 6 || ks == 8);
 }
 
-bool long_shape_ok(int d_pad) { return d_pad == 384 || d_pad == 512 || d_pad == 768 || d_pad == 1024; }
+bool long_shape_ok(int d_pad) { return d_pad == 384 || d_pad == 512 || d_pad == 768 || d_pad == 1024 || d_pad == 1536; }
 
 }  // namespace
 
@@ -1437,7 +1440,9 @@ int mfma_long_stage_rows(int d_pad, int64_t nq) { return (mfma_long_waves(d_pad,
 // half the corpus bytes per contraction go through the L2, measured 4 to 14 % faster at 10 000
 // queries; four waves (two workgroups per CU) finish small batches sooner (16 queries on
 // 500K x 1024: 0.18 against 0.22 ms).
-int mfma_long_waves(int d_pad, int64_t nq) { return (d_pad <= 256 || nq > 512) ? 8 : 4; }
+// (rows of 1536 bytes: four waves always - 192 registers of query fragments leave no room for the
+// second row block's accumulators)
+int mfma_long_waves(int d_pad, int64_t nq) { return (d_pad <= 256 || (nq > 512 && d_pad <= 1024)) ? 8 : 4; }
 
 // Collecting mode: 128 queries per wave when the rows are short enough for the registers to hold them.
 bool mfma_collect_wide(int64_t nq, int d_pad) { return !mfma_row_split(nq, d_pad) && d_pad <= 128 && nq > 256; }

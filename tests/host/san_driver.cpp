@@ -112,7 +112,7 @@ static void planner_checks(void *lib)
     plan_info_fn plan = (plan_info_fn)dlsym(lib, "lpq_search_plan_info");
     CHECK(plan != nullptr, "lpq_search_plan_info not exported");
     if (!plan) return;
-    const int ds[] = {1, 31, 32, 64, 65, 96, 100, 128, 129, 160, 192, 224, 256, 257, 384, 500, 512, 768, 1000, 1024, 1025, 32768};
+    const int ds[] = {1, 31, 32, 64, 65, 96, 100, 128, 129, 160, 192, 224, 256, 257, 384, 500, 512, 768, 1000, 1024, 1025, 1536, 1537, 32768};
     const int bitss[] = {1, 2, 4, 8};
     const int64_t ns[] = {1, 2, 63, 64, 511, 512, 1000, 4095, 4096, 10000, 65535, 65536, 262143, 1000000, 10000000,
                           100000000, (int64_t(1) << 31) - 1025};
@@ -132,7 +132,7 @@ static void planner_checks(void *lib)
 #define SHAPE "(d %d bits %d packed %d n %lld nq %lld k %d)", d, bits, packed, (long long)n, (long long)nq, k
             CHECK(v[0] >= 0 && v[0] <= 3, "mode " SHAPE);
             CHECK(v[3] == 32 || v[3] == 64 || v[3] == 128, "queries per wave " SHAPE);
-            if (v[3] == 32) CHECK(d > 512 && d <= 1024 && v[0] == 3 && !packed, "32 queries per wave: rows of 768 or 1024 bytes only " SHAPE);
+            if (v[3] == 32) CHECK(d > 512 && d <= 1536 && v[0] == 3 && !packed, "32 queries per wave: rows of 768, 1024 or 1536 bytes only " SHAPE);
             CHECK(v[4] >= nq && v[4] >= 1, "query rows cover the batch " SHAPE);
             CHECK(v[5] >= 0 && v[5] <= n, "seeding rows within the corpus " SHAPE);
             CHECK(v[7] >= 1, "at least one split " SHAPE);

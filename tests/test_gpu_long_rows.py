@@ -1,4 +1,4 @@
-"""The matrix-core collecting scan for long rows and its seeding pass (rows of 257 to 1024 features,
+"""The matrix-core collecting scan for long rows and its seeding pass (rows of 257 to 1536 features,
 and large batches on rows of 192 and 256 bytes) against the CPU oracle, bit-exact on ids and int32
 distances.  Needs a real MI355X."""
 import numpy as np
@@ -50,6 +50,9 @@ def _case(lpq, oracle, w, k, metric, mode, scope, expect_collecting=True):
     ("scaled_unit", 1000, 66_000, 513, 10, "ip", "absmax", "global"),
     ("skewed_int", 960, 65_536, 33, 128, "l2sq", "minmax", "global"),     # padded to 1024, largest k of the scan
     ("bimodal", 1024, 75_001, 1, 10, "ip", "absmax", "global"),
+    ("scaled_unit", 1100, 66_000, 200, 10, "l2sq", "absmax", "global"),   # padded to 1536: three segments per row
+    ("skewed_int", 1536, 70_003, 700, 100, "l2sq", "minmax", "per_feature"),
+    ("bimodal", 1536, 66_000, 33, 17, "ip", "absmax", "global"),
 ])
 def test_search_long_rows(lpq, oracle, recipe, d, n, nq, k, metric, mode, scope):
     _case(lpq, oracle, _workload(recipe, d, n, nq, metric), k, metric, mode, scope)
@@ -105,7 +108,7 @@ def _random_case(seed):
     """A random shape that the long-row scan takes: rows of 192 bytes and more, corpora large enough
     for a seeding sample, batches on both sides of the workgroup sizes and of the 1024-query tiles."""
     r = np.random.default_rng(7000 + seed)
-    d = int(r.choice([180, 192, 256, 257, 300, 384, 400, 512, 513, 700, 768, 900, 1000, 1024]))
+    d = int(r.choice([180, 192, 256, 257, 300, 384, 400, 512, 513, 700, 768, 900, 1000, 1024, 1025, 1300, 1536]))
     nq = int(r.choice([1, 33, 64, 300, 512, 513, 700, 1100, 2100, 3000]))
     n = int(r.choice([33_000, 40_001, 66_000, 70_003, 100_000]))
     if d * nq * n > 8e10:                       # keep the oracle to a few seconds
