@@ -154,7 +154,7 @@ int mfma_seed_groups(int S, int SEG, int rs_waves);      // = G, entries per que
 int mfma_queries_per_workgroup(int64_t nq, int d_pad, bool wide = false);   // query tile; wide: 128 queries per wave
 bool mfma_collect_wide(int64_t nq, int d_pad);           // collecting mode may use 128 queries per wave
 bool mfma_row_split(int64_t nq, int d_pad, bool packed = false);   // few queries: waves split rows, share queries
-bool mfma_long_rows(int d_pad, int64_t nq);         // rows of 384 to 1024 bytes, and large batches on 192 and 256: their own collecting scan and seeding pass
+bool mfma_long_rows(int d_pad, int64_t nq);         // rows of 384 to 1536 bytes, and large batches on 192 and 256: their own collecting scan and seeding pass
 int mfma_long_waves(int d_pad, int64_t nq);           // ... in workgroups of this many waves (4: two workgroups per CU, 8: one)
 int mfma_long_stage_rows(int d_pad, int64_t nq);   // ... whose stages hold 32 or 64 rows (the unit of the seeding pass' sample)
 int mfma_long_wave_queries(int d_pad);     // ... which keep 64 (up to 512 bytes) or 32 queries per wave

@@ -767,7 +767,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
     }
 }
 
-// ---- rows of 384 to 1024 bytes, and large batches on rows of 192 and 256 bytes -----------------
+// ---- rows of 384 to 1536 bytes, and large batches on rows of 192 and 256 bytes -----------------
 // The collecting scan and its seeding pass for rows whose operands no longer fit the scheme above
 // (query fragments AND two row blocks' worth of corpus fragments in registers).  What changes:
 //   - a wave holds the fragments of 32 queries (rows of 768 or 1024 bytes), 64 (384 or 512 bytes) or
@@ -1333,7 +1333,7 @@ bool takes_long_scan(const SearchArgs &a)
     return mfma_long_rows(a.d_pad, a.nq) && !a.rsplit && !a.packed && a.wave_queries == mfma_long_wave_queries(a.d_pad);
 }
 
-// Rows of 384 to 1024 bytes: the collecting scan (o.cbuf) or its seeding pass (o.gmax).
+// Rows of 384 to 1536 bytes (and large batches on 192 and 256): the collecting scan (o.cbuf) or its seeding pass (o.gmax).
 template <int KSEG, int NSEG, bool L2, bool SEED, int NW>
 hipError_t launch_long_nw(const SearchArgs &a, int64_t row0, int64_t row1, int S, MfmaIo o, hipStream_t st)
 {
