@@ -770,10 +770,10 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
 // ---- rows of 384 to 1536 bytes, and large batches on rows of 192 and 256 bytes -----------------
 // The collecting scan and its seeding pass for rows whose operands no longer fit the scheme above
 // (query fragments AND two row blocks' worth of corpus fragments in registers).  What changes:
-//   - a wave holds the fragments of 32 queries (rows of 768 or 1024 bytes), 64 (384 or 512 bytes) or
-//     128 (192 or 256 bytes): 128 registers at most;
+//   - a wave holds the fragments of 32 queries (rows of 768, 1024 or 1536 bytes), 64 (384 or 512
+//     bytes) or 128 (192 or 256 bytes): 128 registers at most, 192 on rows of 1536 bytes;
 //   - a stage is one block of 32 rows (two where an eight-wave workgroup has the LDS for it) by one
-//     segment of the row (the whole row up to 512 bytes, else a half), 6 to 32 KB, in a ring of three
+//     segment of the row (the whole row up to 512 bytes, else a half or a third), 6 to 32 KB, in a ring of three
 //     to six; the accumulators of a row block live across its segments, are seeded when its first
 //     segment starts and filtered when its last one ends;
 //   - corpus fragments come from LDS two to four k-steps at a time, one group ahead of the matrix
