@@ -149,3 +149,20 @@ def test_config2_with_200_000_queries_in_one_call(lpq, oracle):
     """Twenty times the benchmark batch in one call (391 query tiles, gigabytes of workspace): offsets
     into the per-query buffers pass 2^31."""
     _full_case(lpq, oracle, synth.SKEWED_1M.scaled(nq=200_000), 10, "minmax", "global", sample=24)
+
+
+@pytest.mark.parametrize("name,nq,k", [("skewed", 10_000, 10), ("skewed", 10_000, 100), ("skewed", 16, 10),
+                                       ("aniso", 10_000, 10), ("product", 10_000, 100)])
+def test_repeated_searches_give_the_same_answer(lpq, name, nq, k):
+    """Nothing in a search depends on timing: thirty calls on one batch return the same ids and
+    distances (the scan's candidates arrive in any order, the selection orders them by (distance, id))."""
+    w = {"skewed": synth.SKEWED_1M, "aniso": synth.ANISO_1M2, "product": synth.PRODUCT_100M.scaled(n=2_000_000)}[name]
+    x, q = w.corpus("cuda"), w.queries("cuda")[:nq]
+    index = lpq.Index(lpq.Quantizer(w.d, 8).calibrate(x, w.calib, w.scope), w.n).add_f32(x)
+    del x
+    ws = torch.empty(index.workspace_bytes(nq, k, w.metric) + 256, dtype=torch.uint8, device="cuda")
+    ids0, dists0 = index.search(q, k, w.metric, workspace=ws)
+    ids0, dists0 = ids0.clone(), dists0.clone()
+    for _ in range(30):
+        ids, dists = index.search(q, k, w.metric, workspace=ws)
+        assert torch.equal(ids, ids0) and torch.equal(dists, dists0)
