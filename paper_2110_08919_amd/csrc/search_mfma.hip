@@ -541,7 +541,7 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
                 bool trip = m >= thr[nb];                                                               \
                 unsigned long long mask = __ballot(trip);                                               \
                 LPQ_SCHED_CHAIN();                                                                      \
-                if (__builtin_expect(mask != 0, 0)) {   /* rare: laid out off the hot path */           \
+                if (__builtin_expect(mask != 0, TRIP_INLINE)) {   /* see TRIP_INLINE */                 \
                     if (qcnt + __popcll(mask) > QCAP) { /* no room: this wave drains alone */           \
                         if (LPQ_DRY(a) < 5) drain_queue<L2, KCAP, LK>(w, qcnt, re, lane, lst, seedC, cbase, qstride, o.Cs); \
                         qcnt = 0;                                                                       \
@@ -601,6 +601,11 @@ __global__ __launch_bounds__(NW * 64, 2) void search_mfma_kernel(
         }                                                                                               \
     } while (0)
 
+    // Where the compiler lays out the path a passing block takes: out of the loop (expected never)
+    // or in line.  In line measured 2 % faster at k = 100 on 128-byte rows with 128 queries per wave
+    // (a third of the epilogues pass there; 1.254 -> 1.229 ms) and the same at k = 10, but 2.6 %
+    // slower on 96-byte rows and 1 % slower in the 64-queries-per-wave kernels: in line for that tile only.
+    constexpr int TRIP_INLINE = (KS == 4 && NB == 4) ? 1 : 0;
     int T = (re > rs) ? (int)((re - rs + RS - 1) / RS) : 0;
     if (pieces) {
         T = o.piece_stages;
