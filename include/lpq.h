@@ -158,7 +158,11 @@ size_t lpq_search_workspace_bytes(const lpq_index *idx, int64_t nq, int k, int m
  *   dist_dev[nq][k] int32: L2SQ the full integer distance sum (cq - cx)^2, ascending;
  *                          IP the integer inner product, descending.
  * Equal distances are ordered by ascending id, so the result is unique.
- * 1 <= k <= min(size, 1024).  nq = 0 is a no-op.  Asynchronous on `stream`. */
+ * 1 <= k <= min(size, 1024).  nq = 0 is a no-op.  Asynchronous on `stream`.
+ * Every shape returns the same exact result; speed differs: indexes of up to 1536 features are
+ * searched on the matrix cores for every k and batch size once they hold enough items for a
+ * threshold sample (a few ten thousand), longer vectors and smaller indexes by a plain
+ * dot-product kernel (about two orders of magnitude slower per contraction). */
 int lpq_search(const lpq_index *idx, const float *q_dev, int64_t nq, int64_t ld, int k,
                int metric, int32_t *ids_dev, int32_t *dist_dev, void *workspace_dev,
                size_t workspace_bytes, void *stream);
