@@ -129,3 +129,42 @@ def test_random_long_row_configuration_bit_exact(lpq, oracle, seed):
     ids2, dists2 = index.search(w.queries("cuda"), k, metric, workspace=ws)      # the same call again: the same answer
     ids1, dists1 = index.search(w.queries("cuda"), k, metric)
     assert torch.equal(ids1, ids2) and torch.equal(dists1, dists2)
+
+
+@pytest.mark.parametrize("recipe,d,n,nq,k,metric", [("bimodal", 768, 70_000, 300, 10, "l2sq"),
+                                                     ("bimodal", 256, 66_000, 2000, 100, "ip"),
+                                                     ("skewed_int", 1536, 40_000, 16, 17, "l2sq")])
+def test_long_row_search_captured_in_a_graph_replays_exactly(lpq, recipe, d, n, nq, k, metric):
+    """The long-row scan too is kernel launches only: captured in a HIP graph (after one eager call),
+    every replay gives the eager result, with eager work in between."""
+    w = _workload(recipe, d, n, nq, metric)
+    x, q = w.corpus("cuda"), w.queries("cuda")
+    index = lpq.Index(lpq.Quantizer(d, 8).calibrate(x, "minmax", "global"), n).add_f32(x)
+    ids = torch.empty((nq, k), dtype=torch.int32, device="cuda")
+    dists = torch.empty_like(ids)
+    ws = torch.empty(index.workspace_bytes(nq, k, metric) + 256, dtype=torch.uint8, device="cuda")
+
+    def step():
+        index.search(q, k, metric, out=(ids, dists), workspace=ws)
+    step()
+    torch.cuda.synchronize()
+    ref_ids, ref_d = ids.clone(), dists.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        ids.fill_(-5)
+        dists.fill_(-5)
+        ws.random_(0, 255)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ids, ref_ids) and torch.equal(dists, ref_d)
+        step()
+        torch.cuda.synchronize()
+        assert torch.equal(ids, ref_ids) and torch.equal(dists, ref_d)
