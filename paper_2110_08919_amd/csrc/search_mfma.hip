@@ -1450,8 +1450,9 @@ int mfma_long_stage_rows(int d_pad, int64_t nq) { return (mfma_long_waves(d_pad,
 int mfma_long_waves(int d_pad, int64_t nq) { return (d_pad <= 256 || (nq > 512 && d_pad <= 1024)) ? 8 : 4; }
 
 // Collecting mode: 128 queries per wave when the rows are short enough for the registers to hold them.
-// (Not for 513 to 768 queries: three tiles of 256 are a quarter less padded work than two of 512,
-// measured 4 to 13 % faster; from 1025 queries on the wider tile's efficiency makes up for its padding.)
+// (Not for 513 to 768 queries: three tiles of 256 - register lists up to k = 10, the collecting scan
+// with 64 queries per wave beyond - are a quarter less padded work than two tiles of 512, measured 4
+// to 13 % faster; from 1025 queries on the wider tile's efficiency makes up for its padding.)
 bool mfma_collect_wide(int64_t nq, int d_pad)
 {
     return !mfma_row_split(nq, d_pad) && d_pad <= 128 && nq > 256 && !(nq > 512 && nq <= 768);

@@ -723,7 +723,7 @@ def test_collecting_scan_on_a_corpus_stored_in_sorted_order(lpq, oracle, order):
     """Similar items next to each other (sorted by norm, or lexicographically): the sampled bound is
     looser and candidates bunch up, but the scan deals its stages round-robin to the splits, so
     the regions fill evenly; results stay exact and at most a few queries need the exact redo."""
-    w = synth.SKEWED_1M.scaled(n=300_000, nq=600)
+    w = synth.SKEWED_1M.scaled(n=300_000, nq=900)   # (513 to 768 queries would take the register lists at k = 10)
     x, q = w.corpus("cuda"), w.queries("cuda")
     key = (x * x).sum(1) if order == "norm" else x[:, 0] * 1000 + x[:, 1]
     x = x[torch.argsort(key, stable=True)].contiguous()
