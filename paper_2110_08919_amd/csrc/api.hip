@@ -638,7 +638,7 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
     const int64_t tiles_q = ceil_div(nq > 0 ? nq : 1, qt);
     const int64_t min_rows = p.mode == PLAN_GENERIC ? 2048 : 512;
     if (seed) {
-        // group maxima per query: 2 per split and segment (8 when rows are split), at most 2048
+        // group maxima per query: 2 per split and segment (8 when rows are split), at most 2048 (4096 for k > 512)
         p.S1 = splits_for(seed, tiles_q, min_rows, slots_now, gmode ? (p.rsplit ? 256 : 1024) : merge_max_lists(k));
         if (gmode) {
             p.SEG = mfma_seed_segments(p.S1, k, p.rs_waves);

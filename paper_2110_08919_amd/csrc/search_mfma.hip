@@ -1500,7 +1500,8 @@ int mfma_seed_segments(int S, int k, int rs_waves)
     const int per = rs_waves ? 2 * rs_waves : 2;   // groups a split contributes per segment
     int seg = (int)ceil_div(6 * k, per * S);   // >= 6k groups: the k-th largest is then close to
     if (seg < 1) seg = 1;                      // the k-th best item of the seeded rows
-    while (per * S * seg > 2048 && seg > 1) --seg;
+    const int most = k > 512 ? 4096 : 2048;    // (k beyond 512: with 2048 groups or fewer the k-th largest
+    while (per * S * seg > most && seg > 1) --seg;   // maximum sits far below the k-th best sampled item)
     return seg;
 }
 
@@ -1535,12 +1536,13 @@ hipError_t launch_seed_finalize(const int32_t *gmax, int64_t nq, int G, int k, c
                                 int32_t *zero_word)
 {
     if (nq <= 0) return hipSuccess;
-    if (G > 2048) return hipErrorInvalidValue;
+    if (G > 4096) return hipErrorInvalidValue;
     const unsigned blocks = (unsigned)ceil_div(nq, (int64_t)4);
     if (G <= 256) seed_finalize_kernel<4><<<blocks, 256, 0, st>>>(gmax, nq, G, k, seeds, zero_word);
     else if (G <= 512) seed_finalize_kernel<8><<<blocks, 256, 0, st>>>(gmax, nq, G, k, seeds, zero_word);
     else if (G <= 1024) seed_finalize_kernel<16><<<blocks, 256, 0, st>>>(gmax, nq, G, k, seeds, zero_word);
-    else seed_finalize_kernel<32><<<blocks, 256, 0, st>>>(gmax, nq, G, k, seeds, zero_word);
+    else if (G <= 2048) seed_finalize_kernel<32><<<blocks, 256, 0, st>>>(gmax, nq, G, k, seeds, zero_word);
+    else seed_finalize_kernel<64><<<blocks, 256, 0, st>>>(gmax, nq, G, k, seeds, zero_word);
     return hipGetLastError();
 }
 
