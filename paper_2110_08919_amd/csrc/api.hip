@@ -592,7 +592,11 @@ Plan make_plan(const lpq_index *idx, int64_t nq, int k)
         }
     }
     seed = seed / 256 * 256;
-    if (seed < 64 * k || seed * (k > 512 ? 2 : 4) > n) seed = 0;
+    // A sample must hold at least 64 k rows for its k-th group maximum to mean something; a small
+    // corpus may give up to half of its rows for that (20 000 x 128, 10 000 queries, k = 100: 0.5 ms
+    // with such a sample against 2.3 ms through the generic kernel).
+    if (p.mode == PLAN_MFMA_COLLECT && seed > 0 && seed < 64 * (int64_t)k) seed = round_up(64 * (int64_t)k, 256);
+    if (seed < 64 * k || seed * 2 > n || (k <= 512 && p.mode != PLAN_MFMA_COLLECT && seed * 4 > n)) seed = 0;
     if (p.mode == PLAN_MFMA_COLLECT && !seed) {   // too few items to sample: exact paths
         // (longer lists without a sample: the generic kernel; the LDS-list matrix-core kernel measured
         // 10 to 70x slower on the corpora this happens for - 1000 x 128, k = 100, 1000 queries: 4.3 ms
